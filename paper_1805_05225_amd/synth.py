@@ -1,0 +1,83 @@
+"""Seeded synthetic inputs for the five benchmark configurations.
+
+This module only draws random numbers and rounds them to the storage type; it holds none of
+the LSTM arithmetic.  Both the CPU oracle's tests and the HIP path's tests take their inputs
+from here, so the two sides always see identical values.
+
+The inputs stand in for the paper's WMT 2017 and Switchboard workloads (Sec. 3-5), which are
+not available: only their shapes are used - embedding width 620, 1000 units per direction,
+six bidirectional encoder layers, decoder cell input 620 + 2000, beam 12 (Listing 1, Sec. 5).
+
+Draw order for configuration k, from torch.Generator(cpu) seeded with 18050522500 + k:
+seq_lens, x, then per layer and per direction W_x, W_h, b, then h0, c0, dy.
+Padded frames of x and dy are filled with N(0,1) noise (not zeros) so a missing mask shows.
+"""
+import numpy as np
+import torch
+
+SEED_BASE = 18050522500
+
+# kind: "lstm" (one direction) or "blstm".  len range is inclusive.  dtype "f32" or "bf16".
+CONFIGS = {
+    1: dict(kind="lstm", dtype="f32", n_in=32, n=64, B=4, layers=1, len_lo=20, len_hi=20, w=0.1),
+    2: dict(kind="blstm", dtype="f32", n_in=620, n=1000, B=64, layers=1, len_lo=10, len_hi=50, w=0.08),
+    3: dict(kind="blstm", dtype="bf16", n_in=620, n=1000, B=64, layers=6, len_lo=20, len_hi=80, w=0.08),
+    4: dict(kind="blstm", dtype="bf16", n_in=40, n=1024, B=32, layers=6, len_lo=200, len_hi=1500, w=0.08),
+    5: dict(kind="lstm", dtype="bf16", n_in=2620, n=1000, B=768, layers=1, len_lo=1, len_hi=1, w=0.08, steps=100),
+}
+
+
+def round_to(a, dtype):
+    """Round a float32 torch tensor to the storage type and return it as float32 (exact)."""
+    if dtype == "bf16":
+        return a.to(torch.bfloat16).to(torch.float32)
+    return a
+
+
+def make(k, **override):
+    """Build configuration k (optionally with overridden sizes, e.g. len_hi=40, layers=2, B=8).
+
+    Returns a dict of numpy arrays (float32 values, already rounded to bf16 where the config
+    stores bf16): seq_lens int32 [B]; x [T,B,n_in]; layers = list of {W_x [D,n_in_k,4n],
+    W_h [D,n,4n], b [D,4n]} with D = 2 for "blstm" and D = 1 for "lstm"; h0, c0 [D,B,n]
+    (zeros, as every configuration prescribes); dy [T,B,D*n] for the top layer's output.
+    """
+    cfg = dict(CONFIGS[k])
+    cfg.update(override)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(SEED_BASE + k)
+    B, n, n_in, dt = cfg["B"], cfg["n"], cfg["n_in"], cfg["dtype"]
+    D = 2 if cfg["kind"] == "blstm" else 1
+    lens = torch.randint(cfg["len_lo"], cfg["len_hi"] + 1, (B,), generator=g, dtype=torch.int64)
+    T = int(lens.max())
+    x = round_to(torch.randn(T, B, n_in, generator=g), dt)
+    layers = []
+    for l in range(cfg["layers"]):
+        ni = n_in if l == 0 else D * n
+        Wx, Wh, bb = [], [], []
+        for d in range(D):
+            Wx.append(round_to((torch.rand(ni, 4 * n, generator=g) * 2 - 1) * cfg["w"], dt))
+            Wh.append(round_to((torch.rand(n, 4 * n, generator=g) * 2 - 1) * cfg["w"], dt))
+            bb.append(torch.zeros(4 * n))
+        layers.append(dict(W_x=torch.stack(Wx).numpy(), W_h=torch.stack(Wh).numpy(), b=torch.stack(bb).numpy()))
+    h0 = torch.zeros(D, B, n)
+    c0 = torch.zeros(D, B, n)
+    dy = round_to(torch.randn(T, B, D * n, generator=g), dt)
+    return dict(cfg=cfg, k=k, T=T, D=D, seq_lens=lens.to(torch.int32).numpy(), x=x.numpy(), layers=layers,
+                h0=h0.numpy(), c0=c0.numpy(), dy=dy.numpy())
+
+
+def real_frames(inp):
+    return int(inp["seq_lens"].astype(np.int64).sum())
+
+
+def flops_fwd_bwd(inp):
+    """Useful floating-point operations of one forward + backward pass over the stack:
+    24*n*(n_in+n) per real frame, per direction, per layer (matrix products only)."""
+    cfg = inp["cfg"]
+    n, D = cfg["n"], inp["D"]
+    tot = 0
+    for l in range(cfg["layers"]):
+        ni = cfg["n_in"] if l == 0 else D * n
+        tot += D * 24 * n * (ni + n)
+    return tot * real_frames(inp)
