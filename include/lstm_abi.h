@@ -1,0 +1,137 @@
+/*
+ * C ABI of the MI355X (gfx950) masked LSTM / BLSTM layer library.
+ *
+ * The operation is the recurrent layer the paper names in Listing 1 ("class": "rec",
+ * "unit": "nativelstm2", "direction": +1 / -1; two such layers on the same input, concatenated,
+ * form one bidirectional layer) and the stepped decoder cell ("rnn_cell" / "LSTMBlock"), with
+ * the input projection taken out of the recurrent loop (Sec. 3, Sec. 7).  The paper prints no
+ * cell equations; the library implements the peephole-free LSTM
+ *
+ *     z = x_t W_x + h W_h + b          (4n columns, gate blocks i | f | g | o)
+ *     i,f,o = sigmoid(z_i,z_f,z_o)     g = tanh(z_g)
+ *     c' = f*c + i*g                   h' = o*tanh(c')
+ *
+ * over end-padded, variable-length batches.  Frame t of row b is valid iff t < seq_lens[b].
+ * At a padded frame the state is carried unchanged, y is 0, the stored cell state is the carried
+ * one, and the frame contributes no gradient; values stored in x / dy at padded frames never
+ * reach a result.  direction -1 walks t = T-1 .. 0 over the same tensors.
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned, row-major,
+ *     time-major.  The library allocates and frees nothing; scratch comes from `workspace`,
+ *     state saved for the backward pass goes to `reserve`; sizes come from lstm_query().
+ *   - `stream` is a hipStream_t cast to void* (NULL = the default stream).  Calls only enqueue
+ *     work; they never synchronise.  Buffers must stay alive until the stream has passed the call.
+ *   - dtype LSTM_F32: every tensor is float.  dtype LSTM_BF16_F32STATE: x, W_x, W_h, y, dy, dx
+ *     are bfloat16; b, c, h0, c0, hT, cT, dhT, dcT, dh0, dc0, dW_x, dW_h, db are float.  All
+ *     accumulation, the cell state and the gate activations are float in both modes.
+ *   - Optional pointers (may be NULL): b (zero bias), h0, c0 (zero state), seq_lens (all rows
+ *     have length T), hT, cT, c, dhT, dcT (zero), dx, dh0, dc0 (not produced).
+ *   - seq_lens is int32[B] in device memory, any order; values are clamped to [0, T] in the kernels.
+ *   - Return value: 0 on success, a negative lstm_status otherwise.  Arguments are validated on
+ *     the host before the first HIP call, so every argument error is reported without a GPU.
+ *     Nothing throws or aborts across this boundary.
+ */
+#ifndef MI355X_LSTM_ABI_H
+#define MI355X_LSTM_ABI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LSTM_F32 = 0, LSTM_BF16_F32STATE = 1 } lstm_dtype;
+
+typedef enum {
+  LSTM_OK = 0,
+  LSTM_ERR_NULL = -1,       /* required pointer (or the descriptor) is NULL                     */
+  LSTM_ERR_DIM = -2,        /* negative T or B, or n / n_in < 1, or a size that overflows int32  */
+  LSTM_ERR_DIRECTION = -3,  /* direction is neither +1 nor -1 (lstm_* only)                      */
+  LSTM_ERR_UNSUPPORTED = -4,/* unknown dtype or flag bit                                         */
+  LSTM_ERR_ALIGN = -5,      /* a pointer is not 16-byte aligned                                  */
+  LSTM_ERR_SIZE = -6,       /* reserve_bytes / workspace_bytes smaller than lstm_query() demands */
+  LSTM_ERR_HIP = -7         /* HIP runtime error while enqueueing, or the device is not gfx950   */
+} lstm_status;
+
+enum {
+  LSTM_FLAG_ACCUMULATE = 1, /* *_bwd: add into dW_x, dW_h, db instead of overwriting them        */
+  LSTM_FLAG_PER_STEP = 2,   /* force one kernel launch per time step (no persistent kernel)      */
+  LSTM_FLAG_INFERENCE = 4   /* *_fwd: nothing is saved for backward; reserve may be NULL         */
+};
+
+typedef struct {
+  int32_t T, B, n_in, n;    /* padded length, batch rows, input width, units per direction       */
+  int32_t direction;        /* +1 or -1; read by lstm_fwd / lstm_bwd only                        */
+  int32_t dtype;            /* lstm_dtype                                                        */
+  int32_t flags;            /* LSTM_FLAG_* bits                                                  */
+  int32_t reserved;         /* must be 0                                                         */
+  uint64_t reserve_bytes;   /* bytes the caller allocated behind `reserve`                       */
+  uint64_t workspace_bytes; /* bytes the caller allocated behind `workspace`                     */
+} lstm_desc;
+
+/* Sizes of `reserve` and `workspace` for this problem (bidirectional != 0 for blstm_*).
+ * The workspace size covers both the forward and the backward call.  T == 0 or B == 0 is legal
+ * (the calls are then no-ops) and yields small non-zero sizes.  Only T, B, n_in, n, dtype and
+ * flags of the descriptor are read. */
+int lstm_query(const lstm_desc* desc, int bidirectional, size_t* reserve_bytes, size_t* workspace_bytes);
+
+/* Forward pass of one direction (Listing 1, "rec"/"nativelstm2" with "direction").
+ *   x[T,B,n_in]  W_x[n_in,4n]  W_h[n,4n]  b[4n]  h0,c0[B,n]  seq_lens[B]
+ *   -> y[T,B,n] (0 at padded frames), c[T,B,n] (cell state after each frame, carried at padded
+ *      frames; may be NULL), hT,cT[B,n] (state after each row's last processed valid frame),
+ *      reserve (opaque: gate activations and the hidden state entering each frame).
+ * With T == 1 and LSTM_FLAG_INFERENCE this is the stepped decoder cell: feed hT,cT back as h0,c0. */
+int lstm_fwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h, const void* b,
+             const void* h0, const void* c0, const int32_t* seq_lens,
+             void* y, void* c, void* hT, void* cT, void* reserve, void* workspace, void* stream);
+
+/* Backward pass (back-propagation through time) of one direction: the exact gradient of
+ * sum(dy*y) + sum(dhT*hT) + sum(dcT*cT).  y, c and reserve must be the forward call's, untouched.
+ *   dy[T,B,n]  dhT,dcT[B,n]
+ *   -> dx[T,B,n_in] (0 at padded frames), dW_x[n_in,4n], dW_h[n,4n], db[4n], dh0,dc0[B,n]. */
+int lstm_bwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h,
+             const void* h0, const void* c0, const int32_t* seq_lens,
+             const void* y, const void* c, const void* reserve,
+             const void* dy, const void* dhT, const void* dcT,
+             void* dx, void* dW_x, void* dW_h, void* db, void* dh0, void* dc0,
+             void* workspace, void* stream);
+
+/* Bidirectional layer (Listing 1: enc*_fw + enc*_bw + "copy"): both directions run concurrently.
+ * W_x[2,n_in,4n], W_h[2,n,4n], b[2,4n], h0,c0,hT,cT[2,B,n], c[2,T,B,n]; index 0 = direction +1,
+ * 1 = direction -1.  y[T,B,2n]: direction +1 in columns 0..n-1, direction -1 in n..2n-1. */
+int blstm_fwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h, const void* b,
+              const void* h0, const void* c0, const int32_t* seq_lens,
+              void* y, void* c, void* hT, void* cT, void* reserve, void* workspace, void* stream);
+
+/* Backward of the bidirectional layer.  dy[T,B,2n]; dx[T,B,n_in] is the SUM of both directions;
+ * dW_x[2,n_in,4n], dW_h[2,n,4n], db[2,4n], dhT,dcT,dh0,dc0[2,B,n]. */
+int blstm_bwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h,
+              const void* h0, const void* c0, const int32_t* seq_lens,
+              const void* y, const void* c, const void* reserve,
+              const void* dy, const void* dhT, const void* dcT,
+              void* dx, void* dW_x, void* dW_h, void* db, void* dh0, void* dc0,
+              void* workspace, void* stream);
+
+/* The hoisted matrix product the layer uses for Zx = X W_x + b, dX = DZ W_x^T, dW_x = X^T DZ and
+ * dW_h = Hprev^T DZ (Sec. 3: work moved out of the recurrent loop), exposed so that each shape can be
+ * tested and timed by itself.  C[M,N] (+)= A B + bias, float accumulation.
+ *   in_bf16 / out_bf16: operand and result storage (bfloat16 or float; out_bf16 requires in_bf16).
+ *   a_kcontig != 0: A is [M][lda] (k contiguous), else [K][lda] (m contiguous);
+ *   b_kcontig != 0: B is [N][ldb] (k contiguous), else [K][ldb] (n contiguous).
+ *   Supported pairs: (1,0), (1,1), (0,0).  bias[N] may be NULL.  accumulate != 0 adds into a float C.
+ *   lens != NULL (only with a_kcontig == 0): row k of the K axis is frame (t = k / Bt, b = k % Bt) of a
+ *   batch of Bt rows and T frames and is read as zero unless t < lens[b].
+ * Leading dimensions are in elements; rows must be aligned to the element size only. */
+int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, int N, int K,
+              const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const float* bias,
+              int accumulate, const int32_t* lens, int Bt, int T, void* stream);
+
+/* Static, human-readable text for a status code (never NULL). */
+const char* lstm_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,157 @@
+"""ctypes binding of the C ABI in include/lstm_abi.h.
+
+Argument marshalling only: every step of the computation runs inside the HIP library.  PyTorch
+is used to own device memory and to name the stream.  If the library is not built the import
+fails loudly - there is no fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmi355x_lstm.so")
+
+LSTM_F32, LSTM_BF16_F32STATE = 0, 1
+FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE = 1, 2, 4
+EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_strerror")
+
+
+class LstmDesc(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("B", ctypes.c_int32), ("n_in", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("direction", ctypes.c_int32), ("dtype", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("reserve_bytes", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64)]
+
+
+class LstmError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__("lstm library status %d: %s" % (status, strerror(status)))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("HIP library %s is not built; run `python -m paper_1805_05225_amd.build`" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ip = ctypes.c_void_p, ctypes.c_int
+    dp = ctypes.POINTER(LstmDesc)
+    lib.lstm_query.restype = ip
+    lib.lstm_query.argtypes = [dp, ip, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
+    for name in ("lstm_fwd", "blstm_fwd"):
+        f = getattr(lib, name)
+        f.restype = ip
+        f.argtypes = [dp] + [vp] * 14
+    for name in ("lstm_bwd", "blstm_bwd"):
+        f = getattr(lib, name)
+        f.restype = ip
+        f.argtypes = [dp] + [vp] * 20
+    lib.lstm_gemm.restype = ip
+    lib.lstm_gemm.argtypes = [ip] * 7 + [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ip, vp, ip, ip, vp]
+    lib.lstm_strerror.restype = ctypes.c_char_p
+    lib.lstm_strerror.argtypes = [ip]
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status):
+    return lib.lstm_strerror(int(status)).decode()
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "tensors crossing the ABI must be contiguous"
+    return t.data_ptr()
+
+
+def _check(status):
+    if status != 0:
+        raise LstmError(status)
+
+
+def make_desc(T, B, n_in, n, dtype, direction=1, flags=0):
+    return LstmDesc(T, B, n_in, n, direction, dtype, flags, 0, 0, 0)
+
+
+def query(desc, bidirectional):
+    r, w = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib.lstm_query(ctypes.byref(desc), int(bool(bidirectional)), ctypes.byref(r), ctypes.byref(w)))
+    return r.value, w.value
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_of(x):
+    return LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else LSTM_F32
+
+
+def forward(x, W_x, W_h, b=None, h0=None, c0=None, seq_lens=None, *, bidirectional, direction=1, flags=0,
+            workspace=None, want_c=True, want_state=True):
+    """Allocates the outputs and calls lstm_fwd / blstm_fwd.  Returns a dict with y, c, hT, cT,
+    reserve, workspace and the descriptor (everything the backward call needs)."""
+    T, B, n_in = x.shape
+    n = W_h.shape[-2]
+    D = 2 if bidirectional else 1
+    dev = x.device
+    desc = make_desc(T, B, n_in, n, _dtype_of(x), direction, flags)
+    rb, wb = query(desc, bidirectional)
+    infer = bool(flags & FLAG_INFERENCE)
+    reserve = None if infer else torch.empty(rb, dtype=torch.uint8, device=dev)
+    if workspace is None or workspace.numel() < wb:
+        workspace = torch.empty(wb, dtype=torch.uint8, device=dev)
+    desc.reserve_bytes = 0 if infer else rb
+    desc.workspace_bytes = workspace.numel()
+    y = torch.empty(T, B, D * n, dtype=x.dtype, device=dev)
+    shp = (D, B, n) if bidirectional else (B, n)
+    c = torch.empty((D, T, B, n) if bidirectional else (T, B, n), dtype=torch.float32, device=dev) if (want_c or not infer) else None
+    hT = torch.empty(shp, dtype=torch.float32, device=dev) if want_state else None
+    cT = torch.empty(shp, dtype=torch.float32, device=dev) if want_state else None
+    fn = lib.blstm_fwd if bidirectional else lib.lstm_fwd
+    _check(fn(ctypes.byref(desc), _ptr(x), _ptr(W_x), _ptr(W_h), _ptr(b), _ptr(h0), _ptr(c0), _ptr(seq_lens),
+              _ptr(y), _ptr(c), _ptr(hT), _ptr(cT), _ptr(reserve), _ptr(workspace), _stream()))
+    return dict(y=y, c=c, hT=hT, cT=cT, reserve=reserve, workspace=workspace, desc=desc, bidirectional=bidirectional)
+
+
+def backward(fwd, x, W_x, W_h, h0, c0, seq_lens, dy, dhT=None, dcT=None, *, want_dx=True, want_dstate=True,
+             accumulate_into=None):
+    """Allocates the gradients and calls lstm_bwd / blstm_bwd with the buffers of `forward`'s result."""
+    desc = fwd["desc"]
+    bidirectional = fwd["bidirectional"]
+    T, B, n_in = x.shape
+    n = W_h.shape[-2]
+    dev = x.device
+    if accumulate_into is not None:
+        dW_x, dW_h, db = accumulate_into
+        desc = LstmDesc(desc.T, desc.B, desc.n_in, desc.n, desc.direction, desc.dtype, desc.flags | FLAG_ACCUMULATE, 0,
+                        desc.reserve_bytes, desc.workspace_bytes)
+    else:
+        dW_x = torch.empty(W_x.shape, dtype=torch.float32, device=dev)
+        dW_h = torch.empty(W_h.shape, dtype=torch.float32, device=dev)
+        db = torch.empty(W_x.shape[:-2] + (4 * n,), dtype=torch.float32, device=dev)
+    dx = torch.empty_like(x) if want_dx else None
+    shp = (2, B, n) if bidirectional else (B, n)
+    dh0 = torch.empty(shp, dtype=torch.float32, device=dev) if want_dstate else None
+    dc0 = torch.empty(shp, dtype=torch.float32, device=dev) if want_dstate else None
+    fn = lib.blstm_bwd if bidirectional else lib.lstm_bwd
+    _check(fn(ctypes.byref(desc), _ptr(x), _ptr(W_x), _ptr(W_h), _ptr(h0), _ptr(c0), _ptr(seq_lens),
+              _ptr(fwd["y"]), _ptr(fwd["c"]), _ptr(fwd["reserve"]), _ptr(dy), _ptr(dhT), _ptr(dcT),
+              _ptr(dx), _ptr(dW_x), _ptr(dW_h), _ptr(db), _ptr(dh0), _ptr(dc0), _ptr(fwd["workspace"]), _stream()))
+    return dict(dx=dx, dW_x=dW_x, dW_h=dW_h, db=db, dh0=dh0, dc0=dc0)
+
+
+def gemm(A, B, *, a_kcontig, b_kcontig, M, N, K, out_dtype=torch.float32, bias=None, C=None, accumulate=False,
+         lens=None, Bt=1, T=0):
+    """C[M,N] (+)= A B + bias through lstm_gemm; A and B are 2-D tensors in the stated storage order."""
+    in_bf16 = A.dtype == torch.bfloat16
+    if C is None:
+        C = torch.empty(M, N, dtype=out_dtype, device=A.device)
+    _check(lib.lstm_gemm(int(in_bf16), int(C.dtype == torch.bfloat16), int(a_kcontig), int(b_kcontig), M, N, K,
+                         _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(C), C.stride(0), _ptr(bias), int(accumulate),
+                         _ptr(lens), Bt, T, _stream()))
+    return C

@@ -1,0 +1,118 @@
+// Internal declarations shared by the translation units of the library (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lstm {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// round-to-nearest-even float -> bf16 bits, NaN kept quiet
+__device__ __forceinline__ uint16_t f2bf_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf_bits2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// Storage-type helpers: T is float or bf16_t.
+template <typename T> struct Store;
+template <> struct Store<float> {
+  static constexpr int kBytes = 4;
+  static constexpr int kPerChunk = 4;                      // elements in a 16-byte chunk
+  __device__ static float load(const void* p, long i) { return ((const float*)p)[i]; }
+  __device__ static void store(void* p, long i, float v) { ((float*)p)[i] = v; }
+};
+template <> struct Store<bf16_t> {
+  static constexpr int kBytes = 2;
+  static constexpr int kPerChunk = 8;
+  __device__ static float load(const void* p, long i) { return bf_bits2f(((const uint16_t*)p)[i]); }
+  __device__ static void store(void* p, long i, float v) { ((uint16_t*)p)[i] = f2bf_bits(v); }
+};
+
+// ------------------------------------------------------------------------------------------
+// Hoisted GEMM:  C[m,n] (+)= sum_seg sum_k A(m,k) B(k,n) + bias[n]
+//   a_kcontig: A is stored [M][lda] (k contiguous); otherwise [K][lda] (m contiguous).
+//   b_kcontig: B is stored [N][ldb] (k contiguous); otherwise [K][ldb] (n contiguous).
+// blockIdx.z batches independent problems (pointer strides s*z, in elements).
+// nseg > 1 sums over several (A,B) pairs (strides s*seg): used to add both directions' dX.
+// lens != NULL masks rows of the K axis: row k is a frame (t = k / Bt, b = k % Bt) and is read
+// as zero unless t < lens[b]  (so values stored at padded frames never enter dW_x).
+struct GemmArgs {
+  const void* A; const void* B; void* C; const float* bias;
+  int M, N, K;
+  long lda, ldb, ldc;
+  long sAz, sBz, sCz, sbiasz;
+  int nz;
+  int nseg; long sAseg, sBseg;
+  int vecA, vecB;            // widest aligned access (bytes) usable on A / B: 16, 8, 4 or 2
+  int accumulate;            // C += result (float C only)
+  const int* lens; int Bt; int T;
+  bool a_kcontig, b_kcontig;
+  bool in_bf16, out_bf16;
+};
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+
+// ------------------------------------------------------------------------------------------
+// Recurrent part.  Fragment geometry of the 16x16 MFMA used by the step kernels: a 16-byte chunk
+// per lane holds kPerChunk consecutive k; lane = g*16 + r with r the row (A) or column (B) inside
+// a 16-wide tile and g in 0..3; one chunk index kc covers KC = 4*kPerChunk values of k:
+//   k = kc*KC + g*kPerChunk + e.
+struct FwdDir {
+  const uint4* Wf;    // packed W_h: [unit tile of 8][2 column tiles][nkc][64] chunks
+  const uint4* hin;   // h entering the step, fragment order: [row tile of 16][nkc][64] chunks
+  void* hout;         // h leaving the step, same layout
+  float* gates;       // frame slab [B][4n]: in = x W_x + b, out = activations i|f|g|o
+  float* hstate;      // [B][n] float running state
+  float* cstate;
+  void* y; long ldy;  // row b of this frame's output at y + b*ldy (storage type)
+  float* cs;          // frame slab [B][n] or NULL
+  void* hprev;        // frame slab [B][n] (storage type) or NULL
+  int t;              // frame index of this step
+};
+struct FwdArgs {
+  FwdDir d[2];
+  const int* lens;
+  int B, n, nkc, T, ndir, write_gates;
+};
+hipError_t launch_step_fwd(const FwdArgs& a, bool bf16, hipStream_t s);
+
+struct BwdDir {
+  const uint4* Wb;    // packed W_h^T: [unit tile of 16][nkc][64] chunks, k runs over the 4n gate columns
+  const uint4* dzin;  // dz of the previous backward step, fragment order [row tile][nkc][64]
+  void* dzout;
+  const float* gates; // frame slab [B][4n] activations
+  const float* cs;    // frame slab [B][n]: cell state after this frame
+  const float* cprev; // [B][n]: cell state entering this frame (slab of the neighbouring frame or c0); NULL = 0
+  const void* dy; long lddy;
+  void* DZ;           // frame slab [B][4n] (storage type)
+  float* Dh; float* Dc;   // [B][n] carried gradients
+  int t;              // frame of this step (pointwise part)
+  int t_next;         // frame whose dz sits in dzin (matmul part)
+};
+struct BwdArgs {
+  BwdDir d[2];
+  const int* lens;
+  int B, n, nkc, T, ndir, do_matmul, do_pointwise;
+};
+hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s);
+
+// Weight / state packing and small helpers (all enqueue-only).
+hipError_t launch_pack_wh_fwd(const void* W_h, uint4* Wf, int n, int nkc, int ndir, bool bf16, hipStream_t s);
+hipError_t launch_pack_wh_bwd(const void* W_h, uint4* Wb, int n, int nkc, int ndir, bool bf16, hipStream_t s);
+// h (float [ndir][B][n]) -> fragment order, zero padded, written to both ping-pong buffers
+hipError_t launch_pack_state(const float* h, uint4* frag0, uint4* frag1, int B, int n, int nkc, int nrt, int ndir,
+                             bool bf16, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);                 // bytes % 4 == 0
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);   // bytes % 4 == 0
+// db[c] (+)= sum_rows DZ[row][c]; part = float scratch [nsplit][ncols] per direction
+hipError_t launch_colsum(const void* DZ, float* db, float* part, int rows, int ncols, int ndir, long sDZ,
+                         bool bf16, int accumulate, hipStream_t s);
+
+inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+
+}  // namespace lstm

@@ -1,0 +1,354 @@
+// Host side of the C ABI: argument validation, buffer planning and the launch sequences.
+// No device code lives here.  Validation never touches the HIP runtime, so every argument error
+// can be produced on a machine without a GPU.
+#include "../../include/lstm_abi.h"
+#include "common.h"
+
+#include <string.h>
+#include <algorithm>
+
+namespace lstm {
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+  int T, B, n_in, n, D;
+  bool bf16;
+  size_t esz;
+  int nkc_f, nkc_b, nrt, ntile_f, ntile_b;
+  // reserve: per direction [gates float T*B*4n][hprev storage T*B*n]
+  size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
+  // workspace
+  size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
+      ws_colsum, workspace_bytes;
+  size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems;
+};
+
+int make_plan(const lstm_desc* d, int bidir, Plan* p) {
+  if (!d) return LSTM_ERR_NULL;
+  if (d->T < 0 || d->B < 0 || d->n_in < 1 || d->n < 1) return LSTM_ERR_DIM;
+  const long TB = (long)d->T * d->B;
+  if (TB >= (1L << 31) || (long)d->n * 4 >= (1L << 29) || d->n_in >= (1 << 29) || d->B >= (1 << 24)) return LSTM_ERR_DIM;
+  if (d->dtype != LSTM_F32 && d->dtype != LSTM_BF16_F32STATE) return LSTM_ERR_UNSUPPORTED;
+  if (d->flags & ~(LSTM_FLAG_ACCUMULATE | LSTM_FLAG_PER_STEP | LSTM_FLAG_INFERENCE)) return LSTM_ERR_UNSUPPORTED;
+  if (d->reserved != 0) return LSTM_ERR_UNSUPPORTED;
+  p->T = d->T; p->B = d->B; p->n_in = d->n_in; p->n = d->n; p->D = bidir ? 2 : 1;
+  p->bf16 = d->dtype == LSTM_BF16_F32STATE;
+  p->esz = p->bf16 ? 2 : 4;
+  const int KC = p->bf16 ? 32 : 16;                 // k covered by one fragment chunk index
+  p->nkc_f = cdiv(d->n, KC);
+  p->nkc_b = cdiv(4L * d->n, KC);
+  p->nrt = 2 * cdiv(d->B > 0 ? d->B : 1, 32);       // 16-row tiles, two per work-group row block
+  p->ntile_f = cdiv(d->n, 8);
+  p->ntile_b = cdiv(d->n, 16);
+  const size_t n = d->n, D = p->D, B = d->B;
+  const bool infer = d->flags & LSTM_FLAG_INFERENCE;
+  p->res_gates = 0;
+  p->res_hprev = up(TB * 4 * n * 4);
+  p->res_dir_stride = p->res_hprev + up(TB * n * p->esz);
+  p->reserve_bytes = D * p->res_dir_stride + kAlign;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
+  p->ws_Wf = take(D * p->ntile_f * 2 * (size_t)p->nkc_f * 1024);
+  p->ws_Wb = take(infer ? 0 : D * p->ntile_b * (size_t)p->nkc_b * 1024);
+  p->hfrag_bytes = D * p->nrt * (size_t)p->nkc_f * 1024;
+  p->dzfrag_bytes = D * p->nrt * (size_t)p->nkc_b * 1024;
+  p->ws_hfrag0 = take(p->hfrag_bytes);
+  p->ws_hfrag1 = take(p->hfrag_bytes);
+  p->ws_dzfrag0 = take(infer ? 0 : p->dzfrag_bytes);
+  p->ws_dzfrag1 = take(infer ? 0 : p->dzfrag_bytes);
+  p->ws_hstate = take(D * B * n * 4);
+  p->ws_cstate = take(D * B * n * 4);
+  p->ws_Dh = take(infer ? 0 : D * B * n * 4);
+  p->ws_Dc = take(infer ? 0 : D * B * n * 4);
+  p->DZ_dir_elems = up(TB * 4 * n * p->esz) / p->esz;
+  p->ws_DZ = take(infer ? 0 : D * p->DZ_dir_elems * p->esz);
+  p->Zx_dir_elems = up(TB * 4 * n * 4) / 4;
+  p->ws_Zx = take(infer ? D * p->Zx_dir_elems * 4 : 0);
+  p->ws_colsum = take(infer ? 0 : D * 64 * 4 * n * 4);
+  p->workspace_bytes = o + kAlign;
+  return LSTM_OK;
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+int widest(long ld_elems, long s1, long s2, size_t esz, int cap) {
+  int v = cap;
+  while (v > (int)esz && ((ld_elems * (long)esz) % v || (s1 * (long)esz) % v || (s2 * (long)esz) % v)) v >>= 1;
+  return v;
+}
+
+int check_device() {
+  static int cached = 1;   // 1 = unknown, 0 = ok, <0 = error
+  if (cached != 1) return cached;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  cached = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 0 : LSTM_ERR_HIP;
+  return cached;
+}
+
+#define HIPCHK(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; } } while (0)
+
+int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, const void* W_h, const void* b,
+            const void* h0, const void* c0, const int32_t* seq_lens, void* y, void* c, void* hT, void* cT, void* reserve,
+            void* workspace, void* stream) {
+  Plan p;
+  int rc = make_plan(desc, bidir, &p);
+  if (rc) return rc;
+  if (!bidir && desc->direction != 1 && desc->direction != -1) return LSTM_ERR_DIRECTION;
+  const bool infer = desc->flags & LSTM_FLAG_INFERENCE;
+  if (!x || !W_x || !W_h || !y || !workspace) return LSTM_ERR_NULL;
+  if (!infer && (!reserve || !c)) return LSTM_ERR_NULL;
+  const void* ptrs[] = {x, W_x, W_h, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace};
+  for (const void* q : ptrs) if (misaligned(q)) return LSTM_ERR_ALIGN;
+  if (desc->workspace_bytes < p.workspace_bytes) return LSTM_ERR_SIZE;
+  if (!infer && desc->reserve_bytes < p.reserve_bytes) return LSTM_ERR_SIZE;
+  if (p.B == 0) return LSTM_OK;
+  if ((rc = check_device())) return rc;
+
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)(((uintptr_t)workspace + kAlign - 1) / kAlign * kAlign);
+  char* rs = reserve ? (char*)(((uintptr_t)reserve + kAlign - 1) / kAlign * kAlign) : nullptr;
+  const size_t n = p.n, B = p.B, D = p.D, T = p.T;
+  float* hstate = (float*)(ws + p.ws_hstate);
+  float* cstate = (float*)(ws + p.ws_cstate);
+  const size_t state_bytes = D * B * n * 4;
+
+  if (h0) HIPCHK(launch_copy(hstate, h0, state_bytes, s)); else HIPCHK(launch_fill_zero(hstate, state_bytes, s));
+  if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else HIPCHK(launch_fill_zero(cstate, state_bytes, s));
+  if (T > 0) {
+    HIPCHK(launch_pack_wh_fwd(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_f, p.D, p.bf16, s));
+    HIPCHK(launch_pack_state(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_f, p.nrt, p.D,
+                             p.bf16, s));
+    // hoisted input projection for all frames and both directions: Zx = X W_x + b
+    float* gates = infer ? (float*)(ws + p.ws_Zx) : (float*)(rs + p.res_gates);
+    const long gates_stride = infer ? (long)p.Zx_dir_elems : (long)(p.res_dir_stride / 4);
+    GemmArgs g = {};
+    g.A = x; g.B = W_x; g.C = gates; g.bias = (const float*)b;
+    g.M = (int)(T * B); g.N = 4 * p.n; g.K = p.n_in;
+    g.lda = p.n_in; g.ldb = 4 * n; g.ldc = 4 * n;
+    g.sAz = 0; g.sBz = (long)p.n_in * 4 * n; g.sCz = gates_stride; g.sbiasz = 4 * n; g.nz = p.D;
+    g.nseg = 1; g.a_kcontig = true; g.b_kcontig = false; g.in_bf16 = p.bf16; g.out_bf16 = false;
+    g.vecA = widest(g.lda, 0, 0, p.esz, 16);
+    g.vecB = widest(g.ldb, g.sBz, 0, p.esz, 4);
+    HIPCHK(launch_gemm(g, s));
+
+    FwdArgs a = {};
+    a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_f; a.T = p.T; a.ndir = p.D; a.write_gates = infer ? 0 : 1;
+    const size_t frag_dir = (size_t)p.nrt * p.nkc_f * 1024;
+    for (size_t tau = 0; tau < T; ++tau) {
+      for (size_t d = 0; d < D; ++d) {
+        const bool rev = bidir ? d == 1 : desc->direction == -1;
+        const size_t t = rev ? T - 1 - tau : tau;
+        FwdDir& fd = a.d[d];
+        fd.Wf = (const uint4*)(ws + p.ws_Wf + d * (size_t)p.ntile_f * 2 * p.nkc_f * 1024);
+        fd.hin = (const uint4*)(ws + ((tau & 1) ? p.ws_hfrag1 : p.ws_hfrag0) + d * frag_dir);
+        fd.hout = ws + ((tau & 1) ? p.ws_hfrag0 : p.ws_hfrag1) + d * frag_dir;
+        fd.gates = gates + d * gates_stride + t * B * 4 * n;
+        fd.hstate = hstate + d * B * n;
+        fd.cstate = cstate + d * B * n;
+        fd.y = (char*)y + (t * B * D * n + d * n) * p.esz;
+        fd.ldy = (long)(D * n);
+        fd.cs = c ? (float*)c + (d * T + t) * B * n : nullptr;
+        fd.hprev = infer ? nullptr : rs + d * p.res_dir_stride + p.res_hprev + t * B * n * p.esz;
+        fd.t = (int)t;
+      }
+      HIPCHK(launch_step_fwd(a, p.bf16, s));
+    }
+  }
+  if (hT) HIPCHK(launch_copy(hT, hstate, state_bytes, s));
+  if (cT) HIPCHK(launch_copy(cT, cstate, state_bytes, s));
+  return LSTM_OK;
+}
+
+int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, const void* W_h, const void* h0,
+            const void* c0, const int32_t* seq_lens, const void* y, const void* c, const void* reserve, const void* dy,
+            const void* dhT, const void* dcT, void* dx, void* dW_x, void* dW_h, void* db, void* dh0, void* dc0,
+            void* workspace, void* stream) {
+  Plan p;
+  int rc = make_plan(desc, bidir, &p);
+  if (rc) return rc;
+  if (!bidir && desc->direction != 1 && desc->direction != -1) return LSTM_ERR_DIRECTION;
+  if (desc->flags & LSTM_FLAG_INFERENCE) return LSTM_ERR_UNSUPPORTED;
+  if (!x || !W_x || !W_h || !c || !reserve || !dy || !dW_x || !dW_h || !db || !workspace) return LSTM_ERR_NULL;
+  const void* ptrs[] = {x, W_x, W_h, h0, c0, seq_lens, y, c, reserve, dy, dhT, dcT, dx, dW_x, dW_h, db, dh0, dc0, workspace};
+  for (const void* q : ptrs) if (misaligned(q)) return LSTM_ERR_ALIGN;
+  if (desc->workspace_bytes < p.workspace_bytes || desc->reserve_bytes < p.reserve_bytes) return LSTM_ERR_SIZE;
+  if ((rc = check_device())) return rc;
+
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)(((uintptr_t)workspace + kAlign - 1) / kAlign * kAlign);
+  const char* rs = (const char*)(((uintptr_t)reserve + kAlign - 1) / kAlign * kAlign);
+  const size_t n = p.n, B = p.B, D = p.D, T = p.T, n_in = p.n_in;
+  const int acc = (desc->flags & LSTM_FLAG_ACCUMULATE) ? 1 : 0;
+  float* Dh = (float*)(ws + p.ws_Dh);
+  float* Dc = (float*)(ws + p.ws_Dc);
+  const size_t state_bytes = D * B * n * 4;
+  if (B == 0 || T == 0) {          // no frames: parameter gradients are zero, state gradients pass through
+    if (!acc) {
+      HIPCHK(launch_fill_zero(dW_x, D * n_in * 4 * n * 4, s));
+      HIPCHK(launch_fill_zero(dW_h, D * n * 4 * n * 4, s));
+      HIPCHK(launch_fill_zero(db, D * 4 * n * 4, s));
+    }
+    if (B > 0) {
+      if (dh0) { if (dhT) HIPCHK(launch_copy(dh0, dhT, state_bytes, s)); else HIPCHK(launch_fill_zero(dh0, state_bytes, s)); }
+      if (dc0) { if (dcT) HIPCHK(launch_copy(dc0, dcT, state_bytes, s)); else HIPCHK(launch_fill_zero(dc0, state_bytes, s)); }
+    }
+    return LSTM_OK;
+  }
+  if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dh, state_bytes, s));
+  if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dc, state_bytes, s));
+  HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
+  HIPCHK(launch_fill_zero(ws + p.ws_dzfrag0, p.dzfrag_bytes, s));
+  HIPCHK(launch_fill_zero(ws + p.ws_dzfrag1, p.dzfrag_bytes, s));
+
+  BwdArgs a = {};
+  a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_b; a.T = p.T; a.ndir = p.D;
+  const size_t frag_dir = (size_t)p.nrt * p.nkc_b * 1024;
+  char* DZ = ws + p.ws_DZ;
+  for (long tau = (long)T - 1; tau >= -1; --tau) {
+    a.do_matmul = tau < (long)T - 1;
+    a.do_pointwise = tau >= 0;
+    for (size_t d = 0; d < D; ++d) {
+      const bool rev = bidir ? d == 1 : desc->direction == -1;
+      const long t = rev ? (long)T - 1 - tau : tau;            // frame of this step (out of range when tau == -1)
+      const long t_next = rev ? t - 1 : t + 1;                 // frame of the previous backward step
+      BwdDir& bd = a.d[d];
+      bd.Wb = (const uint4*)(ws + p.ws_Wb + d * (size_t)p.ntile_b * p.nkc_b * 1024);
+      bd.dzin = (const uint4*)(ws + (((tau + 1) & 1) ? p.ws_dzfrag1 : p.ws_dzfrag0) + d * frag_dir);
+      bd.dzout = ws + ((tau & 1) ? p.ws_dzfrag1 : p.ws_dzfrag0) + d * frag_dir;
+      bd.Dh = Dh + d * B * n;
+      bd.Dc = Dc + d * B * n;
+      bd.t = (int)t; bd.t_next = (int)t_next;
+      if (tau >= 0) {
+        const float* cs = (const float*)c + d * T * B * n;
+        const long tp = rev ? t + 1 : t - 1;                   // frame processed just before t in the forward pass
+        bd.gates = (const float*)(rs + d * p.res_dir_stride + p.res_gates) + t * B * 4 * n;
+        bd.cs = cs + t * B * n;
+        bd.cprev = (tp >= 0 && tp < (long)T) ? cs + tp * B * n : (c0 ? (const float*)c0 + d * B * n : nullptr);
+        bd.dy = (const char*)dy + (t * B * D * n + d * n) * p.esz;
+        bd.lddy = (long)(D * n);
+        bd.DZ = DZ + (d * p.DZ_dir_elems + t * B * 4 * n) * p.esz;
+      }
+    }
+    HIPCHK(launch_step_bwd(a, p.bf16, s));
+  }
+  if (dh0) HIPCHK(launch_copy(dh0, Dh, state_bytes, s));
+  if (dc0) HIPCHK(launch_copy(dc0, Dc, state_bytes, s));
+
+  const int TB = (int)(T * B);
+  if (dx) {                        // dX = sum over directions of DZ W_x^T
+    GemmArgs g = {};
+    g.A = DZ; g.B = W_x; g.C = dx;
+    g.M = TB; g.N = p.n_in; g.K = 4 * p.n;
+    g.lda = 4 * n; g.ldb = 4 * n; g.ldc = n_in; g.nz = 1;
+    g.nseg = p.D; g.sAseg = (long)p.DZ_dir_elems; g.sBseg = (long)(n_in * 4 * n);
+    g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = p.bf16; g.out_bf16 = p.bf16;
+    g.vecA = widest(g.lda, g.sAseg, 0, p.esz, 16);
+    g.vecB = widest(g.ldb, g.sBseg, 0, p.esz, 16);
+    HIPCHK(launch_gemm(g, s));
+  }
+  {                                // dW_x = X^T DZ, padded frames of X masked out
+    GemmArgs g = {};
+    g.A = x; g.B = DZ; g.C = dW_x;
+    g.M = p.n_in; g.N = 4 * p.n; g.K = TB;
+    g.lda = n_in; g.ldb = 4 * n; g.ldc = 4 * n;
+    g.sAz = 0; g.sBz = (long)p.DZ_dir_elems; g.sCz = (long)(n_in * 4 * n); g.nz = p.D; g.nseg = 1;
+    g.a_kcontig = false; g.b_kcontig = false; g.in_bf16 = p.bf16; g.out_bf16 = false; g.accumulate = acc;
+    g.lens = seq_lens; g.Bt = p.B; g.T = p.T;
+    g.vecA = widest(g.lda, 0, 0, p.esz, 4);
+    g.vecB = widest(g.ldb, g.sBz, 0, p.esz, 4);
+    HIPCHK(launch_gemm(g, s));
+    // dW_h = Hprev^T DZ
+    g.A = rs + p.res_hprev; g.C = dW_h; g.M = p.n; g.lda = n;
+    g.sAz = (long)(p.res_dir_stride / p.esz); g.sCz = (long)(n * 4 * n);
+    g.lens = nullptr;
+    g.vecA = widest(g.lda, g.sAz, 0, p.esz, 4);
+    HIPCHK(launch_gemm(g, s));
+  }
+  HIPCHK(launch_colsum(DZ, (float*)db, (float*)(ws + p.ws_colsum), TB, 4 * p.n, p.D, (long)p.DZ_dir_elems, p.bf16, acc, s));
+  return LSTM_OK;
+}
+
+}  // namespace
+}  // namespace lstm
+
+extern "C" {
+
+int lstm_query(const lstm_desc* desc, int bidirectional, size_t* reserve_bytes, size_t* workspace_bytes) {
+  lstm::Plan p;
+  int rc = lstm::make_plan(desc, bidirectional, &p);
+  if (rc) return rc;
+  if (!reserve_bytes || !workspace_bytes) return LSTM_ERR_NULL;
+  *reserve_bytes = (desc->flags & LSTM_FLAG_INFERENCE) ? 0 : p.reserve_bytes;
+  *workspace_bytes = p.workspace_bytes;
+  return LSTM_OK;
+}
+
+int lstm_fwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h, const void* b, const void* h0,
+             const void* c0, const int32_t* seq_lens, void* y, void* c, void* hT, void* cT, void* reserve, void* workspace,
+             void* stream) {
+  return lstm::run_fwd(desc, 0, x, W_x, W_h, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace, stream);
+}
+int blstm_fwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h, const void* b, const void* h0,
+              const void* c0, const int32_t* seq_lens, void* y, void* c, void* hT, void* cT, void* reserve, void* workspace,
+              void* stream) {
+  return lstm::run_fwd(desc, 1, x, W_x, W_h, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace, stream);
+}
+int lstm_bwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h, const void* h0, const void* c0,
+             const int32_t* seq_lens, const void* y, const void* c, const void* reserve, const void* dy, const void* dhT,
+             const void* dcT, void* dx, void* dW_x, void* dW_h, void* db, void* dh0, void* dc0, void* workspace,
+             void* stream) {
+  return lstm::run_bwd(desc, 0, x, W_x, W_h, h0, c0, seq_lens, y, c, reserve, dy, dhT, dcT, dx, dW_x, dW_h, db, dh0, dc0,
+                       workspace, stream);
+}
+int blstm_bwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h, const void* h0, const void* c0,
+              const int32_t* seq_lens, const void* y, const void* c, const void* reserve, const void* dy, const void* dhT,
+              const void* dcT, void* dx, void* dW_x, void* dW_h, void* db, void* dh0, void* dc0, void* workspace,
+              void* stream) {
+  return lstm::run_bwd(desc, 1, x, W_x, W_h, h0, c0, seq_lens, y, c, reserve, dy, dhT, dcT, dx, dW_x, dW_h, db, dh0, dc0,
+                       workspace, stream);
+}
+
+int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, int N, int K, const void* A, int64_t lda,
+              const void* B, int64_t ldb, void* C, int64_t ldc, const float* bias, int accumulate, const int32_t* lens,
+              int Bt, int T, void* stream) {
+  using namespace lstm;
+  if (!A || !B || !C) return LSTM_ERR_NULL;
+  if (M < 0 || N < 0 || K < 0 || lda < 1 || ldb < 1 || ldc < 1) return LSTM_ERR_DIM;
+  if ((out_bf16 && !in_bf16) || (!a_kcontig && b_kcontig) || (lens && (a_kcontig || Bt < 1)) || (accumulate && out_bf16))
+    return LSTM_ERR_UNSUPPORTED;
+  const size_t esz = in_bf16 ? 2 : 4;
+  if (((uintptr_t)A | (uintptr_t)B) & (esz - 1) || ((uintptr_t)C & (out_bf16 ? 1 : 3))) return LSTM_ERR_ALIGN;
+  int rc = check_device();
+  if (rc) return rc;
+  GemmArgs g = {};
+  g.A = A; g.B = B; g.C = C; g.bias = bias; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.nz = 1; g.nseg = 1; g.a_kcontig = a_kcontig; g.b_kcontig = b_kcontig; g.in_bf16 = in_bf16; g.out_bf16 = out_bf16;
+  g.accumulate = accumulate; g.lens = lens; g.Bt = Bt; g.T = T;
+  auto ptr_vec = [&](const void* p, int cap) { int v = cap; while (v > (int)esz && ((uintptr_t)p % v)) v >>= 1; return v; };
+  g.vecA = std::min(widest(lda, 0, 0, esz, a_kcontig ? 16 : 4), ptr_vec(A, a_kcontig ? 16 : 4));
+  g.vecB = std::min(widest(ldb, 0, 0, esz, b_kcontig ? 16 : 4), ptr_vec(B, b_kcontig ? 16 : 4));
+  if (launch_gemm(g, (hipStream_t)stream) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  return LSTM_OK;
+}
+
+const char* lstm_strerror(int status) {
+  switch (status) {
+    case LSTM_OK: return "ok";
+    case LSTM_ERR_NULL: return "a required pointer is NULL";
+    case LSTM_ERR_DIM: return "bad dimension";
+    case LSTM_ERR_DIRECTION: return "direction must be +1 or -1";
+    case LSTM_ERR_UNSUPPORTED: return "unsupported dtype or flag";
+    case LSTM_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case LSTM_ERR_SIZE: return "reserve or workspace too small (see lstm_query)";
+    case LSTM_ERR_HIP: return "HIP runtime error or device is not gfx950";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

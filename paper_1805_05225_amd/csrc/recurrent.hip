@@ -1,0 +1,350 @@
+// The recurrent part of the LSTM layer: what cannot leave the time loop.
+//
+// Forward step  (one launch per time step, both directions of a bidirectional layer in the same
+// launch):   z_t = Zx_t + h W_h ;  gates ;  c' = f c + i g ;  h' = o tanh(c') ;  sequence mask.
+// Backward step:  Dh = dz_{next} W_h^T  (the matrix product of the previous backward step's gate
+// gradients), then the gate gradients dz_t of this frame.
+//
+// Decomposition.  A work-group owns a few hidden units and ALL of their gate columns
+// (forward: 8 units = 32 columns; backward: 16 units), for 32 batch rows.  So the cell update
+// is local to the work-group and only h_t (forward) or dz_t (backward) crosses work-groups
+// between steps.  The small-M product runs on MFMA 16x16 tiles with the K axis split over the
+// four wavefronts, followed by a reduction through LDS and the pointwise epilogue.
+//
+// Operands are kept in "fragment order": the exact register image of an MFMA operand, one
+// 16-byte chunk per lane, so every operand load is one fully coalesced 1 KiB read per wavefront:
+//   chunk (tile, kc, lane = g*16 + r) element e  <->  row/col r of the 16-wide tile,
+//   k = kc*KC + g*E + e,  E = elements per 16 bytes, KC = 4E.
+// W_h is packed once per call; h_t / dz_t are written in this order by the step that makes them.
+#include "common.h"
+
+namespace lstm {
+namespace {
+
+template <typename T> struct Mma16;
+template <> struct Mma16<bf16_t> {
+  __device__ static f32x4 run(uint4 a, uint4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mma16<float> {
+  __device__ static f32x4 run(uint4 a, uint4 b, f32x4 c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    return c;
+  }
+};
+
+// element offset (in elements of T) of (row, k) inside a fragment-ordered buffer with nkc chunks per row tile
+template <typename T>
+__device__ __forceinline__ long frag_offset(int row, int k, int nkc) {
+  constexpr int E = Store<T>::kPerChunk, KC = 4 * E;
+  int rt = row >> 4, r = row & 15;
+  int kc = k / KC, rem = k - kc * KC;
+  int g = rem / E, e = rem - g * E;
+  return ((((long)rt * nkc + kc) * 64 + g * 16 + r) * E + e);
+}
+
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + __expf(-x)); }
+__device__ __forceinline__ float tanhf_(float x) { return 1.f - 2.f / (1.f + __expf(2.f * x)); }
+__device__ __forceinline__ int clamp_len(const int* lens, int b, int T) {
+  if (!lens) return T;
+  int L = lens[b];
+  return L < 0 ? 0 : (L > T ? T : L);
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward step
+template <typename T>
+__global__ __launch_bounds__(256) void step_fwd_kernel(FwdArgs a) {
+  __shared__ float red[4][32][33];
+  const FwdDir& d = a.d[blockIdx.z];
+  const int tile = blockIdx.x, rb = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nkc = a.nkc;
+
+  f32x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const uint4* hA0 = d.hin + ((long)(rb * 2 + 0) * nkc) * 64 + lane;
+  const uint4* hA1 = d.hin + ((long)(rb * 2 + 1) * nkc) * 64 + lane;
+  const uint4* wB0 = d.Wf + ((long)(tile * 2 + 0) * nkc) * 64 + lane;
+  const uint4* wB1 = d.Wf + ((long)(tile * 2 + 1) * nkc) * 64 + lane;
+#pragma unroll 4
+  for (int kc = wave; kc < nkc; kc += 4) {
+    uint4 a0 = hA0[(long)kc * 64], a1 = hA1[(long)kc * 64];
+    uint4 b0 = wB0[(long)kc * 64], b1 = wB1[(long)kc * 64];
+    acc[0][0] = Mma16<T>::run(a0, b0, acc[0][0]);
+    acc[0][1] = Mma16<T>::run(a0, b1, acc[0][1]);
+    acc[1][0] = Mma16<T>::run(a1, b0, acc[1][0]);
+    acc[1][1] = Mma16<T>::run(a1, b1, acc[1][1]);
+  }
+  // accumulator of a 16x16 block: lane holds column lane%16, rows 4*(lane/16) + v
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave][i * 16 + 4 * (lane >> 4) + v][j * 16 + (lane & 15)] = acc[i][j][v];
+  __syncthreads();
+
+  const int r = tid >> 3, u = tid & 7;
+  const int b = rb * 32 + r, j = tile * 8 + u;
+  if (b >= a.B || j >= a.n) return;
+  float z[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) z[q] = red[0][r][q * 8 + u] + red[1][r][q * 8 + u] + red[2][r][q * 8 + u] + red[3][r][q * 8 + u];
+
+  const int n = a.n;
+  const bool valid = d.t < clamp_len(a.lens, b, a.T);
+  float* gp = d.gates + (long)b * 4 * n + j;
+  const float c_prev = d.cstate[(long)b * n + j];
+  const float h_prev = d.hstate[(long)b * n + j];
+  float h_new = h_prev, c_new = c_prev, yv = 0.f;
+  if (valid) {
+    const float gi = sigmoidf_(z[0] + gp[0]);
+    const float gf = sigmoidf_(z[1] + gp[n]);
+    const float gg = tanhf_(z[2] + gp[2 * n]);
+    const float go = sigmoidf_(z[3] + gp[3 * n]);
+    c_new = gf * c_prev + gi * gg;
+    h_new = go * tanhf_(c_new);
+    yv = h_new;
+    if (a.write_gates) { gp[0] = gi; gp[n] = gf; gp[2 * n] = gg; gp[3 * n] = go; }
+    d.cstate[(long)b * n + j] = c_new;
+    d.hstate[(long)b * n + j] = h_new;
+  }
+  Store<T>::store(d.hout, frag_offset<T>(b, j, nkc), h_new);
+  Store<T>::store(d.y, (long)b * d.ldy + j, yv);
+  if (d.cs) d.cs[(long)b * n + j] = c_new;
+  if (d.hprev) Store<T>::store(d.hprev, (long)b * n + j, h_prev);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward step
+template <typename T>
+__global__ __launch_bounds__(256) void step_bwd_kernel(BwdArgs a) {
+  __shared__ float red[4][32][17];
+  const BwdDir& d = a.d[blockIdx.z];
+  const int tile = blockIdx.x, rb = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nkc = a.nkc, n = a.n;
+
+  if (a.do_matmul) {
+    f32x4 acc[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+    const uint4* A0 = d.dzin + ((long)(rb * 2 + 0) * nkc) * 64 + lane;
+    const uint4* A1 = d.dzin + ((long)(rb * 2 + 1) * nkc) * 64 + lane;
+    const uint4* Bp = d.Wb + ((long)tile * nkc) * 64 + lane;
+#pragma unroll 4
+    for (int kc = wave; kc < nkc; kc += 4) {
+      uint4 a0 = A0[(long)kc * 64], a1 = A1[(long)kc * 64], b0 = Bp[(long)kc * 64];
+      acc[0] = Mma16<T>::run(a0, b0, acc[0]);
+      acc[1] = Mma16<T>::run(a1, b0, acc[1]);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave][i * 16 + 4 * (lane >> 4) + v][lane & 15] = acc[i][v];
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int idx = tid + 256 * p;
+    const int r = idx >> 4, u = idx & 15;
+    const int b = rb * 32 + r, j = tile * 16 + u;
+    if (b >= a.B || j >= n) continue;
+    const int L = clamp_len(a.lens, b, a.T);
+    float Dh = d.Dh[(long)b * n + j];
+    if (a.do_matmul && d.t_next < L) Dh = red[0][r][u] + red[1][r][u] + red[2][r][u] + red[3][r][u];
+    d.Dh[(long)b * n + j] = Dh;
+    if (!a.do_pointwise) continue;
+    float dz[4] = {0.f, 0.f, 0.f, 0.f};
+    if (d.t < L) {
+      const float* gp = d.gates + (long)b * 4 * n + j;
+      const float gi = gp[0], gf = gp[n], gg = gp[2 * n], go = gp[3 * n];
+      const float tc = tanhf_(d.cs[(long)b * n + j]);
+      const float c_prev = d.cprev ? d.cprev[(long)b * n + j] : 0.f;
+      const float dh = Store<T>::load(d.dy, (long)b * d.lddy + j) + Dh;
+      const float dc = d.Dc[(long)b * n + j] + dh * go * (1.f - tc * tc);
+      d.Dc[(long)b * n + j] = dc * gf;
+      dz[0] = dc * gg * gi * (1.f - gi);
+      dz[1] = dc * c_prev * gf * (1.f - gf);
+      dz[2] = dc * gi * (1.f - gg * gg);
+      dz[3] = dh * tc * go * (1.f - go);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      Store<T>::store(d.DZ, (long)b * 4 * n + q * n + j, dz[q]);
+      Store<T>::store(d.dzout, frag_offset<T>(b, q * n + j, nkc), dz[q]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// packing
+// forward: chunk index = ((dir*ntiles + tile)*2 + ct)*nkc + kc)*64 + lane ; column ct*16 + (lane%16) of the
+// work-group's 32 columns is gate q = col/8, unit tile*8 + col%8.
+template <typename T>
+__global__ void pack_wh_fwd_kernel(const T* W, uint4* out, int n, int nkc, long total) {
+  constexpr int E = Store<T>::kPerChunk, KC = 4 * E;
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  int lane = idx & 63;
+  long rest = idx >> 6;
+  int kc = rest % nkc; rest /= nkc;
+  int ct = rest & 1; rest >>= 1;
+  int ntiles = (n + 7) / 8;
+  int tile = rest % ntiles;
+  int dir = rest / ntiles;
+  int col = ct * 16 + (lane & 15), g = lane >> 4;
+  int q = col >> 3, unit = tile * 8 + (col & 7);
+  const T* Wd = W + (long)dir * n * 4 * n;
+  T v[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    int k = kc * KC + g * E + e;
+    v[e] = (k < n && unit < n) ? Wd[(long)k * 4 * n + q * n + unit] : (T)0.f;
+  }
+  out[idx] = *(uint4*)v;
+}
+// backward: chunk index = ((dir*ntiles + tile)*nkc + kc)*64 + lane ; column lane%16 = unit tile*16 + c,
+// k runs over the 4n gate columns: element = W_h[unit][k]
+template <typename T>
+__global__ void pack_wh_bwd_kernel(const T* W, uint4* out, int n, int nkc, long total) {
+  constexpr int E = Store<T>::kPerChunk, KC = 4 * E;
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  int lane = idx & 63;
+  long rest = idx >> 6;
+  int kc = rest % nkc; rest /= nkc;
+  int ntiles = (n + 15) / 16;
+  int tile = rest % ntiles;
+  int dir = rest / ntiles;
+  int unit = tile * 16 + (lane & 15), g = lane >> 4;
+  const T* Wd = W + (long)dir * n * 4 * n;
+  T v[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    int k = kc * KC + g * E + e;
+    v[e] = (k < 4 * n && unit < n) ? Wd[(long)unit * 4 * n + k] : (T)0.f;
+  }
+  out[idx] = *(uint4*)v;
+}
+// state: chunk index = ((dir*nrt + rt)*nkc + kc)*64 + lane
+template <typename T>
+__global__ void pack_state_kernel(const float* h, uint4* f0, uint4* f1, int B, int n, int nkc, int nrt, long total) {
+  constexpr int E = Store<T>::kPerChunk, KC = 4 * E;
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  int lane = idx & 63;
+  long rest = idx >> 6;
+  int kc = rest % nkc; rest /= nkc;
+  int rt = rest % nrt;
+  int dir = rest / nrt;
+  int row = rt * 16 + (lane & 15), g = lane >> 4;
+  T v[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    int k = kc * KC + g * E + e;
+    v[e] = (row < B && k < n) ? (T)h[((long)dir * B + row) * n + k] : (T)0.f;
+  }
+  f0[idx] = *(uint4*)v;
+  f1[idx] = *(uint4*)v;
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, size_t nwords) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < nwords; i += stride) p[i] = 0u;
+}
+__global__ void copy_kernel(uint32_t* dst, const uint32_t* src, size_t nwords) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < nwords; i += stride) dst[i] = src[i];
+}
+
+// column sums in two deterministic passes: partial sums over row slices, then a sum over slices
+constexpr int kColsumSplit = 64;
+template <typename T>
+__global__ void colsum_part_kernel(const T* DZ, float* part, int rows, int ncols, long sDZ) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x, sp = blockIdx.y, dir = blockIdx.z;
+  if (c >= ncols) return;
+  int per = (rows + kColsumSplit - 1) / kColsumSplit;
+  int r0 = sp * per, r1 = min(rows, r0 + per);
+  const T* p = DZ + dir * sDZ;
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) s += (float)p[(long)r * ncols + c];
+  part[((long)dir * kColsumSplit + sp) * ncols + c] = s;
+}
+__global__ void colsum_final_kernel(const float* part, float* db, int ncols, int accumulate) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x, dir = blockIdx.y;
+  if (c >= ncols) return;
+  float s = 0.f;
+  for (int sp = 0; sp < kColsumSplit; ++sp) s += part[((long)dir * kColsumSplit + sp) * ncols + c];
+  float* o = db + (long)dir * ncols + c;
+  *o = accumulate ? *o + s : s;
+}
+
+}  // namespace
+
+hipError_t launch_step_fwd(const FwdArgs& a, bool bf16, hipStream_t s) {
+  dim3 grid(cdiv(a.n, 8), cdiv(a.B, 32), a.ndir), block(256);
+  if (bf16) hipLaunchKernelGGL(step_fwd_kernel<bf16_t>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(step_fwd_kernel<float>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s) {
+  dim3 grid(cdiv(a.n, 16), cdiv(a.B, 32), a.ndir), block(256);
+  if (bf16) hipLaunchKernelGGL(step_bwd_kernel<bf16_t>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(step_bwd_kernel<float>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_pack_wh_fwd(const void* W, uint4* Wf, int n, int nkc, int ndir, bool bf16, hipStream_t s) {
+  long total = (long)ndir * cdiv(n, 8) * 2 * nkc * 64;
+  dim3 grid(cdiv(total, 256)), block(256);
+  if (bf16) hipLaunchKernelGGL(pack_wh_fwd_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)W, Wf, n, nkc, total);
+  else hipLaunchKernelGGL(pack_wh_fwd_kernel<float>, grid, block, 0, s, (const float*)W, Wf, n, nkc, total);
+  return hipGetLastError();
+}
+hipError_t launch_pack_wh_bwd(const void* W, uint4* Wb, int n, int nkc, int ndir, bool bf16, hipStream_t s) {
+  long total = (long)ndir * cdiv(n, 16) * nkc * 64;
+  dim3 grid(cdiv(total, 256)), block(256);
+  if (bf16) hipLaunchKernelGGL(pack_wh_bwd_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)W, Wb, n, nkc, total);
+  else hipLaunchKernelGGL(pack_wh_bwd_kernel<float>, grid, block, 0, s, (const float*)W, Wb, n, nkc, total);
+  return hipGetLastError();
+}
+hipError_t launch_pack_state(const float* h, uint4* f0, uint4* f1, int B, int n, int nkc, int nrt, int ndir, bool bf16,
+                             hipStream_t s) {
+  long total = (long)ndir * nrt * nkc * 64;
+  dim3 grid(cdiv(total, 256)), block(256);
+  if (bf16) hipLaunchKernelGGL(pack_state_kernel<bf16_t>, grid, block, 0, s, h, f0, f1, B, n, nkc, nrt, total);
+  else hipLaunchKernelGGL(pack_state_kernel<float>, grid, block, 0, s, h, f0, f1, B, n, nkc, nrt, total);
+  return hipGetLastError();
+}
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  size_t nw = bytes / 4;
+  int blocks = (int)((nw + 255) / 256 > 4096 ? 4096 : (nw + 255) / 256);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint32_t*)p, nw);
+  return hipGetLastError();
+}
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  size_t nw = bytes / 4;
+  int blocks = (int)((nw + 255) / 256 > 4096 ? 4096 : (nw + 255) / 256);
+  hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, s, (uint32_t*)dst, (const uint32_t*)src, nw);
+  return hipGetLastError();
+}
+hipError_t launch_colsum(const void* DZ, float* db, float* part, int rows, int ncols, int ndir, long sDZ, bool bf16,
+                         int accumulate, hipStream_t s) {
+  dim3 grid(cdiv(ncols, 256), kColsumSplit, ndir), block(256);
+  if (bf16) hipLaunchKernelGGL(colsum_part_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)DZ, part, rows, ncols, sDZ);
+  else hipLaunchKernelGGL(colsum_part_kernel<float>, grid, block, 0, s, (const float*)DZ, part, rows, ncols, sDZ);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3(cdiv(ncols, 256), ndir), block, 0, s, part, db, ncols, accumulate);
+  return hipGetLastError();
+}
+
+}  // namespace lstm

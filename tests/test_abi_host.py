@@ -1,0 +1,117 @@
+"""Host-side tests of the C ABI: the library loads, exports every declared symbol, and reports
+every argument error before touching the HIP runtime (so they all run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_1805_05225_amd import binding as Bn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 0x10000  # an aligned fake device pointer: validation must fail before anything dereferences it
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "lstm_abi.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", hdr))
+    assert declared == set(Bn.EXPORTS)
+    for name in declared:
+        assert hasattr(Bn.lib, name)
+
+
+def test_desc_layout_matches_header():
+    assert ctypes.sizeof(Bn.LstmDesc) == 8 * 4 + 2 * 8
+
+
+def _fwd(desc, fn=None, **over):
+    a = dict(x=P, W_x=P, W_h=P, b=None, h0=None, c0=None, lens=None, y=P, c=P, hT=None, cT=None, reserve=P, ws=P)
+    a.update(over)
+    fn = fn or Bn.lib.lstm_fwd
+    return fn(ctypes.byref(desc) if desc is not None else None, a["x"], a["W_x"], a["W_h"], a["b"], a["h0"], a["c0"], a["lens"],
+              a["y"], a["c"], a["hT"], a["cT"], a["reserve"], a["ws"], None)
+
+
+def _bwd(desc, fn=None, **over):
+    a = dict(x=P, W_x=P, W_h=P, h0=None, c0=None, lens=None, y=P, c=P, reserve=P, dy=P, dhT=None, dcT=None, dx=P, dW_x=P,
+             dW_h=P, db=P, dh0=None, dc0=None, ws=P)
+    a.update(over)
+    fn = fn or Bn.lib.lstm_bwd
+    return fn(ctypes.byref(desc) if desc is not None else None, *[a[k] for k in (
+        "x", "W_x", "W_h", "h0", "c0", "lens", "y", "c", "reserve", "dy", "dhT", "dcT", "dx", "dW_x", "dW_h", "db", "dh0",
+        "dc0", "ws")], None)
+
+
+def good_desc(**kw):
+    d = Bn.make_desc(kw.pop("T", 5), kw.pop("B", 3), kw.pop("n_in", 4), kw.pop("n", 6), kw.pop("dtype", 0),
+                     kw.pop("direction", 1), kw.pop("flags", 0))
+    r, w = Bn.query(d, kw.pop("bidir", False))
+    d.reserve_bytes, d.workspace_bytes = r, w
+    return d
+
+
+def test_query_sizes_grow_and_cover_bidirectional():
+    d = Bn.make_desc(10, 4, 8, 16, 0)
+    r1, w1 = Bn.query(d, False)
+    r2, w2 = Bn.query(d, True)
+    assert r2 > r1 > 10 * 4 * 4 * 16 * 4 and w2 > w1 > 0
+    d0 = Bn.make_desc(0, 0, 8, 16, 1)
+    r0, w0 = Bn.query(d0, True)
+    assert r0 > 0 and w0 > 0
+
+
+def test_null_and_dim_errors():
+    assert _fwd(None) == -1
+    for field, val in (("T", -1), ("B", -2), ("n", 0), ("n_in", 0)):
+        d = good_desc()
+        setattr(d, field, val)
+        assert _fwd(d) == -2 and _bwd(d) == -2
+    d = good_desc()
+    assert _fwd(d, x=None) == -1 and _fwd(d, y=None) == -1 and _fwd(d, reserve=None) == -1 and _fwd(d, ws=None) == -1
+    assert _bwd(d, dy=None) == -1 and _bwd(d, dW_h=None) == -1 and _bwd(d, c=None) == -1
+    big = Bn.make_desc(1 << 20, 1 << 20, 4, 4, 0)
+    assert _fwd(big) == -2
+
+
+def test_direction_dtype_flag_errors():
+    d = good_desc()
+    d.direction = 0
+    assert _fwd(d) == -3 and _bwd(d) == -3
+    assert _fwd(d, fn=Bn.lib.blstm_fwd) in (-6, -7)          # blstm ignores direction; sizes are the uni ones
+    d = good_desc(); d.dtype = 7
+    assert _fwd(d) == -4
+    d = good_desc(); d.flags = 64
+    assert _fwd(d) == -4
+    d = good_desc(); d.reserved = 1
+    assert _fwd(d) == -4
+    d = good_desc(flags=Bn.FLAG_INFERENCE)
+    assert _bwd(d) == -4                                       # nothing was saved: backward is impossible
+
+
+def test_alignment_and_size_errors():
+    d = good_desc()
+    assert _fwd(d, x=P + 4) == -5 and _fwd(d, hT=P + 8) == -5 and _bwd(d, dcT=P + 2) == -5
+    d.workspace_bytes -= 1
+    assert _fwd(d) == -6 and _bwd(d) == -6
+    d = good_desc(); d.reserve_bytes = 16
+    assert _fwd(d) == -6
+    d = good_desc(bidir=False)
+    assert _fwd(d, fn=Bn.lib.blstm_fwd) == -6                  # bidirectional needs more than the uni sizes
+
+
+def test_empty_batch_is_a_noop_and_inference_needs_no_reserve():
+    d = good_desc(B=0)
+    assert _fwd(d) == 0
+    d = good_desc(flags=Bn.FLAG_INFERENCE)
+    r, w = Bn.query(d, False)
+    assert r == 0
+    if not torch.cuda.is_available():
+        assert _fwd(d, reserve=None, c=None) == -7             # valid call, but no gfx950 device here
+
+
+def test_strerror():
+    for s in range(0, -8, -1):
+        assert Bn.strerror(s) and "unknown" not in Bn.strerror(s)
+    assert "unknown" in Bn.strerror(-99)

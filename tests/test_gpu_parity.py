@@ -1,0 +1,294 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on identical inputs.
+
+Tolerances (relative to the largest oracle magnitude of each tensor): 1e-4 for float storage,
+2e-2 for bfloat16 storage with float state.  The oracle always gets the storage-rounded inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from oracle import lstm_oracle as O
+from paper_1805_05225_amd import synth
+from tests.gpu_util import TOL, check, dev, host, tdtype
+
+Bn = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _binding():
+    global Bn
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1805_05225_amd import binding
+    Bn = binding
+    yield
+
+
+def rnd_case(rng, T, B, n_in, n, D, lens, dt, scale=0.3, with_state=True, with_bias=True):
+    """Random layer problem with every optional input present; values pre-rounded to the storage type."""
+    def r(a):
+        t = torch.from_numpy(a).to(torch.float32)
+        return (t.to(torch.bfloat16).to(torch.float32) if dt == "bf16" else t).numpy().astype(np.float64)
+    c = dict(x=r(rng.standard_normal((T, B, n_in))), W_x=r(rng.uniform(-scale, scale, (D, n_in, 4 * n))),
+             W_h=r(rng.uniform(-scale, scale, (D, n, 4 * n))), lens=np.asarray(lens, dtype=np.int32),
+             dy=r(rng.standard_normal((T, B, D * n))))
+    f32 = lambda a: a.astype(np.float32).astype(np.float64)
+    c["b"] = f32(rng.uniform(-scale, scale, (D, 4 * n))) if with_bias else None
+    for k in ("h0", "c0", "dhT", "dcT"):
+        c[k] = f32(rng.standard_normal((D, B, n)) * 0.5) if with_state else None
+    return c
+
+
+def run_gpu(c, dt, bidir, direction=1, x_override=None, dy_override=None):
+    sq = (lambda a: a) if bidir else (lambda a: None if a is None else a[0])
+    x = dev(c["x"] if x_override is None else x_override, dt)
+    dy = dev(c["dy"] if dy_override is None else dy_override, dt)
+    Wx, Wh = dev(sq(c["W_x"]), dt), dev(sq(c["W_h"]), dt)
+    b, h0, c0 = dev(sq(c["b"])), dev(sq(c["h0"])), dev(sq(c["c0"]))
+    dhT, dcT = dev(sq(c["dhT"])), dev(sq(c["dcT"]))
+    lens = dev(c["lens"]) if c["lens"] is not None else None
+    f = Bn.forward(x, Wx, Wh, b, h0, c0, lens, bidirectional=bidir, direction=direction)
+    g = Bn.backward(f, x, Wx, Wh, h0, c0, lens, dy, dhT, dcT)
+    torch.cuda.synchronize()
+    return f, g
+
+
+def run_oracle(c, bidir, direction=1):
+    if bidir:
+        f = O.blstm_fwd(c["x"], c["W_x"], c["W_h"], c["b"], c["h0"], c["c0"], c["lens"])
+        g = O.blstm_bwd(c["x"], c["W_x"], c["W_h"], c["b"], c["h0"], c["c0"], c["lens"], c["dy"], c["dhT"], c["dcT"])
+    else:
+        z = lambda a: None if a is None else a[0]
+        f = O.lstm_fwd(c["x"], c["W_x"][0], c["W_h"][0], z(c["b"]), z(c["h0"]), z(c["c0"]), c["lens"], direction)
+        g = O.lstm_bwd(c["x"], c["W_x"][0], c["W_h"][0], z(c["b"]), z(c["h0"]), z(c["c0"]), c["lens"], direction, c["dy"],
+                       z(c["dhT"]), z(c["dcT"]))
+    return f, g
+
+
+def compare(f, g, fo, go, tol):
+    for name, got, ref in (("y", f["y"], fo[0]), ("c", f["c"], fo[1]), ("hT", f["hT"], fo[2]), ("cT", f["cT"], fo[3]),
+                           ("dx", g["dx"], go[0]), ("dW_x", g["dW_x"], go[1]), ("dW_h", g["dW_h"], go[2]),
+                           ("db", g["db"], go[3]), ("dh0", g["dh0"], go[4]), ("dc0", g["dc0"], go[5])):
+        check(name, got, ref, tol)
+
+
+# ---- the hoisted GEMM by itself -----------------------------------------------------------------------
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("M,N,K", [(130, 140, 70), (257, 129, 620), (5, 7, 3), (256, 256, 256)])
+def test_gemm_layouts(dt, M, N, K):
+    rng = np.random.default_rng(M * 1000 + N + K)
+    td = tdtype(dt)
+    A = torch.from_numpy(rng.standard_normal((M, K))).to(td)
+    B = torch.from_numpy(rng.standard_normal((K, N))).to(td)
+    bias = torch.from_numpy(rng.standard_normal(N)).float()
+    ref = A.double() @ B.double()
+    tol = 1e-5 if dt == "f32" else 1e-5          # inputs are exact in both cases; only accumulation order differs
+    Ad, Bd = A.cuda(), B.cuda()
+    print("  gemm", dt, M, N, K, flush=True)
+    C = Bn.gemm(Ad, Bd, a_kcontig=True, b_kcontig=False, M=M, N=N, K=K, bias=bias.cuda())
+    check("NN", C, (ref + bias.double()).numpy(), tol)
+    C = Bn.gemm(Ad, Bd.t().contiguous(), a_kcontig=True, b_kcontig=True, M=M, N=N, K=K)
+    check("NT", C, ref.numpy(), tol)
+    C0 = torch.from_numpy(rng.standard_normal((M, N))).float().cuda()
+    C = Bn.gemm(Ad.t().contiguous(), Bd, a_kcontig=False, b_kcontig=False, M=M, N=N, K=K, C=C0.clone(), accumulate=True)
+    check("TN+acc", C, (ref + C0.cpu().double()).numpy(), tol)
+    if dt == "bf16":
+        C = Bn.gemm(Ad, Bd.t().contiguous(), a_kcontig=True, b_kcontig=True, M=M, N=N, K=K, out_dtype=torch.bfloat16)
+        check("NT->bf16", C, ref.numpy(), 1e-2)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_gemm_frame_mask_ignores_nan_rows(dt):
+    rng = np.random.default_rng(3)
+    T, Bt, M, N = 9, 5, 37, 45
+    lens = np.array([9, 0, 4, 7, 1], dtype=np.int32)
+    td = tdtype(dt)
+    X = torch.from_numpy(rng.standard_normal((T * Bt, M))).to(td)
+    DZ = torch.from_numpy(rng.standard_normal((T * Bt, N))).to(td)
+    valid = (np.arange(T)[:, None] < lens[None, :]).reshape(-1)
+    Xn = X.clone()
+    Xn[torch.from_numpy(~valid)] = float("nan")
+    ref = (X.double() * torch.from_numpy(valid)[:, None]).t() @ DZ.double()
+    C = Bn.gemm(Xn.cuda(), DZ.cuda(), a_kcontig=False, b_kcontig=False, M=M, N=N, K=T * Bt, lens=torch.from_numpy(lens).cuda(),
+                Bt=Bt, T=T)
+    check("masked TN", C, ref.numpy(), 1e-5)
+
+
+# ---- small odd shapes, every optional input, both dtypes ------------------------------------------------
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("direction", [1, -1])
+def test_lstm_small_odd_shapes(dt, direction):
+    rng = np.random.default_rng(42 + direction)
+    c = rnd_case(rng, T=7, B=5, n_in=7, n=20, D=1, lens=[7, 0, 3, 5, 1], dt=dt)
+    print("  lstm small", dt, direction, flush=True)
+    f, g = run_gpu(c, dt, False, direction)
+    fo, go = run_oracle(c, False, direction)
+    compare(f, g, fo, go, TOL[dt])
+    assert (host(f["y"])[3:, 2] == 0).all() and (host(g["dx"])[:, 1] == 0).all()
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_blstm_small_odd_shapes(dt):
+    rng = np.random.default_rng(43)
+    c = rnd_case(rng, T=9, B=35, n_in=12, n=36, D=2, lens=list(rng.integers(0, 10, 35)), dt=dt)
+    c["lens"][0] = 9
+    print("  blstm small", dt, flush=True)
+    f, g = run_gpu(c, dt, True)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL[dt])
+
+
+def test_optional_inputs_null_and_T1_B1():
+    rng = np.random.default_rng(44)
+    c = rnd_case(rng, T=1, B=1, n_in=3, n=5, D=1, lens=None, dt="f32", with_state=False, with_bias=False)
+    c["lens"] = None
+    f, g = run_gpu(c, "f32", False, 1)
+    fo, go = run_oracle(c, False, 1)
+    compare(f, g, fo, go, TOL["f32"])
+
+
+# ---- padding invariance on the GPU: NaN in every padded frame of x and dy ---------------------------------
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_padding_nan_never_reaches_results(dt):
+    rng = np.random.default_rng(45)
+    lens = [6, 2, 0, 4]
+    c = rnd_case(rng, T=8, B=4, n_in=10, n=24, D=2, lens=lens, dt=dt)
+    xn, dyn = c["x"].copy(), c["dy"].copy()
+    for b, L in enumerate(lens):
+        xn[L:, b] = np.nan
+        dyn[L:, b] = np.nan
+    f, g = run_gpu(c, dt, True, x_override=xn, dy_override=dyn)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL[dt])
+
+
+# ---- composition properties on the GPU ----------------------------------------------------------------------
+def test_blstm_equals_two_lstm_and_stepping_equals_sequence():
+    rng = np.random.default_rng(46)
+    dt = "f32"
+    c = rnd_case(rng, T=6, B=3, n_in=9, n=16, D=2, lens=[6, 4, 5], dt=dt)
+    f, g = run_gpu(c, dt, True)
+    for d, direction in enumerate((1, -1)):
+        c1 = {k: (v[d:d + 1] if k in ("W_x", "W_h", "b", "h0", "c0", "dhT", "dcT") else v) for k, v in c.items()}
+        c1["dy"] = c["dy"][:, :, d * 16:(d + 1) * 16]
+        f1, g1 = run_gpu(c1, dt, False, direction)
+        assert torch.equal(f["y"][:, :, d * 16:(d + 1) * 16], f1["y"]) and torch.equal(f["hT"][d], f1["hT"])
+        assert torch.equal(g["dW_h"][d], g1["dW_h"]) and torch.equal(g["dh0"][d], g1["dh0"])
+    # stepping: T calls with T = 1 in inference mode, state fed back
+    x = dev(c["x"], dt)
+    Wx, Wh, b = dev(c["W_x"][0], dt), dev(c["W_h"][0], dt), dev(c["b"][0])
+    h, cc = dev(c["h0"][0]), dev(c["c0"][0])
+    full = Bn.forward(x, Wx, Wh, b, h, cc, None, bidirectional=False, direction=1)
+    ys = []
+    for t in range(6):
+        s = Bn.forward(x[t:t + 1].contiguous(), Wx, Wh, b, h, cc, None, bidirectional=False, direction=1,
+                       flags=Bn.FLAG_INFERENCE, want_c=False)
+        h, cc = s["hT"], s["cT"]
+        ys.append(s["y"][0])
+    torch.cuda.synchronize()
+    assert torch.equal(torch.stack(ys), full["y"]) and torch.equal(h, full["hT"]) and torch.equal(cc, full["cT"])
+
+
+def test_accumulate_flag_adds_into_gradients():
+    rng = np.random.default_rng(47)
+    c = rnd_case(rng, T=5, B=4, n_in=6, n=8, D=1, lens=[5, 3, 4, 1], dt="f32")
+    x, dy = dev(c["x"], "f32"), dev(c["dy"], "f32")
+    Wx, Wh, b = dev(c["W_x"][0], "f32"), dev(c["W_h"][0], "f32"), dev(c["b"][0])
+    lens = dev(c["lens"])
+    f = Bn.forward(x, Wx, Wh, b, None, None, lens, bidirectional=False)
+    g = Bn.backward(f, x, Wx, Wh, None, None, lens, dy)
+    acc = (torch.ones_like(g["dW_x"]), torch.full_like(g["dW_h"], 2.0), torch.full_like(g["db"], 3.0))
+    g2 = Bn.backward(f, x, Wx, Wh, None, None, lens, dy, accumulate_into=acc)
+    torch.cuda.synchronize()
+    assert torch.allclose(g2["dW_x"], g["dW_x"] + 1, atol=1e-5) and torch.allclose(g2["dW_h"], g["dW_h"] + 2, atol=1e-5)
+    assert torch.allclose(g2["db"], g["db"] + 3, atol=1e-5)
+
+
+# ---- the benchmark configurations ------------------------------------------------------------------------------
+def _config_case(inp, layer=0):
+    L = inp["layers"][layer]
+    D = inp["D"]
+    return dict(x=inp["x"].astype(np.float64), W_x=L["W_x"].astype(np.float64), W_h=L["W_h"].astype(np.float64),
+                b=L["b"].astype(np.float64), h0=None, c0=None, dhT=None, dcT=None, lens=inp["seq_lens"],
+                dy=inp["dy"].astype(np.float64))
+
+
+def test_config1_unidirectional_f32():
+    inp = synth.make(1)
+    c = _config_case(inp)
+    f, g = run_gpu(c, "f32", False, 1)
+    fo, go = run_oracle(c, False, 1)
+    compare(f, g, fo, go, TOL["f32"])
+
+
+def test_config2_blstm_f32_full_size():
+    inp = synth.make(2)
+    c = _config_case(inp)
+    print("  config 2: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
+    f, g = run_gpu(c, "f32", True)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL["f32"])
+
+
+def _stack_gpu(inp, dt):
+    lens = dev(inp["seq_lens"])
+    cur = dev(inp["x"], dt)
+    saved = []
+    ws = None
+    for L in inp["layers"]:
+        Wx, Wh, b = dev(L["W_x"], dt), dev(L["W_h"], dt), dev(L["b"])
+        f = Bn.forward(cur, Wx, Wh, b, None, None, lens, bidirectional=True, workspace=ws, want_state=False)
+        ws = f["workspace"]
+        saved.append((cur, Wx, Wh, f))
+        cur = f["y"]
+    y = cur
+    d = dev(inp["dy"], dt)
+    grads = [None] * len(saved)
+    for k in range(len(saved) - 1, -1, -1):
+        xin, Wx, Wh, f = saved[k]
+        g = Bn.backward(f, xin, Wx, Wh, None, None, lens, d, want_dstate=False)
+        grads[k] = g
+        d = g["dx"]
+    torch.cuda.synchronize()
+    return y, d, grads
+
+
+@pytest.mark.parametrize("k,over", [(3, dict(layers=2, len_lo=5, len_hi=24)), (4, dict(layers=2, len_lo=10, len_hi=40, B=32))])
+def test_bf16_stack_reduced(k, over):
+    inp = synth.make(k, **over)
+    print("  config %d reduced: T=%d layers=%d" % (k, inp["T"], len(inp["layers"])), flush=True)
+    y, dx, grads = _stack_gpu(inp, "bf16")
+    layers = [{kk: v.astype(np.float64) for kk, v in L.items()} for L in inp["layers"]]
+    acts, yo = O.blstm_stack_fwd(inp["x"].astype(np.float64), layers, inp["seq_lens"])
+    dxo, go = O.blstm_stack_bwd(acts, layers, inp["seq_lens"], inp["dy"].astype(np.float64))
+    tol = TOL["bf16"]
+    check("y", y, yo, tol)
+    check("dx", dx, dxo, tol)
+    for l, (g, r) in enumerate(zip(grads, go)):
+        check("dW_x%d" % l, g["dW_x"], r[0], tol)
+        check("dW_h%d" % l, g["dW_h"], r[1], tol)
+        check("db%d" % l, g["db"], r[2], tol)
+
+
+def test_config5_decoder_stepping_bf16():
+    inp = synth.make(5)
+    L = inp["layers"][0]
+    rng = np.random.default_rng(5)
+    Wx, Wh = dev(L["W_x"][0], "bf16"), dev(L["W_h"][0], "bf16")
+    h = torch.zeros(768, 1000, device="cuda")
+    c = torch.zeros(768, 1000, device="cuda")
+    ho, co = np.zeros((768, 1000)), np.zeros((768, 1000))
+    ws = None
+    for step in range(4):
+        xt = torch.from_numpy(rng.standard_normal((1, 768, 2620))).to(torch.bfloat16)
+        s = Bn.forward(xt.cuda(), Wx, Wh, None, h, c, None, bidirectional=False, flags=Bn.FLAG_INFERENCE, workspace=ws,
+                       want_c=False)
+        ws = s["workspace"]
+        h, c = s["hT"], s["cT"]
+        _, _, ho, co = O.lstm_fwd(xt.float().numpy().astype(np.float64), L["W_x"][0].astype(np.float64),
+                                  L["W_h"][0].astype(np.float64), None, ho, co, None, 1)
+        torch.cuda.synchronize()
+        print("  step", step, flush=True)
+        check("h", h, ho, TOL["bf16"])
+        check("c", c, co, TOL["bf16"])
