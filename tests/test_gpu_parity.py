@@ -31,7 +31,7 @@ def rnd_case(rng, T, B, n_in, n, D, lens, dt, scale=0.3, with_state=True, with_b
         t = torch.from_numpy(a).to(torch.float32)
         return (t.to(torch.bfloat16).to(torch.float32) if dt == "bf16" else t).numpy().astype(np.float64)
     c = dict(x=r(rng.standard_normal((T, B, n_in))), W_x=r(rng.uniform(-scale, scale, (D, n_in, 4 * n))),
-             W_h=r(rng.uniform(-scale, scale, (D, n, 4 * n))), lens=np.asarray(lens, dtype=np.int32),
+             W_h=r(rng.uniform(-scale, scale, (D, n, 4 * n))), lens=None if lens is None else np.asarray(lens, dtype=np.int32),
              dy=r(rng.standard_normal((T, B, D * n))))
     f32 = lambda a: a.astype(np.float32).astype(np.float64)
     c["b"] = f32(rng.uniform(-scale, scale, (D, 4 * n))) if with_bias else None
@@ -182,7 +182,7 @@ def test_blstm_equals_two_lstm_and_stepping_equals_sequence():
     full = Bn.forward(x, Wx, Wh, b, h, cc, None, bidirectional=False, direction=1)
     ys = []
     for t in range(6):
-        s = Bn.forward(x[t:t + 1].contiguous(), Wx, Wh, b, h, cc, None, bidirectional=False, direction=1,
+        s = Bn.forward(x[t:t + 1].clone(), Wx, Wh, b, h, cc, None, bidirectional=False, direction=1,
                        flags=Bn.FLAG_INFERENCE, want_c=False)
         h, cc = s["hT"], s["cT"]
         ys.append(s["y"][0])
