@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark: BLSTM forward + backward frames/sec at n = 1024 on one MI355X.
+
+One "step" is one forward pass through the six bidirectional layers of the speech-shaped
+configuration (input 40, n = 1024 per direction, B = 32, lengths ~ U{200..1500}, bf16 storage
+with float state) followed by one backward pass through all six layers, on synthetic seeded
+inputs that are resident in HBM before the timed region starts.  frames = sum(seq_lens), each
+real frame counted once for the whole stack.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel (the recurrent forward step);
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+BF16_PEAK_TFLOPS = 2500.0
+
+
+def build_stack(inp, Bn):
+    dt = torch.bfloat16 if inp["cfg"]["dtype"] == "bf16" else torch.float32
+    x = torch.from_numpy(inp["x"]).to(dt).cuda()
+    lens = torch.from_numpy(inp["seq_lens"]).to(torch.int32).cuda()
+    dy = torch.from_numpy(inp["dy"]).to(dt).cuda()
+    layers = []
+    for L in inp["layers"]:
+        layers.append((torch.from_numpy(L["W_x"]).to(dt).cuda(), torch.from_numpy(L["W_h"]).to(dt).cuda(),
+                       torch.from_numpy(L["b"]).float().cuda()))
+    return x, lens, dy, layers
+
+
+class Stack:
+    """Pre-allocates every buffer once so the timed region holds ABI calls only."""
+
+    def __init__(self, Bn, x, lens, dy, layers):
+        import ctypes
+        self.Bn, self.ct = Bn, ctypes
+        self.x, self.lens, self.dy, self.layers = x, lens, dy, layers
+        T, B, _ = x.shape
+        n = layers[0][1].shape[-2]
+        dev = x.device
+        self.bufs = []
+        wmax = 0
+        cur_in = x.shape[2]
+        for (Wx, Wh, b) in layers:
+            desc = Bn.make_desc(T, B, cur_in, n, Bn.LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else Bn.LSTM_F32)
+            rb, wb = Bn.query(desc, True)
+            wmax = max(wmax, wb)
+            desc.reserve_bytes = rb
+            self.bufs.append(dict(
+                desc=desc, reserve=torch.empty(rb, dtype=torch.uint8, device=dev),
+                y=torch.empty(T, B, 2 * n, dtype=x.dtype, device=dev), c=torch.empty(2, T, B, n, dtype=torch.float32, device=dev),
+                dx=torch.empty(T, B, cur_in, dtype=x.dtype, device=dev),
+                dW_x=torch.empty_like(Wx, dtype=torch.float32), dW_h=torch.empty_like(Wh, dtype=torch.float32),
+                db=torch.empty(2, 4 * n, dtype=torch.float32, device=dev)))
+            cur_in = 2 * n
+        self.ws = torch.empty(wmax, dtype=torch.uint8, device=dev)
+        for bf in self.bufs:
+            bf["desc"].workspace_bytes = wmax
+
+    def step(self):
+        Bn, ct = self.Bn, self.ct
+        s = torch.cuda.current_stream().cuda_stream
+        cur = self.x
+        for (Wx, Wh, b), bf in zip(self.layers, self.bufs):
+            rc = Bn.lib.blstm_fwd(ct.byref(bf["desc"]), cur.data_ptr(), Wx.data_ptr(), Wh.data_ptr(), b.data_ptr(), None, None,
+                                  self.lens.data_ptr(), bf["y"].data_ptr(), bf["c"].data_ptr(), None, None,
+                                  bf["reserve"].data_ptr(), self.ws.data_ptr(), s)
+            assert rc == 0, Bn.strerror(rc)
+            cur = bf["y"]
+        d = self.dy
+        for k in range(len(self.layers) - 1, -1, -1):
+            Wx, Wh, b = self.layers[k]
+            bf = self.bufs[k]
+            xin = self.x if k == 0 else self.bufs[k - 1]["y"]
+            rc = Bn.lib.blstm_bwd(ct.byref(bf["desc"]), xin.data_ptr(), Wx.data_ptr(), Wh.data_ptr(), None, None,
+                                  self.lens.data_ptr(), bf["y"].data_ptr(), bf["c"].data_ptr(), bf["reserve"].data_ptr(),
+                                  d.data_ptr(), None, None, bf["dx"].data_ptr(), bf["dW_x"].data_ptr(), bf["dW_h"].data_ptr(),
+                                  bf["db"].data_ptr(), None, None, self.ws.data_ptr(), s)
+            assert rc == 0, Bn.strerror(rc)
+            d = bf["dx"]
+
+
+def cpu_baseline(inp):
+    """The CPU oracle, as it stands (float64 numpy), on a bounded sample: layer 2 of the stack
+    (n_in = 2n) over the first `cap` frames of every sequence, forward + backward; the per-layer
+    rate is divided by the number of layers to stand beside the whole-stack GPU figure."""
+    from oracle import lstm_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    cap = 128
+    nl = len(inp["layers"])
+    L = inp["layers"][min(1, nl - 1)]
+    lens = np.minimum(inp["seq_lens"], cap)
+    T = int(lens.max())
+    n_in = L["W_x"].shape[1]
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((T, len(lens), n_in))
+    dy = rng.standard_normal((T, len(lens), 2 * L["W_h"].shape[1]))
+    Wx, Wh = L["W_x"].astype(np.float64), L["W_h"].astype(np.float64)
+    t0 = time.perf_counter()
+    O.blstm_fwd(x, Wx, Wh, None, None, None, lens)
+    O.blstm_bwd(x, Wx, Wh, None, None, None, lens, dy)
+    dt = time.perf_counter() - t0
+    frames = int(lens.sum())
+    return {"value": frames / dt / nl, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+            "sample": "float64 numpy oracle, layer 2 of %d (n_in=%d, n=%d), B=%d, first %d frames of every sequence "
+                      "(%d frames, %.1f s fwd+bwd); per-layer rate divided by %d layers" % (
+                          nl, n_in, L["W_h"].shape[1], len(lens), cap, frames, dt, nl)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--per-step", action="store_true", help="force one launch per time step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box has one); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_1805_05225_amd import binding as Bn
+    from paper_1805_05225_amd import synth
+
+    torch.cuda.set_device(0)
+    inp = synth.make(args.config)
+    cfg = inp["cfg"]
+    assert cfg["kind"] == "blstm"
+    frames = synth.real_frames(inp)
+    flops = synth.flops_fwd_bwd(inp)
+    x, lens, dy, layers = build_stack(inp, Bn)
+    st = Stack(Bn, x, lens, dy, layers)
+    if args.per_step:
+        for bf in st.bufs:
+            bf["desc"].flags |= Bn.FLAG_PER_STEP
+
+    for _ in range(args.warmup):
+        st.step()
+    torch.cuda.synchronize()
+    Bn.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    Bn.profile_enable(False)
+    prof = Bn.profile_read()
+
+    ms_per_step = dt / args.steps * 1e3
+    T, B, n = inp["T"], cfg["B"], cfg["n"]
+    # algorithmic HBM bytes of one forward recurrent step, both directions (weights resident):
+    # read Zx_t (B*4n*4) and c (B*n*4); write c (B*n*4), y (B*n*2), gate activations (B*4n*4)
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    step_bytes = 2 * (B * 4 * n * 4 + B * n * 4 + B * n * 4 + B * n * esz + B * 4 * n * 4)
+    loop_ms, loop_launches = prof["loop_fwd"]
+    steps_total = args.steps * cfg["layers"] * T                  # time steps executed by the forward loops
+    us_per_step = loop_ms * 1e3 / max(steps_total, 1)
+    achieved = step_bytes / (us_per_step * 1e-6) / 1e9
+    bwd_ms, _ = prof["loop_bwd"]
+    # hoisted GEMM flops actually executed (padded frames included), per step of the benchmark
+    TB = T * B
+    gemm_flops = {"gemm_zx": 0.0, "gemm_dx": 0.0, "gemm_dwx": 0.0, "gemm_dwh": 0.0}
+    for l in range(cfg["layers"]):
+        ni = cfg["n_in"] if l == 0 else 2 * n
+        gemm_flops["gemm_zx"] += 2.0 * TB * ni * 8 * n
+        gemm_flops["gemm_dx"] += 2.0 * TB * ni * 8 * n
+        gemm_flops["gemm_dwx"] += 2.0 * TB * ni * 8 * n
+        gemm_flops["gemm_dwh"] += 2.0 * TB * n * 8 * n
+    gemm_ms = sum(prof[k][0] for k in gemm_flops)
+    gemm_tflops = sum(gemm_flops.values()) * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+
+    out = {
+        "metric": "BLSTM fwd+bwd frames/sec (n=%d)" % n, "value": frames * args.steps / dt, "unit": "frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": "config %d: %d-layer BLSTM stack, n_in=%d, n=%d per direction, B=%d, seq_lens~U{%d..%d} "
+                               "(T=%d, %d real frames), %s storage / f32 state, forward + backward" % (
+                                   args.config, cfg["layers"], cfg["n_in"], n, B, cfg["len_lo"], cfg["len_hi"], T, frames,
+                                   cfg["dtype"]),
+                   "recurrent_path": "per_step" if args.per_step else "default"},
+        "useful_tflops": flops * args.steps / dt / 1e12,
+        "roofline": {"bound": "hbm", "kernel": "forward recurrent step (both directions)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "us_per_step": us_per_step, "algorithmic_bytes_per_step": step_bytes,
+                     "launches": int(loop_launches)},
+        "phases_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+        "bwd_us_per_step": bwd_ms * 1e3 / max(steps_total, 1),
+        "gemm_roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_PEAK_TFLOPS if esz == 2 else 157.3,
+                          "unit": "TFLOP/s", "frac": gemm_tflops / (BF16_PEAK_TFLOPS if esz == 2 else 157.3),
+                          "note": "executed flops of the four hoisted products, padded frames included"},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -128,6 +128,25 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
               const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const float* bias,
               int accumulate, const int32_t* lens, int Bt, int T, void* stream);
 
+/* Phase timing for benchmarks.  While enabled, every *_fwd / *_bwd call brackets its phases with
+ * hipEvents recorded on the call's own stream (the only resource the library ever creates).
+ * lstm_profile_read() waits for the recorded events, adds each phase's elapsed milliseconds and
+ * kernel-launch count into ms[LSTM_PHASE_COUNT] / launches[LSTM_PHASE_COUNT] (caller zeroes them),
+ * and releases the events.  Not thread-safe; meant for a single benchmarking thread. */
+enum {
+  LSTM_PHASE_PREP = 0,      /* weight / state packing, state initialisation and copies            */
+  LSTM_PHASE_GEMM_ZX = 1,   /* Zx = X W_x + b for all frames                                      */
+  LSTM_PHASE_LOOP_FWD = 2,  /* forward recurrence                                                 */
+  LSTM_PHASE_LOOP_BWD = 3,  /* backward recurrence                                                */
+  LSTM_PHASE_GEMM_DX = 4,   /* dX = DZ W_x^T                                                      */
+  LSTM_PHASE_GEMM_DWX = 5,  /* dW_x = X^T DZ                                                      */
+  LSTM_PHASE_GEMM_DWH = 6,  /* dW_h = Hprev^T DZ                                                  */
+  LSTM_PHASE_DB = 7,        /* db = column sums of DZ                                             */
+  LSTM_PHASE_COUNT = 8
+};
+int lstm_profile_enable(int on);
+int lstm_profile_read(double* ms, int64_t* launches);
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* lstm_strerror(int status);
 

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libmi355x_lstm.so")
 
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE = 1, 2, 4
-EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_strerror")
+EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_profile_enable", "lstm_profile_read",
+           "lstm_strerror")
 
 
 class LstmDesc(ctypes.Structure):
@@ -47,6 +48,10 @@ def _load():
         f.argtypes = [dp] + [vp] * 20
     lib.lstm_gemm.restype = ip
     lib.lstm_gemm.argtypes = [ip] * 7 + [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ip, vp, ip, ip, vp]
+    lib.lstm_profile_enable.restype = ip
+    lib.lstm_profile_enable.argtypes = [ip]
+    lib.lstm_profile_read.restype = ip
+    lib.lstm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.lstm_strerror.restype = ctypes.c_char_p
     lib.lstm_strerror.argtypes = [ip]
     return lib
@@ -155,3 +160,18 @@ def gemm(A, B, *, a_kcontig, b_kcontig, M, N, K, out_dtype=torch.float32, bias=N
                          _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(C), C.stride(0), _ptr(bias), int(accumulate),
                          _ptr(lens), Bt, T, _stream()))
     return C
+
+
+PHASES = ("prep", "gemm_zx", "loop_fwd", "loop_bwd", "gemm_dx", "gemm_dwx", "gemm_dwh", "db")
+
+
+def profile_enable(on):
+    _check(lib.lstm_profile_enable(int(on)))
+
+
+def profile_read():
+    """-> {phase: (milliseconds, launches)} accumulated since the last read."""
+    ms = (ctypes.c_double * len(PHASES))()
+    ln = (ctypes.c_int64 * len(PHASES))()
+    _check(lib.lstm_profile_read(ms, ln))
+    return {p: (ms[i], ln[i]) for i, p in enumerate(PHASES)}

@@ -6,6 +6,7 @@
 
 #include <string.h>
 #include <algorithm>
+#include <vector>
 
 namespace lstm {
 namespace {
@@ -91,6 +92,25 @@ int check_device() {
   return cached;
 }
 
+// ---- optional phase timing (hipEvents on the caller's stream) -----------------------------------
+struct PhaseRec { int phase; long launches; hipEvent_t e0, e1; };
+bool g_profile = false;
+std::vector<PhaseRec> g_recs;
+
+struct Phase {
+  int idx = -1;
+  hipStream_t s;
+  Phase(int phase, long launches, hipStream_t stream) : s(stream) {
+    if (!g_profile) return;
+    PhaseRec r{phase, launches, nullptr, nullptr};
+    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) { (void)hipGetLastError(); return; }
+    (void)hipEventRecord(r.e0, s);
+    g_recs.push_back(r);
+    idx = (int)g_recs.size() - 1;
+  }
+  ~Phase() { if (idx >= 0) (void)hipEventRecord(g_recs[idx].e1, s); }
+};
+
 #define HIPCHK(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; } } while (0)
 
 int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, const void* W_h, const void* b,
@@ -118,12 +138,17 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   float* cstate = (float*)(ws + p.ws_cstate);
   const size_t state_bytes = D * B * n * 4;
 
-  if (h0) HIPCHK(launch_copy(hstate, h0, state_bytes, s)); else HIPCHK(launch_fill_zero(hstate, state_bytes, s));
-  if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else HIPCHK(launch_fill_zero(cstate, state_bytes, s));
+  {
+    Phase ph(LSTM_PHASE_PREP, 4, s);
+    if (h0) HIPCHK(launch_copy(hstate, h0, state_bytes, s)); else HIPCHK(launch_fill_zero(hstate, state_bytes, s));
+    if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else HIPCHK(launch_fill_zero(cstate, state_bytes, s));
+    if (T > 0) {
+      HIPCHK(launch_pack_wh_fwd(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_f, p.D, p.bf16, s));
+      HIPCHK(launch_pack_state(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_f, p.nrt,
+                               p.D, p.bf16, s));
+    }
+  }
   if (T > 0) {
-    HIPCHK(launch_pack_wh_fwd(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_f, p.D, p.bf16, s));
-    HIPCHK(launch_pack_state(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_f, p.nrt, p.D,
-                             p.bf16, s));
     // hoisted input projection for all frames and both directions: Zx = X W_x + b
     float* gates = infer ? (float*)(ws + p.ws_Zx) : (float*)(rs + p.res_gates);
     const long gates_stride = infer ? (long)p.Zx_dir_elems : (long)(p.res_dir_stride / 4);
@@ -135,8 +160,12 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.nseg = 1; g.a_kcontig = true; g.b_kcontig = false; g.in_bf16 = p.bf16; g.out_bf16 = false;
     g.vecA = widest(g.lda, 0, 0, p.esz, 16);
     g.vecB = widest(g.ldb, g.sBz, 0, p.esz, 4);
-    HIPCHK(launch_gemm(g, s));
+    {
+      Phase ph(LSTM_PHASE_GEMM_ZX, 1, s);
+      HIPCHK(launch_gemm(g, s));
+    }
 
+    Phase ph(LSTM_PHASE_LOOP_FWD, (long)T, s);
     FwdArgs a = {};
     a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_f; a.T = p.T; a.ndir = p.D; a.write_gates = infer ? 0 : 1;
     const size_t frag_dir = (size_t)p.nrt * p.nkc_f * 1024;
@@ -160,6 +189,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       HIPCHK(launch_step_fwd(a, p.bf16, s));
     }
   }
+  Phase ph(LSTM_PHASE_PREP, 2, s);
   if (hT) HIPCHK(launch_copy(hT, hstate, state_bytes, s));
   if (cT) HIPCHK(launch_copy(cT, cstate, state_bytes, s));
   return LSTM_OK;
@@ -200,16 +230,21 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     }
     return LSTM_OK;
   }
-  if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dh, state_bytes, s));
-  if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dc, state_bytes, s));
-  HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
-  HIPCHK(launch_fill_zero(ws + p.ws_dzfrag0, p.dzfrag_bytes, s));
-  HIPCHK(launch_fill_zero(ws + p.ws_dzfrag1, p.dzfrag_bytes, s));
+  {
+    Phase ph(LSTM_PHASE_PREP, 5, s);
+    if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dh, state_bytes, s));
+    if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dc, state_bytes, s));
+    HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
+    HIPCHK(launch_fill_zero(ws + p.ws_dzfrag0, p.dzfrag_bytes, s));
+    HIPCHK(launch_fill_zero(ws + p.ws_dzfrag1, p.dzfrag_bytes, s));
+  }
 
   BwdArgs a = {};
   a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_b; a.T = p.T; a.ndir = p.D;
   const size_t frag_dir = (size_t)p.nrt * p.nkc_b * 1024;
   char* DZ = ws + p.ws_DZ;
+  {
+  Phase ph(LSTM_PHASE_LOOP_BWD, (long)T + 1, s);
   for (long tau = (long)T - 1; tau >= -1; --tau) {
     a.do_matmul = tau < (long)T - 1;
     a.do_pointwise = tau >= 0;
@@ -237,8 +272,12 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     }
     HIPCHK(launch_step_bwd(a, p.bf16, s));
   }
-  if (dh0) HIPCHK(launch_copy(dh0, Dh, state_bytes, s));
-  if (dc0) HIPCHK(launch_copy(dc0, Dc, state_bytes, s));
+  }
+  {
+    Phase ph(LSTM_PHASE_PREP, 2, s);
+    if (dh0) HIPCHK(launch_copy(dh0, Dh, state_bytes, s));
+    if (dc0) HIPCHK(launch_copy(dc0, Dc, state_bytes, s));
+  }
 
   const int TB = (int)(T * B);
   if (dx) {                        // dX = sum over directions of DZ W_x^T
@@ -250,6 +289,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = p.bf16; g.out_bf16 = p.bf16;
     g.vecA = widest(g.lda, g.sAseg, 0, p.esz, 16);
     g.vecB = widest(g.ldb, g.sBseg, 0, p.esz, 16);
+    Phase ph(LSTM_PHASE_GEMM_DX, 1, s);
     HIPCHK(launch_gemm(g, s));
   }
   {                                // dW_x = X^T DZ, padded frames of X masked out
@@ -262,14 +302,19 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.lens = seq_lens; g.Bt = p.B; g.T = p.T;
     g.vecA = widest(g.lda, 0, 0, p.esz, 4);
     g.vecB = widest(g.ldb, g.sBz, 0, p.esz, 4);
-    HIPCHK(launch_gemm(g, s));
+    {
+      Phase ph(LSTM_PHASE_GEMM_DWX, 1, s);
+      HIPCHK(launch_gemm(g, s));
+    }
     // dW_h = Hprev^T DZ
     g.A = rs + p.res_hprev; g.C = dW_h; g.M = p.n; g.lda = n;
     g.sAz = (long)(p.res_dir_stride / p.esz); g.sCz = (long)(n * 4 * n);
     g.lens = nullptr;
     g.vecA = widest(g.lda, g.sAz, 0, p.esz, 4);
+    Phase ph(LSTM_PHASE_GEMM_DWH, 1, s);
     HIPCHK(launch_gemm(g, s));
   }
+  Phase ph(LSTM_PHASE_DB, 2, s);
   HIPCHK(launch_colsum(DZ, (float*)db, (float*)(ws + p.ws_colsum), TB, 4 * p.n, p.D, (long)p.DZ_dir_elems, p.bf16, acc, s));
   return LSTM_OK;
 }
@@ -335,6 +380,29 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
   g.vecB = std::min(widest(ldb, 0, 0, esz, b_kcontig ? 16 : 4), ptr_vec(B, b_kcontig ? 16 : 4));
   if (launch_gemm(g, (hipStream_t)stream) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
   return LSTM_OK;
+}
+
+int lstm_profile_enable(int on) {
+  lstm::g_profile = on != 0;
+  return LSTM_OK;
+}
+int lstm_profile_read(double* ms, int64_t* launches) {
+  if (!ms || !launches) return LSTM_ERR_NULL;
+  int rc = LSTM_OK;
+  for (auto& r : lstm::g_recs) {
+    float t = 0.f;
+    if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess) {
+      (void)hipGetLastError();
+      rc = LSTM_ERR_HIP;
+    } else {
+      ms[r.phase] += t;
+      launches[r.phase] += r.launches;
+    }
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  lstm::g_recs.clear();
+  return rc;
 }
 
 const char* lstm_strerror(int status) {
