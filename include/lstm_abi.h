@@ -57,7 +57,7 @@ typedef enum {
 
 enum {
   LSTM_FLAG_ACCUMULATE = 1, /* *_bwd: add into dW_x, dW_h, db instead of overwriting them        */
-  LSTM_FLAG_PER_STEP = 2,   /* force one kernel launch per time step (no persistent kernel)      */
+  LSTM_FLAG_PER_STEP = 2,   /* force one kernel launch per time step (no single-launch loop)     */
   LSTM_FLAG_INFERENCE = 4   /* *_fwd: nothing is saved for backward; reserve may be NULL         */
 };
 
@@ -127,6 +127,13 @@ int blstm_bwd(const lstm_desc* desc, const void* x, const void* W_x, const void*
 int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, int N, int K,
               const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const float* bias,
               int accumulate, const int32_t* lens, int Bt, int T, void* stream);
+
+/* Diagnostic for the single-launch (persistent) recurrent kernels, whose work-groups wait for each
+ * other between time steps with BOUNDED waits.  If a wait ever expired, the kernel drained early, the
+ * results of that call are invalid and a word in the workspace says so.  This call copies that word
+ * to the host (it SYNCHRONISES the device) and stores 1 in *timed_out if it is set, else 0.  It refers
+ * to the last *_fwd / *_bwd call that used `workspace` (every call clears the word first). */
+int lstm_sync_status(const void* workspace, int32_t* timed_out);
 
 /* Phase timing for benchmarks.  While enabled, every *_fwd / *_bwd call brackets its phases with
  * hipEvents recorded on the call's own stream (the only resource the library ever creates).

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libmi355x_lstm.so")
 
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE = 1, 2, 4
-EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_profile_enable", "lstm_profile_read",
+EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
            "lstm_strerror")
 
 
@@ -48,6 +48,8 @@ def _load():
         f.argtypes = [dp] + [vp] * 20
     lib.lstm_gemm.restype = ip
     lib.lstm_gemm.argtypes = [ip] * 7 + [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ip, vp, ip, ip, vp]
+    lib.lstm_sync_status.restype = ip
+    lib.lstm_sync_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
     lib.lstm_profile_enable.restype = ip
     lib.lstm_profile_enable.argtypes = [ip]
     lib.lstm_profile_read.restype = ip
@@ -175,3 +177,11 @@ def profile_read():
     ln = (ctypes.c_int64 * len(PHASES))()
     _check(lib.lstm_profile_read(ms, ln))
     return {p: (ms[i], ln[i]) for i, p in enumerate(PHASES)}
+
+
+def sync_status(workspace):
+    """True if a bounded wait of a single-launch recurrent kernel expired in the last call that used
+    this workspace (synchronises the device)."""
+    flag = ctypes.c_int32(0)
+    _check(lib.lstm_sync_status(_ptr(workspace), ctypes.byref(flag)))
+    return bool(flag.value)

@@ -101,6 +101,45 @@ struct BwdArgs {
 };
 hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s);
 
+// Persistent variants: one launch runs every time step.  W_h stays in registers, work-groups of
+// one (direction, row block) meet at a counter in `sync` after each step (sync[0] is an error
+// word set when a bounded wait expires; counters follow).  All work-groups must be co-resident:
+// the launch is cooperative and fails with hipErrorCooperativeLaunchTooLarge otherwise.
+struct PFwdDir {
+  const uint4* Wf; uint4* hfrag0; uint4* hfrag1;
+  float* gates;       // [T][B][4n]
+  float* hstate; float* cstate;
+  void* y; long ldy;  // y + column offset of this direction; frame stride B*ldy
+  float* cs;          // [T][B][n] or NULL
+  void* hprev;        // [T][B][n] or NULL
+  int rev;            // 0: t = tau, 1: t = T-1-tau
+};
+struct PFwdArgs {
+  PFwdDir d[2];
+  const int* lens;
+  int B, n, nkc, T, ndir, write_gates;
+  unsigned* sync; unsigned spin_limit;
+};
+hipError_t launch_persist_fwd(const PFwdArgs& a, bool bf16, hipStream_t s);
+constexpr int kPersistFwdMaxNkcBf16 = 32, kPersistFwdMaxNkcF32 = 64;
+
+struct PBwdDir {
+  const uint4* Wb; uint4* dzfrag0; uint4* dzfrag1;
+  const float* gates; const float* cs; const float* c0;
+  const void* dy; long lddy;
+  void* DZ;           // [T][B][4n]
+  float* Dh; float* Dc;
+  int rev;
+};
+struct PBwdArgs {
+  PBwdDir d[2];
+  const int* lens;
+  int B, n, nkc, T, ndir;
+  unsigned* sync; unsigned spin_limit;
+};
+hipError_t launch_persist_bwd(const PBwdArgs& a, bool bf16, hipStream_t s);
+constexpr int kPersistBwdMaxNkcBf16 = 128, kPersistBwdMaxNkcF32 = 256;
+
 // Weight / state packing and small helpers (all enqueue-only).
 hipError_t launch_pack_wh_fwd(const void* W_h, uint4* Wf, int n, int nkc, int ndir, bool bf16, hipStream_t s);
 hipError_t launch_pack_wh_bwd(const void* W_h, uint4* Wb, int n, int nkc, int ndir, bool bf16, hipStream_t s);

@@ -93,13 +93,6 @@ __device__ __forceinline__ void commit_kcontig(const uint32_t (&st)[16], char* l
 
 // ---- m-contiguous operand: rows of memory are k, the tile is transposed in registers ----------
 // frame mask: row k of the K axis is frame (t = k / Bt, b = k % Bt), valid iff t < lens[b]
-__device__ __forceinline__ bool frame_valid(int k, const int* lens, int Bt, int T) {
-  int t = k / Bt, b = k - t * Bt;
-  int L = lens[b];
-  L = L < 0 ? 0 : (L > T ? T : L);
-  return t < L;
-}
-
 // bf16: micro-tile of 8 k x 2 m (eight 4-byte loads), two micro-tiles per thread
 template <bool MASK>
 __device__ __forceinline__ void fetch_mcontig_bf16(uint32_t (&st)[16], const char* base, long ld, int cols, int col0,
@@ -108,12 +101,17 @@ __device__ __forceinline__ void fetch_mcontig_bf16(uint32_t (&st)[16], const cha
   for (int i = 0; i < 2; ++i) {
     int c = tid + kThreads * i;
     int m = col0 + 2 * (c & 63), kb = k0 + (c >> 6) * 8;
+    int ft = 0, fb = 0;
+    if (MASK) { ft = kb / Bt; fb = kb - ft * Bt; }          // frame (t, b) of row kb; advanced incrementally below
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       int k = kb + kk;
       uint32_t w = 0;
       bool ok = k < K && m < cols;
-      if (MASK) ok = ok && frame_valid(k < K ? k : 0, lens, Bt, T);
+      if (MASK) {
+        if (ok) { int L = lens[fb]; L = L < 0 ? 0 : (L > T ? T : L); ok = ft < L; }
+        if (++fb == Bt) { fb = 0; ++ft; }
+      }
       if (ok) {
         const char* p = base + ((long)k * ld + m) * 2;
         if (vec >= 4 && m + 1 < cols) w = *(const uint32_t*)p;
@@ -150,11 +148,16 @@ __device__ __forceinline__ void fetch_mcontig_f32(uint32_t (&st)[16], const char
   for (int i = 0; i < 4; ++i) {
     int c = tid + kThreads * i;
     int m = col0 + (c & 127), kb = k0 + (c >> 7) * 4;
+    int ft = 0, fb = 0;
+    if (MASK) { ft = kb / Bt; fb = kb - ft * Bt; }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       int k = kb + kk;
       bool ok = k < K && m < cols;
-      if (MASK) ok = ok && frame_valid(k < K ? k : 0, lens, Bt, T);
+      if (MASK) {
+        if (ok) { int L = lens[fb]; L = L < 0 ? 0 : (L > T ? T : L); ok = ft < L; }
+        if (++fb == Bt) { fb = 0; ++ft; }
+      }
       st[4 * i + kk] = ok ? *(const uint32_t*)(base + ((long)k * ld + m) * 4) : 0u;
     }
   }

@@ -12,6 +12,7 @@ namespace lstm {
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr unsigned kSpinLimit = 1u << 21;   // polls before a persistent kernel's wait gives up (seconds, not microseconds)
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
@@ -23,7 +24,7 @@ struct Plan {
   size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
   // workspace
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
-      ws_colsum, workspace_bytes;
+      ws_colsum, ws_sync, sync_bytes, workspace_bytes;
   size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems;
 };
 
@@ -52,6 +53,8 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->reserve_bytes = D * p->res_dir_stride + kAlign;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
+  p->sync_bytes = up((1 + 2 * (size_t)p->nrt) * 4);
+  p->ws_sync = take(p->sync_bytes);              // first, so that lstm_sync_status() finds it without a plan
   p->ws_Wf = take(D * p->ntile_f * 2 * (size_t)p->nkc_f * 1024);
   p->ws_Wb = take(infer ? 0 : D * p->ntile_b * (size_t)p->nkc_b * 1024);
   p->hfrag_bytes = D * p->nrt * (size_t)p->nkc_f * 1024;
@@ -139,7 +142,8 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   const size_t state_bytes = D * B * n * 4;
 
   {
-    Phase ph(LSTM_PHASE_PREP, 4, s);
+    Phase ph(LSTM_PHASE_PREP, 5, s);
+    HIPCHK(launch_fill_zero(ws + p.ws_sync, p.sync_bytes, s));
     if (h0) HIPCHK(launch_copy(hstate, h0, state_bytes, s)); else HIPCHK(launch_fill_zero(hstate, state_bytes, s));
     if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else HIPCHK(launch_fill_zero(cstate, state_bytes, s));
     if (T > 0) {
@@ -165,6 +169,33 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       HIPCHK(launch_gemm(g, s));
     }
 
+    bool done = false;
+    const int max_nkc = p.bf16 ? kPersistFwdMaxNkcBf16 : kPersistFwdMaxNkcF32;
+    if (!(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_f <= max_nkc) {
+      Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
+      PFwdArgs pa = {};
+      pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_f; pa.T = p.T; pa.ndir = p.D; pa.write_gates = infer ? 0 : 1;
+      pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
+      const size_t frag_dir = (size_t)p.nrt * p.nkc_f * 1024;
+      for (size_t d = 0; d < D; ++d) {
+        PFwdDir& fd = pa.d[d];
+        fd.Wf = (const uint4*)(ws + p.ws_Wf + d * (size_t)p.ntile_f * 2 * p.nkc_f * 1024);
+        fd.hfrag0 = (uint4*)(ws + p.ws_hfrag0 + d * frag_dir);
+        fd.hfrag1 = (uint4*)(ws + p.ws_hfrag1 + d * frag_dir);
+        fd.gates = gates + d * gates_stride;
+        fd.hstate = hstate + d * B * n;
+        fd.cstate = cstate + d * B * n;
+        fd.y = (char*)y + d * n * p.esz;
+        fd.ldy = (long)(D * n);
+        fd.cs = c ? (float*)c + d * T * B * n : nullptr;
+        fd.hprev = infer ? nullptr : rs + d * p.res_dir_stride + p.res_hprev;
+        fd.rev = bidir ? d == 1 : desc->direction == -1;
+      }
+      hipError_t e = launch_persist_fwd(pa, p.bf16, s);
+      if (e == hipSuccess) done = true;
+      else (void)hipGetLastError();                 // does not fit on the device together: use one launch per step
+    }
+    if (!done) {
     Phase ph(LSTM_PHASE_LOOP_FWD, (long)T, s);
     FwdArgs a = {};
     a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_f; a.T = p.T; a.ndir = p.D; a.write_gates = infer ? 0 : 1;
@@ -187,6 +218,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         fd.t = (int)t;
       }
       HIPCHK(launch_step_fwd(a, p.bf16, s));
+    }
     }
   }
   Phase ph(LSTM_PHASE_PREP, 2, s);
@@ -218,6 +250,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   float* Dh = (float*)(ws + p.ws_Dh);
   float* Dc = (float*)(ws + p.ws_Dc);
   const size_t state_bytes = D * B * n * 4;
+  if (B > 0) HIPCHK(launch_fill_zero(ws + p.ws_sync, p.sync_bytes, s));
   if (B == 0 || T == 0) {          // no frames: parameter gradients are zero, state gradients pass through
     if (!acc) {
       HIPCHK(launch_fill_zero(dW_x, D * n_in * 4 * n * 4, s));
@@ -239,11 +272,37 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     HIPCHK(launch_fill_zero(ws + p.ws_dzfrag1, p.dzfrag_bytes, s));
   }
 
-  BwdArgs a = {};
-  a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_b; a.T = p.T; a.ndir = p.D;
   const size_t frag_dir = (size_t)p.nrt * p.nkc_b * 1024;
   char* DZ = ws + p.ws_DZ;
-  {
+  bool done = false;
+  const int max_nkc = p.bf16 ? kPersistBwdMaxNkcBf16 : kPersistBwdMaxNkcF32;
+  if (!(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_b <= max_nkc) {
+    Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);
+    PBwdArgs pa = {};
+    pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_b; pa.T = p.T; pa.ndir = p.D;
+    pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
+    for (size_t d = 0; d < D; ++d) {
+      PBwdDir& bd = pa.d[d];
+      bd.Wb = (const uint4*)(ws + p.ws_Wb + d * (size_t)p.ntile_b * p.nkc_b * 1024);
+      bd.dzfrag0 = (uint4*)(ws + p.ws_dzfrag0 + d * frag_dir);
+      bd.dzfrag1 = (uint4*)(ws + p.ws_dzfrag1 + d * frag_dir);
+      bd.gates = (const float*)(rs + d * p.res_dir_stride + p.res_gates);
+      bd.cs = (const float*)c + d * T * B * n;
+      bd.c0 = c0 ? (const float*)c0 + d * B * n : nullptr;
+      bd.dy = (const char*)dy + d * n * p.esz;
+      bd.lddy = (long)(D * n);
+      bd.DZ = DZ + d * p.DZ_dir_elems * p.esz;
+      bd.Dh = Dh + d * B * n;
+      bd.Dc = Dc + d * B * n;
+      bd.rev = bidir ? d == 1 : desc->direction == -1;
+    }
+    hipError_t e = launch_persist_bwd(pa, p.bf16, s);
+    if (e == hipSuccess) done = true;
+    else (void)hipGetLastError();
+  }
+  BwdArgs a = {};
+  a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_b; a.T = p.T; a.ndir = p.D;
+  if (!done) {
   Phase ph(LSTM_PHASE_LOOP_BWD, (long)T + 1, s);
   for (long tau = (long)T - 1; tau >= -1; --tau) {
     a.do_matmul = tau < (long)T - 1;
@@ -379,6 +438,15 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
   g.vecA = std::min(widest(lda, 0, 0, esz, a_kcontig ? 16 : 4), ptr_vec(A, a_kcontig ? 16 : 4));
   g.vecB = std::min(widest(ldb, 0, 0, esz, b_kcontig ? 16 : 4), ptr_vec(B, b_kcontig ? 16 : 4));
   if (launch_gemm(g, (hipStream_t)stream) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  return LSTM_OK;
+}
+
+int lstm_sync_status(const void* workspace, int32_t* timed_out) {
+  if (!workspace || !timed_out) return LSTM_ERR_NULL;
+  const char* ws = (const char*)(((uintptr_t)workspace + lstm::kAlign - 1) / lstm::kAlign * lstm::kAlign);
+  uint32_t word = 0;
+  if (hipMemcpy(&word, ws, 4, hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  *timed_out = word != 0;
   return LSTM_OK;
 }
 

@@ -6,7 +6,7 @@
 // gradients), then the gate gradients dz_t of this frame.
 //
 // Decomposition.  A work-group owns a few hidden units and ALL of their gate columns
-// (forward: 8 units = 32 columns; backward: 16 units), for 32 batch rows.  So the cell update
+// (forward: 8 units = 32 columns for 32 batch rows; backward: 16 units for 16 batch rows).  So the cell update
 // is local to the work-group and only h_t (forward) or dz_t (backward) crosses work-groups
 // between steps.  The small-M product runs on MFMA 16x16 tiles with the K axis split over the
 // four wavefronts, followed by a reduction through LDS and the pointwise epilogue.
@@ -16,44 +16,10 @@
 //   chunk (tile, kc, lane = g*16 + r) element e  <->  row/col r of the 16-wide tile,
 //   k = kc*KC + g*E + e,  E = elements per 16 bytes, KC = 4E.
 // W_h is packed once per call; h_t / dz_t are written in this order by the step that makes them.
-#include "common.h"
+#include "recurrent_dev.h"
 
 namespace lstm {
 namespace {
-
-template <typename T> struct Mma16;
-template <> struct Mma16<bf16_t> {
-  __device__ static f32x4 run(uint4 a, uint4 b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-  }
-};
-template <> struct Mma16<float> {
-  __device__ static f32x4 run(uint4 a, uint4 b, f32x4 c) {
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
-    return c;
-  }
-};
-
-// element offset (in elements of T) of (row, k) inside a fragment-ordered buffer with nkc chunks per row tile
-template <typename T>
-__device__ __forceinline__ long frag_offset(int row, int k, int nkc) {
-  constexpr int E = Store<T>::kPerChunk, KC = 4 * E;
-  int rt = row >> 4, r = row & 15;
-  int kc = k / KC, rem = k - kc * KC;
-  int g = rem / E, e = rem - g * E;
-  return ((((long)rt * nkc + kc) * 64 + g * 16 + r) * E + e);
-}
-
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + __expf(-x)); }
-__device__ __forceinline__ float tanhf_(float x) { return 1.f - 2.f / (1.f + __expf(2.f * x)); }
-__device__ __forceinline__ int clamp_len(const int* lens, int b, int T) {
-  if (!lens) return T;
-  int L = lens[b];
-  return L < 0 ? 0 : (L > T ? T : L);
-}
 
 // ------------------------------------------------------------------------------------------------
 // forward step
@@ -125,63 +91,47 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(FwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward step
+// backward step: a work-group owns 16 units for one tile of 16 batch rows
 template <typename T>
 __global__ __launch_bounds__(256) void step_bwd_kernel(BwdArgs a) {
-  __shared__ float red[4][32][17];
+  __shared__ float red[4][16][17];
   const BwdDir& d = a.d[blockIdx.z];
-  const int tile = blockIdx.x, rb = blockIdx.y;
+  const int tile = blockIdx.x, rt = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n;
 
   if (a.do_matmul) {
-    f32x4 acc[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
-    const uint4* A0 = d.dzin + ((long)(rb * 2 + 0) * nkc) * 64 + lane;
-    const uint4* A1 = d.dzin + ((long)(rb * 2 + 1) * nkc) * 64 + lane;
+    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const uint4* Ap = d.dzin + ((long)rt * nkc) * 64 + lane;
     const uint4* Bp = d.Wb + ((long)tile * nkc) * 64 + lane;
-#pragma unroll 4
-    for (int kc = wave; kc < nkc; kc += 4) {
-      uint4 a0 = A0[(long)kc * 64], a1 = A1[(long)kc * 64], b0 = Bp[(long)kc * 64];
-      acc[0] = Mma16<T>::run(a0, b0, acc[0]);
-      acc[1] = Mma16<T>::run(a1, b0, acc[1]);
-    }
+#pragma unroll 8
+    for (int kc = wave; kc < nkc; kc += 4) acc = Mma16<T>::run(Ap[(long)kc * 64], Bp[(long)kc * 64], acc);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][i * 16 + 4 * (lane >> 4) + v][lane & 15] = acc[i][v];
+    for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = acc[v];
   }
   __syncthreads();
 
+  const int r = tid >> 4, u = tid & 15;
+  const int b = rt * 16 + r, j = tile * 16 + u;
+  if (b >= a.B || j >= n) return;
+  const int L = clamp_len(a.lens, b, a.T);
+  float Dh = d.Dh[(long)b * n + j];
+  if (a.do_matmul && d.t_next < L) Dh = red[0][r][u] + red[1][r][u] + red[2][r][u] + red[3][r][u];
+  d.Dh[(long)b * n + j] = Dh;
+  if (!a.do_pointwise) return;
+  float dz[4] = {0.f, 0.f, 0.f, 0.f};
+  if (d.t < L) {
+    const float* gp = d.gates + (long)b * 4 * n + j;
+    const float c_prev = d.cprev ? d.cprev[(long)b * n + j] : 0.f;
+    const float dh = Store<T>::load(d.dy, (long)b * d.lddy + j) + Dh;
+    float Dc = d.Dc[(long)b * n + j];
+    lstm_cell_grad(gp[0], gp[n], gp[2 * n], gp[3 * n], d.cs[(long)b * n + j], c_prev, dh, Dc, dz);
+    d.Dc[(long)b * n + j] = Dc;
+  }
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    const int idx = tid + 256 * p;
-    const int r = idx >> 4, u = idx & 15;
-    const int b = rb * 32 + r, j = tile * 16 + u;
-    if (b >= a.B || j >= n) continue;
-    const int L = clamp_len(a.lens, b, a.T);
-    float Dh = d.Dh[(long)b * n + j];
-    if (a.do_matmul && d.t_next < L) Dh = red[0][r][u] + red[1][r][u] + red[2][r][u] + red[3][r][u];
-    d.Dh[(long)b * n + j] = Dh;
-    if (!a.do_pointwise) continue;
-    float dz[4] = {0.f, 0.f, 0.f, 0.f};
-    if (d.t < L) {
-      const float* gp = d.gates + (long)b * 4 * n + j;
-      const float gi = gp[0], gf = gp[n], gg = gp[2 * n], go = gp[3 * n];
-      const float tc = tanhf_(d.cs[(long)b * n + j]);
-      const float c_prev = d.cprev ? d.cprev[(long)b * n + j] : 0.f;
-      const float dh = Store<T>::load(d.dy, (long)b * d.lddy + j) + Dh;
-      const float dc = d.Dc[(long)b * n + j] + dh * go * (1.f - tc * tc);
-      d.Dc[(long)b * n + j] = dc * gf;
-      dz[0] = dc * gg * gi * (1.f - gi);
-      dz[1] = dc * c_prev * gf * (1.f - gf);
-      dz[2] = dc * gi * (1.f - gg * gg);
-      dz[3] = dh * tc * go * (1.f - go);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      Store<T>::store(d.DZ, (long)b * 4 * n + q * n + j, dz[q]);
-      Store<T>::store(d.dzout, frag_offset<T>(b, q * n + j, nkc), dz[q]);
-    }
+  for (int q = 0; q < 4; ++q) {
+    Store<T>::store(d.DZ, (long)b * 4 * n + q * n + j, dz[q]);
+    Store<T>::store(d.dzout, frag_offset<T>(b, q * n + j, nkc), dz[q]);
   }
 }
 
@@ -297,7 +247,7 @@ hipError_t launch_step_fwd(const FwdArgs& a, bool bf16, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s) {
-  dim3 grid(cdiv(a.n, 16), cdiv(a.B, 32), a.ndir), block(256);
+  dim3 grid(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), block(256);
   if (bf16) hipLaunchKernelGGL(step_bwd_kernel<bf16_t>, grid, block, 0, s, a);
   else hipLaunchKernelGGL(step_bwd_kernel<float>, grid, block, 0, s, a);
   return hipGetLastError();

@@ -40,7 +40,7 @@ def rnd_case(rng, T, B, n_in, n, D, lens, dt, scale=0.3, with_state=True, with_b
     return c
 
 
-def run_gpu(c, dt, bidir, direction=1, x_override=None, dy_override=None):
+def run_gpu(c, dt, bidir, direction=1, x_override=None, dy_override=None, flags=0):
     sq = (lambda a: a) if bidir else (lambda a: None if a is None else a[0])
     x = dev(c["x"] if x_override is None else x_override, dt)
     dy = dev(c["dy"] if dy_override is None else dy_override, dt)
@@ -48,8 +48,10 @@ def run_gpu(c, dt, bidir, direction=1, x_override=None, dy_override=None):
     b, h0, c0 = dev(sq(c["b"])), dev(sq(c["h0"])), dev(sq(c["c0"]))
     dhT, dcT = dev(sq(c["dhT"])), dev(sq(c["dcT"]))
     lens = dev(c["lens"]) if c["lens"] is not None else None
-    f = Bn.forward(x, Wx, Wh, b, h0, c0, lens, bidirectional=bidir, direction=direction)
+    f = Bn.forward(x, Wx, Wh, b, h0, c0, lens, bidirectional=bidir, direction=direction, flags=flags)
+    assert not Bn.sync_status(f["workspace"]), "a bounded wait expired in the forward kernel"
     g = Bn.backward(f, x, Wx, Wh, h0, c0, lens, dy, dhT, dcT)
+    assert not Bn.sync_status(f["workspace"]), "a bounded wait expired in the backward kernel"
     torch.cuda.synchronize()
     return f, g
 
@@ -203,6 +205,24 @@ def test_accumulate_flag_adds_into_gradients():
     torch.cuda.synchronize()
     assert torch.allclose(g2["dW_x"], g["dW_x"] + 1, atol=1e-5) and torch.allclose(g2["dW_h"], g["dW_h"] + 2, atol=1e-5)
     assert torch.allclose(g2["db"], g["db"] + 3, atol=1e-5)
+
+
+# ---- the single-launch recurrent kernels against one launch per time step ------------------------------------
+@pytest.mark.parametrize("dt,B,n,T", [("bf16", 32, 64, 40), ("f32", 5, 20, 9), ("bf16", 70, 136, 25), ("bf16", 32, 1024, 12)])
+def test_single_launch_equals_per_step(dt, B, n, T):
+    rng = np.random.default_rng(B * n + T)
+    lens = rng.integers(0, T + 1, B)
+    lens[0] = T
+    c = rnd_case(rng, T=T, B=B, n_in=24, n=n, D=2, lens=lens, dt=dt, scale=0.1)
+    print("  single launch vs per step", dt, B, n, T, flush=True)
+    f1, g1 = run_gpu(c, dt, True)
+    f2, g2 = run_gpu(c, dt, True, flags=Bn.FLAG_PER_STEP)
+    for k in ("y", "c", "hT", "cT"):
+        assert torch.equal(f1[k], f2[k]), k
+    for k in ("dx", "dW_x", "dW_h", "db", "dh0", "dc0"):
+        assert torch.equal(g1[k], g2[k]), k
+    fo, go = run_oracle(c, True)
+    compare(f1, g1, fo, go, TOL[dt])
 
 
 # ---- the benchmark configurations ------------------------------------------------------------------------------
