@@ -101,12 +101,28 @@ struct BwdArgs {
 };
 hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s);
 
-// Persistent variants: one launch runs every time step.  W_h stays in registers, work-groups of
-// one (direction, row block) meet at a counter in `sync` after each step (sync[0] is an error
-// word set when a bounded wait expires; counters follow).  All work-groups must be co-resident:
-// the launch is cooperative and fails with hipErrorCooperativeLaunchTooLarge otherwise.
+// Single-launch ("persistent") variants for bfloat16 storage: one launch runs every time step with
+// W_h resident in registers.  A work-group owns 16 hidden units for 16 batch rows.  What crosses
+// work-groups (h_t forward, dz_t backward) travels through a two-slot ring in global memory whose
+// every 8-byte unit carries three bf16 values AND a 16-bit step tag, so a consumer needs no barrier
+// and no fence: it re-reads the ring until every tag shows the step it waits for.
+//   K axis of the ring ("slots"): producer p (unit tile) owns kLLSlots consecutive slots per row;
+//   slot w inside a producer: unit m = w/4, position w%4; position 3 is the tag, positions 0..2
+//   carry value 3m + pos (values beyond the producer's count are padding).  Chunks of 8 slots form
+//   MFMA A-fragments exactly as in the per-step kernels.
+// sync[0] is an error word set when a bounded wait expires.
+constexpr int kLLValsFwd = 16, kLLSlotsFwd = 24;     // 16 h values  -> 6 units  -> 3 chunks per producer and row
+constexpr int kLLValsBwd = 64, kLLSlotsBwd = 88;     // 64 dz values -> 22 units -> 11 chunks
+constexpr int kLLMaxNkcFwd = 48, kLLMaxNkcBwd = 176; // register budget of the kernels (n <= 1024)
+inline int ll_nkc(int n, int slots) { return (int)((((long)(n + 15) / 16) * slots + 31) / 32); }
+__host__ __device__ inline int ll_slot_value(int w, int nvals) {
+  const int pos = w & 3, v = 3 * (w >> 2) + pos;
+  return (pos == 3 || v >= nvals) ? -1 : v;
+}
+
 struct PFwdDir {
-  const uint4* Wf; uint4* hfrag0; uint4* hfrag1;
+  const uint4* Wf;    // [unit tile][gate][nkc][64] chunks
+  uint4* ring0; uint4* ring1;   // [row tile][nkc][64] chunks each
   float* gates;       // [T][B][4n]
   float* hstate; float* cstate;
   void* y; long ldy;  // y + column offset of this direction; frame stride B*ldy
@@ -120,11 +136,11 @@ struct PFwdArgs {
   int B, n, nkc, T, ndir, write_gates;
   unsigned* sync; unsigned spin_limit;
 };
-hipError_t launch_persist_fwd(const PFwdArgs& a, bool bf16, hipStream_t s);
-constexpr int kPersistFwdMaxNkcBf16 = 32, kPersistFwdMaxNkcF32 = 64;
+hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s);
 
 struct PBwdDir {
-  const uint4* Wb; uint4* dzfrag0; uint4* dzfrag1;
+  const uint4* Wb;    // [unit tile][nkc][64] chunks
+  uint4* ring0; uint4* ring1;
   const float* gates; const float* cs; const float* c0;
   const void* dy; long lddy;
   void* DZ;           // [T][B][4n]
@@ -137,8 +153,12 @@ struct PBwdArgs {
   int B, n, nkc, T, ndir;
   unsigned* sync; unsigned spin_limit;
 };
-hipError_t launch_persist_bwd(const PBwdArgs& a, bool bf16, hipStream_t s);
-constexpr int kPersistBwdMaxNkcBf16 = 128, kPersistBwdMaxNkcF32 = 256;
+hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s);
+hipError_t launch_pack_wh_fwd_ll(const void* W_h, uint4* Wf, int n, int nkc, int ndir, hipStream_t s);
+hipError_t launch_pack_wh_bwd_ll(const void* W_h, uint4* Wb, int n, int nkc, int ndir, hipStream_t s);
+// h (float [ndir][B][n]) -> ring slot 0 with tag 1; ring slot 1 cleared
+hipError_t launch_pack_state_ll(const float* h, uint4* ring0, uint4* ring1, int B, int n, int nkc, int nrt, int ndir,
+                                hipStream_t s);
 
 // Weight / state packing and small helpers (all enqueue-only).
 hipError_t launch_pack_wh_fwd(const void* W_h, uint4* Wf, int n, int nkc, int ndir, bool bf16, hipStream_t s);

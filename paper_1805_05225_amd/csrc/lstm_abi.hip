@@ -12,7 +12,7 @@ namespace lstm {
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr unsigned kSpinLimit = 1u << 21;   // polls before a persistent kernel's wait gives up (seconds, not microseconds)
+constexpr unsigned kSpinLimit = 1u << 20;   // polls before a single-launch kernel's wait gives up (about a second)
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
@@ -20,6 +20,7 @@ struct Plan {
   bool bf16;
   size_t esz;
   int nkc_f, nkc_b, nrt, ntile_f, ntile_b;
+  int nkc_ll_f, nkc_ll_b, ntile16;          // ring layout of the single-launch kernels
   // reserve: per direction [gates float T*B*4n][hprev storage T*B*n]
   size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
   // workspace
@@ -45,6 +46,9 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->nrt = 2 * cdiv(d->B > 0 ? d->B : 1, 32);       // 16-row tiles, two per work-group row block
   p->ntile_f = cdiv(d->n, 8);
   p->ntile_b = cdiv(d->n, 16);
+  p->ntile16 = cdiv(d->n, 16);
+  p->nkc_ll_f = ll_nkc(d->n, kLLSlotsFwd);
+  p->nkc_ll_b = ll_nkc(d->n, kLLSlotsBwd);
   const size_t n = d->n, D = p->D, B = d->B;
   const bool infer = d->flags & LSTM_FLAG_INFERENCE;
   p->res_gates = 0;
@@ -55,10 +59,10 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
   p->sync_bytes = up((1 + 2 * (size_t)p->nrt) * 4);
   p->ws_sync = take(p->sync_bytes);              // first, so that lstm_sync_status() finds it without a plan
-  p->ws_Wf = take(D * p->ntile_f * 2 * (size_t)p->nkc_f * 1024);
-  p->ws_Wb = take(infer ? 0 : D * p->ntile_b * (size_t)p->nkc_b * 1024);
-  p->hfrag_bytes = D * p->nrt * (size_t)p->nkc_f * 1024;
-  p->dzfrag_bytes = D * p->nrt * (size_t)p->nkc_b * 1024;
+  p->ws_Wf = take(D * std::max((size_t)p->ntile_f * 2 * p->nkc_f, (size_t)p->ntile16 * 4 * p->nkc_ll_f) * 1024);
+  p->ws_Wb = take(infer ? 0 : D * std::max((size_t)p->ntile_b * p->nkc_b, (size_t)p->ntile16 * p->nkc_ll_b) * 1024);
+  p->hfrag_bytes = D * p->nrt * (size_t)std::max(p->nkc_f, p->nkc_ll_f) * 1024;
+  p->dzfrag_bytes = D * p->nrt * (size_t)std::max(p->nkc_b, p->nkc_ll_b) * 1024;
   p->ws_hfrag0 = take(p->hfrag_bytes);
   p->ws_hfrag1 = take(p->hfrag_bytes);
   p->ws_dzfrag0 = take(infer ? 0 : p->dzfrag_bytes);
@@ -146,11 +150,24 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     HIPCHK(launch_fill_zero(ws + p.ws_sync, p.sync_bytes, s));
     if (h0) HIPCHK(launch_copy(hstate, h0, state_bytes, s)); else HIPCHK(launch_fill_zero(hstate, state_bytes, s));
     if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else HIPCHK(launch_fill_zero(cstate, state_bytes, s));
-    if (T > 0) {
+  }
+  // single-launch path: bf16 storage, at least two steps, register budget of the kernel
+  bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd;
+  auto pack_fwd = [&](bool ll) -> int {
+    Phase ph(LSTM_PHASE_PREP, 2, s);
+    if (ll) {
+      HIPCHK(launch_pack_wh_fwd_ll(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_ll_f, p.D, s));
+      HIPCHK(launch_pack_state_ll(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_ll_f, p.nrt,
+                                  p.D, s));
+    } else {
       HIPCHK(launch_pack_wh_fwd(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_f, p.D, p.bf16, s));
       HIPCHK(launch_pack_state(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_f, p.nrt,
                                p.D, p.bf16, s));
     }
+    return LSTM_OK;
+  };
+  if (T > 0) {
+    if ((rc = pack_fwd(use_ll))) return rc;
   }
   if (T > 0) {
     // hoisted input projection for all frames and both directions: Zx = X W_x + b
@@ -170,18 +187,16 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     }
 
     bool done = false;
-    const int max_nkc = p.bf16 ? kPersistFwdMaxNkcBf16 : kPersistFwdMaxNkcF32;
-    if (!(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_f <= max_nkc) {
-      Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
+    if (use_ll) {
       PFwdArgs pa = {};
-      pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_f; pa.T = p.T; pa.ndir = p.D; pa.write_gates = infer ? 0 : 1;
+      pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_f; pa.T = p.T; pa.ndir = p.D; pa.write_gates = infer ? 0 : 1;
       pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
-      const size_t frag_dir = (size_t)p.nrt * p.nkc_f * 1024;
+      const size_t frag_dir = (size_t)p.nrt * p.nkc_ll_f * 1024;
       for (size_t d = 0; d < D; ++d) {
         PFwdDir& fd = pa.d[d];
-        fd.Wf = (const uint4*)(ws + p.ws_Wf + d * (size_t)p.ntile_f * 2 * p.nkc_f * 1024);
-        fd.hfrag0 = (uint4*)(ws + p.ws_hfrag0 + d * frag_dir);
-        fd.hfrag1 = (uint4*)(ws + p.ws_hfrag1 + d * frag_dir);
+        fd.Wf = (const uint4*)(ws + p.ws_Wf + d * (size_t)p.ntile16 * 4 * p.nkc_ll_f * 1024);
+        fd.ring0 = (uint4*)(ws + p.ws_hfrag0 + d * frag_dir);
+        fd.ring1 = (uint4*)(ws + p.ws_hfrag1 + d * frag_dir);
         fd.gates = gates + d * gates_stride;
         fd.hstate = hstate + d * B * n;
         fd.cstate = cstate + d * B * n;
@@ -191,9 +206,16 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         fd.hprev = infer ? nullptr : rs + d * p.res_dir_stride + p.res_hprev;
         fd.rev = bidir ? d == 1 : desc->direction == -1;
       }
-      hipError_t e = launch_persist_fwd(pa, p.bf16, s);
+      hipError_t e;
+      {
+        Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
+        e = launch_persist_fwd(pa, s);
+      }
       if (e == hipSuccess) done = true;
-      else (void)hipGetLastError();                 // does not fit on the device together: use one launch per step
+      else {                                        // does not fit on the device all at once: one launch per step
+        (void)hipGetLastError();
+        if ((rc = pack_fwd(false))) return rc;
+      }
     }
     if (!done) {
     Phase ph(LSTM_PHASE_LOOP_FWD, (long)T, s);
@@ -267,25 +289,29 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     Phase ph(LSTM_PHASE_PREP, 5, s);
     if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dh, state_bytes, s));
     if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dc, state_bytes, s));
-    HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
     HIPCHK(launch_fill_zero(ws + p.ws_dzfrag0, p.dzfrag_bytes, s));
     HIPCHK(launch_fill_zero(ws + p.ws_dzfrag1, p.dzfrag_bytes, s));
+  }
+  bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_b <= kLLMaxNkcBwd;
+  {
+    Phase ph(LSTM_PHASE_PREP, 1, s);
+    if (use_ll) HIPCHK(launch_pack_wh_bwd_ll(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_ll_b, p.D, s));
+    else HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
   }
 
   const size_t frag_dir = (size_t)p.nrt * p.nkc_b * 1024;
   char* DZ = ws + p.ws_DZ;
   bool done = false;
-  const int max_nkc = p.bf16 ? kPersistBwdMaxNkcBf16 : kPersistBwdMaxNkcF32;
-  if (!(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_b <= max_nkc) {
-    Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);
+  if (use_ll) {
     PBwdArgs pa = {};
-    pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_b; pa.T = p.T; pa.ndir = p.D;
+    pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_b; pa.T = p.T; pa.ndir = p.D;
     pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
+    const size_t ring_dir = (size_t)p.nrt * p.nkc_ll_b * 1024;
     for (size_t d = 0; d < D; ++d) {
       PBwdDir& bd = pa.d[d];
-      bd.Wb = (const uint4*)(ws + p.ws_Wb + d * (size_t)p.ntile_b * p.nkc_b * 1024);
-      bd.dzfrag0 = (uint4*)(ws + p.ws_dzfrag0 + d * frag_dir);
-      bd.dzfrag1 = (uint4*)(ws + p.ws_dzfrag1 + d * frag_dir);
+      bd.Wb = (const uint4*)(ws + p.ws_Wb + d * (size_t)p.ntile16 * p.nkc_ll_b * 1024);
+      bd.ring0 = (uint4*)(ws + p.ws_dzfrag0 + d * ring_dir);
+      bd.ring1 = (uint4*)(ws + p.ws_dzfrag1 + d * ring_dir);
       bd.gates = (const float*)(rs + d * p.res_dir_stride + p.res_gates);
       bd.cs = (const float*)c + d * T * B * n;
       bd.c0 = c0 ? (const float*)c0 + d * B * n : nullptr;
@@ -296,9 +322,17 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       bd.Dc = Dc + d * B * n;
       bd.rev = bidir ? d == 1 : desc->direction == -1;
     }
-    hipError_t e = launch_persist_bwd(pa, p.bf16, s);
+    hipError_t e;
+    {
+      Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);
+      e = launch_persist_bwd(pa, s);
+    }
     if (e == hipSuccess) done = true;
-    else (void)hipGetLastError();
+    else {
+      (void)hipGetLastError();
+      Phase ph(LSTM_PHASE_PREP, 1, s);
+      HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
+    }
   }
   BwdArgs a = {};
   a.lens = seq_lens; a.B = p.B; a.n = p.n; a.nkc = p.nkc_b; a.T = p.T; a.ndir = p.D;

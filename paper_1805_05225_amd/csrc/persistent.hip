@@ -1,70 +1,105 @@
-// Persistent recurrent kernels: the whole time loop of a layer in ONE launch.
+// Single-launch recurrent kernels: the whole time loop of a layer in ONE launch (bfloat16 storage).
 //
 // The per-step kernels pay a launch per time step and re-read their W_h slice from the memory
-// system every step.  Here each work-group loads its slice of the packed W_h into registers once
-// (bf16, n = 1024: 64 KiB per work-group forward, 128 KiB backward) and then walks all T steps.
-// Only h_t (forward) or dz_t (backward) crosses work-groups: it is written in MFMA fragment
-// order to a two-deep ring in global memory, and the work-groups of one (direction, row block)
-// meet at a monotonically increasing counter between steps:
+// system every step.  Here each work-group (16 hidden units x 16 batch rows) loads its slice of
+// the packed W_h into registers once and then walks all T steps.
 //
-//   producer:  stores ; __syncthreads ; thread 0: release fence (agent scope), counter += 1
-//   consumer:  wave 0 polls the counter (bounded), acquire fence (agent scope) ; __syncthreads ; loads
+// Only h_t (forward) or dz_t (backward) crosses work-groups.  Measurements on this device showed
+// that a counter barrier is the wrong tool: atomics on one address serialise at ~16 ns each
+// (4 us for 256 work-groups) and agent-scope fences cost microseconds more.  So there is no
+// barrier and no fence here.  The exchanged data lives in a two-slot ring whose every 8-byte unit
+// holds three bf16 values and a 16-bit step tag, written with one 64-bit agent-scope atomic store
+// and read with cache-bypassing 16-byte loads.  A consumer simply re-reads its operands until
+// every tag shows the step it is waiting for: value and "ready" flag arrive in the same atomic
+// unit, so no ordering between different addresses is ever needed.
 //
-// The eight XCDs of the device have separate L2 caches, so the agent-scope fences are what makes
-// the ring visible across them.  Two ring slots suffice: a work-group can write slot s for step
-// t+1 only after every work-group has signalled step t, i.e. after all reads of slot s for step
-// t-1 have been issued and consumed.
+// Two ring slots suffice: a work-group writes slot s for step t+1 only after it has seen every
+// tag of step t, i.e. after every work-group has finished step t and therefore finished reading
+// slot s (which held step t-1).
 //
-// Every wait is bounded: when `spin_limit` polls pass without progress the work-group raises the
-// error word sync[0] and leaves; all others notice the word in their own waits and leave too, so
-// the grid always drains.  The launch is cooperative, which guarantees that all work-groups are
+// Every wait is bounded: after `spin_limit` polls the wave raises the error word sync[0], stops
+// waiting for the rest of the launch and runs to the end (results are then invalid and the word
+// says so); every other wave notices the word in its own wait loop and does the same, so the
+// grid always drains.  The launch is cooperative, which guarantees that all work-groups are
 // resident together (otherwise the launch is refused and the caller uses the per-step kernels).
 #include "recurrent_dev.h"
 
 namespace lstm {
 namespace {
 
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
+// cache policy of the polling loads: bit 4 = coherent at agent scope (bypasses the XCD-local L2),
+// bit 31 = volatile, so the compiler re-issues the load in every poll
+constexpr int kSc1 = (int)(16u | 0x80000000u);
+
 __device__ __forceinline__ unsigned ld_relaxed(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_relaxed(unsigned* p, unsigned v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-// Executed by wave 0 only.  Returns true when *cnt >= target was observed.
-__device__ __forceinline__ bool wait_counter(const unsigned* cnt, unsigned target, unsigned* err, unsigned limit) {
-  for (unsigned i = 0; i < limit; ++i) {
-    if (ld_relaxed(cnt) >= target) return true;
-    if ((i & 31u) == 31u && ld_relaxed(err) != 0u) return false;
-    __builtin_amdgcn_s_sleep(1);
+// Loads chunks kc = wave + 4*(it0 + i), i < N, of one row tile of a ring slot until every tag equals `tag`.
+// `base` points at the row tile; chunks at or beyond `nchunk_valid` are never written and are zeroed instead of checked.
+// On return the tag positions are cleared so the registers are clean MFMA operands.
+template <int N>
+__device__ __forceinline__ void poll_operands(uint4 (&av)[N], const uint4* base, int nkc, int nchunk_valid, int wave, int lane,
+                                              int it0, unsigned tag, bool& dead, unsigned* err, unsigned limit) {
+  __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nkc * 1024, kBufFlags);
+  const int g = lane >> 4;
+  for (unsigned poll = 0;; ++poll) {
+    bool fresh = true;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int kc = wave + 4 * (it0 + i);
+      av[i] = make_uint4(0, 0, 0, 0);
+      if (kc < nkc) {
+        const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, (kc * 64 + lane) * 16, 0, kSc1);
+        if (kc * 4 + g < nchunk_valid) {
+          fresh = fresh && (x[1] >> 16) == tag && (x[3] >> 16) == tag;
+          av[i] = make_uint4(x[0], x[1] & 0xffffu, x[2], x[3] & 0xffffu);
+        }
+      }
+    }
+    if (dead || __all(fresh)) return;
+    if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+      st_relaxed(err, 1u);
+      dead = true;
+      return;
+    }
   }
-  __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return false;
+}
+
+__device__ __forceinline__ void store_unit(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
+  const unsigned long long u = (unsigned long long)(v0 | (v1 << 16)) | ((unsigned long long)(v2 | (tag << 16)) << 32);
+  __hip_atomic_store((unsigned long long*)ring + unit_index, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename ST, int NIT>
+// forward: z[16 rows, 4 gates x 16 units] = h[16 rows, K] W[K, 64]
+template <int NIT>
 __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
-  __shared__ float red[4][32][33];
-  __shared__ int s_ok;
+  __shared__ float red[4][16][65];
+  __shared__ unsigned short hb[16][18];
   const PFwdDir& d = a.d[blockIdx.z];
-  const int tile = blockIdx.x, rb = blockIdx.y, ntiles = gridDim.x;
+  const int tile = blockIdx.x, rt = blockIdx.y, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   unsigned* err = a.sync;
-  unsigned* cnt = a.sync + 1 + blockIdx.z * gridDim.y + rb;
+  bool dead = false;
 
-  // this work-group's slice of W_h, resident in registers for the whole sequence
-  uint4 w0[NIT], w1[NIT];
+  uint4 w[NIT][4];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int kc = wave + 4 * it;
-    w0[it] = w1[it] = make_uint4(0, 0, 0, 0);
-    if (kc < nkc) {
-      w0[it] = d.Wf[((long)(tile * 2 + 0) * nkc + kc) * 64 + lane];
-      w1[it] = d.Wf[((long)(tile * 2 + 1) * nkc + kc) * 64 + lane];
-    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      w[it][q] = kc < nkc ? d.Wf[((long)(tile * 4 + q) * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
   }
 
-  const int r = tid >> 3, u = tid & 7;
-  const int b = rb * 32 + r, j = tile * 8 + u;
+  const int r = tid >> 4, u = tid & 15;
+  const int b = rt * 16 + r, j = tile * 16 + u;
   const bool active = b < B && j < n;
   float c = 0.f, h = 0.f;
   int L = 0;
@@ -73,7 +108,10 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
     h = d.hstate[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
-  const long hoff = active ? frag_offset<ST>(b, j, nkc) : 0;
+  // the unit this thread publishes (threads 0..95): row r2, unit m of this producer's 6
+  const int r2 = tid / 6, m = tid - 6 * r2;
+  const int cch = tile * 3 + (m >> 1);
+  const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r2) * 2 + (m & 1);
 
   for (int tau = 0; tau < T; ++tau) {
     const int t = d.rev ? T - 1 - tau : tau;
@@ -83,64 +121,48 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
     const bool valid = active && t < L;
     if (valid) { zx[0] = gp[0]; zx[1] = gp[n]; zx[2] = gp[2 * n]; zx[3] = gp[3 * n]; }
 
-    if (tau > 0) {
-      if (wave == 0) {
-        const bool ok = wait_counter(cnt, (unsigned)tau * ntiles, err, a.spin_limit);
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        if (lane == 0) s_ok = ok;
-      }
-      __syncthreads();
-      if (!s_ok) break;
-    }
-    const uint4* hin = (tau & 1) ? d.hfrag1 : d.hfrag0;
-    void* hout = (tau & 1) ? (void*)d.hfrag0 : (void*)d.hfrag1;
+    const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
+    uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
+    uint4 av[NIT];
+    poll_operands<NIT>(av, rin, nkc, ntiles * 3, wave, lane, 0, (unsigned)(tau + 1) & 0xffffu, dead, err, a.spin_limit);
 
-    f32x4 acc[2][2];
+    f32x4 acc[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) acc[i][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const uint4* hA0 = hin + ((long)(rb * 2 + 0) * nkc) * 64 + lane;
-    const uint4* hA1 = hin + ((long)(rb * 2 + 1) * nkc) * 64 + lane;
+    for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-      const int kc = wave + 4 * it;
-      if (kc < nkc) {
-        const uint4 a0 = hA0[(long)kc * 64], a1 = hA1[(long)kc * 64];
-        acc[0][0] = Mma16<ST>::run(a0, w0[it], acc[0][0]);
-        acc[0][1] = Mma16<ST>::run(a0, w1[it], acc[0][1]);
-        acc[1][0] = Mma16<ST>::run(a1, w0[it], acc[1][0]);
-        acc[1][1] = Mma16<ST>::run(a1, w1[it], acc[1][1]);
+      if (wave + 4 * it < nkc) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = Mma16<bf16_t>::run(av[it], w[it][q], acc[q]);
       }
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int q = 0; q < 4; ++q)
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][i * 16 + 4 * (lane >> 4) + v][jj * 16 + (lane & 15)] = acc[i][jj][v];
+      for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][q * 16 + (lane & 15)] = acc[q][v];
     __syncthreads();
 
+    const float h_prev = h;
     if (active) {
-      const float h_prev = h;
       float yv = 0.f;
       if (valid) {
         float zh[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) zh[q] = red[0][r][q * 8 + u] + red[1][r][q * 8 + u] + red[2][r][q * 8 + u] + red[3][r][q * 8 + u];
+        for (int q = 0; q < 4; ++q) zh[q] = red[0][r][q * 16 + u] + red[1][r][q * 16 + u] + red[2][r][q * 16 + u] + red[3][r][q * 16 + u];
         const CellOut o = lstm_cell(zh, zx, c);
         c = o.c; h = o.h; yv = o.h;
         if (a.write_gates) { gp[0] = o.gi; gp[n] = o.gf; gp[2 * n] = o.gg; gp[3 * n] = o.go; }
       }
-      Store<ST>::store(hout, hoff, h);
-      Store<ST>::store(d.y, ((long)t * B + b) * d.ldy + j, yv);
+      Store<bf16_t>::store(d.y, ((long)t * B + b) * d.ldy + j, yv);
       if (d.cs) d.cs[((long)t * B + b) * n + j] = c;
-      if (d.hprev) Store<ST>::store(d.hprev, ((long)t * B + b) * n + j, h_prev);
+      if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)t * B + b) * n + j, h_prev);
     }
+    hb[r][u] = f2bf_bits(h);          // inactive threads hold h = 0: padding rows / units publish zeros
     __syncthreads();
-    if (tid == 0) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-      __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid < 96) {
+      const int v0 = 3 * m;
+      const unsigned x0 = hb[r2][v0], x1 = v0 + 1 < 16 ? hb[r2][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[r2][v0 + 2] : 0u;
+      store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
     }
   }
   if (active) {
@@ -150,16 +172,18 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename ST, int NIT>
+// backward: Dh[16 rows, 16 units] = dz[16 rows, K] W^T[K, 16], then the gate gradients of this frame
+template <int NIT>
 __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
+  static_assert(NIT % 2 == 0, "operands are polled in two halves");
   __shared__ float red[4][16][17];
-  __shared__ int s_ok;
+  __shared__ unsigned short zb[16][66];
   const PBwdDir& d = a.d[blockIdx.z];
   const int tile = blockIdx.x, rt = blockIdx.y, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   unsigned* err = a.sync;
-  unsigned* cnt = a.sync + 1 + blockIdx.z * gridDim.y + rt;
+  bool dead = false;
 
   uint4 w[NIT];
 #pragma unroll
@@ -178,13 +202,9 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
     Dc = d.Dc[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
-  long zoff[4] = {0, 0, 0, 0};
-  if (active) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) zoff[q] = frag_offset<ST>(b, q * n + j, nkc);
-  }
 
   for (int tau = T - 1; tau >= -1; --tau) {
+    const int sigma = T - 1 - tau;                       // 0, 1, ... : count of backward steps done before this one
     const int t = d.rev ? T - 1 - tau : tau;             // frame of this step (out of range when tau == -1)
     const int t_next = d.rev ? t - 1 : t + 1;            // frame of the previous backward step
     const bool pointwise = tau >= 0;
@@ -198,24 +218,20 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
       const int tp = d.rev ? t + 1 : t - 1;               // frame processed just before t in the forward pass
       if (tp >= 0 && tp < T) c_prev = d.cs[((long)tp * B + b) * n + j];
       else if (d.c0) c_prev = d.c0[(long)b * n + j];
-      dyv = Store<ST>::load(d.dy, ((long)t * B + b) * d.lddy + j);
+      dyv = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
     }
 
-    if (tau < T - 1) {
-      if (wave == 0) {
-        const bool ok = wait_counter(cnt, (unsigned)(T - 1 - tau) * ntiles, err, a.spin_limit);
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        if (lane == 0) s_ok = ok;
-      }
-      __syncthreads();
-      if (!s_ok) break;
-      const uint4* zin = ((tau + 1) & 1) ? d.dzfrag1 : d.dzfrag0;
-      const uint4* Ap = zin + ((long)rt * nkc) * 64 + lane;
+    if (sigma > 0) {
+      const uint4* rin = (((sigma - 1) & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
+      const unsigned tag = (unsigned)sigma & 0xffffu;
       f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int kc = wave + 4 * it;
-        if (kc < nkc) acc = Mma16<ST>::run(Ap[(long)kc * 64], w[it], acc);
+      for (int half = 0; half < 2; ++half) {
+        uint4 av[NIT / 2];
+        poll_operands<NIT / 2>(av, rin, nkc, ntiles * 11, wave, lane, half * (NIT / 2), tag, dead, err, a.spin_limit);
+#pragma unroll
+        for (int i = 0; i < NIT / 2; ++i)
+          if (wave + 4 * (half * (NIT / 2) + i) < nkc) acc = Mma16<bf16_t>::run(av[i], w[half * (NIT / 2) + i], acc);
       }
 #pragma unroll
       for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = acc[v];
@@ -223,21 +239,29 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
       if (active && t_next < L) Dh = red[0][r][u] + red[1][r][u] + red[2][r][u] + red[3][r][u];
     }
     if (pointwise) {
-      if (active) {
-        float dz[4] = {0.f, 0.f, 0.f, 0.f};
-        if (valid) lstm_cell_grad(gi, gf, gg, go, c_new, c_prev, dyv + Dh, Dc, dz);
-        void* zout = (tau & 1) ? (void*)d.dzfrag1 : (void*)d.dzfrag0;
+      float dz[4] = {0.f, 0.f, 0.f, 0.f};
+      if (valid) lstm_cell_grad(gi, gf, gg, go, c_new, c_prev, dyv + Dh, Dc, dz);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          Store<ST>::store(d.DZ, ((long)t * B + b) * 4 * n + q * n + j, dz[q]);
-          Store<ST>::store(zout, zoff[q], dz[q]);
-        }
+      for (int q = 0; q < 4; ++q) {
+        const unsigned short bits = f2bf_bits(dz[q]);
+        if (active) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits;
+        zb[r][q * 16 + u] = bits;                          // inactive threads publish zeros
       }
       __syncthreads();
-      if (tid == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint4* rout = (sigma & 1) ? d.ring1 : d.ring0;
+      const unsigned tag_out = (unsigned)(sigma + 1) & 0xffffu;
+#pragma unroll
+      for (int round = 0; round < 2; ++round) {
+        const int id = tid + 256 * round;
+        if (id < 16 * 22) {
+          const int r2 = id / 22, m = id - 22 * r2, v0 = 3 * m;
+          const unsigned x0 = zb[r2][v0], x1 = v0 + 1 < 64 ? zb[r2][v0 + 1] : 0u, x2 = v0 + 2 < 64 ? zb[r2][v0 + 2] : 0u;
+          const int cch = tile * 11 + (m >> 1);
+          const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r2) * 2 + (m & 1);
+          store_unit(rout, unit_index, x0, x1, x2, tag_out);
+        }
       }
+      __syncthreads();                                      // zb and red are reused by the next step
     }
   }
   if (active) {
@@ -246,8 +270,85 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// packing for the ring layout
+// forward weights: chunk index = (((dir*ntile + tile)*4 + q)*nkc + kc)*64 + lane
+__global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nkc, long total) {
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = idx & 63;
+  long rest = idx >> 6;
+  const int kc = rest % nkc; rest /= nkc;
+  const int q = rest & 3; rest >>= 2;
+  const int ntile = (n + 15) / 16;
+  const int tile = rest % ntile, dir = rest / ntile;
+  const int j = tile * 16 + (lane & 15), g = lane >> 4;
+  const bf16_t* Wd = W + (long)dir * n * 4 * n;
+  bf16_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int s = (kc * 4 + g) * 8 + e;
+    const int p = s / kLLSlotsFwd, val = ll_slot_value(s - p * kLLSlotsFwd, kLLValsFwd);
+    const int k = p * 16 + val;
+    v[e] = (val >= 0 && k < n && j < n) ? Wd[(long)k * 4 * n + q * n + j] : (bf16_t)0.f;
+  }
+  out[idx] = *(uint4*)v;
+}
+// backward weights: chunk index = ((dir*ntile + tile)*nkc + kc)*64 + lane ; K runs over the producers' dz values
+__global__ void pack_wh_bwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nkc, long total) {
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = idx & 63;
+  long rest = idx >> 6;
+  const int kc = rest % nkc; rest /= nkc;
+  const int ntile = (n + 15) / 16;
+  const int tile = rest % ntile, dir = rest / ntile;
+  const int unit = tile * 16 + (lane & 15), g = lane >> 4;
+  const bf16_t* Wd = W + (long)dir * n * 4 * n;
+  bf16_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int s = (kc * 4 + g) * 8 + e;
+    const int p = s / kLLSlotsBwd, val = ll_slot_value(s - p * kLLSlotsBwd, kLLValsBwd);
+    const int ju = p * 16 + (val & 15), q = val >> 4;
+    v[e] = (val >= 0 && ju < n && unit < n) ? Wd[(long)unit * 4 * n + q * n + ju] : (bf16_t)0.f;
+  }
+  out[idx] = *(uint4*)v;
+}
+// initial state: unit index = ((((dir*nrt + rt)*nkc + kc)*64 + lane)*2 + half) ; ring0 gets h with tag 1, ring1 zeros
+__global__ void pack_state_ll_kernel(const float* h, uint4* ring0, uint4* ring1, int B, int n, int nkc, int nrt, long total) {
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int half = idx & 1, lane = (idx >> 1) & 63;
+  long rest = idx >> 7;
+  const int kc = rest % nkc; rest /= nkc;
+  const int rt = rest % nrt, dir = rest / nrt;
+  const int row = rt * 16 + (lane & 15), g = lane >> 4;
+  const int U = (kc * 4 + g) * 2 + half;       // unit-of-three index along K
+  const int p = U / 6, m = U - 6 * p;
+  unsigned x[3];
+#pragma unroll
+  for (int e = 0; e < 3; ++e) {
+    const int val = 3 * m + e, k = p * 16 + val;
+    x[e] = (val < 16 && k < n && row < B) ? (unsigned)f2bf_bits(h[((long)dir * B + row) * n + k]) : 0u;
+  }
+  ((unsigned long long*)ring0)[idx] = (unsigned long long)(x[0] | (x[1] << 16)) | ((unsigned long long)(x[2] | (1u << 16)) << 32);
+  ((unsigned long long*)ring1)[idx] = 0ull;
+}
+
+// Cooperative launch; refuses (without launching) a grid that cannot be resident all at once.
 template <typename K, typename A>
 hipError_t coop(K kernel, dim3 grid, const A& a, hipStream_t s) {
+  static int capacity = -1;             // work-groups of this kernel the current device can hold at once
+  if (capacity < 0) {
+    int dev = 0, per_cu = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess)
+      return hipErrorUnknown;
+    capacity = per_cu * prop.multiProcessorCount;
+  }
+  if ((long)grid.x * grid.y * grid.z > capacity) return hipErrorCooperativeLaunchTooLarge;
   A copy = a;
   void* args[] = {&copy};
   return hipLaunchCooperativeKernel((const void*)kernel, grid, dim3(256), args, 0, s);
@@ -255,24 +356,29 @@ hipError_t coop(K kernel, dim3 grid, const A& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_persist_fwd(const PFwdArgs& a, bool bf16, hipStream_t s) {
-  dim3 grid(cdiv(a.n, 8), cdiv(a.B, 32), a.ndir);
-  if (bf16) {
-    if (a.nkc > kPersistFwdMaxNkcBf16) return hipErrorCooperativeLaunchTooLarge;
-    return coop(persist_fwd_kernel<bf16_t, kPersistFwdMaxNkcBf16 / 4>, grid, a, s);
-  }
-  if (a.nkc > kPersistFwdMaxNkcF32) return hipErrorCooperativeLaunchTooLarge;
-  return coop(persist_fwd_kernel<float, kPersistFwdMaxNkcF32 / 4>, grid, a, s);
+hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
+  if (a.nkc > kLLMaxNkcFwd) return hipErrorCooperativeLaunchTooLarge;
+  return coop(persist_fwd_kernel<kLLMaxNkcFwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
 }
-
-hipError_t launch_persist_bwd(const PBwdArgs& a, bool bf16, hipStream_t s) {
-  dim3 grid(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir);
-  if (bf16) {
-    if (a.nkc > kPersistBwdMaxNkcBf16) return hipErrorCooperativeLaunchTooLarge;
-    return coop(persist_bwd_kernel<bf16_t, kPersistBwdMaxNkcBf16 / 4>, grid, a, s);
-  }
-  if (a.nkc > kPersistBwdMaxNkcF32) return hipErrorCooperativeLaunchTooLarge;
-  return coop(persist_bwd_kernel<float, kPersistBwdMaxNkcF32 / 4>, grid, a, s);
+hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s) {
+  if (a.nkc > kLLMaxNkcBwd) return hipErrorCooperativeLaunchTooLarge;
+  return coop(persist_bwd_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
+}
+hipError_t launch_pack_wh_fwd_ll(const void* W, uint4* Wf, int n, int nkc, int ndir, hipStream_t s) {
+  long total = (long)ndir * cdiv(n, 16) * 4 * nkc * 64;
+  hipLaunchKernelGGL(pack_wh_fwd_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wf, n, nkc, total);
+  return hipGetLastError();
+}
+hipError_t launch_pack_wh_bwd_ll(const void* W, uint4* Wb, int n, int nkc, int ndir, hipStream_t s) {
+  long total = (long)ndir * cdiv(n, 16) * nkc * 64;
+  hipLaunchKernelGGL(pack_wh_bwd_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wb, n, nkc, total);
+  return hipGetLastError();
+}
+hipError_t launch_pack_state_ll(const float* h, uint4* ring0, uint4* ring1, int B, int n, int nkc, int nrt, int ndir,
+                                hipStream_t s) {
+  long total = (long)ndir * nrt * nkc * 64 * 2;
+  hipLaunchKernelGGL(pack_state_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, h, ring0, ring1, B, n, nkc, nrt, total);
+  return hipGetLastError();
 }
 
 }  // namespace lstm

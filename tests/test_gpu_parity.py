@@ -208,7 +208,7 @@ def test_accumulate_flag_adds_into_gradients():
 
 
 # ---- the single-launch recurrent kernels against one launch per time step ------------------------------------
-@pytest.mark.parametrize("dt,B,n,T", [("bf16", 32, 64, 40), ("f32", 5, 20, 9), ("bf16", 70, 136, 25), ("bf16", 32, 1024, 12)])
+@pytest.mark.parametrize("dt,B,n,T", [("bf16", 32, 64, 40), ("f32", 5, 20, 9), ("bf16", 70, 136, 25), ("bf16", 32, 1024, 12), ("bf16", 19, 1000, 7)])
 def test_single_launch_equals_per_step(dt, B, n, T):
     rng = np.random.default_rng(B * n + T)
     lens = rng.integers(0, T + 1, B)
@@ -217,12 +217,14 @@ def test_single_launch_equals_per_step(dt, B, n, T):
     print("  single launch vs per step", dt, B, n, T, flush=True)
     f1, g1 = run_gpu(c, dt, True)
     f2, g2 = run_gpu(c, dt, True, flags=Bn.FLAG_PER_STEP)
+    # the two paths sum over K in different orders, so they agree to rounding, not bit for bit
     for k in ("y", "c", "hT", "cT"):
-        assert torch.equal(f1[k], f2[k]), k
+        check(k + " (paths)", f1[k], host(f2[k]), 1e-5 if dt == "f32" else 1e-2)
     for k in ("dx", "dW_x", "dW_h", "db", "dh0", "dc0"):
-        assert torch.equal(g1[k], g2[k]), k
+        check(k + " (paths)", g1[k], host(g2[k]), 1e-5 if dt == "f32" else 1e-2)
     fo, go = run_oracle(c, True)
     compare(f1, g1, fo, go, TOL[dt])
+    compare(f2, g2, fo, go, TOL[dt])
 
 
 # ---- the benchmark configurations ------------------------------------------------------------------------------
