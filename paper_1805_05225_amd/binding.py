@@ -10,7 +10,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmi355x_lstm.so")
+LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm.so"))   # override: diagnostic builds
 
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE = 1, 2, 4

@@ -28,6 +28,21 @@ namespace lstm {
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+// Optional in-kernel phase clocks (build with -DLSTM_PROF; prints from a few work-groups at the end).
+#ifdef LSTM_PROF
+#define PROF_DECL long long pt_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; long long pc_ = wall_clock64(); unsigned npoll_ = 0;
+#define PROF_MARK(i) { long long now_ = wall_clock64(); pt_[i] += now_ - pc_; pc_ = now_; }
+#define PROF_POLLS(n) npoll_ += (n);
+#define PROF_DUMP(name, steps) if ((tid & 63) == 0 && (blockIdx.x % 23) == 0 && blockIdx.y == 0) \
+  printf("%s wg(%d,%d,%d) wave %d: ns/step poll %lld mma %lld red+cell %lld publish %lld other %lld polls/step %.2f\n", name, blockIdx.x, blockIdx.y, blockIdx.z, tid >> 6, \
+         pt_[0] * 10 / (steps), pt_[1] * 10 / (steps), pt_[2] * 10 / (steps), pt_[3] * 10 / (steps), pt_[4] * 10 / (steps), (double)npoll_ / (steps));
+#else
+#define PROF_DECL
+#define PROF_MARK(i)
+#define PROF_POLLS(n)
+#define PROF_DUMP(name, steps)
+#endif
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
 // cache policy of the polling loads: bit 4 = coherent at agent scope (bypasses the XCD-local L2),
 // bit 31 = volatile, so the compiler re-issues the load in every poll
@@ -40,35 +55,80 @@ __device__ __forceinline__ void st_relaxed(unsigned* p, unsigned v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Loads chunks kc = wave + 4*(it0 + i), i < N, of one row tile of a ring slot until every tag equals `tag`.
-// `base` points at the row tile; chunks at or beyond `nchunk_valid` are never written and are zeroed instead of checked.
-// On return the tag positions are cleared so the registers are clean MFMA operands.
-template <int N>
-__device__ __forceinline__ void poll_operands(uint4 (&av)[N], const uint4* base, int nkc, int nchunk_valid, int wave, int lane,
-                                              int it0, unsigned tag, bool& dead, unsigned* err, unsigned limit) {
-  __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nkc * 1024, kBufFlags);
-  const int g = lane >> 4;
-  for (unsigned poll = 0;; ++poll) {
-    bool fresh = true;
+// Ring reads.  One wavefront owns chunks kc = wave + 4*it of its row tile.  Reads of freshly written
+// remote data are latency-bound per compute unit and degrade when more than ~12 KiB per wavefront is in
+// flight, so (a) a wave first polls ONE chunk (its last) until that shows the awaited tag, which is cheap
+// while the producers are still busy, and only then (b) fetches its operands in batches of at most 12
+// chunks, checking every tag; a batch with a stale tag is simply fetched again.
+struct RingReader {
+  __amdgpu_buffer_rsrc_t rs;
+  int nkc, nchunk_valid, wave, lane;
+  unsigned tag;
+  unsigned* err;
+  unsigned limit;
+
+  __device__ __forceinline__ u32x4 load(int kc) const {
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, (kc * 64 + lane) * 16, 0, kSc1);
+  }
+  __device__ __forceinline__ bool chunk_fresh(const u32x4& x, int kc) const {
+    return kc * 4 + (lane >> 4) >= nchunk_valid || ((x[1] >> 16) == tag && (x[3] >> 16) == tag);
+  }
+  // bounded wait on the wave's last chunk; returns the number of polls (diagnostics only)
+  __device__ __forceinline__ unsigned wait_sample(bool& dead) const {
+    if (dead || wave >= nkc) return 0;
+    const int kc = wave + 4 * ((nkc - 1 - wave) / 4);          // last chunk of this wave
+    for (unsigned poll = 0;; ++poll) {
+      const u32x4 x = load(kc);
+      if (__all(chunk_fresh(x, kc))) return poll + 1;
+      if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+        st_relaxed(err, 1u);
+        dead = true;
+        return poll + 1;
+      }
+    }
+  }
+  template <int N>
+  __device__ __forceinline__ void issue(u32x4 (&x)[N], int it0) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int kc = wave + 4 * (it0 + i);
-      av[i] = make_uint4(0, 0, 0, 0);
-      if (kc < nkc) {
-        const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, (kc * 64 + lane) * 16, 0, kSc1);
-        if (kc * 4 + g < nchunk_valid) {
-          fresh = fresh && (x[1] >> 16) == tag && (x[3] >> 16) == tag;
-          av[i] = make_uint4(x[0], x[1] & 0xffffu, x[2], x[3] & 0xffffu);
-        }
-      }
-    }
-    if (dead || __all(fresh)) return;
-    if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
-      st_relaxed(err, 1u);
-      dead = true;
-      return;
+      x[i] = (u32x4){0u, 0u, 0u, 0u};
+      if (kc < nkc) x[i] = load(kc);
     }
   }
+  // checks the tags of a fetched batch (fetching it again while any is stale) and strips them
+  template <int N>
+  __device__ __forceinline__ void settle(u32x4 (&x)[N], uint4 (&av)[N], int it0, bool& dead) const {
+    for (unsigned poll = 0;; ++poll) {
+      bool fresh = true;
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const int kc = wave + 4 * (it0 + i);
+        if (kc < nkc) fresh = fresh && chunk_fresh(x[i], kc);
+      }
+      if (dead || __all(fresh)) break;
+      if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+        st_relaxed(err, 1u);
+        dead = true;
+        break;
+      }
+      issue<N>(x, it0);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int kc = wave + 4 * (it0 + i);
+      const bool use = kc < nkc && kc * 4 + (lane >> 4) < nchunk_valid;
+      av[i] = use ? make_uint4(x[i][0], x[i][1] & 0xffffu, x[i][2], x[i][3] & 0xffffu) : make_uint4(0, 0, 0, 0);
+    }
+  }
+};
+
+__device__ __forceinline__ RingReader make_reader(const uint4* base, int nkc, int nchunk_valid, int wave, int lane, unsigned tag,
+                                                   unsigned* err, unsigned limit) {
+  RingReader r;
+  r.rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nkc * 1024, kBufFlags);
+  r.nkc = nkc; r.nchunk_valid = nchunk_valid; r.wave = wave; r.lane = lane; r.tag = tag; r.err = err; r.limit = limit;
+  return r;
 }
 
 __device__ __forceinline__ void store_unit(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
@@ -113,58 +173,88 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
   const int cch = tile * 3 + (m >> 1);
   const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r2) * 2 + (m & 1);
 
+  // x W_x + b of a frame does not depend on the recurrence: it is fetched one step ahead
+  float zx[4] = {0.f, 0.f, 0.f, 0.f}, zx_next[4] = {0.f, 0.f, 0.f, 0.f};
+  auto fetch_zx = [&](int tau, float (&z)[4]) {
+    const int t = d.rev ? T - 1 - tau : tau;
+    if (tau < T && active && t < L) {
+      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
+      z[0] = gp[0]; z[1] = gp[n]; z[2] = gp[2 * n]; z[3] = gp[3 * n];
+    }
+  };
+  fetch_zx(0, zx);
+  // Outputs of a step are written one step late, after the next step's operands have arrived, so that the
+  // waits of the ring reads never queue behind these stores (loads and stores share one completion counter).
+  struct Out { float y, c, h_prev, gi, gf, gg, go; int t; bool valid; } pend = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, -1, false};
+  auto flush = [&](const Out& p) {
+    if (!active || p.t < 0) return;
+    Store<bf16_t>::store(d.y, ((long)p.t * B + b) * d.ldy + j, p.y);
+    if (d.cs) d.cs[((long)p.t * B + b) * n + j] = p.c;
+    if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)p.t * B + b) * n + j, p.h_prev);
+    if (p.valid && a.write_gates) {
+      float* gp = d.gates + ((long)p.t * B + b) * 4 * n + j;
+      gp[0] = p.gi; gp[n] = p.gf; gp[2 * n] = p.gg; gp[3 * n] = p.go;
+    }
+  };
+
+  PROF_DECL
   for (int tau = 0; tau < T; ++tau) {
     const int t = d.rev ? T - 1 - tau : tau;
-    // the input projection of this frame does not depend on the recurrence: fetch it before waiting
-    float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-    float zx[4] = {0.f, 0.f, 0.f, 0.f};
     const bool valid = active && t < L;
-    if (valid) { zx[0] = gp[0]; zx[1] = gp[n]; zx[2] = gp[2 * n]; zx[3] = gp[3 * n]; }
-
+    PROF_MARK(4)
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
     uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
+    const RingReader rd = make_reader(rin, nkc, ntiles * 3, wave, lane, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit);
+    const unsigned np_ = rd.wait_sample(dead);
+    (void)np_;
+    PROF_POLLS(np_)
+    u32x4 raw[NIT];
     uint4 av[NIT];
-    poll_operands<NIT>(av, rin, nkc, ntiles * 3, wave, lane, 0, (unsigned)(tau + 1) & 0xffffu, dead, err, a.spin_limit);
+    rd.issue<NIT>(raw, 0);
+    fetch_zx(tau + 1, zx_next);
+    rd.settle<NIT>(raw, av, 0, dead);
+    flush(pend);
+    PROF_MARK(0)
 
     f32x4 acc[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      if (wave + 4 * it < nkc) {
+    for (int it = 0; it < NIT; ++it)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) acc[q] = Mma16<bf16_t>::run(av[it], w[it][q], acc[q]);
-      }
-    }
+      for (int q = 0; q < 4; ++q) acc[q] = Mma16<bf16_t>::run(av[it], w[it][q], acc[q]);
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
       for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][q * 16 + (lane & 15)] = acc[q][v];
+    PROF_MARK(1)
     __syncthreads();
 
     const float h_prev = h;
-    if (active) {
-      float yv = 0.f;
-      if (valid) {
-        float zh[4];
+    CellOut o = {};
+    if (valid) {
+      float zh[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) zh[q] = red[0][r][q * 16 + u] + red[1][r][q * 16 + u] + red[2][r][q * 16 + u] + red[3][r][q * 16 + u];
-        const CellOut o = lstm_cell(zh, zx, c);
-        c = o.c; h = o.h; yv = o.h;
-        if (a.write_gates) { gp[0] = o.gi; gp[n] = o.gf; gp[2 * n] = o.gg; gp[3 * n] = o.go; }
-      }
-      Store<bf16_t>::store(d.y, ((long)t * B + b) * d.ldy + j, yv);
-      if (d.cs) d.cs[((long)t * B + b) * n + j] = c;
-      if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)t * B + b) * n + j, h_prev);
+      for (int q = 0; q < 4; ++q) zh[q] = red[0][r][q * 16 + u] + red[1][r][q * 16 + u] + red[2][r][q * 16 + u] + red[3][r][q * 16 + u];
+      o = lstm_cell(zh, zx, c);
+      c = o.c; h = o.h;
     }
     hb[r][u] = f2bf_bits(h);          // inactive threads hold h = 0: padding rows / units publish zeros
     __syncthreads();
-    if (tid < 96) {
+    PROF_MARK(2)
+    if (tid < 96) {                   // the recurrence's critical store goes out first
       const int v0 = 3 * m;
       const unsigned x0 = hb[r2][v0], x1 = v0 + 1 < 16 ? hb[r2][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[r2][v0 + 2] : 0u;
       store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
     }
+    pend = Out{valid ? h : 0.f, c, h_prev, o.gi, o.gf, o.gg, o.go, t, valid};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) zx[q] = zx_next[q];
+    PROF_MARK(3)
   }
+  flush(pend);
+  PROF_DUMP("fwd", T)
   if (active) {
     d.cstate[(long)b * n + j] = c;
     d.hstate[(long)b * n + j] = h;
@@ -173,9 +263,12 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 // backward: Dh[16 rows, 16 units] = dz[16 rows, K] W^T[K, 16], then the gate gradients of this frame
+struct BwdIn { float gi, gf, gg, go, c_new, c_prev, dy; };
+
 template <int NIT>
 __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
-  static_assert(NIT % 2 == 0, "operands are polled in two halves");
+  constexpr int NB = 4, BS = NIT / NB;           // operand batches per step
+  static_assert(NIT % NB == 0, "operands are fetched in equal batches");
   __shared__ float red[4][16][17];
   __shared__ unsigned short zb[16][66];
   const PBwdDir& d = a.d[blockIdx.z];
@@ -202,52 +295,84 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
     Dc = d.Dc[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
+  // everything the gate gradients need except Dh is independent of the recurrence: fetched one step ahead
+  auto fetch_in = [&](int tau) {
+    BwdIn in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int t = d.rev ? T - 1 - tau : tau;
+    if (tau >= 0 && active && t < L) {
+      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
+      in.gi = gp[0]; in.gf = gp[n]; in.gg = gp[2 * n]; in.go = gp[3 * n];
+      in.c_new = d.cs[((long)t * B + b) * n + j];
+      const int tp = d.rev ? t + 1 : t - 1;               // frame processed just before t in the forward pass
+      if (tp >= 0 && tp < T) in.c_prev = d.cs[((long)tp * B + b) * n + j];
+      else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
+      in.dy = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
+    }
+    return in;
+  };
+  BwdIn in = fetch_in(T - 1);
+  // dz of a step reaches the DZ tensor one step late (see the forward kernel)
+  unsigned short pend_bits[4] = {0, 0, 0, 0};
+  int pend_t = -1;
+  auto flush = [&]() {
+    if (!active || pend_t < 0) return;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)pend_t * B + b) * 4 * n + q * n + j] = pend_bits[q];
+    pend_t = -1;
+  };
 
+  PROF_DECL
   for (int tau = T - 1; tau >= -1; --tau) {
-    const int sigma = T - 1 - tau;                       // 0, 1, ... : count of backward steps done before this one
+    PROF_MARK(4)
+    const int sigma = T - 1 - tau;                       // count of backward steps done before this one
     const int t = d.rev ? T - 1 - tau : tau;             // frame of this step (out of range when tau == -1)
     const int t_next = d.rev ? t - 1 : t + 1;            // frame of the previous backward step
     const bool pointwise = tau >= 0;
     const bool valid = pointwise && active && t < L;
-    // everything the gate gradients need except Dh is independent of the recurrence: fetch it first
-    float gi = 0.f, gf = 0.f, gg = 0.f, go = 0.f, c_new = 0.f, c_prev = 0.f, dyv = 0.f;
-    if (valid) {
-      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-      gi = gp[0]; gf = gp[n]; gg = gp[2 * n]; go = gp[3 * n];
-      c_new = d.cs[((long)t * B + b) * n + j];
-      const int tp = d.rev ? t + 1 : t - 1;               // frame processed just before t in the forward pass
-      if (tp >= 0 && tp < T) c_prev = d.cs[((long)tp * B + b) * n + j];
-      else if (d.c0) c_prev = d.c0[(long)b * n + j];
-      dyv = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
-    }
+    BwdIn in_next = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     if (sigma > 0) {
       const uint4* rin = (((sigma - 1) & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
-      const unsigned tag = (unsigned)sigma & 0xffffu;
-      f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const RingReader rd = make_reader(rin, nkc, ntiles * 11, wave, lane, (unsigned)sigma & 0xffffu, err, a.spin_limit);
+      const unsigned np_ = rd.wait_sample(dead);
+      (void)np_;
+      PROF_POLLS(np_)
+      f32x4 acc[4];
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        uint4 av[NIT / 2];
-        poll_operands<NIT / 2>(av, rin, nkc, ntiles * 11, wave, lane, half * (NIT / 2), tag, dead, err, a.spin_limit);
+      for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      u32x4 raw[2][BS];
+      uint4 av[BS];
+      rd.issue<BS>(raw[0], 0);
+      in_next = fetch_in(tau - 1);
 #pragma unroll
-        for (int i = 0; i < NIT / 2; ++i)
-          if (wave + 4 * (half * (NIT / 2) + i) < nkc) acc = Mma16<bf16_t>::run(av[i], w[half * (NIT / 2) + i], acc);
+      for (int bt = 0; bt < NB; ++bt) {
+        if (bt + 1 < NB) rd.issue<BS>(raw[(bt + 1) & 1], (bt + 1) * BS);
+        rd.settle<BS>(raw[bt & 1], av, bt * BS, dead);
+        if (bt == NB - 1) flush();
+        PROF_MARK(0)
+        // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
+#pragma unroll
+        for (int i = 0; i < BS; ++i) acc[(bt * BS + i) & 3] = Mma16<bf16_t>::run(av[i], w[bt * BS + i], acc[(bt * BS + i) & 3]);
+        PROF_MARK(1)
       }
 #pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = acc[v];
+      for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = (acc[0][v] + acc[1][v]) + (acc[2][v] + acc[3][v]);
       __syncthreads();
       if (active && t_next < L) Dh = red[0][r][u] + red[1][r][u] + red[2][r][u] + red[3][r][u];
+    } else {
+      in_next = fetch_in(tau - 1);
     }
     if (pointwise) {
       float dz[4] = {0.f, 0.f, 0.f, 0.f};
-      if (valid) lstm_cell_grad(gi, gf, gg, go, c_new, c_prev, dyv + Dh, Dc, dz);
+      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, in.dy + Dh, Dc, dz);
+      unsigned short bits[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const unsigned short bits = f2bf_bits(dz[q]);
-        if (active) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits;
-        zb[r][q * 16 + u] = bits;                          // inactive threads publish zeros
+        bits[q] = f2bf_bits(dz[q]);
+        zb[r][q * 16 + u] = bits[q];                       // inactive threads publish zeros
       }
       __syncthreads();
+      PROF_MARK(2)
       uint4* rout = (sigma & 1) ? d.ring1 : d.ring0;
       const unsigned tag_out = (unsigned)(sigma + 1) & 0xffffu;
 #pragma unroll
@@ -261,9 +386,16 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
           store_unit(rout, unit_index, x0, x1, x2, tag_out);
         }
       }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) pend_bits[q] = bits[q];
+      pend_t = t;
       __syncthreads();                                      // zb and red are reused by the next step
+      PROF_MARK(3)
     }
+    in = in_next;
   }
+  flush();
+  PROF_DUMP("bwd", T)
   if (active) {
     d.Dh[(long)b * n + j] = Dh;
     d.Dc[(long)b * n + j] = Dc;
