@@ -183,20 +183,6 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
     }
   };
   fetch_zx(0, zx);
-  // Outputs of a step are written one step late, after the next step's operands have arrived, so that the
-  // waits of the ring reads never queue behind these stores (loads and stores share one completion counter).
-  struct Out { float y, c, h_prev, gi, gf, gg, go; int t; bool valid; } pend = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, -1, false};
-  auto flush = [&](const Out& p) {
-    if (!active || p.t < 0) return;
-    Store<bf16_t>::store(d.y, ((long)p.t * B + b) * d.ldy + j, p.y);
-    if (d.cs) d.cs[((long)p.t * B + b) * n + j] = p.c;
-    if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)p.t * B + b) * n + j, p.h_prev);
-    if (p.valid && a.write_gates) {
-      float* gp = d.gates + ((long)p.t * B + b) * 4 * n + j;
-      gp[0] = p.gi; gp[n] = p.gf; gp[2 * n] = p.gg; gp[3 * n] = p.go;
-    }
-  };
-
   PROF_DECL
   for (int tau = 0; tau < T; ++tau) {
     const int t = d.rev ? T - 1 - tau : tau;
@@ -213,7 +199,6 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
     rd.issue<NIT>(raw, 0);
     fetch_zx(tau + 1, zx_next);
     rd.settle<NIT>(raw, av, 0, dead);
-    flush(pend);
     PROF_MARK(0)
 
     f32x4 acc[4];
@@ -248,12 +233,19 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
       const unsigned x0 = hb[r2][v0], x1 = v0 + 1 < 16 ? hb[r2][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[r2][v0 + 2] : 0u;
       store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
     }
-    pend = Out{valid ? h : 0.f, c, h_prev, o.gi, o.gf, o.gg, o.go, t, valid};
+    if (active) {                     // layer outputs and what the backward pass needs
+      Store<bf16_t>::store(d.y, ((long)t * B + b) * d.ldy + j, valid ? h : 0.f);
+      if (d.cs) d.cs[((long)t * B + b) * n + j] = c;
+      if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)t * B + b) * n + j, h_prev);
+      if (valid && a.write_gates) {
+        float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
+        gp[0] = o.gi; gp[n] = o.gf; gp[2 * n] = o.gg; gp[3 * n] = o.go;
+      }
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) zx[q] = zx_next[q];
     PROF_MARK(3)
   }
-  flush(pend);
   PROF_DUMP("fwd", T)
   if (active) {
     d.cstate[(long)b * n + j] = c;
@@ -311,15 +303,6 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
     return in;
   };
   BwdIn in = fetch_in(T - 1);
-  // dz of a step reaches the DZ tensor one step late (see the forward kernel)
-  unsigned short pend_bits[4] = {0, 0, 0, 0};
-  int pend_t = -1;
-  auto flush = [&]() {
-    if (!active || pend_t < 0) return;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)pend_t * B + b) * 4 * n + q * n + j] = pend_bits[q];
-    pend_t = -1;
-  };
 
   PROF_DECL
   for (int tau = T - 1; tau >= -1; --tau) {
@@ -348,7 +331,6 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
       for (int bt = 0; bt < NB; ++bt) {
         if (bt + 1 < NB) rd.issue<BS>(raw[(bt + 1) & 1], (bt + 1) * BS);
         rd.settle<BS>(raw[bt & 1], av, bt * BS, dead);
-        if (bt == NB - 1) flush();
         PROF_MARK(0)
         // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
 #pragma unroll
@@ -386,15 +368,15 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
           store_unit(rout, unit_index, x0, x1, x2, tag_out);
         }
       }
+      if (active) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) pend_bits[q] = bits[q];
-      pend_t = t;
+        for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits[q];
+      }
       __syncthreads();                                      // zb and red are reused by the next step
       PROF_MARK(3)
     }
     in = in_next;
   }
-  flush();
   PROF_DUMP("bwd", T)
   if (active) {
     d.Dh[(long)b * n + j] = Dh;
