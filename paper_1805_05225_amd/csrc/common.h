@@ -56,6 +56,17 @@ struct GemmArgs {
   bool in_bf16, out_bf16;
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+// Fast bfloat16 kernel for problems with both operands k-contiguous, 16-byte aligned rows and K % 8 == 0
+// (launch_gemm routes such problems to it by itself).
+bool gemm_nt_ok(const GemmArgs& g);
+hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s);
+// dst[c][r] = src[r][c] (16-bit elements), r < R, c < C, dst rows zero-padded up to ld_dst; nz problems with
+// strides s_src / s_dst.  lens != NULL: rows of src are frames (t = r / Bt, b = r % Bt) and are read as zero
+// unless t < lens[b].
+hipError_t launch_transpose(const void* src, void* dst, int R, int C, long ld_src, long ld_dst, int nz, long s_src, long s_dst,
+                            const int* lens, int Bt, int T, hipStream_t s);
+// dst[r][0..ld_dst) = src[r][0..C) followed by zeros (16-bit elements)
+hipError_t launch_pad_rows(const void* src, void* dst, long R, int C, int ld_dst, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------
 // Recurrent part.  Fragment geometry of the 16x16 MFMA used by the step kernels: a 16-byte chunk

@@ -101,18 +101,23 @@ __device__ __forceinline__ void fetch_mcontig_bf16(uint32_t (&st)[16], const cha
   for (int i = 0; i < 2; ++i) {
     int c = tid + kThreads * i;
     int m = col0 + 2 * (c & 63), kb = k0 + (c >> 6) * 8;
-    int ft = 0, fb = 0;
-    if (MASK) { ft = kb / Bt; fb = kb - ft * Bt; }          // frame (t, b) of row kb; advanced incrementally below
+    // The frame mask is fetched independently of the data and applied afterwards, so the data loads
+    // never wait for the seq_lens loads.
+    uint32_t keep = 0xffu;
+    if (MASK) {
+      int ft = kb / Bt, fb = kb - ft * Bt;                  // frame (t, b) of row kb, advanced incrementally
+      keep = 0u;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        if (kb + kk < K) { int L = lens[fb]; L = L < 0 ? 0 : (L > T ? T : L); keep |= (ft < L ? 1u : 0u) << kk; }
+        if (++fb == Bt) { fb = 0; ++ft; }
+      }
+    }
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       int k = kb + kk;
       uint32_t w = 0;
-      bool ok = k < K && m < cols;
-      if (MASK) {
-        if (ok) { int L = lens[fb]; L = L < 0 ? 0 : (L > T ? T : L); ok = ft < L; }
-        if (++fb == Bt) { fb = 0; ++ft; }
-      }
-      if (ok) {
+      if (k < K && m < cols) {
         const char* p = base + ((long)k * ld + m) * 2;
         if (vec >= 4 && m + 1 < cols) w = *(const uint32_t*)p;
         else {
@@ -120,7 +125,7 @@ __device__ __forceinline__ void fetch_mcontig_bf16(uint32_t (&st)[16], const cha
           if (m + 1 < cols) w |= ((uint32_t) * (const uint16_t*)(p + 2)) << 16;
         }
       }
-      st[8 * i + kk] = w;
+      st[8 * i + kk] = ((keep >> kk) & 1u) ? w : 0u;
     }
   }
 }
@@ -148,17 +153,21 @@ __device__ __forceinline__ void fetch_mcontig_f32(uint32_t (&st)[16], const char
   for (int i = 0; i < 4; ++i) {
     int c = tid + kThreads * i;
     int m = col0 + (c & 127), kb = k0 + (c >> 7) * 4;
-    int ft = 0, fb = 0;
-    if (MASK) { ft = kb / Bt; fb = kb - ft * Bt; }
+    uint32_t keep = 0xfu;
+    if (MASK) {
+      int ft = kb / Bt, fb = kb - ft * Bt;
+      keep = 0u;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kb + kk < K) { int L = lens[fb]; L = L < 0 ? 0 : (L > T ? T : L); keep |= (ft < L ? 1u : 0u) << kk; }
+        if (++fb == Bt) { fb = 0; ++ft; }
+      }
+    }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       int k = kb + kk;
-      bool ok = k < K && m < cols;
-      if (MASK) {
-        if (ok) { int L = lens[fb]; L = L < 0 ? 0 : (L > T ? T : L); ok = ft < L; }
-        if (++fb == Bt) { fb = 0; ++ft; }
-      }
-      st[4 * i + kk] = ok ? *(const uint32_t*)(base + ((long)k * ld + m) * 4) : 0u;
+      uint32_t w = (k < K && m < cols) ? *(const uint32_t*)(base + ((long)k * ld + m) * 4) : 0u;
+      st[4 * i + kk] = ((keep >> kk) & 1u) ? w : 0u;
     }
   }
 }
@@ -302,6 +311,7 @@ hipError_t dispatch(const GemmArgs& g, hipStream_t s) {
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0 || g.nz <= 0) return hipSuccess;
+  if (gemm_nt_ok(g)) return launch_gemm_nt(g, s);
   if (g.in_bf16) {
     if (g.out_bf16) return dispatch<bf16_t, bf16_t>(g, s);
     return dispatch<bf16_t, float>(g, s);

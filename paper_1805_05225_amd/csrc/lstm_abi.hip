@@ -25,7 +25,8 @@ struct Plan {
   size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
   // workspace
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
-      ws_colsum, ws_sync, sync_bytes, workspace_bytes;
+      ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, workspace_bytes;
+  bool fast_gemm; int n_in_pad; long TBp;   // bf16 products through the k-contiguous kernel (operands transposed once)
   size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems;
 };
 
@@ -76,6 +77,16 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->Zx_dir_elems = up(TB * 4 * n * 4) / 4;
   p->ws_Zx = take(infer ? D * p->Zx_dir_elems * 4 : 0);
   p->ws_colsum = take(infer ? 0 : D * 64 * 4 * n * 4);
+  // transposed / padded operand copies for the fast bf16 products
+  p->fast_gemm = p->bf16 && d->n % 2 == 0;
+  p->n_in_pad = (d->n_in + 7) / 8 * 8;
+  p->TBp = (TB + 63) / 64 * 64;
+  const bool fg = p->fast_gemm;
+  p->ws_WxT = take(fg ? D * 4 * n * p->n_in_pad * 2 : 0);
+  p->ws_xpad = take(fg && d->n_in % 8 ? TB * p->n_in_pad * 2 : 0);
+  p->ws_XT = take(fg && !infer ? (size_t)d->n_in * p->TBp * 2 : 0);
+  p->ws_DZT = take(fg && !infer ? D * 4 * n * p->TBp * 2 : 0);
+  p->ws_HT = take(fg && !infer ? D * n * p->TBp * 2 : 0);
   p->workspace_bytes = o + kAlign;
   return LSTM_OK;
 }
@@ -183,6 +194,16 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.vecB = widest(g.ldb, g.sBz, 0, p.esz, 4);
     {
       Phase ph(LSTM_PHASE_GEMM_ZX, 1, s);
+      if (p.fast_gemm) {                 // W_x is transposed once so that both operands are k-contiguous
+        HIPCHK(launch_transpose(W_x, ws + p.ws_WxT, p.n_in, 4 * p.n, 4 * n, p.n_in_pad, p.D, (long)p.n_in * 4 * n,
+                                (long)(4 * n) * p.n_in_pad, nullptr, 1, 0, s));
+        if (p.n_in % 8) {                // rows of x are not 16-byte aligned: padded copy
+          HIPCHK(launch_pad_rows(x, ws + p.ws_xpad, (long)(T * B), p.n_in, p.n_in_pad, s));
+          g.A = ws + p.ws_xpad;
+        }
+        g.B = ws + p.ws_WxT; g.K = p.n_in_pad; g.lda = p.n_in_pad; g.ldb = p.n_in_pad;
+        g.sBz = (long)(4 * n) * p.n_in_pad; g.b_kcontig = true;
+      }
       HIPCHK(launch_gemm(g, s));
     }
 
@@ -385,7 +406,34 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     Phase ph(LSTM_PHASE_GEMM_DX, 1, s);
     HIPCHK(launch_gemm(g, s));
   }
-  {                                // dW_x = X^T DZ, padded frames of X masked out
+  if (p.fast_gemm) {               // weight gradients with operands transposed once: everything k-contiguous
+    const long TBp = p.TBp;
+    {
+      Phase ph(LSTM_PHASE_GEMM_DWX, 3, s);
+      HIPCHK(launch_transpose(DZ, ws + p.ws_DZT, TB, 4 * p.n, 4 * n, TBp, p.D, (long)p.DZ_dir_elems, (long)(4 * n) * TBp,
+                              nullptr, 1, 0, s));
+      HIPCHK(launch_transpose(x, ws + p.ws_XT, TB, p.n_in, n_in, TBp, 1, 0, 0, seq_lens, p.B, p.T, s));
+      GemmArgs g = {};
+      g.A = ws + p.ws_XT; g.B = ws + p.ws_DZT; g.C = dW_x;
+      g.M = p.n_in; g.N = 4 * p.n; g.K = (int)TBp; g.lda = TBp; g.ldb = TBp; g.ldc = 4 * n;
+      g.sAz = 0; g.sBz = (long)(4 * n) * TBp; g.sCz = (long)(n_in * 4 * n); g.nz = p.D; g.nseg = 1;
+      g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false; g.accumulate = acc;
+      g.vecA = 16; g.vecB = 16;
+      HIPCHK(launch_gemm(g, s));
+    }
+    {
+      Phase ph(LSTM_PHASE_GEMM_DWH, 2, s);
+      HIPCHK(launch_transpose(rs + p.res_hprev, ws + p.ws_HT, TB, p.n, n, TBp, p.D, (long)(p.res_dir_stride / 2), (long)n * TBp,
+                              nullptr, 1, 0, s));
+      GemmArgs g = {};
+      g.A = ws + p.ws_HT; g.B = ws + p.ws_DZT; g.C = dW_h;
+      g.M = p.n; g.N = 4 * p.n; g.K = (int)TBp; g.lda = TBp; g.ldb = TBp; g.ldc = 4 * n;
+      g.sAz = (long)n * TBp; g.sBz = (long)(4 * n) * TBp; g.sCz = (long)(n * 4 * n); g.nz = p.D; g.nseg = 1;
+      g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false; g.accumulate = acc;
+      g.vecA = 16; g.vecB = 16;
+      HIPCHK(launch_gemm(g, s));
+    }
+  } else {                         // dW_x = X^T DZ, padded frames of X masked out
     GemmArgs g = {};
     g.A = x; g.B = DZ; g.C = dW_x;
     g.M = p.n_in; g.N = 4 * p.n; g.K = TB;
