@@ -10,8 +10,8 @@
 //
 // Kernel: 256x256 output tile per work-group of 4 wavefronts (2x2), each wavefront a 128x128
 // sub-tile = 4x4 MFMA 32x32x16 blocks (256 accumulator registers).  K advances 64 at a time through
-// two LDS stages (rows of 128 bytes + 16 bytes padding; 144 KiB of the 160 KiB LDS).  Global loads of
-// stage i+1 are in flight while stage i is multiplied; fragments are double-buffered in registers.
+// two LDS stages (rows of 128 bytes + 16 bytes padding; 144 KiB of the 160 KiB LDS).  Global loads run two
+// stages ahead of the MFMAs (one stage in registers, one in LDS); fragments are double-buffered in registers.
 // Per 16-wide k step a wavefront issues 8 LDS reads for 16 MFMAs, half the LDS bandwidth a 128x128
 // work-group tile would need.
 #include "common.h"
@@ -38,15 +38,37 @@ __device__ __forceinline__ f32x16 mma(uint4 a, uint4 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// 256 rows x 8 chunks of 16 bytes per operand and stage; thread handles chunks tid + 256*i
-__device__ __forceinline__ void fetch(uint4 (&st)[8], const char* base, long ld, int rows, int row0, int K, int k0, int tid) {
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
+
+// One operand of one stage: 256 rows x 8 chunks of 16 bytes; thread handles chunks tid + 256*i, i < 8.
+// Loads go through a buffer descriptor covering exactly the operand's rows: rows past the end read as zero
+// in hardware, so only the K tail needs a mask (and only in the last stage of a segment).
+struct OperandLoader {
+  __amdgpu_buffer_rsrc_t rs;
+  unsigned voff[8];                     // byte offset of chunk i at k = 0
+  int kc8;                              // first k of this thread's chunk inside a stage
+  __device__ __forceinline__ void init(const char* base, long ld, int rows, int row0, int tid) {
+    const long bytes = (long)rows * ld * 2;
+    rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, bytes > 0x7fffffffL ? 0x7fffffff : (int)bytes, kBufFlags);
+    kc8 = (tid & 7) * 8;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int c = tid + kThreads * i;
-    const int row = row0 + (c >> 3), k = k0 + (c & 7) * 8;
-    st[i] = (row < rows && k < K) ? *(const uint4*)(base + ((long)row * ld + k) * 2) : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < 8; ++i) {
+      const long row = row0 + ((tid + kThreads * i) >> 3);
+      const long off = (row * ld + kc8) * 2;
+      voff[i] = off > 0x7ffffff0L ? 0x7ffffff0u : (unsigned)off;      // past-the-end rows land outside the descriptor
+    }
   }
-}
+  template <bool TAIL>
+  __device__ __forceinline__ void fetch(uint4 (&st)[8], int k0, int K) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, voff[i] + k0 * 2, 0, 0);
+      const bool keep = !TAIL || k0 + kc8 < K;
+      st[i] = keep ? make_uint4(x[0], x[1], x[2], x[3]) : make_uint4(0, 0, 0, 0);
+    }
+  }
+};
 __device__ __forceinline__ void commit(const uint4 (&st)[8], char* lds, int tid) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -82,26 +104,44 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int ktiles = (g.K + kKB - 1) / kKB;
+  const bool ktail = (g.K % kKB) != 0;
   const int total = ktiles * g.nseg;
+  OperandLoader la, lb;
+  int seg_loaded = -1;
   uint4 sa[8], sb[8];
-  auto fetch_stage = [&](int it) {
+  // stage `it`: segment it / ktiles, k offset (it % ktiles) * 64
+  auto fetch_a = [&](int it) {
     const int seg = it / ktiles, kt = it - seg * ktiles;
-    const char* A = g.A + (g.sAz * z + g.sAseg * seg) * 2;
-    const char* B = g.B + (g.sBz * z + g.sBseg * seg) * 2;
-    fetch(sa, A, g.lda, g.M, m0, g.K, kt * kKB, tid);
-    fetch(sb, B, g.ldb, g.N, n0, g.K, kt * kKB, tid);
+    if (seg != seg_loaded) {
+      la.init(g.A + (g.sAz * z + g.sAseg * seg) * 2, g.lda, g.M, m0, tid);
+      lb.init(g.B + (g.sBz * z + g.sBseg * seg) * 2, g.ldb, g.N, n0, tid);
+      seg_loaded = seg;
+    }
+    if (ktail && kt == ktiles - 1) la.fetch<true>(sa, kt * kKB, g.K); else la.fetch<false>(sa, kt * kKB, g.K);
   };
+  auto fetch_b = [&](int it) {
+    const int seg = it / ktiles, kt = it - seg * ktiles;
+    if (ktail && kt == ktiles - 1) lb.fetch<true>(sb, kt * kKB, g.K); else lb.fetch<false>(sb, kt * kKB, g.K);
+  };
+  // prologue: stage 0 into LDS buffer 0, stage 1 into registers
   if (total > 0) {
-    fetch_stage(0);
+    fetch_a(0); fetch_b(0);
     commit(sa, lds, tid);
     commit(sb, lds + kOpBytes, tid);
+    if (total > 1) { fetch_a(1); fetch_b(1); }
   }
   __syncthreads();
+
+  // Main loop.  While stage `it` is multiplied out of LDS buffer it&1: the registers holding stage it+1 are
+  // written to the other buffer (k-steps 0-1), then the loads of stage it+2 are issued (k-steps 2-3), so every
+  // global load has a whole stage of MFMAs to complete.  Fragments for k-step s+1 are read from LDS while
+  // the 16 MFMAs of step s run; the scheduling barriers keep the compiler from collapsing that overlap.
+  // (Moving the barrier to mid-stage and pre-reading the next stage's first fragments measured slower.)
   for (int it = 0; it < total; ++it) {
     const int cur = it & 1;
-    if (it + 1 < total) fetch_stage(it + 1);
     const char* As = lds + cur * 2 * kOpBytes + (wm * 128 + r) * kStride + gq * 16;
     const char* Bs = lds + cur * 2 * kOpBytes + kOpBytes + (wn * 128 + r) * kStride + gq * 16;
+    char* nxt = lds + (cur ^ 1) * 2 * kOpBytes;
     uint4 fa[2][4], fb[2][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -118,14 +158,20 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
           fb[c ^ 1][i] = *(const uint4*)(Bs + i * 32 * kStride + (s + 1) * 32);
         }
       }
+      if (it + 1 < total) {
+        if (s == 0) commit(sa, nxt, tid);
+        if (s == 1) commit(sb, nxt + kOpBytes, tid);
+      }
+      if (it + 2 < total) {
+        if (s == 2) fetch_a(it + 2);
+        if (s == 3) fetch_b(it + 2);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
-    }
-    if (it + 1 < total) {
-      commit(sa, lds + (cur ^ 1) * 2 * kOpBytes, tid);
-      commit(sb, lds + (cur ^ 1) * 2 * kOpBytes + kOpBytes, tid);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
   }
@@ -203,6 +249,8 @@ __global__ void pad_rows_kernel(const uint16_t* src, uint16_t* dst, long R, int 
 
 bool gemm_nt_ok(const GemmArgs& g) {
   const auto a16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
+  const long lim = 0x7fffff00L;     // operands are addressed with 32-bit byte offsets
+  if ((long)g.M * g.lda * 2 > lim || (long)g.N * g.ldb * 2 > lim) return false;
   return g.in_bf16 && g.a_kcontig && g.b_kcontig && !g.lens && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
          g.sAz % 8 == 0 && g.sBz % 8 == 0 && g.sAseg % 8 == 0 && g.sBseg % 8 == 0 && a16(g.A) && a16(g.B);
 }
