@@ -129,6 +129,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--per-step", action="store_true", help="force one launch per time step")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); --gpus %d is not supported" % args.gpus,
@@ -153,6 +155,12 @@ def main():
         for bf in st.bufs:
             bf["desc"].flags |= Bn.FLAG_PER_STEP
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         st.step()
     torch.cuda.synchronize()
@@ -167,19 +175,39 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     T, B, n = inp["T"], cfg["B"], cfg["n"]
-    # algorithmic HBM bytes of one forward recurrent step, both directions (weights resident):
-    # read Zx_t (B*4n*4) and c (B*n*4); write c (B*n*4), y (B*n*2), gate activations (B*4n*4)
     esz = 2 if cfg["dtype"] == "bf16" else 4
-    step_bytes = 2 * (B * 4 * n * 4 + B * n * 4 + B * n * 4 + B * n * esz + B * 4 * n * 4)
-    loop_ms, loop_launches = prof["loop_fwd"]
-    steps_total = args.steps * cfg["layers"] * T                  # time steps executed by the forward loops
-    us_per_step = loop_ms * 1e3 / max(steps_total, 1)
-    achieved = step_bytes / (us_per_step * 1e-6) / 1e9
-    bwd_ms, _ = prof["loop_bwd"]
-    # hoisted GEMM flops actually executed (padded frames included), per step of the benchmark
+    nl = cfg["layers"]
+    # Algorithmic HBM bytes of ONE recurrent time step, both directions, W_h resident on chip:
+    #   forward : read Zx_t (B*4n*4), write gate activations (B*4n*4), c_t (B*n*4), y_t (B*n*esz); c_{t-1} stays on chip
+    #   backward: read gate activations (B*4n*4), c_t and c_{t-1} (2*B*n*4), dy_t (B*n*esz); write dz_t (B*4n*esz)
+    fwd_step_bytes = 2 * (2 * B * 4 * n * 4 + B * n * 4 + B * n * esz)
+    bwd_step_bytes = 2 * (B * 4 * n * 4 + 2 * B * n * 4 + B * n * esz + B * 4 * n * esz)
+    steps_total = args.steps * nl * T
+
+    def loop_roofline(phase, step_bytes, name):
+        ms, launches = prof[phase]
+        per_launch_ms = ms / max(launches, 1)
+        steps_per_launch = steps_total / max(launches, 1)
+        achieved = step_bytes * steps_per_launch / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        return {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "launches": int(launches),
+                "avg_launch_ms": per_launch_ms, "us_per_time_step": ms * 1e3 / max(steps_total, 1),
+                "algorithmic_bytes_per_time_step": step_bytes}
+
+    roof_bwd = loop_roofline("loop_bwd", bwd_step_bytes, "backward recurrent loop (both directions, one launch per layer)")
+    roof_fwd = loop_roofline("loop_fwd", fwd_step_bytes, "forward recurrent loop (both directions, one launch per layer)")
+    try:   # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as fh:
+            tr = json.load(fh)
+        if tr.get("workload") == "config %d" % args.config:
+            roof_bwd["traffic"] = tr.get("persist_bwd_bytes_per_launch")
+            roof_fwd["traffic"] = tr.get("persist_fwd_bytes_per_launch")
+    except (OSError, ValueError):
+        pass
+    # hoisted products: flops executed (padded frames included) per benchmark step
     TB = T * B
     gemm_flops = {"gemm_zx": 0.0, "gemm_dx": 0.0, "gemm_dwx": 0.0, "gemm_dwh": 0.0}
-    for l in range(cfg["layers"]):
+    for l in range(nl):
         ni = cfg["n_in"] if l == 0 else 2 * n
         gemm_flops["gemm_zx"] += 2.0 * TB * ni * 8 * n
         gemm_flops["gemm_dx"] += 2.0 * TB * ni * 8 * n
@@ -187,6 +215,8 @@ def main():
         gemm_flops["gemm_dwh"] += 2.0 * TB * n * 8 * n
     gemm_ms = sum(prof[k][0] for k in gemm_flops)
     gemm_tflops = sum(gemm_flops.values()) * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    mfma_peak = BF16_PEAK_TFLOPS if esz == 2 else 157.3
+    dominant = roof_bwd if prof["loop_bwd"][0] >= prof["loop_fwd"][0] else roof_fwd
 
     out = {
         "metric": "BLSTM fwd+bwd frames/sec (n=%d)" % n, "value": frames * args.steps / dt, "unit": "frames/s",
@@ -194,19 +224,17 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": "config %d: %d-layer BLSTM stack, n_in=%d, n=%d per direction, B=%d, seq_lens~U{%d..%d} "
                                "(T=%d, %d real frames), %s storage / f32 state, forward + backward" % (
-                                   args.config, cfg["layers"], cfg["n_in"], n, B, cfg["len_lo"], cfg["len_hi"], T, frames,
+                                   args.config, nl, cfg["n_in"], n, B, cfg["len_lo"], cfg["len_hi"], T, frames,
                                    cfg["dtype"]),
                    "recurrent_path": "per_step" if args.per_step else "default"},
         "useful_tflops": flops * args.steps / dt / 1e12,
-        "roofline": {"bound": "hbm", "kernel": "forward recurrent step (both directions)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "us_per_step": us_per_step, "algorithmic_bytes_per_step": step_bytes,
-                     "launches": int(loop_launches)},
+        "roofline": dominant,
+        "roofline_forward_loop": roof_fwd if dominant is roof_bwd else roof_bwd,
+        "roofline_hoisted_gemms": {"bound": "mfma", "achieved": gemm_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
+                                   "frac": gemm_tflops / mfma_peak,
+                                   "note": "executed flops of the four hoisted products per layer (padded frames included, "
+                                           "operand transposes inside the timed phases)"},
         "phases_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
-        "bwd_us_per_step": bwd_ms * 1e3 / max(steps_total, 1),
-        "gemm_roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_PEAK_TFLOPS if esz == 2 else 157.3,
-                          "unit": "TFLOP/s", "frac": gemm_tflops / (BF16_PEAK_TFLOPS if esz == 2 else 157.3),
-                          "note": "executed flops of the four hoisted products, padded frames included"},
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inp)
