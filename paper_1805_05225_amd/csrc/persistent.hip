@@ -1,16 +1,17 @@
 // Single-launch recurrent kernels: the whole time loop of a layer in ONE launch (bfloat16 storage).
 //
 // The per-step kernels pay a launch per time step and re-read their W_h slice from the memory
-// system every step.  Here each work-group (16 hidden units x 16 batch rows) loads its slice of
-// the packed W_h into registers once and then walks all T steps.
+// system every step.  Here each work-group (forward: 16 hidden units x 16 batch rows; backward:
+// 32 units x 8 rows, or 16 x 16 when that does not fit) loads its slice of the packed W_h into
+// registers once and then walks all T steps.
 //
 // Only h_t (forward) or dz_t (backward) crosses work-groups.  Measurements on this device showed
 // that a counter barrier is the wrong tool: atomics on one address serialise at ~16 ns each
 // (4 us for 256 work-groups) and agent-scope fences cost microseconds more.  So there is no
 // barrier and no fence here.  The exchanged data lives in a two-slot ring whose every 8-byte unit
 // holds three bf16 values and a 16-bit step tag, written with one 64-bit agent-scope atomic store
-// and read with cache-bypassing 16-byte loads.  A consumer simply re-reads its operands until
-// every tag shows the step it is waiting for: value and "ready" flag arrive in the same atomic
+// and read with cache-bypassing 16-byte loads.  A consumer simply re-reads an operand until
+// its tags show the step it is waiting for: value and "ready" flag arrive in the same atomic
 // unit, so no ordering between different addresses is ever needed.
 //
 // Two ring slots suffice: a work-group writes slot s for step t+1 only after it has seen every
@@ -35,8 +36,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define PROF_MARK(i) { long long now_ = wall_clock64(); pt_[i] += now_ - pc_; pc_ = now_; }
 #define PROF_POLLS(n) npoll_ += (n);
 #define PROF_DUMP(name, steps) if ((tid & 63) == 0 && (blockIdx.x % 23) == 0 && blockIdx.y == 0) \
-  printf("%s wg(%d,%d,%d) wave %d: ns/step poll %lld mma %lld red+cell %lld publish %lld other %lld polls/step %.2f\n", name, blockIdx.x, blockIdx.y, blockIdx.z, tid >> 6, \
-         pt_[0] * 10 / (steps), pt_[1] * 10 / (steps), pt_[2] * 10 / (steps), pt_[3] * 10 / (steps), pt_[4] * 10 / (steps), (double)npoll_ / (steps));
+  printf("%s wg(%d,%d,%d) wave %d: ns/step sample %lld stream %lld mma %lld red+cell %lld publish %lld other %lld polls/step %.2f\n", name, blockIdx.x, blockIdx.y, blockIdx.z, (int)(threadIdx.x >> 6), \
+         pt_[5] * 10 / (steps), pt_[0] * 10 / (steps), pt_[1] * 10 / (steps), pt_[2] * 10 / (steps), pt_[3] * 10 / (steps), pt_[4] * 10 / (steps), (double)npoll_ / (steps));
 #else
 #define PROF_DECL
 #define PROF_MARK(i)
@@ -44,6 +45,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define PROF_DUMP(name, steps)
 #endif
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
+constexpr int kWindow = 10;             // ring loads in flight per wavefront (measured knee: 10-12)
 // cache policy of the polling loads: bit 4 = coherent at agent scope (bypasses the XCD-local L2),
 // bit 31 = volatile, so the compiler re-issues the load in every poll
 constexpr int kSc1 = (int)(16u | 0x80000000u);
@@ -58,28 +60,47 @@ __device__ __forceinline__ void st_relaxed(unsigned* p, unsigned v) {
 // Ring reads.  One wavefront owns chunks kc = wave + 4*it of its row tile.  Reads of freshly written
 // remote data are latency-bound per compute unit and degrade when more than ~12 KiB per wavefront is in
 // flight, so (a) a wave first polls ONE chunk (its last) until that shows the awaited tag, which is cheap
-// while the producers are still busy, and only then (b) fetches its operands in batches of at most 12
-// chunks, checking every tag; a batch with a stale tag is simply fetched again.
+// while the producers are still busy, and only then (b) streams its operands with a bounded window of loads
+// in flight, checking every tag; if any tag is stale the whole stream is repeated.
+//
+// Nothing in the stream is predicated.  The buffer descriptor covers exactly the nkc chunks of the row tile,
+// so a load past the end (chunks the template bound adds beyond nkc, lanes whose rows this work-group does
+// not own: their offset is parked far outside) returns zeros from the bounds check without touching memory.
+// Padding units inside the ring hold zero values (nobody writes them after the initial fill), so masking off
+// the tag halves is all the clean-up an operand needs.  Keeping branches and lane masks out of this loop
+// matters: with them the instruction stream between two loads, not the memory system, set the step time.
+// Order in which a work-group walks the nitv loads of its row tile: rotated by `rot`, so that the work-groups of
+// one XCD, which all read the same tile at the same time, do not all ask the same L2 channel for the same lines.
+__device__ __forceinline__ int rot_index(int i, int rot, int nitv) {
+  const int j = i + rot;
+  return i >= nitv ? i : (j >= nitv ? j - nitv : j);
+}
 struct RingReader {
   __amdgpu_buffer_rsrc_t rs;
-  int nkc, nchunk_valid, wave, lane;
+  int nkc, wave, chunks_per_it;
+  int rot, nitv;                         // load i of the stream fetches iteration (i + rot) mod nitv of the row tile
+  unsigned voff;                         // byte offset of this lane's first load (parked out of range if the lane is off)
+  unsigned it_bytes;                     // byte distance between consecutive loads of a lane
+  int lim, lim_step;                     // load `it` carries awaited tags for this lane iff lim_step*it < lim
   unsigned tag;
   unsigned* err;
   unsigned limit;
 
-  __device__ __forceinline__ u32x4 load(int kc) const {
-    return __builtin_amdgcn_raw_buffer_load_b128(rs, (kc * 64 + lane) * 16, 0, kSc1);
+  __device__ __forceinline__ int it_of(int i) const { return rot_index(i, rot, nitv); }
+  __device__ __forceinline__ u32x4 load_it(int it) const {
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, voff + (unsigned)it * it_bytes, 0, kSc1);
   }
-  __device__ __forceinline__ bool chunk_fresh(const u32x4& x, int kc) const {
-    return kc * 4 + (lane >> 4) >= nchunk_valid || ((x[1] >> 16) == tag && (x[3] >> 16) == tag);
+  __device__ __forceinline__ unsigned stale_bits(const u32x4& x, int it) const {
+    const unsigned d = ((x[1] >> 16) ^ tag) | ((x[3] >> 16) ^ tag);
+    return lim_step * it < lim ? d : 0u;
   }
   // bounded wait on the wave's last chunk; returns the number of polls (diagnostics only)
   __device__ __forceinline__ unsigned wait_sample(bool& dead) const {
     if (dead || wave >= nkc) return 0;
-    const int kc = wave + 4 * ((nkc - 1 - wave) / 4);          // last chunk of this wave
+    const int it = it_of(nitv - 1);                            // last load of this wave's stream
     for (unsigned poll = 0;; ++poll) {
-      const u32x4 x = load(kc);
-      if (__all(chunk_fresh(x, kc))) return poll + 1;
+      const u32x4 x = load_it(it);
+      if (__all(stale_bits(x, it) == 0u)) return poll + 1;
       if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
         st_relaxed(err, 1u);
         dead = true;
@@ -87,53 +108,119 @@ struct RingReader {
       }
     }
   }
-  template <int N>
-  __device__ __forceinline__ void issue(u32x4 (&x)[N], int it0) const {
+  // Streams the wave's NIT loads through `use(i, operand)` with at most W loads in flight: a window of that
+  // size is the most the memory path of one compute unit sustains before the latency per load climbs.
+  // A load in which any lane saw a stale tag contributes a zero operand instead and is recorded in the
+  // returned bit mask (wave-uniform); `fix_up` then fetches exactly those loads again.  Once the sample has
+  // turned this is rare, and it costs one extra load latency instead of a second pass over everything.
+  template <int NIT, int W, typename F>
+  __device__ __forceinline__ unsigned long long stream(F&& use) const {
+    u32x4 x[W];
+    unsigned long long redo = 0ull;
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int kc = wave + 4 * (it0 + i);
-      x[i] = (u32x4){0u, 0u, 0u, 0u};
-      if (kc < nkc) x[i] = load(kc);
+    for (int i = 0; i < W && i < NIT; ++i) x[i] = load_it(it_of(i));
+#pragma unroll
+    for (int i = 0; i < NIT; ++i) {
+      const u32x4 v = x[i % W];
+      if (i + W < NIT) x[i % W] = load_it(it_of(i + W));
+      const bool stale = __builtin_amdgcn_ballot_w64(stale_bits(v, it_of(i)) != 0u) != 0ull;
+      redo |= stale ? 1ull << i : 0ull;
+      const unsigned keep = stale ? 0u : 0xffffffffu;
+      use(i, make_uint4(v[0] & keep, v[1] & 0xffffu & keep, v[2] & keep, v[3] & 0xffffu & keep));
     }
+    return redo;
   }
-  // checks the tags of a fetched batch (fetching it again while any is stale) and strips them
-  template <int N>
-  __device__ __forceinline__ void settle(u32x4 (&x)[N], uint4 (&av)[N], int it0, bool& dead) const {
-    for (unsigned poll = 0;; ++poll) {
-      bool fresh = true;
+  // Second pass over the loads marked in `redo`: each is polled (bounded) until all its tags are the awaited
+  // ones and then fed to `use`.
+  template <int NIT, typename F>
+  __device__ __forceinline__ void fix_up(unsigned long long redo, bool& dead, F&& use) const {
 #pragma unroll
-      for (int i = 0; i < N; ++i) {
-        const int kc = wave + 4 * (it0 + i);
-        if (kc < nkc) fresh = fresh && chunk_fresh(x[i], kc);
+    for (int i = 0; i < NIT; ++i) {
+      if (!((redo >> i) & 1ull) || dead) continue;
+      const int it = it_of(i);
+      for (unsigned poll = 0;; ++poll) {
+        const u32x4 v = load_it(it);
+        if (__builtin_amdgcn_ballot_w64(stale_bits(v, it) != 0u) == 0ull) {
+          use(i, make_uint4(v[0], v[1] & 0xffffu, v[2], v[3] & 0xffffu));
+          break;
+        }
+        if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+          st_relaxed(err, 1u);
+          dead = true;
+          break;
+        }
       }
-      if (dead || __all(fresh)) break;
-      if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
-        st_relaxed(err, 1u);
-        dead = true;
-        break;
-      }
-      issue<N>(x, it0);
-    }
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int kc = wave + 4 * (it0 + i);
-      const bool use = kc < nkc && kc * 4 + (lane >> 4) < nchunk_valid;
-      av[i] = use ? make_uint4(x[i][0], x[i][1] & 0xffffu, x[i][2], x[i][3] & 0xffffu) : make_uint4(0, 0, 0, 0);
     }
   }
 };
 
+// `nchunk_valid` counts the 16-lane groups (quarter chunks) that producers write; `lane_on` is false for lanes
+// whose fragment rows belong to another work-group.
 __device__ __forceinline__ RingReader make_reader(const uint4* base, int nkc, int nchunk_valid, int wave, int lane, unsigned tag,
-                                                   unsigned* err, unsigned limit) {
+                                                   unsigned* err, unsigned limit, int rot, bool lane_on = true) {
   RingReader r;
+  r.nitv = (nkc + 3) / 4; r.rot = rot;
   r.rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nkc * 1024, kBufFlags);
-  r.nkc = nkc; r.nchunk_valid = nchunk_valid; r.wave = wave; r.lane = lane; r.tag = tag; r.err = err; r.limit = limit;
+  r.voff = lane_on ? (unsigned)(wave * 1024 + lane * 16) : 0x7ff00000u;
+  r.it_bytes = 4096u; r.chunks_per_it = 4;
+  r.lim = lane_on ? nchunk_valid - (lane >> 4) - 4 * wave : -0x40000000;
+  r.lim_step = 16;
+  r.nkc = nkc; r.wave = wave; r.tag = tag; r.err = err; r.limit = limit;
   return r;
+}
+
+// Reader for a work-group that owns only 8 of a row tile's 16 rows (`half` selects which).  A load would
+// leave half the lanes idle, and the time of a ring read goes with the number of loads, not their bytes; so one
+// load serves TWO chunks: lanes whose fragment row is below 8 fetch our rows of chunk wave + 8*it, the others
+// our rows of chunk wave + 8*it + 4.  The registers as loaded are the A operand of the first chunk with our rows
+// in fragment rows 0-7 (rows 8-15 hold the other chunk's data: rows of a matrix product are independent, and
+// those output rows are never read); rotating each group of 16 lanes by 8 gives the operand of the second.
+__device__ __forceinline__ RingReader make_reader_half(const uint4* base, int nkc, int nchunk_valid, int wave, int lane, int half,
+                                                        unsigned tag, unsigned* err, unsigned limit, int rot) {
+  RingReader r;
+  r.nitv = (nkc + 7) / 8; r.rot = rot;
+  const int row = lane & 15, g = lane >> 4, second = row >> 3;
+  r.rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nkc * 1024, kBufFlags);
+  r.voff = (unsigned)((wave + 4 * second) * 1024 + (g * 16 + half * 8 + (row & 7)) * 16);
+  r.it_bytes = 8192u; r.chunks_per_it = 8;
+  r.lim = nchunk_valid - g - 4 * wave - 16 * second;
+  r.lim_step = 32;
+  r.nkc = nkc; r.wave = wave; r.tag = tag; r.err = err; r.limit = limit;
+  return r;
+}
+__device__ __forceinline__ uint4 rotate_rows_by_8(uint4 v) {
+  constexpr int kRowRor8 = 0x128;        // DPP control: rotate right by 8 inside each row of 16 lanes
+  uint4 o;
+  o.x = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v.x, kRowRor8, 0xf, 0xf, false);
+  o.y = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v.y, kRowRor8, 0xf, 0xf, false);
+  o.z = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v.z, kRowRor8, 0xf, 0xf, false);
+  o.w = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v.w, kRowRor8, 0xf, 0xf, false);
+  return o;
 }
 
 __device__ __forceinline__ void store_unit(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
   const unsigned long long u = (unsigned long long)(v0 | (v1 << 16)) | ((unsigned long long)(v2 | (tag << 16)) << 32);
   __hip_atomic_store((unsigned long long*)ring + unit_index, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Work-group -> (unit tile, row tile, direction).  Work-groups are dealt to the 8 XCDs round-robin in launch
+// order, and every work-group of one (direction, row tile) group reads the same ring tile each step.  When the
+// shape allows it the groups are laid out so that each XCD serves a single group: its L2 then fetches one
+// ring tile per step instead of all of them.  Any bijection is correct; this one is only faster.
+struct WgCoord { int tile, rt, dir; };
+__device__ __forceinline__ WgCoord wg_coord() {
+  const int ntiles = gridDim.x, nrt = gridDim.y, ndir = gridDim.z;
+  const int groups = nrt * ndir, total = ntiles * groups;
+  const int lin = blockIdx.x + ntiles * (blockIdx.y + nrt * blockIdx.z);
+  WgCoord c = {(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z};
+  if (groups <= 8 && 8 % groups == 0 && total % 8 == 0) {
+    const int xcd = lin & 7, slot = lin >> 3, per_group = 8 / groups;     // XCDs per group
+    const int group = xcd % groups;
+    c.tile = xcd / groups + per_group * slot;
+    c.rt = group % nrt;
+    c.dir = group / nrt;
+  }
+  return c;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -142,17 +229,19 @@ template <int NIT>
 __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
   __shared__ float red[4][16][65];
   __shared__ unsigned short hb[16][18];
-  const PFwdDir& d = a.d[blockIdx.z];
-  const int tile = blockIdx.x, rt = blockIdx.y, ntiles = gridDim.x;
+  const WgCoord wg = wg_coord();
+  const PFwdDir& d = a.d[wg.dir];
+  const int tile = wg.tile, rt = wg.rt, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   unsigned* err = a.sync;
   bool dead = false;
 
-  uint4 w[NIT][4];
+  const int nitv = (nkc + 3) / 4, rot = tile % nitv;
+  uint4 w[NIT][4];                       // register set `it` holds the chunk that load `it` of the stream fetches
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
-    const int kc = wave + 4 * it;
+    const int kc = wave + 4 * rot_index(it, rot, nitv);
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       w[it][q] = kc < nkc ? d.Wf[((long)(tile * 4 + q) * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
@@ -168,8 +257,9 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
     h = d.hstate[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
-  // the unit this thread publishes (threads 0..95): row r2, unit m of this producer's 6
-  const int r2 = tid / 6, m = tid - 6 * r2;
+  // the unit this thread publishes (threads 0..95).  Consecutive threads write consecutive 8-byte units, so a
+  // wavefront's publish is one contiguous run of full cache lines: chunk tid/32, row (tid/2)%16, half tid%2.
+  const int r2 = (tid >> 1) & 15, m = ((tid >> 5) << 1) | (tid & 1);
   const int cch = tile * 3 + (m >> 1);
   const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r2) * 2 + (m & 1);
 
@@ -190,25 +280,26 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
     PROF_MARK(4)
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
     uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
-    const RingReader rd = make_reader(rin, nkc, ntiles * 3, wave, lane, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit);
+    const RingReader rd = make_reader(rin, nkc, ntiles * 3, wave, lane, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
     const unsigned np_ = rd.wait_sample(dead);
     (void)np_;
     PROF_POLLS(np_)
-    u32x4 raw[NIT];
-    uint4 av[NIT];
-    rd.issue<NIT>(raw, 0);
-    fetch_zx(tau + 1, zx_next);
-    rd.settle<NIT>(raw, av, 0, dead);
-    PROF_MARK(0)
-
+    PROF_MARK(5)
     f32x4 acc[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
+    {
+      // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
+      auto use = [&](int it, uint4 av) {
 #pragma unroll
-    for (int it = 0; it < NIT; ++it)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) acc[q] = Mma16<bf16_t>::run(av[it], w[it][q], acc[q]);
+        for (int q = 0; q < 4; ++q) acc[q] = Mma16<bf16_t>::run(av, w[it][q], acc[q]);
+      };
+      const unsigned long long redo = rd.stream<NIT, kWindow>(use);
+      PROF_POLLS(100 * __popcll(redo))
+      if (redo) rd.fix_up<NIT>(redo, dead, use);
+    }
+    fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
+    PROF_MARK(0)
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -259,21 +350,21 @@ struct BwdIn { float gi, gf, gg, go, c_new, c_prev, dy; };
 
 template <int NIT>
 __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
-  constexpr int NB = 4, BS = NIT / NB;           // operand batches per step
-  static_assert(NIT % NB == 0, "operands are fetched in equal batches");
   __shared__ float red[4][16][17];
   __shared__ unsigned short zb[16][66];
-  const PBwdDir& d = a.d[blockIdx.z];
-  const int tile = blockIdx.x, rt = blockIdx.y, ntiles = gridDim.x;
+  const WgCoord wg = wg_coord();
+  const PBwdDir& d = a.d[wg.dir];
+  const int tile = wg.tile, rt = wg.rt, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   unsigned* err = a.sync;
   bool dead = false;
 
-  uint4 w[NIT];
+  const int nitv = (nkc + 3) / 4, rot = tile % nitv;
+  uint4 w[NIT];                          // register set `it` holds the chunk that load `it` of the stream fetches
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
-    const int kc = wave + 4 * it;
+    const int kc = wave + 4 * rot_index(it, rot, nitv);
     w[it] = kc < nkc ? d.Wb[((long)tile * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
   }
 
@@ -316,27 +407,24 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
 
     if (sigma > 0) {
       const uint4* rin = (((sigma - 1) & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
-      const RingReader rd = make_reader(rin, nkc, ntiles * 11, wave, lane, (unsigned)sigma & 0xffffu, err, a.spin_limit);
+      const RingReader rd = make_reader(rin, nkc, ntiles * 11, wave, lane, (unsigned)sigma & 0xffffu, err, a.spin_limit, rot);
       const unsigned np_ = rd.wait_sample(dead);
       (void)np_;
       PROF_POLLS(np_)
+      PROF_MARK(5)
       f32x4 acc[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      u32x4 raw[2][BS];
-      uint4 av[BS];
-      rd.issue<BS>(raw[0], 0);
-      in_next = fetch_in(tau - 1);
-#pragma unroll
-      for (int bt = 0; bt < NB; ++bt) {
-        if (bt + 1 < NB) rd.issue<BS>(raw[(bt + 1) & 1], (bt + 1) * BS);
-        rd.settle<BS>(raw[bt & 1], av, bt * BS, dead);
-        PROF_MARK(0)
+      {
+        // four independent accumulators keep the MFMA pipe from waiting on its own result;
         // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
-#pragma unroll
-        for (int i = 0; i < BS; ++i) acc[(bt * BS + i) & 3] = Mma16<bf16_t>::run(av[i], w[bt * BS + i], acc[(bt * BS + i) & 3]);
-        PROF_MARK(1)
+        auto use = [&](int it, uint4 av) { acc[it & 3] = Mma16<bf16_t>::run(av, w[it], acc[it & 3]); };
+        const unsigned long long redo = rd.stream<NIT, kWindow>(use);
+        PROF_POLLS(100 * __popcll(redo))
+        if (redo) rd.fix_up<NIT>(redo, dead, use);
       }
+      in_next = fetch_in(tau - 1);    // after the ring loads: loads complete in order, and these come from HBM
+      PROF_MARK(0)
 #pragma unroll
       for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = (acc[0][v] + acc[1][v]) + (acc[2][v] + acc[3][v]);
       __syncthreads();
@@ -360,8 +448,8 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
 #pragma unroll
       for (int round = 0; round < 2; ++round) {
         const int id = tid + 256 * round;
-        if (id < 16 * 22) {
-          const int r2 = id / 22, m = id - 22 * r2, v0 = 3 * m;
+        if (id < 16 * 22) {                               // consecutive threads -> consecutive 8-byte units
+          const int r2 = (id >> 1) & 15, m = ((id >> 5) << 1) | (id & 1), v0 = 3 * m;
           const unsigned x0 = zb[r2][v0], x1 = v0 + 1 < 64 ? zb[r2][v0 + 1] : 0u, x2 = v0 + 2 < 64 ? zb[r2][v0 + 2] : 0u;
           const int cch = tile * 11 + (m >> 1);
           const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r2) * 2 + (m & 1);
@@ -378,6 +466,153 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
     in = in_next;
   }
   PROF_DUMP("bwd", T)
+  if (active) {
+    d.Dh[(long)b * n + j] = Dh;
+    d.Dc[(long)b * n + j] = Dc;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, second decomposition: a work-group owns 32 units for 8 batch rows (half a row tile).
+// What bounds the backward step is the ring read, rows x K bytes per work-group; halving the rows halves it.
+// The price is a W_h^T slice twice as large (352 registers per lane), which still fits the register file.
+template <int NIT>
+__global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
+  __shared__ float red[4][8][33];
+  __shared__ unsigned short zb[8][2][66];
+  const WgCoord wg = wg_coord();
+  const PBwdDir& d = a.d[wg.dir];
+  const int tile2 = wg.tile, rt = wg.rt >> 1, half = wg.rt & 1;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
+  const int ntiles16 = (n + 15) / 16;
+  unsigned* err = a.sync;
+  bool dead = false;
+
+  const int nitv = (nkc + 7) / 8, rot = tile2 % nitv;
+  uint4 w[NIT][2];                       // register sets 2p, 2p+1 hold the two chunks that load p of the stream fetches
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int kc = wave + 4 * (2 * rot_index(it >> 1, rot, nitv) + (it & 1));
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+      const int t16 = tile2 * 2 + ct;
+      w[it][ct] = (kc < nkc && t16 < ntiles16) ? d.Wb[((long)t16 * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  const int r8 = tid >> 5, u = tid & 31;                 // pointwise pair of this thread: row r8 of the half, unit u of 32
+  const int b = rt * 16 + half * 8 + r8, j = tile2 * 32 + u;
+  const bool active = b < B && j < n;
+  float Dh = 0.f, Dc = 0.f;
+  int L = 0;
+  if (active) {
+    Dh = d.Dh[(long)b * n + j];
+    Dc = d.Dc[(long)b * n + j];
+    L = clamp_len(a.lens, b, T);
+  }
+  auto fetch_in = [&](int tau) {
+    BwdIn in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int t = d.rev ? T - 1 - tau : tau;
+    if (tau >= 0 && active && t < L) {
+      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
+      in.gi = gp[0]; in.gf = gp[n]; in.gg = gp[2 * n]; in.go = gp[3 * n];
+      in.c_new = d.cs[((long)t * B + b) * n + j];
+      const int tp = d.rev ? t + 1 : t - 1;
+      if (tp >= 0 && tp < T) in.c_prev = d.cs[((long)tp * B + b) * n + j];
+      else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
+      in.dy = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
+    }
+    return in;
+  };
+  BwdIn in = fetch_in(T - 1);
+
+  PROF_DECL
+  for (int tau = T - 1; tau >= -1; --tau) {
+    PROF_MARK(4)
+    const int sigma = T - 1 - tau;
+    const int t = d.rev ? T - 1 - tau : tau;
+    const int t_next = d.rev ? t - 1 : t + 1;
+    const bool pointwise = tau >= 0;
+    const bool valid = pointwise && active && t < L;
+    BwdIn in_next = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    if (sigma > 0) {
+      const uint4* rin = (((sigma - 1) & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
+      const RingReader rd = make_reader_half(rin, nkc, ntiles16 * 11, wave, lane, half, (unsigned)sigma & 0xffffu, err, a.spin_limit, rot);
+      const unsigned np_ = rd.wait_sample(dead);
+      (void)np_;
+      PROF_POLLS(np_)
+      PROF_MARK(5)
+      f32x4 acc[2][2];
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) acc[x][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      {
+        auto use = [&](int p, uint4 av) {
+          const uint4 av2 = rotate_rows_by_8(av);
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct) {
+            acc[0][ct] = Mma16<bf16_t>::run(av, w[2 * p][ct], acc[0][ct]);
+            acc[1][ct] = Mma16<bf16_t>::run(av2, w[2 * p + 1][ct], acc[1][ct]);
+          }
+        };
+        const unsigned long long redo = rd.stream<NIT / 2, kWindow>(use);
+        PROF_POLLS(100 * __popcll(redo))
+        if (redo) rd.fix_up<NIT / 2>(redo, dead, use);
+      }
+      in_next = fetch_in(tau - 1);
+      PROF_MARK(0)
+      // accumulator rows 4*(lane/16) + v; this work-group's rows sit in fragment rows 0..7
+      if (lane < 32) {
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][ct * 16 + (lane & 15)] = acc[0][ct][v] + acc[1][ct][v];
+      }
+      __syncthreads();
+      if (active && t_next < L) Dh = red[0][r8][u] + red[1][r8][u] + red[2][r8][u] + red[3][r8][u];
+    } else {
+      in_next = fetch_in(tau - 1);
+    }
+    if (pointwise) {
+      float dz[4] = {0.f, 0.f, 0.f, 0.f};
+      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, in.dy + Dh, Dc, dz);
+      unsigned short bits[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        bits[q] = f2bf_bits(dz[q]);
+        zb[r8][u >> 4][q * 16 + (u & 15)] = bits[q];      // inactive threads publish zeros
+      }
+      __syncthreads();
+      PROF_MARK(2)
+      uint4* rout = (sigma & 1) ? d.ring1 : d.ring0;
+      const unsigned tag_out = (unsigned)(sigma + 1) & 0xffffu;
+#pragma unroll
+      for (int round = 0; round < 2; ++round) {
+        const int id = tid + 256 * round;                 // 8 rows x 2 producers x 22 units
+        if (id < 8 * 2 * 22) {                            // consecutive threads -> consecutive 8-byte units of a chunk
+          const int pp = id / 176, rest = id - 176 * pp, rr = (rest >> 1) & 7, m = ((rest >> 4) << 1) | (rest & 1), v0 = 3 * m;
+          const int t16 = tile2 * 2 + pp;
+          if (t16 < ntiles16) {
+            const unsigned x0 = zb[rr][pp][v0], x1 = v0 + 1 < 64 ? zb[rr][pp][v0 + 1] : 0u, x2 = v0 + 2 < 64 ? zb[rr][pp][v0 + 2] : 0u;
+            const int cch = t16 * 11 + (m >> 1);
+            const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + half * 8 + rr) * 2 + (m & 1);
+            store_unit(rout, unit_index, x0, x1, x2, tag_out);
+          }
+        }
+      }
+      if (active) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits[q];
+      }
+      __syncthreads();
+      PROF_MARK(3)
+    }
+    in = in_next;
+  }
+  PROF_DUMP("bwd8", T)
   if (active) {
     d.Dh[(long)b * n + j] = Dh;
     d.Dc[(long)b * n + j] = Dc;
@@ -476,6 +711,10 @@ hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
 }
 hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s) {
   if (a.nkc > kLLMaxNkcBwd) return hipErrorCooperativeLaunchTooLarge;
+  // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
+  hipError_t e = coop(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(cdiv(a.n, 16), 2), 2 * cdiv(a.B, 16), a.ndir), a, s);
+  if (e == hipSuccess) return e;
+  (void)hipGetLastError();
   return coop(persist_bwd_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
 }
 hipError_t launch_pack_wh_fwd_ll(const void* W, uint4* Wf, int n, int nkc, int ndir, hipStream_t s) {
