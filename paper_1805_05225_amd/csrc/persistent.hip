@@ -45,7 +45,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define PROF_DUMP(name, steps)
 #endif
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
-constexpr int kWindow = 10;             // ring loads in flight per wavefront (measured knee: 10-12)
+constexpr int kWindow = 10;             // ring loads in flight per wavefront (6 to 16 measured alike; all at once is slower)
 // cache policy of the polling loads: bit 4 = coherent at agent scope (bypasses the XCD-local L2),
 // bit 31 = volatile, so the compiler re-issues the load in every poll
 constexpr int kSc1 = (int)(16u | 0x80000000u);
@@ -119,6 +119,7 @@ struct RingReader {
     unsigned long long redo = 0ull;
 #pragma unroll
     for (int i = 0; i < W && i < NIT; ++i) x[i] = load_it(it_of(i));
+    __builtin_amdgcn_sched_barrier(0);   // the whole window is issued before anything waits on it
 #pragma unroll
     for (int i = 0; i < NIT; ++i) {
       const u32x4 v = x[i % W];
@@ -338,6 +339,148 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
     PROF_MARK(3)
   }
   PROF_DUMP("fwd", T)
+  if (active) {
+    d.cstate[(long)b * n + j] = c;
+    d.hstate[(long)b * n + j] = h;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward, second decomposition: a work-group owns 32 units for 8 batch rows (half a row tile); one load
+// serves two chunks (see make_reader_half).  Half the ring bytes per work-group, twice the W_h slice
+// (384 registers per lane).
+template <int NIT>
+__global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
+  __shared__ float red[4][8][129];
+  __shared__ unsigned short hb[8][2][18];
+  const WgCoord wg = wg_coord();
+  const PFwdDir& d = a.d[wg.dir];
+  const int tile2 = wg.tile, rt = wg.rt >> 1, half = wg.rt & 1;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
+  const int ntiles16 = (n + 15) / 16;
+  unsigned* err = a.sync;
+  bool dead = false;
+
+  const int nitv = (nkc + 7) / 8, rot = tile2 % nitv;
+  uint4 w[NIT][2][4];                    // register sets 2p, 2p+1 hold the two chunks that load p of the stream fetches
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int kc = wave + 4 * (2 * rot_index(it >> 1, rot, nitv) + (it & 1));
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+      const int t16 = tile2 * 2 + ct;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        w[it][ct][q] = (kc < nkc && t16 < ntiles16) ? d.Wf[((long)(t16 * 4 + q) * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  const int r8 = tid >> 5, u = tid & 31;                 // pointwise pair of this thread: row r8 of the half, unit u of 32
+  const int b = rt * 16 + half * 8 + r8, j = tile2 * 32 + u;
+  const bool active = b < B && j < n;
+  float c = 0.f, h = 0.f;
+  int L = 0;
+  if (active) {
+    c = d.cstate[(long)b * n + j];
+    h = d.hstate[(long)b * n + j];
+    L = clamp_len(a.lens, b, T);
+  }
+  // the unit this thread publishes (threads 0..95): producer tile pp = tid/48, then consecutive threads write
+  // consecutive 8-byte units of a quarter chunk's 8 rows
+  const int pp = tid / 48, rest = tid - 48 * pp, rr = (rest >> 1) & 7, m = ((rest >> 4) << 1) | (rest & 1);
+  const int t16p = tile2 * 2 + pp;
+  const int cch = t16p * 3 + (m >> 1);
+  const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + half * 8 + rr) * 2 + (m & 1);
+  const bool publishes = tid < 96 && t16p < ntiles16;
+
+  float zx[4] = {0.f, 0.f, 0.f, 0.f}, zx_next[4] = {0.f, 0.f, 0.f, 0.f};
+  auto fetch_zx = [&](int tau, float (&z)[4]) {
+    const int t = d.rev ? T - 1 - tau : tau;
+    if (tau < T && active && t < L) {
+      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
+      z[0] = gp[0]; z[1] = gp[n]; z[2] = gp[2 * n]; z[3] = gp[3 * n];
+    }
+  };
+  fetch_zx(0, zx);
+  PROF_DECL
+  for (int tau = 0; tau < T; ++tau) {
+    const int t = d.rev ? T - 1 - tau : tau;
+    const bool valid = active && t < L;
+    PROF_MARK(4)
+    const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
+    uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
+    const RingReader rd = make_reader_half(rin, nkc, ntiles16 * 3, wave, lane, half, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
+    const unsigned np_ = rd.wait_sample(dead);
+    (void)np_;
+    PROF_POLLS(np_)
+    PROF_MARK(5)
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[ct][q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      auto use = [&](int p, uint4 av) {
+        const uint4 av2 = rotate_rows_by_8(av);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[ct][q] = Mma16<bf16_t>::run(av, w[2 * p][ct][q], acc[ct][q]);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[ct][q] = Mma16<bf16_t>::run(av2, w[2 * p + 1][ct][q], acc[ct][q]);
+      };
+      const unsigned long long redo = rd.stream<NIT / 2, NIT / 2>(use);
+      PROF_POLLS(100 * __popcll(redo))
+      if (redo) rd.fix_up<NIT / 2>(redo, dead, use);
+    }
+    fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
+    PROF_MARK(0)
+    // accumulator rows 4*(lane/16) + v; this work-group's rows sit in fragment rows 0..7
+    if (lane < 32) {
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][q * 32 + ct * 16 + (lane & 15)] = acc[ct][q][v];
+    }
+    PROF_MARK(1)
+    __syncthreads();
+
+    const float h_prev = h;
+    CellOut o = {};
+    if (valid) {
+      float zh[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) zh[q] = red[0][r8][q * 32 + u] + red[1][r8][q * 32 + u] + red[2][r8][q * 32 + u] + red[3][r8][q * 32 + u];
+      o = lstm_cell(zh, zx, c);
+      c = o.c; h = o.h;
+    }
+    hb[r8][u >> 4][u & 15] = f2bf_bits(h);          // inactive threads hold h = 0: padding rows / units publish zeros
+    __syncthreads();
+    PROF_MARK(2)
+    if (publishes) {                  // the recurrence's critical store goes out first
+      const int v0 = 3 * m;
+      const unsigned x0 = hb[rr][pp][v0], x1 = v0 + 1 < 16 ? hb[rr][pp][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[rr][pp][v0 + 2] : 0u;
+      store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
+    }
+    if (active) {                     // layer outputs and what the backward pass needs
+      Store<bf16_t>::store(d.y, ((long)t * B + b) * d.ldy + j, valid ? h : 0.f);
+      if (d.cs) d.cs[((long)t * B + b) * n + j] = c;
+      if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)t * B + b) * n + j, h_prev);
+      if (valid && a.write_gates) {
+        float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
+        gp[0] = o.gi; gp[n] = o.gf; gp[2 * n] = o.gg; gp[3 * n] = o.go;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) zx[q] = zx_next[q];
+    PROF_MARK(3)
+  }
+  PROF_DUMP("fwd8", T)
   if (active) {
     d.cstate[(long)b * n + j] = c;
     d.hstate[(long)b * n + j] = h;
@@ -707,6 +850,10 @@ hipError_t coop(K kernel, dim3 grid, const A& a, hipStream_t s) {
 
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
   if (a.nkc > kLLMaxNkcFwd) return hipErrorCooperativeLaunchTooLarge;
+  // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
+  hipError_t e = coop(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, dim3(cdiv(cdiv(a.n, 16), 2), 2 * cdiv(a.B, 16), a.ndir), a, s);
+  if (e == hipSuccess) return e;
+  (void)hipGetLastError();
   return coop(persist_fwd_kernel<kLLMaxNkcFwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
 }
 hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s) {
