@@ -54,6 +54,12 @@ struct GemmArgs {
   const int* lens; int Bt; int T;
   bool a_kcontig, b_kcontig;
   bool in_bf16, out_bf16;
+  // Fast kernel only (callers check gemm_nt_ok first and leave these zero otherwise):
+  const int* a_rows; const int* c_rows;   // logical row r of A / C lives at physical row a_rows[r] / c_rows[r]
+  int a_phys_rows;                        // rows of A in memory when a_rows is given
+  const int* m_dev; const int* k_dev;     // M / K read from device memory (capped by M / K above, which size the grid)
+  int ksplit;                             // > 1: K cut into that many ranges whose parts are ADDED to C atomically
+                                          // (float C, nseg == 1; C must hold zeros or the value to add to)
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 // Fast bfloat16 kernel for problems with both operands k-contiguous, 16-byte aligned rows and K % 8 == 0
@@ -62,9 +68,15 @@ bool gemm_nt_ok(const GemmArgs& g);
 hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s);
 // dst[c][r] = src[r][c] (16-bit elements), r < R, c < C, dst rows zero-padded up to ld_dst; nz problems with
 // strides s_src / s_dst.  lens != NULL: rows of src are frames (t = r / Bt, b = r % Bt) and are read as zero
-// unless t < lens[b].
+// unless t < lens[b].  With cidx / fidx / count from launch_frame_map the kept frames are packed instead: column
+// cidx[r] receives row r, padded frames are dropped, and columns count[0] .. count[1]-1 are zeroed (ld_dst must
+// then be a multiple of 64).
 hipError_t launch_transpose(const void* src, void* dst, int R, int C, long ld_src, long ld_dst, int nz, long s_src, long s_dst,
-                            const int* lens, int Bt, int T, hipStream_t s);
+                            const int* lens, int Bt, int T, hipStream_t s, const int* cidx = nullptr, const int* fidx = nullptr,
+                            const int* count = nullptr);
+// Numbers the frames (t, b) with t < lens[b] in (t, b) order: cidx[T*B] frame -> number or -1, fidx[number] -> frame,
+// count[0] = how many, count[1] = that rounded up to a multiple of 64.
+hipError_t launch_frame_map(const int* lens, int T, int B, int* cidx, int* fidx, int* count, hipStream_t s);
 // dst[r][0..ld_dst) = src[r][0..C) followed by zeros (16-bit elements)
 hipError_t launch_pad_rows(const void* src, void* dst, long R, int C, int ld_dst, hipStream_t s);
 
@@ -156,6 +168,7 @@ struct PBwdDir {
   const void* dy; long lddy;
   void* DZ;           // [T][B][4n]
   float* Dh; float* Dc;
+  float* dbpart;      // NULL or [2 * row tiles][4n]: slice g receives the bias gradient summed over row group g (8 rows)
   int rev;
 };
 struct PBwdArgs {
@@ -177,9 +190,12 @@ hipError_t launch_pack_wh_bwd(const void* W_h, uint4* Wb, int n, int nkc, int nd
 // h (float [ndir][B][n]) -> fragment order, zero padded, written to both ping-pong buffers
 hipError_t launch_pack_state(const float* h, uint4* frag0, uint4* frag1, int B, int n, int nkc, int nrt, int ndir,
                              bool bf16, hipStream_t s);
-hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);                 // bytes % 4 == 0
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);                 // p 4-byte aligned, bytes % 2 == 0
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);   // bytes % 4 == 0
 // db[c] (+)= sum_rows DZ[row][c]; part = float scratch [nsplit][ncols] per direction
+// db[dir][c] (+)= sum over the first nslices slices of part[dir][kColsumSlices][ncols]
+constexpr int kColsumSlices = 64;
+hipError_t launch_colsum_final(const float* part, float* db, int ncols, int ndir, int nslices, int accumulate, hipStream_t s);
 hipError_t launch_colsum(const void* DZ, float* db, float* part, int rows, int ncols, int ndir, long sDZ,
                          bool bf16, int accumulate, hipStream_t s);
 

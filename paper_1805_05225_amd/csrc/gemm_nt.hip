@@ -32,6 +32,10 @@ struct NtArgs {
   long sAz, sBz, sCz, sbiasz; int nz;
   int nseg; long sAseg, sBseg;
   int accumulate;
+  const int* a_rows; const int* c_rows;   // logical row -> physical row of A / of C (NULL: identity)
+  const int* m_dev; const int* k_dev;     // device-resident M / K (NULL: use M / K above)
+  int a_phys_rows;                        // rows of A in memory when a_rows is given
+  int ksplit;                             // > 1: K is cut into that many ranges, each adds its part to C atomically
 };
 
 __device__ __forceinline__ f32x16 mma(uint4 a, uint4 b, f32x16 c) {
@@ -48,15 +52,18 @@ struct OperandLoader {
   __amdgpu_buffer_rsrc_t rs;
   unsigned voff[8];                     // byte offset of chunk i at k = 0
   int kc8;                              // first k of this thread's chunk inside a stage
-  __device__ __forceinline__ void init(const char* base, long ld, int rows, int row0, int tid) {
-    const long bytes = (long)rows * ld * 2;
+  // `rows` logical rows; with a row map, logical row r lives at physical row map[r] (< phys_rows)
+  __device__ __forceinline__ void init(const char* base, long ld, int rows, int row0, int tid, const int* map = nullptr,
+                                       int phys_rows = 0) {
+    const long bytes = (long)(map ? phys_rows : rows) * ld * 2;
     rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, bytes > 0x7fffffffL ? 0x7fffffff : (int)bytes, kBufFlags);
     kc8 = (tid & 7) * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const long row = row0 + ((tid + kThreads * i) >> 3);
+      long row = row0 + ((tid + kThreads * i) >> 3);
+      if (map) row = row < rows ? (long)map[row] : 0x7fffffffL;
       const long off = (row * ld + kc8) * 2;
-      voff[i] = off > 0x7ffffff0L ? 0x7ffffff0u : (unsigned)off;      // past-the-end rows land outside the descriptor
+      voff[i] = (off > 0x7ffffff0L || off < 0) ? 0x7ffffff0u : (unsigned)off;   // past-the-end rows land outside the descriptor
     }
   }
   template <bool TAIL>
@@ -86,6 +93,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
 
   // tile raster: bands of 8 tile-columns, row-major inside a band: the eight XCDs (work-groups are dealt to
   // them round-robin) each keep one B tile-column in their L2 while the A tiles stream through
+  const int M = g.m_dev ? min(g.M, *g.m_dev) : g.M;        // the grid is sized for g.M; surplus tiles leave at once
+  const int K = g.k_dev ? min(g.K, *g.k_dev) : g.K;
   const int tiles_m = (g.M + kT - 1) / kT, tiles_n = (g.N + kT - 1) / kT;
   const int bid = blockIdx.x;
   const int band = bid / (8 * tiles_m);
@@ -93,7 +102,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
   const int rel = bid - band * 8 * tiles_m;
   const int tn = band * 8 + rel % width, tm = rel / width;
   const int m0 = tm * kT, n0 = tn * kT;
-  const int z = blockIdx.y;
+  if (m0 >= M) return;
+  const int ksplit = g.ksplit > 1 ? g.ksplit : 1;
+  const int z = blockIdx.y / ksplit, ks = blockIdx.y - z * ksplit;
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -103,25 +114,30 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int ktiles = (g.K + kKB - 1) / kKB;
-  const bool ktail = (g.K % kKB) != 0;
-  const int total = ktiles * g.nseg;
+  const int ktiles = (K + kKB - 1) / kKB;
+  const bool ktail = (K % kKB) != 0;
+  const int nstage = ktiles * g.nseg;
+  // stages [it0, it0 + total) belong to this work-group (all of them unless K is split)
+  const int it0 = (int)((long)nstage * ks / ksplit);
+  const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
   OperandLoader la, lb;
   int seg_loaded = -1;
   uint4 sa[8], sb[8];
   // stage `it`: segment it / ktiles, k offset (it % ktiles) * 64
-  auto fetch_a = [&](int it) {
+  auto fetch_a = [&](int rel_it) {
+    const int it = it0 + rel_it;
     const int seg = it / ktiles, kt = it - seg * ktiles;
     if (seg != seg_loaded) {
-      la.init(g.A + (g.sAz * z + g.sAseg * seg) * 2, g.lda, g.M, m0, tid);
+      la.init(g.A + (g.sAz * z + g.sAseg * seg) * 2, g.lda, M, m0, tid, g.a_rows, g.a_phys_rows);
       lb.init(g.B + (g.sBz * z + g.sBseg * seg) * 2, g.ldb, g.N, n0, tid);
       seg_loaded = seg;
     }
-    if (ktail && kt == ktiles - 1) la.fetch<true>(sa, kt * kKB, g.K); else la.fetch<false>(sa, kt * kKB, g.K);
+    if (ktail && kt == ktiles - 1) la.fetch<true>(sa, kt * kKB, K); else la.fetch<false>(sa, kt * kKB, K);
   };
-  auto fetch_b = [&](int it) {
+  auto fetch_b = [&](int rel_it) {
+    const int it = it0 + rel_it;
     const int seg = it / ktiles, kt = it - seg * ktiles;
-    if (ktail && kt == ktiles - 1) lb.fetch<true>(sb, kt * kKB, g.K); else lb.fetch<false>(sb, kt * kKB, g.K);
+    if (ktail && kt == ktiles - 1) lb.fetch<true>(sb, kt * kKB, K); else lb.fetch<false>(sb, kt * kKB, K);
   };
   // prologue: stage 0 into LDS buffer 0, stage 1 into registers
   if (total > 0) {
@@ -183,16 +199,20 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
   for (int j = 0; j < 4; ++j) {
     const int col = n0 + wn * 128 + j * 32 + r;
     if (col >= g.N) continue;
-    const float bv = bias ? bias[col] : 0.f;
+    const float bv = (bias && ks == 0) ? bias[col] : 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-        if (row < g.M) {
+        if (row < M) {
           float val = acc[i][j][v] + bv;
-          const long off = (long)row * g.ldc + col;
+          const long off = (long)(g.c_rows ? g.c_rows[row] : row) * g.ldc + col;
           if constexpr (sizeof(TC) == 4) {
+            if (ksplit > 1) {
+              unsafeAtomicAdd((float*)C + off, val);
+              continue;
+            }
             if (g.accumulate) val += ((float*)C)[off];
             ((float*)C)[off] = val;
           } else {
@@ -205,8 +225,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
 
 // dst[c][r] = keep(r) ? src[r][c] : 0 for r < R, c < C ; dst rows are padded with zeros up to ldd.
 // keep(r): rows of src are frames (t = r / Bt, b = r % Bt), kept iff lens == NULL or t < lens[b].
+// With `cidx` (compact index of every frame, -1 for padded frames) the kept frames are packed instead:
+// dst[c][cidx[r]] = src[r][c]; columns past the last kept frame are left to zero_tail_kernel.
 __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* src, uint16_t* dst, int R, int C, long lds_, long ldd,
-                                                        long s_src, long s_dst, const int* lens, int Bt, int T) {
+                                                        long s_src, long s_dst, const int* lens, int Bt, int T, const int* cidx) {
   __shared__ uint16_t tile[64][66];
   src += s_src * blockIdx.z;
   dst += s_dst * blockIdx.z;
@@ -224,15 +246,133 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* src, uin
         L = L < 0 ? 0 : (L > T ? T : L);
         keep = t < L;
       }
+      if (cidx) keep = cidx[rr] >= 0;
       if (keep) v = src[(long)rr * lds_ + cc];
     }
     tile[ty + 4 * i][tx] = v;
   }
   __syncthreads();
+  if (cidx) {
+    const int rr = r0 + tx;
+    const int dcol = rr < R ? cidx[rr] : -1;
+    if (dcol < 0) return;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int cc = c0 + ty + 4 * i;
+      if (cc < C) dst[(long)cc * ldd + dcol] = tile[tx][ty + 4 * i];
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int cc = c0 + ty + 4 * i, rr = r0 + tx;
     if (cc < C && rr < ldd) dst[(long)cc * ldd + rr] = tile[tx][ty + 4 * i];
+  }
+}
+
+// Same operation for 16-byte aligned operands (C, lds_, ldd, strides all multiples of 8 elements), written around
+// the destination: a work-group produces 64 consecutive destination columns (packed frames when `fidx` maps them
+// back to source rows) for 256 source columns.  Source rows are read as 16-byte vectors, the tile is turned in
+// LDS, and every destination row receives one aligned 128-byte run.  Columns from the last kept frame up to
+// the next multiple of 64 (packed) or up to ldd (not packed) are written as zeros here.
+__global__ __launch_bounds__(256) void transpose_frames_kernel(const uint16_t* src, uint16_t* dst, int R, int C, long lds_, long ldd,
+                                                               long s_src, long s_dst, const int* lens, int Bt, int T,
+                                                               const int* fidx, const int* count) {
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64][264];
+  src += s_src * blockIdx.z;
+  dst += s_dst * blockIdx.z;
+  const int tid = threadIdx.x;
+  const int f0 = blockIdx.x * 64, c0 = blockIdx.y * 256;
+  const int nkeep = fidx ? min(count[0], R) : R;
+  if (fidx && f0 >= count[1]) return;            // past the zeroed tail of the packed columns
+  {
+    const int cv = tid & 31, fr = tid >> 5;
+    const int col = c0 + cv * 8;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int f = pass * 8 + fr, c = f0 + f;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (c < nkeep && col < C) {
+        const int row = fidx ? fidx[c] : c;
+        bool keep = row >= 0 && row < R;
+        if (keep && lens && !fidx) {
+          const int t = row / Bt, b = row - t * Bt;
+          int L = lens[b];
+          L = L < 0 ? 0 : (L > T ? T : L);
+          keep = t < L;
+        }
+        if (keep) v = *(const uint4*)(src + (long)row * lds_ + col);
+      }
+      *(uint4*)&tile[f][cv * 8] = v;
+    }
+  }
+  __syncthreads();
+  {
+    const int g = tid & 7, cl = tid >> 3;          // 8 lanes cover the 64 columns (128 bytes) of one destination row
+    const int c = f0 + g * 8;
+    if (c >= ldd) return;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int sc = cl + 32 * pass;               // source column inside the tile
+      if (c0 + sc >= C) break;
+      uint16_t e[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) e[k] = tile[g * 8 + k][sc];
+      uint4 o;
+      o.x = e[0] | ((unsigned)e[1] << 16); o.y = e[2] | ((unsigned)e[3] << 16);
+      o.z = e[4] | ((unsigned)e[5] << 16); o.w = e[6] | ((unsigned)e[7] << 16);
+      *(uint4*)(dst + (long)(c0 + sc) * ldd + c) = o;
+    }
+  }
+}
+
+// dst[row][count[0] .. count[1]) = 0 for every row: the k tail of packed operands (count[1] = count[0] rounded up to 64)
+__global__ void zero_tail_kernel(uint16_t* dst, long rows, long ldd, const int* count) {
+  const int k0 = count[0], k1 = count[1];
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long row = idx >> 6;
+  const int k = k0 + (int)(idx & 63);
+  if (row < rows && k < k1 && k < ldd) dst[row * ldd + k] = 0;
+}
+
+// Frame map of a batch of end-padded sequences: frame (t, b) is kept iff t < lens[b].  Kept frames are numbered
+// in (t, b) order: cidx[t*B + b] = that number or -1, fidx[number] = t*B + b, count[0] = how many are kept,
+// count[1] = count[0] rounded up to a multiple of 64.  One wavefront per time step.
+__global__ __launch_bounds__(256) void frame_map_kernel(const int* lens, int T, int B, int* cidx, int* fidx, int* count) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  // kept frames before time t: sum over b of min(len_b, t)
+  long before = 0, all = 0;
+  for (int b = lane; b < B; b += 64) {
+    int L = lens[b];
+    L = L < 0 ? 0 : (L > T ? T : L);
+    before += L < t ? L : t;
+    all += L;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    before += __shfl_xor(before, o);
+    all += __shfl_xor(all, o);
+  }
+  if (t == 0 && lane == 0) {
+    count[0] = (int)all;
+    count[1] = (int)((all + 63) / 64 * 64);
+  }
+  int base = (int)before;
+  for (int b0 = 0; b0 < B; b0 += 64) {
+    const int b = b0 + lane;
+    bool keep = false;
+    if (b < B) {
+      int L = lens[b];
+      L = L < 0 ? 0 : (L > T ? T : L);
+      keep = t < L;
+    }
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
+    const int mine = base + __popcll(m & ((1ull << lane) - 1ull));
+    if (b < B) cidx[(long)t * B + b] = keep ? mine : -1;
+    if (keep) fidx[mine] = t * B + b;
+    base += __popcll(m);
   }
 }
 
@@ -262,6 +402,8 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   a.M = g.M; a.N = g.N; a.K = g.K; a.lda = g.lda; a.ldb = g.ldb; a.ldc = g.ldc;
   a.sAz = g.sAz; a.sBz = g.sBz; a.sCz = g.sCz; a.sbiasz = g.sbiasz; a.nz = g.nz;
   a.nseg = g.nseg; a.sAseg = g.sAseg; a.sBseg = g.sBseg; a.accumulate = g.accumulate;
+  a.a_rows = g.a_rows; a.c_rows = g.c_rows; a.m_dev = g.m_dev; a.k_dev = g.k_dev; a.a_phys_rows = g.a_phys_rows;
+  a.ksplit = (g.ksplit > 1 && !g.out_bf16 && g.nseg == 1) ? g.ksplit : 1;
   const int tiles = cdiv(g.M, kT) * cdiv(g.N, kT);
   const size_t shmem = 4 * kOpBytes;
   static bool attr_set = false;
@@ -272,15 +414,33 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
     attr_set = true;
   }
   if (g.out_bf16) hipLaunchKernelGGL(gemm_nt_kernel<uint16_t>, dim3(tiles, g.nz), dim3(kThreads), shmem, s, a);
-  else hipLaunchKernelGGL(gemm_nt_kernel<float>, dim3(tiles, g.nz), dim3(kThreads), shmem, s, a);
+  else hipLaunchKernelGGL(gemm_nt_kernel<float>, dim3(tiles, g.nz * a.ksplit), dim3(kThreads), shmem, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_transpose(const void* src, void* dst, int R, int C, long ld_src, long ld_dst, int nz, long s_src, long s_dst,
-                            const int* lens, int Bt, int T, hipStream_t s) {
+                            const int* lens, int Bt, int T, hipStream_t s, const int* cidx, const int* fidx, const int* count) {
   if (R <= 0 || C <= 0 || nz <= 0) return hipSuccess;
+  const bool aligned = C % 8 == 0 && ld_src % 8 == 0 && ld_dst % 8 == 0 && s_src % 8 == 0 && s_dst % 8 == 0 &&
+                       ((uintptr_t)src & 15u) == 0 && ((uintptr_t)dst & 15u) == 0;
+  if (aligned) {
+    hipLaunchKernelGGL(transpose_frames_kernel, dim3(cdiv(ld_dst, 64), cdiv(C, 256), nz), dim3(256), 0, s, (const uint16_t*)src,
+                       (uint16_t*)dst, R, C, ld_src, ld_dst, s_src, s_dst, lens, Bt, T, cidx ? fidx : nullptr, count);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(transpose_kernel, dim3(cdiv(ld_dst, 64), cdiv(C, 64), nz), dim3(256), 0, s, (const uint16_t*)src,
-                     (uint16_t*)dst, R, C, ld_src, ld_dst, s_src, s_dst, lens, Bt, T);
+                     (uint16_t*)dst, R, C, ld_src, ld_dst, s_src, s_dst, lens, Bt, T, cidx);
+  if (cidx) {                           // packed columns: zero from the last kept frame to the next multiple of 64
+    for (int z = 0; z < nz; ++z)
+      hipLaunchKernelGGL(zero_tail_kernel, dim3(cdiv((long)C * 64, 256)), dim3(256), 0, s, (uint16_t*)dst + s_dst * z, (long)C,
+                         ld_dst, count);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_frame_map(const int* lens, int T, int B, int* cidx, int* fidx, int* count, hipStream_t s) {
+  if (T <= 0 || B <= 0) return hipSuccess;
+  hipLaunchKernelGGL(frame_map_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, lens, T, B, cidx, fidx, count);
   return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ struct Plan {
   size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
   // workspace
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
-      ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, workspace_bytes;
+      ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, workspace_bytes;
   bool fast_gemm; int n_in_pad; long TBp;   // bf16 products through the k-contiguous kernel (operands transposed once)
   size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems;
 };
@@ -87,6 +87,10 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ws_XT = take(fg && !infer ? (size_t)d->n_in * p->TBp * 2 : 0);
   p->ws_DZT = take(fg && !infer ? D * 4 * n * p->TBp * 2 : 0);
   p->ws_HT = take(fg && !infer ? D * n * p->TBp * 2 : 0);
+  // frame map of the batch (which frames are real), used to leave padded frames out of the products
+  p->ws_cidx = take(fg ? (size_t)TB * 4 : 0);
+  p->ws_fidx = take(fg ? (size_t)p->TBp * 4 : 0);
+  p->ws_count = take(fg ? 256 : 0);
   p->workspace_bytes = o + kAlign;
   return LSTM_OK;
 }
@@ -203,6 +207,14 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         }
         g.B = ws + p.ws_WxT; g.K = p.n_in_pad; g.lda = p.n_in_pad; g.ldb = p.n_in_pad;
         g.sBz = (long)(4 * n) * p.n_in_pad; g.b_kcontig = true;
+        if (seq_lens && gemm_nt_ok(g)) {
+          // only real frames are projected: row r of the product is frame fidx[r]; the pre-activations of padded
+          // frames stay unwritten and are never read
+          int* fidx = (int*)(ws + p.ws_fidx);
+          int* count = (int*)(ws + p.ws_count);
+          HIPCHK(launch_frame_map(seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), fidx, count, s));
+          g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = g.M; g.m_dev = count;
+        }
       }
       HIPCHK(launch_gemm(g, s));
     }
@@ -323,6 +335,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   const size_t frag_dir = (size_t)p.nrt * p.nkc_b * 1024;
   char* DZ = ws + p.ws_DZ;
   bool done = false;
+  const bool db_in_loop = 2 * p.nrt <= kColsumSlices;   // the single-launch kernel also sums the bias gradient
   if (use_ll) {
     PBwdArgs pa = {};
     pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_b; pa.T = p.T; pa.ndir = p.D;
@@ -341,8 +354,10 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       bd.DZ = DZ + d * p.DZ_dir_elems * p.esz;
       bd.Dh = Dh + d * B * n;
       bd.Dc = Dc + d * B * n;
+      bd.dbpart = db_in_loop ? (float*)(ws + p.ws_colsum) + d * kColsumSlices * 4 * n : nullptr;
       bd.rev = bidir ? d == 1 : desc->direction == -1;
     }
+    if (db_in_loop) HIPCHK(launch_fill_zero(ws + p.ws_colsum, D * kColsumSlices * 4 * n * 4, s));   // row groups the grid lacks
     hipError_t e;
     {
       Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);
@@ -394,6 +409,26 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   }
 
   const int TB = (int)(T * B);
+  // With sequence lengths given, the products below run over the real frames only (about two thirds of T*B for
+  // the length mix of speech batches): frames are numbered once, row-indexed products gather / scatter through
+  // that numbering and the transposed operands of the weight gradients are packed by it.
+  int* cidx = (int*)(ws + p.ws_cidx);
+  int* fidx = (int*)(ws + p.ws_fidx);
+  int* count = (int*)(ws + p.ws_count);
+  const auto fits = [](long rows, long ld) { return rows * ld * 2 <= 0x7fffff00L; };
+  const bool compact = p.fast_gemm && seq_lens && TB > 0;
+  const bool compact_w = compact && fits(p.n_in, p.TBp) && fits(4L * p.n, p.TBp) && fits(p.n, p.TBp);
+  if (compact) {
+    Phase ph(LSTM_PHASE_PREP, 1, s);
+    HIPCHK(launch_frame_map(seq_lens, p.T, p.B, cidx, fidx, count, s));
+  }
+  // weight-gradient products with few output tiles split K so that the whole device works on them
+  const auto ksplit_for = [&](int M, int N) {
+    const long tiles = (long)cdiv(M, 256) * cdiv(N, 256) * p.D;
+    const long want = 256 / (tiles > 0 ? tiles : 1);
+    const long most = p.TBp / 4096 > 0 ? p.TBp / 4096 : 1;        // every range keeps a long k loop
+    return (int)std::max(1L, std::min(std::min(want, most), 8L));
+  };
   if (dx) {                        // dX = sum over directions of DZ W_x^T
     GemmArgs g = {};
     g.A = DZ; g.B = W_x; g.C = dx;
@@ -404,33 +439,44 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.vecA = widest(g.lda, g.sAseg, 0, p.esz, 16);
     g.vecB = widest(g.ldb, g.sBseg, 0, p.esz, 16);
     Phase ph(LSTM_PHASE_GEMM_DX, 1, s);
+    if (compact && gemm_nt_ok(g)) {      // rows of padded frames: zero, and left out of the product
+      HIPCHK(launch_fill_zero(dx, (size_t)TB * n_in * p.esz, s));
+      g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = TB; g.m_dev = count;
+    }
     HIPCHK(launch_gemm(g, s));
   }
   if (p.fast_gemm) {               // weight gradients with operands transposed once: everything k-contiguous
     const long TBp = p.TBp;
     {
       Phase ph(LSTM_PHASE_GEMM_DWX, 3, s);
+      const int* cmap = compact_w ? cidx : nullptr;
       HIPCHK(launch_transpose(DZ, ws + p.ws_DZT, TB, 4 * p.n, 4 * n, TBp, p.D, (long)p.DZ_dir_elems, (long)(4 * n) * TBp,
-                              nullptr, 1, 0, s));
-      HIPCHK(launch_transpose(x, ws + p.ws_XT, TB, p.n_in, n_in, TBp, 1, 0, 0, seq_lens, p.B, p.T, s));
+                              nullptr, 1, 0, s, cmap, fidx, count));
+      HIPCHK(launch_transpose(x, ws + p.ws_XT, TB, p.n_in, n_in, TBp, 1, 0, 0, seq_lens, p.B, p.T, s, cmap, fidx, count));
       GemmArgs g = {};
       g.A = ws + p.ws_XT; g.B = ws + p.ws_DZT; g.C = dW_x;
       g.M = p.n_in; g.N = 4 * p.n; g.K = (int)TBp; g.lda = TBp; g.ldb = TBp; g.ldc = 4 * n;
       g.sAz = 0; g.sBz = (long)(4 * n) * TBp; g.sCz = (long)(n_in * 4 * n); g.nz = p.D; g.nseg = 1;
       g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false; g.accumulate = acc;
       g.vecA = 16; g.vecB = 16;
+      if (compact_w) g.k_dev = count + 1;
+      if (gemm_nt_ok(g) && (g.ksplit = ksplit_for(g.M, g.N)) > 1 && !acc)
+        HIPCHK(launch_fill_zero(dW_x, D * n_in * 4 * n * 4, s));
       HIPCHK(launch_gemm(g, s));
     }
     {
       Phase ph(LSTM_PHASE_GEMM_DWH, 2, s);
       HIPCHK(launch_transpose(rs + p.res_hprev, ws + p.ws_HT, TB, p.n, n, TBp, p.D, (long)(p.res_dir_stride / 2), (long)n * TBp,
-                              nullptr, 1, 0, s));
+                              nullptr, 1, 0, s, compact_w ? cidx : nullptr, fidx, count));
       GemmArgs g = {};
       g.A = ws + p.ws_HT; g.B = ws + p.ws_DZT; g.C = dW_h;
       g.M = p.n; g.N = 4 * p.n; g.K = (int)TBp; g.lda = TBp; g.ldb = TBp; g.ldc = 4 * n;
       g.sAz = (long)n * TBp; g.sBz = (long)(4 * n) * TBp; g.sCz = (long)(n * 4 * n); g.nz = p.D; g.nseg = 1;
       g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false; g.accumulate = acc;
       g.vecA = 16; g.vecB = 16;
+      if (compact_w) g.k_dev = count + 1;
+      if (gemm_nt_ok(g) && (g.ksplit = ksplit_for(g.M, g.N)) > 1 && !acc)
+        HIPCHK(launch_fill_zero(dW_h, D * n * 4 * n * 4, s));
       HIPCHK(launch_gemm(g, s));
     }
   } else {                         // dW_x = X^T DZ, padded frames of X masked out
@@ -456,6 +502,10 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     HIPCHK(launch_gemm(g, s));
   }
   Phase ph(LSTM_PHASE_DB, 2, s);
+  if (done && db_in_loop) {
+    HIPCHK(launch_colsum_final((const float*)(ws + p.ws_colsum), (float*)db, 4 * p.n, p.D, 2 * p.nrt, acc, s));
+    return LSTM_OK;
+  }
   HIPCHK(launch_colsum(DZ, (float*)db, (float*)(ws + p.ws_colsum), TB, 4 * p.n, p.D, (long)p.DZ_dir_elems, p.bf16, acc, s));
   return LSTM_OK;
 }

@@ -59,7 +59,7 @@ __device__ __forceinline__ void st_relaxed(unsigned* p, unsigned v) {
 
 // Ring reads.  One wavefront owns chunks kc = wave + 4*it of its row tile.  Reads of freshly written
 // remote data are latency-bound per compute unit and degrade when more than ~12 KiB per wavefront is in
-// flight, so (a) a wave first polls ONE chunk (its last) until that shows the awaited tag, which is cheap
+// flight, so (a) a wave first polls two of its chunks until they show the awaited tag, which is cheap
 // while the producers are still busy, and only then (b) streams its operands with a bounded window of loads
 // in flight, checking every tag; if any tag is stale the whole stream is repeated.
 //
@@ -97,10 +97,13 @@ struct RingReader {
   // bounded wait on the wave's last chunk; returns the number of polls (diagnostics only)
   __device__ __forceinline__ unsigned wait_sample(bool& dead) const {
     if (dead || wave >= nkc) return 0;
-    const int it = it_of(nitv - 1);                            // last load of this wave's stream
+    // two loads of this wave's stream, the last and the middle one: a second sample costs nothing extra per
+    // poll and makes stale operands in the stream that follows several times rarer
+    const int it = it_of(nitv - 1), it2 = it_of((nitv - 1) / 2);
     for (unsigned poll = 0;; ++poll) {
       const u32x4 x = load_it(it);
-      if (__all(stale_bits(x, it) == 0u)) return poll + 1;
+      const u32x4 x2 = load_it(it2);
+      if (__all((stale_bits(x, it) | stale_bits(x2, it2)) == 0u)) return poll + 1;
       if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
         st_relaxed(err, 1u);
         dead = true;
@@ -113,13 +116,15 @@ struct RingReader {
   // A load in which any lane saw a stale tag contributes a zero operand instead and is recorded in the
   // returned bit mask (wave-uniform); `fix_up` then fetches exactly those loads again.  Once the sample has
   // turned this is rare, and it costs one extra load latency instead of a second pass over everything.
-  template <int NIT, int W, typename F>
+  template <int NIT, int W, bool PIN = false, typename F>
   __device__ __forceinline__ unsigned long long stream(F&& use) const {
     u32x4 x[W];
     unsigned long long redo = 0ull;
 #pragma unroll
     for (int i = 0; i < W && i < NIT; ++i) x[i] = load_it(it_of(i));
-    __builtin_amdgcn_sched_barrier(0);   // the whole window is issued before anything waits on it
+    // PIN: nothing is scheduled across this point, so the whole window is issued before anything waits on it
+    // (needed where register pressure would otherwise make the compiler serialise the loads)
+    if (PIN) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < NIT; ++i) {
       const u32x4 v = x[i % W];
@@ -432,7 +437,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) acc[ct][q] = Mma16<bf16_t>::run(av2, w[2 * p + 1][ct][q], acc[ct][q]);
       };
-      const unsigned long long redo = rd.stream<NIT / 2, NIT / 2>(use);
+      const unsigned long long redo = rd.stream<NIT / 2, NIT / 2, true>(use);
       PROF_POLLS(100 * __popcll(redo))
       if (redo) rd.fix_up<NIT / 2>(redo, dead, use);
     }
@@ -515,6 +520,7 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
   const int b = rt * 16 + r, j = tile * 16 + u;
   const bool active = b < B && j < n;
   float Dh = 0.f, Dc = 0.f;
+  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};                 // this (row, unit)'s share of the bias gradient
   int L = 0;
   if (active) {
     Dh = d.Dh[(long)b * n + j];
@@ -581,6 +587,7 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
       unsigned short bits[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
+        dbsum[q] += dz[q];
         bits[q] = f2bf_bits(dz[q]);
         zb[r][q * 16 + u] = bits[q];                       // inactive threads publish zeros
       }
@@ -612,6 +619,22 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
   if (active) {
     d.Dh[(long)b * n + j] = Dh;
     d.Dc[(long)b * n + j] = Dc;
+  }
+  if (d.dbpart) {                       // bias gradient: sum this work-group's 16 rows, one slice per row group
+    __shared__ float dbred[16][65];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dbred[r][q * 16 + u] = dbsum[q];
+    __syncthreads();
+    if (tid < 64) {
+      const int q = tid >> 4, uu = tid & 15, jj = tile * 16 + uu;
+      float sum = 0.f;
+#pragma unroll
+      for (int rr = 0; rr < 16; ++rr) sum += dbred[rr][q * 16 + uu];
+      if (jj < n) {
+        d.dbpart[(long)(2 * rt) * 4 * n + q * n + jj] = sum;
+        d.dbpart[(long)(2 * rt + 1) * 4 * n + q * n + jj] = 0.f;
+      }
+    }
   }
 }
 
@@ -648,6 +671,7 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
   const int b = rt * 16 + half * 8 + r8, j = tile2 * 32 + u;
   const bool active = b < B && j < n;
   float Dh = 0.f, Dc = 0.f;
+  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};                 // this (row, unit)'s share of the bias gradient
   int L = 0;
   if (active) {
     Dh = d.Dh[(long)b * n + j];
@@ -725,6 +749,7 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
       unsigned short bits[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
+        dbsum[q] += dz[q];
         bits[q] = f2bf_bits(dz[q]);
         zb[r8][u >> 4][q * 16 + (u & 15)] = bits[q];      // inactive threads publish zeros
       }
@@ -759,6 +784,19 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
   if (active) {
     d.Dh[(long)b * n + j] = Dh;
     d.Dc[(long)b * n + j] = Dc;
+  }
+  if (d.dbpart) {                       // bias gradient: sum this work-group's 8 rows, one slice per row group
+    __shared__ float dbred[8][129];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dbred[r8][q * 32 + u] = dbsum[q];
+    __syncthreads();
+    if (tid < 128) {
+      const int q = tid >> 5, uu = tid & 31, jj = tile2 * 32 + uu;
+      float sum = 0.f;
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) sum += dbred[rr][q * 32 + uu];
+      if (jj < n) d.dbpart[(long)wg.rt * 4 * n + q * n + jj] = sum;
+    }
   }
 }
 

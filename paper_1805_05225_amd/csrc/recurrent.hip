@@ -207,8 +207,9 @@ __global__ void pack_state_kernel(const float* h, uint4* f0, uint4* f1, int B, i
   f1[idx] = *(uint4*)v;
 }
 
-__global__ void fill_zero_kernel(uint32_t* p, size_t nwords) {
+__global__ void fill_zero_kernel(uint32_t* p, size_t nwords, int tail16) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+  if (i == 0 && tail16) ((uint16_t*)(p + nwords))[0] = 0;
   for (; i < nwords; i += stride) p[i] = 0u;
 }
 __global__ void copy_kernel(uint32_t* dst, const uint32_t* src, size_t nwords) {
@@ -217,7 +218,7 @@ __global__ void copy_kernel(uint32_t* dst, const uint32_t* src, size_t nwords) {
 }
 
 // column sums in two deterministic passes: partial sums over row slices, then a sum over slices
-constexpr int kColsumSplit = 64;
+constexpr int kColsumSplit = kColsumSlices;
 template <typename T>
 __global__ void colsum_part_kernel(const T* DZ, float* part, int rows, int ncols, long sDZ) {
   int c = blockIdx.x * blockDim.x + threadIdx.x, sp = blockIdx.y, dir = blockIdx.z;
@@ -229,11 +230,11 @@ __global__ void colsum_part_kernel(const T* DZ, float* part, int rows, int ncols
   for (int r = r0; r < r1; ++r) s += (float)p[(long)r * ncols + c];
   part[((long)dir * kColsumSplit + sp) * ncols + c] = s;
 }
-__global__ void colsum_final_kernel(const float* part, float* db, int ncols, int accumulate) {
+__global__ void colsum_final_kernel(const float* part, float* db, int ncols, int nslices, int accumulate) {
   int c = blockIdx.x * blockDim.x + threadIdx.x, dir = blockIdx.y;
   if (c >= ncols) return;
   float s = 0.f;
-  for (int sp = 0; sp < kColsumSplit; ++sp) s += part[((long)dir * kColsumSplit + sp) * ncols + c];
+  for (int sp = 0; sp < nslices; ++sp) s += part[((long)dir * kColsumSplit + sp) * ncols + c];
   float* o = db + (long)dir * ncols + c;
   *o = accumulate ? *o + s : s;
 }
@@ -278,7 +279,8 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   if (bytes == 0) return hipSuccess;
   size_t nw = bytes / 4;
   int blocks = (int)((nw + 255) / 256 > 4096 ? 4096 : (nw + 255) / 256);
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint32_t*)p, nw);
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint32_t*)p, nw, (int)((bytes & 2) != 0));
   return hipGetLastError();
 }
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
@@ -293,7 +295,11 @@ hipError_t launch_colsum(const void* DZ, float* db, float* part, int rows, int n
   dim3 grid(cdiv(ncols, 256), kColsumSplit, ndir), block(256);
   if (bf16) hipLaunchKernelGGL(colsum_part_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)DZ, part, rows, ncols, sDZ);
   else hipLaunchKernelGGL(colsum_part_kernel<float>, grid, block, 0, s, (const float*)DZ, part, rows, ncols, sDZ);
-  hipLaunchKernelGGL(colsum_final_kernel, dim3(cdiv(ncols, 256), ndir), block, 0, s, part, db, ncols, accumulate);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3(cdiv(ncols, 256), ndir), block, 0, s, part, db, ncols, kColsumSplit, accumulate);
+  return hipGetLastError();
+}
+hipError_t launch_colsum_final(const float* part, float* db, int ncols, int ndir, int nslices, int accumulate, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_final_kernel, dim3(cdiv(ncols, 256), ndir), dim3(256), 0, s, part, db, ncols, nslices, accumulate);
   return hipGetLastError();
 }
 
