@@ -192,34 +192,76 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
     __syncthreads();
   }
 
-  // epilogue: a lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 block
+  // Epilogue.  A lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 block: stored as
+  // it is that would be 128-byte pieces, eight of them per row at different times.  The tile goes through LDS
+  // instead (two halves of 128 rows, the main loop's buffers are free by now) and leaves as whole rows: one
+  // wavefront store = 256 consecutive columns of one row.
   TC* C = (TC*)g.C + g.sCz * z;
   const float* bias = g.bias ? g.bias + g.sbiasz * z : nullptr;
+  constexpr int kEpStride = 260;                      // floats per staged row (16-byte aligned, off the bank period)
+  float* ep = (float*)lds;
+  const bool vec_ok = (g.ldc % 4 == 0) && (((uintptr_t)C & 15u) == 0);
+  float bv[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int col = n0 + wn * 128 + j * 32 + r;
-    if (col >= g.N) continue;
-    const float bv = (bias && ks == 0) ? bias[col] : 0.f;
+    bv[j] = (bias && ks == 0 && col < g.N) ? bias[col] : 0.f;
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+  for (int half = 0; half < 2; ++half) {
+    __syncthreads();                                   // LDS free: main loop done / previous half stored
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-        if (row < M) {
-          float val = acc[i][j][v] + bv;
-          const long off = (long)(g.c_rows ? g.c_rows[row] : row) * g.ldc + col;
-          if constexpr (sizeof(TC) == 4) {
-            if (ksplit > 1) {
-              unsafeAtomicAdd((float*)C + off, val);
-              continue;
-            }
-            if (g.accumulate) val += ((float*)C)[off];
-            ((float*)C)[off] = val;
-          } else {
-            ((uint16_t*)C)[off] = f2bf_bits(val);
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int rowl = wm * 64 + ii * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
+          ep[rowl * kEpStride + wn * 128 + j * 32 + r] = acc[2 * half + ii][j][v] + bv[j];
+        }
+    __syncthreads();
+    const int col = n0 + lane * 4;
+    for (int rr = 0; rr < 32; ++rr) {
+      const int rowl = wave * 32 + rr;
+      const int row = m0 + (rowl >> 6) * 128 + half * 64 + (rowl & 63);
+      if (row >= M) break;                             // rows ascend with rr inside a wave's share
+      if (col >= g.N) continue;
+      const float4 val = *(const float4*)&ep[rowl * kEpStride + lane * 4];
+      const float e[4] = {val.x, val.y, val.z, val.w};
+      const long off = (long)(g.c_rows ? g.c_rows[row] : row) * g.ldc + col;
+      const bool whole = vec_ok && col + 3 < g.N;
+      if constexpr (sizeof(TC) == 4) {
+        float* Cf = (float*)C + off;
+        if (ksplit > 1) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (col + k < g.N) unsafeAtomicAdd(Cf + k, e[k]);
+        } else if (whole) {
+          float4 o = val;
+          if (g.accumulate) {
+            const float4 old = *(const float4*)Cf;
+            o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
           }
+          *(float4*)Cf = o;
+        } else {
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (col + k < g.N) Cf[k] = g.accumulate ? Cf[k] + e[k] : e[k];
+        }
+      } else {
+        uint16_t* Cb = (uint16_t*)C + off;
+        if (whole) {
+          uint2 o;
+          o.x = f2bf_bits(e[0]) | ((unsigned)f2bf_bits(e[1]) << 16);
+          o.y = f2bf_bits(e[2]) | ((unsigned)f2bf_bits(e[3]) << 16);
+          *(uint2*)Cb = o;
+        } else {
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (col + k < g.N) Cb[k] = f2bf_bits(e[k]);
         }
       }
+    }
   }
 }
 
