@@ -293,6 +293,20 @@ def test_bf16_stack_reduced(k, over):
         check("db%d" % l, g["db"], r[2], tol)
 
 
+@pytest.mark.timeout(900)
+def test_config4_first_layer_full_size():
+    """Config 4 at its full size (T = 1491, B = 32, n = 1024, bf16): the launch configuration the benchmark times
+    (single-launch recurrent kernels on 256 work-groups, products over real frames only).  One layer, because the
+    oracle's inputs must be synthetic: every output of the first layer is compared element by element.  The oracle
+    needs about a minute for it."""
+    inp = synth.make(4, layers=1)
+    c = _config_case(inp)
+    print("  config 4, first layer, full size: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
+    f, g = run_gpu(c, "bf16", True)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL["bf16"])
+
+
 def test_config5_decoder_stepping_bf16():
     inp = synth.make(5)
     L = inp["layers"][0]
