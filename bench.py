@@ -7,8 +7,8 @@ with float state) followed by one backward pass through all six layers, on synth
 inputs that are resident in HBM before the timed region starts.  frames = sum(seq_lens), each
 real frame counted once for the whole stack.
 
-Prints ONE JSON line.  `roofline` describes the dominant kernel (the recurrent forward step);
-`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line.  `roofline` describes the dominant kernel (the backward recurrent loop, one
+launch per layer); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -204,15 +204,14 @@ def main():
             roof_fwd["traffic"] = tr.get("persist_fwd_bytes_per_launch")
     except (OSError, ValueError):
         pass
-    # hoisted products: flops executed (padded frames included) per benchmark step
-    TB = T * B
+    # hoisted products: algorithmic flops per benchmark step (the products run over the real frames only)
     gemm_flops = {"gemm_zx": 0.0, "gemm_dx": 0.0, "gemm_dwx": 0.0, "gemm_dwh": 0.0}
     for l in range(nl):
         ni = cfg["n_in"] if l == 0 else 2 * n
-        gemm_flops["gemm_zx"] += 2.0 * TB * ni * 8 * n
-        gemm_flops["gemm_dx"] += 2.0 * TB * ni * 8 * n
-        gemm_flops["gemm_dwx"] += 2.0 * TB * ni * 8 * n
-        gemm_flops["gemm_dwh"] += 2.0 * TB * n * 8 * n
+        gemm_flops["gemm_zx"] += 2.0 * frames * ni * 8 * n
+        gemm_flops["gemm_dx"] += 2.0 * frames * ni * 8 * n
+        gemm_flops["gemm_dwx"] += 2.0 * frames * ni * 8 * n
+        gemm_flops["gemm_dwh"] += 2.0 * frames * n * 8 * n
     gemm_ms = sum(prof[k][0] for k in gemm_flops)
     gemm_tflops = sum(gemm_flops.values()) * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     mfma_peak = BF16_PEAK_TFLOPS if esz == 2 else 157.3
@@ -232,8 +231,8 @@ def main():
         "roofline_forward_loop": roof_fwd if dominant is roof_bwd else roof_bwd,
         "roofline_hoisted_gemms": {"bound": "mfma", "achieved": gemm_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
                                    "frac": gemm_tflops / mfma_peak,
-                                   "note": "executed flops of the four hoisted products per layer (padded frames included, "
-                                           "operand transposes inside the timed phases)"},
+                                   "note": "flops of the four hoisted products per layer over the real frames; the operand "
+                                           "transposes and the frame map are inside the timed phases"},
         "phases_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
     }
     if not args.no_cpu:
