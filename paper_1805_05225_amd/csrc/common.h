@@ -176,8 +176,20 @@ struct PBwdArgs {
   const int* lens;
   int B, n, nkc, T, ndir;
   unsigned* sync; unsigned spin_limit;
+  unsigned* xcc;      // NULL or one zeroed word per work-group: lets an exchange group find out whether it shares an XCD
 };
-hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s);
+// Which single-launch backward kernel fits the device for this problem (decided before W_h is packed, because the
+// forms pack it differently): partial sums of Dh exchanged (fastest; W_h via launch_pack_wh_bwdp, ring of
+// bwdp_ring_bytes per direction and slot), dz exchanged with 32x8 or 16x16 work-groups (launch_pack_wh_bwd_ll), none.
+enum { kBwdNone = 0, kBwdPartialSums = 1, kBwdDz8 = 2, kBwdDz16 = 3 };
+int persist_bwd_variant(const PBwdArgs& a);
+hipError_t launch_persist_bwd(const PBwdArgs& a, int variant, hipStream_t s);
+hipError_t launch_pack_wh_bwdp(const void* W_h, uint4* Wb, int n, int ndir, hipStream_t s);
+inline size_t bwdp_wh_bytes(int n) { return (size_t)((n + 31) / 32) * 262144; }                  // per direction
+inline size_t bwdp_ring_bytes(int B, int n) {                                                      // per direction and slot
+  const size_t groups = 2 * (size_t)(((B > 0 ? B : 1) + 15) / 16), tiles = (size_t)((n + 31) / 32);
+  return groups * tiles * tiles * 1024;
+}
 hipError_t launch_pack_wh_fwd_ll(const void* W_h, uint4* Wf, int n, int nkc, int ndir, hipStream_t s);
 hipError_t launch_pack_wh_bwd_ll(const void* W_h, uint4* Wb, int n, int nkc, int ndir, hipStream_t s);
 // h (float [ndir][B][n]) -> ring slot 0 with tag 1; ring slot 1 cleared

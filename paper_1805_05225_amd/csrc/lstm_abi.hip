@@ -58,12 +58,16 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->reserve_bytes = D * p->res_dir_stride + kAlign;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
-  p->sync_bytes = up((1 + 2 * (size_t)p->nrt) * 4);
+  // error word, per-row-tile words, then one word per work-group of a single-launch kernel (its XCD)
+  p->sync_bytes = up((64 + 2 * (size_t)p->nrt) * 4 + D * 2 * (size_t)p->nrt * cdiv(d->n, 32) * 4);
   p->ws_sync = take(p->sync_bytes);              // first, so that lstm_sync_status() finds it without a plan
   p->ws_Wf = take(D * std::max((size_t)p->ntile_f * 2 * p->nkc_f, (size_t)p->ntile16 * 4 * p->nkc_ll_f) * 1024);
-  p->ws_Wb = take(infer ? 0 : D * std::max((size_t)p->ntile_b * p->nkc_b, (size_t)p->ntile16 * p->nkc_ll_b) * 1024);
+  const bool part = p->bf16 && d->n <= 1024;          // the partial-sum backward kernel may be chosen
+  p->ws_Wb = take(infer ? 0 : D * std::max(std::max((size_t)p->ntile_b * p->nkc_b, (size_t)p->ntile16 * p->nkc_ll_b) * 1024,
+                                           part ? bwdp_wh_bytes(d->n) : (size_t)0));
   p->hfrag_bytes = D * p->nrt * (size_t)std::max(p->nkc_f, p->nkc_ll_f) * 1024;
-  p->dzfrag_bytes = D * p->nrt * (size_t)std::max(p->nkc_b, p->nkc_ll_b) * 1024;
+  p->dzfrag_bytes = D * std::max(p->nrt * (size_t)std::max(p->nkc_b, p->nkc_ll_b) * 1024,
+                                 part ? bwdp_ring_bytes(d->B, d->n) : (size_t)0);
   p->ws_hfrag0 = take(p->hfrag_bytes);
   p->ws_hfrag1 = take(p->hfrag_bytes);
   p->ws_dzfrag0 = take(infer ? 0 : p->dzfrag_bytes);
@@ -325,10 +329,18 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     HIPCHK(launch_fill_zero(ws + p.ws_dzfrag0, p.dzfrag_bytes, s));
     HIPCHK(launch_fill_zero(ws + p.ws_dzfrag1, p.dzfrag_bytes, s));
   }
-  bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_b <= kLLMaxNkcBwd;
+  // single-launch path: bf16 storage, at least two steps, and one of the kernel forms fits the device
+  PBwdArgs pa = {};
+  pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_b; pa.T = p.T; pa.ndir = p.D;
+  pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
+  pa.xcc = (unsigned*)(ws + p.ws_sync) + 64 + 2 * (size_t)p.nrt;
+  int variant = kBwdNone;
+  if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2) variant = persist_bwd_variant(pa);
+  const bool use_ll = variant != kBwdNone;
   {
     Phase ph(LSTM_PHASE_PREP, 1, s);
-    if (use_ll) HIPCHK(launch_pack_wh_bwd_ll(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_ll_b, p.D, s));
+    if (variant == kBwdPartialSums) HIPCHK(launch_pack_wh_bwdp(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, s));
+    else if (use_ll) HIPCHK(launch_pack_wh_bwd_ll(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_ll_b, p.D, s));
     else HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
   }
 
@@ -337,13 +349,12 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   bool done = false;
   const bool db_in_loop = 2 * p.nrt <= kColsumSlices;   // the single-launch kernel also sums the bias gradient
   if (use_ll) {
-    PBwdArgs pa = {};
-    pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_b; pa.T = p.T; pa.ndir = p.D;
-    pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
-    const size_t ring_dir = (size_t)p.nrt * p.nkc_ll_b * 1024;
+    const bool part = variant == kBwdPartialSums;
+    const size_t ring_dir = part ? bwdp_ring_bytes(p.B, p.n) : (size_t)p.nrt * p.nkc_ll_b * 1024;
+    const size_t wb_dir = part ? bwdp_wh_bytes(p.n) : (size_t)p.ntile16 * p.nkc_ll_b * 1024;
     for (size_t d = 0; d < D; ++d) {
       PBwdDir& bd = pa.d[d];
-      bd.Wb = (const uint4*)(ws + p.ws_Wb + d * (size_t)p.ntile16 * p.nkc_ll_b * 1024);
+      bd.Wb = (const uint4*)(ws + p.ws_Wb + d * wb_dir);
       bd.ring0 = (uint4*)(ws + p.ws_dzfrag0 + d * ring_dir);
       bd.ring1 = (uint4*)(ws + p.ws_dzfrag1 + d * ring_dir);
       bd.gates = (const float*)(rs + d * p.res_dir_stride + p.res_gates);
@@ -361,7 +372,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     hipError_t e;
     {
       Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);
-      e = launch_persist_bwd(pa, s);
+      e = launch_persist_bwd(pa, variant, s);
     }
     if (e == hipSuccess) done = true;
     else {

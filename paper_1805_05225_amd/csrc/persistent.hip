@@ -24,6 +24,8 @@
 // grid always drains.  The launch is cooperative, which guarantees that all work-groups are
 // resident together (otherwise the launch is refused and the caller uses the per-step kernels).
 #include "recurrent_dev.h"
+#include <map>
+#include <mutex>
 
 namespace lstm {
 namespace {
@@ -202,6 +204,62 @@ __device__ __forceinline__ uint4 rotate_rows_by_8(uint4 v) {
   o.z = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v.z, kRowRor8, 0xf, 0xf, false);
   o.w = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v.w, kRowRor8, 0xf, 0xf, false);
   return o;
+}
+
+// two floats -> two bf16 (round to nearest even) in one register, low half first
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_;
+  const bf16x2_ r = __builtin_convertvector((f32x2_){lo, hi}, bf16x2_);
+  return __builtin_bit_cast(unsigned, r);
+}
+// --- W_h in accumulation registers ---------------------------------------------------------------------------
+// The register file of a wavefront is 256 architectural + 256 accumulation registers.  A W_h slice larger than
+// what is left of the first 256 is parked by the compiler in accumulation registers and copied back, four moves
+// per MFMA, before every use - with one wavefront per SIMD those moves are on the critical path.  MFMA can read
+// its B operand from accumulation registers directly, so the slice is loaded straight into them and the products
+// are issued through inline assembly.  The compiler does not see an MFMA in that text, so the wait states the
+// hardware needs between the last MFMA and the first read of its result are inserted by hand (mfma_settle).
+__device__ __forceinline__ u32x4 load_to_agpr(const uint4* p) {
+  u32x4 r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(r) : "v"(p) : "memory");
+  return r;
+}
+__device__ __forceinline__ void agpr_loads_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// acc += A (16 rows x 32 k, vector registers) x B (32 k x 16 columns, accumulation registers)
+__device__ __forceinline__ void mfma_b_agpr(f32x4& acc, const u32x4& a, const u32x4& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+// 20 wait states: more than any MFMA of this shape needs before its result may be read or overwritten
+__device__ __forceinline__ void mfma_settle(f32x4& a0, f32x4& a1, f32x4& a2, f32x4& a3) {
+  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3));
+}
+
+// Is every work-group of this one's exchange group on the same XCD?  Then their ring stores need not be written
+// through to memory: the XCD's L2 is the point where those work-groups meet (measured: one-way latency 212 ns
+// instead of 350, and the ring's store traffic stays out of the fabric).  Each work-group publishes the XCD it runs on
+// (hardware register XCC_ID) in `tab` (zero-filled by the host, one word per work-group, a group's words consecutive
+// from `group_base`) and reads the group's words; anything but "all equal to mine" - a word still unset after the
+// poll limit included - means "not local", and the caller then uses agent-scope stores as before.  The verdict
+// needs no agreement: a work-group that says "local" has seen every member on its own XCD.
+__device__ __forceinline__ bool group_is_xcd_local(unsigned* tab, int group_base, int members, int me, unsigned limit) {
+  __shared__ int verdict;
+  if (threadIdx.x == 0) {
+    const unsigned mine = (__builtin_amdgcn_s_getreg(((4 - 1) << 11) | 20) & 15u) + 1u;     // XCC_ID, bits 3:0
+    st_relaxed(&tab[group_base + me], mine);
+    bool same = true;
+    for (int p = 0; p < members && same; ++p) {
+      unsigned v = 0u;
+      for (unsigned poll = 0; poll < limit; ++poll) {
+        v = ld_relaxed(&tab[group_base + p]);
+        if (v != 0u) break;
+      }
+      same = v == mine;
+    }
+    verdict = same ? 1 : 0;
+  }
+  __syncthreads();
+  return verdict != 0;
 }
 
 __device__ __forceinline__ void store_unit(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
@@ -801,6 +859,212 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// backward, third decomposition ("partial sums"): no dz crosses work-groups.  A work-group still owns 32 units for
+// 8 rows, but it multiplies ITS dz (8 rows x 128 gate columns) by the matching 128 rows of W_h^T for ALL n outputs
+// and publishes, per destination tile of 32 units, a partial sum of Dh (bf16).  A consumer adds the partial sums
+// of its tile from all producers: 1 KiB per producer, 32 KiB per step at n = 1024, where reading dz itself takes
+// 88 KiB.  The ring read is what bounds the backward step, so this is the fastest of the three forms.  Dh is
+// therefore a sum of bf16-rounded partial sums (accumulated in float), not a float product of bf16-rounded dz.
+//
+// With one wavefront per SIMD every instruction's latency is exposed (about 2 ns each), so the formats are chosen
+// to keep instruction counts low: an 8-byte unit holds values of ONE output for three ROWS (plus the tag), which
+// is how an MFMA accumulator lane holds them, so a producer stores straight from its accumulators - no staging,
+// no cross-lane moves.  Ring layout per direction and slot:
+//   [row group][destination tile][producer tile][32 outputs][2 row halves] x 16 bytes,
+//   16 bytes = unit A (rows 4g, 4g+1, 4g+2, tag) + unit B (row 4g+3, 0, 0, tag).
+// W_h slice in registers: w[kc][c] = B fragment of gate kc (K = this tile's 32 units) for column tile
+// wave*16 + c of the n outputs.
+constexpr int kPartBytes = 1024;                          // one (producer, destination tile)
+
+template <int NPW>                                        // producers per wavefront at most: n <= 128 * NPW
+__global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
+  __shared__ float red[4][8][33];
+  __shared__ __attribute__((aligned(16))) unsigned short zb[8][136];
+  const WgCoord wg = wg_coord();
+  const PBwdDir& d = a.d[wg.dir];
+  const int J = wg.tile, R = wg.rt, ntile2 = gridDim.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n = a.n, B = a.B, T = a.T;
+  unsigned* err = a.sync;
+  bool dead = false;
+
+  u32x4 w[4][16];                                        // all 256 accumulation registers
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+    for (int c = 0; c < 16; ++c) w[kc][c] = load_to_agpr(&d.Wb[((((long)J * 4 + wave) * 4 + kc) * 16 + c) * 64 + lane]);
+  agpr_loads_done();
+
+  const int r8 = tid >> 5, u = tid & 31;                 // pointwise pair of this thread
+  const int b = R * 8 + r8, j = J * 32 + u;
+  const bool active = b < B && j < n;
+  float Dh = 0.f, Dc = 0.f;
+  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};
+  int L = 0;
+  if (active) {
+    Dh = d.Dh[(long)b * n + j];
+    Dc = d.Dc[(long)b * n + j];
+    L = clamp_len(a.lens, b, T);
+  }
+  auto fetch_in = [&](int tau) {
+    BwdIn in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int t = d.rev ? T - 1 - tau : tau;
+    if (tau >= 0 && active && t < L) {
+      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
+      in.gi = gp[0]; in.gf = gp[n]; in.gg = gp[2 * n]; in.go = gp[3 * n];
+      in.c_new = d.cs[((long)t * B + b) * n + j];
+      const int tp = d.rev ? t + 1 : t - 1;
+      if (tp >= 0 && tp < T) in.c_prev = d.cs[((long)tp * B + b) * n + j];
+      else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
+      in.dy = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
+    }
+    return in;
+  };
+  BwdIn in = fetch_in(T - 1);
+
+  // consumer side: lane reads output lane/2, row half lane%2 of every producer's block
+  const int ccol = lane >> 1, cg = lane & 1;
+  const int nitv = (ntile2 + 3) / 4, rot = J % nitv;
+  const long ring_tile = ((long)R * ntile2 + J) * ntile2 * (kPartBytes / 16);     // uint4 index of [R][J][0]
+  // producer side: lanes 0..31 hold rows 4*(lane/16) .. +3 of output column lane%16 of each accumulator tile
+  const int pg = (lane >> 4) & 1, pcol = lane & 15;
+  const bool local = a.xcc != nullptr &&
+                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + R) * ntile2, ntile2, J, a.spin_limit);
+
+  PROF_DECL
+  for (int tau = T - 1; tau >= -1; --tau) {
+    PROF_MARK(4)
+    const int sigma = T - 1 - tau;
+    const int t = d.rev ? T - 1 - tau : tau;
+    const int t_next = d.rev ? t - 1 : t + 1;
+    const bool pointwise = tau >= 0;
+    const bool valid = pointwise && active && t < L;
+    BwdIn in_next = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    if (sigma > 0) {
+      RingReader rd;
+      rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + ring_tile), 0, ntile2 * kPartBytes,
+                                                kBufFlags);
+      rd.voff = (unsigned)(wave * kPartBytes + lane * 16);
+      rd.it_bytes = 4u * kPartBytes; rd.chunks_per_it = 4;
+      rd.lim = ntile2 - wave; rd.lim_step = 4;
+      rd.nkc = ntile2; rd.wave = wave; rd.tag = (unsigned)sigma & 0xffffu; rd.err = err; rd.limit = a.spin_limit;
+      rd.nitv = nitv; rd.rot = rot;
+      const unsigned np_ = rd.wait_sample(dead);
+      (void)np_;
+      PROF_POLLS(np_)
+      PROF_MARK(5)
+      float ps[4] = {0.f, 0.f, 0.f, 0.f};
+      {
+        auto use = [&](int, uint4 v) {                     // tags arrive masked off
+          ps[0] += __uint_as_float(v.x << 16); ps[1] += __uint_as_float(v.x & 0xffff0000u);
+          ps[2] += __uint_as_float(v.y << 16); ps[3] += __uint_as_float(v.z << 16);
+        };
+        const unsigned long long redo = rd.stream<NPW, NPW, true>(use);
+        PROF_POLLS(100 * __popcll(redo))
+        if (redo) rd.fix_up<NPW>(redo, dead, use);
+      }
+      in_next = fetch_in(tau - 1);
+      PROF_MARK(0)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave][4 * cg + v][ccol] = ps[v];
+      __syncthreads();
+      if (active && t_next < L) Dh = red[0][r8][u] + red[1][r8][u] + red[2][r8][u] + red[3][r8][u];
+    } else {
+      in_next = fetch_in(tau - 1);
+    }
+    if (pointwise) {
+      float dz[4] = {0.f, 0.f, 0.f, 0.f};
+      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, in.dy + Dh, Dc, dz);
+      unsigned short bits[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        dbsum[q] += dz[q];
+        bits[q] = f2bf_bits(dz[q]);
+        zb[r8][q * 32 + u] = bits[q];                      // inactive threads contribute zeros
+      }
+      __syncthreads();
+      PROF_MARK(2)
+      // partial sums of Dh for all n outputs: [16 rows (8 real, repeated), K = 128] x [128, 256 outputs of this wave],
+      // in four groups of four column tiles: while the MFMAs of one group run, the previous group's results are
+      // converted and stored.  One 16-byte store per accumulator tile: the 32 storing lanes of a wavefront cover 512
+      // consecutive bytes.  Each 8-byte half carries its own tag in its upper dword, so the only thing relied on
+      // beyond the 64-bit units of the other kernels is that an aligned 16-byte lane store is not split below 8 bytes.
+      const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(((sigma & 1) ? d.ring1 : d.ring0) + (long)R * ntile2 * ntile2 * (kPartBytes / 16)), 0, ntile2 * ntile2 * kPartBytes, kBufFlags);
+      const unsigned tag_hi = ((unsigned)(sigma + 1) & 0xffffu) << 16;
+      u32x4 av[4];
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 7][kc * 32 + (lane >> 4) * 8];
+      f32x4 acc[16];
+      auto multiply = [&](int g4) {
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) acc[g4 * 4 + cc] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) mfma_b_agpr(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
+      };
+      auto publish = [&](int g4) {
+        if (lane < 32) {
+          u32x4 val[4];
+          unsigned off[4];
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) {
+            const int c = g4 * 4 + cc;
+            const int Jd = wave * 8 + (c >> 1);            // destination tile; one past the last falls outside `ro`
+            off[cc] = (unsigned)(((Jd * ntile2 + J) * 32 + (c & 1) * 16 + pcol) * 2 + pg) * 16u;
+            const unsigned x = pack_bf16x2(acc[c][0], acc[c][1]), y = pack_bf16x2(acc[c][2], acc[c][3]);
+            val[cc] = (u32x4){x, (y & 0xffffu) | tag_hi, y >> 16, tag_hi};
+          }
+          if (local) {                                     // stays in this XCD's L2
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) __builtin_amdgcn_raw_buffer_store_b128(val[cc], ro, off[cc], 0, 0);
+          } else {                                         // sc1: agent scope, written through
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) __builtin_amdgcn_raw_buffer_store_b128(val[cc], ro, off[cc], 0, 16);
+          }
+        }
+      };
+      multiply(0);
+#pragma unroll
+      for (int g4 = 1; g4 < 4; ++g4) {
+        multiply(g4);
+        mfma_settle(acc[g4 * 4 - 4], acc[g4 * 4 - 3], acc[g4 * 4 - 2], acc[g4 * 4 - 1]);
+        publish(g4 - 1);
+      }
+      mfma_settle(acc[12], acc[13], acc[14], acc[15]);
+      publish(3);
+      PROF_MARK(1)
+      if (active) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits[q];
+      }
+      PROF_MARK(3)
+    }
+    in = in_next;
+  }
+  PROF_DUMP("bwdp", T)
+  if (active) {
+    d.Dh[(long)b * n + j] = Dh;
+    d.Dc[(long)b * n + j] = Dc;
+  }
+  if (d.dbpart) {                       // bias gradient: sum this work-group's 8 rows, one slice per row group
+    __shared__ float dbred[8][129];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dbred[r8][q * 32 + u] = dbsum[q];
+    __syncthreads();
+    if (tid < 128) {
+      const int q = tid >> 5, uu = tid & 31, jj = J * 32 + uu;
+      float sum = 0.f;
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) sum += dbred[rr][q * 32 + uu];
+      if (jj < n) d.dbpart[(long)R * 4 * n + q * n + jj] = sum;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // packing for the ring layout
 // forward weights: chunk index = (((dir*ntile + tile)*4 + q)*nkc + kc)*64 + lane
 __global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nkc, long total) {
@@ -845,6 +1109,24 @@ __global__ void pack_wh_bwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nk
   }
   out[idx] = *(uint4*)v;
 }
+// partial-sum backward kernel: chunk index = ((((dir*ntile2 + J)*4 + wave)*4 + kc)*16 + c)*64 + lane ; B fragment of
+// gate kc, K = the 32 units of tile J, columns = outputs (wave*16 + c)*16 .. +15
+__global__ void pack_wh_bwdp_kernel(const bf16_t* W, uint4* out, int n, int ntile2, long total) {
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = idx & 63, c = (idx >> 6) & 15, kc = (idx >> 10) & 3, wave = (idx >> 12) & 3;
+  const long rest = idx >> 14;
+  const int J = rest % ntile2, dir = rest / ntile2;
+  const int jout = (wave * 16 + c) * 16 + (lane & 15), g = lane >> 4;
+  const bf16_t* Wd = W + (long)dir * n * 4 * n;
+  bf16_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int unit = J * 32 + g * 8 + e;
+    v[e] = (jout < n && unit < n) ? Wd[(long)jout * 4 * n + kc * n + unit] : (bf16_t)0.f;
+  }
+  out[idx] = *(uint4*)v;
+}
 // initial state: unit index = ((((dir*nrt + rt)*nkc + kc)*64 + lane)*2 + half) ; ring0 gets h with tag 1, ring1 zeros
 __global__ void pack_state_ll_kernel(const float* h, uint4* ring0, uint4* ring1, int B, int n, int nkc, int nrt, long total) {
   long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -867,22 +1149,33 @@ __global__ void pack_state_ll_kernel(const float* h, uint4* ring0, uint4* ring1,
 }
 
 // Cooperative launch; refuses (without launching) a grid that cannot be resident all at once.
-template <typename K, typename A>
-hipError_t coop(K kernel, dim3 grid, const A& a, hipStream_t s) {
-  static int capacity = -1;             // work-groups of this kernel the current device can hold at once
-  if (capacity < 0) {
+template <typename K>
+bool fits_device(K kernel, dim3 grid) {
+  static std::mutex mu;
+  static std::map<const void*, int> cache;   // kernel -> work-groups of it the current device can hold at once
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = cache.find((const void*)kernel);
+  if (it == cache.end()) {
     int dev = 0, per_cu = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess)
-      return hipErrorUnknown;
-    capacity = per_cu * prop.multiProcessorCount;
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    it = cache.emplace((const void*)kernel, per_cu * prop.multiProcessorCount).first;
   }
-  if ((long)grid.x * grid.y * grid.z > capacity) return hipErrorCooperativeLaunchTooLarge;
+  return (long)grid.x * grid.y * grid.z <= it->second;
+}
+template <typename K, typename A>
+hipError_t coop(K kernel, dim3 grid, const A& a, hipStream_t s) {
+  if (!fits_device(kernel, grid)) return hipErrorCooperativeLaunchTooLarge;
   A copy = a;
   void* args[] = {&copy};
   return hipLaunchCooperativeKernel((const void*)kernel, grid, dim3(256), args, 0, s);
 }
+
+dim3 grid8(const PBwdArgs& a) { return dim3(cdiv(cdiv(a.n, 16), 2), 2 * cdiv(a.B, 16), a.ndir); }
 
 }  // namespace
 
@@ -894,13 +1187,26 @@ hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
   (void)hipGetLastError();
   return coop(persist_fwd_kernel<kLLMaxNkcFwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
 }
-hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s) {
-  if (a.nkc > kLLMaxNkcBwd) return hipErrorCooperativeLaunchTooLarge;
-  // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
-  hipError_t e = coop(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(cdiv(a.n, 16), 2), 2 * cdiv(a.B, 16), a.ndir), a, s);
-  if (e == hipSuccess) return e;
-  (void)hipGetLastError();
-  return coop(persist_bwd_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
+int persist_bwd_variant(const PBwdArgs& a) {
+  if (a.n <= 1024 && fits_device(persist_bwdp_kernel<8>, grid8(a))) return kBwdPartialSums;
+  if (a.nkc > kLLMaxNkcBwd) return kBwdNone;
+  if (fits_device(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, grid8(a))) return kBwdDz8;
+  if (fits_device(persist_bwd_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir))) return kBwdDz16;
+  return kBwdNone;
+}
+hipError_t launch_persist_bwd(const PBwdArgs& a, int variant, hipStream_t s) {
+  switch (variant) {
+    case kBwdPartialSums: return coop(persist_bwdp_kernel<8>, grid8(a), a, s);
+    case kBwdDz8: return coop(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, grid8(a), a, s);
+    case kBwdDz16: return coop(persist_bwd_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
+    default: return hipErrorCooperativeLaunchTooLarge;
+  }
+}
+hipError_t launch_pack_wh_bwdp(const void* W, uint4* Wb, int n, int ndir, hipStream_t s) {
+  const int ntile2 = cdiv(n, 32);
+  long total = (long)ndir * ntile2 * 4 * 4 * 16 * 64;
+  hipLaunchKernelGGL(pack_wh_bwdp_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wb, n, ntile2, total);
+  return hipGetLastError();
 }
 hipError_t launch_pack_wh_fwd_ll(const void* W, uint4* Wf, int n, int nkc, int ndir, hipStream_t s) {
   long total = (long)ndir * cdiv(n, 16) * 4 * nkc * 64;
