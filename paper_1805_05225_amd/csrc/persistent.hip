@@ -976,11 +976,11 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     if (pointwise) {
       float dz[4] = {0.f, 0.f, 0.f, 0.f};
       if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, in.dy + Dh, Dc, dz);
-      unsigned short bits[4];
+      const unsigned b01 = pack_bf16x2(dz[0], dz[1]), b23 = pack_bf16x2(dz[2], dz[3]);
+      const unsigned short bits[4] = {(unsigned short)b01, (unsigned short)(b01 >> 16), (unsigned short)b23, (unsigned short)(b23 >> 16)};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         dbsum[q] += dz[q];
-        bits[q] = f2bf_bits(dz[q]);
         zb[r8][q * 32 + u] = bits[q];                      // inactive threads contribute zeros
       }
       __syncthreads();
@@ -997,6 +997,9 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 7][kc * 32 + (lane >> 4) * 8];
       f32x4 acc[16];
+      // Four groups of four column tiles: the previous group's results are converted and stored after the next
+      // group's MFMAs have been issued.  (Placing the conversions and stores between the individual MFMAs was
+      // measured slower: the lane masks and branches around each store cost more than the overlap gains.)
       auto multiply = [&](int g4) {
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) acc[g4 * 4 + cc] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -1004,6 +1007,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         for (int kc = 0; kc < 4; ++kc)
 #pragma unroll
           for (int cc = 0; cc < 4; ++cc) mfma_b_agpr(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
+        mfma_settle(acc[g4 * 4], acc[g4 * 4 + 1], acc[g4 * 4 + 2], acc[g4 * 4 + 3]);
       };
       auto publish = [&](int g4) {
         if (lane < 32) {
@@ -1030,10 +1034,8 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
       for (int g4 = 1; g4 < 4; ++g4) {
         multiply(g4);
-        mfma_settle(acc[g4 * 4 - 4], acc[g4 * 4 - 3], acc[g4 * 4 - 2], acc[g4 * 4 - 1]);
         publish(g4 - 1);
       }
-      mfma_settle(acc[12], acc[13], acc[14], acc[15]);
       publish(3);
       PROF_MARK(1)
       if (active) {
