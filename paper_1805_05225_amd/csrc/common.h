@@ -145,6 +145,7 @@ __host__ __device__ inline int ll_slot_value(int w, int nvals) {
 
 struct PFwdDir {
   const uint4* Wf;    // [unit tile][gate][nkc][64] chunks
+  const uint4* Wzero; // one chunk (64 x 16 bytes) of zeros
   uint4* ring0; uint4* ring1;   // [row tile][nkc][64] chunks each
   float* gates;       // [T][B][4n]
   float* hstate; float* cstate;
@@ -158,6 +159,7 @@ struct PFwdArgs {
   const int* lens;
   int B, n, nkc, T, ndir, write_gates;
   unsigned* sync; unsigned spin_limit;
+  unsigned* xcc;      // NULL or one zeroed word per work-group (see PBwdArgs)
 };
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s);
 

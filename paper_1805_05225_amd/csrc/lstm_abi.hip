@@ -5,6 +5,7 @@
 #include "common.h"
 
 #include <string.h>
+#include <stdlib.h>
 #include <algorithm>
 #include <vector>
 
@@ -27,7 +28,7 @@ struct Plan {
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
       ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, workspace_bytes;
   bool fast_gemm; int n_in_pad; long TBp;   // bf16 products through the k-contiguous kernel (operands transposed once)
-  size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems;
+  size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems, Wf_bytes;
 };
 
 int make_plan(const lstm_desc* d, int bidir, Plan* p) {
@@ -61,7 +62,8 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   // error word, per-row-tile words, then one word per work-group of a single-launch kernel (its XCD)
   p->sync_bytes = up((64 + 2 * (size_t)p->nrt) * 4 + D * 2 * (size_t)p->nrt * cdiv(d->n, 32) * 4);
   p->ws_sync = take(p->sync_bytes);              // first, so that lstm_sync_status() finds it without a plan
-  p->ws_Wf = take(D * std::max((size_t)p->ntile_f * 2 * p->nkc_f, (size_t)p->ntile16 * 4 * p->nkc_ll_f) * 1024);
+  p->Wf_bytes = D * std::max((size_t)p->ntile_f * 2 * p->nkc_f, (size_t)p->ntile16 * 4 * p->nkc_ll_f) * 1024;
+  p->ws_Wf = take(p->Wf_bytes + 1024);            // packed W_h, then one chunk of zeros
   const bool part = p->bf16 && d->n <= 1024;          // the partial-sum backward kernel may be chosen
   p->ws_Wb = take(infer ? 0 : D * std::max(std::max((size_t)p->ntile_b * p->nkc_b, (size_t)p->ntile16 * p->nkc_ll_b) * 1024,
                                            part ? bwdp_wh_bytes(d->n) : (size_t)0));
@@ -176,6 +178,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     Phase ph(LSTM_PHASE_PREP, 2, s);
     if (ll) {
       HIPCHK(launch_pack_wh_fwd_ll(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_ll_f, p.D, s));
+      HIPCHK(launch_fill_zero(ws + p.ws_Wf + p.Wf_bytes, 1024, s));
       HIPCHK(launch_pack_state_ll(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_ll_f, p.nrt,
                                   p.D, s));
     } else {
@@ -228,10 +231,12 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       PFwdArgs pa = {};
       pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_f; pa.T = p.T; pa.ndir = p.D; pa.write_gates = infer ? 0 : 1;
       pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
+      pa.xcc = (unsigned*)(ws + p.ws_sync) + 64 + 2 * (size_t)p.nrt;
       const size_t frag_dir = (size_t)p.nrt * p.nkc_ll_f * 1024;
       for (size_t d = 0; d < D; ++d) {
         PFwdDir& fd = pa.d[d];
         fd.Wf = (const uint4*)(ws + p.ws_Wf + d * (size_t)p.ntile16 * 4 * p.nkc_ll_f * 1024);
+        fd.Wzero = (const uint4*)(ws + p.ws_Wf + p.Wf_bytes);
         fd.ring0 = (uint4*)(ws + p.ws_hfrag0 + d * frag_dir);
         fd.ring1 = (uint4*)(ws + p.ws_hfrag1 + d * frag_dir);
         fd.gates = gates + d * gates_stride;

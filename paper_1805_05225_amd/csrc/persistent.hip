@@ -129,6 +129,9 @@ struct RingReader {
     if (PIN) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < NIT; ++i) {
+      // PIN: each load is waited for, checked and consumed in turn (otherwise the compiler gathers the waits and
+      // checks of all loads in front of consumers it cannot see into, and nothing overlaps the later loads)
+      if (PIN) __builtin_amdgcn_sched_barrier(0);
       const u32x4 v = x[i % W];
       if (i + W < NIT) x[i % W] = load_it(it_of(i + W));
       const bool stale = __builtin_amdgcn_ballot_w64(stale_bits(v, it_of(i)) != 0u) != 0ull;
@@ -230,6 +233,22 @@ __device__ __forceinline__ void agpr_loads_done() { asm volatile("s_waitcnt vmcn
 __device__ __forceinline__ void mfma_b_agpr(f32x4& acc, const u32x4& a, const u32x4& b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
 }
+__device__ __forceinline__ void mfma_b_vgpr(f32x4& acc, const u32x4& a, const u32x4& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+// Wait states between the last ordinary (vector ALU, DPP, LDS) write of registers and an MFMA reading them.  For
+// MFMAs it emits itself the compiler knows what the hardware needs; for these it cannot, and an MFMA issued right
+// behind DPP moves was observed to read the old register contents.
+#ifndef LSTM_OPERAND_NOPS
+#define LSTM_OPERAND_NOPS "7"
+#endif
+__device__ __forceinline__ void operands_settle(u32x4& a, u32x4& b) { asm volatile("s_nop " LSTM_OPERAND_NOPS : "+v"(a), "+v"(b)); }
+__device__ __forceinline__ void operands_settle(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
+  asm volatile("s_nop " LSTM_OPERAND_NOPS : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+__device__ __forceinline__ void operands_settle(f32x4& a, f32x4& b, f32x4& c, f32x4& d) {
+  asm volatile("s_nop " LSTM_OPERAND_NOPS : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
 // 20 wait states: more than any MFMA of this shape needs before its result may be read or overwritten
 __device__ __forceinline__ void mfma_settle(f32x4& a0, f32x4& a1, f32x4& a2, f32x4& a3) {
   asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3));
@@ -265,6 +284,11 @@ __device__ __forceinline__ bool group_is_xcd_local(unsigned* tab, int group_base
 __device__ __forceinline__ void store_unit(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
   const unsigned long long u = (unsigned long long)(v0 | (v1 << 16)) | ((unsigned long long)(v2 | (tag << 16)) << 32);
   __hip_atomic_store((unsigned long long*)ring + unit_index, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// the same unit for a group whose members share an XCD: a store that stays in that XCD's L2
+__device__ __forceinline__ void store_unit_local(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
+  const unsigned long long u = (unsigned long long)(v0 | (v1 << 16)) | ((unsigned long long)(v2 | (tag << 16)) << 32);
+  __hip_atomic_store((unsigned long long*)ring + unit_index, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // Work-group -> (unit tile, row tile, direction).  Work-groups are dealt to the 8 XCDs round-robin in launch
@@ -426,7 +450,12 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   bool dead = false;
 
   const int nitv = (nkc + 7) / 8, rot = tile2 % nitv;
-  uint4 w[NIT][2][4];                    // register sets 2p, 2p+1 hold the two chunks that load p of the stream fetches
+  // Register sets 2p, 2p+1 hold the two chunks that load p of the stream fetches.  The first kAccIts sets fill the
+  // 256 accumulation registers, the rest sit in vector registers.  Sets of chunks past the end (or of a unit tile
+  // past the end) are loaded from a chunk of zeros that the host keeps behind the packed weights.
+  constexpr int kAccIts = NIT < 8 ? NIT : 8;
+  u32x4 wa[kAccIts][2][4];
+  u32x4 wv[NIT - kAccIts > 0 ? NIT - kAccIts : 1][2][4];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int kc = wave + 4 * (2 * rot_index(it >> 1, rot, nitv) + (it & 1));
@@ -434,10 +463,14 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     for (int ct = 0; ct < 2; ++ct) {
       const int t16 = tile2 * 2 + ct;
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        w[it][ct][q] = (kc < nkc && t16 < ntiles16) ? d.Wf[((long)(t16 * 4 + q) * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
+      for (int q = 0; q < 4; ++q) {
+        const uint4* src = (kc < nkc && t16 < ntiles16) ? &d.Wf[((long)(t16 * 4 + q) * nkc + kc) * 64 + lane] : &d.Wzero[lane];
+        if (it < kAccIts) wa[it][ct][q] = load_to_agpr(src);
+        else wv[it - kAccIts][ct][q] = *(const u32x4*)src;
+      }
     }
   }
+  agpr_loads_done();
 
   const int r8 = tid >> 5, u = tid & 31;                 // pointwise pair of this thread: row r8 of the half, unit u of 32
   const int b = rt * 16 + half * 8 + r8, j = tile2 * 32 + u;
@@ -456,6 +489,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   const int cch = t16p * 3 + (m >> 1);
   const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + half * 8 + rr) * 2 + (m & 1);
   const bool publishes = tid < 96 && t16p < ntiles16;
+  const bool local = a.xcc != nullptr &&
+                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * (int)gridDim.x, gridDim.x, tile2, a.spin_limit);
 
   float zx[4] = {0.f, 0.f, 0.f, 0.f}, zx_next[4] = {0.f, 0.f, 0.f, 0.f};
   auto fetch_zx = [&](int tau, float (&z)[4]) {
@@ -483,21 +518,51 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
       for (int q = 0; q < 4; ++q) acc[ct][q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    operands_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+    operands_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     {
-      auto use = [&](int p, uint4 av) {
-        const uint4 av2 = rotate_rows_by_8(av);
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) acc[ct][q] = Mma16<bf16_t>::run(av, w[2 * p][ct][q], acc[ct][q]);
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) acc[ct][q] = Mma16<bf16_t>::run(av2, w[2 * p + 1][ct][q], acc[ct][q]);
+      // One MFMA of register set `it` into accumulator (ct, q).
+      auto mma_one = [&](int it, int ct, int q, const u32x4& a_op) {
+        if (it < kAccIts) mfma_b_agpr(acc[ct][q], a_op, wa[it < kAccIts ? it : 0][ct][q]);
+        else mfma_b_vgpr(acc[ct][q], a_op, wv[it >= kAccIts ? it - kAccIts : 0][ct][q]);
       };
-      const unsigned long long redo = rd.stream<NIT / 2, NIT / 2, true>(use);
+      // Consecutive MFMAs into the SAME accumulator issue every 16 cycles; switching accumulators costs as much
+      // again (measured: 7.7 ns chained, 18.8 ns when 8 accumulators take turns).  So the stream hands its loads
+      // over in pairs: four chunks, and every accumulator takes its four products in a row.
+      u32x4 held[2];                                       // operands of the even load of a pair
+      auto use_pair = [&](int p, uint4 av_) {
+        const uint4 av2_ = rotate_rows_by_8(av_);
+        u32x4 av = {av_.x, av_.y, av_.z, av_.w}, av2 = {av2_.x, av2_.y, av2_.z, av2_.w};
+        if ((p & 1) == 0) { held[0] = av; held[1] = av2; return; }
+        operands_settle(held[0], held[1], av, av2);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            mma_one(2 * p - 2, ct, q, held[0]);
+            mma_one(2 * p - 1, ct, q, held[1]);
+            mma_one(2 * p, ct, q, av);
+            mma_one(2 * p + 1, ct, q, av2);
+          }
+      };
+      auto use_single = [&](int p, uint4 av_) {            // a load fetched again after the stream
+        const uint4 av2_ = rotate_rows_by_8(av_);
+        u32x4 av = {av_.x, av_.y, av_.z, av_.w}, av2 = {av2_.x, av2_.y, av2_.z, av2_.w};
+        operands_settle(av, av2);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            mma_one(2 * p, ct, q, av);
+            mma_one(2 * p + 1, ct, q, av2);
+          }
+      };
+      static_assert((NIT / 2) % 2 == 0, "loads are consumed in pairs");
+      const unsigned long long redo = rd.stream<NIT / 2, NIT / 2, true>(use_pair);
       PROF_POLLS(100 * __popcll(redo))
-      if (redo) rd.fix_up<NIT / 2>(redo, dead, use);
+      if (redo) rd.fix_up<NIT / 2>(redo, dead, use_single);
+      mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+      mfma_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     }
     fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
     PROF_MARK(0)
@@ -528,7 +593,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     if (publishes) {                  // the recurrence's critical store goes out first
       const int v0 = 3 * m;
       const unsigned x0 = hb[rr][pp][v0], x1 = v0 + 1 < 16 ? hb[rr][pp][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[rr][pp][v0 + 2] : 0u;
-      store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
+      if (local) store_unit_local(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
+      else store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
     }
     if (active) {                     // layer outputs and what the backward pass needs
       Store<bf16_t>::store(d.y, ((long)t * B + b) * d.ldy + j, valid ? h : 0.f);
@@ -996,6 +1062,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       u32x4 av[4];
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 7][kc * 32 + (lane >> 4) * 8];
+      operands_settle(av[0], av[1], av[2], av[3]);
       f32x4 acc[16];
       // Four groups of four column tiles: the previous group's results are converted and stored after the next
       // group's MFMAs have been issued.  (Placing the conversions and stores between the individual MFMAs was
@@ -1003,10 +1070,13 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       auto multiply = [&](int g4) {
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) acc[g4 * 4 + cc] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        operands_settle(acc[g4 * 4], acc[g4 * 4 + 1], acc[g4 * 4 + 2], acc[g4 * 4 + 3]);
+        // consecutive MFMAs into the SAME accumulator issue every 16 cycles; switching accumulators costs as much
+        // again (measured: 7.7 ns chained, 18.8 ns when 8 accumulators take turns), so the k loop is the inner one
 #pragma unroll
-        for (int kc = 0; kc < 4; ++kc)
+        for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
-          for (int cc = 0; cc < 4; ++cc) mfma_b_agpr(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
+          for (int kc = 0; kc < 4; ++kc) mfma_b_agpr(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
         mfma_settle(acc[g4 * 4], acc[g4 * 4 + 1], acc[g4 * 4 + 2], acc[g4 * 4 + 3]);
       };
       auto publish = [&](int g4) {
