@@ -24,6 +24,11 @@ constexpr int kKB = 64;                   // k per stage (bf16 elements)
 constexpr int kStride = 144;              // LDS row stride in bytes
 constexpr int kOpBytes = kT * kStride;    // one operand, one stage
 constexpr int kThreads = 256;
+#ifndef GEMM_SUPM
+#define GEMM_SUPM 8
+#define GEMM_SUPN 4
+#endif
+constexpr int kSupM = GEMM_SUPM, kSupN = GEMM_SUPN;   // tiles per XCD-resident block (kSupM * kSupN = 32 CUs)
 
 struct NtArgs {
   const char* A; const char* B; void* C; const float* bias;
@@ -97,10 +102,23 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
   const int K = g.k_dev ? min(g.K, *g.k_dev) : g.K;
   const int tiles_m = (g.M + kT - 1) / kT, tiles_n = (g.N + kT - 1) / kT;
   const int bid = blockIdx.x;
+#ifdef GEMM_OLD_RASTER
   const int band = bid / (8 * tiles_m);
   const int width = min(8, tiles_n - band * 8);
   const int rel = bid - band * 8 * tiles_m;
   const int tn = band * 8 + rel % width, tm = rel / width;
+#else
+  // Work-groups are dealt to the eight XCDs round-robin, so blockIdx & 7 is the XCD and blockIdx >> 3 counts the
+  // work-groups of that XCD in launch order.  The 32 work-groups an XCD runs at a time form a block of
+  // kSupM x kSupN tiles: kSupM + kSupN operand panels feed kSupM * kSupN tiles out of that XCD's L2.
+  const int sup_m = (tiles_m + kSupM - 1) / kSupM, sup_n = (tiles_n + kSupN - 1) / kSupN;
+  const int xcd = bid & 7, slot = bid >> 3;
+  const int sup = (slot / (kSupM * kSupN)) * 8 + xcd, pos = slot % (kSupM * kSupN);
+  if (sup >= sup_m * sup_n) return;
+  const int sn = sup % sup_n, sm = sup / sup_n;
+  const int tm = sm * kSupM + pos / kSupN, tn = sn * kSupN + pos % kSupN;
+  if (tm >= tiles_m || tn >= tiles_n) return;
+#endif
   const int m0 = tm * kT, n0 = tn * kT;
   if (m0 >= M) return;
   const int ksplit = g.ksplit > 1 ? g.ksplit : 1;
@@ -170,14 +188,20 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
       if (s < 3) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+#ifdef GEMM_NO_LDSREAD
+          fa[c ^ 1][i] = fa[c][i]; fb[c ^ 1][i] = fb[c][i];
+#else
           fa[c ^ 1][i] = *(const uint4*)(As + i * 32 * kStride + (s + 1) * 32);
           fb[c ^ 1][i] = *(const uint4*)(Bs + i * 32 * kStride + (s + 1) * 32);
+#endif
         }
       }
+#ifndef GEMM_NO_COMMIT
       if (it + 1 < total) {
         if (s == 0) commit(sa, nxt, tid);
         if (s == 1) commit(sb, nxt + kOpBytes, tid);
       }
+#endif
       if (it + 2 < total) {
         if (s == 2) fetch_a(it + 2);
         if (s == 3) fetch_b(it + 2);
@@ -186,7 +210,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
+        for (int j = 0; j < 4; ++j) {
+#ifdef GEMM_NO_MFMA
+          acc[i][j][0] += __uint_as_float((fa[c][i].x ^ fb[c][j].x) & 0x3fffffffu);
+#else
+          acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
+#endif
+        }
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
@@ -446,7 +476,12 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   a.nseg = g.nseg; a.sAseg = g.sAseg; a.sBseg = g.sBseg; a.accumulate = g.accumulate;
   a.a_rows = g.a_rows; a.c_rows = g.c_rows; a.m_dev = g.m_dev; a.k_dev = g.k_dev; a.a_phys_rows = g.a_phys_rows;
   a.ksplit = (g.ksplit > 1 && !g.out_bf16 && g.nseg == 1) ? g.ksplit : 1;
+#ifdef GEMM_OLD_RASTER
   const int tiles = cdiv(g.M, kT) * cdiv(g.N, kT);
+#else
+  const int sups = cdiv(cdiv(g.M, kT), kSupM) * cdiv(cdiv(g.N, kT), kSupN);
+  const int tiles = cdiv(sups, 8) * 8 * kSupM * kSupN;      // whole blocks, a multiple of 8 of them
+#endif
   const size_t shmem = 4 * kOpBytes;
   static bool attr_set = false;
   if (!attr_set) {
