@@ -15,6 +15,7 @@
 // Per 16-wide k step a wavefront issues 8 LDS reads for 16 MFMAs, half the LDS bandwidth a 128x128
 // work-group tile would need.
 #include "common.h"
+#include <algorithm>
 
 namespace lstm {
 namespace {
@@ -24,11 +25,7 @@ constexpr int kKB = 64;                   // k per stage (bf16 elements)
 constexpr int kStride = 144;              // LDS row stride in bytes
 constexpr int kOpBytes = kT * kStride;    // one operand, one stage
 constexpr int kThreads = 256;
-#ifndef GEMM_SUPM
-#define GEMM_SUPM 8
-#define GEMM_SUPN 4
-#endif
-constexpr int kSupM = GEMM_SUPM, kSupN = GEMM_SUPN;   // tiles per XCD-resident block (kSupM * kSupN = 32 CUs)
+constexpr int kSupM = 8, kSupN = 4;   // tiles per XCD-resident block (kSupM * kSupN = 32 CUs)
 
 struct NtArgs {
   const char* A; const char* B; void* C; const float* bias;
@@ -41,6 +38,7 @@ struct NtArgs {
   const int* m_dev; const int* k_dev;     // device-resident M / K (NULL: use M / K above)
   int a_phys_rows;                        // rows of A in memory when a_rows is given
   int ksplit;                             // > 1: K is cut into that many ranges, each adds its part to C atomically
+  int blocked;                            // tile raster: 1 = blocks of kSupM x kSupN tiles per XCD, 0 = bands of 8 tile columns
 };
 
 __device__ __forceinline__ f32x16 mma(uint4 a, uint4 b, f32x16 c) {
@@ -89,139 +87,49 @@ __device__ __forceinline__ void commit(const uint4 (&st)[8], char* lds, int tid)
   }
 }
 
+// What every kernel variant needs to know about its tile.
+struct TileCoord { int M, K, m0, n0, z, ks, ksplit; bool live; };
+__device__ __forceinline__ TileCoord tile_coord(const NtArgs& g) {
+  TileCoord t;
+  t.live = false;
+  t.M = g.m_dev ? min(g.M, *g.m_dev) : g.M;        // the grid is sized for g.M; surplus tiles leave at once
+  t.K = g.k_dev ? min(g.K, *g.k_dev) : g.K;
+  const int tiles_m = (g.M + kT - 1) / kT, tiles_n = (g.N + kT - 1) / kT;
+  const int bid = blockIdx.x;
+  int tm, tn;
+  if (g.blocked) {
+    // Work-groups are dealt to the eight XCDs round-robin, so blockIdx & 7 is the XCD and blockIdx >> 3 counts the
+    // work-groups of that XCD in launch order.  The 32 work-groups an XCD runs at a time form a block of
+    // kSupM x kSupN tiles: kSupM + kSupN operand panels feed kSupM * kSupN tiles out of that XCD's L2.
+    const int sup_m = (tiles_m + kSupM - 1) / kSupM, sup_n = (tiles_n + kSupN - 1) / kSupN;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int sup = (slot / (kSupM * kSupN)) * 8 + xcd, pos = slot % (kSupM * kSupN);
+    if (sup >= sup_m * sup_n) return t;
+    const int sn = sup % sup_n, sm = sup / sup_n;
+    tm = sm * kSupM + pos / kSupN; tn = sn * kSupN + pos % kSupN;
+    if (tm >= tiles_m || tn >= tiles_n) return t;
+  } else {
+    // few tiles: bands of 8 tile columns, row-major inside a band; every XCD keeps one B tile column in its L2
+    const int band = bid / (8 * tiles_m);
+    const int width = min(8, tiles_n - band * 8);
+    const int rel = bid - band * 8 * tiles_m;
+    tn = band * 8 + rel % width; tm = rel / width;
+  }
+  t.m0 = tm * kT; t.n0 = tn * kT;
+  if (t.m0 >= t.M) return t;
+  t.ksplit = g.ksplit > 1 ? g.ksplit : 1;
+  t.z = blockIdx.y / t.ksplit; t.ks = blockIdx.y - t.z * t.ksplit;
+  t.live = true;
+  return t;
+}
+
+// Writes a work-group's 256x256 accumulator tile (2x2 wavefronts of 4x4 MFMA blocks) to C.
 template <typename TC>
-__global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];   // [stage][A | B]
+__device__ __forceinline__ void store_tile(f32x16 (&acc)[4][4], char* lds, const NtArgs& g, int M, int m0, int n0, int z, int ks,
+                                           int ksplit) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const int r = lane & 31, gq = lane >> 5;
-
-  // tile raster: bands of 8 tile-columns, row-major inside a band: the eight XCDs (work-groups are dealt to
-  // them round-robin) each keep one B tile-column in their L2 while the A tiles stream through
-  const int M = g.m_dev ? min(g.M, *g.m_dev) : g.M;        // the grid is sized for g.M; surplus tiles leave at once
-  const int K = g.k_dev ? min(g.K, *g.k_dev) : g.K;
-  const int tiles_m = (g.M + kT - 1) / kT, tiles_n = (g.N + kT - 1) / kT;
-  const int bid = blockIdx.x;
-#ifdef GEMM_OLD_RASTER
-  const int band = bid / (8 * tiles_m);
-  const int width = min(8, tiles_n - band * 8);
-  const int rel = bid - band * 8 * tiles_m;
-  const int tn = band * 8 + rel % width, tm = rel / width;
-#else
-  // Work-groups are dealt to the eight XCDs round-robin, so blockIdx & 7 is the XCD and blockIdx >> 3 counts the
-  // work-groups of that XCD in launch order.  The 32 work-groups an XCD runs at a time form a block of
-  // kSupM x kSupN tiles: kSupM + kSupN operand panels feed kSupM * kSupN tiles out of that XCD's L2.
-  const int sup_m = (tiles_m + kSupM - 1) / kSupM, sup_n = (tiles_n + kSupN - 1) / kSupN;
-  const int xcd = bid & 7, slot = bid >> 3;
-  const int sup = (slot / (kSupM * kSupN)) * 8 + xcd, pos = slot % (kSupM * kSupN);
-  if (sup >= sup_m * sup_n) return;
-  const int sn = sup % sup_n, sm = sup / sup_n;
-  const int tm = sm * kSupM + pos / kSupN, tn = sn * kSupN + pos % kSupN;
-  if (tm >= tiles_m || tn >= tiles_n) return;
-#endif
-  const int m0 = tm * kT, n0 = tn * kT;
-  if (m0 >= M) return;
-  const int ksplit = g.ksplit > 1 ? g.ksplit : 1;
-  const int z = blockIdx.y / ksplit, ks = blockIdx.y - z * ksplit;
-
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const int ktiles = (K + kKB - 1) / kKB;
-  const bool ktail = (K % kKB) != 0;
-  const int nstage = ktiles * g.nseg;
-  // stages [it0, it0 + total) belong to this work-group (all of them unless K is split)
-  const int it0 = (int)((long)nstage * ks / ksplit);
-  const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
-  OperandLoader la, lb;
-  int seg_loaded = -1;
-  uint4 sa[8], sb[8];
-  // stage `it`: segment it / ktiles, k offset (it % ktiles) * 64
-  auto fetch_a = [&](int rel_it) {
-    const int it = it0 + rel_it;
-    const int seg = it / ktiles, kt = it - seg * ktiles;
-    if (seg != seg_loaded) {
-      la.init(g.A + (g.sAz * z + g.sAseg * seg) * 2, g.lda, M, m0, tid, g.a_rows, g.a_phys_rows);
-      lb.init(g.B + (g.sBz * z + g.sBseg * seg) * 2, g.ldb, g.N, n0, tid);
-      seg_loaded = seg;
-    }
-    if (ktail && kt == ktiles - 1) la.fetch<true>(sa, kt * kKB, K); else la.fetch<false>(sa, kt * kKB, K);
-  };
-  auto fetch_b = [&](int rel_it) {
-    const int it = it0 + rel_it;
-    const int seg = it / ktiles, kt = it - seg * ktiles;
-    if (ktail && kt == ktiles - 1) lb.fetch<true>(sb, kt * kKB, K); else lb.fetch<false>(sb, kt * kKB, K);
-  };
-  // prologue: stage 0 into LDS buffer 0, stage 1 into registers
-  if (total > 0) {
-    fetch_a(0); fetch_b(0);
-    commit(sa, lds, tid);
-    commit(sb, lds + kOpBytes, tid);
-    if (total > 1) { fetch_a(1); fetch_b(1); }
-  }
-  __syncthreads();
-
-  // Main loop.  While stage `it` is multiplied out of LDS buffer it&1: the registers holding stage it+1 are
-  // written to the other buffer (k-steps 0-1), then the loads of stage it+2 are issued (k-steps 2-3), so every
-  // global load has a whole stage of MFMAs to complete.  Fragments for k-step s+1 are read from LDS while
-  // the 16 MFMAs of step s run; the scheduling barriers keep the compiler from collapsing that overlap.
-  // (Moving the barrier to mid-stage and pre-reading the next stage's first fragments measured slower.)
-  for (int it = 0; it < total; ++it) {
-    const int cur = it & 1;
-    const char* As = lds + cur * 2 * kOpBytes + (wm * 128 + r) * kStride + gq * 16;
-    const char* Bs = lds + cur * 2 * kOpBytes + kOpBytes + (wn * 128 + r) * kStride + gq * 16;
-    char* nxt = lds + (cur ^ 1) * 2 * kOpBytes;
-    uint4 fa[2][4], fb[2][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      fa[0][i] = *(const uint4*)(As + i * 32 * kStride);
-      fb[0][i] = *(const uint4*)(Bs + i * 32 * kStride);
-    }
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int c = s & 1;
-      if (s < 3) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-#ifdef GEMM_NO_LDSREAD
-          fa[c ^ 1][i] = fa[c][i]; fb[c ^ 1][i] = fb[c][i];
-#else
-          fa[c ^ 1][i] = *(const uint4*)(As + i * 32 * kStride + (s + 1) * 32);
-          fb[c ^ 1][i] = *(const uint4*)(Bs + i * 32 * kStride + (s + 1) * 32);
-#endif
-        }
-      }
-#ifndef GEMM_NO_COMMIT
-      if (it + 1 < total) {
-        if (s == 0) commit(sa, nxt, tid);
-        if (s == 1) commit(sb, nxt + kOpBytes, tid);
-      }
-#endif
-      if (it + 2 < total) {
-        if (s == 2) fetch_a(it + 2);
-        if (s == 3) fetch_b(it + 2);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#ifdef GEMM_NO_MFMA
-          acc[i][j][0] += __uint_as_float((fa[c][i].x ^ fb[c][j].x) & 0x3fffffffu);
-#else
-          acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
-#endif
-        }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    __syncthreads();
-  }
-
   // Epilogue.  A lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 block: stored as
   // it is that would be 128-byte pieces, eight of them per row at different times.  The tile goes through LDS
   // instead (two halves of 128 rows, the main loop's buffers are free by now) and leaves as whole rows: one
@@ -293,6 +201,108 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
       }
     }
   }
+}
+
+template <typename TC>
+__global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // [stage][A | B]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r = lane & 31, gq = lane >> 5;
+
+  const TileCoord tc = tile_coord(g);
+  if (!tc.live) return;
+  const int M = tc.M, K = tc.K, m0 = tc.m0, n0 = tc.n0, z = tc.z, ks = tc.ks, ksplit = tc.ksplit;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int ktiles = (K + kKB - 1) / kKB;
+  const bool ktail = (K % kKB) != 0;
+  const int nstage = ktiles * g.nseg;
+  // stages [it0, it0 + total) belong to this work-group (all of them unless K is split)
+  const int it0 = (int)((long)nstage * ks / ksplit);
+  const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
+  OperandLoader la, lb;
+  int seg_loaded = -1;
+  uint4 sa[8], sb[8];
+  // stage `it`: segment it / ktiles, k offset (it % ktiles) * 64
+  auto fetch_a = [&](int rel_it) {
+    const int it = it0 + rel_it;
+    const int seg = it / ktiles, kt = it - seg * ktiles;
+    if (seg != seg_loaded) {
+      la.init(g.A + (g.sAz * z + g.sAseg * seg) * 2, g.lda, M, m0, tid, g.a_rows, g.a_phys_rows);
+      lb.init(g.B + (g.sBz * z + g.sBseg * seg) * 2, g.ldb, g.N, n0, tid);
+      seg_loaded = seg;
+    }
+    if (ktail && kt == ktiles - 1) la.fetch<true>(sa, kt * kKB, K); else la.fetch<false>(sa, kt * kKB, K);
+  };
+  auto fetch_b = [&](int rel_it) {
+    const int it = it0 + rel_it;
+    const int seg = it / ktiles, kt = it - seg * ktiles;
+    if (ktail && kt == ktiles - 1) lb.fetch<true>(sb, kt * kKB, K); else lb.fetch<false>(sb, kt * kKB, K);
+  };
+  // prologue: stage 0 into LDS buffer 0, stage 1 into registers
+  if (total > 0) {
+    fetch_a(0); fetch_b(0);
+    commit(sa, lds, tid);
+    commit(sb, lds + kOpBytes, tid);
+    if (total > 1) { fetch_a(1); fetch_b(1); }
+  }
+  __syncthreads();
+
+  // Main loop.  While stage `it` is multiplied out of LDS buffer it&1: the registers holding stage it+1 are
+  // written to the other buffer (k-steps 0-1), then the loads of stage it+2 are issued (k-steps 2-3), so every
+  // global load has a whole stage of MFMAs to complete.  Fragments for k-step s+1 are read from LDS while
+  // the 16 MFMAs of step s run; the scheduling barriers keep the compiler from collapsing that overlap.
+  // (Moving the barrier to mid-stage and pre-reading the next stage's first fragments measured slower.)
+  for (int it = 0; it < total; ++it) {
+    const int cur = it & 1;
+    const char* As = lds + cur * 2 * kOpBytes + (wm * 128 + r) * kStride + gq * 16;
+    const char* Bs = lds + cur * 2 * kOpBytes + kOpBytes + (wn * 128 + r) * kStride + gq * 16;
+    char* nxt = lds + (cur ^ 1) * 2 * kOpBytes;
+    uint4 fa[2][4], fb[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      fa[0][i] = *(const uint4*)(As + i * 32 * kStride);
+      fb[0][i] = *(const uint4*)(Bs + i * 32 * kStride);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int c = s & 1;
+      if (s < 3) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          fa[c ^ 1][i] = *(const uint4*)(As + i * 32 * kStride + (s + 1) * 32);
+          fb[c ^ 1][i] = *(const uint4*)(Bs + i * 32 * kStride + (s + 1) * 32);
+        }
+      }
+      if (it + 1 < total) {
+        if (s == 0) commit(sa, nxt, tid);
+        if (s == 1) commit(sb, nxt + kOpBytes, tid);
+      }
+      if (it + 2 < total) {
+        if (s == 2) fetch_a(it + 2);
+        if (s == 3) fetch_b(it + 2);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+  }
+
+  store_tile<TC>(acc, lds, g, M, m0, n0, z, ks, ksplit);
 }
 
 // dst[c][r] = keep(r) ? src[r][c] : 0 for r < R, c < C ; dst rows are padded with zeros up to ldd.
@@ -476,12 +486,10 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   a.nseg = g.nseg; a.sAseg = g.sAseg; a.sBseg = g.sBseg; a.accumulate = g.accumulate;
   a.a_rows = g.a_rows; a.c_rows = g.c_rows; a.m_dev = g.m_dev; a.k_dev = g.k_dev; a.a_phys_rows = g.a_phys_rows;
   a.ksplit = (g.ksplit > 1 && !g.out_bf16 && g.nseg == 1) ? g.ksplit : 1;
-#ifdef GEMM_OLD_RASTER
-  const int tiles = cdiv(g.M, kT) * cdiv(g.N, kT);
-#else
+  // the blocked raster pays when every XCD gets several blocks; with few tiles it would leave XCDs idle
   const int sups = cdiv(cdiv(g.M, kT), kSupM) * cdiv(cdiv(g.N, kT), kSupN);
-  const int tiles = cdiv(sups, 8) * 8 * kSupM * kSupN;      // whole blocks, a multiple of 8 of them
-#endif
+  a.blocked = sups >= 32 ? 1 : 0;
+  const int tiles = a.blocked ? cdiv(sups, 8) * 8 * kSupM * kSupN : cdiv(g.M, kT) * cdiv(g.N, kT);
   const size_t shmem = 4 * kOpBytes;
   static bool attr_set = false;
   if (!attr_set) {
