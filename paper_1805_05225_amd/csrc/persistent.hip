@@ -216,6 +216,13 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
   const bf16x2_ r = __builtin_convertvector((f32x2_){lo, hi}, bf16x2_);
   return __builtin_bit_cast(unsigned, r);
 }
+// Streaming accesses of the recurrent kernels (every byte touched once): marked non-temporal so that they do not
+// push the exchange ring, which is re-read every step, out of the L2.
+__device__ __forceinline__ float ld_stream(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ unsigned short ld_stream(const unsigned short* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void st_stream(unsigned short* p, unsigned short v) { __builtin_nontemporal_store(v, p); }
+
 // --- W_h in accumulation registers ---------------------------------------------------------------------------
 // The register file of a wavefront is 256 architectural + 256 accumulation registers.  A W_h slice larger than
 // what is left of the first 256 is parked by the compiler in accumulation registers and copied back, four moves
@@ -497,7 +504,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     const int t = d.rev ? T - 1 - tau : tau;
     if (tau < T && active && t < L) {
       const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-      z[0] = gp[0]; z[1] = gp[n]; z[2] = gp[2 * n]; z[3] = gp[3 * n];
+      z[0] = ld_stream(gp); z[1] = ld_stream(gp + n); z[2] = ld_stream(gp + 2 * n); z[3] = ld_stream(gp + 3 * n);
     }
   };
   fetch_zx(0, zx);
@@ -597,12 +604,12 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       else store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
     }
     if (active) {                     // layer outputs and what the backward pass needs
-      Store<bf16_t>::store(d.y, ((long)t * B + b) * d.ldy + j, valid ? h : 0.f);
-      if (d.cs) d.cs[((long)t * B + b) * n + j] = c;
-      if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)t * B + b) * n + j, h_prev);
+      st_stream((unsigned short*)d.y + ((long)t * B + b) * d.ldy + j, f2bf_bits(valid ? h : 0.f));
+      if (d.cs) st_stream(&d.cs[((long)t * B + b) * n + j], c);
+      if (d.hprev) st_stream((unsigned short*)d.hprev + ((long)t * B + b) * n + j, f2bf_bits(h_prev));
       if (valid && a.write_gates) {
         float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-        gp[0] = o.gi; gp[n] = o.gf; gp[2 * n] = o.gg; gp[3 * n] = o.go;
+        st_stream(gp, o.gi); st_stream(gp + n, o.gf); st_stream(gp + 2 * n, o.gg); st_stream(gp + 3 * n, o.go);
       }
     }
 #pragma unroll
@@ -977,12 +984,12 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     const int t = d.rev ? T - 1 - tau : tau;
     if (tau >= 0 && active && t < L) {
       const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-      in.gi = gp[0]; in.gf = gp[n]; in.gg = gp[2 * n]; in.go = gp[3 * n];
-      in.c_new = d.cs[((long)t * B + b) * n + j];
+      in.gi = ld_stream(gp); in.gf = ld_stream(gp + n); in.gg = ld_stream(gp + 2 * n); in.go = ld_stream(gp + 3 * n);
+      in.c_new = ld_stream(&d.cs[((long)t * B + b) * n + j]);
       const int tp = d.rev ? t + 1 : t - 1;
-      if (tp >= 0 && tp < T) in.c_prev = d.cs[((long)tp * B + b) * n + j];
+      if (tp >= 0 && tp < T) in.c_prev = ld_stream(&d.cs[((long)tp * B + b) * n + j]);
       else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
-      in.dy = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
+      in.dy = bf_bits2f(ld_stream((const unsigned short*)d.dy + ((long)t * B + b) * d.lddy + j));
     }
     return in;
   };
@@ -1110,7 +1117,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       PROF_MARK(1)
       if (active) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits[q];
+        for (int q = 0; q < 4; ++q) st_stream((unsigned short*)d.DZ + ((long)t * B + b) * 4 * n + q * n + j, bits[q]);
       }
       PROF_MARK(3)
     }
