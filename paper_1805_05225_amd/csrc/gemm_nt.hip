@@ -8,7 +8,10 @@
 // once by `launch_transpose` below - a bandwidth-bound pass that costs a few percent of the product
 // it feeds - instead of being transposed on the fly inside the MFMA loop.
 //
-// Kernel: 256x256 output tile per work-group of 4 wavefronts (2x2), each wavefront a 128x128
+// Two kernels share the tile raster and the epilogue: gemm_dl8_* (K a multiple of 64: operands loaded straight into
+// LDS, eight wavefronts; described where it is defined) and gemm_nt_kernel (any K a multiple of 8), which follows.
+//
+// gemm_nt_kernel: 256x256 output tile per work-group of 4 wavefronts (2x2), each wavefront a 128x128
 // sub-tile = 4x4 MFMA 32x32x16 blocks (256 accumulator registers).  K advances 64 at a time through
 // two LDS stages (rows of 128 bytes + 16 bytes padding; 144 KiB of the 160 KiB LDS).  Global loads run two
 // stages ahead of the MFMAs (one stage in registers, one in LDS); fragments are double-buffered in registers.
@@ -123,12 +126,14 @@ __device__ __forceinline__ TileCoord tile_coord(const NtArgs& g) {
   return t;
 }
 
-// Writes a work-group's 256x256 accumulator tile (2x2 wavefronts of 4x4 MFMA blocks) to C.
-template <typename TC>
-__device__ __forceinline__ void store_tile(f32x16 (&acc)[4][4], char* lds, const NtArgs& g, int M, int m0, int n0, int z, int ks,
+// Writes a work-group's 256x256 accumulator tile to C.  The tile is held by 2 x (8 / TN) wavefronts, each
+// 4 x TN MFMA blocks of 32x32 (TN = 4: 2x2 wavefronts of 128x128; TN = 2: 2x4 wavefronts of 128x64).
+template <typename TC, int TN>
+__device__ __forceinline__ void store_tile(f32x16 (&acc)[4][TN], char* lds, const NtArgs& g, int M, int m0, int n0, int z, int ks,
                                            int ksplit) {
+  constexpr int WN = 8 / TN, NW = 2 * WN;            // wavefronts along N, wavefronts in all
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int r = lane & 31, gq = lane >> 5;
   // Epilogue.  A lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 block: stored as
   // it is that would be 128-byte pieces, eight of them per row at different times.  The tile goes through LDS
@@ -139,10 +144,10 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][4], char* lds, const
   constexpr int kEpStride = 260;                      // floats per staged row (16-byte aligned, off the bank period)
   float* ep = (float*)lds;
   const bool vec_ok = (g.ldc % 4 == 0) && (((uintptr_t)C & 15u) == 0);
-  float bv[4];
+  float bv[TN];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int col = n0 + wn * 128 + j * 32 + r;
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn * (TN * 32) + j * 32 + r;
     bv[j] = (bias && ks == 0 && col < g.N) ? bias[col] : 0.f;
   }
 #pragma unroll
@@ -151,16 +156,16 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][4], char* lds, const
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int rowl = wm * 64 + ii * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-          ep[rowl * kEpStride + wn * 128 + j * 32 + r] = acc[2 * half + ii][j][v] + bv[j];
+          ep[rowl * kEpStride + wn * (TN * 32) + j * 32 + r] = acc[2 * half + ii][j][v] + bv[j];
         }
     __syncthreads();
     const int col = n0 + lane * 4;
-    for (int rr = 0; rr < 32; ++rr) {
-      const int rowl = wave * 32 + rr;
+    for (int rr = 0; rr < 128 / NW; ++rr) {
+      const int rowl = wave * (128 / NW) + rr;
       const int row = m0 + (rowl >> 6) * 128 + half * 64 + (rowl & 63);
       if (row >= M) break;                             // rows ascend with rr inside a wave's share
       if (col >= g.N) continue;
@@ -302,8 +307,184 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
     __syncthreads();
   }
 
-  store_tile<TC>(acc, lds, g, M, m0, n0, z, ks, ksplit);
+  store_tile<TC, 4>(acc, lds, g, M, m0, n0, z, ks, ksplit);
 }
+
+// ---------------------------------------------------------------------------------------------------------
+// Same product with the operands brought from global memory straight into LDS (16-byte-per-lane buffer loads
+// with the LDS destination: no staging registers, no LDS store instructions), for K a multiple of 64.
+//
+// LDS holds two stages of [A | B], each operand 256 rows of 128 bytes (64 bf16), unpadded: a wavefront-wide
+// load fills 1 KiB = 8 consecutive rows, lane l writing bytes 16*l of it.  Bank conflicts of the fragment reads
+// are avoided by the placement instead of padding: the 16-byte slot p of row r holds k-chunk p ^ ((r >> 1) & 7),
+// which the loading lane arranges by choosing WHICH global chunk it fetches.
+//
+// Wavefronts: 2 x (8 / TN), each 4 x TN MFMA blocks; the kernels below use TN = 2: eight wavefronts of 128x64,
+// two per SIMD, so one wavefront's LDS reads and waits hide behind the other's MFMAs (four wavefronts of 128x128
+// measured 15-20 % slower).  Measured on the device: what bounds this kernel is the path from L2 to LDS - with the
+// MFMAs taken out the loop needs the same number of cycles (about 3500 per stage against 2050 of MFMA work), because
+// a fifth of a stage's lines is a first touch per XCD and the work-groups sharing a panel wait for the same miss.
+//
+// Loop, per stage `it` (k advances 64 = four MFMA k-steps): fragments of k-step s+1 are read while the MFMAs of
+// step s run.  Before the last k-step the wavefront waits for its own loads of stage it+1 and meets the others at
+// the barrier; after it every load of stage it+1 has landed and every read of stage it's buffer has completed,
+// so the loads of stage it+2 are issued into that buffer and the first fragments of stage it+1 are read - both
+// under the MFMAs of the last k-step.  A load therefore has a whole stage of MFMAs to complete.
+constexpr int kDlRow = 128;                  // bytes per LDS row
+constexpr int kDlOp = kT * kDlRow;           // one operand, one stage (32 KiB)
+constexpr int kDlStage = 2 * kDlOp;
+constexpr int kDlLds = 133120;               // max(two stages, the epilogue's staging of 128 rows x 260 floats)
+// A buffer load whose data goes to LDS (M0 = wavefront-uniform LDS byte address; lane l writes M0 + size * l) instead of
+// registers.  Written as assembly on purpose: the compiler makes every later LDS read wait for ALL such loads
+// it knows to be in flight (it cannot tell that they fill the other stage), which would serialise loads and MFMAs.
+// The kernel orders them itself with explicit vmcnt waits and barriers.  Nothing else in these kernels uses M0.
+__device__ __forceinline__ void load_to_lds_b128(const u32x4& rsrc, unsigned lds_addr, unsigned voff, unsigned soff) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+__device__ __forceinline__ u32x4 make_rsrc(const void* base, unsigned bytes) {
+  const unsigned long long a = (unsigned long long)base;
+  u32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((unsigned)a);
+  r[1] = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32) & 0xffffu);
+  r[2] = __builtin_amdgcn_readfirstlane(bytes);
+  r[3] = kBufFlags;
+  return r;
+}
+
+template <typename TC, int TN>
+__device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int WN = 8 / TN, NW = 2 * WN, NLD = 32 / NW;       // loads per wavefront, operand and stage
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int r = lane & 31, gq = lane >> 5;
+
+  const TileCoord tc = tile_coord(g);
+  if (!tc.live) return;
+  const int M = tc.M, K = tc.K, m0 = tc.m0, n0 = tc.n0, z = tc.z, ks = tc.ks, ksplit = tc.ksplit;
+
+  f32x16 acc[4][TN];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int ktiles = K / kKB;                      // K is a multiple of 64 here
+  const int nstage = ktiles * g.nseg;
+  const int it0 = (int)((long)nstage * ks / ksplit);
+  const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
+
+  // Loads.  Wavefront-load i of this wavefront fills rows 8 * (i * NW + wave) .. + 7 of an operand; lane l fills
+  // slot l & 7 of row (l >> 3) of those, i.e. fetches k-chunk (l & 7) ^ swizzle(row).  Rows past the operand's end
+  // point outside the buffer descriptor and arrive as zeros.
+  unsigned voa[NLD], vob[NLD];
+  {
+    const long a_rows_mem = g.a_rows ? g.a_phys_rows : M;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int rl = (i * NW + wave) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((rl >> 1) & 7);
+      long ra = m0 + rl;
+      if (g.a_rows) ra = ra < M ? (long)g.a_rows[ra] : 0x7fffffffL; else if (ra >= M) ra = 0x7fffffffL;
+      long rb = n0 + rl;
+      if (rb >= g.N) rb = 0x7fffffffL;
+      const long oa = (ra * g.lda) * 2 + chunk * 16, ob = (rb * g.ldb) * 2 + chunk * 16;
+      voa[i] = (ra >= a_rows_mem || oa > 0x7ffffff0L) ? 0x7ffffff0u : (unsigned)oa;
+      vob[i] = (rb >= g.N || ob > 0x7ffffff0L) ? 0x7ffffff0u : (unsigned)ob;
+    }
+  }
+  const long a_bytes = (long)(g.a_rows ? g.a_phys_rows : M) * g.lda * 2, b_bytes = (long)g.N * g.ldb * 2;
+  const unsigned lds_base = (unsigned)(unsigned long long)(__attribute__((address_space(3))) char*)lds;
+  const int a_rec = a_bytes > 0x7fffffffL ? 0x7fffffff : (int)a_bytes, b_rec = b_bytes > 0x7fffffffL ? 0x7fffffff : (int)b_bytes;
+  // Wavefront-loads of a stage are numbered 0 .. 2*NLD-1 (even: A, odd: B); `issue` enqueues numbers [first, last).
+  auto issue = [&](int rel_it, int buf, int first, int last) __attribute__((always_inline)) {
+    const int it = it0 + rel_it;
+    const int seg = it / ktiles, kt = it - seg * ktiles;
+    const u32x4 ra = make_rsrc(g.A + (g.sAz * z + g.sAseg * seg) * 2, (unsigned)a_rec);
+    const u32x4 rb = make_rsrc(g.B + (g.sBz * z + g.sBseg * seg) * 2, (unsigned)b_rec);
+    const unsigned dst = lds_base + buf * kDlStage + wave * 1024;
+    const unsigned koff = kt * (kKB * 2);
+#pragma unroll
+    for (int q = 0; q < 2 * NLD; ++q) {
+      if (q < first || q >= last) continue;
+      const int i = q >> 1;
+      if (q & 1) load_to_lds_b128(rb, dst + kDlOp + i * NW * 1024, vob[i], koff);
+      else load_to_lds_b128(ra, dst + i * NW * 1024, voa[i], koff);
+    }
+  };
+  constexpr int NQ = 2 * NLD;                               // wavefront-loads per stage and wavefront
+
+  // Fragment reads: row (wm*128 + i*32 + r) of A / (wn*TN*32 + j*32 + r) of B, k-chunk 2*s + gq, which sits in
+  // slot (2*s + gq) ^ ((r >> 1) & 7): one XOR with s * 32 per k-step on a per-lane base offset.
+  const int fa_off = (wm * 128 + r) * kDlRow + ((gq ^ ((r >> 1) & 7)) * 16);
+  const int fb_off = kDlOp + (wn * TN * 32 + r) * kDlRow + ((gq ^ ((r >> 1) & 7)) * 16);
+  uint4 fa[2][4], fb[2][TN];
+  auto read_frags = [&](int buf, int s, int c) __attribute__((always_inline)) {
+    const char* base = lds + buf * kDlStage;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[c][i] = *(const uint4*)(base + (fa_off ^ (s * 32)) + i * 32 * kDlRow);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[c][j] = *(const uint4*)(base + (fb_off ^ (s * 32)) + j * 32 * kDlRow);
+  };
+
+  // One k-step: the MFMAs of fragment buffer c.  With `ld`, the NQ wavefront-loads of stage `ld_it` go out between
+  // them, one after every second MFMA, the rest behind the last.  (Spreading them over three k-steps measured
+  // slower: the last ones then have too little time left; so did L2 prefetches of the coming stages.)
+  auto kstep = [&](int c, bool ld, int ld_it, int ld_buf) __attribute__((always_inline)) {
+    int q = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
+        if (((i * TN + j) & 1) && q < NQ) {
+          if (ld) issue(ld_it, ld_buf, q, q + 1);
+          ++q;
+        }
+      }
+    if (q < NQ && ld) issue(ld_it, ld_buf, q, NQ);
+  };
+
+  if (total > 0) {
+    issue(0, 0, 0, NQ);
+    __builtin_amdgcn_s_waitcnt(0x0f70);            // vmcnt(0)
+    __syncthreads();
+    if (total > 1) issue(1, 1, 0, NQ);
+    read_frags(0, 0, 0);
+  }
+  for (int it = 0; it < total; ++it) {
+    const int cur = it & 1;
+    read_frags(cur, 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(0, false, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(cur, 2, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(1, false, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(cur, 3, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(0, false, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // last k-step: stage it+1 must be in LDS and this stage's buffer free
+    if (it + 1 < total) {
+      __builtin_amdgcn_s_waitcnt(0x0070);          // vmcnt(0) lgkmcnt(0): own loads of stage it+1 landed, own reads of this stage done
+      __syncthreads();
+      read_frags(cur ^ 1, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(1, it + 2 < total, it + 2, cur);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  store_tile<TC, TN>(acc, lds, g, M, m0, n0, z, ks, ksplit);
+}
+
+// (kernels with literal launch bounds: a bound that depends on a template parameter loses the host-side stub)
+__global__ __launch_bounds__(512, 1) void gemm_dl8_f32_kernel(NtArgs g) { gemm_dl_body<float, 2>(g); }
+__global__ __launch_bounds__(512, 1) void gemm_dl8_bf16_kernel(NtArgs g) { gemm_dl_body<uint16_t, 2>(g); }
 
 // dst[c][r] = keep(r) ? src[r][c] : 0 for r < R, c < C ; dst rows are padded with zeros up to ldd.
 // keep(r): rows of src are frames (t = r / Bt, b = r % Bt), kept iff lens == NULL or t < lens[b].
@@ -490,6 +671,20 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   const int sups = cdiv(cdiv(g.M, kT), kSupM) * cdiv(cdiv(g.N, kT), kSupN);
   a.blocked = sups >= 32 ? 1 : 0;
   const int tiles = a.blocked ? cdiv(sups, 8) * 8 * kSupM * kSupN : cdiv(g.M, kT) * cdiv(g.N, kT);
+  // K a multiple of 64 (device-resident K values are multiples of 64 by contract): operands go straight into LDS
+  if (g.K % kKB == 0) {
+    static bool dl_attr_set = false;
+    if (!dl_attr_set) {
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_dl8_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
+      if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_dl8_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
+      if (e != hipSuccess) return e;
+      dl_attr_set = true;
+    }
+    const dim3 grid(tiles, g.out_bf16 ? g.nz : g.nz * a.ksplit);
+    if (g.out_bf16) hipLaunchKernelGGL(gemm_dl8_bf16_kernel, grid, dim3(512), kDlLds, s, a);
+    else hipLaunchKernelGGL(gemm_dl8_f32_kernel, grid, dim3(512), kDlLds, s, a);
+    return hipGetLastError();
+  }
   const size_t shmem = 4 * kOpBytes;
   static bool attr_set = false;
   if (!attr_set) {
@@ -502,6 +697,7 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   else hipLaunchKernelGGL(gemm_nt_kernel<float>, dim3(tiles, g.nz * a.ksplit), dim3(kThreads), shmem, s, a);
   return hipGetLastError();
 }
+
 
 hipError_t launch_transpose(const void* src, void* dst, int R, int C, long ld_src, long ld_dst, int nz, long s_src, long s_dst,
                             const int* lens, int Bt, int T, hipStream_t s, const int* cidx, const int* fidx, const int* count) {
