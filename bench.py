@@ -121,12 +121,70 @@ def cpu_baseline(inp):
                           nl, n_in, L["W_h"].shape[1], len(lens), cap, frames, dt, nl)}
 
 
+def bench_decoder(args, Bn, synth):
+    """--config 5: the stepped decoder cell (one LSTM of n = 1000 fed by 620 + 2000 inputs, 768 rows = 64 sentences x
+    beam 12), forward only, one time step per call with the state fed back.  One "step" here is one block of 100
+    dependent decoder steps; the figure of merit is the latency of one decoder step."""
+    import ctypes as ct
+    inp = synth.make(5)
+    cfg = inp["cfg"]
+    L = inp["layers"][0]
+    n, n_in, B, nsteps = cfg["n"], cfg["n_in"], cfg["B"], cfg["steps"]
+    Wx = torch.from_numpy(L["W_x"][0]).to(torch.bfloat16).cuda()
+    Wh = torch.from_numpy(L["W_h"][0]).to(torch.bfloat16).cuda()
+    b = torch.from_numpy(L["b"][0]).float().cuda()
+    g = torch.Generator(device="cpu").manual_seed(5)
+    xs = torch.randn(nsteps, B, n_in, generator=g).to(torch.bfloat16).cuda()     # embedding | context, fresh every step
+    desc = Bn.make_desc(1, B, n_in, n, Bn.LSTM_BF16_F32STATE, 1, Bn.FLAG_INFERENCE)
+    _, wb = Bn.query(desc, False)
+    desc.workspace_bytes = wb
+    desc_packed = Bn.make_desc(1, B, n_in, n, Bn.LSTM_BF16_F32STATE, 1, Bn.FLAG_INFERENCE | Bn.FLAG_WEIGHTS_PACKED)
+    desc_packed.workspace_bytes = wb
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    y = torch.empty(1, B, n, dtype=torch.bfloat16, device="cuda")
+    state = [torch.zeros(B, n, device="cuda") for _ in range(4)]                  # h, c ping-pong
+    s = torch.cuda.current_stream().cuda_stream
+
+    def block(first_call):
+        for i in range(nsteps):
+            h0, c0, h1, c1 = state if i % 2 == 0 else (state[2], state[3], state[0], state[1])
+            d = desc if (first_call and i == 0) else desc_packed
+            rc = Bn.lib.lstm_fwd(ct.byref(d), xs[i].data_ptr(), Wx.data_ptr(), Wh.data_ptr(), b.data_ptr(), h0.data_ptr(),
+                                 c0.data_ptr(), None, y.data_ptr(), None, h1.data_ptr(), c1.data_ptr(), None, ws.data_ptr(), s)
+            assert rc == 0, Bn.strerror(rc)
+
+    block(True)                                   # packs the weights once
+    for _ in range(args.warmup):
+        block(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        block(False)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us = dt / (args.steps * nsteps) * 1e6
+    flops = 8.0 * n * (n_in + n) * B
+    tflops = flops / (us * 1e-6) / 1e12
+    out = {
+        "metric": "LSTM decoder step latency (n=%d, %d rows)" % (n, B), "value": us, "unit": "us/step", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 5: one LSTM stepped one time step per call, n_in=%d (620 + 2000), n=%d, rows=%d, "
+                               "%d dependent steps per block, bf16 storage / f32 state, forward only" % (n_in, n, B, nsteps)},
+        "useful_tflops": tflops,
+        "roofline": {"bound": "mfma", "kernel": "step product [x | h] [W_x ; W_h] (+ concatenation and cell update)",
+                     "achieved": tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / BF16_PEAK_TFLOPS,
+                     "traffic": None},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024)")
+    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--per-step", action="store_true", help="force one launch per time step")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -144,6 +202,9 @@ def main():
     from paper_1805_05225_amd import synth
 
     torch.cuda.set_device(0)
+    if args.config == 5:
+        bench_decoder(args, Bn, synth)
+        return
     inp = synth.make(args.config)
     cfg = inp["cfg"]
     assert cfg["kind"] == "blstm"

@@ -58,7 +58,13 @@ typedef enum {
 enum {
   LSTM_FLAG_ACCUMULATE = 1, /* *_bwd: add into dW_x, dW_h, db instead of overwriting them        */
   LSTM_FLAG_PER_STEP = 2,   /* force one kernel launch per time step (no single-launch loop)     */
-  LSTM_FLAG_INFERENCE = 4   /* *_fwd: nothing is saved for backward; reserve may be NULL         */
+  LSTM_FLAG_INFERENCE = 4,  /* *_fwd: nothing is saved for backward; reserve may be NULL         */
+  LSTM_FLAG_WEIGHTS_PACKED = 8 /* *_fwd with T == 1 and LSTM_FLAG_INFERENCE: the caller states that the
+                              * previous *_fwd call on this workspace had the same T, B, n_in, n, dtype,
+                              * bidirectionality and the same W_x, W_h contents, so the packed copy of the
+                              * weights that the workspace still holds is used again instead of being
+                              * rebuilt (a false statement gives wrong results, not an error).  Ignored
+                              * by every other call. */
 };
 
 typedef struct {
@@ -82,7 +88,10 @@ int lstm_query(const lstm_desc* desc, int bidirectional, size_t* reserve_bytes, 
  *   -> y[T,B,n] (0 at padded frames), c[T,B,n] (cell state after each frame, carried at padded
  *      frames; may be NULL), hT,cT[B,n] (state after each row's last processed valid frame),
  *      reserve (opaque: gate activations and the hidden state entering each frame).
- * With T == 1 and LSTM_FLAG_INFERENCE this is the stepped decoder cell: feed hT,cT back as h0,c0. */
+ * With T == 1 and LSTM_FLAG_INFERENCE this is the stepped decoder cell (Sec. 5, Listing 1: the decoder's
+ * recurrent unit, stepped once per output word for all beam entries): feed hT,cT back as h0,c0.  For
+ * bfloat16 storage that step runs as one product [x_t | h] [W_x ; W_h] + b over all rows followed by the
+ * cell update; pass LSTM_FLAG_WEIGHTS_PACKED from the second step on to keep the packed weights. */
 int lstm_fwd(const lstm_desc* desc, const void* x, const void* W_x, const void* W_h, const void* b,
              const void* h0, const void* c0, const int32_t* seq_lens,
              void* y, void* c, void* hT, void* cT, void* reserve, void* workspace, void* stream);

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm.so"))   # override: diagnostic builds
 
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
-FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE = 1, 2, 4
+FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED = 1, 2, 4, 8
 EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
            "lstm_strerror")
 

@@ -213,6 +213,18 @@ hipError_t launch_colsum_final(const float* part, float* db, int ncols, int ndir
 hipError_t launch_colsum(const void* DZ, float* db, float* part, int rows, int ncols, int ndir, long sDZ,
                          bool bf16, int accumulate, hipStream_t s);
 
+// One time step for all rows as a single product (inference, bfloat16 storage; see single_step.hip):
+// Wcat[ndir][4n][Kc] = [W_x^T | 0 up to n_in_pad | W_h^T | 0 up to Kc]
+hipError_t launch_pack_wcat(const void* W_x, const void* W_h, void* Wcat, int n_in, int n_in_pad, int n, int Kc, int ndir, hipStream_t s);
+// Acat[ndir][B][Kc] = [x | 0 | bf16(h[dir]) | 0] in the same column layout (h == NULL: zeros)
+hipError_t launch_concat_xh(const void* x, const float* h, void* Acat, int B, int n_in, int n_in_pad, int n, int Kc, int ndir, hipStream_t s);
+// cell update from the pre-activations z = bias + sum of `nparts` partial products, laid out [ndir][nparts][part floats]
+// with [B][4n] inside a part.  h_in, c_in [ndir][B][n]: state entering the step (NULL = zeros); h_out, c_out: state
+// leaving it (NULL = not wanted); y[B][ldy] (direction d at column d*n); cs[ndir][B][n] or NULL; rows with lens[b] < 1
+// keep their state and output zero
+hipError_t launch_cell_step(const float* z, long part, int nparts, const float* bias, const float* h_in, const float* c_in, float* h_out,
+                            float* c_out, void* y, long ldy, float* cs, const int* lens, int B, int n, int ndir, hipStream_t s);
+
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
 }  // namespace lstm

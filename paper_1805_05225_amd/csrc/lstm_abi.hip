@@ -26,7 +26,8 @@ struct Plan {
   size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
   // workspace
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
-      ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, workspace_bytes;
+      ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, ws_Wcat, ws_Acat, workspace_bytes;
+  bool single_step; int Kc, ksplit;         // T == 1 inference in bfloat16: the step is one product over [x | h], K cut in ksplit ranges
   bool fast_gemm; int n_in_pad; long TBp;   // bf16 products through the k-contiguous kernel (operands transposed once)
   size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems, Wf_bytes;
 };
@@ -37,7 +38,7 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   const long TB = (long)d->T * d->B;
   if (TB >= (1L << 31) || (long)d->n * 4 >= (1L << 29) || d->n_in >= (1 << 29) || d->B >= (1 << 24)) return LSTM_ERR_DIM;
   if (d->dtype != LSTM_F32 && d->dtype != LSTM_BF16_F32STATE) return LSTM_ERR_UNSUPPORTED;
-  if (d->flags & ~(LSTM_FLAG_ACCUMULATE | LSTM_FLAG_PER_STEP | LSTM_FLAG_INFERENCE)) return LSTM_ERR_UNSUPPORTED;
+  if (d->flags & ~(LSTM_FLAG_ACCUMULATE | LSTM_FLAG_PER_STEP | LSTM_FLAG_INFERENCE | LSTM_FLAG_WEIGHTS_PACKED)) return LSTM_ERR_UNSUPPORTED;
   if (d->reserved != 0) return LSTM_ERR_UNSUPPORTED;
   p->T = d->T; p->B = d->B; p->n_in = d->n_in; p->n = d->n; p->D = bidir ? 2 : 1;
   p->bf16 = d->dtype == LSTM_BF16_F32STATE;
@@ -81,7 +82,17 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->DZ_dir_elems = up(TB * 4 * n * p->esz) / p->esz;
   p->ws_DZ = take(infer ? 0 : D * p->DZ_dir_elems * p->esz);
   p->Zx_dir_elems = up(TB * 4 * n * 4) / 4;
-  p->ws_Zx = take(infer ? D * p->Zx_dir_elems * 4 : 0);
+  // T == 1 inference, bfloat16: few output tiles, so K is cut into ranges that separate work-groups multiply (each at
+  // least four 64-wide stages); their partial products lie side by side and the cell kernel adds them
+  p->single_step = p->bf16 && d->n % 2 == 0 && infer && d->T == 1 && !(d->flags & LSTM_FLAG_PER_STEP);
+  p->n_in_pad = (d->n_in + 7) / 8 * 8;
+  {
+    const long tiles = (long)cdiv(B > 0 ? B : 1, 256) * cdiv(4L * d->n, 256) * p->D;
+    const long stages = cdiv((long)p->n_in_pad + d->n, 64);
+    p->ksplit = (int)std::max(1L, std::min(std::min(256 / tiles, stages / 4), 8L));
+    p->Kc = cdiv((long)p->n_in_pad + d->n, 64L * p->ksplit) * 64 * p->ksplit;
+  }
+  p->ws_Zx = take(infer ? D * p->Zx_dir_elems * 4 * (p->single_step ? p->ksplit : 1) : 0);
   p->ws_colsum = take(infer ? 0 : D * 64 * 4 * n * 4);
   // transposed / padded operand copies for the fast bf16 products
   p->fast_gemm = p->bf16 && d->n % 2 == 0;
@@ -97,6 +108,8 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ws_cidx = take(fg ? (size_t)TB * 4 : 0);
   p->ws_fidx = take(fg ? (size_t)p->TBp * 4 : 0);
   p->ws_count = take(fg ? 256 : 0);
+  p->ws_Wcat = take(p->single_step ? D * 4 * n * p->Kc * 2 : 0);
+  p->ws_Acat = take(p->single_step ? D * B * p->Kc * 2 : 0);
   p->workspace_bytes = o + kAlign;
   return LSTM_OK;
 }
@@ -166,6 +179,38 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   float* cstate = (float*)(ws + p.ws_cstate);
   const size_t state_bytes = D * B * n * 4;
 
+  if (p.single_step) {
+    // the stepped cell: z = [x | h] [W_x ; W_h] + b as one product over all rows, then the cell update
+    const long Kc = p.Kc;
+    char* Wcat = ws + p.ws_Wcat;
+    char* Acat = ws + p.ws_Acat;
+    float* z = (float*)(ws + p.ws_Zx);
+    {
+      Phase ph(LSTM_PHASE_PREP, 2, s);
+      if (!(desc->flags & LSTM_FLAG_WEIGHTS_PACKED))
+        HIPCHK(launch_pack_wcat(W_x, W_h, Wcat, p.n_in, p.n_in_pad, p.n, p.Kc, p.D, s));
+      HIPCHK(launch_concat_xh(x, (const float*)h0, Acat, p.B, p.n_in, p.n_in_pad, p.n, p.Kc, p.D, s));
+    }
+    // batch index of the product = K range: A and B advance by Kr columns, C by one partial result
+    const long Kr = Kc / p.ksplit, part = (long)p.Zx_dir_elems;
+    {
+      Phase ph(LSTM_PHASE_GEMM_ZX, (long)D, s);
+      for (size_t d = 0; d < D; ++d) {
+        GemmArgs g = {};
+        g.A = Acat + d * B * Kc * 2; g.B = Wcat + d * (4 * n) * Kc * 2; g.C = z + d * p.ksplit * part;
+        g.M = p.B; g.N = 4 * p.n; g.K = (int)Kr; g.lda = Kc; g.ldb = Kc; g.ldc = 4 * n;
+        g.sAz = Kr; g.sBz = Kr; g.sCz = part; g.nz = p.ksplit; g.nseg = 1;
+        g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false; g.vecA = 16; g.vecB = 16;
+        HIPCHK(launch_gemm(g, s));
+      }
+    }
+    {
+      Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
+      HIPCHK(launch_cell_step(z, part, p.ksplit, (const float*)b, (const float*)h0, (const float*)c0, (float*)hT, (float*)cT, y,
+                              (long)(D * n), (float*)c, seq_lens, p.B, p.n, p.D, s));
+    }
+    return LSTM_OK;
+  }
   {
     Phase ph(LSTM_PHASE_PREP, 5, s);
     HIPCHK(launch_fill_zero(ws + p.ws_sync, p.sync_bytes, s));

@@ -308,6 +308,40 @@ def test_config4_first_layer_full_size():
     compare(f, g, fo, go, TOL["bf16"])
 
 
+
+@pytest.mark.parametrize("bidir,B,n_in,n", [(False, 70, 37, 50), (True, 33, 24, 18), (False, 300, 136, 100), (False, 1, 5, 6)])
+def test_single_step_cell_bf16(bidir, B, n_in, n):
+    """T = 1 in inference mode (the stepped decoder cell runs as one product over [x | h]): three chained steps with
+    bias, initial state, rows of length 0 and the packed weights kept from the second step on, against the oracle."""
+    rng = np.random.default_rng(1000 + B)
+    D = 2 if bidir else 1
+    lens = np.ones(B, dtype=np.int32)
+    lens[::5] = 0                                           # these rows keep their state and output zero
+    c = rnd_case(rng, 1, B, n_in, n, D, lens, "bf16")
+    sq = (lambda a: a) if bidir else (lambda a: a[0])
+    Wx, Wh, b = dev(sq(c["W_x"]), "bf16"), dev(sq(c["W_h"]), "bf16"), dev(sq(c["b"]))
+    h, cc = dev(sq(c["h0"])), dev(sq(c["c0"]))
+    ho, co = sq(c["h0"]), sq(c["c0"])
+    ws = None
+    for step in range(3):
+        xt = torch.from_numpy(rng.standard_normal((1, B, n_in))).to(torch.bfloat16)
+        flags = Bn.FLAG_INFERENCE | (Bn.FLAG_WEIGHTS_PACKED if step else 0)
+        s = Bn.forward(xt.cuda(), Wx, Wh, b, h, cc, dev(lens), bidirectional=bidir, flags=flags, workspace=ws, want_c=True)
+        ws = s["workspace"]
+        x64 = xt.float().numpy().astype(np.float64)
+        if bidir:
+            yo, cso, ho, co = O.blstm_fwd(x64, c["W_x"], c["W_h"], c["b"], ho, co, lens)
+        else:
+            yo, cso, ho, co = O.lstm_fwd(x64, c["W_x"][0], c["W_h"][0], c["b"][0], ho, co, lens, 1)
+        torch.cuda.synchronize()
+        check("y", s["y"], yo, TOL["bf16"])
+        check("c", s["c"], cso, TOL["bf16"])
+        check("hT", s["hT"], ho, TOL["bf16"])
+        check("cT", s["cT"], co, TOL["bf16"])
+        assert float(s["y"].float()[0, ::5].abs().max()) == 0.0
+        h, cc = s["hT"], s["cT"]
+
+
 def test_config5_decoder_stepping_bf16():
     inp = synth.make(5)
     L = inp["layers"][0]
@@ -319,8 +353,8 @@ def test_config5_decoder_stepping_bf16():
     ws = None
     for step in range(4):
         xt = torch.from_numpy(rng.standard_normal((1, 768, 2620))).to(torch.bfloat16)
-        s = Bn.forward(xt.cuda(), Wx, Wh, None, h, c, None, bidirectional=False, flags=Bn.FLAG_INFERENCE, workspace=ws,
-                       want_c=False)
+        s = Bn.forward(xt.cuda(), Wx, Wh, None, h, c, None, bidirectional=False,
+                       flags=Bn.FLAG_INFERENCE | (Bn.FLAG_WEIGHTS_PACKED if step else 0), workspace=ws, want_c=False)
         ws = s["workspace"]
         h, c = s["hT"], s["cT"]
         _, _, ho, co = O.lstm_fwd(xt.float().numpy().astype(np.float64), L["W_x"][0].astype(np.float64),
