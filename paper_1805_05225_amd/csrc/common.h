@@ -59,7 +59,9 @@ struct GemmArgs {
   int a_phys_rows;                        // rows of A in memory when a_rows is given
   const int* m_dev; const int* k_dev;     // M / K read from device memory (capped by M / K above, which size the grid)
   int ksplit;                             // > 1: K cut into that many ranges whose parts are ADDED to C atomically
-                                          // (float C, nseg == 1; C must hold zeros or the value to add to)
+                                          // (float C, nseg == 1; C must hold zeros or the value to add to) ...
+  float* parts;                           // ... or, if not NULL (nz * ksplit * M * ldc floats, no c_rows): every range stores
+                                          // its part there and a second kernel writes C (+)= their sum (`accumulate` honoured)
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 // Fast bfloat16 kernel for problems with both operands k-contiguous, 16-byte aligned rows and K % 8 == 0

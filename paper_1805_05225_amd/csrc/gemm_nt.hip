@@ -40,7 +40,8 @@ struct NtArgs {
   const int* a_rows; const int* c_rows;   // logical row -> physical row of A / of C (NULL: identity)
   const int* m_dev; const int* k_dev;     // device-resident M / K (NULL: use M / K above)
   int a_phys_rows;                        // rows of A in memory when a_rows is given
-  int ksplit;                             // > 1: K is cut into that many ranges, each adds its part to C atomically
+  int ksplit;                             // > 1: K is cut into that many ranges, each adds its part to C atomically ...
+  float* parts; long sPart;               // ... or, if parts != NULL, stores it at parts + (z * ksplit + range) * sPart (layout of C)
   int blocked;                            // tile raster: 1 = blocks of kSupM x kSupN tiles per XCD, 0 = bands of 8 tile columns
 };
 
@@ -139,7 +140,8 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][TN], char* lds, cons
   // it is that would be 128-byte pieces, eight of them per row at different times.  The tile goes through LDS
   // instead (two halves of 128 rows, the main loop's buffers are free by now) and leaves as whole rows: one
   // wavefront store = 256 consecutive columns of one row.
-  TC* C = (TC*)g.C + g.sCz * z;
+  const bool to_parts = ksplit > 1 && g.parts != nullptr;      // this K range keeps its own copy: plain stores, no atomics
+  TC* C = to_parts ? (TC*)(g.parts + ((long)z * ksplit + ks) * g.sPart) : (TC*)g.C + g.sCz * z;
   const float* bias = g.bias ? g.bias + g.sbiasz * z : nullptr;
   constexpr int kEpStride = 260;                      // floats per staged row (16-byte aligned, off the bank period)
   float* ep = (float*)lds;
@@ -175,13 +177,13 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][TN], char* lds, cons
       const bool whole = vec_ok && col + 3 < g.N;
       if constexpr (sizeof(TC) == 4) {
         float* Cf = (float*)C + off;
-        if (ksplit > 1) {
+        if (ksplit > 1 && !to_parts) {
 #pragma unroll
           for (int k = 0; k < 4; ++k)
             if (col + k < g.N) unsafeAtomicAdd(Cf + k, e[k]);
         } else if (whole) {
           float4 o = val;
-          if (g.accumulate) {
+          if (g.accumulate && !to_parts) {
             const float4 old = *(const float4*)Cf;
             o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
           }
@@ -189,7 +191,7 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][TN], char* lds, cons
         } else {
 #pragma unroll
           for (int k = 0; k < 4; ++k)
-            if (col + k < g.N) Cf[k] = g.accumulate ? Cf[k] + e[k] : e[k];
+            if (col + k < g.N) Cf[k] = (g.accumulate && !to_parts) ? Cf[k] + e[k] : e[k];
         }
       } else {
         uint16_t* Cb = (uint16_t*)C + off;
@@ -486,6 +488,21 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
 __global__ __launch_bounds__(512, 1) void gemm_dl8_f32_kernel(NtArgs g) { gemm_dl_body<float, 2>(g); }
 __global__ __launch_bounds__(512, 1) void gemm_dl8_bf16_kernel(NtArgs g) { gemm_dl_body<uint16_t, 2>(g); }
 
+// C[z][m][n] (+)= sum over the K ranges of parts[z][range][m][n]  (parts in the layout of C, one after the other)
+__global__ void sum_parts_kernel(const float* parts, float* C, int M, int N, long ldc, long sCz, long sPart, int ksplit, int accumulate,
+                                 long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int n = (int)(idx % N);
+  const long rest = idx / N;
+  const int m = (int)(rest % M);
+  const long z = rest / M;
+  const long off = (long)m * ldc + n;
+  float v = accumulate ? C[z * sCz + off] : 0.f;
+  for (int ks = 0; ks < ksplit; ++ks) v += __builtin_nontemporal_load(parts + (z * ksplit + ks) * sPart + off);
+  C[z * sCz + off] = v;
+}
+
 // dst[c][r] = keep(r) ? src[r][c] : 0 for r < R, c < C ; dst rows are padded with zeros up to ldd.
 // keep(r): rows of src are frames (t = r / Bt, b = r % Bt), kept iff lens == NULL or t < lens[b].
 // With `cidx` (compact index of every frame, -1 for padded frames) the kept frames are packed instead:
@@ -658,6 +675,16 @@ bool gemm_nt_ok(const GemmArgs& g) {
          g.sAz % 8 == 0 && g.sBz % 8 == 0 && g.sAseg % 8 == 0 && g.sBseg % 8 == 0 && a16(g.A) && a16(g.B);
 }
 
+// second half of a product whose K ranges stored their parts side by side: C (+)= their sum
+static hipError_t sum_parts(const NtArgs& a, hipStream_t s) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !a.parts) return e;
+  const long total = (long)a.nz * a.M * a.N;
+  hipLaunchKernelGGL(sum_parts_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, a.parts, (float*)a.C, a.M, a.N, a.ldc, a.sCz, a.sPart, a.ksplit,
+                     a.accumulate, total);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0 || g.nz <= 0) return hipSuccess;
   NtArgs a;
@@ -667,6 +694,7 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   a.nseg = g.nseg; a.sAseg = g.sAseg; a.sBseg = g.sBseg; a.accumulate = g.accumulate;
   a.a_rows = g.a_rows; a.c_rows = g.c_rows; a.m_dev = g.m_dev; a.k_dev = g.k_dev; a.a_phys_rows = g.a_phys_rows;
   a.ksplit = (g.ksplit > 1 && !g.out_bf16 && g.nseg == 1) ? g.ksplit : 1;
+  a.parts = a.ksplit > 1 && !g.c_rows ? g.parts : nullptr; a.sPart = (long)g.M * g.ldc;
   // the blocked raster pays when every XCD gets several blocks; with few tiles it would leave XCDs idle
   const int sups = cdiv(cdiv(g.M, kT), kSupM) * cdiv(cdiv(g.N, kT), kSupN);
   a.blocked = sups >= 32 ? 1 : 0;
@@ -683,7 +711,7 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
     const dim3 grid(tiles, g.out_bf16 ? g.nz : g.nz * a.ksplit);
     if (g.out_bf16) hipLaunchKernelGGL(gemm_dl8_bf16_kernel, grid, dim3(512), kDlLds, s, a);
     else hipLaunchKernelGGL(gemm_dl8_f32_kernel, grid, dim3(512), kDlLds, s, a);
-    return hipGetLastError();
+    return sum_parts(a, s);
   }
   const size_t shmem = 4 * kOpBytes;
   static bool attr_set = false;
@@ -695,7 +723,7 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   }
   if (g.out_bf16) hipLaunchKernelGGL(gemm_nt_kernel<uint16_t>, dim3(tiles, g.nz), dim3(kThreads), shmem, s, a);
   else hipLaunchKernelGGL(gemm_nt_kernel<float>, dim3(tiles, g.nz * a.ksplit), dim3(kThreads), shmem, s, a);
-  return hipGetLastError();
+  return sum_parts(a, s);
 }
 
 

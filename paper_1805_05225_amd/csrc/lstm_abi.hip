@@ -26,7 +26,8 @@ struct Plan {
   size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
   // workspace
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
-      ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, ws_Wcat, ws_Acat, workspace_bytes;
+      ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, ws_Wcat, ws_Acat, ws_parts, workspace_bytes;
+  int ks_dwx, ks_dwh;                       // K ranges of the weight-gradient products (few output tiles: the whole device works on them)
   bool single_step; int Kc, ksplit;         // T == 1 inference in bfloat16: the step is one product over [x | h], K cut in ksplit ranges
   bool fast_gemm; int n_in_pad; long TBp;   // bf16 products through the k-contiguous kernel (operands transposed once)
   size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems, Wf_bytes;
@@ -110,6 +111,16 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ws_count = take(fg ? 256 : 0);
   p->ws_Wcat = take(p->single_step ? D * 4 * n * p->Kc * 2 : 0);
   p->ws_Acat = take(p->single_step ? D * B * p->Kc * 2 : 0);
+  // weight-gradient products with few output tiles cut K into ranges whose partial results are summed afterwards
+  const auto ksplit_for = [&](long M, long N) {
+    const long tiles = (long)cdiv(M, 256) * cdiv(N, 256) * p->D;
+    const long want = 256 / (tiles > 0 ? tiles : 1);
+    const long most = p->TBp / 4096 > 0 ? p->TBp / 4096 : 1;        // every range keeps a long k loop
+    return (int)std::max(1L, std::min(std::min(want, most), 8L));
+  };
+  p->ks_dwx = fg && !infer ? ksplit_for(d->n_in, 4L * d->n) : 1;
+  p->ks_dwh = fg && !infer ? ksplit_for(d->n, 4L * d->n) : 1;
+  p->ws_parts = take(std::max(p->ks_dwx > 1 ? D * p->ks_dwx * d->n_in * 4 * n * 4 : 0, p->ks_dwh > 1 ? D * p->ks_dwh * n * 4 * n * 4 : 0));
   p->workspace_bytes = o + kAlign;
   return LSTM_OK;
 }
@@ -483,13 +494,6 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     Phase ph(LSTM_PHASE_PREP, 1, s);
     HIPCHK(launch_frame_map(seq_lens, p.T, p.B, cidx, fidx, count, s));
   }
-  // weight-gradient products with few output tiles split K so that the whole device works on them
-  const auto ksplit_for = [&](int M, int N) {
-    const long tiles = (long)cdiv(M, 256) * cdiv(N, 256) * p.D;
-    const long want = 256 / (tiles > 0 ? tiles : 1);
-    const long most = p.TBp / 4096 > 0 ? p.TBp / 4096 : 1;        // every range keeps a long k loop
-    return (int)std::max(1L, std::min(std::min(want, most), 8L));
-  };
   if (dx) {                        // dX = sum over directions of DZ W_x^T
     GemmArgs g = {};
     g.A = DZ; g.B = W_x; g.C = dx;
@@ -521,8 +525,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false; g.accumulate = acc;
       g.vecA = 16; g.vecB = 16;
       if (compact_w) g.k_dev = count + 1;
-      if (gemm_nt_ok(g) && (g.ksplit = ksplit_for(g.M, g.N)) > 1 && !acc)
-        HIPCHK(launch_fill_zero(dW_x, D * n_in * 4 * n * 4, s));
+      if (gemm_nt_ok(g) && p.ks_dwx > 1) { g.ksplit = p.ks_dwx; g.parts = (float*)(ws + p.ws_parts); }
       HIPCHK(launch_gemm(g, s));
     }
     {
@@ -536,8 +539,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false; g.accumulate = acc;
       g.vecA = 16; g.vecB = 16;
       if (compact_w) g.k_dev = count + 1;
-      if (gemm_nt_ok(g) && (g.ksplit = ksplit_for(g.M, g.N)) > 1 && !acc)
-        HIPCHK(launch_fill_zero(dW_h, D * n * 4 * n * 4, s));
+      if (gemm_nt_ok(g) && p.ks_dwh > 1) { g.ksplit = p.ks_dwh; g.parts = (float*)(ws + p.ws_parts); }
       HIPCHK(launch_gemm(g, s));
     }
   } else {                         // dW_x = X^T DZ, padded frames of X masked out
