@@ -24,6 +24,7 @@
 // grid always drains.  The launch is cooperative, which guarantees that all work-groups are
 // resident together (otherwise the launch is refused and the caller uses the per-step kernels).
 #include "recurrent_dev.h"
+#include <algorithm>
 #include <map>
 #include <mutex>
 
@@ -326,7 +327,7 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
   __shared__ unsigned short hb[16][18];
   const WgCoord wg = wg_coord();
   const PFwdDir& d = a.d[wg.dir];
-  const int tile = wg.tile, rt = wg.rt, ntiles = gridDim.x;
+  const int tile = wg.tile, rt = a.rt0 + wg.rt, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   unsigned* err = a.sync;
@@ -449,7 +450,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   __shared__ unsigned short hb[8][2][18];
   const WgCoord wg = wg_coord();
   const PFwdDir& d = a.d[wg.dir];
-  const int tile2 = wg.tile, rt = wg.rt >> 1, half = wg.rt & 1;
+  const int tile2 = wg.tile, rt = a.rt0 + (wg.rt >> 1), half = wg.rt & 1;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   const int ntiles16 = (n + 15) / 16;
@@ -633,7 +634,7 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
   __shared__ unsigned short zb[16][66];
   const WgCoord wg = wg_coord();
   const PBwdDir& d = a.d[wg.dir];
-  const int tile = wg.tile, rt = wg.rt, ntiles = gridDim.x;
+  const int tile = wg.tile, rt = a.rt0 + wg.rt, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   unsigned* err = a.sync;
@@ -779,7 +780,7 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
   __shared__ unsigned short zb[8][2][66];
   const WgCoord wg = wg_coord();
   const PBwdDir& d = a.d[wg.dir];
-  const int tile2 = wg.tile, rt = wg.rt >> 1, half = wg.rt & 1;
+  const int tile2 = wg.tile, rt = a.rt0 + (wg.rt >> 1), half = wg.rt & 1;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
   const int ntiles16 = (n + 15) / 16;
@@ -926,7 +927,7 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
       float sum = 0.f;
 #pragma unroll
       for (int rr = 0; rr < 8; ++rr) sum += dbred[rr][q * 32 + uu];
-      if (jj < n) d.dbpart[(long)wg.rt * 4 * n + q * n + jj] = sum;
+      if (jj < n) d.dbpart[(long)(2 * a.rt0 + wg.rt) * 4 * n + q * n + jj] = sum;
     }
   }
 }
@@ -955,7 +956,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned short zb[8][136];
   const WgCoord wg = wg_coord();
   const PBwdDir& d = a.d[wg.dir];
-  const int J = wg.tile, R = wg.rt, ntile2 = gridDim.x;
+  const int J = wg.tile, R = 2 * a.rt0 + wg.rt, ntile2 = gridDim.x;     // R: row group of 8 rows, counted over the whole batch
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = a.n, B = a.B, T = a.T;
   unsigned* err = a.sync;
@@ -1002,7 +1003,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   // producer side: lanes 0..31 hold rows 4*(lane/16) .. +3 of output column lane%16 of each accumulator tile
   const int pg = (lane >> 4) & 1, pcol = lane & 15;
   const bool local = a.xcc != nullptr &&
-                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + R) * ntile2, ntile2, J, a.spin_limit);
+                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * ntile2, ntile2, J, a.spin_limit);
 
   PROF_DECL
   for (int tau = T - 1; tau >= -1; --tau) {
@@ -1227,7 +1228,10 @@ __global__ void pack_state_ll_kernel(const float* h, uint4* ring0, uint4* ring1,
   ((unsigned long long*)ring1)[idx] = 0ull;
 }
 
-// Cooperative launch; refuses (without launching) a grid that cannot be resident all at once.
+std::mutex g_capacity_mu;
+std::map<const void*, int> g_capacity;    // kernel -> work-groups of it the current device holds at once
+
+// Can `grid` be resident all at once (the condition of a cooperative launch)?
 template <typename K>
 bool fits_device(K kernel, dim3 grid) {
   static std::mutex mu;
@@ -1244,40 +1248,74 @@ bool fits_device(K kernel, dim3 grid) {
     }
     it = cache.emplace((const void*)kernel, per_cu * prop.multiProcessorCount).first;
   }
+  { std::lock_guard<std::mutex> l2(g_capacity_mu); g_capacity[(const void*)kernel] = it->second; }
   return (long)grid.x * grid.y * grid.z <= it->second;
 }
-template <typename K, typename A>
-hipError_t coop(K kernel, dim3 grid, const A& a, hipStream_t s) {
-  if (!fits_device(kernel, grid)) return hipErrorCooperativeLaunchTooLarge;
-  A copy = a;
-  void* args[] = {&copy};
-  return hipLaunchCooperativeKernel((const void*)kernel, grid, dim3(256), args, 0, s);
+int capacity_of(const void* kernel) {
+  std::lock_guard<std::mutex> lock(g_capacity_mu);
+  auto it = g_capacity.find(kernel);
+  return it == g_capacity.end() ? 0 : it->second;
 }
+// How many work-groups of `kernel` the device holds at once (0 if that cannot be found out).
+template <typename K>
+int capacity(K kernel) { return fits_device(kernel, dim3(1, 1, 1)) ? capacity_of((const void*)kernel) : 0; }
 
-dim3 grid8(const PBwdArgs& a) { return dim3(cdiv(cdiv(a.n, 16), 2), 2 * cdiv(a.B, 16), a.ndir); }
+// Cooperative launches over the batch in slabs of whole 16-row tiles.  A work-group owns `rows_per_y` rows (16 or 8),
+// so one row tile takes grid.x * (16 / rows_per_y) * ndir work-groups; as many row tiles as the device can hold at
+// once go into one launch (the kernels need every work-group of a launch resident together), the rest follow in
+// further launches on the same stream: batch rows never interact, each launch walks all T steps of its rows.
+// Between launches the table in which exchange groups record their XCD is cleared again.  Returns
+// hipErrorCooperativeLaunchTooLarge without launching anything if not even one row tile fits.
+template <typename K, typename A>
+hipError_t coop_slabs(K kernel, int grid_x, int rows_per_y, const A& a, hipStream_t s) {
+  const int per_rt = 16 / rows_per_y, nrt = cdiv(a.B, 16);
+  const long cap = capacity(kernel);
+  const long slab = cap / ((long)grid_x * per_rt * a.ndir);            // row tiles per launch
+  if (slab < 1) return hipErrorCooperativeLaunchTooLarge;
+  for (int rt0 = 0; rt0 < nrt; rt0 += (int)slab) {
+    A copy = a;
+    copy.rt0 = rt0;
+    const int here = (int)std::min<long>(slab, nrt - rt0);
+    const dim3 grid(grid_x, per_rt * here, a.ndir);
+    if (rt0 > 0 && a.xcc) {
+      const hipError_t e = launch_fill_zero(a.xcc, (size_t)grid_x * per_rt * slab * a.ndir * 4, s);
+      if (e != hipSuccess) return e;
+    }
+    void* args[] = {&copy};
+    const hipError_t e = hipLaunchCooperativeKernel((const void*)kernel, grid, dim3(256), args, 0, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+template <typename K>
+bool slab_fits(K kernel, int grid_x, int rows_per_y, int ndir) {
+  return capacity(kernel) >= (long)grid_x * (16 / rows_per_y) * ndir;
+}
 
 }  // namespace
 
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
   if (a.nkc > kLLMaxNkcFwd) return hipErrorCooperativeLaunchTooLarge;
   // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
-  hipError_t e = coop(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, dim3(cdiv(cdiv(a.n, 16), 2), 2 * cdiv(a.B, 16), a.ndir), a, s);
-  if (e == hipSuccess) return e;
+  hipError_t e = coop_slabs(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, cdiv(cdiv(a.n, 16), 2), 8, a, s);
+  if (e != hipErrorCooperativeLaunchTooLarge) return e;
   (void)hipGetLastError();
-  return coop(persist_fwd_kernel<kLLMaxNkcFwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
+  return coop_slabs(persist_fwd_kernel<kLLMaxNkcFwd / 4>, cdiv(a.n, 16), 16, a, s);
 }
 int persist_bwd_variant(const PBwdArgs& a) {
-  if (a.n <= 1024 && fits_device(persist_bwdp_kernel<8>, grid8(a))) return kBwdPartialSums;
+  const int t32 = cdiv(cdiv(a.n, 16), 2);
+  if (a.n <= 1024 && slab_fits(persist_bwdp_kernel<8>, t32, 8, a.ndir)) return kBwdPartialSums;
   if (a.nkc > kLLMaxNkcBwd) return kBwdNone;
-  if (fits_device(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, grid8(a))) return kBwdDz8;
-  if (fits_device(persist_bwd_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir))) return kBwdDz16;
+  if (slab_fits(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, t32, 8, a.ndir)) return kBwdDz8;
+  if (slab_fits(persist_bwd_kernel<kLLMaxNkcBwd / 4>, cdiv(a.n, 16), 16, a.ndir)) return kBwdDz16;
   return kBwdNone;
 }
 hipError_t launch_persist_bwd(const PBwdArgs& a, int variant, hipStream_t s) {
+  const int t32 = cdiv(cdiv(a.n, 16), 2);
   switch (variant) {
-    case kBwdPartialSums: return coop(persist_bwdp_kernel<8>, grid8(a), a, s);
-    case kBwdDz8: return coop(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, grid8(a), a, s);
-    case kBwdDz16: return coop(persist_bwd_kernel<kLLMaxNkcBwd / 4>, dim3(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), a, s);
+    case kBwdPartialSums: return coop_slabs(persist_bwdp_kernel<8>, t32, 8, a, s);
+    case kBwdDz8: return coop_slabs(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, t32, 8, a, s);
+    case kBwdDz16: return coop_slabs(persist_bwd_kernel<kLLMaxNkcBwd / 4>, cdiv(a.n, 16), 16, a, s);
     default: return hipErrorCooperativeLaunchTooLarge;
   }
 }

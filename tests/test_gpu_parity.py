@@ -209,7 +209,8 @@ def test_accumulate_flag_adds_into_gradients():
 
 
 # ---- the single-launch recurrent kernels against one launch per time step ------------------------------------
-@pytest.mark.parametrize("dt,B,n,T", [("bf16", 32, 64, 40), ("f32", 5, 20, 9), ("bf16", 70, 136, 25), ("bf16", 32, 1024, 12), ("bf16", 19, 1000, 7)])
+@pytest.mark.parametrize("dt,B,n,T", [("bf16", 32, 64, 40), ("f32", 5, 20, 9), ("bf16", 70, 136, 25), ("bf16", 32, 1024, 12), ("bf16", 19, 1000, 7),
+                                      ("bf16", 64, 1000, 9), ("bf16", 41, 1024, 6), ("bf16", 150, 264, 8)])
 def test_single_launch_equals_per_step(dt, B, n, T):
     rng = np.random.default_rng(B * n + T)
     lens = rng.integers(0, T + 1, B)
