@@ -58,6 +58,7 @@ struct GemmArgs {
   const int* a_rows; const int* c_rows;   // logical row r of A / C lives at physical row a_rows[r] / c_rows[r]
   int a_phys_rows;                        // rows of A in memory when a_rows is given
   const int* m_dev; const int* k_dev;     // M / K read from device memory (capped by M / K above, which size the grid)
+  const int* k_rows; int k_phys_rows;     // k-major kernel only: k -> row of A and of B in memory; rows each holds in memory
   int ksplit;                             // > 1: K cut into that many ranges whose parts are ADDED to C atomically
                                           // (float C, nseg == 1; C must hold zeros or the value to add to) ...
   float* parts;                           // ... or, if not NULL (nz * ksplit * M * ldc floats, no c_rows): every range stores
@@ -68,6 +69,10 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 // (launch_gemm routes such problems to it by itself).
 bool gemm_nt_ok(const GemmArgs& g);
 hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s);
+// Fast bfloat16 kernel for the opposite storage: both operands k-major (A[K][lda], B[K][ldb], 16-byte aligned rows),
+// float C.  Row k of both operands is row k_rows[k] in memory if k_rows is given (launch_gemm routes to it by itself).
+bool gemm_tn_ok(const GemmArgs& g);
+hipError_t launch_gemm_tn(const GemmArgs& g, hipStream_t s);
 // dst[c][r] = src[r][c] (16-bit elements), r < R, c < C, dst rows zero-padded up to ld_dst; nz problems with
 // strides s_src / s_dst.  lens != NULL: rows of src are frames (t = r / Bt, b = r % Bt) and are read as zero
 // unless t < lens[b].  With cidx / fidx / count from launch_frame_map the kept frames are packed instead: column

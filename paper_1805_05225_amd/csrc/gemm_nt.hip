@@ -38,6 +38,7 @@ struct NtArgs {
   int nseg; long sAseg, sBseg;
   int accumulate;
   const int* a_rows; const int* c_rows;   // logical row -> physical row of A / of C (NULL: identity)
+  const int* k_rows; int k_phys_rows;     // k-major kernel: k -> row of A and B in memory (NULL: identity), rows in memory
   const int* m_dev; const int* k_dev;     // device-resident M / K (NULL: use M / K above)
   int a_phys_rows;                        // rows of A in memory when a_rows is given
   int ksplit;                             // > 1: K is cut into that many ranges, each adds its part to C atomically ...
@@ -484,6 +485,174 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
   store_tile<TC, TN>(acc, lds, g, M, m0, n0, z, ks, ksplit);
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The weight-gradient shape, C[M,N] = sum_k A[k][m] B[k][n] with BOTH operands stored k-major (a row per frame:
+// dW_x = X^T DZ, dW_h = Hprev^T DZ; float C), without transposing anything in memory.  Same tile, wavefront
+// layout, stage pipeline and epilogue as gemm_dl_body; what differs is how a stage sits in LDS and how MFMA
+// fragments leave it:
+//   * a stage is 64 k-rows of 256 columns (512 bytes) per operand; a wavefront-load brings two whole rows (full
+//     lines).  Row k may be any row of the operand in memory (`k_rows`: the packed list of real frames), looked up
+//     one stage ahead of the load that needs it;
+//   * MFMA wants, per lane, 8 consecutive k of ONE column, which in a k-major tile are 512 bytes apart.  The LDS
+//     transpose read (8 bytes per lane, 16-bit elements) does that turn inside each group of 16 lanes: lane s
+//     supplies the address of row kbase + s/4, columns cbase + 4*(s%4) .. +3, and lane l receives column cbase + l
+//     of rows kbase .. kbase+3 (layout measured on the device).  Two such reads make one MFMA operand;
+//   * the four rows a 16-lane group reads together lie 512 bytes apart, i.e. in the same banks; so the 64-byte
+//     blocks of row k are stored XORed with k % 4 (again by choosing which global chunk a loading lane fetches).
+template <typename TC>
+__device__ __forceinline__ void gemm_tn_body(const NtArgs& g) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int TN = 2, WN = 4, NW = 8, NLD = 4;               // 8 wavefronts of 128x64; 4 wavefront-loads per operand
+  constexpr int kRow = 512;                                    // bytes per k-row of a stage (256 columns)
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+
+  const TileCoord tc = tile_coord(g);
+  if (!tc.live) return;
+  const int M = tc.M, K = tc.K, m0 = tc.m0, n0 = tc.n0, z = tc.z, ks = tc.ks, ksplit = tc.ksplit;
+
+  f32x16 acc[4][TN];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nstage = (K + kKB - 1) / kKB;                      // rows past K arrive as zeros
+  const int it0 = (int)((long)nstage * ks / ksplit);
+  const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
+
+  // Loads.  Wavefront-load i of this wavefront fills k-rows 2*(i*NW + wave) and +1 of the stage; lane l fills
+  // 16-byte slot l % 32 of row l / 32, i.e. fetches column chunk (l % 32) ^ 4*(k % 4).
+  const int krow_in_stage = 2 * wave + (lane >> 5);            // + 2*NW*i
+  const int chunk = (lane & 31) ^ (4 * (krow_in_stage & 3));   // 2*NW*i is a multiple of 4
+  const bool a_col_ok = m0 + chunk * 8 < M, b_col_ok = n0 + chunk * 8 < g.N;
+  const long a_col = ((long)m0 + chunk * 8) * 2, b_col = ((long)n0 + chunk * 8) * 2;
+  const long a_rows_mem = g.k_rows ? g.k_phys_rows : K;
+  const long a_bytes = a_rows_mem * g.lda * 2, b_bytes = a_rows_mem * g.ldb * 2;
+  const unsigned a_rec = a_bytes > 0x7fffffffL ? 0x7fffffffu : (unsigned)a_bytes, b_rec = b_bytes > 0x7fffffffL ? 0x7fffffffu : (unsigned)b_bytes;
+  const u32x4 ra = make_rsrc(g.A + g.sAz * z * 2, a_rec), rb = make_rsrc(g.B + g.sBz * z * 2, b_rec);
+  const unsigned lds_base = (unsigned)(unsigned long long)(__attribute__((address_space(3))) char*)lds;
+  // Memory rows of the stage whose loads go out next.  A wavefront-load covers rows k and k+1 of the list, the same
+  // for all lanes of a half, so the look-up is a scalar load of two consecutive entries - written as assembly and
+  // waited for by hand (together with the operand loads, before the barrier of the next stage): the compiler would
+  // wait for a look-up it knows about right where it is issued, and with vector loads that wait would also
+  // cover every operand load in flight.  The list must be readable up to the next multiple of 64 entries.
+  typedef __attribute__((ext_vector_type(2))) int i32x2;
+  i32x2 prow2[NLD];
+  int pk0 = 0;
+  auto lookup = [&](int rel_it) __attribute__((always_inline)) {
+    pk0 = (it0 + rel_it) * kKB + krow_in_stage;                // k of wavefront-load 0 for this lane; load i adds 2 * NW * i
+    if (g.k_rows && rel_it < total) {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int* p = g.k_rows + (long)(it0 + rel_it) * kKB + 2 * (NW * i + wave);
+        asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(prow2[i]) : "s"(p) : "memory");
+      }
+    }
+  };
+  auto row_of = [&](int i) __attribute__((always_inline)) {
+    return g.k_rows ? ((lane >> 5) ? prow2[i][1] : prow2[i][0]) : pk0 + 2 * NW * i;
+  };
+  auto issue = [&](int buf, int first, int last) __attribute__((always_inline)) {
+    const unsigned dst = lds_base + buf * kDlStage + wave * 1024;
+#pragma unroll
+    for (int q = 0; q < 2 * NLD; ++q) {
+      if (q < first || q >= last) continue;
+      const int i = q >> 1;
+      const int row = row_of(i);
+      const bool row_ok = pk0 + 2 * NW * i < K && row >= 0 && row < a_rows_mem;
+      if (q & 1) {
+        const long o = (long)row * g.ldb * 2 + b_col;
+        load_to_lds_b128(rb, dst + kDlOp + i * NW * 1024, (row_ok && b_col_ok && o <= 0x7ffffff0L) ? (unsigned)o : 0x7ffffff0u, 0);
+      } else {
+        const long o = (long)row * g.lda * 2 + a_col;
+        load_to_lds_b128(ra, dst + i * NW * 1024, (row_ok && a_col_ok && o <= 0x7ffffff0L) ? (unsigned)o : 0x7ffffff0u, 0);
+      }
+    }
+  };
+  constexpr int NQ = 2 * NLD;
+
+  // Fragment reads (see the head of this function).  Lane L = 32*kg + 16*grp + l: source row kg*8 + l/4 (+4 for the
+  // second read) of the 16-row k-step, columns block*32 + grp*16 + 4*(l%4) .. +3, 64-byte blocks XORed with row % 4.
+  const int l16 = lane & 15, grp = (lane >> 4) & 1, kg = lane >> 5;
+  const int fr_row = (kg * 8 + (l16 >> 2)) * kRow, fr_sw = (l16 >> 2) & 3, fr_low = grp * 32 + (l16 & 3) * 8;
+  int fa_off[4], fb_off[TN];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fa_off[i] = fr_row + ((((wm * 4 + i) ^ fr_sw) & 7) << 6) + fr_low;          // column block wm*4 + i of 8
+#pragma unroll
+  for (int j = 0; j < TN; ++j) fb_off[j] = kDlOp + fr_row + ((((wn * TN + j) ^ fr_sw) & 7) << 6) + fr_low;
+  typedef __attribute__((ext_vector_type(4))) short s16x4;
+  uint4 fa[2][4], fb[2][TN];
+  auto tr_read = [&](const char* p) __attribute__((always_inline)) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * kRow));
+    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+    return make_uint4(l2.x, l2.y, h2.x, h2.y);
+  };
+  auto read_frags = [&](int buf, int s, int c) __attribute__((always_inline)) {
+    const char* base = lds + buf * kDlStage + s * 16 * kRow;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[c][i] = tr_read(base + fa_off[i]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[c][j] = tr_read(base + fb_off[j]);
+  };
+  auto kstep = [&](int c, bool ld, int ld_buf) __attribute__((always_inline)) {
+    int q = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
+        if (((i * TN + j) & 1) && q < NQ) {
+          if (ld) issue(ld_buf, q, q + 1);
+          ++q;
+        }
+      }
+    if (q < NQ && ld) issue(ld_buf, q, NQ);
+  };
+
+  if (total > 0) {
+    lookup(0);
+    __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the look-up
+    issue(0, 0, NQ);
+    lookup(1);
+    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0)
+    __syncthreads();
+    if (total > 1) issue(1, 0, NQ);
+    lookup(2);
+    read_frags(0, 0, 0);
+  }
+  for (int it = 0; it < total; ++it) {
+    const int cur = it & 1;
+    read_frags(cur, 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(0, false, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(cur, 2, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(1, false, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(cur, 3, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(0, false, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (it + 1 < total) {
+      __builtin_amdgcn_s_waitcnt(0x0070);          // vmcnt(0) lgkmcnt(0): own loads of stage it+1 (and row look-ups) landed, own reads done
+      __syncthreads();
+      read_frags(cur ^ 1, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(1, it + 2 < total, cur);                 // loads of stage it+2 (rows looked up during the previous stage)
+    __builtin_amdgcn_sched_barrier(0);
+    lookup(it + 3);
+  }
+  store_tile<TC, TN>(acc, lds, g, M, m0, n0, z, ks, ksplit);
+}
+__global__ __launch_bounds__(512, 1) void gemm_tn8_f32_kernel(NtArgs g) { gemm_tn_body<float>(g); }
+
 // (kernels with literal launch bounds: a bound that depends on a template parameter loses the host-side stub)
 __global__ __launch_bounds__(512, 1) void gemm_dl8_f32_kernel(NtArgs g) { gemm_dl_body<float, 2>(g); }
 __global__ __launch_bounds__(512, 1) void gemm_dl8_bf16_kernel(NtArgs g) { gemm_dl_body<uint16_t, 2>(g); }
@@ -683,6 +852,37 @@ static hipError_t sum_parts(const NtArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(sum_parts_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, a.parts, (float*)a.C, a.M, a.N, a.ldc, a.sCz, a.sPart, a.ksplit,
                      a.accumulate, total);
   return hipGetLastError();
+}
+
+bool gemm_tn_ok(const GemmArgs& g) {
+  const auto a16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
+  const long lim = 0x7fffff00L;     // operands are addressed with 32-bit byte offsets
+  const long rows = g.k_rows ? g.k_phys_rows : g.K;
+  if (rows * g.lda * 2 > lim || rows * g.ldb * 2 > lim) return false;
+  return g.in_bf16 && !g.out_bf16 && !g.a_kcontig && !g.b_kcontig && !g.lens && g.nseg == 1 && !g.a_rows && !g.c_rows && !g.m_dev &&
+         g.lda % 8 == 0 && g.ldb % 8 == 0 && g.sAz % 8 == 0 && g.sBz % 8 == 0 && a16(g.A) && a16(g.B);
+}
+
+hipError_t launch_gemm_tn(const GemmArgs& g, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0 || g.nz <= 0) return hipSuccess;
+  NtArgs a = {};
+  a.A = (const char*)g.A; a.B = (const char*)g.B; a.C = g.C; a.bias = g.bias;
+  a.M = g.M; a.N = g.N; a.K = g.K; a.lda = g.lda; a.ldb = g.ldb; a.ldc = g.ldc;
+  a.sAz = g.sAz; a.sBz = g.sBz; a.sCz = g.sCz; a.sbiasz = g.sbiasz; a.nz = g.nz; a.nseg = 1;
+  a.accumulate = g.accumulate; a.k_dev = g.k_dev; a.k_rows = g.k_rows; a.k_phys_rows = g.k_phys_rows;
+  a.ksplit = g.ksplit > 1 ? g.ksplit : 1;
+  a.parts = a.ksplit > 1 ? g.parts : nullptr; a.sPart = (long)g.M * g.ldc;
+  const int sups = cdiv(cdiv(g.M, kT), kSupM) * cdiv(cdiv(g.N, kT), kSupN);
+  a.blocked = sups >= 32 ? 1 : 0;
+  const int tiles = a.blocked ? cdiv(sups, 8) * 8 * kSupM * kSupN : cdiv(g.M, kT) * cdiv(g.N, kT);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute((const void*)gemm_tn8_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(gemm_tn8_f32_kernel, dim3(tiles, g.nz * a.ksplit), dim3(512), kDlLds, s, a);
+  return sum_parts(a, s);
 }
 
 hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {

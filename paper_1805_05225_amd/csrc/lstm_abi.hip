@@ -510,7 +510,31 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     }
     HIPCHK(launch_gemm(g, s));
   }
-  if (p.fast_gemm) {               // weight gradients with operands transposed once: everything k-contiguous
+  // Weight gradients straight from the frame-major tensors (a row per frame in X, Hprev and DZ: both operands of
+  // X^T DZ are k-major), over the packed list of real frames when lengths are given.
+  auto frame_major = [&](const void* A, long lda, long sAz, int M, void* C, int ks) {
+    GemmArgs g = {};
+    g.A = A; g.B = DZ; g.C = C;
+    g.M = M; g.N = 4 * p.n; g.K = (int)TB; g.lda = lda; g.ldb = 4 * n; g.ldc = 4 * n;
+    g.sAz = sAz; g.sBz = (long)p.DZ_dir_elems; g.sCz = (long)M * 4 * n; g.nz = p.D; g.nseg = 1;
+    g.a_kcontig = false; g.b_kcontig = false; g.in_bf16 = true; g.out_bf16 = false; g.accumulate = acc;
+    g.vecA = 16; g.vecB = 16;
+    if (compact) { g.k_rows = fidx; g.k_phys_rows = (int)TB; g.k_dev = count; }
+    if (ks > 1) { g.ksplit = ks; g.parts = (float*)(ws + p.ws_parts); }
+    return g;
+  };
+  const GemmArgs gx = frame_major(x, n_in, 0, p.n_in, dW_x, p.ks_dwx);
+  const GemmArgs gh = frame_major(rs + p.res_hprev, n, (long)(p.res_dir_stride / 2), p.n, dW_h, p.ks_dwh);
+  if (p.fast_gemm && (!seq_lens || compact) && gemm_tn_ok(gx) && gemm_tn_ok(gh)) {
+    {
+      Phase ph(LSTM_PHASE_GEMM_DWX, 1, s);
+      HIPCHK(launch_gemm(gx, s));
+    }
+    {
+      Phase ph(LSTM_PHASE_GEMM_DWH, 1, s);
+      HIPCHK(launch_gemm(gh, s));
+    }
+  } else if (p.fast_gemm) {        // operands transposed once: everything k-contiguous
     const long TBp = p.TBp;
     {
       Phase ph(LSTM_PHASE_GEMM_DWX, 3, s);
