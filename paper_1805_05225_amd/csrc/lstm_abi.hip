@@ -86,7 +86,9 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   // T == 1 inference, bfloat16: few output tiles, so K is cut into ranges that separate work-groups multiply (each at
   // least four 64-wide stages); their partial products lie side by side and the cell kernel adds them
   p->single_step = p->bf16 && d->n % 2 == 0 && infer && d->T == 1 && !(d->flags & LSTM_FLAG_PER_STEP);
-  p->n_in_pad = (d->n_in + 7) / 8 * 8;
+  // k extent of the input projection: a multiple of 8 (16-byte rows), and for narrow inputs a multiple of 64 so that
+  // the product runs through the kernel that loads straight into LDS (x is then copied into zero-padded rows)
+  p->n_in_pad = d->n_in < 256 ? (d->n_in + 63) / 64 * 64 : (d->n_in + 7) / 8 * 8;
   {
     const long tiles = (long)cdiv(B > 0 ? B : 1, 256) * cdiv(4L * d->n, 256) * p->D;
     const long stages = cdiv((long)p->n_in_pad + d->n, 64);
@@ -97,11 +99,10 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ws_colsum = take(infer ? 0 : D * 64 * 4 * n * 4);
   // transposed / padded operand copies for the fast bf16 products
   p->fast_gemm = p->bf16 && d->n % 2 == 0;
-  p->n_in_pad = (d->n_in + 7) / 8 * 8;
   p->TBp = (TB + 63) / 64 * 64;
   const bool fg = p->fast_gemm;
   p->ws_WxT = take(fg ? D * 4 * n * p->n_in_pad * 2 : 0);
-  p->ws_xpad = take(fg && d->n_in % 8 ? TB * p->n_in_pad * 2 : 0);
+  p->ws_xpad = take(fg && p->n_in_pad != d->n_in ? TB * p->n_in_pad * 2 : 0);
   p->ws_XT = take(fg && !infer ? (size_t)d->n_in * p->TBp * 2 : 0);
   p->ws_DZT = take(fg && !infer ? D * 4 * n * p->TBp * 2 : 0);
   p->ws_HT = take(fg && !infer ? D * n * p->TBp * 2 : 0);
@@ -264,7 +265,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       if (p.fast_gemm) {                 // W_x is transposed once so that both operands are k-contiguous
         HIPCHK(launch_transpose(W_x, ws + p.ws_WxT, p.n_in, 4 * p.n, 4 * n, p.n_in_pad, p.D, (long)p.n_in * 4 * n,
                                 (long)(4 * n) * p.n_in_pad, nullptr, 1, 0, s));
-        if (p.n_in % 8) {                // rows of x are not 16-byte aligned: padded copy
+        if (p.n_in_pad != p.n_in) {      // rows of x are not 16-byte aligned, or narrow: zero-padded copy
           HIPCHK(launch_pad_rows(x, ws + p.ws_xpad, (long)(T * B), p.n_in, p.n_in_pad, s));
           g.A = ws + p.ws_xpad;
         }
