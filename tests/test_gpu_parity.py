@@ -310,6 +310,29 @@ def test_config4_first_layer_full_size():
 
 
 
+def test_config4_deeper_layer_full_size_sampled_rows():
+    """A layer k > 1 of config 4 at its full size (n_in = 2n = 2048, T = 1491, B = 32, n = 1024, bf16), i.e. the products
+    of the benchmark's five upper layers in the benchmark's launch configuration.  The oracle cannot do all 31 597 frames of
+    that shape in test time, but batch rows never interact, so it computes the two shortest rows one by one (as batches of
+    one row cut to their length) and every output that belongs to a row - y, c, hT, cT, dx - is compared for them."""
+    inp = synth.make(4, layers=1, n_in=2048)
+    c = _config_case(inp)
+    lens = inp["seq_lens"]
+    print("  config 4, deeper layer, full size: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
+    f, g = run_gpu(c, "bf16", True)
+    for b in np.argsort(lens)[:2]:
+        L = int(lens[b])
+        one = dict(c, x=c["x"][:L, b:b + 1], dy=c["dy"][:L, b:b + 1], lens=np.array([L], dtype=np.int32))
+        fo, go = run_oracle(one, True)
+        print("  row %d (length %d)" % (b, L), flush=True)
+        check("y", f["y"][:L, b:b + 1], fo[0], TOL["bf16"])
+        check("c", f["c"][:, :L, b:b + 1], fo[1], TOL["bf16"])
+        check("hT", f["hT"][:, b:b + 1], fo[2], TOL["bf16"])
+        check("cT", f["cT"][:, b:b + 1], fo[3], TOL["bf16"])
+        check("dx", g["dx"][:L, b:b + 1], go[0], TOL["bf16"])
+        assert float(f["y"][L:, b].float().abs().max()) == 0.0 and float(g["dx"][L:, b].float().abs().max()) == 0.0
+
+
 @pytest.mark.parametrize("bidir,B,n_in,n", [(False, 70, 37, 50), (True, 33, 24, 18), (False, 300, 136, 100), (False, 1, 5, 6)])
 def test_single_step_cell_bf16(bidir, B, n_in, n):
     """T = 1 in inference mode (the stepped decoder cell runs as one product over [x | h]): three chained steps with
