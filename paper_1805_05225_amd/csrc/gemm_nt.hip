@@ -93,10 +93,11 @@ __device__ __forceinline__ void commit(const uint4 (&st)[8], char* lds, int tid)
 }
 
 // What every kernel variant needs to know about its tile.
-struct TileCoord { int M, K, m0, n0, z, ks, ksplit; bool live; };
+struct TileCoord { int M, K, m0, n0, z, ks, ksplit, pos; bool live; };
 __device__ __forceinline__ TileCoord tile_coord(const NtArgs& g) {
   TileCoord t;
   t.live = false;
+  t.pos = 0;                                        // place inside the XCD's block of tiles (blocked raster; else 0)
   t.M = g.m_dev ? min(g.M, *g.m_dev) : g.M;        // the grid is sized for g.M; surplus tiles leave at once
   t.K = g.k_dev ? min(g.K, *g.k_dev) : g.K;
   const int tiles_m = (g.M + kT - 1) / kT, tiles_n = (g.N + kT - 1) / kT;
@@ -112,6 +113,7 @@ __device__ __forceinline__ TileCoord tile_coord(const NtArgs& g) {
     if (sup >= sup_m * sup_n) return t;
     const int sn = sup % sup_n, sm = sup / sup_n;
     tm = sm * kSupM + pos / kSupN; tn = sn * kSupN + pos % kSupN;
+    t.pos = pos;
     if (tm >= tiles_m || tn >= tiles_n) return t;
   } else {
     // few tiles: bands of 8 tile columns, row-major inside a band; every XCD keeps one B tile column in its L2
@@ -383,18 +385,25 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
   // Loads.  Wavefront-load i of this wavefront fills rows 8 * (i * NW + wave) .. + 7 of an operand; lane l fills
   // slot l & 7 of row (l >> 3) of those, i.e. fetches k-chunk (l & 7) ^ swizzle(row).  Rows past the operand's end
   // point outside the buffer descriptor and arrive as zeros.
-  unsigned voa[NLD], vob[NLD];
+  // The order in which a work-group asks for the row groups of a stage is rotated by its place in the XCD's block of
+  // tiles: the 4 (8) work-groups that share an A (B) panel each start with a different quarter (half) of it, so the
+  // first request for a line - the one that has to fetch it from beyond L2 - goes out early in every work-group's
+  // burst instead of all sharers asking for the same lines in the same order.
+  const int rotA = tc.pos % kSupN, rotB = (tc.pos / kSupN) >> 1;
+  unsigned voa[NLD], vob[NLD], lda_off[NLD], ldb_off[NLD];
   {
     const long a_rows_mem = g.a_rows ? g.a_phys_rows : M;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int rl = (i * NW + wave) * 8 + (lane >> 3);
-      const int chunk = (lane & 7) ^ ((rl >> 1) & 7);
+      const int ia = (i + rotA) % NLD, ib = (i + rotB) % NLD;
+      lda_off[i] = ia * NW * 1024; ldb_off[i] = kDlOp + ib * NW * 1024;
+      const int rl = (ia * NW + wave) * 8 + (lane >> 3), rlb = (ib * NW + wave) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((rl >> 1) & 7), chunkb = (lane & 7) ^ ((rlb >> 1) & 7);
       long ra = m0 + rl;
       if (g.a_rows) ra = ra < M ? (long)g.a_rows[ra] : 0x7fffffffL; else if (ra >= M) ra = 0x7fffffffL;
-      long rb = n0 + rl;
+      long rb = n0 + rlb;
       if (rb >= g.N) rb = 0x7fffffffL;
-      const long oa = (ra * g.lda) * 2 + chunk * 16, ob = (rb * g.ldb) * 2 + chunk * 16;
+      const long oa = (ra * g.lda) * 2 + chunk * 16, ob = (rb * g.ldb) * 2 + chunkb * 16;
       voa[i] = (ra >= a_rows_mem || oa > 0x7ffffff0L) ? 0x7ffffff0u : (unsigned)oa;
       vob[i] = (rb >= g.N || ob > 0x7ffffff0L) ? 0x7ffffff0u : (unsigned)ob;
     }
@@ -414,8 +423,8 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
     for (int q = 0; q < 2 * NLD; ++q) {
       if (q < first || q >= last) continue;
       const int i = q >> 1;
-      if (q & 1) load_to_lds_b128(rb, dst + kDlOp + i * NW * 1024, vob[i], koff);
-      else load_to_lds_b128(ra, dst + i * NW * 1024, voa[i], koff);
+      if (q & 1) load_to_lds_b128(rb, dst + ldb_off[i], vob[i], koff);
+      else load_to_lds_b128(ra, dst + lda_off[i], voa[i], koff);
     }
   };
   constexpr int NQ = 2 * NLD;                               // wavefront-loads per stage and wavefront
@@ -535,6 +544,10 @@ __device__ __forceinline__ void gemm_tn_body(const NtArgs& g) {
   const unsigned a_rec = a_bytes > 0x7fffffffL ? 0x7fffffffu : (unsigned)a_bytes, b_rec = b_bytes > 0x7fffffffL ? 0x7fffffffu : (unsigned)b_bytes;
   const u32x4 ra = make_rsrc(g.A + g.sAz * z * 2, a_rec), rb = make_rsrc(g.B + g.sBz * z * 2, b_rec);
   const unsigned lds_base = (unsigned)(unsigned long long)(__attribute__((address_space(3))) char*)lds;
+  // Work-groups that run side by side on an XCD all want the same 64 frame rows of a stage; each starts its burst
+  // of wavefront-loads with a different quarter of them, so that the first request for a line goes out early in
+  // some work-group's burst.
+  const int rot = (int)(blockIdx.x >> 3) % NLD;
   // Memory rows of the stage whose loads go out next.  A wavefront-load covers rows k and k+1 of the list, the same
   // for all lanes of a half, so the look-up is a scalar load of two consecutive entries - written as assembly and
   // waited for by hand (together with the operand loads, before the barrier of the next stage): the compiler would
@@ -548,13 +561,13 @@ __device__ __forceinline__ void gemm_tn_body(const NtArgs& g) {
     if (g.k_rows && rel_it < total) {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int* p = g.k_rows + (long)(it0 + rel_it) * kKB + 2 * (NW * i + wave);
+        const int* p = g.k_rows + (long)(it0 + rel_it) * kKB + 2 * (NW * ((i + rot) % NLD) + wave);
         asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(prow2[i]) : "s"(p) : "memory");
       }
     }
   };
   auto row_of = [&](int i) __attribute__((always_inline)) {
-    return g.k_rows ? ((lane >> 5) ? prow2[i][1] : prow2[i][0]) : pk0 + 2 * NW * i;
+    return g.k_rows ? ((lane >> 5) ? prow2[i][1] : prow2[i][0]) : pk0 + 2 * NW * ((i + rot) % NLD);
   };
   auto issue = [&](int buf, int first, int last) __attribute__((always_inline)) {
     const unsigned dst = lds_base + buf * kDlStage + wave * 1024;
@@ -562,14 +575,14 @@ __device__ __forceinline__ void gemm_tn_body(const NtArgs& g) {
     for (int q = 0; q < 2 * NLD; ++q) {
       if (q < first || q >= last) continue;
       const int i = q >> 1;
-      const int row = row_of(i);
-      const bool row_ok = pk0 + 2 * NW * i < K && row >= 0 && row < a_rows_mem;
+      const int row = row_of(i), ir = (i + rot) % NLD;
+      const bool row_ok = pk0 + 2 * NW * ir < K && row >= 0 && row < a_rows_mem;
       if (q & 1) {
         const long o = (long)row * g.ldb * 2 + b_col;
-        load_to_lds_b128(rb, dst + kDlOp + i * NW * 1024, (row_ok && b_col_ok && o <= 0x7ffffff0L) ? (unsigned)o : 0x7ffffff0u, 0);
+        load_to_lds_b128(rb, dst + kDlOp + ir * NW * 1024, (row_ok && b_col_ok && o <= 0x7ffffff0L) ? (unsigned)o : 0x7ffffff0u, 0);
       } else {
         const long o = (long)row * g.lda * 2 + a_col;
-        load_to_lds_b128(ra, dst + i * NW * 1024, (row_ok && a_col_ok && o <= 0x7ffffff0L) ? (unsigned)o : 0x7ffffff0u, 0);
+        load_to_lds_b128(ra, dst + ir * NW * 1024, (row_ok && a_col_ok && o <= 0x7ffffff0L) ? (unsigned)o : 0x7ffffff0u, 0);
       }
     }
   };
