@@ -208,6 +208,48 @@ def test_accumulate_flag_adds_into_gradients():
     assert torch.allclose(g2["db"], g["db"] + 3, atol=1e-5)
 
 
+def test_accumulate_with_split_k_bf16():
+    """bf16 storage with enough frames that the weight-gradient products cut K into ranges (partial results summed by a
+    second kernel): the accumulate flag must add the sum of the ranges to what the caller's buffers hold."""
+    rng = np.random.default_rng(48)
+    T, B, n_in, n = 300, 32, 24, 64
+    lens = rng.integers(T // 2, T + 1, B)
+    c = rnd_case(rng, T=T, B=B, n_in=n_in, n=n, D=2, lens=lens, dt="bf16", scale=0.1, with_state=False)
+    x, dy = dev(c["x"], "bf16"), dev(c["dy"], "bf16")
+    Wx, Wh, b = dev(c["W_x"], "bf16"), dev(c["W_h"], "bf16"), dev(c["b"])
+    ln = dev(c["lens"])
+    f = Bn.forward(x, Wx, Wh, b, None, None, ln, bidirectional=True)
+    g = Bn.backward(f, x, Wx, Wh, None, None, ln, dy)
+    acc = (torch.ones_like(g["dW_x"]), torch.full_like(g["dW_h"], 2.0), torch.full_like(g["db"], 3.0))
+    g2 = Bn.backward(f, x, Wx, Wh, None, None, ln, dy, accumulate_into=acc)
+    torch.cuda.synchronize()
+    fo, go = run_oracle(c, True)
+    check("dW_x", g["dW_x"], go[1], TOL["bf16"])
+    check("dW_h", g["dW_h"], go[2], TOL["bf16"])
+    scale = float(g["dW_h"].abs().max())
+    assert torch.allclose(g2["dW_x"], g["dW_x"] + 1, atol=1e-3 * scale) and torch.allclose(g2["dW_h"], g["dW_h"] + 2, atol=1e-3 * scale)
+    assert torch.allclose(g2["db"], g["db"] + 3, atol=1e-3 * float(g["db"].abs().max()))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_all_rows_empty_and_single_frame_training(dt):
+    """Degenerate batches: every length 0 (outputs zero, state and its gradient passed through, weight gradients zero), and
+    T = 1 in training mode (forward + backward of a single frame)."""
+    rng = np.random.default_rng(49)
+    c = rnd_case(rng, T=6, B=5, n_in=16, n=24, D=2, lens=[0, 0, 0, 0, 0], dt=dt)
+    f, g = run_gpu(c, dt, True)
+    assert float(f["y"].float().abs().max()) == 0.0 and float(g["dx"].float().abs().max()) == 0.0
+    assert float(g["dW_x"].abs().max()) == 0.0 and float(g["dW_h"].abs().max()) == 0.0 and float(g["db"].abs().max()) == 0.0
+    check("hT", f["hT"], c["h0"], 1e-6)
+    check("cT", f["cT"], c["c0"], 1e-6)
+    check("dh0", g["dh0"], c["dhT"], 1e-6)
+    check("dc0", g["dc0"], c["dcT"], 1e-6)
+    c = rnd_case(rng, T=1, B=9, n_in=16, n=24, D=2, lens=[1, 1, 0, 1, 1, 1, 0, 1, 1], dt=dt)
+    f, g = run_gpu(c, dt, True)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL[dt])
+
+
 # ---- the single-launch recurrent kernels against one launch per time step ------------------------------------
 @pytest.mark.parametrize("dt,B,n,T", [("bf16", 32, 64, 40), ("f32", 5, 20, 9), ("bf16", 70, 136, 25), ("bf16", 32, 1024, 12), ("bf16", 19, 1000, 7),
                                       ("bf16", 64, 1000, 9), ("bf16", 41, 1024, 6), ("bf16", 150, 264, 8)])
