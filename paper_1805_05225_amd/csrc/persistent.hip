@@ -326,7 +326,7 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
   __shared__ float red[4][16][65];
   __shared__ unsigned short hb[16][18];
   const WgCoord wg = wg_coord();
-  const PFwdDir& d = a.d[wg.dir];
+  const PFwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
   const int tile = wg.tile, rt = a.rt0 + wg.rt, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   __shared__ float red[4][8][129];
   __shared__ unsigned short hb[8][2][18];
   const WgCoord wg = wg_coord();
-  const PFwdDir& d = a.d[wg.dir];
+  const PFwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
   const int tile2 = wg.tile, rt = a.rt0 + (wg.rt >> 1), half = wg.rt & 1;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
@@ -633,7 +633,7 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
   __shared__ float red[4][16][17];
   __shared__ unsigned short zb[16][66];
   const WgCoord wg = wg_coord();
-  const PBwdDir& d = a.d[wg.dir];
+  const PBwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
   const int tile = wg.tile, rt = a.rt0 + wg.rt, ntiles = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
@@ -779,7 +779,7 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
   __shared__ float red[4][8][33];
   __shared__ unsigned short zb[8][2][66];
   const WgCoord wg = wg_coord();
-  const PBwdDir& d = a.d[wg.dir];
+  const PBwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
   const int tile2 = wg.tile, rt = a.rt0 + (wg.rt >> 1), half = wg.rt & 1;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
@@ -955,7 +955,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   __shared__ float red[4][8][33];
   __shared__ __attribute__((aligned(16))) unsigned short zb[8][136];
   const WgCoord wg = wg_coord();
-  const PBwdDir& d = a.d[wg.dir];
+  const PBwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
   const int J = wg.tile, R = 2 * a.rt0 + wg.rt, ntile2 = gridDim.x;     // R: row group of 8 rows, counted over the whole batch
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = a.n, B = a.B, T = a.T;

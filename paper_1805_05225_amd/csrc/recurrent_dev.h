@@ -31,8 +31,10 @@ __device__ __forceinline__ long frag_offset(int row, int k, int nkc) {
   return ((((long)rt * nkc + kc) * 64 + g * 16 + r) * E + e);
 }
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + __expf(-x)); }
-__device__ __forceinline__ float tanhf_(float x) { return 1.f - 2.f / (1.f + __expf(2.f * x)); }
+// Reciprocals through the hardware approximation (1 ulp): a correctly rounded float division is ten dependent
+// instructions, and with one wavefront per SIMD the recurrent kernels pay for every one of them in every step.
+__device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
+__device__ __forceinline__ float tanhf_(float x) { return 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + __expf(2.f * x)); }
 __device__ __forceinline__ int clamp_len(const int* lens, int b, int T) {
   if (!lens) return T;
   int L = lens[b];
