@@ -93,6 +93,7 @@ struct RingReader {
   __device__ __forceinline__ u32x4 load_it(int it) const {
     return __builtin_amdgcn_raw_buffer_load_b128(rs, voff + (unsigned)it * it_bytes, 0, kSc1);
   }
+  __device__ __forceinline__ bool expects(int it) const { return lim_step * it < lim; }   // does this lane's unit of load `it` carry a tag?
   __device__ __forceinline__ unsigned stale_bits(const u32x4& x, int it) const {
     const unsigned d = ((x[1] >> 16) ^ tag) | ((x[3] >> 16) ^ tag);
     return lim_step * it < lim ? d : 0u;
@@ -247,6 +248,12 @@ __device__ __forceinline__ void mfma_b_vgpr(f32x4& acc, const u32x4& a, const u3
 // Wait states between the last ordinary (vector ALU, DPP, LDS) write of registers and an MFMA reading them.  For
 // MFMAs it emits itself the compiler knows what the hardware needs; for these it cannot, and an MFMA issued right
 // behind DPP moves was observed to read the old register contents.
+// first MFMA of a pair behind which a preparation step of the next pair is placed (the next pair's loads were
+// issued together with this pair's and have had that much more time to arrive)
+#ifndef LSTM_PREP_DELAY
+#define LSTM_PREP_DELAY 6
+#endif
+constexpr int kPrepDelay = LSTM_PREP_DELAY;
 #ifndef LSTM_OPERAND_NOPS
 #define LSTM_OPERAND_NOPS "7"
 #endif
@@ -534,25 +541,6 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
         if (it < kAccIts) mfma_b_agpr(acc[ct][q], a_op, wa[it < kAccIts ? it : 0][ct][q]);
         else mfma_b_vgpr(acc[ct][q], a_op, wv[it >= kAccIts ? it - kAccIts : 0][ct][q]);
       };
-      // Consecutive MFMAs into the SAME accumulator issue every 16 cycles; switching accumulators costs as much
-      // again (measured: 7.7 ns chained, 18.8 ns when 8 accumulators take turns).  So the stream hands its loads
-      // over in pairs: four chunks, and every accumulator takes its four products in a row.
-      u32x4 held[2];                                       // operands of the even load of a pair
-      auto use_pair = [&](int p, uint4 av_) {
-        const uint4 av2_ = rotate_rows_by_8(av_);
-        u32x4 av = {av_.x, av_.y, av_.z, av_.w}, av2 = {av2_.x, av2_.y, av2_.z, av2_.w};
-        if ((p & 1) == 0) { held[0] = av; held[1] = av2; return; }
-        operands_settle(held[0], held[1], av, av2);
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            mma_one(2 * p - 2, ct, q, held[0]);
-            mma_one(2 * p - 1, ct, q, held[1]);
-            mma_one(2 * p, ct, q, av);
-            mma_one(2 * p + 1, ct, q, av2);
-          }
-      };
       auto use_single = [&](int p, uint4 av_) {            // a load fetched again after the stream
         const uint4 av2_ = rotate_rows_by_8(av_);
         u32x4 av = {av_.x, av_.y, av_.z, av_.w}, av2 = {av2_.x, av2_.y, av2_.z, av2_.w};
@@ -565,8 +553,71 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
             mma_one(2 * p + 1, ct, q, av2);
           }
       };
+      // The stream.  All loads are issued at once and consumed in pairs: a pair is four chunks, and every accumulator
+      // takes its four products in a row, because consecutive MFMAs into the SAME accumulator issue every 16 cycles
+      // while switching accumulators costs as much again (measured: 7.7 ns chained, 18.8 ns when 8 take turns).
+      // An MFMA occupies the issue slot of the wavefront for 4 of those 16 cycles.  What turns the next pair's loads
+      // into operands (tag test, masking the tags off, the rotated copies) is cut into single instructions, and one
+      // is placed behind each of the first MFMAs of the pair before: there it costs nothing, in front of the pair's
+      // own MFMAs it was a fifth of the step.  A pair with a stale tag in any lane is skipped (wave-uniform branch)
+      // and both its loads are fetched again by fix_up.
       static_assert((NIT / 2) % 2 == 0, "loads are consumed in pairs");
-      const unsigned long long redo = rd.stream<NIT / 2, NIT / 2, true>(use_pair);
+      constexpr int NL = NIT / 2, NP = NL / 2, kPrepSteps = 14;
+      u32x4 x[NL];
+#pragma unroll
+      for (int i = 0; i < NL; ++i) x[i] = rd.load_it(rd.it_of(i));
+      __builtin_amdgcn_sched_barrier(0);
+      const unsigned tagw = rd.tag << 16;
+      u32x4 ops[NP][4];                                    // [0] load 2p as fetched, [1] its rows rotated by 8, [2], [3]: load 2p+1
+      unsigned bad[NP];                                    // tag mismatches of the pair, per lane, in the upper 16 bits
+      auto prep = [&](int p, int k) __attribute__((always_inline)) {
+        const int second = k >= kPrepSteps / 2, i = 2 * p + second, kk = second ? k - kPrepSteps / 2 : k;
+        if (kk == 0) {
+          const unsigned e = rd.expects(rd.it_of(i)) ? tagw : 0u;
+          const unsigned m = (x[i][1] ^ e) | (x[i][3] ^ e);
+          bad[p] = second ? (bad[p] | m) : m;
+        } else if (kk == 1) {
+          x[i][1] &= 0xffffu;
+        } else if (kk == 2) {
+          x[i][3] &= 0xffffu;
+          ops[p][2 * second] = x[i];
+        } else {
+          ops[p][2 * second + 1][kk - 3] = (unsigned)__builtin_amdgcn_mov_dpp((int)x[i][kk - 3], 0x128, 0xf, 0xf, false);
+        }
+      };
+      unsigned long long redo = 0ull;
+#pragma unroll
+      for (int k = 0; k < kPrepSteps; ++k) prep(0, k);
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (__builtin_amdgcn_ballot_w64(bad[p] > 0xffffu) == 0ull) {
+          operands_settle(ops[p][0], ops[p][1], ops[p][2], ops[p][3]);
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int o = 0; o < 4; ++o) {
+                mma_one(4 * p + o, ct, q, ops[p][o]);
+                const int m = (ct * 4 + q) * 4 + o - kPrepDelay;
+                if (p + 1 < NP && m >= 0 && m < kPrepSteps) {
+                  __builtin_amdgcn_sched_barrier(0);
+                  prep(p + 1, m);
+                  __builtin_amdgcn_sched_barrier(0);
+                }
+              }
+        } else {                                           // rare once the sample has turned
+          redo |= 3ull << (2 * p);
+          if (p + 1 < NP) {
+            // The empty statement makes the loads' registers new values on this path: instructions that are the
+            // same on both paths are moved in front of the branch, and with them the wait for the next pair's loads.
+            asm volatile("" : "+v"(x[2 * p + 2]), "+v"(x[2 * p + 3]));
+#pragma unroll
+            for (int k = 0; k < kPrepSteps; ++k) prep(p + 1, k);
+          }
+        }
+      }
       PROF_POLLS(100 * __popcll(redo))
       if (redo) rd.fix_up<NIT / 2>(redo, dead, use_single);
       mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
