@@ -24,6 +24,7 @@
 // grid always drains.  The launch is cooperative, which guarantees that all work-groups are
 // resident together (otherwise the launch is refused and the caller uses the per-step kernels).
 #include "recurrent_dev.h"
+#include <type_traits>
 #include <algorithm>
 #include <map>
 #include <mutex>
@@ -35,16 +36,18 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 // Optional in-kernel phase clocks (build with -DLSTM_PROF; prints from a few work-groups at the end).
 #ifdef LSTM_PROF
-#define PROF_DECL long long pt_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; long long pc_ = wall_clock64(); unsigned npoll_ = 0;
+#define PROF_DECL long long pt_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; long long pc_ = wall_clock64(); unsigned npoll_ = 0, nredo_ = 0;
 #define PROF_MARK(i) { long long now_ = wall_clock64(); pt_[i] += now_ - pc_; pc_ = now_; }
 #define PROF_POLLS(n) npoll_ += (n);
+#define PROF_REDO(n) nredo_ += (n);
 #define PROF_DUMP(name, steps) if ((tid & 63) == 0 && (blockIdx.x % 23) == 0 && blockIdx.y == 0) \
-  printf("%s wg(%d,%d,%d) wave %d: ns/step sample %lld stream %lld mma %lld red+cell %lld publish %lld other %lld polls/step %.2f\n", name, blockIdx.x, blockIdx.y, blockIdx.z, (int)(threadIdx.x >> 6), \
-         pt_[5] * 10 / (steps), pt_[0] * 10 / (steps), pt_[1] * 10 / (steps), pt_[2] * 10 / (steps), pt_[3] * 10 / (steps), pt_[4] * 10 / (steps), (double)npoll_ / (steps));
+  printf("%s wg(%d,%d,%d) wave %d: ns/step sample %lld stream %lld mma %lld red+cell %lld publish %lld other %lld polls/step %.2f loads fetched again per 1000 steps %.1f\n", name, blockIdx.x, blockIdx.y, blockIdx.z, (int)(threadIdx.x >> 6), \
+         pt_[5] * 10 / (steps), pt_[0] * 10 / (steps), pt_[1] * 10 / (steps), pt_[2] * 10 / (steps), pt_[3] * 10 / (steps), pt_[4] * 10 / (steps), (double)npoll_ / (steps), 1000.0 * nredo_ / (steps));
 #else
 #define PROF_DECL
 #define PROF_MARK(i)
 #define PROF_POLLS(n)
+#define PROF_REDO(n)
 #define PROF_DUMP(name, steps)
 #endif
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
@@ -117,8 +120,8 @@ struct RingReader {
   }
   // Streams the wave's NIT loads through `use(i, operand)` with at most W loads in flight: a window of that
   // size is the most the memory path of one compute unit sustains before the latency per load climbs.
-  // A load in which any lane saw a stale tag contributes a zero operand instead and is recorded in the
-  // returned bit mask (wave-uniform); `fix_up` then fetches exactly those loads again.  Once the sample has
+  // A load in which any lane saw a stale tag is skipped (wave-uniform branch) and recorded in the returned bit
+  // mask; `fix_up` then fetches exactly those loads again.  Once the sample has
   // turned this is rare, and it costs one extra load latency instead of a second pass over everything.
   template <int NIT, int W, bool PIN = false, typename F>
   __device__ __forceinline__ unsigned long long stream(F&& use) const {
@@ -136,12 +139,40 @@ struct RingReader {
       if (PIN) __builtin_amdgcn_sched_barrier(0);
       const u32x4 v = x[i % W];
       if (i + W < NIT) x[i % W] = load_it(it_of(i + W));
-      const bool stale = __builtin_amdgcn_ballot_w64(stale_bits(v, it_of(i)) != 0u) != 0ull;
-      redo |= stale ? 1ull << i : 0ull;
-      const unsigned keep = stale ? 0u : 0xffffffffu;
-      use(i, make_uint4(v[0] & keep, v[1] & 0xffffu & keep, v[2] & keep, v[3] & 0xffffu & keep));
+      // (v1 ^ e) | (v3 ^ e) has a bit above the low half iff one of the two tags differs from the awaited one;
+      // lanes that expect no tag (padding, out of range: zeros) compare against zero.  A vector compare into VCC and
+      // a branch on it: anything that routes the verdict through scalar registers (a ballot kept in a mask, selects
+      // on it) stalls on the vector-to-scalar hand-over, which was a third of the backward kernel's stream phase.
+      const unsigned e = expects(it_of(i)) ? tag << 16 : 0u;
+      const unsigned t = (v[1] ^ e) | (v[3] ^ e);
+      if (__builtin_expect(__builtin_amdgcn_ballot_w64(t > 0xffffu) == 0ull, 1)) use(i, make_uint4(v[0], v[1] & 0xffffu, v[2], v[3] & 0xffffu));
+      else redo |= 1ull << i;
     }
     return redo;
+  }
+  // Second pass over the loads marked in `redo`, all of them in flight at once: every round fetches those still
+  // marked, hands the ones whose tags have all turned to `use` (operand as loaded, tags included) and keeps the
+  // rest for the next round (bounded).
+  template <int NIT, typename F>
+  __device__ __forceinline__ void fix_up_batch(unsigned long long redo, bool& dead, F&& use) const {
+    for (unsigned poll = 0; redo != 0ull && !dead; ++poll) {
+      u32x4 x[NIT];
+#pragma unroll
+      for (int i = 0; i < NIT; ++i)
+        if ((redo >> i) & 1ull) x[i] = load_it(it_of(i));
+#pragma unroll
+      for (int i = 0; i < NIT; ++i) {
+        if (!((redo >> i) & 1ull)) continue;
+        if (__builtin_amdgcn_ballot_w64(stale_bits(x[i], it_of(i)) != 0u) == 0ull) {
+          use(i, x[i]);
+          redo &= ~(1ull << i);
+        }
+      }
+      if (redo != 0ull && (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u))) {
+        st_relaxed(err, 1u);
+        dead = true;
+      }
+    }
   }
   // Second pass over the loads marked in `redo`: each is polled (bounded) until all its tags are the awaited
   // ones and then fed to `use`.
@@ -244,6 +275,12 @@ __device__ __forceinline__ void mfma_b_agpr(f32x4& acc, const u32x4& a, const u3
 }
 __device__ __forceinline__ void mfma_b_vgpr(f32x4& acc, const u32x4& a, const u32x4& b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+// acc = A x B: the first product of a chain takes the constant 0 as its addend, so the accumulators need no clearing
+// (64 moves per step in the backward kernel, and the wait states between them and the first MFMA).  The result may not share
+// registers with an operand: early clobber.
+__device__ __forceinline__ void mfma_b_agpr_first(f32x4& acc, const u32x4& a, const u32x4& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
 }
 // Wait states between the last ordinary (vector ALU, DPP, LDS) write of registers and an MFMA reading them.  For
 // MFMAs it emits itself the compiler knows what the hardware needs; for these it cannot, and an MFMA issued right
@@ -398,7 +435,7 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
         for (int q = 0; q < 4; ++q) acc[q] = Mma16<bf16_t>::run(av, w[it][q], acc[q]);
       };
       const unsigned long long redo = rd.stream<NIT, kWindow>(use);
-      PROF_POLLS(100 * __popcll(redo))
+      PROF_REDO(__popcll(redo))
       if (redo) rd.fix_up<NIT>(redo, dead, use);
     }
     fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
@@ -529,6 +566,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     PROF_POLLS(np_)
     PROF_MARK(5)
     f32x4 acc[2][4];
+    // (cleared by moves: starting each chain with an MFMA that adds to the constant 0, as the backward kernel does,
+    // was measured 10 % slower per step here)
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -537,7 +576,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     operands_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     {
       // One MFMA of register set `it` into accumulator (ct, q).
-      auto mma_one = [&](int it, int ct, int q, const u32x4& a_op) {
+      auto mma_one = [&](int it, int ct, int q, const u32x4& a_op) __attribute__((always_inline)) {
         if (it < kAccIts) mfma_b_agpr(acc[ct][q], a_op, wa[it < kAccIts ? it : 0][ct][q]);
         else mfma_b_vgpr(acc[ct][q], a_op, wv[it >= kAccIts ? it - kAccIts : 0][ct][q]);
       };
@@ -591,7 +630,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
         __builtin_amdgcn_sched_barrier(0);
-        if (__builtin_amdgcn_ballot_w64(bad[p] > 0xffffu) == 0ull) {
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad[p] > 0xffffu) == 0ull, 1)) {
           operands_settle(ops[p][0], ops[p][1], ops[p][2], ops[p][3]);
 #pragma unroll
           for (int ct = 0; ct < 2; ++ct)
@@ -618,7 +657,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
           }
         }
       }
-      PROF_POLLS(100 * __popcll(redo))
+      PROF_REDO(__popcll(redo))
       if (redo) rd.fix_up<NIT / 2>(redo, dead, use_single);
       mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
       mfma_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
@@ -752,7 +791,7 @@ __global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
         // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
         auto use = [&](int it, uint4 av) { acc[it & 3] = Mma16<bf16_t>::run(av, w[it], acc[it & 3]); };
         const unsigned long long redo = rd.stream<NIT, kWindow>(use);
-        PROF_POLLS(100 * __popcll(redo))
+        PROF_REDO(__popcll(redo))
         if (redo) rd.fix_up<NIT>(redo, dead, use);
       }
       in_next = fetch_in(tau - 1);    // after the ring loads: loads complete in order, and these come from HBM
@@ -909,7 +948,7 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
           }
         };
         const unsigned long long redo = rd.stream<NIT / 2, kWindow>(use);
-        PROF_POLLS(100 * __popcll(redo))
+        PROF_REDO(__popcll(redo))
         if (redo) rd.fix_up<NIT / 2>(redo, dead, use);
       }
       in_next = fetch_in(tau - 1);
@@ -1053,13 +1092,26 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   const long ring_tile = ((long)R * ntile2 + J) * ntile2 * (kPartBytes / 16);     // uint4 index of [R][J][0]
   // producer side: lanes 0..31 hold rows 4*(lane/16) .. +3 of output column lane%16 of each accumulator tile
   const int pg = (lane >> 4) & 1, pcol = lane & 15;
-  const bool local = a.xcc != nullptr &&
-                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * ntile2, ntile2, J, a.spin_limit);
+  // (the verdict comes out of shared memory; the compiler has to be told that it is the same in every lane, or the
+  // two copies of the publishing code below become one divergent region)
+  const bool local = __builtin_amdgcn_readfirstlane((int)(a.xcc != nullptr &&
+                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * ntile2, ntile2, J, a.spin_limit))) != 0;
+  // byte offset, from row group R's part of the ring, of what this lane stores for accumulator tile c: destination tile
+  // wave*8 + c/2 (one past the last falls outside the buffer), this producer's block, output column, row half.  Lanes
+  // 32..63 hold copies of the same rows; their offset is parked outside the buffer and the store is dropped.
+  unsigned pub_off[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) {
+    const int Jd = wave * 8 + (c >> 1);
+    pub_off[c] = lane < 32 ? (unsigned)(((Jd * ntile2 + J) * 32 + (c & 1) * 16 + pcol) * 2 + pg) * 16u : 0xfff00000u;
+  }
 
   PROF_DECL
-  for (int tau = T - 1; tau >= -1; --tau) {
+  for (int tau = T - 1; tau >= -1; tau = __builtin_amdgcn_readfirstlane(tau) - 1) {
     PROF_MARK(4)
-    const int sigma = T - 1 - tau;
+    // (told to be wave-uniform: computed next to per-lane uses of tau it ends up in vector registers, and a buffer
+    // descriptor derived from it is then applied lane by lane in a loop)
+    const int sigma = __builtin_amdgcn_readfirstlane(T - 1 - tau);
     const int t = d.rev ? T - 1 - tau : tau;
     const int t_next = d.rev ? t - 1 : t + 1;
     const bool pointwise = tau >= 0;
@@ -1081,13 +1133,44 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       PROF_MARK(5)
       float ps[4] = {0.f, 0.f, 0.f, 0.f};
       {
-        auto use = [&](int, uint4 v) {                     // tags arrive masked off
-          ps[0] += __uint_as_float(v.x << 16); ps[1] += __uint_as_float(v.x & 0xffff0000u);
-          ps[2] += __uint_as_float(v.y << 16); ps[3] += __uint_as_float(v.z << 16);
+        // The sums need none of the tag halves masked off: the shifts drop them.  With one wavefront per SIMD what
+        // bounds this phase is its instruction stream, and a verdict per load (compare, branch, or worse a ballot
+        // handed to scalar registers) cost as much as the additions themselves.  So the loads are taken four at a
+        // time: their values are added into sums of the group's own without looking, the tag differences of the four
+        // are ORed per lane, and one compare and branch decides whether the group's sums count.  A group with a stale
+        // tag in any lane is dropped whole and its loads are fetched again, all at once, by fix_up_batch.
+        auto add = [&](float (&acc)[4], const u32x4& v) __attribute__((always_inline)) {
+          acc[0] += __uint_as_float(v[0] << 16); acc[1] += __uint_as_float(v[0] & 0xffff0000u);
+          acc[2] += __uint_as_float(v[1] << 16); acc[3] += __uint_as_float(v[2] << 16);
         };
-        const unsigned long long redo = rd.stream<NPW, NPW, true>(use);
-        PROF_POLLS(100 * __popcll(redo))
-        if (redo) rd.fix_up<NPW>(redo, dead, use);
+        static_assert(NPW % 4 == 0, "loads are checked in groups of four");
+        u32x4 x[NPW];
+#pragma unroll
+        for (int i = 0; i < NPW; ++i) x[i] = rd.load_it(rd.it_of(i));
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned tagw = rd.tag << 16;
+        unsigned long long redo = 0ull;
+#pragma unroll
+        for (int g = 0; g < NPW / 4; ++g) {
+          float pg[4] = {0.f, 0.f, 0.f, 0.f};
+          unsigned bad = 0u;
+#pragma unroll
+          for (int i = 4 * g; i < 4 * g + 4; ++i) {
+            __builtin_amdgcn_sched_barrier(0);             // each load is waited for and consumed in turn
+            const unsigned e = rd.expects(rd.it_of(i)) ? tagw : 0u;
+            bad |= (x[i][1] ^ e) | (x[i][3] ^ e);
+            add(pg, x[i]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad > 0xffffu) == 0ull, 1)) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ps[v] += pg[v];
+          } else {
+            redo |= 0xfull << (4 * g);
+          }
+        }
+        PROF_REDO(__popcll(redo))
+        if (redo) rd.fix_up_batch<NPW>(redo, dead, [&](int, const u32x4& v) __attribute__((always_inline)) { add(ps, v); });
       }
       in_next = fetch_in(tau - 1);
       PROF_MARK(0)
@@ -1121,51 +1204,52 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       u32x4 av[4];
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 7][kc * 32 + (lane >> 4) * 8];
-      operands_settle(av[0], av[1], av[2], av[3]);
       f32x4 acc[16];
-      // Four groups of four column tiles: the previous group's results are converted and stored after the next
-      // group's MFMAs have been issued.  (Placing the conversions and stores between the individual MFMAs was
-      // measured slower: the lane masks and branches around each store cost more than the overlap gains.)
-      auto multiply = [&](int g4) {
+      // Four groups of four column tiles.  Consecutive MFMAs into the SAME accumulator issue every 16 cycles, of which
+      // the wavefront's issue slot is taken for 4; switching accumulators costs as much again (measured: 7.7 ns
+      // chained, 18.8 ns when 8 accumulators take turns), so the k loop is the inner one.  What publishes a group
+      // (two conversions, three moves and one store per tile) is cut into single instructions, and two of them follow
+      // each MFMA of the NEXT group from its third on: by then the group's last result has been written (more than
+      // the 20 wait states mfma_settle would spend), and the instructions cost nothing there, where behind the
+      // group's MFMAs they were a sixth of the step.  Nothing is predicated: lanes that hold no result have their
+      // store offset parked outside the buffer (pub_off), and the two cache policies are two copies of the code.
+      constexpr int kPubSteps = 24;
+      auto mma_publish = [&](auto local_c) __attribute__((always_inline)) {
+        constexpr bool kLocal = decltype(local_c)::value;
+        u32x4 val[2][4];
+        auto pub_step = [&](int g4, int k) __attribute__((always_inline)) {
+          const int cc = k / 6, kk = k % 6, c = g4 * 4 + cc;
+          u32x4& v = val[g4 & 1][cc];
+          if (kk == 0) v[0] = pack_bf16x2(acc[c][0], acc[c][1]);
+          else if (kk == 1) v[2] = pack_bf16x2(acc[c][2], acc[c][3]);
+          else if (kk == 2) v[1] = (v[2] & 0xffffu) | tag_hi;
+          else if (kk == 3) v[2] = v[2] >> 16;
+          else if (kk == 4) v[3] = tag_hi;
+          else __builtin_amdgcn_raw_buffer_store_b128(v, ro, pub_off[c], 0, kLocal ? 0 : 16);   // 16: sc1, agent scope, written through
+        };
+        operands_settle(av[0], av[1], av[2], av[3]);
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) acc[g4 * 4 + cc] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        operands_settle(acc[g4 * 4], acc[g4 * 4 + 1], acc[g4 * 4 + 2], acc[g4 * 4 + 3]);
-        // consecutive MFMAs into the SAME accumulator issue every 16 cycles; switching accumulators costs as much
-        // again (measured: 7.7 ns chained, 18.8 ns when 8 accumulators take turns), so the k loop is the inner one
+        for (int g4 = 0; g4 < 4; ++g4)
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc)
+          for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
-          for (int kc = 0; kc < 4; ++kc) mfma_b_agpr(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
-        mfma_settle(acc[g4 * 4], acc[g4 * 4 + 1], acc[g4 * 4 + 2], acc[g4 * 4 + 3]);
+            for (int kc = 0; kc < 4; ++kc) {
+              if (kc == 0) mfma_b_agpr_first(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
+              else mfma_b_agpr(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
+              const int m = cc * 4 + kc - 2;
+              if (g4 > 0 && m >= 0 && 2 * m < kPubSteps) {
+                __builtin_amdgcn_sched_barrier(0);
+                pub_step(g4 - 1, 2 * m);
+                pub_step(g4 - 1, 2 * m + 1);
+                __builtin_amdgcn_sched_barrier(0);
+              }
+            }
+        mfma_settle(acc[12], acc[13], acc[14], acc[15]);
+#pragma unroll
+        for (int k = 0; k < kPubSteps; ++k) pub_step(3, k);
       };
-      auto publish = [&](int g4) {
-        if (lane < 32) {
-          u32x4 val[4];
-          unsigned off[4];
-#pragma unroll
-          for (int cc = 0; cc < 4; ++cc) {
-            const int c = g4 * 4 + cc;
-            const int Jd = wave * 8 + (c >> 1);            // destination tile; one past the last falls outside `ro`
-            off[cc] = (unsigned)(((Jd * ntile2 + J) * 32 + (c & 1) * 16 + pcol) * 2 + pg) * 16u;
-            const unsigned x = pack_bf16x2(acc[c][0], acc[c][1]), y = pack_bf16x2(acc[c][2], acc[c][3]);
-            val[cc] = (u32x4){x, (y & 0xffffu) | tag_hi, y >> 16, tag_hi};
-          }
-          if (local) {                                     // stays in this XCD's L2
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) __builtin_amdgcn_raw_buffer_store_b128(val[cc], ro, off[cc], 0, 0);
-          } else {                                         // sc1: agent scope, written through
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) __builtin_amdgcn_raw_buffer_store_b128(val[cc], ro, off[cc], 0, 16);
-          }
-        }
-      };
-      multiply(0);
-#pragma unroll
-      for (int g4 = 1; g4 < 4; ++g4) {
-        multiply(g4);
-        publish(g4 - 1);
-      }
-      publish(3);
+      if (local) mma_publish(std::true_type{});
+      else mma_publish(std::false_type{});
       PROF_MARK(1)
       if (active) {
 #pragma unroll
