@@ -544,15 +544,23 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   const bool local = a.xcc != nullptr &&
                      group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * (int)gridDim.x, gridDim.x, tile2, a.spin_limit);
 
+  // This thread's entries of the per-frame arrays, as pointers that move by one frame per step (with one wavefront
+  // per SIMD the 64-bit multiplications of an index computed afresh every step are paid in full).
+  const long row0 = (long)(d.rev ? T - 1 : 0) * B + b, frames = d.rev ? -(long)B : (long)B;
+  const long y_step = frames * d.ldy, s_step = frames * n, g_step = 4 * s_step;
+  unsigned short* y_p = (unsigned short*)d.y + row0 * d.ldy + j;
+  float* cs_p = d.cs + row0 * n + j;                        // (not dereferenced where the array is absent)
+  unsigned short* hp_p = (unsigned short*)d.hprev + row0 * n + j;
+  float* g_p = d.gates + row0 * 4 * n + j;
+
   float zx[4] = {0.f, 0.f, 0.f, 0.f}, zx_next[4] = {0.f, 0.f, 0.f, 0.f};
-  auto fetch_zx = [&](int tau, float (&z)[4]) {
+  auto fetch_zx = [&](int tau, const float* gp, float (&z)[4]) {
     const int t = d.rev ? T - 1 - tau : tau;
     if (tau < T && active && t < L) {
-      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
       z[0] = ld_stream(gp); z[1] = ld_stream(gp + n); z[2] = ld_stream(gp + 2 * n); z[3] = ld_stream(gp + 3 * n);
     }
   };
-  fetch_zx(0, zx);
+  fetch_zx(0, g_p, zx);
   PROF_DECL
   for (int tau = 0; tau < T; ++tau) {
     const int t = d.rev ? T - 1 - tau : tau;
@@ -561,6 +569,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
     uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
     const RingReader rd = make_reader_half(rin, nkc, ntiles16 * 3, wave, lane, half, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
+    // (Nine times out of ten the first poll succeeds, yet starting the stream without it was measured slower, 12 % in
+    // the backward kernel: the values arrive while the poll is in flight.)
     const unsigned np_ = rd.wait_sample(dead);
     (void)np_;
     PROF_POLLS(np_)
@@ -580,7 +590,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
         if (it < kAccIts) mfma_b_agpr(acc[ct][q], a_op, wa[it < kAccIts ? it : 0][ct][q]);
         else mfma_b_vgpr(acc[ct][q], a_op, wv[it >= kAccIts ? it - kAccIts : 0][ct][q]);
       };
-      auto use_single = [&](int p, uint4 av_) {            // a load fetched again after the stream
+      auto use_single = [&](int p, const u32x4& raw) {     // a load fetched again after the stream, tags still in it
+        const uint4 av_ = make_uint4(raw[0], raw[1] & 0xffffu, raw[2], raw[3] & 0xffffu);
         const uint4 av2_ = rotate_rows_by_8(av_);
         u32x4 av = {av_.x, av_.y, av_.z, av_.w}, av2 = {av2_.x, av2_.y, av2_.z, av2_.w};
         operands_settle(av, av2);
@@ -658,11 +669,11 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
         }
       }
       PROF_REDO(__popcll(redo))
-      if (redo) rd.fix_up<NIT / 2>(redo, dead, use_single);
+      if (redo) rd.fix_up_batch<NL>(redo, dead, use_single);
       mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
       mfma_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     }
-    fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
+    fetch_zx(tau + 1, g_p + g_step, zx_next);   // after the ring loads: loads complete in order, and these come from HBM
     PROF_MARK(0)
     // accumulator rows 4*(lane/16) + v; this work-group's rows sit in fragment rows 0..7
     if (lane < 32) {
@@ -695,14 +706,14 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       else store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
     }
     if (active) {                     // layer outputs and what the backward pass needs
-      st_stream((unsigned short*)d.y + ((long)t * B + b) * d.ldy + j, f2bf_bits(valid ? h : 0.f));
-      if (d.cs) st_stream(&d.cs[((long)t * B + b) * n + j], c);
-      if (d.hprev) st_stream((unsigned short*)d.hprev + ((long)t * B + b) * n + j, f2bf_bits(h_prev));
+      st_stream(y_p, f2bf_bits(valid ? h : 0.f));
+      if (d.cs) st_stream(cs_p, c);
+      if (d.hprev) st_stream(hp_p, f2bf_bits(h_prev));
       if (valid && a.write_gates) {
-        float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-        st_stream(gp, o.gi); st_stream(gp + n, o.gf); st_stream(gp + 2 * n, o.gg); st_stream(gp + 3 * n, o.go);
+        st_stream(g_p, o.gi); st_stream(g_p + n, o.gf); st_stream(g_p + 2 * n, o.gg); st_stream(g_p + 3 * n, o.go);
       }
     }
+    y_p += y_step; cs_p += s_step; hp_p += s_step; g_p += g_step;
 #pragma unroll
     for (int q = 0; q < 4; ++q) zx[q] = zx_next[q];
     PROF_MARK(3)
@@ -1070,17 +1081,25 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     Dc = d.Dc[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
-  auto fetch_in = [&](int tau) {
+  // This thread's entries of the per-frame arrays, as pointers that move by one frame per step (with one wavefront
+  // per SIMD the 64-bit multiplications of an index computed afresh every step are paid in full).  The loop runs
+  // from the last processed frame to the first; the `f` pointers are at the frame being fetched, one step ahead.
+  const long row_last = (long)(d.rev ? 0 : T - 1) * B + b, frames = d.rev ? (long)B : -(long)B;
+  const long s_step = frames * n, g_step = 4 * s_step, dy_step = frames * d.lddy;
+  const float* gf_p = d.gates + row_last * 4 * n + j;
+  const float* cf_p = d.cs + row_last * n + j;
+  const unsigned short* dyf_p = (const unsigned short*)d.dy + row_last * d.lddy + j;
+  unsigned short* dz_p = (unsigned short*)d.DZ + row_last * 4 * n + j;
+  auto fetch_in = [&](int tau) {                           // the caller has moved the `f` pointers to tau's frame
     BwdIn in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const int t = d.rev ? T - 1 - tau : tau;
     if (tau >= 0 && active && t < L) {
-      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-      in.gi = ld_stream(gp); in.gf = ld_stream(gp + n); in.gg = ld_stream(gp + 2 * n); in.go = ld_stream(gp + 3 * n);
-      in.c_new = ld_stream(&d.cs[((long)t * B + b) * n + j]);
-      const int tp = d.rev ? t + 1 : t - 1;
-      if (tp >= 0 && tp < T) in.c_prev = ld_stream(&d.cs[((long)tp * B + b) * n + j]);
+      in.gi = ld_stream(gf_p); in.gf = ld_stream(gf_p + n); in.gg = ld_stream(gf_p + 2 * n); in.go = ld_stream(gf_p + 3 * n);
+      in.c_new = ld_stream(cf_p);
+      const int tp = d.rev ? t + 1 : t - 1;                // the frame before t in processing order: the next one fetched
+      if (tp >= 0 && tp < T) in.c_prev = ld_stream(cf_p + s_step);
       else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
-      in.dy = bf_bits2f(ld_stream((const unsigned short*)d.dy + ((long)t * B + b) * d.lddy + j));
+      in.dy = bf_bits2f(ld_stream(dyf_p));
     }
     return in;
   };
@@ -1117,6 +1136,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     const bool pointwise = tau >= 0;
     const bool valid = pointwise && active && t < L;
     BwdIn in_next = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    gf_p += g_step; cf_p += s_step; dyf_p += dy_step;       // to the frame of tau - 1
 
     if (sigma > 0) {
       RingReader rd;
@@ -1253,8 +1273,9 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       PROF_MARK(1)
       if (active) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) st_stream((unsigned short*)d.DZ + ((long)t * B + b) * 4 * n + q * n + j, bits[q]);
+        for (int q = 0; q < 4; ++q) st_stream(dz_p + q * n, bits[q]);
       }
+      dz_p += g_step;
       PROF_MARK(3)
     }
     in = in_next;
