@@ -1081,29 +1081,48 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     Dc = d.Dc[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
-  // This thread's entries of the per-frame arrays, as pointers that move by one frame per step (with one wavefront
-  // per SIMD the 64-bit multiplications of an index computed afresh every step are paid in full).  The loop runs
-  // from the last processed frame to the first; the `f` pointers are at the frame being fetched, one step ahead.
-  const long row_last = (long)(d.rev ? 0 : T - 1) * B + b, frames = d.rev ? (long)B : -(long)B;
-  const long s_step = frames * n, g_step = 4 * s_step, dy_step = frames * d.lddy;
-  const float* gf_p = d.gates + row_last * 4 * n + j;
-  const float* cf_p = d.cs + row_last * n + j;
-  const unsigned short* dyf_p = (const unsigned short*)d.dy + row_last * d.lddy + j;
-  unsigned short* dz_p = (unsigned short*)d.DZ + row_last * 4 * n + j;
-  auto fetch_in = [&](int tau) {                           // the caller has moved the `f` pointers to tau's frame
-    BwdIn in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const int t = d.rev ? T - 1 - tau : tau;
-    if (tau >= 0 && active && t < L) {
-      in.gi = ld_stream(gf_p); in.gf = ld_stream(gf_p + n); in.gg = ld_stream(gf_p + 2 * n); in.go = ld_stream(gf_p + 3 * n);
-      in.c_new = ld_stream(cf_p);
-      const int tp = d.rev ? t + 1 : t - 1;                // the frame before t in processing order: the next one fetched
-      if (tp >= 0 && tp < T) in.c_prev = ld_stream(cf_p + s_step);
-      else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
-      in.dy = bf_bits2f(ld_stream(dyf_p));
-    }
+  // What the gate gradients of one frame need.  dy stays as the 16 bits that were loaded: a conversion right behind
+  // the load would make the wavefront wait for it - and for every load in front of it - where it is issued.
+  struct In { float gi, gf, gg, go, c_new, c_prev; unsigned dy_bits; };
+  // The per-frame arrays are read through buffer descriptors that cover exactly one frame: the frame's address is
+  // scalar arithmetic, a lane's offset inside the frame never changes, and a lane with nothing to fetch (row past the
+  // batch, unit past n, frame past the row's length) has its offset parked outside the frame and gets zeros without
+  // touching memory - as does every lane when the frame itself does not exist (zero-sized descriptor).  Nothing is
+  // predicated, so every step issues the same seven loads; with loads that may or may not have been issued the
+  // compiler has to assume the fewest, and made the wavefront wait for the loads of the NEXT frame, just issued and
+  // on their way from HBM, where it only needed those of this one.
+  constexpr unsigned kParked = 0x7ff00000u;
+  const unsigned g_bytes = (unsigned)B * 4u * n * 4u, s_bytes = (unsigned)B * n * 4u, y_bytes = (unsigned)B * d.lddy * 2u;
+  const unsigned g_off = active ? ((unsigned)b * 4u * n + j) * 4u : kParked;
+  const unsigned s_off = active ? ((unsigned)b * n + j) * 4u : kParked;
+  const unsigned y_off = active ? ((unsigned)b * d.lddy + j) * 2u : kParked;
+  auto frame_of = [&](const void* base, int t, unsigned bytes) {
+    const bool ok = t >= 0 && t < T;
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (long)(ok ? t : 0) * bytes), 0, ok ? bytes : 0u, kBufFlags);
+  };
+  auto ld_f = [&](__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {     // 2: non-temporal
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 2));
+  };
+  auto fetch_in = [&](int tau) {
+    const int t = tau < 0 ? -1 : (d.rev ? T - 1 - tau : tau);
+    const bool lane_on = t < L;                            // (L is 0 in lanes without a row)
+    const unsigned go = lane_on ? g_off : kParked, so = lane_on ? s_off : kParked, yo = lane_on ? y_off : kParked;
+    In in;
+    const __amdgpu_buffer_rsrc_t rg = frame_of(d.gates, t, g_bytes);
+    in.gi = ld_f(rg, go, 0u); in.gf = ld_f(rg, go, 4u * n); in.gg = ld_f(rg, go, 8u * n); in.go = ld_f(rg, go, 12u * n);
+    in.c_new = ld_f(frame_of(d.cs, t, s_bytes), so, 0u);
+    const int tp = d.rev ? t + 1 : t - 1;                  // the frame before t in processing order
+    const bool inside = t >= 0 && tp >= 0 && tp < T, initial = t >= 0 && !inside && d.c0 != nullptr;
+    const __amdgpu_buffer_rsrc_t rp = initial ? __builtin_amdgcn_make_buffer_rsrc((void*)d.c0, 0, s_bytes, kBufFlags)
+                                              : frame_of(d.cs, inside ? tp : -1, s_bytes);
+    in.c_prev = ld_f(rp, so, 0u);
+    in.dy_bits = __builtin_amdgcn_raw_buffer_load_b16(frame_of(d.dy, t, y_bytes), yo, 0, 2);
     return in;
   };
-  BwdIn in = fetch_in(T - 1);
+  // entries of DZ, which this thread stores: a pointer that moves by one frame per step
+  const long row_last = (long)(d.rev ? 0 : T - 1) * B + b, g_step = (d.rev ? (long)B : -(long)B) * 4 * n;
+  unsigned short* dz_p = (unsigned short*)d.DZ + row_last * 4 * n + j;
+  In in_a = fetch_in(T - 1), in_b = in_a;
 
   // consumer side: lane reads output lane/2, row half lane%2 of every producer's block
   const int ccol = lane >> 1, cg = lane & 1;
@@ -1126,7 +1145,10 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   }
 
   PROF_DECL
-  for (int tau = T - 1; tau >= -1; tau = __builtin_amdgcn_readfirstlane(tau) - 1) {
+  // One time step.  `in` holds the inputs of this step's frame and `in_next` receives those of the next; the loop
+  // below calls it with the two in alternating roles, because a copy at the end of a step would have to wait for
+  // the loads (and, counted with them, the step's stores) at that point.
+  auto step = [&](const int tau, const In& in, In& in_next) __attribute__((always_inline)) {
     PROF_MARK(4)
     // (told to be wave-uniform: computed next to per-lane uses of tau it ends up in vector registers, and a buffer
     // descriptor derived from it is then applied lane by lane in a loop)
@@ -1135,8 +1157,6 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     const int t_next = d.rev ? t - 1 : t + 1;
     const bool pointwise = tau >= 0;
     const bool valid = pointwise && active && t < L;
-    BwdIn in_next = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    gf_p += g_step; cf_p += s_step; dyf_p += dy_step;       // to the frame of tau - 1
 
     if (sigma > 0) {
       RingReader rd;
@@ -1203,7 +1223,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     }
     if (pointwise) {
       float dz[4] = {0.f, 0.f, 0.f, 0.f};
-      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, in.dy + Dh, Dc, dz);
+      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, bf_bits2f((unsigned short)in.dy_bits) + Dh, Dc, dz);
       const unsigned b01 = pack_bf16x2(dz[0], dz[1]), b23 = pack_bf16x2(dz[2], dz[3]);
       const unsigned short bits[4] = {(unsigned short)b01, (unsigned short)(b01 >> 16), (unsigned short)b23, (unsigned short)(b23 >> 16)};
 #pragma unroll
@@ -1278,7 +1298,11 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       dz_p += g_step;
       PROF_MARK(3)
     }
-    in = in_next;
+  };
+  // (tau is told to be wave-uniform: computed next to per-lane uses it ends up in vector registers)
+  for (int tau = T - 1; tau >= -1; tau = __builtin_amdgcn_readfirstlane(tau) - 2) {
+    step(tau, in_a, in_b);
+    if (tau - 1 >= -1) step(__builtin_amdgcn_readfirstlane(tau - 1), in_b, in_a);
   }
   PROF_DUMP("bwdp", T)
   if (active) {
