@@ -50,6 +50,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define PROF_REDO(n)
 #define PROF_DUMP(name, steps)
 #endif
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
 constexpr int kWindow = 10;             // ring loads in flight per wavefront (6 to 16 measured alike; all at once is slower)
 // cache policy of the polling loads: bit 4 = coherent at agent scope (bypasses the XCD-local L2),
@@ -544,25 +545,40 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   const bool local = a.xcc != nullptr &&
                      group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * (int)gridDim.x, gridDim.x, tile2, a.spin_limit);
 
-  // This thread's entries of the per-frame arrays, as pointers that move by one frame per step (with one wavefront
-  // per SIMD the 64-bit multiplications of an index computed afresh every step are paid in full).
-  const long row0 = (long)(d.rev ? T - 1 : 0) * B + b, frames = d.rev ? -(long)B : (long)B;
-  const long y_step = frames * d.ldy, s_step = frames * n, g_step = 4 * s_step;
-  unsigned short* y_p = (unsigned short*)d.y + row0 * d.ldy + j;
-  float* cs_p = d.cs + row0 * n + j;                        // (not dereferenced where the array is absent)
-  unsigned short* hp_p = (unsigned short*)d.hprev + row0 * n + j;
-  float* g_p = d.gates + row0 * 4 * n + j;
-
-  float zx[4] = {0.f, 0.f, 0.f, 0.f}, zx_next[4] = {0.f, 0.f, 0.f, 0.f};
-  auto fetch_zx = [&](int tau, const float* gp, float (&z)[4]) {
-    const int t = d.rev ? T - 1 - tau : tau;
-    if (tau < T && active && t < L) {
-      z[0] = ld_stream(gp); z[1] = ld_stream(gp + n); z[2] = ld_stream(gp + 2 * n); z[3] = ld_stream(gp + 3 * n);
-    }
+  // x W_x + b of a frame is read through a buffer descriptor that covers exactly that frame: a lane with nothing to
+  // fetch (row past the batch, unit past n, frame past the row's length) has its offset parked outside and gets zeros
+  // without touching memory, as does every lane once the frames are used up (zero-sized descriptor).  Nothing is
+  // predicated, so every step issues the same four loads: with loads that may or may not have been issued the
+  // compiler has to assume the fewest when it places the waits.
+  // The outputs go the same way: one descriptor per array and frame (zero-sized if the array is absent), offsets
+  // that never change, parked where a lane has nothing to store; and so does the ring store, whose descriptor ends
+  // below the parking offset.  Frame sizes in bytes: gates [B,4n] float, y [B,ldy] bf16, cs [B,n] float, hprev [B,n] bf16.
+  constexpr unsigned kParked = 0x7ff00000u;
+  const unsigned g_bytes = (unsigned)B * 4u * n * 4u, y_bytes = (unsigned)B * d.ldy * 2u, s_bytes = (unsigned)B * n * 4u;
+  const unsigned g_off = active ? ((unsigned)b * 4u * n + j) * 4u : kParked;
+  const unsigned y_off = active ? ((unsigned)b * d.ldy + j) * 2u : kParked;
+  const unsigned s_off = active ? ((unsigned)b * n + j) * 4u : kParked;        // (half of it in the bf16 array; still parked)
+  const unsigned pub_off = publishes ? (unsigned)unit_index * 8u : kParked;
+  auto frame_of = [&](const void* base, int t, unsigned bytes, bool present = true) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (long)t * bytes), 0, present && base != nullptr ? bytes : 0u, kBufFlags);
   };
-  fetch_zx(0, g_p, zx);
+  auto fetch_zx = [&](int tau, float (&z)[4]) {
+    const bool ok = tau < T;
+    const int t = d.rev ? T - 1 - tau : tau;
+    const __amdgpu_buffer_rsrc_t rg =
+        __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)d.gates + (long)(ok ? t : 0) * g_bytes), 0, ok ? g_bytes : 0u, kBufFlags);
+    const unsigned go = t < L ? g_off : kParked;           // (L is 0 in lanes without a row)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) z[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rg, go, (unsigned)q * 4u * n, 2));   // 2: non-temporal
+  };
+  float zx_a[4], zx_b[4];
+  unsigned h_prev_bits = pack_bf16x2(h, 0.f) & 0xffffu;     // what hprev receives: h before the step, as bf16
+  fetch_zx(0, zx_a);
   PROF_DECL
-  for (int tau = 0; tau < T; ++tau) {
+  // One time step.  `zx` holds this step's x W_x + b and `zx_next` receives the next step's; the loop below calls it
+  // with the two in alternating roles, because a copy at the end of a step would have to wait for the loads (and,
+  // counted with them, the step's stores) at that point.
+  auto step = [&](const int tau, const float (&zx)[4], float (&zx_next)[4]) __attribute__((always_inline)) {
     const int t = d.rev ? T - 1 - tau : tau;
     const bool valid = active && t < L;
     PROF_MARK(4)
@@ -673,7 +689,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
       mfma_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     }
-    fetch_zx(tau + 1, g_p + g_step, zx_next);   // after the ring loads: loads complete in order, and these come from HBM
+    fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
     PROF_MARK(0)
     // accumulator rows 4*(lane/16) + v; this work-group's rows sit in fragment rows 0..7
     if (lane < 32) {
@@ -687,7 +703,6 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     PROF_MARK(1)
     __syncthreads();
 
-    const float h_prev = h;
     CellOut o = {};
     if (valid) {
       float zh[4];
@@ -696,27 +711,36 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       o = lstm_cell(zh, zx, c);
       c = o.c; h = o.h;
     }
-    hb[r8][u >> 4][u & 15] = f2bf_bits(h);          // inactive threads hold h = 0: padding rows / units publish zeros
+    const unsigned h_bits = pack_bf16x2(h, 0.f) & 0xffffu; // inactive threads hold h = 0: padding rows / units publish zeros
+    hb[r8][u >> 4][u & 15] = (unsigned short)h_bits;
     __syncthreads();
     PROF_MARK(2)
-    if (publishes) {                  // the recurrence's critical store goes out first
-      const int v0 = 3 * m;
-      const unsigned x0 = hb[rr][pp][v0], x1 = v0 + 1 < 16 ? hb[rr][pp][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[rr][pp][v0 + 2] : 0u;
-      if (local) store_unit_local(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
-      else store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
+    {                                 // the recurrence's critical store goes out first
+      const int rr_ = publishes ? rr : 0, pp_ = publishes ? pp : 0, v0 = publishes ? 3 * m : 0;
+      const unsigned x0 = hb[rr_][pp_][v0], x1 = v0 + 1 < 16 ? hb[rr_][pp_][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[rr_][pp_][v0 + 2] : 0u;
+      const u32x2 unit = {x0 | (x1 << 16), x2 | (((unsigned)(tau + 2) & 0xffffu) << 16)};
+      const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, kParked, kBufFlags);
+      // 1: workgroup scope, stays in this XCD's L2;  16: agent scope, written through
+      if (local) __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off, 0, 1);
+      else __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off, 0, 16);
     }
-    if (active) {                     // layer outputs and what the backward pass needs
-      st_stream(y_p, f2bf_bits(valid ? h : 0.f));
-      if (d.cs) st_stream(cs_p, c);
-      if (d.hprev) st_stream(hp_p, f2bf_bits(h_prev));
-      if (valid && a.write_gates) {
-        st_stream(g_p, o.gi); st_stream(g_p + n, o.gf); st_stream(g_p + 2 * n, o.gg); st_stream(g_p + 3 * n, o.go);
-      }
+    {                                 // layer outputs and what the backward pass needs (2: non-temporal)
+      __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(valid ? h_bits : 0u), frame_of(d.y, t, y_bytes), y_off, 0, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c), frame_of(d.cs, t, s_bytes), s_off, 0, 2);
+      __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h_prev_bits, frame_of(d.hprev, t, s_bytes >> 1), s_off >> 1, 0, 2);
+      const __amdgpu_buffer_rsrc_t rw = frame_of(d.gates, t, g_bytes, a.write_gates != 0);
+      const unsigned gw = valid ? g_off : kParked;
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o.gi), rw, gw, 0u, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o.gf), rw, gw, 4u * n, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o.gg), rw, gw, 8u * n, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o.go), rw, gw, 12u * n, 2);
     }
-    y_p += y_step; cs_p += s_step; hp_p += s_step; g_p += g_step;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) zx[q] = zx_next[q];
+    h_prev_bits = h_bits;
     PROF_MARK(3)
+  };
+  for (int tau = 0; tau < T; tau += 2) {
+    step(tau, zx_a, zx_b);
+    if (tau + 1 < T) step(tau + 1, zx_b, zx_a);
   }
   PROF_DUMP("fwd8", T)
   if (active) {
