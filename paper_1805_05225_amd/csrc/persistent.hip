@@ -491,8 +491,7 @@ __global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
 // (384 registers per lane).
 template <int NIT>
 __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
-  __shared__ float red[4][8][129];
-  __shared__ unsigned short hb[8][2][18];
+  __shared__ float red[2][4][8][129];                    // two copies, used by even and odd steps: one barrier per step
   const WgCoord wg = wg_coord();
   const PFwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
   const int tile2 = wg.tile, rt = a.rt0 + (wg.rt >> 1), half = wg.rt & 1;
@@ -535,13 +534,14 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     h = d.hstate[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
-  // the unit this thread publishes (threads 0..95): producer tile pp = tid/48, then consecutive threads write
-  // consecutive 8-byte units of a quarter chunk's 8 rows
-  const int pp = tid / 48, rest = tid - 48 * pp, rr = (rest >> 1) & 7, m = ((rest >> 4) << 1) | (rest & 1);
+  // The unit this thread publishes.  A unit is three consecutive units' h of one row (plus the tag), and a row's 32
+  // units sit in 32 consecutive lanes, so the thread of every third unit of a 16-unit tile takes its neighbours' values
+  // through DPP shifts: no staging in shared memory, no second barrier.  m = which unit of the tile (0..5).
+  const int pp = u >> 4, m = (u & 15) / 3;
   const int t16p = tile2 * 2 + pp;
   const int cch = t16p * 3 + (m >> 1);
-  const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + half * 8 + rr) * 2 + (m & 1);
-  const bool publishes = tid < 96 && t16p < ntiles16;
+  const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + half * 8 + r8) * 2 + (m & 1);
+  const bool publishes = (u & 15) % 3 == 0 && t16p < ntiles16;
   const bool local = a.xcc != nullptr &&
                      group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * (int)gridDim.x, gridDim.x, tile2, a.spin_limit);
 
@@ -578,7 +578,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   // One time step.  `zx` holds this step's x W_x + b and `zx_next` receives the next step's; the loop below calls it
   // with the two in alternating roles, because a copy at the end of a step would have to wait for the loads (and,
   // counted with them, the step's stores) at that point.
-  auto step = [&](const int tau, const float (&zx)[4], float (&zx_next)[4]) __attribute__((always_inline)) {
+  auto step = [&](const int tau, const float (&zx)[4], float (&zx_next)[4], auto parity) __attribute__((always_inline)) {
+    float (&red_)[4][8][129] = red[decltype(parity)::value];
     const int t = d.rev ? T - 1 - tau : tau;
     const bool valid = active && t < L;
     PROF_MARK(4)
@@ -698,7 +699,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][q * 32 + ct * 16 + (lane & 15)] = acc[ct][q][v];
+          for (int v = 0; v < 4; ++v) red_[wave][4 * (lane >> 4) + v][q * 32 + ct * 16 + (lane & 15)] = acc[ct][q][v];
     }
     PROF_MARK(1)
     __syncthreads();
@@ -707,17 +708,17 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     if (valid) {
       float zh[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) zh[q] = red[0][r8][q * 32 + u] + red[1][r8][q * 32 + u] + red[2][r8][q * 32 + u] + red[3][r8][q * 32 + u];
+      for (int q = 0; q < 4; ++q) zh[q] = red_[0][r8][q * 32 + u] + red_[1][r8][q * 32 + u] + red_[2][r8][q * 32 + u] + red_[3][r8][q * 32 + u];
       o = lstm_cell(zh, zx, c);
       c = o.c; h = o.h;
     }
     const unsigned h_bits = pack_bf16x2(h, 0.f) & 0xffffu; // inactive threads hold h = 0: padding rows / units publish zeros
-    hb[r8][u >> 4][u & 15] = (unsigned short)h_bits;
-    __syncthreads();
     PROF_MARK(2)
     {                                 // the recurrence's critical store goes out first
-      const int rr_ = publishes ? rr : 0, pp_ = publishes ? pp : 0, v0 = publishes ? 3 * m : 0;
-      const unsigned x0 = hb[rr_][pp_][v0], x1 = v0 + 1 < 16 ? hb[rr_][pp_][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[rr_][pp_][v0 + 2] : 0u;
+      // h of the next and the next but one unit of the tile (DPP row_shl:1, row_shl:2; past the tile's end: zero)
+      const unsigned x0 = h_bits;
+      const unsigned x1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits, 0x101, 0xf, 0xf, true);
+      const unsigned x2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits, 0x102, 0xf, 0xf, true);
       const u32x2 unit = {x0 | (x1 << 16), x2 | (((unsigned)(tau + 2) & 0xffffu) << 16)};
       const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, kParked, kBufFlags);
       // 1: workgroup scope, stays in this XCD's L2;  16: agent scope, written through
@@ -739,8 +740,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     PROF_MARK(3)
   };
   for (int tau = 0; tau < T; tau += 2) {
-    step(tau, zx_a, zx_b);
-    if (tau + 1 < T) step(tau + 1, zx_b, zx_a);
+    step(tau, zx_a, zx_b, std::integral_constant<int, 0>{});
+    if (tau + 1 < T) step(tau + 1, zx_b, zx_a, std::integral_constant<int, 1>{});
   }
   PROF_DUMP("fwd8", T)
   if (active) {
@@ -1501,9 +1502,11 @@ bool slab_fits(K kernel, int grid_x, int rows_per_y, int ndir) {
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
   if (a.nkc > kLLMaxNkcFwd) return hipErrorCooperativeLaunchTooLarge;
   // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
+#ifndef LSTM_FORCE_FWD16
   hipError_t e = coop_slabs(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, cdiv(cdiv(a.n, 16), 2), 8, a, s);
   if (e != hipErrorCooperativeLaunchTooLarge) return e;
   (void)hipGetLastError();
+#endif
   return coop_slabs(persist_fwd_kernel<kLLMaxNkcFwd / 4>, cdiv(a.n, 16), 16, a, s);
 }
 int persist_bwd_variant(const PBwdArgs& a) {
