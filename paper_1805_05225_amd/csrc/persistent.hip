@@ -1502,11 +1502,9 @@ bool slab_fits(K kernel, int grid_x, int rows_per_y, int ndir) {
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
   if (a.nkc > kLLMaxNkcFwd) return hipErrorCooperativeLaunchTooLarge;
   // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
-#ifndef LSTM_FORCE_FWD16
   hipError_t e = coop_slabs(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, cdiv(cdiv(a.n, 16), 2), 8, a, s);
   if (e != hipErrorCooperativeLaunchTooLarge) return e;
   (void)hipGetLastError();
-#endif
   return coop_slabs(persist_fwd_kernel<kLLMaxNkcFwd / 4>, cdiv(a.n, 16), 16, a, s);
 }
 int persist_bwd_variant(const PBwdArgs& a) {
