@@ -98,6 +98,12 @@ struct RingReader {
     return __builtin_amdgcn_raw_buffer_load_b128(rs, voff + (unsigned)it * it_bytes, 0, kSc1);
   }
   __device__ __forceinline__ bool expects(int it) const { return lim_step * it < lim; }   // does this lane's unit of load `it` carry a tag?
+  // Tag differences of one load, per lane: a bit above the low half iff one of the lane's two tags is not `tagw >> 16`.
+  // Lanes whose units carry no tag (padding inside the ring, chunks past the end) report nothing, whatever they read.
+  __device__ __forceinline__ unsigned tag_diff(const u32x4& x, int it, unsigned tagw) const {
+    const unsigned t = (x[1] ^ tagw) | (x[3] ^ tagw);
+    return expects(it) ? t : 0u;
+  }
   __device__ __forceinline__ unsigned stale_bits(const u32x4& x, int it) const {
     const unsigned d = ((x[1] >> 16) ^ tag) | ((x[3] >> 16) ^ tag);
     return lim_step * it < lim ? d : 0u;
@@ -140,12 +146,10 @@ struct RingReader {
       if (PIN) __builtin_amdgcn_sched_barrier(0);
       const u32x4 v = x[i % W];
       if (i + W < NIT) x[i % W] = load_it(it_of(i + W));
-      // (v1 ^ e) | (v3 ^ e) has a bit above the low half iff one of the two tags differs from the awaited one;
-      // lanes that expect no tag (padding, out of range: zeros) compare against zero.  A vector compare into VCC and
+      // A vector compare into VCC and
       // a branch on it: anything that routes the verdict through scalar registers (a ballot kept in a mask, selects
       // on it) stalls on the vector-to-scalar hand-over, which was a third of the backward kernel's stream phase.
-      const unsigned e = expects(it_of(i)) ? tag << 16 : 0u;
-      const unsigned t = (v[1] ^ e) | (v[3] ^ e);
+      const unsigned t = tag_diff(v, it_of(i), tag << 16);
       if (__builtin_expect(__builtin_amdgcn_ballot_w64(t > 0xffffu) == 0ull, 1)) use(i, make_uint4(v[0], v[1] & 0xffffu, v[2], v[3] & 0xffffu));
       else redo |= 1ull << i;
     }
@@ -586,12 +590,6 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
     uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
     const RingReader rd = make_reader_half(rin, nkc, ntiles16 * 3, wave, lane, half, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
-    // (Nine times out of ten the first poll succeeds, yet starting the stream without it was measured slower, 12 % in
-    // the backward kernel: the values arrive while the poll is in flight.)
-    const unsigned np_ = rd.wait_sample(dead);
-    (void)np_;
-    PROF_POLLS(np_)
-    PROF_MARK(5)
     f32x4 acc[2][4];
     // (cleared by moves: starting each chain with an MFMA that adds to the constant 0, as the backward kernel does,
     // was measured 10 % slower per step here)
@@ -631,17 +629,35 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       static_assert((NIT / 2) % 2 == 0, "loads are consumed in pairs");
       constexpr int NL = NIT / 2, NP = NL / 2, kPrepSteps = 14;
       u32x4 x[NL];
-#pragma unroll
-      for (int i = 0; i < NL; ++i) x[i] = rd.load_it(rd.it_of(i));
-      __builtin_amdgcn_sched_barrier(0);
       const unsigned tagw = rd.tag << 16;
+      // The poll IS the first pair of loads: they are repeated (bounded) until all their tags have turned, and what
+      // the last round fetched is kept.  Only then are the other loads issued; their round trip passes behind the
+      // first pair's MFMAs instead of in front of the whole stream (a poll of its own followed by all loads cost one
+      // round trip more per step, a tenth of it).  (Nine times out of ten the first round succeeds; yet issuing
+      // everything at once without looking was measured slower: the values arrive while the poll is in flight.)
+      for (unsigned poll = 0;; ++poll) {
+        x[0] = rd.load_it(rd.it_of(0));
+        x[1] = rd.load_it(rd.it_of(1));
+        if (dead) break;
+        const unsigned stale = rd.tag_diff(x[0], rd.it_of(0), tagw) | rd.tag_diff(x[1], rd.it_of(1), tagw);
+        if (__builtin_amdgcn_ballot_w64(stale > 0xffffu) == 0ull) break;
+        if (poll >= rd.limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+          st_relaxed(err, 1u);
+          dead = true;
+          break;
+        }
+        PROF_POLLS(1)
+      }
+      PROF_MARK(5)
+#pragma unroll
+      for (int i = 2; i < NL; ++i) x[i] = rd.load_it(rd.it_of(i));
+      __builtin_amdgcn_sched_barrier(0);
       u32x4 ops[NP][4];                                    // [0] load 2p as fetched, [1] its rows rotated by 8, [2], [3]: load 2p+1
       unsigned bad[NP];                                    // tag mismatches of the pair, per lane, in the upper 16 bits
       auto prep = [&](int p, int k) __attribute__((always_inline)) {
         const int second = k >= kPrepSteps / 2, i = 2 * p + second, kk = second ? k - kPrepSteps / 2 : k;
         if (kk == 0) {
-          const unsigned e = rd.expects(rd.it_of(i)) ? tagw : 0u;
-          const unsigned m = (x[i][1] ^ e) | (x[i][3] ^ e);
+          const unsigned m = rd.tag_diff(x[i], rd.it_of(i), tagw);
           bad[p] = second ? (bad[p] | m) : m;
         } else if (kk == 1) {
           x[i][1] &= 0xffffu;
@@ -667,7 +683,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
 #pragma unroll
               for (int o = 0; o < 4; ++o) {
                 mma_one(4 * p + o, ct, q, ops[p][o]);
-                const int m = (ct * 4 + q) * 4 + o - kPrepDelay;
+                // the second pair's loads were issued just before the first pair's MFMAs: their turn comes late
+                const int m = (ct * 4 + q) * 4 + o - (p == 0 ? 32 - kPrepSteps : kPrepDelay);
                 if (p + 1 < NP && m >= 0 && m < kPrepSteps) {
                   __builtin_amdgcn_sched_barrier(0);
                   prep(p + 1, m);
@@ -1222,8 +1239,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
           for (int i = 4 * g; i < 4 * g + 4; ++i) {
             __builtin_amdgcn_sched_barrier(0);             // each load is waited for and consumed in turn
-            const unsigned e = rd.expects(rd.it_of(i)) ? tagw : 0u;
-            bad |= (x[i][1] ^ e) | (x[i][3] ^ e);
+            bad |= rd.tag_diff(x[i], rd.it_of(i), tagw);
             add(pg, x[i]);
           }
           __builtin_amdgcn_sched_barrier(0);
