@@ -1209,10 +1209,6 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       rd.lim = ntile2 - wave; rd.lim_step = 4;
       rd.nkc = ntile2; rd.wave = wave; rd.tag = (unsigned)sigma & 0xffffu; rd.err = err; rd.limit = a.spin_limit;
       rd.nitv = nitv; rd.rot = rot;
-      const unsigned np_ = rd.wait_sample(dead);
-      (void)np_;
-      PROF_POLLS(np_)
-      PROF_MARK(5)
       float ps[4] = {0.f, 0.f, 0.f, 0.f};
       {
         // The sums need none of the tag halves masked off: the shifts drop them.  With one wavefront per SIMD what
@@ -1227,10 +1223,26 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         };
         static_assert(NPW % 4 == 0, "loads are checked in groups of four");
         u32x4 x[NPW];
-#pragma unroll
-        for (int i = 0; i < NPW; ++i) x[i] = rd.load_it(rd.it_of(i));
-        __builtin_amdgcn_sched_barrier(0);
         const unsigned tagw = rd.tag << 16;
+        // The poll is the first two loads, repeated (bounded) until their tags have turned and then kept; the others
+        // are issued behind it (see the forward kernel).
+        for (unsigned poll = 0;; ++poll) {
+          x[0] = rd.load_it(rd.it_of(0));
+          x[1] = rd.load_it(rd.it_of(1));
+          if (dead) break;
+          const unsigned stale = rd.tag_diff(x[0], rd.it_of(0), tagw) | rd.tag_diff(x[1], rd.it_of(1), tagw);
+          if (__builtin_amdgcn_ballot_w64(stale > 0xffffu) == 0ull) break;
+          if (poll >= rd.limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+            st_relaxed(err, 1u);
+            dead = true;
+            break;
+          }
+          PROF_POLLS(1)
+        }
+        PROF_MARK(5)
+#pragma unroll
+        for (int i = 2; i < NPW; ++i) x[i] = rd.load_it(rd.it_of(i));
+        __builtin_amdgcn_sched_barrier(0);
         unsigned long long redo = 0ull;
 #pragma unroll
         for (int g = 0; g < NPW / 4; ++g) {
