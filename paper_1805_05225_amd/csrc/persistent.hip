@@ -1200,6 +1200,20 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     const bool pointwise = tau >= 0;
     const bool valid = pointwise && active && t < L;
 
+    // The gate gradients of a valid frame, dh = dy + Dh (recurrent_dev.h has the plain form):
+    //   dc = Dc + dh go (1 - tanh(c)^2), Dc' = dc gf, dz = (dc gg gi (1-gi), dc c_prev gf (1-gf), dc gi (1-gg^2), dh tanh(c) go (1-go)).
+    // Everything that does not involve dh or Dc is computed while the ring loads are in flight.
+    float f_c = 0.f, f_i = 0.f, f_f = 0.f, f_g = 0.f, f_o = 0.f;
+    auto factors = [&]() __attribute__((always_inline)) {
+      if (valid) {
+        const float tc = tanhf_(in.c_new);
+        f_c = in.go * (1.f - tc * tc);
+        f_i = in.gg * in.gi * (1.f - in.gi);
+        f_f = in.c_prev * in.gf * (1.f - in.gf);
+        f_g = in.gi * (1.f - in.gg * in.gg);
+        f_o = tc * in.go * (1.f - in.go);
+      }
+    };
     if (sigma > 0) {
       RingReader rd;
       rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + ring_tile), 0, ntile2 * kPartBytes,
@@ -1221,7 +1235,6 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
           acc[0] += __uint_as_float(v[0] << 16); acc[1] += __uint_as_float(v[0] & 0xffff0000u);
           acc[2] += __uint_as_float(v[1] << 16); acc[3] += __uint_as_float(v[2] << 16);
         };
-        static_assert(NPW % 4 == 0, "loads are checked in groups of four");
         u32x4 x[NPW];
         const unsigned tagw = rd.tag << 16;
         // The poll is the first two loads, repeated (bounded) until their tags have turned and then kept; the others
@@ -1243,13 +1256,22 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
         for (int i = 2; i < NPW; ++i) x[i] = rd.load_it(rd.it_of(i));
         __builtin_amdgcn_sched_barrier(0);
+        // while those loads are on their way: the polled loads' values, and the part of the gate gradients that
+        // does not need Dh
+        add(ps, x[0]);
+        add(ps, x[1]);
+        factors();
+        in_next = fetch_in(tau - 1);  // behind the ring loads: loads complete in order, and these come from HBM
+        __builtin_amdgcn_sched_barrier(0);
         unsigned long long redo = 0ull;
+        constexpr int kGroup = (NPW - 2) / 2;              // the other loads: two groups
 #pragma unroll
-        for (int g = 0; g < NPW / 4; ++g) {
+        for (int g = 0; g < 2; ++g) {
+          const int i0 = 2 + g * kGroup, i1 = g == 0 ? 2 + kGroup : NPW;
           float pg[4] = {0.f, 0.f, 0.f, 0.f};
           unsigned bad = 0u;
 #pragma unroll
-          for (int i = 4 * g; i < 4 * g + 4; ++i) {
+          for (int i = i0; i < i1; ++i) {
             __builtin_amdgcn_sched_barrier(0);             // each load is waited for and consumed in turn
             bad |= rd.tag_diff(x[i], rd.it_of(i), tagw);
             add(pg, x[i]);
@@ -1259,24 +1281,28 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) ps[v] += pg[v];
           } else {
-            redo |= 0xfull << (4 * g);
+            redo |= ((1ull << i1) - 1ull) & ~((1ull << i0) - 1ull);
           }
         }
         PROF_REDO(__popcll(redo))
         if (redo) rd.fix_up_batch<NPW>(redo, dead, [&](int, const u32x4& v) __attribute__((always_inline)) { add(ps, v); });
       }
-      in_next = fetch_in(tau - 1);
       PROF_MARK(0)
 #pragma unroll
       for (int v = 0; v < 4; ++v) red[wave][4 * cg + v][ccol] = ps[v];
       __syncthreads();
       if (active && t_next < L) Dh = red[0][r8][u] + red[1][r8][u] + red[2][r8][u] + red[3][r8][u];
     } else {
+      factors();
       in_next = fetch_in(tau - 1);
     }
     if (pointwise) {
       float dz[4] = {0.f, 0.f, 0.f, 0.f};
-      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, bf_bits2f((unsigned short)in.dy_bits) + Dh, Dc, dz);
+      if (valid) {
+        const float dh = bf_bits2f((unsigned short)in.dy_bits) + Dh, dc = Dc + dh * f_c;
+        Dc = dc * in.gf;
+        dz[0] = dc * f_i; dz[1] = dc * f_f; dz[2] = dc * f_g; dz[3] = dh * f_o;
+      }
       const unsigned b01 = pack_bf16x2(dz[0], dz[1]), b23 = pack_bf16x2(dz[2], dz[3]);
       const unsigned short bits[4] = {(unsigned short)b01, (unsigned short)(b01 >> 16), (unsigned short)b23, (unsigned short)(b23 >> 16)};
 #pragma unroll
