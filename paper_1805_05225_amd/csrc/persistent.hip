@@ -310,6 +310,9 @@ __device__ __forceinline__ void operands_settle(f32x4& a, f32x4& b, f32x4& c, f3
 __device__ __forceinline__ void mfma_settle(f32x4& a0, f32x4& a1, f32x4& a2, f32x4& a3) {
   asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3));
 }
+__device__ __forceinline__ void mfma_settle(f32x4& a0, f32x4& a1, f32x4& a2, f32x4& a3, f32x4& a4, f32x4& a5, f32x4& a6, f32x4& a7) {
+  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7));
+}
 
 // Is every work-group of this one's exchange group on the same XCD?  Then their ring stores need not be written
 // through to memory: the XCD's L2 is the point where those work-groups meet (measured: one-way latency 212 ns
@@ -690,6 +693,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
                   prep(p + 1, m);
                   __builtin_amdgcn_sched_barrier(0);
                 }
+
               }
         } else {                                           // rare once the sample has turned
           redo |= 3ull << (2 * p);
@@ -704,10 +708,11 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       }
       PROF_REDO(__popcll(redo))
       if (redo) rd.fix_up_batch<NL>(redo, dead, use_single);
-      mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
-      mfma_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+      mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3], acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     }
-    fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
+    // after the ring loads: loads complete in order, and these come from HBM.  (Issued earlier, between the first
+    // pair's MFMAs, they made the step 15 % slower.)
+    fetch_zx(tau + 1, zx_next);
     PROF_MARK(0)
     // accumulator rows 4*(lane/16) + v; this work-group's rows sit in fragment rows 0..7
     if (lane < 32) {
