@@ -567,13 +567,13 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   const unsigned s_off = active ? ((unsigned)b * n + j) * 4u : kParked;        // (half of it in the bf16 array; still parked)
   const unsigned pub_off = publishes ? (unsigned)unit_index * 8u : kParked;
   auto frame_of = [&](const void* base, int t, unsigned bytes, bool present = true) {
-    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (long)t * bytes), 0, present && base != nullptr ? bytes : 0u, kBufFlags);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (unsigned long long)(unsigned)t * bytes), 0, present && base != nullptr ? bytes : 0u, kBufFlags);
   };
   auto fetch_zx = [&](int tau, float (&z)[4]) {
     const bool ok = tau < T;
     const int t = d.rev ? T - 1 - tau : tau;
     const __amdgpu_buffer_rsrc_t rg =
-        __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)d.gates + (long)(ok ? t : 0) * g_bytes), 0, ok ? g_bytes : 0u, kBufFlags);
+        __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)d.gates + (unsigned long long)(unsigned)(ok ? t : 0) * g_bytes), 0, ok ? g_bytes : 0u, kBufFlags);
     const unsigned go = t < L ? g_off : kParked;           // (L is 0 in lanes without a row)
 #pragma unroll
     for (int q = 0; q < 4; ++q) z[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rg, go, (unsigned)q * 4u * n, 2));   // 2: non-temporal
@@ -594,14 +594,6 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
     const RingReader rd = make_reader_half(rin, nkc, ntiles16 * 3, wave, lane, half, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
     f32x4 acc[2][4];
-    // (cleared by moves: starting each chain with an MFMA that adds to the constant 0, as the backward kernel does,
-    // was measured 10 % slower per step here)
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) acc[ct][q] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    operands_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
-    operands_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     {
       // One MFMA of register set `it` into accumulator (ct, q).
       auto mma_one = [&](int it, int ct, int q, const u32x4& a_op) __attribute__((always_inline)) {
@@ -641,6 +633,16 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       for (unsigned poll = 0;; ++poll) {
         x[0] = rd.load_it(rd.it_of(0));
         x[1] = rd.load_it(rd.it_of(1));
+        // The accumulators are cleared while the poll is in flight.  (By moves: starting each chain with an MFMA that
+        // adds to the constant 0, as the backward kernel does, was measured 10 % slower per step here.)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[ct][q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        operands_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+        operands_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+        __builtin_amdgcn_sched_barrier(0);
         if (dead) break;
         const unsigned stale = rd.tag_diff(x[0], rd.it_of(0), tagw) | rd.tag_diff(x[1], rd.it_of(1), tagw);
         if (__builtin_amdgcn_ballot_w64(stale > 0xffffu) == 0ull) break;
@@ -1145,7 +1147,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   const unsigned y_off = active ? ((unsigned)b * d.lddy + j) * 2u : kParked;
   auto frame_of = [&](const void* base, int t, unsigned bytes) {
     const bool ok = t >= 0 && t < T;
-    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (long)(ok ? t : 0) * bytes), 0, ok ? bytes : 0u, kBufFlags);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (unsigned long long)(unsigned)(ok ? t : 0) * bytes), 0, ok ? bytes : 0u, kBufFlags);
   };
   auto ld_f = [&](__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {     // 2: non-temporal
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 2));
