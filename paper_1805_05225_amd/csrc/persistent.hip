@@ -613,10 +613,10 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
             mma_one(2 * p + 1, ct, q, av2);
           }
       };
-      // The stream.  All loads are issued at once and consumed in pairs: a pair is four chunks, and every accumulator
-      // takes its four products in a row, because consecutive MFMAs into the SAME accumulator issue every 16 cycles
-      // while switching accumulators costs as much again (measured: 7.7 ns chained, 18.8 ns when 8 take turns).
-      // An MFMA occupies the issue slot of the wavefront for 4 of those 16 cycles.  What turns the next pair's loads
+      // The stream.  The loads are consumed in pairs: a pair is four chunks, and every accumulator takes its four
+      // products in a row.  An MFMA of this shape issues every 16 cycles (7.05 ns measured, in any order of the
+      // accumulators) and occupies the issue slot of the wavefront for 4 of them: one independent instruction behind
+      // it is free (7.4 ns per MFMA measured), three dependent ones are not (12.4 ns).  What turns the next pair's loads
       // into operands (tag test, masking the tags off, the rotated copies) is cut into single instructions, and one
       // is placed behind each of the first MFMAs of the pair before: there it costs nothing, in front of the pair's
       // own MFMAs it was a fifth of the step.  A pair with a stale tag in any lane is skipped (wave-uniform branch)
@@ -1331,9 +1331,8 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 7][kc * 32 + (lane >> 4) * 8];
       f32x4 acc[16];
-      // Four groups of four column tiles.  Consecutive MFMAs into the SAME accumulator issue every 16 cycles, of which
-      // the wavefront's issue slot is taken for 4; switching accumulators costs as much again (measured: 7.7 ns
-      // chained, 18.8 ns when 8 accumulators take turns), so the k loop is the inner one.  What publishes a group
+      // Four groups of four column tiles, the k loop inside.  An MFMA of this shape issues every 16 cycles, of which
+      // the wavefront's issue slot is taken for 4 (see the forward kernel for the measurements).  What publishes a group
       // (two conversions, three moves and one store per tile) is cut into single instructions, and two of them follow
       // each MFMA of the NEXT group from its third on: by then the group's last result has been written (more than
       // the 20 wait states mfma_settle would spend), and the instructions cost nothing there, where behind the
