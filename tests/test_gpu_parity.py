@@ -271,6 +271,30 @@ def test_single_launch_equals_per_step(dt, B, n, T):
     compare(f2, g2, fo, go, TOL[dt])
 
 
+def test_single_launch_random_shapes_bf16():
+    """Seeded sweep over batch sizes, hidden sizes (multiples of 4 and not, below and above a 32-unit tile, padded
+    and exact), lengths and directions: the single-launch kernels (or their fallbacks) against the oracle."""
+    rng0 = np.random.default_rng(7)
+    for it in range(12):
+        B = int(rng0.choice([1, 3, 9, 16, 17, 32, 33, 64, 100]))
+        n = int(rng0.choice([4, 20, 33, 36, 100, 132, 260, 500, 1000, 1024, 7]))
+        T = int(rng0.integers(1, 30))
+        uni = bool(rng0.integers(0, 2))
+        rng = np.random.default_rng(500 + it)
+        lens = rng.integers(0, T + 1, B)
+        lens[rng.integers(0, B)] = T
+        c = rnd_case(rng, T=T, B=B, n_in=int(rng0.choice([8, 24, 40])), n=n, D=1 if uni else 2, lens=lens, dt="bf16", scale=0.1)
+        direction = int(rng0.choice([1, -1]))
+        print("  random shape", it, "B", B, "n", n, "T", T, "uni %d" % direction if uni else "bi", flush=True)
+        if uni:
+            f, g = run_gpu(c, "bf16", False, direction)
+            fo, go = run_oracle(c, False, direction)
+        else:
+            f, g = run_gpu(c, "bf16", True)
+            fo, go = run_oracle(c, True)
+        compare(f, g, fo, go, TOL["bf16"])
+
+
 # ---- the benchmark configurations ------------------------------------------------------------------------------
 def _config_case(inp, layer=0):
     L = inp["layers"][layer]
