@@ -31,6 +31,10 @@ invariance with NaN padding; batch independence; reversal identity for direction
 composition; time splitting; hoisting exactness; agreement with torch.nn.LSTM (CPU, float64,
 packed sequences) as an independent library implementation; a scalar case evaluated in
 50-digit arithmetic.
+
+Second function pair, time_maxpool_fwd / time_maxpool_bwd (max-pooling in time between encoder layers, see the
+comment above them): pinned by a hand-worked example (tests/golden/maxpool_case.txt), torch's max_pool1d and its
+gradient on unpadded rows, brute force from the definition, NaN-padding invariance and central differences.
 """
 import numpy as np
 
@@ -206,3 +210,53 @@ def blstm_stack_bwd(acts, layers, seq_lens, dy_top):
         grads[k] = (dW_x, dW_h, db)
         d = dx
     return d, grads
+
+
+# ---- max-pooling in time between encoder layers ---------------------------------------------------------------
+# The paper's attention-based speech encoder (Sec. "Speech recognition experiments", Switchboard attention model)
+# "applies max-pooling in the time dimension" between its six bidirectional layers and thereby shortens the input
+# by a factor of 8 in total; window, stride and the treatment of padding are not given.  Reading of this repository:
+# non-overlapping windows of `pool` consecutive frames (stride = window; 2 after each of three layers gives the
+# factor 8), windows are taken inside every sequence separately:
+#     T' = ceil(T / pool),  lens'[b] = ceil(lens[b] / pool),
+#     out[t', b, :] = max over the VALID frames t in [pool t', pool t' + pool), t < lens[b], of y[t, b, :]
+# for t' < lens'[b] and 0 at padded output frames; the last window of a sequence may be short.  Values stored at
+# padded input frames are never read.  The gradient of an output element goes to the frame that supplied the maximum,
+# to the earliest one when several are equal; every other element of dy, padded frames included, is 0.
+
+def time_maxpool_fwd(y, seq_lens, pool):
+    """Returns (out [T', B, F], lens' [B], arg [T', B, F]) with arg = offset of the chosen frame inside its window."""
+    y = np.asarray(y, dtype=F64)
+    T, B, F = y.shape
+    lens = np.full(B, T, dtype=np.int64) if seq_lens is None else np.clip(np.asarray(seq_lens, dtype=np.int64), 0, T)
+    assert pool >= 1
+    Tp = -(-T // pool)
+    lens_out = -(-lens // pool)
+    out = np.zeros((Tp, B, F), dtype=F64)
+    arg = np.zeros((Tp, B, F), dtype=np.int64)
+    for b in range(B):
+        for tp in range(int(lens_out[b])):
+            t0 = pool * tp
+            t1 = min(t0 + pool, int(lens[b]))
+            best = y[t0, b, :].copy()
+            which = np.zeros(F, dtype=np.int64)
+            for t in range(t0 + 1, t1):
+                better = y[t, b, :] > best          # strictly greater: ties keep the earliest frame
+                best = np.where(better, y[t, b, :], best)
+                which = np.where(better, t - t0, which)
+            out[tp, b, :] = best
+            arg[tp, b, :] = which
+    return out, lens_out, arg
+
+
+def time_maxpool_bwd(dout, arg, seq_lens, pool, T):
+    """dy [T, B, F] from dout [T', B, F] and the arg of the forward pass."""
+    dout = np.asarray(dout, dtype=F64)
+    Tp, B, F = dout.shape
+    lens = np.full(B, T, dtype=np.int64) if seq_lens is None else np.clip(np.asarray(seq_lens, dtype=np.int64), 0, T)
+    dy = np.zeros((T, B, F), dtype=F64)
+    cols = np.arange(F)
+    for b in range(B):
+        for tp in range(int(-(-lens[b] // pool))):
+            dy[pool * tp + arg[tp, b, :], b, cols] = dout[tp, b, :]
+    return dy

@@ -401,3 +401,93 @@ def test_stack_matches_manual_chain_and_fd():
             ll = [dict(d) for d in layers]; a = ll[l][key].copy(); a[idx] += s; ll[l][key] = a; return ll
         num = (L(ll=pert(eps)) - L(ll=pert(-eps))) / (2 * eps)
         assert abs(num - grads_[l][gi][idx]) < 1e-7 * max(1.0, np.abs(grads_[l][gi]).max())
+
+
+# ---- max-pooling in time (the speech encoder's pooling between layers) -----------------------------------------
+def _pool_case(T=9, B=4, F=6, lens=(9, 4, 0, 7), seed=5):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((T, B, F)), np.array(lens, dtype=np.int64)
+
+
+def test_maxpool_hand_worked_example():
+    """tests/golden/maxpool_case.txt: a case small enough to do by hand, ties and short last windows included."""
+    import os
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "maxpool_case.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        vals[k] = v
+    T, B, pool = int(vals["T"][0]), int(vals["T"][2]), int(vals["T"][4])
+    lens = np.array(vals["lens"], dtype=np.int64)
+    row_major = lambda k, n: np.array(vals[k], dtype=np.float64).reshape(B, n).T[:, :, None]     # file lists row after row
+    y, out_ref, dout, dy_ref = row_major("y", T), row_major("out", 3), row_major("dout", 3), row_major("dy", T)
+    out, lens_out, arg = O.time_maxpool_fwd(y, lens, pool)
+    assert np.array_equal(out, out_ref)
+    assert np.array_equal(lens_out, np.array(vals["lens_out"], dtype=np.int64))
+    assert np.array_equal(arg[:, :, 0].T.reshape(-1), np.array(vals["arg"], dtype=np.int64))
+    assert np.array_equal(O.time_maxpool_bwd(dout, arg, lens, pool, T), dy_ref)
+
+
+@pytest.mark.parametrize("pool", [2, 3])
+def test_maxpool_against_torch_on_full_length_rows(pool):
+    """An independent library: torch max_pool1d with ceil_mode on rows without padding, forward and gradient."""
+    T, B, F = 11, 3, 4
+    y, _ = _pool_case(T, B, F, (T,) * B)
+    out, lens_out, arg = O.time_maxpool_fwd(y, None, pool)
+    yt = torch.tensor(y, dtype=torch.float64).permute(1, 2, 0).clone().requires_grad_(True)      # [B, F, T]
+    ot = torch.nn.functional.max_pool1d(yt, pool, pool, ceil_mode=True)
+    assert np.array_equal(out, ot.detach().permute(2, 0, 1).numpy())
+    assert np.all(lens_out == -(-T // pool))
+    dout = np.random.default_rng(3).standard_normal(out.shape)
+    ot.backward(torch.tensor(dout).permute(1, 2, 0))
+    assert np.array_equal(O.time_maxpool_bwd(dout, arg, None, pool, T), yt.grad.permute(2, 0, 1).numpy())
+
+
+def test_maxpool_brute_force_padding_and_identities():
+    y, lens = _pool_case()
+    T, B, F = y.shape
+    for pool in (1, 2, 4):
+        out, lens_out, arg = O.time_maxpool_fwd(y, lens, pool)
+        # brute force, element by element, straight from the definition
+        for b in range(B):
+            assert lens_out[b] == -(-lens[b] // pool)
+            for tp in range(out.shape[0]):
+                for f in range(F):
+                    window = [y[t, b, f] for t in range(pool * tp, min(pool * tp + pool, lens[b]))]
+                    assert out[tp, b, f] == (max(window) if window else 0.0)
+                    if window:
+                        assert arg[tp, b, f] == window.index(max(window))        # list.index: the earliest maximum
+        # padded frames are never read
+        ynan = y.copy()
+        for b in range(B):
+            ynan[lens[b]:, b, :] = np.nan
+        out2, _, arg2 = O.time_maxpool_fwd(ynan, lens, pool)
+        assert np.array_equal(out, out2) and np.array_equal(arg, arg2)
+        # the gradient is moved, not changed: same sum, one non-zero per window and feature, nothing at padded frames
+        dout = np.random.default_rng(9).standard_normal(out.shape)
+        dy = O.time_maxpool_bwd(dout, arg, lens, pool, T)
+        valid = np.arange(out.shape[0])[:, None] < lens_out[None, :]
+        assert np.isclose(dy.sum(), (dout * valid[:, :, None]).sum())
+        assert np.count_nonzero(dy) == int(valid.sum()) * F
+        for b in range(B):
+            assert not dy[lens[b]:, b, :].any()
+        if pool == 1:                                           # windows of one frame: the identity on valid frames
+            mask = (np.arange(T)[:, None] < lens[None, :])[:, :, None]
+            assert np.array_equal(out, y * mask) and np.array_equal(dy, dout * mask)
+
+
+def test_maxpool_gradient_is_the_derivative():
+    """Central differences of L = sum(dout * out) away from ties."""
+    y, lens = _pool_case(T=6, B=2, F=3, lens=(6, 5), seed=11)
+    pool = 2
+    out, _, arg = O.time_maxpool_fwd(y, lens, pool)
+    dout = np.random.default_rng(4).standard_normal(out.shape)
+    dy = O.time_maxpool_bwd(dout, arg, lens, pool, y.shape[0])
+    eps = 1e-6
+    for idx in [(0, 0, 0), (1, 0, 2), (4, 1, 1), (5, 0, 0), (3, 1, 2)]:
+        yp, ym = y.copy(), y.copy()
+        yp[idx] += eps
+        ym[idx] -= eps
+        num = ((O.time_maxpool_fwd(yp, lens, pool)[0] - O.time_maxpool_fwd(ym, lens, pool)[0]) * dout).sum() / (2 * eps)
+        assert abs(num - dy[idx]) < 1e-8
