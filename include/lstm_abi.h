@@ -137,6 +137,31 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
               const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const float* bias,
               int accumulate, const int32_t* lens, int Bt, int T, void* stream);
 
+/* Max-pooling in time between encoder layers.  The paper's attention-based speech encoder (Sec. "Speech
+ * recognition experiments", the attention model on Switchboard: "a 6 layer bidirectional encoder, which also
+ * applies max-pooling in the time dimension", a reduction by a factor of 8 in total) pools the layer outputs
+ * over time; window, stride and padding are not given.  This library's reading: non-overlapping windows of
+ * `pool` frames (stride = window; pool = 2 after each of three layers gives the factor 8), taken inside every
+ * sequence separately:
+ *     T' = ceil(T / pool),  lens_out[b] = ceil(seq_lens[b] / pool),
+ *     out[t', b, :] = max over the valid frames t in [pool t', pool t' + pool), t < seq_lens[b], of y[t, b, :]
+ * for t' < lens_out[b], and 0 at padded output frames (the last window of a sequence may be short; values stored
+ * at padded input frames are never read).  The backward call sends the gradient of an output element to the
+ * frame that supplied the maximum - the earliest one if several are equal - and writes 0 everywhere else,
+ * padded frames included: dy is written completely and need not be cleared.
+ *   dtype: LSTM_F32 (float tensors) or LSTM_BF16_F32STATE (bfloat16 tensors); the maximum is exact in both.
+ *   y [T][B][ldy >= F], out [T'][B][ldo >= F], dout like out, dy like y: device pointers, element-aligned
+ *   (16-byte aligned rows are faster); leading dimensions in elements.  1 <= pool <= 255.
+ *   arg: device, T' * B * F bytes, written by the forward call (offset of the chosen frame inside its window)
+ *   and read by the backward call; may be NULL in the forward call if no backward call follows.
+ *   seq_lens: device int32[B] or NULL (all rows have length T); lens_out: device int32[B] or NULL.
+ * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM (negative sizes, F < 1, pool out of range, ld < F), LSTM_ERR_UNSUPPORTED
+ * (dtype), LSTM_ERR_ALIGN, LSTM_ERR_HIP.  The calls only enqueue work on `stream`. */
+int lstm_time_pool_fwd(int dtype, int T, int B, int F, int pool, const void* y, int64_t ldy, const int32_t* seq_lens,
+                       void* out, int64_t ldo, uint8_t* arg, int32_t* lens_out, void* stream);
+int lstm_time_pool_bwd(int dtype, int T, int B, int F, int pool, const void* dout, int64_t ldo, const uint8_t* arg,
+                       const int32_t* seq_lens, void* dy, int64_t ldy, void* stream);
+
 /* Diagnostic for the single-launch (persistent) recurrent kernels, whose work-groups wait for each
  * other between time steps with BOUNDED waits.  If a wait ever expired, the kernel drained early, the
  * results of that call are invalid and a word in the workspace says so.  This call copies that word

@@ -14,7 +14,7 @@ LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm
 
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED = 1, 2, 4, 8
-EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
+EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_time_pool_fwd", "lstm_time_pool_bwd", "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
            "lstm_strerror")
 
 
@@ -48,6 +48,11 @@ def _load():
         f.argtypes = [dp] + [vp] * 20
     lib.lstm_gemm.restype = ip
     lib.lstm_gemm.argtypes = [ip] * 7 + [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ip, vp, ip, ip, vp]
+    i64 = ctypes.c_int64
+    lib.lstm_time_pool_fwd.restype = ip
+    lib.lstm_time_pool_fwd.argtypes = [ip] * 5 + [vp, i64, vp, vp, i64, vp, vp, vp]
+    lib.lstm_time_pool_bwd.restype = ip
+    lib.lstm_time_pool_bwd.argtypes = [ip] * 5 + [vp, i64, vp, vp, vp, i64, vp]
     lib.lstm_sync_status.restype = ip
     lib.lstm_sync_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
     lib.lstm_profile_enable.restype = ip
@@ -162,6 +167,29 @@ def gemm(A, B, *, a_kcontig, b_kcontig, M, N, K, out_dtype=torch.float32, bias=N
                          _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(C), C.stride(0), _ptr(bias), int(accumulate),
                          _ptr(lens), Bt, T, _stream()))
     return C
+
+
+def time_pool_fwd(y, seq_lens, pool, *, want_arg=True):
+    """Max-pooling in time of y [T, B, F] (float or bfloat16) with windows of `pool` frames inside every sequence.
+    -> dict(out [T', B, F], lens [B] int32, arg [T', B, F] uint8 or None)."""
+    T, B, F = y.shape
+    assert y.stride(2) == 1 and y.stride(0) == B * y.stride(1)
+    Tp = -(-T // pool)
+    out = torch.empty(Tp, B, F, dtype=y.dtype, device=y.device)
+    arg = torch.empty(Tp, B, F, dtype=torch.uint8, device=y.device) if want_arg else None
+    lens_out = torch.empty(B, dtype=torch.int32, device=y.device)
+    _check(lib.lstm_time_pool_fwd(_dtype_of(y), T, B, F, pool, y.data_ptr(), y.stride(1), _ptr(seq_lens), _ptr(out), F, _ptr(arg),
+                                  _ptr(lens_out), _stream()))
+    return dict(out=out, lens=lens_out, arg=arg)
+
+
+def time_pool_bwd(dout, arg, seq_lens, pool, T):
+    """Gradient of time_pool_fwd: dy [T, B, F] from dout [T', B, F]."""
+    Tp, B, F = dout.shape
+    assert dout.is_contiguous()
+    dy = torch.empty(T, B, F, dtype=dout.dtype, device=dout.device)
+    _check(lib.lstm_time_pool_bwd(_dtype_of(dout), T, B, F, pool, _ptr(dout), F, _ptr(arg), _ptr(seq_lens), _ptr(dy), F, _stream()))
+    return dy
 
 
 PHASES = ("prep", "gemm_zx", "loop_fwd", "loop_bwd", "gemm_dx", "gemm_dwx", "gemm_dwh", "db")

@@ -226,6 +226,11 @@ hipError_t launch_colsum(const void* DZ, float* db, float* part, int rows, int n
 // Wcat[ndir][4n][Kc] = [W_x^T | 0 up to n_in_pad | W_h^T | 0 up to Kc]
 hipError_t launch_pack_wcat(const void* W_x, const void* W_h, void* Wcat, int n_in, int n_in_pad, int n, int Kc, int ndir, hipStream_t s);
 // Acat[ndir][B][Kc] = [x | 0 | bf16(h[dir]) | 0] in the same column layout (h == NULL: zeros)
+// max-pooling in time (time_pool.hip); arg [T'][B][F] bytes, lens_out [B] may be NULL
+hipError_t launch_time_pool_fwd(bool bf16, const void* y, long ldy, const int* lens, void* out, long ldo, uint8_t* arg, int* lens_out, int T,
+                                int B, int F, int pool, hipStream_t s);
+hipError_t launch_time_pool_bwd(bool bf16, const void* dout, long ldo, const uint8_t* arg, const int* lens, void* dy, long ldy, int T, int B,
+                                int F, int pool, hipStream_t s);
 hipError_t launch_concat_xh(const void* x, const float* h, void* Acat, int B, int n_in, int n_in_pad, int n, int Kc, int ndir, hipStream_t s);
 // cell update from the pre-activations z = bias + sum of `nparts` partial products, laid out [ndir][nparts][part floats]
 // with [B][4n] inside a part.  h_in, c_in [ndir][B][n]: state entering the step (NULL = zeros); h_out, c_out: state

@@ -661,6 +661,42 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
   return LSTM_OK;
 }
 
+static int pool_args(int dtype, int T, int B, int F, int pool, const void* a, int64_t lda, const void* o, int64_t ldo) {
+  if (!a || !o) return LSTM_ERR_NULL;
+  if (T < 0 || B < 0 || F < 1 || pool < 1 || pool > 255 || lda < F || ldo < F || B > 65535) return LSTM_ERR_DIM;
+  if (dtype != LSTM_F32 && dtype != LSTM_BF16_F32STATE) return LSTM_ERR_UNSUPPORTED;
+  const uintptr_t mask = dtype == LSTM_F32 ? 3 : 1;
+  if (((uintptr_t)a | (uintptr_t)o) & mask) return LSTM_ERR_ALIGN;
+  return LSTM_OK;
+}
+
+int lstm_time_pool_fwd(int dtype, int T, int B, int F, int pool, const void* y, int64_t ldy, const int32_t* seq_lens, void* out,
+                       int64_t ldo, uint8_t* arg, int32_t* lens_out, void* stream) {
+  int rc = pool_args(dtype, T, B, F, pool, y, ldy, out, ldo);
+  if (rc) return rc;
+  if ((rc = lstm::check_device())) return rc;
+  if (lstm::launch_time_pool_fwd(dtype == LSTM_BF16_F32STATE, y, ldy, seq_lens, out, ldo, arg, lens_out, T, B, F, pool,
+                                 (hipStream_t)stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return LSTM_ERR_HIP;
+  }
+  return LSTM_OK;
+}
+
+int lstm_time_pool_bwd(int dtype, int T, int B, int F, int pool, const void* dout, int64_t ldo, const uint8_t* arg,
+                       const int32_t* seq_lens, void* dy, int64_t ldy, void* stream) {
+  int rc = pool_args(dtype, T, B, F, pool, dout, ldo, dy, ldy);
+  if (rc) return rc;
+  if (!arg) return LSTM_ERR_NULL;
+  if ((rc = lstm::check_device())) return rc;
+  if (lstm::launch_time_pool_bwd(dtype == LSTM_BF16_F32STATE, dout, ldo, arg, seq_lens, dy, ldy, T, B, F, pool,
+                                 (hipStream_t)stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return LSTM_ERR_HIP;
+  }
+  return LSTM_OK;
+}
+
 int lstm_sync_status(const void* workspace, int32_t* timed_out) {
   if (!workspace || !timed_out) return LSTM_ERR_NULL;
   const char* ws = (const char*)(((uintptr_t)workspace + lstm::kAlign - 1) / lstm::kAlign * lstm::kAlign);

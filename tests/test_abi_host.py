@@ -111,6 +111,19 @@ def test_empty_batch_is_a_noop_and_inference_needs_no_reserve():
         assert _fwd(d, reserve=None, c=None) == -7             # valid call, but no gfx950 device here
 
 
+def test_time_pool_argument_errors():
+    f, b = Bn.lib.lstm_time_pool_fwd, Bn.lib.lstm_time_pool_bwd
+    ok = dict(dtype=1, T=8, B=2, F=16, pool=2)
+    fwd = lambda y=P, out=P, ldy=16, ldo=16, **o: f(*[{**ok, **o}[k] for k in ("dtype", "T", "B", "F", "pool")], y, ldy, None, out, ldo, None, None, None)
+    bwd = lambda dout=P, dy=P, arg=P, ldo=16, ldy=16, **o: b(*[{**ok, **o}[k] for k in ("dtype", "T", "B", "F", "pool")], dout, ldo, arg, None, dy, ldy, None)
+    assert fwd(y=None) == -1 and fwd(out=None) == -1 and bwd(dout=None) == -1 and bwd(dy=None) == -1 and bwd(arg=None) == -1
+    for bad in (dict(T=-1), dict(B=-1), dict(F=0), dict(pool=0), dict(pool=256), dict(B=70000)):
+        assert fwd(**bad) == -2 and bwd(**bad) == -2
+    assert fwd(ldy=15) == -2 and fwd(ldo=8) == -2 and bwd(ldy=3) == -2
+    assert fwd(dtype=7) == -4 and bwd(dtype=-1) == -4
+    assert fwd(y=P + 1) == -5 and bwd(dy=P + 1) == -5 and fwd(dtype=0, out=P + 2) == -5
+
+
 def test_strerror():
     for s in range(0, -8, -1):
         assert Bn.strerror(s) and "unknown" not in Bn.strerror(s)

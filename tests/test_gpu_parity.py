@@ -295,6 +295,48 @@ def test_single_launch_random_shapes_bf16():
         compare(f, g, fo, go, TOL["bf16"])
 
 
+# ---- max-pooling in time between encoder layers: exact operation, bit-exact bar ---------------------------------
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+@pytest.mark.parametrize("T,B,F,pool", [(9, 4, 16, 2), (7, 3, 5, 3), (1, 2, 8, 2), (40, 33, 2048, 2), (13, 5, 264, 4), (6, 2, 24, 1)])
+def test_time_pool_matches_oracle_exactly(dt, T, B, F, pool):
+    rng = np.random.default_rng(T * 1000 + F + pool)
+    lens = rng.integers(0, T + 1, B)
+    lens[0] = T
+    if B > 1:
+        lens[1] = 0                                           # an empty row
+    y = dev(rng.integers(-6, 7, (T, B, F)) * 0.25 if F == 16 else rng.standard_normal((T, B, F)), dt)      # F == 16: many ties
+    yo = host(y)                                              # the oracle gets the storage-rounded values
+    yo_nan = yo.copy()
+    for b in range(B):
+        yo_nan[lens[b]:, b, :] = np.nan                       # and must not look at padded frames
+    out_o, lens_o, arg_o = O.time_maxpool_fwd(yo_nan, lens, pool)
+    r = Bn.time_pool_fwd(y, dev(lens), pool)
+    assert np.array_equal(host(r["out"]), out_o)
+    assert np.array_equal(r["lens"].cpu().numpy(), lens_o)
+    valid = (np.arange(out_o.shape[0])[:, None] < lens_o[None, :])[:, :, None]
+    assert np.array_equal(np.where(valid, r["arg"].cpu().numpy(), 0), arg_o)
+    dout = dev(rng.standard_normal(out_o.shape), dt)
+    dy = Bn.time_pool_bwd(dout, r["arg"], dev(lens), pool, T)
+    assert np.array_equal(host(dy), O.time_maxpool_bwd(host(dout), arg_o, lens, pool, T))
+    # without lengths every row is full
+    r2 = Bn.time_pool_fwd(y, None, pool, want_arg=False)
+    assert np.array_equal(host(r2["out"]), O.time_maxpool_fwd(yo, None, pool)[0]) and r2["arg"] is None
+
+
+def test_time_pool_unaligned_rows_and_strided_input():
+    """Rows that are not 16-byte multiples (scalar path) and a pooled view of one direction's half of a wider tensor."""
+    rng = np.random.default_rng(77)
+    T, B, F, pool = 10, 3, 24, 2
+    lens = np.array([10, 7, 3])
+    wide = dev(rng.standard_normal((T, B, 2 * F + 3)), "bf16")
+    y = wide[:, :, 3:3 + F]                                   # element-aligned only, leading dimension 2F + 3
+    r = Bn.time_pool_fwd(y, dev(lens), pool)
+    out_o, _, arg_o = O.time_maxpool_fwd(host(y), lens, pool)
+    assert np.array_equal(host(r["out"]), out_o)
+    dout = dev(rng.standard_normal(out_o.shape), "bf16")
+    assert np.array_equal(host(Bn.time_pool_bwd(dout, r["arg"], dev(lens), pool, T)), O.time_maxpool_bwd(host(dout), arg_o, lens, pool, T))
+
+
 # ---- the benchmark configurations ------------------------------------------------------------------------------
 def _config_case(inp, layer=0):
     L = inp["layers"][layer]
