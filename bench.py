@@ -179,12 +179,137 @@ def bench_decoder(args, Bn, synth):
     print(json.dumps(out))
 
 
+class PooledStack:
+    """The config-4 stack with max-pooling in time (windows of 2 frames) behind layers 1, 2 and 3: the shape of the
+    paper's attention-based speech encoder (6 bidirectional layers, input shortened by a factor of 8 in total)."""
+
+    def __init__(self, Bn, x, lens, dy_top, layers, pool_after=(0, 1, 2), pool=2):
+        import ctypes
+        self.Bn, self.ct, self.layers, self.pool, self.pool_after = Bn, ctypes, layers, pool, set(pool_after)
+        dev = x.device
+        B = x.shape[1]
+        n = layers[0][1].shape[-2]
+        dtype_id = Bn.LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else Bn.LSTM_F32
+        self.dtype_id = dtype_id
+        self.bufs, wmax, cur, cur_lens, lens_np = [], 0, x, lens, lens.cpu().numpy()
+        self.frames_per_layer = []
+        for k, (Wx, Wh, b) in enumerate(layers):
+            T, cur_in = cur.shape[0], cur.shape[2]
+            desc = Bn.make_desc(T, B, cur_in, n, dtype_id)
+            rb, wb = Bn.query(desc, True)
+            wmax = max(wmax, wb)
+            desc.reserve_bytes = rb
+            self.frames_per_layer.append(int(lens_np.sum()))
+            bf = dict(desc=desc, T=T, xin=cur, lens=cur_lens, reserve=torch.empty(rb, dtype=torch.uint8, device=dev),
+                      y=torch.empty(T, B, 2 * n, dtype=x.dtype, device=dev), c=torch.empty(2, T, B, n, dtype=torch.float32, device=dev),
+                      dx=torch.empty(T, B, cur_in, dtype=x.dtype, device=dev), dW_x=torch.empty_like(Wx, dtype=torch.float32),
+                      dW_h=torch.empty_like(Wh, dtype=torch.float32), db=torch.empty(2, 4 * n, dtype=torch.float32, device=dev))
+            cur = bf["y"]
+            if k in self.pool_after:
+                Tp = -(-T // pool)
+                bf.update(pooled=torch.empty(Tp, B, 2 * n, dtype=x.dtype, device=dev), arg=torch.empty(Tp, B, 2 * n, dtype=torch.uint8, device=dev),
+                          lens_out=torch.empty(B, dtype=torch.int32, device=dev), dy=torch.empty(T, B, 2 * n, dtype=x.dtype, device=dev))
+                cur = bf["pooled"]
+                cur_lens = bf["lens_out"]
+                lens_np = -(-lens_np // pool)
+            self.bufs.append(bf)
+        self.dy_top = dy_top[:cur.shape[0]].contiguous()
+        self.ws = torch.empty(wmax, dtype=torch.uint8, device=dev)
+        for bf in self.bufs:
+            bf["desc"].workspace_bytes = wmax
+        self.pool_events = []
+
+    def step(self, timed=False):
+        Bn, ct, lib = self.Bn, self.ct, self.Bn.lib
+        s = torch.cuda.current_stream().cuda_stream
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        F = self.bufs[0]["y"].shape[2]
+        for (Wx, Wh, b), bf in zip(self.layers, self.bufs):
+            rc = lib.blstm_fwd(ct.byref(bf["desc"]), bf["xin"].data_ptr(), Wx.data_ptr(), Wh.data_ptr(), b.data_ptr(), None, None,
+                               bf["lens"].data_ptr(), bf["y"].data_ptr(), bf["c"].data_ptr(), None, None, bf["reserve"].data_ptr(),
+                               self.ws.data_ptr(), s)
+            assert rc == 0, Bn.strerror(rc)
+            if "pooled" in bf:
+                e0, e1 = ev(), ev()
+                e0.record()
+                rc = lib.lstm_time_pool_fwd(self.dtype_id, bf["T"], bf["y"].shape[1], F, self.pool, bf["y"].data_ptr(), F, bf["lens"].data_ptr(),
+                                            bf["pooled"].data_ptr(), F, bf["arg"].data_ptr(), bf["lens_out"].data_ptr(), s)
+                e1.record()
+                assert rc == 0, Bn.strerror(rc)
+                if timed:
+                    self.pool_events.append(("fwd", bf["T"], e0, e1))
+        d = self.dy_top
+        for k in range(len(self.layers) - 1, -1, -1):
+            Wx, Wh, b = self.layers[k]
+            bf = self.bufs[k]
+            if "pooled" in bf:                                   # d is the gradient of the pooled output
+                e0, e1 = ev(), ev()
+                e0.record()
+                rc = lib.lstm_time_pool_bwd(self.dtype_id, bf["T"], bf["y"].shape[1], F, self.pool, d.data_ptr(), F, bf["arg"].data_ptr(),
+                                            bf["lens"].data_ptr(), bf["dy"].data_ptr(), F, s)
+                e1.record()
+                assert rc == 0, Bn.strerror(rc)
+                if timed:
+                    self.pool_events.append(("bwd", bf["T"], e0, e1))
+                d = bf["dy"]
+            rc = lib.blstm_bwd(ct.byref(bf["desc"]), bf["xin"].data_ptr(), Wx.data_ptr(), Wh.data_ptr(), None, None, bf["lens"].data_ptr(),
+                               bf["y"].data_ptr(), bf["c"].data_ptr(), bf["reserve"].data_ptr(), d.data_ptr(), None, None, bf["dx"].data_ptr(),
+                               bf["dW_x"].data_ptr(), bf["dW_h"].data_ptr(), bf["db"].data_ptr(), None, None, self.ws.data_ptr(), s)
+            assert rc == 0, Bn.strerror(rc)
+            d = bf["dx"]
+
+
+def bench_pooled(args, Bn, synth):
+    """--config 6: config 4's stack with max-pooling in time behind layers 1, 2 and 3 (total factor 8)."""
+    inp = synth.make(4)
+    cfg = inp["cfg"]
+    frames = synth.real_frames(inp)
+    x, lens, dy, layers = build_stack(inp, Bn)
+    st = PooledStack(Bn, x, lens, dy, layers)
+    for _ in range(args.warmup):
+        st.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.step(timed=True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    B, n, esz = cfg["B"], cfg["n"], 2
+    F = 2 * n
+    # pooling kernels: algorithmic bytes = input read once + output written once (+ one argument byte per output element);
+    # the backward kernel writes every frame of dy, padded ones included (zeros), so that nothing has to be cleared first
+    ms = {"fwd": 0.0, "bwd": 0.0}
+    by = {"fwd": 0.0, "bwd": 0.0}
+    for kind, T, e0, e1 in st.pool_events:
+        ms[kind] += e0.elapsed_time(e1)
+    for k, bf in enumerate(st.bufs):
+        if "pooled" not in bf:
+            continue
+        fin, fout = st.frames_per_layer[k], st.frames_per_layer[k + 1]
+        by["fwd"] += args.steps * (fin * F * esz + fout * F * (esz + 1))
+        by["bwd"] += args.steps * (fout * F * (esz + 1) + bf["T"] * B * F * esz)
+    tot_ms, tot_by = ms["fwd"] + ms["bwd"], by["fwd"] + by["bwd"]
+    gbs = tot_by / (tot_ms * 1e-3) / 1e9 if tot_ms > 0 else 0.0
+    out = {
+        "metric": "BLSTM fwd+bwd frames/sec (n=%d), encoder with time pooling" % n, "value": frames * args.steps / dt, "unit": "frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": "config 6: config 4's 6-layer BLSTM stack (n_in=40, n=%d, B=%d, T=%d, %d real input frames) with max-pooling "
+                               "in time, windows of 2 frames, behind layers 1, 2 and 3; frames per layer %s; forward + backward" % (
+                                   n, B, inp["T"], frames, st.frames_per_layer)},
+        "roofline": {"bound": "hbm", "kernel": "time_pool_fwd_kernel + time_pool_bwd_kernel (three of each per step)", "achieved": gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "ms_per_step": tot_ms / args.steps, "algorithmic_bytes_per_step": tot_by / args.steps},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell)")
+    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell; 6 = config 4 with max-pooling in time between layers)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--per-step", action="store_true", help="force one launch per time step")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -204,6 +329,9 @@ def main():
     torch.cuda.set_device(0)
     if args.config == 5:
         bench_decoder(args, Bn, synth)
+        return
+    if args.config == 6:
+        bench_pooled(args, Bn, synth)
         return
     inp = synth.make(args.config)
     cfg = inp["cfg"]
