@@ -35,6 +35,10 @@ packed sequences) as an independent library implementation; a scalar case evalua
 Second function pair, time_maxpool_fwd / time_maxpool_bwd (max-pooling in time between encoder layers, see the
 comment above them): pinned by a hand-worked example (tests/golden/maxpool_case.txt), torch's max_pool1d and its
 gradient on unpadded rows, brute force from the definition, NaN-padding invariance and central differences.
+
+encoder_stack_fwd / encoder_stack_bwd (one bidirectional layer below unidirectional ones): pinned by chained
+torch.nn.LSTM modules over packed sequences (outputs and every gradient), by its reduction to the bidirectional stack,
+by causality of the top layer and by central differences.
 """
 import numpy as np
 
@@ -212,10 +216,50 @@ def blstm_stack_bwd(acts, layers, seq_lens, dy_top):
     return d, grads
 
 
+# ---- encoders that mix bidirectional and unidirectional layers --------------------------------------------------
+# The translation encoder of the paper's speed comparison (Sec. 4, caption of the training-speed table; Sec. 5 for the
+# comparison system) has one bidirectional layer at the bottom and 3 or 5 unidirectional layers above it.  A layer is
+# bidirectional here when its weights carry two directions (W_x[2, n_in, 4n]) and runs forward in time when they carry
+# one (W_x[1, n_in, 4n]); the layer above a bidirectional one sees 2n inputs, the layer above a unidirectional one n.
+def encoder_stack_fwd(x, layers, seq_lens):
+    """layers = list of dicts with W_x[D,n_in_k,4n], W_h[D,n,4n], b[D,4n] (or None), D in {1, 2}; zero initial
+    states.  -> list of per-layer inputs, final y ([T,B,D_top*n])."""
+    acts = []
+    cur = np.asarray(x, dtype=F64)
+    for L in layers:
+        acts.append(cur)
+        D = np.asarray(L["W_x"]).shape[0]
+        b = L.get("b")
+        if D == 2:
+            cur = blstm_fwd(cur, L["W_x"], L["W_h"], b, None, None, seq_lens)[0]
+        else:
+            cur = lstm_fwd(cur, L["W_x"][0], L["W_h"][0], None if b is None else b[0], None, None, seq_lens, direction=1)[0]
+    return acts, cur
+
+
+def encoder_stack_bwd(acts, layers, seq_lens, dy_top):
+    """Back-propagate dy_top through the mixed stack.  -> dx of the bottom layer, list of (dW_x, dW_h, db) per
+    layer, bottom first, each with the leading direction axis of its layer."""
+    grads = [None] * len(layers)
+    d = np.asarray(dy_top, dtype=F64)
+    for k in range(len(layers) - 1, -1, -1):
+        L = layers[k]
+        b = L.get("b")
+        if np.asarray(L["W_x"]).shape[0] == 2:
+            dx, dW_x, dW_h, db, _, _ = blstm_bwd(acts[k], L["W_x"], L["W_h"], b, None, None, seq_lens, d)
+        else:
+            dx, dW_x, dW_h, db, _, _ = lstm_bwd(acts[k], L["W_x"][0], L["W_h"][0], None if b is None else b[0], None, None,
+                                                seq_lens, 1, d)
+            dW_x, dW_h, db = dW_x[None], dW_h[None], db[None]
+        grads[k] = (dW_x, dW_h, db)
+        d = dx
+    return d, grads
+
+
 # ---- max-pooling in time between encoder layers ---------------------------------------------------------------
 # The paper's attention-based speech encoder (Sec. "Speech recognition experiments", Switchboard attention model)
-# "applies max-pooling in the time dimension" between its six bidirectional layers and thereby shortens the input
-# by a factor of 8 in total; window, stride and the treatment of padding are not given.  Reading of this repository:
+# takes a maximum over time between its six bidirectional layers, which shortens the input by a factor of 8 in
+# total; window, stride and the treatment of padding are not given.  Reading of this repository:
 # non-overlapping windows of `pool` consecutive frames (stride = window; 2 after each of three layers gives the
 # factor 8), windows are taken inside every sequence separately:
 #     T' = ceil(T / pool),  lens'[b] = ceil(lens[b] / pool),

@@ -403,6 +403,82 @@ def test_stack_matches_manual_chain_and_fd():
         assert abs(num - grads_[l][gi][idx]) < 1e-7 * max(1.0, np.abs(grads_[l][gi]).max())
 
 
+def _mixed_layers(rng, n_in, n, n_uni):
+    layers = [dict(W_x=rng.uniform(-.5, .5, (2, n_in, 4 * n)), W_h=rng.uniform(-.5, .5, (2, n, 4 * n)), b=rng.uniform(-.5, .5, (2, 4 * n)))]
+    for l in range(n_uni):
+        layers.append(dict(W_x=rng.uniform(-.5, .5, (1, 2 * n if l == 0 else n, 4 * n)), W_h=rng.uniform(-.5, .5, (1, n, 4 * n)),
+                           b=rng.uniform(-.5, .5, (1, 4 * n))))
+    return layers
+
+
+def test_mixed_stack_against_torch_modules():
+    """One bidirectional layer below two unidirectional ones (Sec. 4, caption of the training-speed table) against
+    torch.nn.LSTM modules chained over packed sequences: outputs and every gradient."""
+    rng = np.random.default_rng(21)
+    T, B, n_in, n = 7, 4, 3, 5
+    lens = np.array([7, 2, 5, 1])
+    layers = _mixed_layers(rng, n_in, n, 2)
+    x = rng.standard_normal((T, B, n_in)); dy = rng.standard_normal((T, B, n))
+    acts, y = O.encoder_stack_fwd(x, layers, lens)
+    dx, grads_ = O.encoder_stack_bwd(acts, layers, lens, dy)
+    assert y.shape == (T, B, n) and acts[1].shape == (T, B, 2 * n) and acts[2].shape == (T, B, n)
+    mods = [torch.nn.LSTM(n_in, n, bidirectional=True).double(), torch.nn.LSTM(2 * n, n).double(), torch.nn.LSTM(n, n).double()]
+    with torch.no_grad():
+        for m, L in zip(mods, layers):
+            for d, suf in enumerate(("", "_reverse")[:L["W_x"].shape[0]]):
+                getattr(m, "weight_ih_l0" + suf).copy_(torch.from_numpy(L["W_x"][d].T.copy()))
+                getattr(m, "weight_hh_l0" + suf).copy_(torch.from_numpy(L["W_h"][d].T.copy()))
+                getattr(m, "bias_ih_l0" + suf).copy_(torch.from_numpy(L["b"][d]))
+                getattr(m, "bias_hh_l0" + suf).zero_()
+    xt = torch.from_numpy(x).requires_grad_(True)
+    cur = torch.nn.utils.rnn.pack_padded_sequence(xt, torch.from_numpy(lens), enforce_sorted=False)
+    for m in mods:
+        cur, _ = m(cur)
+    yt, _ = torch.nn.utils.rnn.pad_packed_sequence(cur, total_length=T)
+    (torch.from_numpy(dy) * yt).sum().backward()
+    tol = dict(rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(y, yt.detach().numpy(), **tol)
+    np.testing.assert_allclose(dx, xt.grad.numpy(), **tol)
+    for m, L, g in zip(mods, layers, grads_):
+        assert g[0].shape == L["W_x"].shape and g[1].shape == L["W_h"].shape and g[2].shape == L["b"].shape
+        for d, suf in enumerate(("", "_reverse")[:L["W_x"].shape[0]]):
+            np.testing.assert_allclose(g[0][d], getattr(m, "weight_ih_l0" + suf).grad.numpy().T, **tol)
+            np.testing.assert_allclose(g[1][d], getattr(m, "weight_hh_l0" + suf).grad.numpy().T, **tol)
+            np.testing.assert_allclose(g[2][d], getattr(m, "bias_ih_l0" + suf).grad.numpy(), **tol)
+
+
+def test_mixed_stack_reduces_to_its_parts_and_fd():
+    """An all-bidirectional list gives the bidirectional stack; a unidirectional layer on top never looks ahead
+    (its output at frame t does not change when later frames of its input change); central differences."""
+    rng = np.random.default_rng(22)
+    T, B, n_in, n = 6, 3, 3, 4
+    lens = np.array([6, 4, 0])
+    bl = [dict(W_x=rng.uniform(-.5, .5, (2, n_in if l == 0 else 2 * n, 4 * n)), W_h=rng.uniform(-.5, .5, (2, n, 4 * n)),
+               b=rng.uniform(-.5, .5, (2, 4 * n))) for l in range(2)]
+    x = rng.standard_normal((T, B, n_in))
+    np.testing.assert_array_equal(O.encoder_stack_fwd(x, bl, lens)[1], O.blstm_stack_fwd(x, bl, lens)[1])
+    layers = _mixed_layers(rng, n_in, n, 3)
+    dy = rng.standard_normal((T, B, n))
+    acts, y = O.encoder_stack_fwd(x, layers, lens)
+    top_in = acts[-1].copy(); top_in[4:] += 1.0                 # change the last layer's input from frame 4 on
+    y2 = O.lstm_fwd(top_in, layers[-1]["W_x"][0], layers[-1]["W_h"][0], layers[-1]["b"][0], None, None, lens, direction=1)[0]
+    np.testing.assert_array_equal(y2[:4], y[:4])
+    assert np.abs(y2[4:, 0] - y[4:, 0]).max() > 1e-3
+    dx, grads_ = O.encoder_stack_bwd(acts, layers, lens, dy)
+    assert np.all(dx[:, 2] == 0) and np.all(dx[4:, 1] == 0)
+    def L(xx=x, ll=layers):
+        return (O.encoder_stack_fwd(xx, ll, lens)[1] * dy).sum()
+    eps = 1e-5
+    for idx in [(0, 0, 0), (5, 0, 2), (3, 1, 1)]:
+        p = x.copy(); p[idx] += eps; m = x.copy(); m[idx] -= eps
+        assert abs((L(p) - L(m)) / (2 * eps) - dx[idx]) < 1e-7 * max(1.0, np.abs(dx).max())
+    for (l, key, gi, idx) in [(0, "W_x", 0, (1, 2, 5)), (1, "W_x", 0, (0, 7, 3)), (2, "W_h", 1, (0, 3, 9)), (3, "b", 2, (0, 6)), (3, "W_x", 0, (0, 1, 15))]:
+        def pert(s):
+            ll = [dict(d) for d in layers]; a = ll[l][key].copy(); a[idx] += s; ll[l][key] = a; return ll
+        num = (L(ll=pert(eps)) - L(ll=pert(-eps))) / (2 * eps)
+        assert abs(num - grads_[l][gi][idx]) < 1e-7 * max(1.0, np.abs(grads_[l][gi]).max())
+
+
 # ---- max-pooling in time (the speech encoder's pooling between layers) -----------------------------------------
 def _pool_case(T=9, B=4, F=6, lens=(9, 4, 0, 7), seed=5):
     rng = np.random.default_rng(seed)
