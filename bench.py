@@ -90,6 +90,102 @@ class Stack:
             d = bf["dx"]
 
 
+class MixedStack:
+    """One bidirectional layer below unidirectional ones; every buffer allocated once."""
+
+    def __init__(self, Bn, x, lens, dy, layers):
+        import ctypes
+        self.Bn, self.ct = Bn, ctypes
+        self.x, self.lens, self.dy, self.layers = x, lens, dy, layers
+        T, B, _ = x.shape
+        n = layers[0][1].shape[-2]
+        dev = x.device
+        self.bufs = []
+        wmax = 0
+        cur = x
+        for (Wx, Wh, b) in layers:
+            D = Wx.shape[0]
+            desc = Bn.make_desc(T, B, cur.shape[2], n, Bn.LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else Bn.LSTM_F32)
+            rb, wb = Bn.query(desc, D == 2)
+            wmax = max(wmax, wb)
+            desc.reserve_bytes = rb
+            bf = dict(desc=desc, D=D, xin=cur, reserve=torch.empty(rb, dtype=torch.uint8, device=dev),
+                      y=torch.empty(T, B, D * n, dtype=x.dtype, device=dev), c=torch.empty(D, T, B, n, dtype=torch.float32, device=dev),
+                      dx=torch.empty_like(cur), dW_x=torch.empty_like(Wx, dtype=torch.float32),
+                      dW_h=torch.empty_like(Wh, dtype=torch.float32), db=torch.empty(D, 4 * n, dtype=torch.float32, device=dev))
+            self.bufs.append(bf)
+            cur = bf["y"]
+        self.ws = torch.empty(wmax, dtype=torch.uint8, device=dev)
+        for bf in self.bufs:
+            bf["desc"].workspace_bytes = wmax
+
+    def step(self):
+        lib, ct = self.Bn.lib, self.ct
+        s = torch.cuda.current_stream().cuda_stream
+        for (Wx, Wh, b), bf in zip(self.layers, self.bufs):
+            fn = lib.blstm_fwd if bf["D"] == 2 else lib.lstm_fwd
+            rc = fn(ct.byref(bf["desc"]), bf["xin"].data_ptr(), Wx.data_ptr(), Wh.data_ptr(), b.data_ptr(), None, None,
+                    self.lens.data_ptr(), bf["y"].data_ptr(), bf["c"].data_ptr(), None, None, bf["reserve"].data_ptr(),
+                    self.ws.data_ptr(), s)
+            assert rc == 0, self.Bn.strerror(rc)
+        d = self.dy
+        for k in range(len(self.layers) - 1, -1, -1):
+            Wx, Wh, b = self.layers[k]
+            bf = self.bufs[k]
+            fn = lib.blstm_bwd if bf["D"] == 2 else lib.lstm_bwd
+            rc = fn(ct.byref(bf["desc"]), bf["xin"].data_ptr(), Wx.data_ptr(), Wh.data_ptr(), None, None, self.lens.data_ptr(),
+                    bf["y"].data_ptr(), bf["c"].data_ptr(), bf["reserve"].data_ptr(), d.data_ptr(), None, None, bf["dx"].data_ptr(),
+                    bf["dW_x"].data_ptr(), bf["dW_h"].data_ptr(), bf["db"].data_ptr(), None, None, self.ws.data_ptr(), s)
+            assert rc == 0, self.Bn.strerror(rc)
+            d = bf["dx"]
+
+
+def bench_mixed(args, Bn, synth):
+    """--config 7: the translation encoder of the speed comparison, one bidirectional layer below five unidirectional ones."""
+    inp = synth.make(7)
+    cfg = inp["cfg"]
+    frames = synth.real_frames(inp)
+    flops = synth.flops_fwd_bwd(inp)
+    x, lens, dy, layers = build_stack(inp, Bn)
+    st = MixedStack(Bn, x, lens, dy, layers)
+    for _ in range(args.warmup):
+        st.step()
+    torch.cuda.synchronize()
+    Bn.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    Bn.profile_enable(False)
+    prof = Bn.profile_read()
+    T, B, n, nl = inp["T"], cfg["B"], cfg["n"], cfg["layers"]
+    # recurrent loops: algorithmic HBM bytes of one time step of ONE direction (as for the bidirectional stacks);
+    # the stack runs (nl + 1) directions' worth of time steps per pass
+    fwd_dir_bytes = 2 * B * 4 * n * 4 + B * n * 4 + B * n * 2
+    bwd_dir_bytes = B * 4 * n * 4 + 2 * B * n * 4 + B * n * 2 + B * 4 * n * 2
+    dir_steps = args.steps * (nl + 1) * T
+    def loop(phase, by, name):
+        ms, launches = prof[phase]
+        gbs = by * dir_steps / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        return {"bound": "hbm", "kernel": name, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                "traffic": None, "launches": int(launches), "avg_launch_ms": ms / max(launches, 1),
+                "us_per_layer_time_step": ms * 1e3 / (args.steps * nl * T), "algorithmic_bytes_per_direction_time_step": by}
+    out = {
+        "metric": "encoder fwd+bwd frames/sec (n=%d), 1 bidirectional + %d unidirectional layers" % (n, nl - 1),
+        "value": frames * args.steps / dt, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"],
+        "data": "synthetic",
+        "config": {"workload": "config 7: 1 BLSTM layer + %d LSTM layers, n_in=%d, n=%d, B=%d, seq_lens~U{%d..%d} (T=%d, %d real frames), "
+                               "bf16 storage / f32 state, forward + backward" % (nl - 1, cfg["n_in"], n, B, cfg["len_lo"], cfg["len_hi"], T, frames)},
+        "useful_tflops": flops * args.steps / dt / 1e12,
+        "roofline": loop("loop_bwd", bwd_dir_bytes, "backward recurrent loops"),
+        "roofline_forward_loop": loop("loop_fwd", fwd_dir_bytes, "forward recurrent loops"),
+        "phases_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+    }
+    print(json.dumps(out))
+
+
 def cpu_baseline(inp):
     """The CPU oracle, as it stands (float64 numpy), on a bounded sample: layer 2 of the stack
     (n_in = 2n) over the first `cap` frames of every sequence, forward + backward; the per-layer
@@ -309,7 +405,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell; 6 = config 4 with max-pooling in time between layers)")
+    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell; 6 = config 4 with max-pooling in time between layers; 7 = one bidirectional layer below five unidirectional ones)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--per-step", action="store_true", help="force one launch per time step")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -332,6 +428,9 @@ def main():
         return
     if args.config == 6:
         bench_pooled(args, Bn, synth)
+        return
+    if args.config == 7:
+        bench_mixed(args, Bn, synth)
         return
     inp = synth.make(args.config)
     cfg = inp["cfg"]

@@ -17,13 +17,16 @@ import torch
 
 SEED_BASE = 18050522500
 
-# kind: "lstm" (one direction) or "blstm".  len range is inclusive.  dtype "f32" or "bf16".
+# kind: "lstm" (one direction), "blstm", or "mixed" (first layer bidirectional, the others forward in time).
+# len range is inclusive.  dtype "f32" or "bf16".
 CONFIGS = {
     1: dict(kind="lstm", dtype="f32", n_in=32, n=64, B=4, layers=1, len_lo=20, len_hi=20, w=0.1),
     2: dict(kind="blstm", dtype="f32", n_in=620, n=1000, B=64, layers=1, len_lo=10, len_hi=50, w=0.08),
     3: dict(kind="blstm", dtype="bf16", n_in=620, n=1000, B=64, layers=6, len_lo=20, len_hi=80, w=0.08),
     4: dict(kind="blstm", dtype="bf16", n_in=40, n=1024, B=32, layers=6, len_lo=200, len_hi=1500, w=0.08),
     5: dict(kind="lstm", dtype="bf16", n_in=2620, n=1000, B=768, layers=1, len_lo=1, len_hi=1, w=0.08, steps=100),
+    # the translation encoder of the speed comparison: one bidirectional layer below `layers - 1` unidirectional ones
+    7: dict(kind="mixed", dtype="bf16", n_in=620, n=1000, B=64, layers=6, len_lo=20, len_hi=80, w=0.08),
 }
 
 
@@ -39,7 +42,8 @@ def make(k, **override):
 
     Returns a dict of numpy arrays (float32 values, already rounded to bf16 where the config
     stores bf16): seq_lens int32 [B]; x [T,B,n_in]; layers = list of {W_x [D,n_in_k,4n],
-    W_h [D,n,4n], b [D,4n]} with D = 2 for "blstm" and D = 1 for "lstm"; h0, c0 [D,B,n]
+    W_h [D,n,4n], b [D,4n]} with D = 2 for "blstm" and D = 1 for "lstm" ("mixed": 2 for the first layer, 1 above,
+    and the second layer sees 2n inputs); h0, c0 [D,B,n]
     (zeros, as every configuration prescribes); dy [T,B,D*n] for the top layer's output.
     """
     cfg = dict(CONFIGS[k])
@@ -47,15 +51,17 @@ def make(k, **override):
     g = torch.Generator(device="cpu")
     g.manual_seed(SEED_BASE + k)
     B, n, n_in, dt = cfg["B"], cfg["n"], cfg["n_in"], cfg["dtype"]
-    D = 2 if cfg["kind"] == "blstm" else 1
+    mixed = cfg["kind"] == "mixed"
+    D = 2 if cfg["kind"] == "blstm" else 1             # directions of the top layer (and of every layer unless mixed)
     lens = torch.randint(cfg["len_lo"], cfg["len_hi"] + 1, (B,), generator=g, dtype=torch.int64)
     T = int(lens.max())
     x = round_to(torch.randn(T, B, n_in, generator=g), dt)
     layers = []
     for l in range(cfg["layers"]):
-        ni = n_in if l == 0 else D * n
+        Dl = 2 if (mixed and l == 0) else D
+        ni = n_in if l == 0 else (2 * n if (mixed and l == 1) else D * n)
         Wx, Wh, bb = [], [], []
-        for d in range(D):
+        for d in range(Dl):
             Wx.append(round_to((torch.rand(ni, 4 * n, generator=g) * 2 - 1) * cfg["w"], dt))
             Wh.append(round_to((torch.rand(n, 4 * n, generator=g) * 2 - 1) * cfg["w"], dt))
             bb.append(torch.zeros(4 * n))
@@ -77,7 +83,7 @@ def flops_fwd_bwd(inp):
     cfg = inp["cfg"]
     n, D = cfg["n"], inp["D"]
     tot = 0
-    for l in range(cfg["layers"]):
-        ni = cfg["n_in"] if l == 0 else D * n
-        tot += D * 24 * n * (ni + n)
+    for l, L in enumerate(inp["layers"]):
+        Dl, ni = L["W_x"].shape[0], L["W_x"].shape[1]
+        tot += Dl * 24 * n * (ni + n)
     return tot * real_frames(inp)

@@ -370,7 +370,7 @@ def _stack_gpu(inp, dt):
     ws = None
     for L in inp["layers"]:
         Wx, Wh, b = dev(L["W_x"], dt), dev(L["W_h"], dt), dev(L["b"])
-        f = Bn.forward(cur, Wx, Wh, b, None, None, lens, bidirectional=True, workspace=ws, want_state=False)
+        f = Bn.forward(cur, Wx, Wh, b, None, None, lens, bidirectional=L["W_x"].shape[0] == 2, workspace=ws, want_state=False)
         ws = f["workspace"]
         saved.append((cur, Wx, Wh, f))
         cur = f["y"]
@@ -394,6 +394,27 @@ def test_bf16_stack_reduced(k, over):
     layers = [{kk: v.astype(np.float64) for kk, v in L.items()} for L in inp["layers"]]
     acts, yo = O.blstm_stack_fwd(inp["x"].astype(np.float64), layers, inp["seq_lens"])
     dxo, go = O.blstm_stack_bwd(acts, layers, inp["seq_lens"], inp["dy"].astype(np.float64))
+    tol = TOL["bf16"]
+    check("y", y, yo, tol)
+    check("dx", dx, dxo, tol)
+    for l, (g, r) in enumerate(zip(grads, go)):
+        check("dW_x%d" % l, g["dW_x"], r[0], tol)
+        check("dW_h%d" % l, g["dW_h"], r[1], tol)
+        check("db%d" % l, g["db"], r[2], tol)
+
+
+@pytest.mark.parametrize("over", [dict(layers=4, len_lo=5, len_hi=24), dict(layers=3, len_lo=3, len_hi=40, B=32, n=1024),
+                                  dict(layers=3, len_lo=0, len_hi=21, B=19, n=200, n_in=70)])
+def test_mixed_encoder_stack_reduced(over):
+    """One bidirectional layer below unidirectional ones (the translation encoder of the speed comparison), reduced in
+    depth and length so that the oracle finishes in seconds: y of the top layer, dx of the bottom layer and every
+    weight gradient against the oracle's mixed stack."""
+    inp = synth.make(7, **over)
+    print("  config 7 reduced: T=%d B=%d n=%d layers=%d" % (inp["T"], inp["cfg"]["B"], inp["cfg"]["n"], len(inp["layers"])), flush=True)
+    y, dx, grads = _stack_gpu(inp, "bf16")
+    layers = [{kk: v.astype(np.float64) for kk, v in L.items()} for L in inp["layers"]]
+    acts, yo = O.encoder_stack_fwd(inp["x"].astype(np.float64), layers, inp["seq_lens"])
+    dxo, go = O.encoder_stack_bwd(acts, layers, inp["seq_lens"], inp["dy"].astype(np.float64))
     tol = TOL["bf16"]
     check("y", y, yo, tol)
     check("dx", dx, dxo, tol)
