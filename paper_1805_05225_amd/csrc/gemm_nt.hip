@@ -8,7 +8,7 @@
 // once by `launch_transpose` below - a bandwidth-bound pass that costs a few percent of the product
 // it feeds - instead of being transposed on the fly inside the MFMA loop.
 //
-// Two kernels share the tile raster and the epilogue: gemm_dl8_* (K a multiple of 64: operands loaded straight into
+// Two kernels share the tile raster and the epilogue: gemm_dl8_* (K a multiple of 8: operands loaded straight into
 // LDS, eight wavefronts; described where it is defined) and gemm_nt_kernel (any K a multiple of 8), which follows.
 //
 // gemm_nt_kernel: 256x256 output tile per work-group of 4 wavefronts (2x2), each wavefront a 128x128
@@ -176,7 +176,7 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][TN], char* lds, cons
       if (col >= g.N) continue;
       const float4 val = *(const float4*)&ep[rowl * kEpStride + lane * 4];
       const float e[4] = {val.x, val.y, val.z, val.w};
-      const long off = (long)(g.c_rows ? g.c_rows[row] : row) * g.ldc + col;
+      const long off = (long)((g.c_rows && !to_parts) ? g.c_rows[row] : row) * g.ldc + col;     // parts keep the packed rows
       const bool whole = vec_ok && col + 3 < g.N;
       if constexpr (sizeof(TC) == 4) {
         float* Cf = (float*)C + off;
@@ -377,7 +377,11 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int ktiles = K / kKB;                      // K is a multiple of 64 here
+  // K is a multiple of 8 (whole 16-byte chunks).  The last k-tile of a segment may hold fewer than 8 chunks: the lanes
+  // that would fetch a chunk past K point outside the buffer descriptor for that tile and their slots arrive as zeros.
+  const int ktiles = (K + kKB - 1) / kKB;
+  const int tail_chunks = (K - (ktiles - 1) * kKB) >> 3;       // 1 .. 8 chunks in the last k-tile
+  const bool ragged = tail_chunks < 8;
   const int nstage = ktiles * g.nseg;
   const int it0 = (int)((long)nstage * ks / ksplit);
   const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
@@ -391,6 +395,7 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
   // burst instead of all sharers asking for the same lines in the same order.
   const int rotA = tc.pos % kSupN, rotB = (tc.pos / kSupN) >> 1;
   unsigned voa[NLD], vob[NLD], lda_off[NLD], ldb_off[NLD];
+  bool a_past[NLD], b_past[NLD];                                // this lane's chunk lies past K in a ragged last k-tile
   {
     const long a_rows_mem = g.a_rows ? g.a_phys_rows : M;
 #pragma unroll
@@ -406,6 +411,7 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
       const long oa = (ra * g.lda) * 2 + chunk * 16, ob = (rb * g.ldb) * 2 + chunkb * 16;
       voa[i] = (ra >= a_rows_mem || oa > 0x7ffffff0L) ? 0x7ffffff0u : (unsigned)oa;
       vob[i] = (rb >= g.N || ob > 0x7ffffff0L) ? 0x7ffffff0u : (unsigned)ob;
+      a_past[i] = chunk >= tail_chunks; b_past[i] = chunkb >= tail_chunks;
     }
   }
   const long a_bytes = (long)(g.a_rows ? g.a_phys_rows : M) * g.lda * 2, b_bytes = (long)g.N * g.ldb * 2;
@@ -419,12 +425,13 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
     const u32x4 rb = make_rsrc(g.B + (g.sBz * z + g.sBseg * seg) * 2, (unsigned)b_rec);
     const unsigned dst = lds_base + buf * kDlStage + wave * 1024;
     const unsigned koff = kt * (kKB * 2);
+    const bool cut = ragged && kt == ktiles - 1;
 #pragma unroll
     for (int q = 0; q < 2 * NLD; ++q) {
       if (q < first || q >= last) continue;
       const int i = q >> 1;
-      if (q & 1) load_to_lds_b128(rb, dst + ldb_off[i], vob[i], koff);
-      else load_to_lds_b128(ra, dst + lda_off[i], voa[i], koff);
+      if (q & 1) load_to_lds_b128(rb, dst + ldb_off[i], (cut && b_past[i]) ? 0x7ffffff0u : vob[i], koff);
+      else load_to_lds_b128(ra, dst + lda_off[i], (cut && a_past[i]) ? 0x7ffffff0u : voa[i], koff);
     }
   };
   constexpr int NQ = 2 * NLD;                               // wavefront-loads per stage and wavefront
@@ -685,6 +692,39 @@ __global__ void sum_parts_kernel(const float* parts, float* C, int M, int N, lon
   C[z * sCz + off] = v;
 }
 
+// The same for a bfloat16 C without z: C[rows[m]][n] = sum over the K ranges of parts[range][m][n], m below *m_dev
+// when given (the rows above it were never computed); four columns per lane.
+__global__ void sum_parts_bf16_kernel(const float* parts, uint16_t* C, int M, int N, long ldc, long sPart, int ksplit, const int* c_rows,
+                                      const int* m_dev) {
+  const int nq = (N + 3) / 4;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int m = (int)(idx / nq), n = (int)(idx % nq) * 4;
+  if (m >= (m_dev ? min(M, *m_dev) : M)) return;
+  const long src = (long)m * ldc + n, dst = (long)(c_rows ? c_rows[m] : m) * ldc + n;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  const bool whole = n + 3 < N && ldc % 4 == 0;
+  for (int ks = 0; ks < ksplit; ++ks) {
+    const float* p = parts + ks * sPart + src;
+    if (whole) {
+      typedef __attribute__((ext_vector_type(4))) float f32x4_;
+      const f32x4_ q = __builtin_nontemporal_load((const f32x4_*)p);
+      v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
+    } else {
+      for (int k = 0; k < 4; ++k)
+        if (n + k < N) v[k] += p[k];
+    }
+  }
+  if (whole && (((uintptr_t)C & 7u) == 0)) {
+    uint2 o;
+    o.x = f2bf_bits(v[0]) | ((unsigned)f2bf_bits(v[1]) << 16);
+    o.y = f2bf_bits(v[2]) | ((unsigned)f2bf_bits(v[3]) << 16);
+    *(uint2*)(C + dst) = o;
+  } else {
+    for (int k = 0; k < 4; ++k)
+      if (n + k < N) C[dst + k] = f2bf_bits(v[k]);
+  }
+}
+
 // dst[c][r] = keep(r) ? src[r][c] : 0 for r < R, c < C ; dst rows are padded with zeros up to ldd.
 // keep(r): rows of src are frames (t = r / Bt, b = r % Bt), kept iff lens == NULL or t < lens[b].
 // With `cidx` (compact index of every frame, -1 for padded frames) the kept frames are packed instead:
@@ -906,14 +946,19 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   a.sAz = g.sAz; a.sBz = g.sBz; a.sCz = g.sCz; a.sbiasz = g.sbiasz; a.nz = g.nz;
   a.nseg = g.nseg; a.sAseg = g.sAseg; a.sBseg = g.sBseg; a.accumulate = g.accumulate;
   a.a_rows = g.a_rows; a.c_rows = g.c_rows; a.m_dev = g.m_dev; a.k_dev = g.k_dev; a.a_phys_rows = g.a_phys_rows;
-  a.ksplit = (g.ksplit > 1 && !g.out_bf16 && g.nseg == 1) ? g.ksplit : 1;
-  a.parts = a.ksplit > 1 && !g.c_rows ? g.parts : nullptr; a.sPart = (long)g.M * g.ldc;
+  // bfloat16 output over K ranges: float parts (packed rows) from the float kernel, then one pass that adds them,
+  // rounds once and scatters the rows; needs the direct-to-LDS kernel (segments and ranges share its stage counter)
+  const bool dl = !g.k_dev || g.K % kKB == 0;
+  const bool parts_bf16 = g.out_bf16 && g.ksplit > 1 && g.parts && dl && g.nz == 1 && !g.accumulate && !g.bias;
+  a.ksplit = (g.ksplit > 1 && ((!g.out_bf16 && g.nseg == 1) || parts_bf16)) ? g.ksplit : 1;
+  a.parts = a.ksplit > 1 && (!g.c_rows || parts_bf16) ? g.parts : nullptr; a.sPart = (long)g.M * g.ldc;
   // the blocked raster pays when every XCD gets several blocks; with few tiles it would leave XCDs idle
   const int sups = cdiv(cdiv(g.M, kT), kSupM) * cdiv(cdiv(g.N, kT), kSupN);
   a.blocked = sups >= 32 ? 1 : 0;
   const int tiles = a.blocked ? cdiv(sups, 8) * 8 * kSupM * kSupN : cdiv(g.M, kT) * cdiv(g.N, kT);
-  // K a multiple of 64 (device-resident K values are multiples of 64 by contract): operands go straight into LDS
-  if (g.K % kKB == 0) {
+  // operands go straight into LDS; K any multiple of 8 (a device-resident K is a multiple of 64 by contract, and so
+  // must then be the host's bound on it)
+  if (dl) {
     static bool dl_attr_set = false;
     if (!dl_attr_set) {
       hipError_t e = hipFuncSetAttribute((const void*)gemm_dl8_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
@@ -921,9 +966,17 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
       if (e != hipSuccess) return e;
       dl_attr_set = true;
     }
-    const dim3 grid(tiles, g.out_bf16 ? g.nz : g.nz * a.ksplit);
-    if (g.out_bf16) hipLaunchKernelGGL(gemm_dl8_bf16_kernel, grid, dim3(512), kDlLds, s, a);
+    const dim3 grid(tiles, g.nz * a.ksplit);
+    if (g.out_bf16 && !parts_bf16) hipLaunchKernelGGL(gemm_dl8_bf16_kernel, grid, dim3(512), kDlLds, s, a);
     else hipLaunchKernelGGL(gemm_dl8_f32_kernel, grid, dim3(512), kDlLds, s, a);
+    if (parts_bf16) {
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      const long total = (long)a.M * ((a.N + 3) / 4);
+      hipLaunchKernelGGL(sum_parts_bf16_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, a.parts, (uint16_t*)a.C, a.M, a.N, a.ldc, a.sPart,
+                         a.ksplit, a.c_rows, a.m_dev);
+      return hipGetLastError();
+    }
     return sum_parts(a, s);
   }
   const size_t shmem = 4 * kOpBytes;

@@ -27,7 +27,7 @@ struct Plan {
   // workspace
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
       ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, ws_Wcat, ws_Acat, ws_parts, workspace_bytes;
-  int ks_dwx, ks_dwh;                       // K ranges of the weight-gradient products (few output tiles: the whole device works on them)
+  int ks_dwx, ks_dwh, ks_dx;                // K ranges of the weight-gradient products and of dX (few output tiles: the whole device works on them)
   bool single_step; int Kc, ksplit;         // T == 1 inference in bfloat16: the step is one product over [x | h], K cut in ksplit ranges
   bool fast_gemm; int n_in_pad; long TBp;   // bf16 products through the k-contiguous kernel (operands transposed once)
   size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems, Wf_bytes;
@@ -116,12 +116,18 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   const auto ksplit_for = [&](long M, long N) {
     const long tiles = (long)cdiv(M, 256) * cdiv(N, 256) * p->D;
     const long want = 256 / (tiles > 0 ? tiles : 1);
-    const long most = p->TBp / 4096 > 0 ? p->TBp / 4096 : 1;        // every range keeps a long k loop
+    const long most = p->TBp / 1024 > 0 ? p->TBp / 1024 : 1;        // every range keeps at least 16 stages of 64 frames
     return (int)std::max(1L, std::min(std::min(want, most), 8L));
   };
+  // dX on a short batch has few output tiles too (rows = frames): K = 4n per direction cut into ranges of >= 16 stages
+  {
+    const long tiles = (long)cdiv(TB, 256) * cdiv(d->n_in, 256), stages = (long)p->D * cdiv(4L * d->n, 64);
+    p->ks_dx = fg && !infer && p->bf16 && tiles > 0 ? (int)std::max(1L, std::min(std::min(256 / tiles, stages / 16), 8L)) : 1;
+  }
   p->ks_dwx = fg && !infer ? ksplit_for(d->n_in, 4L * d->n) : 1;
   p->ks_dwh = fg && !infer ? ksplit_for(d->n, 4L * d->n) : 1;
-  p->ws_parts = take(std::max(p->ks_dwx > 1 ? D * p->ks_dwx * d->n_in * 4 * n * 4 : 0, p->ks_dwh > 1 ? D * p->ks_dwh * n * 4 * n * 4 : 0));
+  p->ws_parts = take(std::max({p->ks_dwx > 1 ? D * p->ks_dwx * d->n_in * 4 * n * 4 : 0, p->ks_dwh > 1 ? D * p->ks_dwh * n * 4 * n * 4 : 0,
+                               p->ks_dx > 1 ? (size_t)p->ks_dx * TB * d->n_in * 4 : 0}));
   p->workspace_bytes = o + kAlign;
   return LSTM_OK;
 }
@@ -509,6 +515,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       HIPCHK(launch_fill_zero(dx, (size_t)TB * n_in * p.esz, s));
       g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = TB; g.m_dev = count;
     }
+    if (p.ks_dx > 1 && gemm_nt_ok(g)) { g.ksplit = p.ks_dx; g.parts = (float*)(ws + p.ws_parts); }
     HIPCHK(launch_gemm(g, s));
   }
   // Weight gradients straight from the frame-major tensors (a row per frame in X, Hprev and DZ: both operands of

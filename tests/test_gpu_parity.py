@@ -78,7 +78,8 @@ def compare(f, g, fo, go, tol):
 # ---- the hoisted GEMM by itself -----------------------------------------------------------------------
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("M,N,K", [(130, 140, 70), (257, 129, 620), (5, 7, 3), (256, 256, 256), (300, 520, 136), (1000, 260, 2048),
-                                   (300, 520, 160), (513, 300, 4096), (40, 1030, 32), (264, 520, 200), (40, 4096, 333), (1024, 256, 64)])
+                                   (300, 520, 160), (513, 300, 4096), (40, 1030, 32), (264, 520, 200), (40, 4096, 333), (1024, 256, 64),
+                                   (300, 520, 1000), (520, 300, 4000), (260, 260, 8), (260, 260, 72)])
 def test_gemm_layouts(dt, M, N, K):
     rng = np.random.default_rng(M * 1000 + N + K)
     td = tdtype(dt)
