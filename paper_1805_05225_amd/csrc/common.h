@@ -215,6 +215,19 @@ hipError_t launch_pack_state(const float* h, uint4* frag0, uint4* frag1, int B, 
                              bool bf16, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);                 // p 4-byte aligned, bytes % 2 == 0
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);   // bytes % 4 == 0
+// Up to kMax regions cleared by one launch (the set-up of a layer clears half a dozen small buffers; one launch each
+// costs more in launch gaps than in work).  Every region 4-byte aligned, bytes % 4 == 0.
+struct ZeroRegions {
+  static constexpr int kMax = 8;
+  void* ptr[kMax];
+  size_t words[kMax];
+  int first_block[kMax + 1];
+  int count;
+  bool overflow;
+  ZeroRegions() : ptr{}, words{}, first_block{}, count(0), overflow(false) {}
+  void add(void* p, size_t bytes);
+};
+hipError_t launch_fill_zero_many(const ZeroRegions& r, hipStream_t s);
 // db[c] (+)= sum_rows DZ[row][c]; part = float scratch [nsplit][ncols] per direction
 // db[dir][c] (+)= sum over the first nslices slices of part[dir][kColsumSlices][ncols]
 constexpr int kColsumSlices = 64;

@@ -356,7 +356,7 @@ __device__ __forceinline__ u32x4 make_rsrc(const void* base, unsigned bytes) {
   return r;
 }
 
-template <typename TC, int TN>
+template <typename TC, int TN, bool RAGGED>
 __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int WN = 8 / TN, NW = 2 * WN, NLD = 32 / NW;       // loads per wavefront, operand and stage
@@ -381,7 +381,7 @@ __device__ __forceinline__ void gemm_dl_body(const NtArgs& g) {
   // that would fetch a chunk past K point outside the buffer descriptor for that tile and their slots arrive as zeros.
   const int ktiles = (K + kKB - 1) / kKB;
   const int tail_chunks = (K - (ktiles - 1) * kKB) >> 3;       // 1 .. 8 chunks in the last k-tile
-  const bool ragged = tail_chunks < 8;
+  const bool ragged = RAGGED && tail_chunks < 8;              // RAGGED = false: the launcher saw K % 64 == 0
   const int nstage = ktiles * g.nseg;
   const int it0 = (int)((long)nstage * ks / ksplit);
   const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
@@ -674,8 +674,8 @@ __device__ __forceinline__ void gemm_tn_body(const NtArgs& g) {
 __global__ __launch_bounds__(512, 1) void gemm_tn8_f32_kernel(NtArgs g) { gemm_tn_body<float>(g); }
 
 // (kernels with literal launch bounds: a bound that depends on a template parameter loses the host-side stub)
-__global__ __launch_bounds__(512, 1) void gemm_dl8_f32_kernel(NtArgs g) { gemm_dl_body<float, 2>(g); }
-__global__ __launch_bounds__(512, 1) void gemm_dl8_bf16_kernel(NtArgs g) { gemm_dl_body<uint16_t, 2>(g); }
+template <bool RAGGED> __global__ __launch_bounds__(512, 1) void gemm_dl8_f32_kernel(NtArgs g) { gemm_dl_body<float, 2, RAGGED>(g); }
+template <bool RAGGED> __global__ __launch_bounds__(512, 1) void gemm_dl8_bf16_kernel(NtArgs g) { gemm_dl_body<uint16_t, 2, RAGGED>(g); }
 
 // C[z][m][n] (+)= sum over the K ranges of parts[z][range][m][n]  (parts in the layout of C, one after the other)
 __global__ void sum_parts_kernel(const float* parts, float* C, int M, int N, long ldc, long sCz, long sPart, int ksplit, int accumulate,
@@ -961,14 +961,19 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   if (dl) {
     static bool dl_attr_set = false;
     if (!dl_attr_set) {
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_dl8_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
-      if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_dl8_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
-      if (e != hipSuccess) return e;
+      for (const void* k : {(const void*)gemm_dl8_f32_kernel<false>, (const void*)gemm_dl8_f32_kernel<true>,
+                            (const void*)gemm_dl8_bf16_kernel<false>, (const void*)gemm_dl8_bf16_kernel<true>}) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
+        if (e != hipSuccess) return e;
+      }
       dl_attr_set = true;
     }
     const dim3 grid(tiles, g.nz * a.ksplit);
-    if (g.out_bf16 && !parts_bf16) hipLaunchKernelGGL(gemm_dl8_bf16_kernel, grid, dim3(512), kDlLds, s, a);
-    else hipLaunchKernelGGL(gemm_dl8_f32_kernel, grid, dim3(512), kDlLds, s, a);
+    const bool ragged = g.K % kKB != 0, bf = g.out_bf16 && !parts_bf16;
+    if (bf && ragged) hipLaunchKernelGGL(gemm_dl8_bf16_kernel<true>, grid, dim3(512), kDlLds, s, a);
+    else if (bf) hipLaunchKernelGGL(gemm_dl8_bf16_kernel<false>, grid, dim3(512), kDlLds, s, a);
+    else if (ragged) hipLaunchKernelGGL(gemm_dl8_f32_kernel<true>, grid, dim3(512), kDlLds, s, a);
+    else hipLaunchKernelGGL(gemm_dl8_f32_kernel<false>, grid, dim3(512), kDlLds, s, a);
     if (parts_bf16) {
       const hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;

@@ -231,9 +231,13 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   }
   {
     Phase ph(LSTM_PHASE_PREP, 5, s);
-    HIPCHK(launch_fill_zero(ws + p.ws_sync, p.sync_bytes, s));
-    if (h0) HIPCHK(launch_copy(hstate, h0, state_bytes, s)); else HIPCHK(launch_fill_zero(hstate, state_bytes, s));
-    if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else HIPCHK(launch_fill_zero(cstate, state_bytes, s));
+    ZeroRegions z;
+    z.add(ws + p.ws_sync, p.sync_bytes);
+    if (h0) HIPCHK(launch_copy(hstate, h0, state_bytes, s)); else z.add(hstate, state_bytes);
+    if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else z.add(cstate, state_bytes);
+    if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd)
+      z.add(ws + p.ws_Wf + p.Wf_bytes, 1024);              // the chunk of zeros behind the packed W_h (single-launch path)
+    HIPCHK(launch_fill_zero_many(z, s));
   }
   // single-launch path: bf16 storage, at least two steps, register budget of the kernel
   bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd;
@@ -241,7 +245,6 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     Phase ph(LSTM_PHASE_PREP, 2, s);
     if (ll) {
       HIPCHK(launch_pack_wh_fwd_ll(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_ll_f, p.D, s));
-      HIPCHK(launch_fill_zero(ws + p.ws_Wf + p.Wf_bytes, 1024, s));
       HIPCHK(launch_pack_state_ll(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_ll_f, p.nrt,
                                   p.D, s));
     } else {
@@ -377,7 +380,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   float* Dh = (float*)(ws + p.ws_Dh);
   float* Dc = (float*)(ws + p.ws_Dc);
   const size_t state_bytes = D * B * n * 4;
-  if (B > 0) HIPCHK(launch_fill_zero(ws + p.ws_sync, p.sync_bytes, s));
+  if (B > 0 && T == 0) HIPCHK(launch_fill_zero(ws + p.ws_sync, p.sync_bytes, s));
   if (B == 0 || T == 0) {          // no frames: parameter gradients are zero, state gradients pass through
     if (!acc) {
       HIPCHK(launch_fill_zero(dW_x, D * n_in * 4 * n * 4, s));
@@ -392,10 +395,14 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   }
   {
     Phase ph(LSTM_PHASE_PREP, 5, s);
-    if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dh, state_bytes, s));
-    if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else HIPCHK(launch_fill_zero(Dc, state_bytes, s));
-    HIPCHK(launch_fill_zero(ws + p.ws_dzfrag0, p.dzfrag_bytes, s));
-    HIPCHK(launch_fill_zero(ws + p.ws_dzfrag1, p.dzfrag_bytes, s));
+    ZeroRegions z;
+    z.add(ws + p.ws_sync, p.sync_bytes);
+    if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else z.add(Dh, state_bytes);
+    if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else z.add(Dc, state_bytes);
+    z.add(ws + p.ws_dzfrag0, p.dzfrag_bytes);
+    z.add(ws + p.ws_dzfrag1, p.dzfrag_bytes);
+    if (2 * p.nrt <= kColsumSlices) z.add(ws + p.ws_colsum, D * kColsumSlices * 4 * n * 4);   // bias-gradient slices of row groups the grid lacks
+    HIPCHK(launch_fill_zero_many(z, s));
   }
   // single-launch path: bf16 storage, at least two steps, and one of the kernel forms fits the device
   PBwdArgs pa = {};
@@ -436,7 +443,6 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       bd.dbpart = db_in_loop ? (float*)(ws + p.ws_colsum) + d * kColsumSlices * 4 * n : nullptr;
       bd.rev = bidir ? d == 1 : desc->direction == -1;
     }
-    if (db_in_loop) HIPCHK(launch_fill_zero(ws + p.ws_colsum, D * kColsumSlices * 4 * n * 4, s));   // row groups the grid lacks
     hipError_t e;
     {
       Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);

@@ -212,6 +212,18 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t nwords, int tail16) {
   if (i == 0 && tail16) ((uint16_t*)(p + nwords))[0] = 0;
   for (; i < nwords; i += stride) p[i] = 0u;
 }
+// several fills in one launch: block b works on the region whose block range holds b
+__global__ void fill_zero_many_kernel(ZeroRegions r) {
+  int k = 0;
+#pragma unroll
+  for (int j = 1; j < ZeroRegions::kMax; ++j)
+    if (j < r.count && (int)blockIdx.x >= r.first_block[j]) k = j;
+  uint32_t* p = (uint32_t*)r.ptr[k];
+  const size_t nwords = r.words[k];
+  const size_t nb = (size_t)(r.first_block[k + 1] - r.first_block[k]);
+  size_t i = (size_t)(blockIdx.x - r.first_block[k]) * blockDim.x + threadIdx.x;
+  for (; i < nwords; i += nb * blockDim.x) p[i] = 0u;
+}
 __global__ void copy_kernel(uint32_t* dst, const uint32_t* src, size_t nwords) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
   for (; i < nwords; i += stride) dst[i] = src[i];
@@ -281,6 +293,20 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   int blocks = (int)((nw + 255) / 256 > 4096 ? 4096 : (nw + 255) / 256);
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint32_t*)p, nw, (int)((bytes & 2) != 0));
+  return hipGetLastError();
+}
+void ZeroRegions::add(void* p, size_t bytes) {
+  if (bytes == 0 || count >= kMax) { overflow |= bytes != 0; return; }
+  const size_t nw = bytes / 4;
+  const size_t blocks = std::min<size_t>((nw + 1023) / 1024, 512);      // a few words per lane
+  ptr[count] = p; words[count] = nw;
+  first_block[count + 1] = first_block[count] + (int)std::max<size_t>(blocks, 1);
+  ++count;
+}
+hipError_t launch_fill_zero_many(const ZeroRegions& r, hipStream_t s) {
+  if (r.overflow) return hipErrorInvalidValue;
+  if (r.count == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_many_kernel, dim3(r.first_block[r.count]), dim3(256), 0, s, r);
   return hipGetLastError();
 }
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
