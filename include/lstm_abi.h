@@ -137,10 +137,10 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
               const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const float* bias,
               int accumulate, const int32_t* lens, int Bt, int T, void* stream);
 
-/* Max-pooling in time between encoder layers.  The paper's attention-based speech encoder (Sec. "Speech
- * recognition experiments", the attention model on Switchboard: "a 6 layer bidirectional encoder, which also
- * applies max-pooling in the time dimension", a reduction by a factor of 8 in total) pools the layer outputs
- * over time; window, stride and padding are not given.  This library's reading: non-overlapping windows of
+/* Max-pooling in time between encoder layers.  The paper's attention-based speech encoder (Sec. 8, the
+ * attention model on Switchboard: six bidirectional layers, a maximum taken over time between them, the
+ * input shortened by a factor of 8 in total) pools the layer outputs over time; window, stride and padding
+ * are not given.  This library's reading: non-overlapping windows of
  * `pool` frames (stride = window; pool = 2 after each of three layers gives the factor 8), taken inside every
  * sequence separately:
  *     T' = ceil(T / pool),  lens_out[b] = ceil(seq_lens[b] / pool),
