@@ -162,6 +162,49 @@ int lstm_time_pool_fwd(int dtype, int T, int B, int F, int pool, const void* y, 
 int lstm_time_pool_bwd(int dtype, int T, int B, int F, int pool, const void* dout, int64_t ldo, const uint8_t* arg,
                        const int32_t* seq_lens, void* dy, int64_t ldy, void* stream);
 
+/* One step of the attention decoder, from the cell output s to the attention context (Listing 1, sub-network of
+ * layer "output": "s_tr", "weight_feedback", "e_in", "e_tanh", "e", "a", "accum_a", "att"; "enc_ctx" is the
+ * loop-invariant projection of the encoder states and is computed by the caller once per sentence, e.g. with
+ * lstm_gemm, as Sec. 7 describes for work that does not depend on the loop).  With j a source position, r a row
+ * of the decoder batch and q(r) = r / beam its sentence (the `beam` hypotheses of a sentence are neighbours):
+ *     s_tr[r]   = s[r] W_s + b_s
+ *     e[r, j]   = v . tanh(enc_ctx[j, q(r)] + accum_in[r, j] * w_fb + b_fb + s_tr[r]) + b_e
+ *     a[r, :]   = softmax of e[r, :] over j < src_lens[q(r)];  a[r, j] = 0 for the other j
+ *     accum_out = accum_in + a   (0 at j >= src_lens[q(r)])
+ *     att[r]    = sum_j a[r, j] enc[j, q(r)]
+ * Values stored at positions j >= src_lens[q] in enc, enc_ctx or accum_in are never read; a sentence of length 0
+ * gives a = 0, att = 0.  The cell that produces s is lstm_fwd with T = 1 and LSTM_FLAG_INFERENCE.
+ *   desc: S source positions (1..1024), Q sentences, beam hypotheses per sentence (1..16), A attention width,
+ *         E encoder state width (even), n cell width, workspace_bytes as lstm_attention_query() returns.
+ *   enc      bfloat16 [S][Q][E]      enc_ctx  bfloat16 [S][Q][A]      src_lens int32 [Q] or NULL (all S)
+ *   s        bfloat16 [Q*beam][ld_s >= n]                W_s bfloat16 [A][n] (a row per output feature)
+ *   b_s, w_fb, b_fb, v   float [A]   b_e float (passed by value)
+ *   accum_in, accum_out, a   float [Q*beam][S] (a may be NULL; accum_out must not overlap accum_in)
+ *   att      bfloat16 [Q*beam][ld_att >= E], ld_att even, 4-byte aligned: may point into a wider row, e.g. the
+ *            concatenated input of lstm_readout or of the next step's cell.
+ * All pointers are device pointers owned by the caller; arithmetic is float.  The call only enqueues work.
+ * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM, LSTM_ERR_UNSUPPORTED (beam > 16, S > 1024, odd E), LSTM_ERR_ALIGN,
+ * LSTM_ERR_SIZE (workspace), LSTM_ERR_HIP. */
+typedef struct lstm_att_desc {
+  int32_t S, Q, beam, A, E, n;
+  uint64_t workspace_bytes;
+} lstm_att_desc;
+int lstm_attention_query(const lstm_att_desc* desc, uint64_t* workspace_bytes);
+int lstm_attention_step(const lstm_att_desc* desc, const void* enc, const void* enc_ctx, const int32_t* src_lens,
+                        const void* s, int64_t ld_s, const void* W_s, const float* b_s, const float* w_fb,
+                        const float* b_fb, const float* v, float b_e, const float* accum_in, float* accum_out,
+                        float* a, void* att, int64_t ld_att, void* workspace, void* stream);
+
+/* The decoder's readout (Listing 1, "readout": a linear layer with relu over the cell output, the previous target
+ * embedding and the attention context): out = max(0, x W_r + b_r) with x[B][ld_x >= K] the rows [s | trg | att]
+ * laid side by side by the caller (lstm_attention_step can write att straight into them).
+ *   x bfloat16, W_r bfloat16 [R][K] (a row per output feature), b_r float [R] or NULL, out bfloat16 [B][ld_out >= R];
+ *   workspace of lstm_readout_query(B, R, K) bytes.  Float accumulation, one rounding at the end.
+ * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM, LSTM_ERR_ALIGN, LSTM_ERR_SIZE, LSTM_ERR_HIP. */
+int lstm_readout_query(int B, int R, int K, uint64_t* workspace_bytes);
+int lstm_readout(int B, int R, int K, const void* x, int64_t ld_x, const void* W_r, const float* b_r, void* out,
+                 int64_t ld_out, void* workspace, uint64_t workspace_bytes, void* stream);
+
 /* Diagnostic for the single-launch (persistent) recurrent kernels, whose work-groups wait for each
  * other between time steps with BOUNDED waits.  If a wait ever expired, the kernel drained early, the
  * results of that call are invalid and a word in the workspace says so.  This call copies that word

@@ -14,8 +14,14 @@ LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm
 
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED = 1, 2, 4, 8
-EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_time_pool_fwd", "lstm_time_pool_bwd", "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
+EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_time_pool_fwd", "lstm_time_pool_bwd", "lstm_attention_query", "lstm_attention_step",
+           "lstm_readout_query", "lstm_readout", "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
            "lstm_strerror")
+
+
+class AttDesc(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int32), ("Q", ctypes.c_int32), ("beam", ctypes.c_int32), ("A", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("n", ctypes.c_int32), ("workspace_bytes", ctypes.c_uint64)]
 
 
 class LstmDesc(ctypes.Structure):
@@ -53,6 +59,15 @@ def _load():
     lib.lstm_time_pool_fwd.argtypes = [ip] * 5 + [vp, i64, vp, vp, i64, vp, vp, vp]
     lib.lstm_time_pool_bwd.restype = ip
     lib.lstm_time_pool_bwd.argtypes = [ip] * 5 + [vp, i64, vp, vp, vp, i64, vp]
+    fp, u64p = ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint64)
+    lib.lstm_attention_query.restype = ip
+    lib.lstm_attention_query.argtypes = [ctypes.POINTER(AttDesc), u64p]
+    lib.lstm_attention_step.restype = ip
+    lib.lstm_attention_step.argtypes = [ctypes.POINTER(AttDesc), vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i64, vp, vp]
+    lib.lstm_readout_query.restype = ip
+    lib.lstm_readout_query.argtypes = [ip, ip, ip, u64p]
+    lib.lstm_readout.restype = ip
+    lib.lstm_readout.argtypes = [ip, ip, ip, vp, i64, vp, vp, vp, i64, vp, ctypes.c_uint64, vp]
     lib.lstm_sync_status.restype = ip
     lib.lstm_sync_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
     lib.lstm_profile_enable.restype = ip
@@ -190,6 +205,52 @@ def time_pool_bwd(dout, arg, seq_lens, pool, T):
     dy = torch.empty(T, B, F, dtype=dout.dtype, device=dout.device)
     _check(lib.lstm_time_pool_bwd(_dtype_of(dout), T, B, F, pool, _ptr(dout), F, _ptr(arg), _ptr(seq_lens), _ptr(dy), F, _stream()))
     return dy
+
+
+def attention_query(S, Q, beam, A, E, n):
+    d = AttDesc(S, Q, beam, A, E, n, 0)
+    need = ctypes.c_uint64(0)
+    _check(lib.lstm_attention_query(ctypes.byref(d), ctypes.byref(need)))
+    d.workspace_bytes = need.value
+    return d
+
+
+def attention_step(enc, enc_ctx, src_lens, beam, s, W_s, b_s, w_fb, b_fb, v, b_e, accum, *, att=None, workspace=None, want_a=True):
+    """One attention step through lstm_attention_step.  enc [S,Q,E], enc_ctx [S,Q,A], s [B,n] (a view with a row stride is
+    fine), W_s [A,n] bfloat16; b_s, w_fb, b_fb, v float [A]; accum float [B,S]; att: optional bfloat16 [B,>=E] view to write into.
+    -> dict(a, accum, att, workspace)."""
+    S, Q, E = enc.shape
+    A = enc_ctx.shape[2]
+    B, n = s.shape
+    d = attention_query(S, Q, beam, A, E, n)
+    if workspace is None or workspace.numel() < d.workspace_bytes:
+        workspace = torch.empty(d.workspace_bytes, dtype=torch.uint8, device=enc.device)
+    d.workspace_bytes = workspace.numel()
+    if att is None:
+        att = torch.empty(B, E, dtype=torch.bfloat16, device=enc.device)
+    a = torch.empty(B, S, dtype=torch.float32, device=enc.device) if want_a else None
+    accum_out = torch.empty(B, S, dtype=torch.float32, device=enc.device)
+    assert enc.is_contiguous() and enc_ctx.is_contiguous() and accum.is_contiguous() and s.stride(1) == 1 and att.stride(1) == 1
+    _check(lib.lstm_attention_step(ctypes.byref(d), _ptr(enc), _ptr(enc_ctx), _ptr(src_lens), s.data_ptr(), s.stride(0), _ptr(W_s), _ptr(b_s),
+                                   _ptr(w_fb), _ptr(b_fb), _ptr(v), float(b_e), _ptr(accum), _ptr(accum_out), _ptr(a), att.data_ptr(),
+                                   att.stride(0), _ptr(workspace), _stream()))
+    return dict(a=a, accum=accum_out, att=att, workspace=workspace)
+
+
+def readout(x, W_r, b_r, *, out=None, workspace=None):
+    """out = relu(x W_r^T + b_r) through lstm_readout; x [B,K] bfloat16 (row stride allowed), W_r [R,K] bfloat16, b_r float [R]."""
+    B, K = x.shape
+    R = W_r.shape[0]
+    need = ctypes.c_uint64(0)
+    _check(lib.lstm_readout_query(B, R, K, ctypes.byref(need)))
+    if workspace is None or workspace.numel() < need.value:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty(B, R, dtype=torch.bfloat16, device=x.device)
+    assert x.stride(1) == 1 and W_r.is_contiguous() and out.stride(1) == 1
+    _check(lib.lstm_readout(B, R, K, x.data_ptr(), x.stride(0), _ptr(W_r), _ptr(b_r), out.data_ptr(), out.stride(0), _ptr(workspace),
+                            workspace.numel(), _stream()))
+    return out
 
 
 PHASES = ("prep", "gemm_zx", "loop_fwd", "loop_bwd", "gemm_dx", "gemm_dwx", "gemm_dwh", "db")

@@ -1,0 +1,263 @@
+// One step of the attention decoder between the stepped LSTM cell and the readout (Listing 1, sub-network of layer
+// "output": "s_tr", "weight_feedback", "e_in", "e_tanh", "e", "a", "accum_a", "att", "readout"):
+//
+//     s_tr[r]   = s[r] W_s + b_s                                       one product over all rows (MFMA)
+//     e[r, j]   = v . tanh(ctx[j, q(r)] + accum[r, j] w_fb + b_fb + s_tr[r]) + b_e      att_energy_kernel (vector ALU)
+//     a[r, :]   = softmax of e[r, :] over j < src_lens[q(r)],  accum' = accum + a        att_context_kernel
+//     att[r]    = sum_j a[r, j] H[j, q(r)]                                               att_context_kernel (reads H once per sentence)
+//     readout   = max(0, [s, trg, att] W_r + b_r)                      one product + bias_relu_kernel
+//
+// q(r) = r / beam: the hypotheses of a sentence are neighbours in the decoder batch, so one work-group serves all of
+// them from a single read of the sentence's ctx / H rows.  Storage: ctx, H, s, att, readout bfloat16; s_tr, e, a, accum
+// float; all arithmetic float.
+#include <algorithm>
+
+#include "../../include/lstm_abi.h"
+#include "common.h"
+#include "recurrent_dev.h"
+
+namespace lstm {
+namespace {
+
+constexpr int kMaxBeam = 16;          // hypotheses per sentence (register budget of the energy kernel)
+constexpr int kJB = 4;                // source positions per work-group of the energy kernel
+constexpr int kPartStride = 260;      // floats per partial-sum row in LDS: 4 * value + slot hits 64 different banks
+
+__device__ __forceinline__ int src_len(const int* lens, int q, int S) {
+  if (!lens) return S;
+  const int L = lens[q];
+  return L < 0 ? 0 : (L > S ? S : L);
+}
+
+// e[r][j] for the rows of sentence q = blockIdx.y and the kJB positions from blockIdx.x * kJB.  A lane owns the
+// attention features k = lane, lane + 256, ...: it loads ctx[j][q][k] once and uses it for every hypothesis of the
+// sentence.  The beam x kJB partial sums of the 256 lanes are added through LDS.
+__global__ __launch_bounds__(256) void att_energy_kernel(const uint16_t* __restrict__ ctx, const float* __restrict__ s_tr,
+                                                          const float* __restrict__ accum, const float* __restrict__ w_fb,
+                                                          const float* __restrict__ b_fb, const float* __restrict__ v, float b_e,
+                                                          const int* __restrict__ lens, float* __restrict__ e, int S, int Q, int beam,
+                                                          int A) {
+  __shared__ float part[kMaxBeam / 2 * kJB * kPartStride];     // half of the hypotheses at a time
+  const int q = blockIdx.y, j0 = blockIdx.x * kJB, tid = threadIdx.x;
+  const int L = src_len(lens, q, S);
+  if (j0 >= L) return;
+  const int nj = min(kJB, L - j0);
+  float sum[kMaxBeam][kJB];
+#pragma unroll
+  for (int r = 0; r < kMaxBeam; ++r)
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) sum[r][j] = 0.f;
+  for (int k = tid; k < A; k += 256) {
+    float c[kJB];
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) c[j] = j < nj ? bf_bits2f(ctx[((long)(j0 + j) * Q + q) * A + k]) + b_fb[k] : 0.f;
+    const float wf = w_fb[k], vk = v[k];
+#pragma unroll
+    for (int r = 0; r < kMaxBeam; ++r) {
+      if (r < beam) {                                          // uniform: a scalar branch
+        const long row = (long)q * beam + r;
+        const float st = s_tr[row * A + k];
+#pragma unroll
+        for (int j = 0; j < kJB; ++j) {
+          const float ac = j < nj ? accum[row * S + j0 + j] : 0.f;          // uniform address
+          sum[r][j] += vk * tanhf_(c[j] + ac * wf + st);
+        }
+      }
+    }
+  }
+  constexpr int kHalf = kMaxBeam / 2;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    if (half * kHalf >= beam) break;
+    if (half) __syncthreads();                                  // the first half has been read
+#pragma unroll
+    for (int rr = 0; rr < kHalf; ++rr)
+      if (half * kHalf + rr < beam) {
+#pragma unroll
+        for (int j = 0; j < kJB; ++j) part[(rr * kJB + j) * kPartStride + tid] = sum[half * kHalf + rr][j];
+      }
+    __syncthreads();
+    // value `vid` (= rr * kJB + j) is added up by four lanes, each taking every fourth of the 256 partial sums
+    const int vid = tid >> 2, sub = tid & 3;
+    const int r = half * kHalf + vid / kJB, j = vid % kJB;
+    const bool live = vid < kHalf * kJB && r < beam;
+    float t = 0.f;
+    if (live) {
+      for (int i = 0; i < 64; ++i) t += part[vid * kPartStride + 4 * i + sub];
+    }
+    t += __shfl_xor(t, 1);
+    t += __shfl_xor(t, 2);
+    if (sub == 0 && live && j < nj) e[((long)q * beam + r) * S + j0 + j] = t + b_e;
+  }
+}
+
+// Softmax over the valid positions for every hypothesis of sentence q = blockIdx.y (each work-group of the sentence
+// repeats it: beam x S exponentials), the first work-group also writes a and accum'; then a slice of 512 features of
+// att: a lane owns two neighbouring features and walks the source positions, reading H once for all hypotheses.
+// Dynamic LDS: S * kMaxBeam floats, w[j][r].
+__global__ __launch_bounds__(256) void att_context_kernel(const uint16_t* __restrict__ H, const float* __restrict__ e,
+                                                           const float* __restrict__ accum_in, const int* __restrict__ lens,
+                                                           float* __restrict__ a_out, float* __restrict__ accum_out,
+                                                           uint16_t* __restrict__ att, long ldatt, int S, int Q, int beam, int E) {
+  extern __shared__ float w[];
+  const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int L = src_len(lens, q, S);
+  for (int r = wave; r < beam; r += 4) {
+    const long row = (long)q * beam + r;
+    float m = -3.0e38f;
+    for (int j = lane; j < L; j += 64) m = fmaxf(m, e[row * S + j]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    float z = 0.f;
+    for (int j = lane; j < L; j += 64) z += __expf(e[row * S + j] - m);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
+    const float inv = L > 0 ? 1.f / z : 0.f;
+    for (int j = lane; j < S; j += 64) {
+      const float p = j < L ? __expf(e[row * S + j] - m) * inv : 0.f;
+      if (j < L) w[j * kMaxBeam + r] = p;
+      if (blockIdx.x == 0) {
+        if (a_out) a_out[row * S + j] = p;
+        accum_out[row * S + j] = j < L ? accum_in[row * S + j] + p : 0.f;
+      }
+    }
+  }
+  __syncthreads();
+  const int f = (blockIdx.x * 256 + tid) * 2;
+  if (f >= E) return;
+  float acc[kMaxBeam][2];
+#pragma unroll
+  for (int r = 0; r < kMaxBeam; ++r) acc[r][0] = acc[r][1] = 0.f;
+  for (int j = 0; j < L; ++j) {
+    const unsigned hh = *(const unsigned*)(H + ((long)j * Q + q) * E + f);        // E even, rows 4-byte aligned
+    const float h0 = __uint_as_float(hh << 16), h1 = __uint_as_float(hh & 0xffff0000u);
+#pragma unroll
+    for (int r = 0; r < kMaxBeam; ++r)
+      if (r < beam) {
+        const float p = w[j * kMaxBeam + r];
+        acc[r][0] += p * h0;
+        acc[r][1] += p * h1;
+      }
+  }
+#pragma unroll
+  for (int r = 0; r < kMaxBeam; ++r)
+    if (r < beam) {
+      const unsigned o = (unsigned)f2bf_bits(acc[r][0]) | ((unsigned)f2bf_bits(acc[r][1]) << 16);
+      *(unsigned*)(att + ((long)q * beam + r) * ldatt + f) = o;
+    }
+}
+
+// out = bfloat16(max(0, z)) for a float z[M][N] that already holds product + bias
+__global__ void relu_bf16_kernel(const float* __restrict__ z, uint16_t* __restrict__ out, int M, int N, long ldo) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long)M * N) return;
+  const int m = (int)(idx / N), n = (int)(idx % N);
+  out[(long)m * ldo + n] = f2bf_bits(fmaxf(z[idx], 0.f));
+}
+
+inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+// C[M][N] float = A[M][lda] (bf16) . W[N][ldw]^T (bf16, a row per output) + bias, K cut into ranges when the product has
+// few output tiles; `parts` holds ksplit * M * N floats.
+hipError_t linear_rows(const void* A, long lda, const void* W, long ldw, const float* bias, float* C, int M, int N, int K, float* parts,
+                       int ksplit, hipStream_t s) {
+  GemmArgs g = {};
+  g.A = A; g.B = W; g.C = C; g.bias = bias; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldw; g.ldc = N;
+  g.nz = 1; g.nseg = 1; g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false;
+  const auto vec = [](const void* p, long ld) { int v = 16; while (v > 2 && (((uintptr_t)p % v) || ((ld * 2) % v))) v >>= 1; return v; };
+  g.vecA = vec(A, lda); g.vecB = vec(W, ldw);
+  if (ksplit > 1 && gemm_nt_ok(g)) { g.ksplit = ksplit; g.parts = parts; }
+  return launch_gemm(g, s);
+}
+int ranges_for(int M, int N, int K) {
+  const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256), stages = (K + 63) / 64;
+  return (int)std::max(1L, std::min(std::min(256 / std::max(tiles, 1L), stages / 4), 8L));
+}
+
+}  // namespace
+}  // namespace lstm
+
+using namespace lstm;
+
+extern "C" {
+
+static int att_check(const lstm_att_desc* d) {
+  if (!d) return LSTM_ERR_NULL;
+  if (d->S < 1 || d->Q < 0 || d->beam < 1 || d->A < 1 || d->E < 2 || d->n < 1 || d->Q > 65535 || (long)d->Q * d->beam > 0x7fffffffL / d->S)
+    return LSTM_ERR_DIM;
+  if (d->beam > kMaxBeam || d->S > 1024 || (d->E & 1)) return LSTM_ERR_UNSUPPORTED;
+  return LSTM_OK;
+}
+
+int lstm_attention_query(const lstm_att_desc* d, uint64_t* workspace_bytes) {
+  int rc = att_check(d);
+  if (rc) return rc;
+  if (!workspace_bytes) return LSTM_ERR_NULL;
+  const size_t B = (size_t)d->Q * d->beam;
+  const int ks = ranges_for((int)B, d->A, d->n);
+  *workspace_bytes = 256 + up256(B * d->A * 4) + up256(B * d->S * 4) + (ks > 1 ? up256((size_t)ks * B * d->A * 4) : 0);
+  return LSTM_OK;
+}
+
+int lstm_attention_step(const lstm_att_desc* d, const void* enc, const void* enc_ctx, const int32_t* src_lens, const void* s, int64_t ld_s,
+                        const void* W_s, const float* b_s, const float* w_fb, const float* b_fb, const float* v, float b_e,
+                        const float* accum_in, float* accum_out, float* a, void* att, int64_t ld_att, void* workspace, void* stream) {
+  int rc = att_check(d);
+  if (rc) return rc;
+  if (!enc || !enc_ctx || !s || !W_s || !b_s || !w_fb || !b_fb || !v || !accum_in || !accum_out || !att || !workspace) return LSTM_ERR_NULL;
+  if (ld_s < d->n || ld_att < d->E) return LSTM_ERR_DIM;
+  if ((ld_att & 1) || ((uintptr_t)att & 3) || ((uintptr_t)enc & 3) || ((uintptr_t)enc_ctx & 1) || ((uintptr_t)s & 1) || ((uintptr_t)W_s & 1) ||
+      (((uintptr_t)b_s | (uintptr_t)w_fb | (uintptr_t)b_fb | (uintptr_t)v | (uintptr_t)accum_in | (uintptr_t)accum_out | (uintptr_t)a) & 3))
+    return LSTM_ERR_ALIGN;
+  uint64_t need = 0;
+  lstm_attention_query(d, &need);
+  if (d->workspace_bytes < need) return LSTM_ERR_SIZE;
+  if (d->Q == 0) return LSTM_OK;
+  if ((rc = device_ok())) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const int B = d->Q * d->beam;
+  char* ws = (char*)(((uintptr_t)workspace + 255) / 256 * 256);
+  float* s_tr = (float*)ws;
+  float* e = (float*)(ws + up256((size_t)B * d->A * 4));
+  float* parts = (float*)(ws + up256((size_t)B * d->A * 4) + up256((size_t)B * d->S * 4));
+  const int ks = ranges_for(B, d->A, d->n);
+  if (linear_rows(s, ld_s, W_s, d->n, b_s, s_tr, B, d->A, d->n, parts, ks, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  hipLaunchKernelGGL(att_energy_kernel, dim3((d->S + kJB - 1) / kJB, d->Q), dim3(256), 0, st, (const uint16_t*)enc_ctx, s_tr, accum_in, w_fb,
+                     b_fb, v, b_e, src_lens, e, d->S, d->Q, d->beam, d->A);
+  hipLaunchKernelGGL(att_context_kernel, dim3((d->E / 2 + 255) / 256, d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, (const uint16_t*)enc, e,
+                     accum_in, src_lens, a, accum_out, (uint16_t*)att, (long)ld_att, d->S, d->Q, d->beam, d->E);
+  if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
+  return LSTM_OK;
+}
+
+int lstm_readout_query(int B, int R, int K, uint64_t* workspace_bytes) {
+  if (!workspace_bytes) return LSTM_ERR_NULL;
+  if (B < 0 || R < 1 || K < 1 || (long)B * R > 0x7fffffffL) return LSTM_ERR_DIM;
+  const int ks = ranges_for(B, R, K);
+  *workspace_bytes = 256 + up256((size_t)B * R * 4) + (ks > 1 ? up256((size_t)ks * B * R * 4) : 0);
+  return LSTM_OK;
+}
+
+int lstm_readout(int B, int R, int K, const void* x, int64_t ld_x, const void* W_r, const float* b_r, void* out, int64_t ld_out,
+                 void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!x || !W_r || !out || !workspace) return LSTM_ERR_NULL;
+  if (B < 0 || R < 1 || K < 1 || ld_x < K || ld_out < R || (long)B * R > 0x7fffffffL) return LSTM_ERR_DIM;
+  if ((((uintptr_t)x | (uintptr_t)W_r | (uintptr_t)out) & 1) || ((uintptr_t)b_r & 3)) return LSTM_ERR_ALIGN;
+  uint64_t need = 0;
+  lstm_readout_query(B, R, K, &need);
+  if (workspace_bytes < need) return LSTM_ERR_SIZE;
+  if (B == 0) return LSTM_OK;
+  int rc = device_ok();
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)(((uintptr_t)workspace + 255) / 256 * 256);
+  float* z = (float*)ws;
+  float* parts = (float*)(ws + up256((size_t)B * R * 4));
+  if (linear_rows(x, ld_x, W_r, K, b_r, z, B, R, K, parts, ranges_for(B, R, K), st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  const long total = (long)B * R;
+  hipLaunchKernelGGL(relu_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, z, (uint16_t*)out, B, R, (long)ld_out);
+  if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
+  return LSTM_OK;
+}
+
+}  // extern "C"

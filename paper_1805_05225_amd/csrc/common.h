@@ -213,6 +213,7 @@ hipError_t launch_pack_wh_bwd(const void* W_h, uint4* Wb, int n, int nkc, int nd
 // h (float [ndir][B][n]) -> fragment order, zero padded, written to both ping-pong buffers
 hipError_t launch_pack_state(const float* h, uint4* frag0, uint4* frag1, int B, int n, int nkc, int nrt, int ndir,
                              bool bf16, hipStream_t s);
+int device_ok();   // 0 if the current device is gfx950, else a negative lstm_status (cached after the first call)
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);                 // p 4-byte aligned, bytes % 2 == 0
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);   // bytes % 4 == 0
 // Up to kMax regions cleared by one launch (the set-up of a layer clears half a dozen small buffers; one launch each

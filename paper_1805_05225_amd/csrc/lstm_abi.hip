@@ -612,6 +612,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
 }
 
 }  // namespace
+int device_ok() { return check_device(); }
 }  // namespace lstm
 
 extern "C" {

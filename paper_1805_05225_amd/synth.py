@@ -87,3 +87,38 @@ def flops_fwd_bwd(inp):
         Dl, ni = L["W_x"].shape[0], L["W_x"].shape[1]
         tot += Dl * 24 * n * (ni + n)
     return tot * real_frames(inp)
+
+
+# ---- one step of the attention decoder (Listing 1: 620-wide target embedding, 1000-wide cell, attention and readout,
+# 2000-wide encoder states; Sec. 5: beam 12) ------------------------------------------------------------------------
+DECODER = dict(Q=64, beam=12, len_lo=20, len_hi=80, A=1000, E=2000, n=1000, n_trg=620, R=1000, w=0.05)
+
+
+def make_decoder(**override):
+    """Seeded inputs of one decoder step, every bfloat16-stored tensor already rounded (float32 numpy arrays):
+    src_lens int32 [Q]; H [S,Q,E] encoder states and ctx [S,Q,A] their projection, both drawn directly (the step takes
+    ctx as an input); s [B,n] cell output, trg [B,n_trg] previous target embedding, accum [B,S] accumulated weights
+    (zero at padded positions); W_s [A,n], b_s, w_fb, b_fb, v [A], b_e; W_r [R, n+n_trg+E], b_r [R].  B = Q*beam.
+    Draw order: src_lens, H, ctx, s, trg, accum, W_s, b_s, w_fb, b_fb, v, b_e, W_r, b_r."""
+    cfg = dict(DECODER)
+    cfg.update(override)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(SEED_BASE + 8)
+    Q, beam, A, E, n, nt, R, w = cfg["Q"], cfg["beam"], cfg["A"], cfg["E"], cfg["n"], cfg["n_trg"], cfg["R"], cfg["w"]
+    B = Q * beam
+    lens = torch.randint(cfg["len_lo"], cfg["len_hi"] + 1, (Q,), generator=g, dtype=torch.int64)
+    S = max(int(lens.max()), 1) if Q > 0 else 1
+    bf = lambda a: round_to(a, "bf16")
+    u = lambda *shape: torch.rand(*shape, generator=g) * 2 - 1
+    H = bf(u(S, Q, E))
+    ctx = bf(torch.randn(S, Q, A, generator=g))
+    s = bf(u(B, n))
+    trg = bf(torch.randn(B, nt, generator=g) * 0.5)
+    accum = torch.rand(B, S, generator=g) * 1.5
+    valid = torch.arange(S)[None, :] < lens.repeat_interleave(beam)[:, None]
+    accum = accum * valid
+    out = dict(cfg=cfg, S=S, B=B, src_lens=lens.to(torch.int32).numpy(), H=H.numpy(), ctx=ctx.numpy(), s=s.numpy(), trg=trg.numpy(),
+               accum=accum.numpy(), W_s=bf(u(A, n) * w).numpy(), b_s=(u(A) * 0.1).numpy(), w_fb=(u(A) * 0.5).numpy(),
+               b_fb=(u(A) * 0.1).numpy(), v=(u(A) * 0.2).numpy(), b_e=float(u(1)[0]) * 0.1,
+               W_r=bf(u(R, n + nt + E) * w).numpy(), b_r=(u(R) * 0.1).numpy())
+    return out

@@ -124,6 +124,39 @@ def test_time_pool_argument_errors():
     assert fwd(y=P + 1) == -5 and bwd(dy=P + 1) == -5 and fwd(dtype=0, out=P + 2) == -5
 
 
+def test_attention_and_readout_argument_errors():
+    import ctypes
+    q = ctypes.c_uint64(0)
+    mk = lambda **o: Bn.AttDesc(*[{**dict(S=8, Q=2, beam=3, A=16, E=32, n=24), **o}[k] for k in ("S", "Q", "beam", "A", "E", "n")], 1 << 30)
+    query = lambda **o: Bn.lib.lstm_attention_query(ctypes.byref(mk(**o)), ctypes.byref(q))
+    assert query() == 0 and q.value > 0
+    assert Bn.lib.lstm_attention_query(None, ctypes.byref(q)) == -1 and Bn.lib.lstm_attention_query(ctypes.byref(mk()), None) == -1
+    for bad in (dict(S=0), dict(Q=-1), dict(beam=0), dict(A=0), dict(E=0), dict(n=0), dict(Q=70000)):
+        assert query(**bad) == -2
+    for bad in (dict(beam=17), dict(S=1025), dict(E=33)):
+        assert query(**bad) == -4
+    names = ("enc", "ctx", "lens", "s", "ld_s", "W_s", "b_s", "w_fb", "b_fb", "v", "b_e", "acc_in", "acc_out", "a", "att", "ld_att", "ws")
+    base = dict(enc=P, ctx=P, lens=None, s=P, ld_s=24, W_s=P, b_s=P, w_fb=P, b_fb=P, v=P, b_e=0.0, acc_in=P, acc_out=P, a=None, att=P, ld_att=32, ws=P)
+    step = lambda d=None, **o: Bn.lib.lstm_attention_step(ctypes.byref(d or mk()), *[{**base, **o}[k] for k in names], None)
+    for k in ("enc", "ctx", "s", "W_s", "b_s", "w_fb", "b_fb", "v", "acc_in", "acc_out", "att", "ws"):
+        assert step(**{k: None}) == -1, k
+    assert step(ld_s=23) == -2 and step(ld_att=30) == -2
+    assert step(ld_att=33) == -5 and step(att=P + 2) == -5 and step(b_s=P + 2) == -5 and step(s=P + 1) == -5
+    small = mk(); small.workspace_bytes = 16
+    assert step(small) == -6
+    assert step(mk(Q=0)) == 0                                   # nothing to do, nothing launched
+    # readout
+    rq = lambda B=4, R=8, K=16: Bn.lib.lstm_readout_query(B, R, K, ctypes.byref(q))
+    assert rq() == 0 and q.value > 0 and rq(B=-1) == -2 and rq(R=0) == -2 and rq(K=0) == -2
+    assert Bn.lib.lstm_readout_query(4, 8, 16, None) == -1
+    ro = lambda B=4, R=8, K=16, x=P, ld_x=16, W=P, b=None, out=P, ld_out=8, ws=P, wsb=1 << 30: Bn.lib.lstm_readout(B, R, K, x, ld_x, W, b, out, ld_out, ws, wsb, None)
+    assert ro(x=None) == -1 and ro(W=None) == -1 and ro(out=None) == -1 and ro(ws=None) == -1
+    assert ro(ld_x=15) == -2 and ro(ld_out=7) == -2 and ro(B=-1) == -2
+    assert ro(x=P + 1) == -5 and ro(b=P + 2) == -5
+    assert ro(wsb=8) == -6
+    assert ro(B=0) == 0
+
+
 def test_strerror():
     for s in range(0, -8, -1):
         assert Bn.strerror(s) and "unknown" not in Bn.strerror(s)
