@@ -275,6 +275,113 @@ def bench_decoder(args, Bn, synth):
     print(json.dumps(out))
 
 
+def bench_decoder_attention(args, Bn, synth):
+    """--config 8: the whole recurrent part of one decoder step (Listing 1): stepped LSTM cell on [trg | att of the previous
+    step], attention (energies with weight feedback, softmax over the source positions, accumulated weights, context) and
+    readout, for 64 sentences x beam 12.  The context of step i is written straight into the cell input of step i+1, so the
+    steps of a block depend on each other exactly as in a search; the target embedding is a fixed random one (choosing the
+    output label is not part of this path).  One "step" is a block of 100 dependent decoder steps; the figure of merit is the
+    latency of one decoder step."""
+    import ctypes as ct
+    inp5 = synth.make(5)
+    L = inp5["layers"][0]
+    dec = synth.make_decoder()
+    cfg = dec["cfg"]
+    Q, beam, A, E, n, nt, R, S, B = cfg["Q"], cfg["beam"], cfg["A"], cfg["E"], cfg["n"], cfg["n_trg"], cfg["R"], dec["S"], dec["B"]
+    nsteps = inp5["cfg"]["steps"]
+    assert inp5["cfg"]["n"] == n and inp5["cfg"]["n_in"] == nt + E and inp5["cfg"]["B"] == B
+    bf = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    f32 = lambda a: torch.from_numpy(a).float().cuda()
+    Wx, Wh, b = bf(L["W_x"][0]), bf(L["W_h"][0]), f32(L["b"][0])
+    enc, W_s, W_r = bf(dec["H"]), bf(dec["W_s"]), bf(dec["W_r"])
+    b_s, w_fb, b_fb, v, b_r = (f32(dec[k]) for k in ("b_s", "w_fb", "b_fb", "v", "b_r"))
+    lens = torch.from_numpy(dec["src_lens"]).cuda()
+    # the loop-invariant projection of the encoder states, once per sentence batch: one product over all S*Q positions
+    g = torch.Generator(device="cpu").manual_seed(8)
+    W_ctx = ((torch.rand(E, A, generator=g) * 2 - 1) * 0.05).to(torch.bfloat16).cuda()
+    ctx = Bn.gemm(enc.view(S * Q, E), W_ctx, a_kcontig=True, b_kcontig=False, M=S * Q, N=A, K=E, out_dtype=torch.bfloat16).view(S, Q, A)
+    xin = [torch.zeros(B, nt + E, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    for t in xin:
+        t[:, :nt] = bf(dec["trg"])
+    state = [torch.zeros(B, n, device="cuda") for _ in range(4)]                  # h, c ping-pong
+    accum = [torch.zeros(B, S, device="cuda") for _ in range(2)]
+    y = torch.empty(1, B, n, dtype=torch.bfloat16, device="cuda")
+    ro = torch.empty(B, R, dtype=torch.bfloat16, device="cuda")
+    desc = Bn.make_desc(1, B, nt + E, n, Bn.LSTM_BF16_F32STATE, 1, Bn.FLAG_INFERENCE)
+    _, wb = Bn.query(desc, False)
+    desc.workspace_bytes = wb
+    desc_packed = Bn.make_desc(1, B, nt + E, n, Bn.LSTM_BF16_F32STATE, 1, Bn.FLAG_INFERENCE | Bn.FLAG_WEIGHTS_PACKED)
+    desc_packed.workspace_bytes = wb
+    ws_cell = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    ad = Bn.attention_query(S, Q, beam, A, E, n)
+    ws_att = torch.empty(ad.workspace_bytes, dtype=torch.uint8, device="cuda")
+    need = ct.c_uint64(0)
+    assert Bn.lib.lstm_readout_query(B, R, n, nt, E, ct.byref(need)) == 0
+    ws_ro = torch.empty(need.value, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    lib = Bn.lib
+
+    def one(i, first, ev=None):
+        p = i % 2
+        h0, c0, h1, c1 = (state[0], state[1], state[2], state[3]) if p == 0 else (state[2], state[3], state[0], state[1])
+        if ev: ev[0].record()
+        rc = lib.lstm_fwd(ct.byref(desc if first else desc_packed), xin[p].data_ptr(), Wx.data_ptr(), Wh.data_ptr(), b.data_ptr(),
+                          h0.data_ptr(), c0.data_ptr(), None, y.data_ptr(), None, h1.data_ptr(), c1.data_ptr(), None, ws_cell.data_ptr(), st)
+        assert rc == 0, Bn.strerror(rc)
+        if ev: ev[1].record()
+        rc = lib.lstm_attention_step(ct.byref(ad), enc.data_ptr(), ctx.data_ptr(), lens.data_ptr(), y.data_ptr(), n, W_s.data_ptr(),
+                                     b_s.data_ptr(), w_fb.data_ptr(), b_fb.data_ptr(), v.data_ptr(), float(dec["b_e"]), accum[p].data_ptr(),
+                                     accum[1 - p].data_ptr(), None, xin[1 - p].data_ptr() + 2 * nt, nt + E, ws_att.data_ptr(), st)
+        assert rc == 0, Bn.strerror(rc)
+        if ev: ev[2].record()
+        rc = lib.lstm_readout(0 if first else Bn.FLAG_WEIGHTS_PACKED, B, R, y.data_ptr(), n, n, xin[p].data_ptr(), nt + E, nt,
+                              xin[1 - p].data_ptr() + 2 * nt, nt + E, E, W_r.data_ptr(), b_r.data_ptr(), ro.data_ptr(), R, ws_ro.data_ptr(),
+                              ws_ro.numel(), st)
+        assert rc == 0, Bn.strerror(rc)
+        if ev: ev[3].record()
+
+    def block(first=False):
+        for i in range(nsteps):
+            one(i, first and i == 0)
+
+    block(True)                                   # packs the weights once
+    for _ in range(args.warmup):
+        block()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        block()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us = dt / (args.steps * nsteps) * 1e6
+    # break-down from one more block with events between the three calls (not part of `value`)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(nsteps)]
+    for i in range(nsteps):
+        one(i, False, evs[i])
+    torch.cuda.synchronize()
+    part = [sum(e[k].elapsed_time(e[k + 1]) for e in evs) / nsteps * 1e3 for k in range(3)]
+    # attention energies: per (row, valid source position, attention feature) 11 float operations (multiply-add of the weight
+    # feedback, add of s_tr, tanh as 2x, exp, +1, reciprocal, multiply-add, multiply-add into the sum), on the vector ALU
+    valid = int(dec["src_lens"].astype("int64").sum()) * beam
+    alu_flops = 11.0 * valid * A
+    mfma_flops = 2.0 * B * (n * (nt + E + n) * 4 + n * A + (n + nt + E) * R)
+    out = {
+        "metric": "attention decoder step latency (n=%d, %d rows)" % (n, B), "value": us, "unit": "us/step", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 8: LSTM cell (620 + 2000 -> %d) + attention over S<=%d source positions (A=%d, E=%d, weight "
+                               "feedback) + readout (-> %d), %d sentences x beam %d = %d rows, %d dependent steps per block, bf16 storage, "
+                               "forward only" % (n, S, A, E, R, Q, beam, B, nsteps)},
+        "us_per_step_cell_attention_readout": part,
+        "useful_tflops_products": mfma_flops / (us * 1e-6) / 1e12,
+        "roofline": {"bound": "alu", "kernel": "att_energy_kernel (inside the attention call, which also runs the s_tr product and "
+                                               "att_context_kernel)", "achieved": alu_flops / (part[1] * 1e-6) / 1e12, "peak": 157.3,
+                     "unit": "TFLOP/s", "frac": alu_flops / (part[1] * 1e-6) / 1e12 / 157.3, "traffic": None,
+                     "note": "achieved = energy flops / time of the whole attention call; see profiles/ for the kernel alone"},
+    }
+    print(json.dumps(out))
+
+
 class PooledStack:
     """The config-4 stack with max-pooling in time (windows of 2 frames) behind layers 1, 2 and 3: the shape of the
     paper's attention-based speech encoder (6 bidirectional layers, input shortened by a factor of 8 in total)."""
@@ -405,7 +512,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell; 6 = config 4 with max-pooling in time between layers; 7 = one bidirectional layer below five unidirectional ones)")
+    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell; 6 = config 4 with max-pooling in time between layers; 7 = one bidirectional layer below five unidirectional ones; 8 = decoder step with attention and readout)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--per-step", action="store_true", help="force one launch per time step")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -431,6 +538,9 @@ def main():
         return
     if args.config == 7:
         bench_mixed(args, Bn, synth)
+        return
+    if args.config == 8:
+        bench_decoder_attention(args, Bn, synth)
         return
     inp = synth.make(args.config)
     cfg = inp["cfg"]

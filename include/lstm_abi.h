@@ -195,15 +195,22 @@ int lstm_attention_step(const lstm_att_desc* desc, const void* enc, const void* 
                         const float* b_fb, const float* v, float b_e, const float* accum_in, float* accum_out,
                         float* a, void* att, int64_t ld_att, void* workspace, void* stream);
 
-/* The decoder's readout (Listing 1, "readout": a linear layer with relu over the cell output, the previous target
- * embedding and the attention context): out = max(0, x W_r + b_r) with x[B][ld_x >= K] the rows [s | trg | att]
- * laid side by side by the caller (lstm_attention_step can write att straight into them).
- *   x bfloat16, W_r bfloat16 [R][K] (a row per output feature), b_r float [R] or NULL, out bfloat16 [B][ld_out >= R];
- *   workspace of lstm_readout_query(B, R, K) bytes.  Float accumulation, one rounding at the end.
- * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM, LSTM_ERR_ALIGN, LSTM_ERR_SIZE, LSTM_ERR_HIP. */
-int lstm_readout_query(int B, int R, int K, uint64_t* workspace_bytes);
-int lstm_readout(int B, int R, int K, const void* x, int64_t ld_x, const void* W_r, const float* b_r, void* out,
-                 int64_t ld_out, void* workspace, uint64_t workspace_bytes, void* stream);
+/* The decoder's readout (Listing 1, "readout": a linear layer with relu over the cell output s, the previous target
+ * embedding trg and the attention context att):  out[r] = max(0, [s[r] | trg[r] | att[r]] W_r + b_r).
+ *   s bfloat16 [B][ld_s >= n], trg bfloat16 [B][ld_trg >= n_trg], att bfloat16 [B][ld_att >= E]: three separate
+ *   arrays with their own row strides (att may be where lstm_attention_step wrote it, trg and att may be the two
+ *   halves of the cell's input rows); trg may be NULL if n_trg = 0, att if E = 0.
+ *   W_r bfloat16 [R][n + n_trg + E] (a row per output feature, columns ordered s | trg | att), b_r float [R] or NULL,
+ *   out bfloat16 [B][ld_out >= R]; workspace of lstm_readout_query(B, R, n, n_trg, E) bytes.
+ *   flags: 0, or LSTM_FLAG_WEIGHTS_PACKED from the second call on: the caller states that W_r and the workspace
+ *   are unchanged since the previous call, which left a copy of W_r with padded rows there (as for the stepped cell).
+ *   Float accumulation, one rounding at the end.  Device pointers owned by the caller; the call only enqueues work.
+ * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM, LSTM_ERR_UNSUPPORTED (other flag bits), LSTM_ERR_ALIGN (element alignment),
+ * LSTM_ERR_SIZE, LSTM_ERR_HIP. */
+int lstm_readout_query(int B, int R, int n, int n_trg, int E, uint64_t* workspace_bytes);
+int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, const void* trg, int64_t ld_trg, int n_trg,
+                 const void* att, int64_t ld_att, int E, const void* W_r, const float* b_r, void* out, int64_t ld_out,
+                 void* workspace, uint64_t workspace_bytes, void* stream);
 
 /* Diagnostic for the single-launch (persistent) recurrent kernels, whose work-groups wait for each
  * other between time steps with BOUNDED waits.  If a wait ever expired, the kernel drained early, the

@@ -65,9 +65,9 @@ def _load():
     lib.lstm_attention_step.restype = ip
     lib.lstm_attention_step.argtypes = [ctypes.POINTER(AttDesc), vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i64, vp, vp]
     lib.lstm_readout_query.restype = ip
-    lib.lstm_readout_query.argtypes = [ip, ip, ip, u64p]
+    lib.lstm_readout_query.argtypes = [ip, ip, ip, ip, ip, u64p]
     lib.lstm_readout.restype = ip
-    lib.lstm_readout.argtypes = [ip, ip, ip, vp, i64, vp, vp, vp, i64, vp, ctypes.c_uint64, vp]
+    lib.lstm_readout.argtypes = [ip, ip, ip, vp, i64, ip, vp, i64, ip, vp, i64, ip, vp, vp, vp, i64, vp, ctypes.c_uint64, vp]
     lib.lstm_sync_status.restype = ip
     lib.lstm_sync_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
     lib.lstm_profile_enable.restype = ip
@@ -237,19 +237,20 @@ def attention_step(enc, enc_ctx, src_lens, beam, s, W_s, b_s, w_fb, b_fb, v, b_e
     return dict(a=a, accum=accum_out, att=att, workspace=workspace)
 
 
-def readout(x, W_r, b_r, *, out=None, workspace=None):
-    """out = relu(x W_r^T + b_r) through lstm_readout; x [B,K] bfloat16 (row stride allowed), W_r [R,K] bfloat16, b_r float [R]."""
-    B, K = x.shape
-    R = W_r.shape[0]
+def readout(s, trg, att, W_r, b_r, *, out=None, workspace=None, flags=0):
+    """out = relu([s | trg | att] W_r^T + b_r) through lstm_readout; s [B,n], trg [B,n_trg], att [B,E] bfloat16 (views with a
+    row stride are fine), W_r [R, n+n_trg+E] bfloat16, b_r float [R]."""
+    B, n = s.shape
+    nt, E, R = trg.shape[1], att.shape[1], W_r.shape[0]
     need = ctypes.c_uint64(0)
-    _check(lib.lstm_readout_query(B, R, K, ctypes.byref(need)))
+    _check(lib.lstm_readout_query(B, R, n, nt, E, ctypes.byref(need)))
     if workspace is None or workspace.numel() < need.value:
-        workspace = torch.empty(need.value, dtype=torch.uint8, device=x.device)
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=s.device)
     if out is None:
-        out = torch.empty(B, R, dtype=torch.bfloat16, device=x.device)
-    assert x.stride(1) == 1 and W_r.is_contiguous() and out.stride(1) == 1
-    _check(lib.lstm_readout(B, R, K, x.data_ptr(), x.stride(0), _ptr(W_r), _ptr(b_r), out.data_ptr(), out.stride(0), _ptr(workspace),
-                            workspace.numel(), _stream()))
+        out = torch.empty(B, R, dtype=torch.bfloat16, device=s.device)
+    assert s.stride(1) == 1 and trg.stride(1) == 1 and att.stride(1) == 1 and W_r.is_contiguous() and out.stride(1) == 1
+    _check(lib.lstm_readout(flags, B, R, s.data_ptr(), s.stride(0), n, trg.data_ptr(), trg.stride(0), nt, att.data_ptr(), att.stride(0), E,
+                            _ptr(W_r), _ptr(b_r), out.data_ptr(), out.stride(0), _ptr(workspace), workspace.numel(), _stream()))
     return out
 
 

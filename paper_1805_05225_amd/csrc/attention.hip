@@ -155,6 +155,17 @@ __global__ void relu_bf16_kernel(const float* __restrict__ z, uint16_t* __restri
   out[(long)m * ldo + n] = f2bf_bits(fmaxf(z[idx], 0.f));
 }
 
+// cat[r] = [s[r] | trg[r] | att[r] | zeros up to ldc]: the three inputs of the readout side by side (16-bit elements, any
+// row strides)
+__global__ void concat3_kernel(const uint16_t* __restrict__ x0, long ld0, int k0, const uint16_t* __restrict__ x1, long ld1, int k1,
+                               const uint16_t* __restrict__ x2, long ld2, int k2, uint16_t* __restrict__ cat, long ldc, int B) {
+  const int K = k0 + k1 + k2;                                  // columns K .. ldc-1 of cat are padding: zeros
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long)B * ldc) return;
+  const int r = (int)(idx / ldc), k = (int)(idx % ldc);
+  cat[idx] = k < k0 ? x0[(long)r * ld0 + k] : (k < k0 + k1 ? x1[(long)r * ld1 + k - k0] : (k < K ? x2[(long)r * ld2 + k - k0 - k1] : (uint16_t)0));
+}
+
 inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 // C[M][N] float = A[M][lda] (bf16) . W[N][ldw]^T (bf16, a row per output) + bias, K cut into ranges when the product has
@@ -230,30 +241,54 @@ int lstm_attention_step(const lstm_att_desc* d, const void* enc, const void* enc
   return LSTM_OK;
 }
 
-int lstm_readout_query(int B, int R, int K, uint64_t* workspace_bytes) {
+static int readout_dims(int B, int R, int n, int n_trg, int E) {
+  if (B < 0 || R < 1 || n < 1 || n_trg < 0 || E < 0 || (long)n + n_trg + E > 0x7fffff || (long)B * R > 0x7fffffffL ||
+      (long)B * ((long)n + n_trg + E) > 0x7fffffffL)
+    return LSTM_ERR_DIM;
+  return LSTM_OK;
+}
+static long readout_kpad(int n, int n_trg, int E) { return ((long)n + n_trg + E + 7) / 8 * 8; }     // rows of whole 16-byte chunks
+
+int lstm_readout_query(int B, int R, int n, int n_trg, int E, uint64_t* workspace_bytes) {
   if (!workspace_bytes) return LSTM_ERR_NULL;
-  if (B < 0 || R < 1 || K < 1 || (long)B * R > 0x7fffffffL) return LSTM_ERR_DIM;
-  const int ks = ranges_for(B, R, K);
-  *workspace_bytes = 256 + up256((size_t)B * R * 4) + (ks > 1 ? up256((size_t)ks * B * R * 4) : 0);
+  const int rc = readout_dims(B, R, n, n_trg, E);
+  if (rc) return rc;
+  const long Kp = readout_kpad(n, n_trg, E);
+  const int ks = ranges_for(B, R, (int)Kp);
+  *workspace_bytes = 256 + up256((size_t)R * Kp * 2) + up256((size_t)B * Kp * 2) + up256((size_t)B * R * 4) +
+                     (ks > 1 ? up256((size_t)ks * B * R * 4) : 0);
   return LSTM_OK;
 }
 
-int lstm_readout(int B, int R, int K, const void* x, int64_t ld_x, const void* W_r, const float* b_r, void* out, int64_t ld_out,
-                 void* workspace, uint64_t workspace_bytes, void* stream) {
-  if (!x || !W_r || !out || !workspace) return LSTM_ERR_NULL;
-  if (B < 0 || R < 1 || K < 1 || ld_x < K || ld_out < R || (long)B * R > 0x7fffffffL) return LSTM_ERR_DIM;
-  if ((((uintptr_t)x | (uintptr_t)W_r | (uintptr_t)out) & 1) || ((uintptr_t)b_r & 3)) return LSTM_ERR_ALIGN;
+int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, const void* trg, int64_t ld_trg, int n_trg, const void* att,
+                 int64_t ld_att, int E, const void* W_r, const float* b_r, void* out, int64_t ld_out, void* workspace,
+                 uint64_t workspace_bytes, void* stream) {
+  if (!s || (!trg && n_trg > 0) || (!att && E > 0) || !W_r || !out || !workspace) return LSTM_ERR_NULL;
+  if (flags & ~LSTM_FLAG_WEIGHTS_PACKED) return LSTM_ERR_UNSUPPORTED;
+  int rc = readout_dims(B, R, n, n_trg, E);
+  if (rc) return rc;
+  if (ld_s < n || ld_trg < n_trg || ld_att < E || ld_out < R) return LSTM_ERR_DIM;
+  if ((((uintptr_t)s | (uintptr_t)trg | (uintptr_t)att | (uintptr_t)W_r | (uintptr_t)out) & 1) || ((uintptr_t)b_r & 3)) return LSTM_ERR_ALIGN;
   uint64_t need = 0;
-  lstm_readout_query(B, R, K, &need);
+  lstm_readout_query(B, R, n, n_trg, E, &need);
   if (workspace_bytes < need) return LSTM_ERR_SIZE;
   if (B == 0) return LSTM_OK;
-  int rc = device_ok();
-  if (rc) return rc;
+  if ((rc = device_ok())) return rc;
   hipStream_t st = (hipStream_t)stream;
+  const int K = n + n_trg + E;
+  const long Kp = readout_kpad(n, n_trg, E);
   char* ws = (char*)(((uintptr_t)workspace + 255) / 256 * 256);
-  float* z = (float*)ws;
-  float* parts = (float*)(ws + up256((size_t)B * R * 4));
-  if (linear_rows(x, ld_x, W_r, K, b_r, z, B, R, K, parts, ranges_for(B, R, K), st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  // workspace: W_r with its rows padded with zeros to whole 16-byte chunks (kept between calls under
+  // LSTM_FLAG_WEIGHTS_PACKED), the concatenated inputs padded the same way, the float product, the K ranges' parts
+  uint16_t* Wp = (uint16_t*)ws;
+  uint16_t* cat = (uint16_t*)(ws + up256((size_t)R * Kp * 2));
+  float* z = (float*)((char*)cat + up256((size_t)B * Kp * 2));
+  float* parts = (float*)((char*)z + up256((size_t)B * R * 4));
+  if (!(flags & LSTM_FLAG_WEIGHTS_PACKED) && launch_pad_rows(W_r, Wp, R, K, (int)Kp, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  const long total_cat = (long)B * Kp;
+  hipLaunchKernelGGL(concat3_kernel, dim3((unsigned)((total_cat + 255) / 256)), dim3(256), 0, st, (const uint16_t*)s, (long)ld_s, n,
+                     (const uint16_t*)trg, (long)ld_trg, n_trg, (const uint16_t*)att, (long)ld_att, E, cat, Kp, B);
+  if (linear_rows(cat, Kp, Wp, Kp, b_r, z, B, R, (int)Kp, parts, ranges_for(B, R, (int)Kp), st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
   const long total = (long)B * R;
   hipLaunchKernelGGL(relu_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, z, (uint16_t*)out, B, R, (long)ld_out);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;

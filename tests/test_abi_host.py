@@ -146,15 +146,16 @@ def test_attention_and_readout_argument_errors():
     assert step(small) == -6
     assert step(mk(Q=0)) == 0                                   # nothing to do, nothing launched
     # readout
-    rq = lambda B=4, R=8, K=16: Bn.lib.lstm_readout_query(B, R, K, ctypes.byref(q))
-    assert rq() == 0 and q.value > 0 and rq(B=-1) == -2 and rq(R=0) == -2 and rq(K=0) == -2
-    assert Bn.lib.lstm_readout_query(4, 8, 16, None) == -1
-    ro = lambda B=4, R=8, K=16, x=P, ld_x=16, W=P, b=None, out=P, ld_out=8, ws=P, wsb=1 << 30: Bn.lib.lstm_readout(B, R, K, x, ld_x, W, b, out, ld_out, ws, wsb, None)
-    assert ro(x=None) == -1 and ro(W=None) == -1 and ro(out=None) == -1 and ro(ws=None) == -1
-    assert ro(ld_x=15) == -2 and ro(ld_out=7) == -2 and ro(B=-1) == -2
-    assert ro(x=P + 1) == -5 and ro(b=P + 2) == -5
-    assert ro(wsb=8) == -6
-    assert ro(B=0) == 0
+    rq = lambda B=4, R=8, n=16, nt=4, E=6: Bn.lib.lstm_readout_query(B, R, n, nt, E, ctypes.byref(q))
+    assert rq() == 0 and q.value > 0 and rq(B=-1) == -2 and rq(R=0) == -2 and rq(n=0) == -2 and rq(nt=-1) == -2
+    assert Bn.lib.lstm_readout_query(4, 8, 16, 4, 6, None) == -1
+    ro = lambda fl=0, B=4, R=8, s=P, ld_s=16, n=16, trg=P, ld_trg=4, nt=4, att=P, ld_att=6, E=6, W=P, b=None, out=P, ld_out=8, ws=P, wsb=1 << 30: \
+        Bn.lib.lstm_readout(fl, B, R, s, ld_s, n, trg, ld_trg, nt, att, ld_att, E, W, b, out, ld_out, ws, wsb, None)
+    assert ro(s=None) == -1 and ro(trg=None) == -1 and ro(att=None) == -1 and ro(W=None) == -1 and ro(out=None) == -1 and ro(ws=None) == -1
+    assert ro(ld_s=15) == -2 and ro(ld_trg=3) == -2 and ro(ld_att=5) == -2 and ro(ld_out=7) == -2 and ro(B=-1) == -2
+    assert ro(s=P + 1) == -5 and ro(b=P + 2) == -5
+    assert ro(wsb=8) == -6 and ro(fl=3) == -4
+    assert ro(B=0) == 0 and ro(fl=8, B=0) == 0
 
 
 def test_strerror():

@@ -101,18 +101,20 @@ def test_readout_matches_oracle():
     inp = synth.make_decoder(Q=5, beam=12, len_lo=3, len_hi=9, A=8, E=2000, n=1000)
     f = lambda k: inp[k].astype(np.float64)
     att = np.asarray(torch.from_numpy(np.random.default_rng(1).uniform(-1, 1, (inp["B"], 2000))).to(torch.bfloat16).float())
-    x = np.concatenate([inp["s"], inp["trg"], att], axis=1)
-    out = Bn.readout(dev(x, "bf16"), dev(inp["W_r"], "bf16"), dev(inp["b_r"]))
+    # trg and att as the two halves of the cell's input rows (row stride 2620), s by itself
+    xin = dev(np.concatenate([inp["trg"], att], axis=1), "bf16")
+    out = Bn.readout(dev(inp["s"], "bf16"), xin[:, :620], xin[:, 620:], dev(inp["W_r"], "bf16"), dev(inp["b_r"]))
     torch.cuda.synchronize()
     ref = D.readout(f("s"), f("trg"), att.astype(np.float64), f("W_r").T, f("b_r"))
     check("readout", out, ref, TOL_BF16)
     assert (out == 0).any() and (out > 0).any()
-    # a small, ragged shape through the same entry point
+    # a small, ragged shape through the same entry point (K = 5 + 3 + 7: not a multiple of 8)
     rng = np.random.default_rng(2)
     bfr = lambda a: torch.from_numpy(a).to(torch.bfloat16).float().numpy()
-    x2, W2, b2 = bfr(rng.standard_normal((7, 30))), bfr(rng.standard_normal((9, 30))), rng.standard_normal(9).astype(np.float32)
-    out2 = Bn.readout(dev(x2, "bf16"), dev(W2, "bf16"), dev(b2))
-    check("readout small", out2, np.maximum(x2.astype(np.float64) @ W2.astype(np.float64).T + b2, 0), TOL_BF16)
+    s2, t2, a2 = bfr(rng.standard_normal((7, 5))), bfr(rng.standard_normal((7, 3))), bfr(rng.standard_normal((7, 7)))
+    W2, b2 = bfr(rng.standard_normal((9, 15))), rng.standard_normal(9).astype(np.float32)
+    out2 = Bn.readout(dev(s2, "bf16"), dev(t2, "bf16"), dev(a2, "bf16"), dev(W2, "bf16"), dev(b2))
+    check("readout small", out2, D.readout(s2, t2, a2, W2.astype(np.float64).T, b2.astype(np.float64)), TOL_BF16)
 
 
 def test_hoisted_enc_ctx_through_lstm_gemm():
