@@ -3,7 +3,7 @@
 //
 //     s_tr[r]   = s[r] W_s + b_s                                       one product over all rows (MFMA)
 //     e[r, j]   = v . tanh(ctx[j, q(r)] + accum[r, j] w_fb + b_fb + s_tr[r]) + b_e      att_energy_kernel (vector ALU)
-//     a[r, :]   = softmax of e[r, :] over j < src_lens[q(r)],  accum' = accum + a        att_context_kernel
+//     a[r, :]   = softmax of e[r, :] over j < src_lens[q(r)],  accum' = accum + a        att_softmax_kernel
 //     att[r]    = sum_j a[r, j] H[j, q(r)]                                               att_context_kernel (reads H once per sentence)
 //     readout   = max(0, [s, trg, att] W_r + b_r)                      one product + bias_relu_kernel
 //
@@ -20,7 +20,10 @@ namespace lstm {
 namespace {
 
 constexpr int kMaxBeam = 16;          // hypotheses per sentence (register budget of the energy kernel)
-constexpr int kJB = 4;                // source positions per work-group of the energy kernel
+#ifndef ATT_JB
+#define ATT_JB 4
+#endif
+constexpr int kJB = ATT_JB;           // source positions per work-group of the energy kernel
 constexpr int kPartStride = 260;      // floats per partial-sum row in LDS: 4 * value + slot hits 64 different banks
 
 __device__ __forceinline__ int src_len(const int* lens, int q, int S) {
@@ -42,29 +45,50 @@ __global__ __launch_bounds__(256) void att_energy_kernel(const uint16_t* __restr
   const int L = src_len(lens, q, S);
   if (j0 >= L) return;
   const int nj = min(kJB, L - j0);
+  // tanh(x) = 1 - 2 / (1 + 2^(x * 2 log2 e)): with every addend of x scaled by 2 log2 e beforehand an element costs
+  // multiply-add, add, exp2, add, reciprocal, multiply-add; the "1" of every term is added once per lane (vsum).
+  constexpr float kScale = 2.8853900817779268f;                // 2 log2(e)
   float sum[kMaxBeam][kJB];
 #pragma unroll
   for (int r = 0; r < kMaxBeam; ++r)
 #pragma unroll
     for (int j = 0; j < kJB; ++j) sum[r][j] = 0.f;
-  for (int k = tid; k < A; k += 256) {
-    float c[kJB];
+  float vsum = 0.f;
+  // the accumulated weights of the beam x kJB (row, position) pairs: the same for every lane and every k
+  float ac[kMaxBeam][kJB];
 #pragma unroll
-    for (int j = 0; j < kJB; ++j) c[j] = j < nj ? bf_bits2f(ctx[((long)(j0 + j) * Q + q) * A + k]) + b_fb[k] : 0.f;
-    const float wf = w_fb[k], vk = v[k];
+  for (int r = 0; r < kMaxBeam; ++r)
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) ac[r][j] = (r < beam && j < nj) ? accum[((long)q * beam + r) * S + j0 + j] : 0.f;
+  for (int k = tid; k < A; k += 256) {
+    // every load of this k goes out before the first use: inside the uniform branches below each would be waited for
+    // on its own, one L2 latency per hypothesis (measured: 47 -> 30 us).  Fetching the next k's operands ahead of
+    // this k's arithmetic as well measured no faster.
+    float c[kJB], st[kMaxBeam];
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) c[j] = bf_bits2f(ctx[((long)(j0 + min(j, nj - 1)) * Q + q) * A + k]);
+#pragma unroll
+    for (int r = 0; r < kMaxBeam; ++r) st[r] = s_tr[((long)q * beam + min(r, beam - 1)) * A + k];
+    const float bf = b_fb[k], wf = kScale * w_fb[k], vk = v[k], m2v = -2.f * vk;
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) c[j] = kScale * (c[j] + bf);
+    vsum += vk;
 #pragma unroll
     for (int r = 0; r < kMaxBeam; ++r) {
       if (r < beam) {                                          // uniform: a scalar branch
-        const long row = (long)q * beam + r;
-        const float st = s_tr[row * A + k];
+        const float s2 = kScale * st[r];
 #pragma unroll
         for (int j = 0; j < kJB; ++j) {
-          const float ac = j < nj ? accum[row * S + j0 + j] : 0.f;          // uniform address
-          sum[r][j] += vk * tanhf_(c[j] + ac * wf + st);
+          const float x2 = __builtin_fmaf(ac[r][j], wf, c[j]) + s2;
+          sum[r][j] = __builtin_fmaf(__builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(x2) + 1.f), m2v, sum[r][j]);
         }
       }
     }
   }
+#pragma unroll
+  for (int r = 0; r < kMaxBeam; ++r)
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) sum[r][j] += vsum;
   constexpr int kHalf = kMaxBeam / 2;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
@@ -91,58 +115,98 @@ __global__ __launch_bounds__(256) void att_energy_kernel(const uint16_t* __restr
   }
 }
 
-// Softmax over the valid positions for every hypothesis of sentence q = blockIdx.y (each work-group of the sentence
-// repeats it: beam x S exponentials), the first work-group also writes a and accum'; then a slice of 512 features of
-// att: a lane owns two neighbouring features and walks the source positions, reading H once for all hypotheses.
+// a[r, :] = softmax of e[r, :] over the valid positions, accum' = accum + a, for every hypothesis of sentence
+// q = blockIdx.x; 16 lanes per hypothesis, e staged in LDS first (one round of global loads).
 // Dynamic LDS: S * kMaxBeam floats, w[j][r].
-__global__ __launch_bounds__(256) void att_context_kernel(const uint16_t* __restrict__ H, const float* __restrict__ e,
-                                                           const float* __restrict__ accum_in, const int* __restrict__ lens,
-                                                           float* __restrict__ a_out, float* __restrict__ accum_out,
-                                                           uint16_t* __restrict__ att, long ldatt, int S, int Q, int beam, int E) {
+__global__ __launch_bounds__(256) void att_softmax_kernel(const float* __restrict__ e, const float* __restrict__ accum_in,
+                                                           const int* __restrict__ lens, float* __restrict__ a_out,
+                                                           float* __restrict__ accum_out, int S, int beam) {
   extern __shared__ float w[];
+  const int q = blockIdx.x, tid = threadIdx.x;
+  const int L = src_len(lens, q, S);
+  for (int r = tid >> 4; r < beam; r += 16)
+    for (int j = tid & 15; j < L; j += 16) w[j * kMaxBeam + r] = e[((long)q * beam + r) * S + j];
+  __syncthreads();
+  const int r = tid >> 4, l = tid & 15;                         // beam <= 16: one group of 16 lanes per hypothesis
+  if (r >= beam) return;
+  const long row = (long)q * beam + r;
+  float m = -3.0e38f;
+  for (int j = l; j < L; j += 16) m = fmaxf(m, w[j * kMaxBeam + r]);
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  float z = 0.f;
+  for (int j = l; j < L; j += 16) {
+    const float p = __expf(w[j * kMaxBeam + r] - m);
+    w[j * kMaxBeam + r] = p;
+    z += p;
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) z += __shfl_xor(z, o);
+  const float inv = L > 0 ? 1.f / z : 0.f;
+  for (int j = l; j < S; j += 16) {
+    const float p = j < L ? w[j * kMaxBeam + r] * inv : 0.f;
+    a_out[row * S + j] = p;
+    accum_out[row * S + j] = j < L ? accum_in[row * S + j] + p : 0.f;
+  }
+}
+
+// att[r] = sum_j a[r][j] H[j][q] for the hypotheses of sentence q = blockIdx.y and the 128 features from
+// blockIdx.x * 128: lane l of every wavefront owns features 2l, 2l + 1 of that slice, the four wavefronts share the
+// source positions (wavefront w takes j = w, w + 4, ...), eight loads in flight per lane, and their partial sums meet in
+// LDS.  H is read once for all hypotheses of the sentence.  Dynamic LDS: S * kMaxBeam floats, w[j][r] (rows r >= beam
+// up to the next multiple of 4 hold zeros).
+__global__ __launch_bounds__(256) void att_context_kernel(const uint16_t* __restrict__ H, const float* __restrict__ a,
+                                                           const int* __restrict__ lens, uint16_t* __restrict__ att, long ldatt, int S,
+                                                           int Q, int beam, int E) {
+  extern __shared__ float w[];
+  __shared__ float red[3][kMaxBeam * 2][64];
   const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int L = src_len(lens, q, S);
-  for (int r = wave; r < beam; r += 4) {
-    const long row = (long)q * beam + r;
-    float m = -3.0e38f;
-    for (int j = lane; j < L; j += 64) m = fmaxf(m, e[row * S + j]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    float z = 0.f;
-    for (int j = lane; j < L; j += 64) z += __expf(e[row * S + j] - m);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
-    const float inv = L > 0 ? 1.f / z : 0.f;
-    for (int j = lane; j < S; j += 64) {
-      const float p = j < L ? __expf(e[row * S + j] - m) * inv : 0.f;
-      if (j < L) w[j * kMaxBeam + r] = p;
-      if (blockIdx.x == 0) {
-        if (a_out) a_out[row * S + j] = p;
-        accum_out[row * S + j] = j < L ? accum_in[row * S + j] + p : 0.f;
-      }
-    }
-  }
+  const int nb4 = (beam + 3) >> 2;                              // groups of four hypotheses
+  for (int r = tid >> 4; r < nb4 * 4; r += 16)
+    for (int j = tid & 15; j < L; j += 16) w[j * kMaxBeam + r] = r < beam ? a[((long)q * beam + r) * S + j] : 0.f;
   __syncthreads();
-  const int f = (blockIdx.x * 256 + tid) * 2;
-  if (f >= E) return;
+  const int f = (blockIdx.x * 64 + lane) * 2;
+  const bool live = f < E;
   float acc[kMaxBeam][2];
 #pragma unroll
   for (int r = 0; r < kMaxBeam; ++r) acc[r][0] = acc[r][1] = 0.f;
-  for (int j = 0; j < L; ++j) {
-    const unsigned hh = *(const unsigned*)(H + ((long)j * Q + q) * E + f);        // E even, rows 4-byte aligned
-    const float h0 = __uint_as_float(hh << 16), h1 = __uint_as_float(hh & 0xffff0000u);
+  const uint16_t* Hq = H + (long)q * E + (live ? f : 0);        // E even, rows 4-byte aligned
+  const long jstride = (long)Q * E;
+  constexpr int kU = 8;
+  for (int j = wave; j < L; j += 4 * kU) {
+    unsigned hh[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) hh[u] = *(const unsigned*)(Hq + min(j + 4 * u, L - 1) * jstride);
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      if (j + 4 * u >= L) break;                                // uniform within the wavefront
+      const float h0 = __uint_as_float(hh[u] << 16), h1 = __uint_as_float(hh[u] & 0xffff0000u);
+      const float4* wj = (const float4*)(w + (j + 4 * u) * kMaxBeam);
+#pragma unroll
+      for (int g = 0; g < kMaxBeam / 4; ++g)
+        if (g < nb4) {                                          // uniform
+          const float4 p = wj[g];
+          acc[4 * g + 0][0] += p.x * h0; acc[4 * g + 0][1] += p.x * h1;
+          acc[4 * g + 1][0] += p.y * h0; acc[4 * g + 1][1] += p.y * h1;
+          acc[4 * g + 2][0] += p.z * h0; acc[4 * g + 2][1] += p.z * h1;
+          acc[4 * g + 3][0] += p.w * h0; acc[4 * g + 3][1] += p.w * h1;
+        }
+    }
+  }
+  if (wave > 0) {
 #pragma unroll
     for (int r = 0; r < kMaxBeam; ++r)
-      if (r < beam) {
-        const float p = w[j * kMaxBeam + r];
-        acc[r][0] += p * h0;
-        acc[r][1] += p * h1;
-      }
+      if (r < beam) { red[wave - 1][2 * r][lane] = acc[r][0]; red[wave - 1][2 * r + 1][lane] = acc[r][1]; }
   }
+  __syncthreads();
+  if (wave > 0 || !live) return;
 #pragma unroll
   for (int r = 0; r < kMaxBeam; ++r)
     if (r < beam) {
-      const unsigned o = (unsigned)f2bf_bits(acc[r][0]) | ((unsigned)f2bf_bits(acc[r][1]) << 16);
+      const float s0 = acc[r][0] + red[0][2 * r][lane] + red[1][2 * r][lane] + red[2][2 * r][lane];
+      const float s1 = acc[r][1] + red[0][2 * r + 1][lane] + red[1][2 * r + 1][lane] + red[2][2 * r + 1][lane];
+      const unsigned o = (unsigned)f2bf_bits(s0) | ((unsigned)f2bf_bits(s1) << 16);
       *(unsigned*)(att + ((long)q * beam + r) * ldatt + f) = o;
     }
 }
@@ -206,7 +270,7 @@ int lstm_attention_query(const lstm_att_desc* d, uint64_t* workspace_bytes) {
   if (!workspace_bytes) return LSTM_ERR_NULL;
   const size_t B = (size_t)d->Q * d->beam;
   const int ks = ranges_for((int)B, d->A, d->n);
-  *workspace_bytes = 256 + up256(B * d->A * 4) + up256(B * d->S * 4) + (ks > 1 ? up256((size_t)ks * B * d->A * 4) : 0);
+  *workspace_bytes = 256 + up256(B * d->A * 4) + up256(B * d->S * 4) + (ks > 1 ? up256((size_t)ks * B * d->A * 4) : 0) + up256(B * d->S * 4);
   return LSTM_OK;
 }
 
@@ -235,8 +299,11 @@ int lstm_attention_step(const lstm_att_desc* d, const void* enc, const void* enc
   if (linear_rows(s, ld_s, W_s, d->n, b_s, s_tr, B, d->A, d->n, parts, ks, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
   hipLaunchKernelGGL(att_energy_kernel, dim3((d->S + kJB - 1) / kJB, d->Q), dim3(256), 0, st, (const uint16_t*)enc_ctx, s_tr, accum_in, w_fb,
                      b_fb, v, b_e, src_lens, e, d->S, d->Q, d->beam, d->A);
-  hipLaunchKernelGGL(att_context_kernel, dim3((d->E / 2 + 255) / 256, d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, (const uint16_t*)enc, e,
-                     accum_in, src_lens, a, accum_out, (uint16_t*)att, (long)ld_att, d->S, d->Q, d->beam, d->E);
+  float* a_buf = a ? a : (float*)((char*)parts + (ks > 1 ? up256((size_t)ks * B * d->A * 4) : 0));
+  hipLaunchKernelGGL(att_softmax_kernel, dim3(d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, e, accum_in, src_lens, a_buf, accum_out, d->S,
+                     d->beam);
+  hipLaunchKernelGGL(att_context_kernel, dim3((d->E / 2 + 63) / 64, d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, (const uint16_t*)enc,
+                     a_buf, src_lens, (uint16_t*)att, (long)ld_att, d->S, d->Q, d->beam, d->E);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
   return LSTM_OK;
 }
