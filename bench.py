@@ -377,7 +377,8 @@ def bench_decoder_attention(args, Bn, synth):
         "roofline": {"bound": "alu", "kernel": "att_energy_kernel (inside the attention call, which also runs the s_tr product and "
                                                "att_context_kernel)", "achieved": alu_flops / (part[1] * 1e-6) / 1e12, "peak": 157.3,
                      "unit": "TFLOP/s", "frac": alu_flops / (part[1] * 1e-6) / 1e12 / 157.3, "traffic": None,
-                     "note": "achieved = energy flops / time of the whole attention call; see profiles/ for the kernel alone"},
+                     "note": "achieved = energy flops / time of the whole attention call (s_tr product, energies, softmax, context); "
+                             "the kernel alone: profiles/bench_config8_kernel_trace.txt"},
     }
     print(json.dumps(out))
 
