@@ -470,6 +470,12 @@ def bench_pooled(args, Bn, synth):
     frames = synth.real_frames(inp)
     x, lens, dy, layers = build_stack(inp, Bn)
     st = PooledStack(Bn, x, lens, dy, layers)
+    if args.copy_calibration:                       # a plain copy of known size, for scaling the HBM byte counters
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         st.step()
     torch.cuda.synchronize()
@@ -493,6 +499,12 @@ def bench_pooled(args, Bn, synth):
         by["fwd"] += args.steps * (fin * F * esz + fout * F * (esz + 1))
         by["bwd"] += args.steps * (fout * F * (esz + 1) + bf["T"] * B * F * esz)
     tot_ms, tot_by = ms["fwd"] + ms["bwd"], by["fwd"] + by["bwd"]
+    traffic = None
+    try:   # HBM bytes of the six pooling launches of one step, measured with rocprofv3 --pmc (see profiles/)
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as fh:
+            traffic = json.load(fh).get("config6_pool_bytes_per_step")
+    except (OSError, ValueError):
+        pass
     gbs = tot_by / (tot_ms * 1e-3) / 1e9 if tot_ms > 0 else 0.0
     out = {
         "metric": "BLSTM fwd+bwd frames/sec (n=%d), encoder with time pooling" % n, "value": frames * args.steps / dt, "unit": "frames/s",
@@ -502,7 +514,7 @@ def bench_pooled(args, Bn, synth):
                                "in time, windows of 2 frames, behind layers 1, 2 and 3; frames per layer %s; forward + backward" % (
                                    n, B, inp["T"], frames, st.frames_per_layer)},
         "roofline": {"bound": "hbm", "kernel": "time_pool_fwd_kernel + time_pool_bwd_kernel (three of each per step)", "achieved": gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "ms_per_step": tot_ms / args.steps, "algorithmic_bytes_per_step": tot_by / args.steps},
     }
     print(json.dumps(out))
