@@ -175,3 +175,62 @@ def test_enc_ctx_and_readout():
     # rows of W_r are ordered s | trg | att: zeroing the att rows removes att's influence
     W0 = W_r.copy(); W0[5:] = 0
     np.testing.assert_array_equal(D.readout(s, trg, att, W0, b_r), D.readout(s, trg, att * 3 + 1, W0, b_r))
+
+
+# ---- beam-search step ----------------------------------------------------------------------------------------------
+def test_beam_hand_worked_example():
+    want = np.loadtxt(os.path.join(HERE, "golden", "beam_case.txt"))
+    sc, src, lab = D.beam_step(np.log([[1.0, 2.0, 5.0], [1.0, 1.0, 1.0]]), np.log([[0.5, 0.25]]), 2)
+    np.testing.assert_allclose(np.exp(sc[0]), want[:2], rtol=1e-14)
+    assert src[0].tolist() == want[2:4].tolist() and lab[0].tolist() == want[4:6].tolist()
+
+
+def test_beam_brute_force_and_invariants():
+    rng = np.random.default_rng(12)
+    Q, beam, V = 3, 4, 9
+    logits = rng.standard_normal((Q * beam, V)) * 2
+    score = -rng.uniform(0, 5, (Q, beam))
+    sc, src, lab = D.beam_step(logits, score, beam)
+    for q in range(Q):
+        cands = []
+        for b in range(beam):
+            row = logits[q * beam + b]
+            lse = math.log(sum(math.exp(x) for x in row))
+            cands += [(-(score[q, b] + x - lse), b * V + v) for v, x in enumerate(row)]
+        cands.sort()
+        for k in range(beam):
+            assert abs(-cands[k][0] - sc[q, k]) < 1e-12 and cands[k][1] == src[q, k] * V + lab[q, k]
+    assert np.all(np.diff(sc, axis=1) <= 0)                                           # best first
+    sc2, src2, lab2 = D.beam_step(logits + rng.standard_normal((Q * beam, 1)) * 10, score, beam)   # softmax ignores a row shift
+    np.testing.assert_allclose(sc2, sc, rtol=1e-12, atol=1e-12)
+    assert np.array_equal(src2, src) and np.array_equal(lab2, lab)
+    np.testing.assert_allclose(np.exp(D.log_softmax_rows(logits)).sum(axis=1), 1.0, rtol=1e-13)
+
+
+def test_beam_ties_first_step_and_torch_topk():
+    # uniform logits: every label has log-probability -log V; the best hypotheses win, labels ascending on ties
+    sc, src, lab = D.beam_step(np.zeros((3, 5)), np.array([[-1.0, -0.5, -2.0]]), 3)
+    np.testing.assert_allclose(sc[0], -0.5 - math.log(5), rtol=1e-14)
+    assert src[0].tolist() == [1, 1, 1] and lab[0].tolist() == [0, 1, 2]
+    # first step of a search: only hypothesis 0 is alive
+    rng = np.random.default_rng(13)
+    logits = rng.standard_normal((4, 7))
+    sc, src, lab = D.beam_step(logits, np.array([[0.0, -np.inf, -np.inf, -np.inf]]), 4)
+    assert src[0].tolist() == [0, 0, 0, 0] and lab[0].tolist() == np.argsort(-logits[0], kind="stable")[:4].tolist()
+    # torch.log_softmax + torch.topk on tie-free data
+    Q, beam, V = 5, 6, 50
+    logits = rng.standard_normal((Q * beam, V)) * 3
+    score = -rng.uniform(0, 3, (Q, beam))
+    sc, src, lab = D.beam_step(logits, score, beam)
+    cand = torch.from_numpy(score)[:, :, None] + torch.log_softmax(torch.from_numpy(logits), dim=1).view(Q, beam, V)
+    top = torch.topk(cand.view(Q, -1), beam, dim=1)
+    np.testing.assert_allclose(sc, top.values.numpy(), rtol=1e-12)
+    assert np.array_equal(src * V + lab, top.indices.numpy())
+
+
+def test_gather_rows_and_embed():
+    st = np.arange(6 * 2).reshape(6, 2)
+    src = np.array([[2, 0, 0], [1, 1, 2]])
+    assert D.gather_rows(st, src, 3)[:, 0].tolist() == [4, 0, 0, 8, 8, 10]
+    W, b = np.arange(12.0).reshape(4, 3), np.array([0.5, 0.5, 0.5])
+    np.testing.assert_array_equal(D.embed(np.array([[3, 0]]), W, b), np.array([[9.5, 10.5, 11.5], [0.5, 1.5, 2.5]]))
