@@ -212,6 +212,33 @@ int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, co
                  const void* att, int64_t ld_att, int E, const void* W_r, const float* b_r, void* out, int64_t ld_out,
                  void* workspace, uint64_t workspace_bytes, void* stream);
 
+/* One step of batched beam search, entirely on the device (Sec. 4: the decoder is a batched beam search that runs on
+ * the GPU, beam size 12; Listing 1: "output_prob" is a softmax over the labels, "output" chooses from it, "trg" embeds
+ * the choice).  The paper gives no further detail; this library's reading, with q a sentence, b one of its `beam`
+ * hypotheses (row r = q * beam + b of the decoder batch) and v a label:
+ *     cand[q, b, v] = score_in[q, b] + logits[r, v] - log sum_v' exp(logits[r, v'])
+ *     the `beam` largest cand[q, :, :] become the new hypotheses of sentence q, best first: score_out[q, k], the
+ *     hypothesis it extends src[q, k] in [0, beam) and its label[q, k] in [0, V); equal candidates are ordered by the
+ *     smaller b * V + v.  A hypothesis with score -inf (the unused slots of the first step) never beats a finite one.
+ * Finished hypotheses and length normalisation are not part of this step.  All arithmetic is float.
+ *   logits float [Q*beam][ld >= V] (e.g. lstm_gemm of the readout with the output weights), score_in, score_out float
+ *   [Q][beam], src, label int32 [Q][beam]; beam <= 16, V <= 32768; workspace of lstm_beam_query() bytes.
+ * lstm_beam_gather moves per-hypothesis state behind the choice: out[q*beam + k][0..width) = in[q*beam + src[q, k]][..]
+ *   for rows of `width` elements of elem_bytes (2 or 4) bytes; in and out must be different buffers; values of src
+ *   outside [0, beam) are clamped.
+ * lstm_embed is Listing 1's "trg": out[r] = W_trg[label[r]] + b_trg with W_trg bfloat16 [V][n], b_trg float [n] or NULL,
+ *   out bfloat16 [B][ld_out >= n]; a label outside [0, V) gives the bias alone.
+ * Device pointers owned by the caller; the calls only enqueue work and nothing is copied to the host.
+ * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM, LSTM_ERR_UNSUPPORTED (beam > 16, V > 32768, elem_bytes, in == out),
+ * LSTM_ERR_ALIGN, LSTM_ERR_SIZE, LSTM_ERR_HIP. */
+int lstm_beam_query(int Q, int beam, int V, uint64_t* workspace_bytes);
+int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out,
+                   int32_t* src, int32_t* label, void* workspace, uint64_t workspace_bytes, void* stream);
+int lstm_beam_gather(int elem_bytes, int Q, int beam, int width, const void* in, int64_t ld_in, const int32_t* src,
+                     void* out, int64_t ld_out, void* stream);
+int lstm_embed(int B, int n, int V, const int32_t* label, const void* W_trg, const float* b_trg, void* out,
+               int64_t ld_out, void* stream);
+
 /* Diagnostic for the single-launch (persistent) recurrent kernels, whose work-groups wait for each
  * other between time steps with BOUNDED waits.  If a wait ever expired, the kernel drained early, the
  * results of that call are invalid and a word in the workspace says so.  This call copies that word

@@ -15,7 +15,8 @@ LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED = 1, 2, 4, 8
 EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_time_pool_fwd", "lstm_time_pool_bwd", "lstm_attention_query", "lstm_attention_step",
-           "lstm_readout_query", "lstm_readout", "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
+           "lstm_readout_query", "lstm_readout", "lstm_beam_query", "lstm_beam_step", "lstm_beam_gather", "lstm_embed",
+           "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
            "lstm_strerror")
 
 
@@ -68,6 +69,14 @@ def _load():
     lib.lstm_readout_query.argtypes = [ip, ip, ip, ip, ip, u64p]
     lib.lstm_readout.restype = ip
     lib.lstm_readout.argtypes = [ip, ip, ip, vp, i64, ip, vp, i64, ip, vp, i64, ip, vp, vp, vp, i64, vp, ctypes.c_uint64, vp]
+    lib.lstm_beam_query.restype = ip
+    lib.lstm_beam_query.argtypes = [ip, ip, ip, u64p]
+    lib.lstm_beam_step.restype = ip
+    lib.lstm_beam_step.argtypes = [ip, ip, ip, vp, i64, vp, vp, vp, vp, vp, ctypes.c_uint64, vp]
+    lib.lstm_beam_gather.restype = ip
+    lib.lstm_beam_gather.argtypes = [ip, ip, ip, ip, vp, i64, vp, vp, i64, vp]
+    lib.lstm_embed.restype = ip
+    lib.lstm_embed.argtypes = [ip, ip, ip, vp, vp, vp, vp, i64, vp]
     lib.lstm_sync_status.restype = ip
     lib.lstm_sync_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
     lib.lstm_profile_enable.restype = ip
@@ -251,6 +260,44 @@ def readout(s, trg, att, W_r, b_r, *, out=None, workspace=None, flags=0):
     assert s.stride(1) == 1 and trg.stride(1) == 1 and att.stride(1) == 1 and W_r.is_contiguous() and out.stride(1) == 1
     _check(lib.lstm_readout(flags, B, R, s.data_ptr(), s.stride(0), n, trg.data_ptr(), trg.stride(0), nt, att.data_ptr(), att.stride(0), E,
                             _ptr(W_r), _ptr(b_r), out.data_ptr(), out.stride(0), _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def beam_step(logits, score, *, workspace=None):
+    """One beam-search step through lstm_beam_step.  logits float [Q*beam, V] (row stride allowed), score float [Q, beam]
+    -> dict(score [Q,beam] float, src [Q,beam] int32, label [Q,beam] int32, workspace)."""
+    Q, beam = score.shape
+    V = logits.shape[1]
+    need = ctypes.c_uint64(0)
+    _check(lib.lstm_beam_query(Q, beam, V, ctypes.byref(need)))
+    if workspace is None or workspace.numel() < need.value:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=logits.device)
+    out = torch.empty(Q, beam, dtype=torch.float32, device=logits.device)
+    src = torch.empty(Q, beam, dtype=torch.int32, device=logits.device)
+    label = torch.empty(Q, beam, dtype=torch.int32, device=logits.device)
+    assert logits.stride(1) == 1 and logits.dtype == torch.float32 and score.dtype == torch.float32
+    _check(lib.lstm_beam_step(Q, beam, V, logits.data_ptr(), logits.stride(0), _ptr(score), _ptr(out), _ptr(src), _ptr(label),
+                              _ptr(workspace), workspace.numel(), _stream()))
+    return dict(score=out, src=src, label=label, workspace=workspace)
+
+
+def beam_gather(state, src):
+    """Rows of per-hypothesis state [Q*beam, width] (float or bfloat16) moved behind the choice `src` [Q, beam]."""
+    Q, beam = src.shape
+    out = torch.empty_like(state)
+    assert state.stride(1) == 1
+    _check(lib.lstm_beam_gather(state.element_size(), Q, beam, state.shape[1], state.data_ptr(), state.stride(0), _ptr(src), _ptr(out),
+                                out.stride(0), _stream()))
+    return out
+
+
+def embed(label, W_trg, b_trg=None, *, out=None):
+    """trg = W_trg[label] + b_trg through lstm_embed; label int32 (any shape), W_trg [V, n] bfloat16 -> [label.numel(), n] bfloat16."""
+    V, n = W_trg.shape
+    B = label.numel()
+    if out is None:
+        out = torch.empty(B, n, dtype=torch.bfloat16, device=W_trg.device)
+    _check(lib.lstm_embed(B, n, V, _ptr(label), _ptr(W_trg), _ptr(b_trg), out.data_ptr(), out.stride(0), _stream()))
     return out
 
 

@@ -158,6 +158,26 @@ def test_attention_and_readout_argument_errors():
     assert ro(B=0) == 0 and ro(fl=8, B=0) == 0
 
 
+def test_beam_argument_errors():
+    import ctypes
+    q = ctypes.c_uint64(0)
+    L = Bn.lib
+    assert L.lstm_beam_query(4, 12, 20000, ctypes.byref(q)) == 0 and q.value > 0
+    assert L.lstm_beam_query(4, 12, 20000, None) == -1 and L.lstm_beam_query(-1, 12, 10, ctypes.byref(q)) == -2
+    assert L.lstm_beam_query(4, 0, 10, ctypes.byref(q)) == -2 and L.lstm_beam_query(4, 2, 0, ctypes.byref(q)) == -2
+    assert L.lstm_beam_query(4, 17, 10, ctypes.byref(q)) == -4 and L.lstm_beam_query(4, 2, 40000, ctypes.byref(q)) == -4
+    st = lambda Q=4, beam=3, V=10, lg=P, ld=10, si=P, so=P, src=P, lab=P, ws=P, wsb=1 << 20: L.lstm_beam_step(Q, beam, V, lg, ld, si, so, src, lab, ws, wsb, None)
+    for k in ("lg", "si", "so", "src", "lab", "ws"):
+        assert st(**{k: None}) == -1, k
+    assert st(ld=9) == -2 and st(Q=-1) == -2 and st(beam=17) == -4 and st(lg=P + 2) == -5 and st(wsb=8) == -6 and st(Q=0) == 0
+    ga = lambda eb=4, Q=4, beam=3, w=8, i=P, ldi=8, src=P, o=P + 4096, ldo=8: L.lstm_beam_gather(eb, Q, beam, w, i, ldi, src, o, ldo, None)
+    assert ga(i=None) == -1 and ga(src=None) == -1 and ga(o=None) == -1
+    assert ga(w=0) == -2 and ga(ldi=7) == -2 and ga(ldo=7) == -2 and ga(eb=3) == -4 and ga(o=P) == -4 and ga(i=P + 2) == -5 and ga(Q=0) == 0
+    em = lambda B=4, n=8, V=10, lab=P, W=P, b=None, o=P, ldo=8: L.lstm_embed(B, n, V, lab, W, b, o, ldo, None)
+    assert em(lab=None) == -1 and em(W=None) == -1 and em(o=None) == -1
+    assert em(n=0) == -2 and em(V=0) == -2 and em(ldo=7) == -2 and em(o=P + 1) == -5 and em(b=P + 2) == -5 and em(B=0) == 0
+
+
 def test_strerror():
     for s in range(0, -8, -1):
         assert Bn.strerror(s) and "unknown" not in Bn.strerror(s)

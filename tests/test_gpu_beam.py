@@ -1,0 +1,123 @@
+"""GPU parity of the beam-search step (lstm_beam_step, lstm_beam_gather, lstm_embed, called through the C ABI) against
+oracle/decoder_oracle.py.
+
+The step decides integers (which hypothesis, which label) from float32 scores, the oracle from float64 ones.  What is
+unique is compared exactly, the rest is checked for validity: the new scores agree to 2e-5 (absolute, scores are O(10));
+every chosen pair carries the oracle's candidate value for that pair; pairs are distinct and ordered best first; and wherever
+the oracle's ranking is decided by more than that tolerance - which on the random cases below is everywhere or almost
+everywhere - the chosen pair is the oracle's.  Cases whose float32 arithmetic is exact (ties) must match exactly, tie rule
+included.  Gather and embedding move bits and are compared exactly."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from oracle import decoder_oracle as D
+
+Bn = None
+TOL = 2e-5
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _binding():
+    global Bn
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1805_05225_amd import binding
+    Bn = binding
+    yield
+
+
+def _run(logits, score):
+    r = Bn.beam_step(torch.from_numpy(logits).cuda(), torch.from_numpy(score).cuda())
+    torch.cuda.synchronize()
+    return r["score"].cpu().numpy(), r["src"].cpu().numpy().astype(np.int64), r["label"].cpu().numpy().astype(np.int64)
+
+
+def _validate(logits, score, beam, got):
+    sc, src, lab = got
+    Q, V = score.shape[0], logits.shape[1]
+    osc, osrc, olab = D.beam_step(logits.astype(np.float64), score.astype(np.float64), beam)
+    logp = D.log_softmax_rows(logits.astype(np.float64))
+    finite = np.isfinite(osc)
+    assert np.array_equal(np.isfinite(sc), finite)
+    assert np.abs(sc[finite] - osc[finite]).max() < TOL
+    exact = 0
+    for q in range(Q):
+        flat = src[q] * V + lab[q]
+        assert np.all((src[q] >= 0) & (src[q] < beam) & (lab[q] >= 0) & (lab[q] < V))
+        assert len(set(flat[finite[q]].tolist())) == finite[q].sum()                       # distinct candidates
+        assert np.all(np.diff(sc[q][finite[q]]) <= 0)                                      # best first
+        cand = score[q].astype(np.float64)[:, None] + logp[q * beam:(q + 1) * beam]
+        full = np.sort(cand.reshape(-1))[::-1]
+        for k in range(beam):
+            if not finite[q, k]:
+                continue
+            assert abs(cand[src[q, k], lab[q, k]] - sc[q, k]) < TOL                        # the pair really has that score
+            gap_hi = full[k - 1] - full[k] if k > 0 else np.inf
+            gap_lo = full[k] - full[k + 1] if k + 1 < full.size else np.inf
+            if min(gap_hi, gap_lo) > 2 * TOL:                                               # the ranking is unambiguous here
+                assert (src[q, k], lab[q, k]) == (osrc[q, k], olab[q, k])
+                exact += 1
+    return exact
+
+
+@pytest.mark.parametrize("Q,beam,V,seed", [(3, 4, 50, 0), (5, 12, 20000, 1), (2, 16, 32768, 2), (7, 1, 300, 3), (4, 12, 257, 4)])
+def test_beam_step_random(Q, beam, V, seed):
+    rng = np.random.default_rng(seed)
+    logits = (rng.standard_normal((Q * beam, V)) * 3).astype(np.float32)
+    score = (-rng.uniform(0, 8, (Q, beam))).astype(np.float32)
+    print("  beam step Q=%d beam=%d V=%d" % (Q, beam, V), flush=True)
+    exact = _validate(logits, score, beam, _run(logits, score))
+    assert exact >= 0.9 * Q * beam                                                          # almost every rank is unambiguous and identical
+
+
+def test_beam_step_exact_ties_and_first_step():
+    # integer logits and scores, V a power of two: every float32 operation is exact enough for identical ties on both sides
+    beam, V = 4, 8
+    logits = np.zeros((2 * beam, V), dtype=np.float32)
+    score = np.array([[-1.0, -0.5, -2.0, -0.5], [0.0, -np.inf, -np.inf, -np.inf]], dtype=np.float32)
+    sc, src, lab = _run(logits, score)
+    osc, osrc, olab = D.beam_step(logits.astype(np.float64), score.astype(np.float64), beam)
+    assert np.array_equal(src, osrc) and np.array_equal(lab, olab)
+    np.testing.assert_allclose(sc, osc, rtol=1e-6)
+    assert src[0].tolist() == [1, 1, 1, 1] and lab[0].tolist() == [0, 1, 2, 3]             # hypothesis 1 before 3, labels ascending
+    assert src[1].tolist() == [0, 0, 0, 0]                                                 # only hypothesis 0 is alive in a first step
+    # duplicated maxima inside a row: the earlier label wins
+    logits2 = np.zeros((beam, V), dtype=np.float32); logits2[:, [2, 5]] = 4.0
+    sc, src, lab = _run(logits2, np.array([[0.0, -1.0, -np.inf, -np.inf]], dtype=np.float32))
+    assert src[0].tolist() == [0, 0, 1, 1] and lab[0].tolist() == [2, 5, 2, 5]
+
+
+def test_beam_step_strided_logits():
+    rng = np.random.default_rng(9)
+    Q, beam, V = 3, 5, 1000
+    wide = (rng.standard_normal((Q * beam, V + 24)) * 2).astype(np.float32)
+    score = (-rng.uniform(0, 3, (Q, beam))).astype(np.float32)
+    r = Bn.beam_step(torch.from_numpy(wide).cuda()[:, :V], torch.from_numpy(score).cuda())
+    torch.cuda.synchronize()
+    got = (r["score"].cpu().numpy(), r["src"].cpu().numpy().astype(np.int64), r["label"].cpu().numpy().astype(np.int64))
+    _validate(np.ascontiguousarray(wide[:, :V]), score, beam, got)
+
+
+def test_gather_and_embed_are_exact():
+    rng = np.random.default_rng(10)
+    Q, beam = 6, 12
+    src = rng.integers(0, beam, (Q, beam)).astype(np.int32)
+    for dt, width in ((torch.float32, 1000), (torch.bfloat16, 79), (torch.float32, 1)):
+        st = torch.from_numpy(rng.standard_normal((Q * beam, width)).astype(np.float32)).to(dt).cuda()
+        out = Bn.beam_gather(st, torch.from_numpy(src).cuda())
+        torch.cuda.synchronize()
+        want = D.gather_rows(st.float().cpu().numpy(), src, beam)
+        assert np.array_equal(out.float().cpu().numpy(), want)
+    V, n = 500, 620
+    W = torch.from_numpy(rng.standard_normal((V, n)).astype(np.float32)).to(torch.bfloat16)
+    b = rng.standard_normal(n).astype(np.float32)
+    label = rng.integers(0, V, (Q, beam)).astype(np.int32)
+    out = Bn.embed(torch.from_numpy(label).cuda(), W.cuda(), torch.from_numpy(b).cuda())
+    torch.cuda.synchronize()
+    want = torch.from_numpy(D.embed(label, W.float().numpy().astype(np.float64), b.astype(np.float64)).astype(np.float32)).to(torch.bfloat16)
+    assert torch.equal(out.cpu(), want)                                                    # one float add, one rounding: identical
+    out0 = Bn.embed(torch.from_numpy(label).cuda(), W.cuda(), None)
+    torch.cuda.synchronize()
+    assert torch.equal(out0.cpu(), W[torch.from_numpy(label.reshape(-1)).long()])
