@@ -383,6 +383,117 @@ def bench_decoder_attention(args, Bn, synth):
     print(json.dumps(out))
 
 
+def bench_search_step(args, Bn, synth):
+    """--config 9: one complete step of the batched beam search (Sec. 4; Listing 1): cell, attention, readout, output
+    layer over V = 20000 labels, beam step, state gather and target embedding, for 64 sentences x beam 12, with no host
+    round trip between the steps: the labels and hypotheses chosen in step i feed step i+1 on the device.  One "step" is a
+    block of 50 dependent search steps; the figure of merit is the latency of one search step."""
+    import ctypes as ct
+    inp5 = synth.make(5)
+    L = inp5["layers"][0]
+    dec = synth.make_decoder()
+    cfg = dec["cfg"]
+    Q, beam, A, E, n, nt, R, S, B = cfg["Q"], cfg["beam"], cfg["A"], cfg["E"], cfg["n"], cfg["n_trg"], cfg["R"], dec["S"], dec["B"]
+    V, nsteps = 20000, 50
+    bf = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    f32 = lambda a: torch.from_numpy(a).float().cuda()
+    Wx, Wh, b = bf(L["W_x"][0]), bf(L["W_h"][0]), f32(L["b"][0])
+    enc, W_s, W_r = bf(dec["H"]), bf(dec["W_s"]), bf(dec["W_r"])
+    b_s, w_fb, b_fb, v, b_r = (f32(dec[k]) for k in ("b_s", "w_fb", "b_fb", "v", "b_r"))
+    lens = torch.from_numpy(dec["src_lens"]).cuda()
+    g = torch.Generator(device="cpu").manual_seed(9)
+    u = lambda *shape: torch.rand(*shape, generator=g) * 2 - 1
+    W_ctx = (u(E, A) * 0.05).to(torch.bfloat16).cuda()
+    W_o = (u(V, R) * 0.1).to(torch.bfloat16).cuda()              # output layer, a row per label
+    b_o = (u(V) * 0.5).cuda()
+    W_trg = (u(V, nt) * 0.5).to(torch.bfloat16).cuda()            # target embedding table
+    ctx = Bn.gemm(enc.view(S * Q, E), W_ctx, a_kcontig=True, b_kcontig=False, M=S * Q, N=A, K=E, out_dtype=torch.bfloat16).view(S, Q, A)
+    z = lambda *shape, dt=torch.float32: torch.zeros(*shape, dtype=dt, device="cuda")
+    xin = [z(B, nt + E, dt=torch.bfloat16) for _ in range(2)]
+    h, c, accum, score = [z(B, n) for _ in range(2)], [z(B, n) for _ in range(2)], [z(B, S) for _ in range(2)], [z(Q, beam) for _ in range(2)]
+    score[0][:, 1:] = float("-inf")                               # first step: one live hypothesis per sentence
+    h_new, c_new, accum_new = z(B, n), z(B, n), z(B, S)
+    att_buf, y, ro = z(B, E, dt=torch.bfloat16), z(1, B, n, dt=torch.bfloat16), z(B, R, dt=torch.bfloat16)
+    logits = torch.empty(B, V, dtype=torch.float32, device="cuda")
+    src, label = torch.zeros(Q, beam, dtype=torch.int32, device="cuda"), torch.zeros(Q, beam, dtype=torch.int32, device="cuda")
+    desc = Bn.make_desc(1, B, nt + E, n, Bn.LSTM_BF16_F32STATE, 1, Bn.FLAG_INFERENCE)
+    _, wb = Bn.query(desc, False)
+    desc.workspace_bytes = wb
+    desc_packed = Bn.make_desc(1, B, nt + E, n, Bn.LSTM_BF16_F32STATE, 1, Bn.FLAG_INFERENCE | Bn.FLAG_WEIGHTS_PACKED)
+    desc_packed.workspace_bytes = wb
+    ws_cell = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    ad = Bn.attention_query(S, Q, beam, A, E, n)
+    ws_att = torch.empty(ad.workspace_bytes, dtype=torch.uint8, device="cuda")
+    need = ct.c_uint64(0)
+    assert Bn.lib.lstm_readout_query(B, R, n, nt, E, ct.byref(need)) == 0
+    ws_ro = torch.empty(need.value, dtype=torch.uint8, device="cuda")
+    assert Bn.lib.lstm_beam_query(Q, beam, V, ct.byref(need)) == 0
+    ws_beam = torch.empty(need.value, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    lib = Bn.lib
+    NEV = 6
+
+    def one(i, first, ev=None):
+        p = i % 2
+        ck = lambda rc: Bn._check(rc)
+        if ev: ev[0].record()
+        ck(lib.lstm_fwd(ct.byref(desc if first else desc_packed), xin[p].data_ptr(), Wx.data_ptr(), Wh.data_ptr(), b.data_ptr(),
+                        h[p].data_ptr(), c[p].data_ptr(), None, y.data_ptr(), None, h_new.data_ptr(), c_new.data_ptr(), None, ws_cell.data_ptr(), st))
+        if ev: ev[1].record()
+        ck(lib.lstm_attention_step(ct.byref(ad), enc.data_ptr(), ctx.data_ptr(), lens.data_ptr(), y.data_ptr(), n, W_s.data_ptr(),
+                                   b_s.data_ptr(), w_fb.data_ptr(), b_fb.data_ptr(), v.data_ptr(), float(dec["b_e"]), accum[p].data_ptr(),
+                                   accum_new.data_ptr(), None, att_buf.data_ptr(), E, ws_att.data_ptr(), st))
+        if ev: ev[2].record()
+        ck(lib.lstm_readout(0 if first else Bn.FLAG_WEIGHTS_PACKED, B, R, y.data_ptr(), n, n, xin[p].data_ptr(), nt + E, nt,
+                            att_buf.data_ptr(), E, E, W_r.data_ptr(), b_r.data_ptr(), ro.data_ptr(), R, ws_ro.data_ptr(), ws_ro.numel(), st))
+        if ev: ev[3].record()
+        ck(lib.lstm_gemm(1, 0, 1, 1, B, V, R, ro.data_ptr(), R, W_o.data_ptr(), R, logits.data_ptr(), V, b_o.data_ptr(), 0, None, 1, 0, st))
+        if ev: ev[4].record()
+        ck(lib.lstm_beam_step(Q, beam, V, logits.data_ptr(), V, score[p].data_ptr(), score[1 - p].data_ptr(), src.data_ptr(), label.data_ptr(),
+                              ws_beam.data_ptr(), ws_beam.numel(), st))
+        for (a_in, a_out, width, ld_out, eb) in ((h_new, h[1 - p].data_ptr(), n, n, 4), (c_new, c[1 - p].data_ptr(), n, n, 4),
+                                                   (accum_new, accum[1 - p].data_ptr(), S, S, 4),
+                                                   (att_buf, xin[1 - p].data_ptr() + 2 * nt, E, nt + E, 2)):
+            ck(lib.lstm_beam_gather(eb, Q, beam, width, a_in.data_ptr(), width, src.data_ptr(), a_out, ld_out, st))
+        ck(lib.lstm_embed(B, nt, V, label.data_ptr(), W_trg.data_ptr(), None, xin[1 - p].data_ptr(), nt + E, st))
+        if ev: ev[5].record()
+
+    def block(first=False):
+        for i in range(nsteps):
+            one(i, first and i == 0)
+
+    block(True)
+    for _ in range(args.warmup):
+        block()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        block()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us = dt / (args.steps * nsteps) * 1e6
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(NEV)] for _ in range(nsteps)]
+    for i in range(nsteps):
+        one(i, False, evs[i])
+    torch.cuda.synchronize()
+    part = [sum(e[k].elapsed_time(e[k + 1]) for e in evs) / nsteps * 1e3 for k in range(NEV - 1)]
+    assert bool(torch.isfinite(score[0]).all()) and int(label.min()) >= 0 and int(label.max()) < V and int(src.max()) < beam
+    # beam step: algorithmic bytes = the logits read once (they were just written by the output layer)
+    beam_bytes = float(B) * V * 4
+    out = {
+        "metric": "beam search step latency (n=%d, %d rows, V=%d)" % (n, B, V), "value": us, "unit": "us/step", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 9: config 8's decoder step + output layer (%d -> %d labels) + beam step (beam %d) + state gather + "
+                               "target embedding; %d sentences, %d rows, %d dependent steps per block, no host round trip" % (R, V, beam, Q, B, nsteps)},
+        "us_per_step_cell_attention_readout_output_beam": part,
+        "roofline": {"bound": "hbm", "kernel": "beam step + gathers + embedding (beam_row_kernel dominates: one read of the logits)",
+                     "achieved": beam_bytes / (part[4] * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": beam_bytes / (part[4] * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+    }
+    print(json.dumps(out))
+
+
 class PooledStack:
     """The config-4 stack with max-pooling in time (windows of 2 frames) behind layers 1, 2 and 3: the shape of the
     paper's attention-based speech encoder (6 bidirectional layers, input shortened by a factor of 8 in total)."""
@@ -525,7 +636,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell; 6 = config 4 with max-pooling in time between layers; 7 = one bidirectional layer below five unidirectional ones; 8 = decoder step with attention and readout)")
+    ap.add_argument("--config", type=int, default=4, help="synthetic configuration (4 = headline, n = 1024; 2, 3 = other BLSTM stacks; 5 = stepped decoder cell; 6 = config 4 with max-pooling in time between layers; 7 = one bidirectional layer below five unidirectional ones; 8 = decoder step with attention and readout; 9 = complete beam-search step)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--per-step", action="store_true", help="force one launch per time step")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -554,6 +665,9 @@ def main():
         return
     if args.config == 8:
         bench_decoder_attention(args, Bn, synth)
+        return
+    if args.config == 9:
+        bench_search_step(args, Bn, synth)
         return
     inp = synth.make(args.config)
     cfg = inp["cfg"]

@@ -222,14 +222,14 @@ int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, co
  *     smaller b * V + v.  A hypothesis with score -inf (the unused slots of the first step) never beats a finite one.
  * Finished hypotheses and length normalisation are not part of this step.  All arithmetic is float.
  *   logits float [Q*beam][ld >= V] (e.g. lstm_gemm of the readout with the output weights), score_in, score_out float
- *   [Q][beam], src, label int32 [Q][beam]; beam <= 16, V <= 32768; workspace of lstm_beam_query() bytes.
+ *   [Q][beam], src, label int32 [Q][beam]; beam <= 16, V <= 2^26; workspace of lstm_beam_query() bytes.
  * lstm_beam_gather moves per-hypothesis state behind the choice: out[q*beam + k][0..width) = in[q*beam + src[q, k]][..]
  *   for rows of `width` elements of elem_bytes (2 or 4) bytes; in and out must be different buffers; values of src
  *   outside [0, beam) are clamped.
  * lstm_embed is Listing 1's "trg": out[r] = W_trg[label[r]] + b_trg with W_trg bfloat16 [V][n], b_trg float [n] or NULL,
  *   out bfloat16 [B][ld_out >= n]; a label outside [0, V) gives the bias alone.
  * Device pointers owned by the caller; the calls only enqueue work and nothing is copied to the host.
- * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM, LSTM_ERR_UNSUPPORTED (beam > 16, V > 32768, elem_bytes, in == out),
+ * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM, LSTM_ERR_UNSUPPORTED (beam > 16, V > 2^26, elem_bytes, in == out),
  * LSTM_ERR_ALIGN, LSTM_ERR_SIZE, LSTM_ERR_HIP. */
 int lstm_beam_query(int Q, int beam, int V, uint64_t* workspace_bytes);
 int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out,

@@ -7,8 +7,8 @@
 //     trg[r] = W_trg[label[r]] + b_trg
 //
 // No candidate list of beam * V entries is ever sorted: a sentence's best `beam` candidates contain at most `beam` from one
-// row, so every row first picks its own best `beam` labels out of a copy of the row in LDS (beam_row_kernel), and one small
-// work-group per sentence merges the beam * beam survivors (beam_merge_kernel).  Nothing returns to the host.
+// row, so every row first picks its own best `beam` labels in one pass over its logits (beam_row_kernel, a wavefront per
+// row), and one wavefront per sentence merges the beam * beam survivors (beam_merge_kernel).  Nothing returns to the host.
 #include <algorithm>
 
 #include "../../include/lstm_abi.h"
@@ -18,7 +18,7 @@ namespace lstm {
 namespace {
 
 constexpr int kBeamMax = 16;
-constexpr int kVocabMax = 32768;      // a row of logits must fit into LDS as floats (128 KiB)
+constexpr int kVocabMax = 1 << 26;    // beam * V must fit an int32 flat index
 
 // (value, index) pairs ordered by larger value first, then smaller index: `better(a, b)` = a comes before b
 struct Cand { float v; int i; };
@@ -34,85 +34,131 @@ __device__ __forceinline__ Cand wave_best(Cand c) {
   }
   return c;
 }
-// best candidate of the work-group (256 lanes); every lane receives it.  `slot` = 4 entries of LDS scratch.
-__device__ __forceinline__ Cand block_best(Cand c, Cand* slot) {
-  c = wave_best(c);
-  __syncthreads();                                              // the previous round's readers are done with `slot`
-  if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = c;
-  __syncthreads();
-  return pick(pick(slot[0], slot[1]), pick(slot[2], slot[3]));
-}
-
-// Row r of the logits: logsumexp, then the row's best `beam` labels, each found as the best entry that comes after the
-// previous pick in the order above (so nothing has to be marked or removed).  Writes cand_val[r][k] = score[r] +
-// logits[r][label] - logsumexp and cand_lab[r][k] = label.  Dynamic LDS: V floats.
-__global__ __launch_bounds__(256) void beam_row_kernel(const float* __restrict__ logits, long ld, const float* __restrict__ score,
-                                                        float* __restrict__ cand_val, int* __restrict__ cand_lab, int V, int beam) {
-  extern __shared__ float row[];
-  __shared__ Cand slot[4];
-  __shared__ float fsum[4];
-  const int r = blockIdx.x, tid = threadIdx.x;
-  const float* src = logits + (long)r * ld;
-  const Cand none = {-__builtin_inff(), 0x7fffffff};
-  Cand best = none;
-  for (int i = tid; i < V; i += 256) {
-    const float x = src[i];
-    row[i] = x;
-    const Cand c = {x, i};
-    best = pick(best, c);
-  }
-  best = block_best(best, slot);                                // also makes the whole row visible
-  const float m = best.v;
-  float z = 0.f;
-  for (int i = tid; i < V; i += 256) z += __expf(row[i] - m);
+// A lane's best kBeamMax candidates so far, best first.
+struct TopList {
+  float v[kBeamMax];
+  int i[kBeamMax];
+  __device__ __forceinline__ void clear() {
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
-  if ((tid & 63) == 0) fsum[tid >> 6] = z;
-  __syncthreads();
-  const float lse = m + __logf(fsum[0] + fsum[1] + fsum[2] + fsum[3]);
-  const float sc = score[r];
-  Cand prev = best;
+    for (int p = 0; p < kBeamMax; ++p) { v[p] = -__builtin_inff(); i[p] = 0x7fffffff; }
+  }
+  // insert c, dropping the last entry; ORDERED: the caller offers candidates in ascending index order, so one that
+  // equals an entry in value comes after it and a value comparison is enough
+  template <bool ORDERED>
+  __device__ __forceinline__ void insert(const Cand& c) {
+    const auto before = [&](int p) { return ORDERED ? c.v > v[p] : better(c, Cand{v[p], i[p]}); };
+#pragma unroll
+    for (int p = kBeamMax - 1; p > 0; --p) {
+      const bool shift = before(p - 1), here = before(p);
+      v[p] = shift ? v[p - 1] : (here ? c.v : v[p]);
+      i[p] = shift ? i[p - 1] : (here ? c.i : i[p]);
+    }
+    const bool first = before(0);
+    v[0] = first ? c.v : v[0];
+    i[0] = first ? c.i : i[0];
+  }
+  __device__ __forceinline__ void pop() {
+#pragma unroll
+    for (int p = 0; p + 1 < kBeamMax; ++p) { v[p] = v[p + 1]; i[p] = i[p + 1]; }
+    v[kBeamMax - 1] = -__builtin_inff();
+    i[kBeamMax - 1] = 0x7fffffff;
+  }
+};
+
+// The wavefront's best `beam` candidates out of its 64 lists, best first: `beam` rounds in which every lane offers the
+// head of its list and the lane that wins drops it.  emit(k, winner) runs in every lane.
+template <typename F>
+__device__ __forceinline__ void wave_select(TopList& t, int beam, F emit) {
   for (int k = 0; k < beam; ++k) {
-    if (k > 0) {
-      Cand c = none;
-      for (int i = tid; i < V; i += 256) {
-        const Cand x = {row[i], i};
-        if (better(prev, x)) c = pick(c, x);                    // strictly after the previous pick
-      }
-      prev = block_best(c, slot);
-    }
-    if (tid == 0) {
-      const bool found = prev.i < V;                             // fewer than `beam` labels in the row: the rest never wins
-      cand_val[(long)r * beam + k] = found ? sc + (prev.v - lse) : -__builtin_inff();
-      cand_lab[(long)r * beam + k] = found ? prev.i : 0;
-    }
+    const Cand head = {t.v[0], t.i[0]};
+    const Cand win = wave_best(head);
+    if (win.i == head.i && win.i != 0x7fffffff) t.pop();        // indices are unique, so exactly one lane owns the winner
+    emit(k, win);
   }
 }
 
-// The beam * beam survivors of sentence q = blockIdx.x: the best `beam`, by value and then by flat index b * V + label.
-__global__ __launch_bounds__(256) void beam_merge_kernel(const float* __restrict__ cand_val, const int* __restrict__ cand_lab,
-                                                          float* __restrict__ score_out, int* __restrict__ src_out,
-                                                          int* __restrict__ label_out, int V, int beam) {
-  __shared__ Cand slot[4];
-  const int q = blockIdx.x, tid = threadIdx.x;
-  const Cand none = {-__builtin_inff(), 0x7fffffff};
-  Cand mine = none;
-  if (tid < beam * beam) {
-    const int b = tid / beam;
-    mine.v = cand_val[(long)q * beam * beam + tid];
-    mine.i = b * V + cand_lab[(long)q * beam * beam + tid];
-  }
-  Cand prev = none;
-  for (int k = 0; k < beam; ++k) {
-    const bool eligible = k == 0 || better(prev, mine);
-    prev = block_best(eligible ? mine : none, slot);
-    if (tid == 0) {
-      // with every hypothesis at -inf no candidate is "better" than another after the first pick: flat indices still are
-      score_out[q * beam + k] = prev.v;
-      src_out[q * beam + k] = prev.i == 0x7fffffff ? 0 : prev.i / V;
-      label_out[q * beam + k] = prev.i == 0x7fffffff ? 0 : prev.i % V;
+// Row r of the logits, one wavefront: a single pass over the row in which every lane keeps the best 16 of the entries it
+// sees (in registers; an insertion is needed ever more rarely as the list fills up with large values) and a running
+// logsumexp, then wave_select.  Writes cand_val[r][k] = score[r] + logits[r][label] - logsumexp and cand_lab[r][k].
+__global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ logits, long ld, const float* __restrict__ score,
+                                                       float* __restrict__ cand_val, int* __restrict__ cand_lab, int V, int beam) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  const float* src = logits + (long)r * ld;
+  TopList t;
+  t.clear();
+  float m = -__builtin_inff(), z = 0.f;                          // running maximum and sum of exp(x - m) of this lane's entries
+  const auto fold = [&](float gm, float gz) {                    // merge (gm, gz) into (m, z)
+    const float mn = fmaxf(m, gm);
+    if (mn > -__builtin_inff()) z = z * __expf(m - mn) + gz * __expf(gm - mn);
+    m = mn;
+  };
+  const bool vec = (ld & 3) == 0 && ((uintptr_t)logits & 15) == 0;
+  const int n4 = vec ? V >> 2 : 0;
+  constexpr int kU = 8;                                          // loads of 16 bytes in flight per lane
+  for (int i0 = lane; i0 < n4; i0 += 64 * kU) {
+    float4 x4[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) x4[u] = ((const float4*)src)[min(i0 + u * 64, n4 - 1)];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int i4 = i0 + u * 64;
+      if (i4 < n4) {
+        const float x[4] = {x4[u].x, x4[u].y, x4[u].z, x4[u].w};
+        const float gm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+        if (gm > -__builtin_inff()) fold(gm, __expf(x[0] - gm) + __expf(x[1] - gm) + __expf(x[2] - gm) + __expf(x[3] - gm));
+        if (gm > t.v[kBeamMax - 1]) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (x[e] > t.v[kBeamMax - 1]) t.insert<true>(Cand{x[e], 4 * i4 + e});
+        }
+      }
     }
   }
+  for (int i = 4 * n4 + lane; i < V; i += 64) {
+    const float x = src[i];
+    if (x > -__builtin_inff()) fold(x, 1.f);
+    if (x > t.v[kBeamMax - 1]) t.insert<true>(Cand{x, i});
+  }
+  // logsumexp of the whole row
+  float mw = m;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mw = fmaxf(mw, __shfl_xor(mw, o));
+  float zw = mw > -__builtin_inff() ? z * __expf(m - mw) : 0.f;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) zw += __shfl_xor(zw, o);
+  const float lse = mw + __logf(zw);
+  const float sc = score[r];
+  wave_select(t, beam, [&](int k, const Cand& win) {
+    if (lane == 0) {
+      const bool found = win.i != 0x7fffffff;                    // fewer than `beam` usable labels in the row: the rest never wins
+      cand_val[(long)r * beam + k] = found ? sc + (win.v - lse) : -__builtin_inff();
+      cand_lab[(long)r * beam + k] = found ? win.i : 0;
+    }
+  });
+}
+
+// The beam * beam survivors of sentence q = blockIdx.x, one wavefront: the best `beam`, by value and then by flat index
+// b * V + label.
+__global__ __launch_bounds__(64) void beam_merge_kernel(const float* __restrict__ cand_val, const int* __restrict__ cand_lab,
+                                                         float* __restrict__ score_out, int* __restrict__ src_out,
+                                                         int* __restrict__ label_out, int V, int beam) {
+  const int q = blockIdx.x, lane = threadIdx.x;
+  TopList t;
+  t.clear();
+  for (int c = lane; c < beam * beam; c += 64) {
+    const float val = cand_val[(long)q * beam * beam + c];
+    const int flat = (c / beam) * V + cand_lab[(long)q * beam * beam + c];
+    // a row with fewer than `beam` labels pads with (-inf, label 0): give the padding indices that cannot collide
+    t.insert<false>(Cand{val, val == -__builtin_inff() ? 0x7ffffffe - c : flat});
+  }
+  wave_select(t, beam, [&](int k, const Cand& win) {
+    if (lane == 0) {
+      const bool real = win.i < beam * V;
+      score_out[q * beam + k] = win.v;
+      src_out[q * beam + k] = real ? win.i / V : 0;
+      label_out[q * beam + k] = real ? win.i % V : 0;
+    }
+  });
 }
 
 // out[q * beam + k][0..width) = in[q * beam + src[q * beam + k]][0..width), elements of `esz` bytes copied as bytes pairs
@@ -174,16 +220,8 @@ int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, cons
   char* ws = (char*)(((uintptr_t)workspace + 255) / 256 * 256);
   float* cand_val = (float*)ws;
   int* cand_lab = (int*)(ws + ((size_t)Q * beam * beam * 4 + 255) / 256 * 256);
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)beam_row_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kVocabMax * 4) != hipSuccess) {
-      (void)hipGetLastError();
-      return LSTM_ERR_HIP;
-    }
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(beam_row_kernel, dim3(Q * beam), dim3(256), (size_t)V * 4, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
-  hipLaunchKernelGGL(beam_merge_kernel, dim3(Q), dim3(256), 0, st, cand_val, cand_lab, score_out, src, label, V, beam);
+  hipLaunchKernelGGL(beam_row_kernel, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
+  hipLaunchKernelGGL(beam_merge_kernel, dim3(Q), dim3(64), 0, st, cand_val, cand_lab, score_out, src, label, V, beam);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
   return LSTM_OK;
 }

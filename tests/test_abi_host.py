@@ -165,7 +165,7 @@ def test_beam_argument_errors():
     assert L.lstm_beam_query(4, 12, 20000, ctypes.byref(q)) == 0 and q.value > 0
     assert L.lstm_beam_query(4, 12, 20000, None) == -1 and L.lstm_beam_query(-1, 12, 10, ctypes.byref(q)) == -2
     assert L.lstm_beam_query(4, 0, 10, ctypes.byref(q)) == -2 and L.lstm_beam_query(4, 2, 0, ctypes.byref(q)) == -2
-    assert L.lstm_beam_query(4, 17, 10, ctypes.byref(q)) == -4 and L.lstm_beam_query(4, 2, 40000, ctypes.byref(q)) == -4
+    assert L.lstm_beam_query(4, 17, 10, ctypes.byref(q)) == -4 and L.lstm_beam_query(4, 2, (1 << 26) + 1, ctypes.byref(q)) == -4
     st = lambda Q=4, beam=3, V=10, lg=P, ld=10, si=P, so=P, src=P, lab=P, ws=P, wsb=1 << 20: L.lstm_beam_step(Q, beam, V, lg, ld, si, so, src, lab, ws, wsb, None)
     for k in ("lg", "si", "so", "src", "lab", "ws"):
         assert st(**{k: None}) == -1, k
