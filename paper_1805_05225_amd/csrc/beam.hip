@@ -95,6 +95,23 @@ __global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ 
   const bool vec = (ld & 3) == 0 && ((uintptr_t)logits & 15) == 0;
   const int n4 = vec ? V >> 2 : 0;
   constexpr int kU = 8;                                          // loads of 16 bytes in flight per lane
+  // Inserting is a hundred instructions for the whole wavefront whenever ONE lane needs it, and with 64 private lists
+  // some lane nearly always does.  So entries are first held against a bound that at least `beam` entries seen so far
+  // reach: the `beam`-th largest of the 64 list heads, found by bisection over the ordered bit patterns with ballots,
+  // renewed once per round of loads.  Whatever lies strictly below it cannot be among the row's best `beam`.
+  float bound = -__builtin_inff();
+  const int need = min(beam, 64);
+  const auto renew_bound = [&]() {
+    const unsigned f = __float_as_uint(t.v[0]);
+    const unsigned key = (f & 0x80000000u) ? ~f : (f | 0x80000000u);             // larger float <=> larger key
+    unsigned lo = 0u, hi = 0xffffffffu;
+    while (lo < hi) {
+      const unsigned mid = lo + ((hi - lo) >> 1) + 1u;
+      if (__popcll(__ballot(key >= mid)) >= need) lo = mid; else hi = mid - 1u;
+    }
+    // lo = the need-th largest key; keys at or below that of -inf mean fewer than `need` lanes hold anything yet
+    bound = lo <= 0x007fffffu ? -__builtin_inff() : __uint_as_float((lo & 0x80000000u) ? (lo & 0x7fffffffu) : ~lo);
+  };
   for (int i0 = lane; i0 < n4; i0 += 64 * kU) {
     float4 x4[kU];
 #pragma unroll
@@ -106,13 +123,14 @@ __global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ 
         const float x[4] = {x4[u].x, x4[u].y, x4[u].z, x4[u].w};
         const float gm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
         if (gm > -__builtin_inff()) fold(gm, __expf(x[0] - gm) + __expf(x[1] - gm) + __expf(x[2] - gm) + __expf(x[3] - gm));
-        if (gm > t.v[kBeamMax - 1]) {
+        if (gm >= bound && gm > t.v[kBeamMax - 1]) {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (x[e] > t.v[kBeamMax - 1]) t.insert<true>(Cand{x[e], 4 * i4 + e});
+            if (x[e] >= bound && x[e] > t.v[kBeamMax - 1]) t.insert<true>(Cand{x[e], 4 * i4 + e});
         }
       }
     }
+    renew_bound();
   }
   for (int i = 4 * n4 + lane; i < V; i += 64) {
     const float x = src[i];
