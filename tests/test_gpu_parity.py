@@ -324,6 +324,25 @@ def test_time_pool_matches_oracle_exactly(dt, T, B, F, pool):
     assert np.array_equal(host(r2["out"]), O.time_maxpool_fwd(yo, None, pool)[0]) and r2["arg"] is None
 
 
+def test_time_pool_full_size_of_the_pooled_encoder():
+    """The first pooling of the pooled-encoder benchmark at its full size and in its launch configuration: T = 1491, B = 32,
+    F = 2048 bfloat16, windows of 2, config 4's sequence lengths; every element of out, arg (at valid frames), lens and dy."""
+    inp = synth.make(4, layers=1)
+    T, B, F, pool = inp["T"], inp["cfg"]["B"], 2 * inp["cfg"]["n"], 2
+    lens = inp["seq_lens"].astype(np.int64)
+    g = torch.Generator(device="cpu").manual_seed(46)
+    y = torch.randn(T, B, F, generator=g).to(torch.bfloat16).cuda()
+    print("  pooling at full size: T=%d B=%d F=%d" % (T, B, F), flush=True)
+    out_o, lens_o, arg_o = O.time_maxpool_fwd(host(y), lens, pool)
+    r = Bn.time_pool_fwd(y, dev(inp["seq_lens"]), pool)
+    assert np.array_equal(host(r["out"]), out_o) and np.array_equal(r["lens"].cpu().numpy(), lens_o)
+    valid = (np.arange(out_o.shape[0])[:, None] < lens_o[None, :])[:, :, None]
+    assert np.array_equal(np.where(valid, r["arg"].cpu().numpy(), 0), arg_o)
+    dout = torch.randn(out_o.shape, generator=g).to(torch.bfloat16).cuda()
+    dy = Bn.time_pool_bwd(dout, r["arg"], dev(inp["seq_lens"]), pool, T)
+    assert np.array_equal(host(dy), O.time_maxpool_bwd(host(dout), arg_o, lens, pool, T))
+
+
 def test_time_pool_unaligned_rows_and_strided_input():
     """Rows that are not 16-byte multiples (scalar path) and a pooled view of one direction's half of a wider tensor."""
     rng = np.random.default_rng(77)
