@@ -20,6 +20,7 @@ namespace lstm {
 namespace {
 
 constexpr int kMaxBeam = 16;          // hypotheses per sentence (register budget of the energy kernel)
+constexpr int kMaxS = 1024;           // source positions: beam x S weights sit in LDS
 constexpr int kJB = 2;                // source positions per work-group of the energy kernel (measured: 1: 31 us, 2: 27, 4: 29, 8: 41)
 constexpr int kPartStride = 260;      // floats per partial-sum row in LDS: 4 * value + slot hits 64 different banks
 
@@ -258,7 +259,7 @@ static int att_check(const lstm_att_desc* d) {
   if (!d) return LSTM_ERR_NULL;
   if (d->S < 1 || d->Q < 0 || d->beam < 1 || d->A < 1 || d->E < 2 || d->n < 1 || d->Q > 65535 || (long)d->Q * d->beam > 0x7fffffffL / d->S)
     return LSTM_ERR_DIM;
-  if (d->beam > kMaxBeam || d->S > 1024 || (d->E & 1)) return LSTM_ERR_UNSUPPORTED;
+  if (d->beam > kMaxBeam || d->S > kMaxS || (d->E & 1)) return LSTM_ERR_UNSUPPORTED;
   return LSTM_OK;
 }
 
@@ -297,6 +298,15 @@ int lstm_attention_step(const lstm_att_desc* d, const void* enc, const void* enc
   if (linear_rows(s, ld_s, W_s, d->n, b_s, s_tr, B, d->A, d->n, parts, ks, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
   hipLaunchKernelGGL(att_energy_kernel, dim3((d->S + kJB - 1) / kJB, d->Q), dim3(256), 0, st, (const uint16_t*)enc_ctx, s_tr, accum_in, w_fb,
                      b_fb, v, b_e, src_lens, e, d->S, d->Q, d->beam, d->A);
+  static bool attr_set = false;                                  // S = 1024 needs 64 KiB of dynamic LDS beside the static arrays
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)att_softmax_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxS * kMaxBeam * 4) != hipSuccess ||
+        hipFuncSetAttribute((const void*)att_context_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxS * kMaxBeam * 4) != hipSuccess) {
+      (void)hipGetLastError();
+      return LSTM_ERR_HIP;
+    }
+    attr_set = true;
+  }
   float* a_buf = a ? a : (float*)((char*)parts + (ks > 1 ? up256((size_t)ks * B * d->A * 4) : 0));
   hipLaunchKernelGGL(att_softmax_kernel, dim3(d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, e, accum_in, src_lens, a_buf, accum_out, d->S,
                      d->beam);

@@ -45,7 +45,8 @@ CASES = [dict(Q=3, beam=2, len_lo=1, len_hi=9, A=40, E=6, n=24),                
          dict(Q=4, beam=1, len_lo=60, len_hi=70, A=300, E=514, n=136),            # no beam, S > 64, E not a multiple of 512
          dict(Q=2, beam=16, len_lo=5, len_hi=5, A=257, E=1026, n=72),             # widest beam, odd A
          dict(Q=7, beam=5, len_lo=1, len_hi=130, A=64, E=64, n=8),                # S > 128
-         dict(Q=64, beam=12, len_lo=20, len_hi=80, A=1000, E=2000, n=1000)]       # the benchmark's decoder step at its full size
+         dict(Q=64, beam=12, len_lo=20, len_hi=80, A=1000, E=2000, n=1000),       # the benchmark's decoder step at its full size
+         dict(Q=2, beam=16, len_lo=1024, len_hi=1024, A=64, E=128, n=16)]         # the largest S and beam the entry point takes
 
 
 @pytest.mark.parametrize("over", CASES)
