@@ -80,6 +80,7 @@ __device__ __forceinline__ void wave_select(TopList& t, int beam, F emit) {
 // Row r of the logits, one wavefront: a single pass over the row in which every lane keeps the best 16 of the entries it
 // sees (in registers; an insertion is needed ever more rarely as the list fills up with large values) and a running
 // logsumexp, then wave_select.  Writes cand_val[r][k] = score[r] + logits[r][label] - logsumexp and cand_lab[r][k].
+// (Four wavefronts per row, each with a quarter of the row and a second merge, measured slower: 63 -> 77 us.)
 __global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ logits, long ld, const float* __restrict__ score,
                                                        float* __restrict__ cand_val, int* __restrict__ cand_lab, int V, int beam) {
   const int r = blockIdx.x, lane = threadIdx.x;
