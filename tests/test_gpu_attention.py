@@ -3,7 +3,7 @@ against oracle/decoder_oracle.py on identical seeded inputs.
 
 Tolerances, relative to the largest oracle magnitude of each tensor: 1e-4 for the float outputs a and accum' (float
 accumulation over A = 1000 terms, hardware exp / reciprocal inside tanh and softmax), 5e-3 for the bfloat16 outputs
-att and readout (one rounding to 8 significant bits = 2^-9 of the element, plus the above)."""
+att and readout (one rounding to 8 significant bits: at most 2^-8 = 3.9e-3 of the element, plus the above)."""
 import numpy as np
 import pytest
 import torch
