@@ -34,13 +34,14 @@ __device__ __forceinline__ Cand wave_best(Cand c) {
   }
   return c;
 }
-// A lane's best kBeamMax candidates so far, best first.
+// A lane's best CAP candidates so far, best first.
+template <int CAP>
 struct TopList {
-  float v[kBeamMax];
-  int i[kBeamMax];
+  float v[CAP];
+  int i[CAP];
   __device__ __forceinline__ void clear() {
 #pragma unroll
-    for (int p = 0; p < kBeamMax; ++p) { v[p] = -__builtin_inff(); i[p] = 0x7fffffff; }
+    for (int p = 0; p < CAP; ++p) { v[p] = -__builtin_inff(); i[p] = 0x7fffffff; }
   }
   // insert c, dropping the last entry; ORDERED: the caller offers candidates in ascending index order, so one that
   // equals an entry in value comes after it and a value comparison is enough
@@ -48,7 +49,7 @@ struct TopList {
   __device__ __forceinline__ void insert(const Cand& c) {
     const auto before = [&](int p) { return ORDERED ? c.v > v[p] : better(c, Cand{v[p], i[p]}); };
 #pragma unroll
-    for (int p = kBeamMax - 1; p > 0; --p) {
+    for (int p = CAP - 1; p > 0; --p) {
       const bool shift = before(p - 1), here = before(p);
       v[p] = shift ? v[p - 1] : (here ? c.v : v[p]);
       i[p] = shift ? i[p - 1] : (here ? c.i : i[p]);
@@ -59,16 +60,16 @@ struct TopList {
   }
   __device__ __forceinline__ void pop() {
 #pragma unroll
-    for (int p = 0; p + 1 < kBeamMax; ++p) { v[p] = v[p + 1]; i[p] = i[p + 1]; }
-    v[kBeamMax - 1] = -__builtin_inff();
-    i[kBeamMax - 1] = 0x7fffffff;
+    for (int p = 0; p + 1 < CAP; ++p) { v[p] = v[p + 1]; i[p] = i[p + 1]; }
+    v[CAP - 1] = -__builtin_inff();
+    i[CAP - 1] = 0x7fffffff;
   }
 };
 
 // The wavefront's best `beam` candidates out of its 64 lists, best first: `beam` rounds in which every lane offers the
 // head of its list and the lane that wins drops it.  emit(k, winner) runs in every lane.
-template <typename F>
-__device__ __forceinline__ void wave_select(TopList& t, int beam, F emit) {
+template <int CAP, typename F>
+__device__ __forceinline__ void wave_select(TopList<CAP>& t, int beam, F emit) {
   for (int k = 0; k < beam; ++k) {
     const Cand head = {t.v[0], t.i[0]};
     const Cand win = wave_best(head);
@@ -81,11 +82,12 @@ __device__ __forceinline__ void wave_select(TopList& t, int beam, F emit) {
 // sees (in registers; an insertion is needed ever more rarely as the list fills up with large values) and a running
 // logsumexp, then wave_select.  Writes cand_val[r][k] = score[r] + logits[r][label] - logsumexp and cand_lab[r][k].
 // (Four wavefronts per row, each with a quarter of the row and a second merge, measured slower: 63 -> 77 us.)
+template <int CAP>
 __global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ logits, long ld, const float* __restrict__ score,
                                                        float* __restrict__ cand_val, int* __restrict__ cand_lab, int V, int beam) {
   const int r = blockIdx.x, lane = threadIdx.x;
   const float* src = logits + (long)r * ld;
-  TopList t;
+  TopList<CAP> t;
   t.clear();
   float m = -__builtin_inff(), z = 0.f;                          // running maximum and sum of exp(x - m) of this lane's entries
   const auto fold = [&](float gm, float gz) {                    // merge (gm, gz) into (m, z)
@@ -124,10 +126,10 @@ __global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ 
         const float x[4] = {x4[u].x, x4[u].y, x4[u].z, x4[u].w};
         const float gm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
         if (gm > -__builtin_inff()) fold(gm, __expf(x[0] - gm) + __expf(x[1] - gm) + __expf(x[2] - gm) + __expf(x[3] - gm));
-        if (gm >= bound && gm > t.v[kBeamMax - 1]) {
+        if (gm >= bound && gm > t.v[CAP - 1]) {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (x[e] >= bound && x[e] > t.v[kBeamMax - 1]) t.insert<true>(Cand{x[e], 4 * i4 + e});
+            if (x[e] >= bound && x[e] > t.v[CAP - 1]) t.template insert<true>(Cand{x[e], 4 * i4 + e});
         }
       }
     }
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ 
   for (int i = 4 * n4 + lane; i < V; i += 64) {
     const float x = src[i];
     if (x > -__builtin_inff()) fold(x, 1.f);
-    if (x > t.v[kBeamMax - 1]) t.insert<true>(Cand{x, i});
+    if (x > t.v[CAP - 1]) t.template insert<true>(Cand{x, i});
   }
   // logsumexp of the whole row
   float mw = m;
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(64) void beam_merge_kernel(const float* __restrict_
                                                          float* __restrict__ score_out, int* __restrict__ src_out,
                                                          int* __restrict__ label_out, int V, int beam) {
   const int q = blockIdx.x, lane = threadIdx.x;
-  TopList t;
+  TopList<4> t;                                                 // beam * beam / 64 <= 4 candidates per lane
   t.clear();
   for (int c = lane; c < beam * beam; c += 64) {
     const float val = cand_val[(long)q * beam * beam + c];
@@ -239,7 +241,11 @@ int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, cons
   char* ws = (char*)(((uintptr_t)workspace + 255) / 256 * 256);
   float* cand_val = (float*)ws;
   int* cand_lab = (int*)(ws + ((size_t)Q * beam * beam * 4 + 255) / 256 * 256);
-  hipLaunchKernelGGL(beam_row_kernel, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
+  // a lane's list holds as many entries as the beam asks for (in the worst case all of the row's best lie in one lane)
+  if (beam <= 4) hipLaunchKernelGGL(beam_row_kernel<4>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
+  else if (beam <= 8) hipLaunchKernelGGL(beam_row_kernel<8>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
+  else if (beam <= 12) hipLaunchKernelGGL(beam_row_kernel<12>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
+  else hipLaunchKernelGGL(beam_row_kernel<16>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
   hipLaunchKernelGGL(beam_merge_kernel, dim3(Q), dim3(64), 0, st, cand_val, cand_lab, score_out, src, label, V, beam);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
   return LSTM_OK;
