@@ -16,6 +16,12 @@
  * one, and the frame contributes no gradient; values stored in x / dy at padded frames never
  * reach a result.  direction -1 walks t = T-1 .. 0 over the same tensors.
  *
+ * Beside the layer (lstm_query, lstm_fwd, lstm_bwd, blstm_fwd, blstm_bwd) the library holds what the paper's encoders
+ * and decoder put around it, each documented at its declaration below: the hoisted product by itself (lstm_gemm),
+ * max-pooling in time between encoder layers (lstm_time_pool_fwd / _bwd), one step of the attention decoder
+ * (lstm_attention_step, lstm_readout), one step of batched beam search (lstm_beam_step, lstm_beam_gather, lstm_embed),
+ * and diagnostics (lstm_sync_status, lstm_profile_*, lstm_strerror).
+ *
  * Conventions common to every entry point
  *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned, row-major,
  *     time-major.  The library allocates and frees nothing; scratch comes from `workspace`,
