@@ -23,7 +23,8 @@
  * and diagnostics (lstm_sync_status, lstm_profile_*, lstm_strerror).
  *
  * Conventions common to every entry point
- *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned, row-major,
+ *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned (unless an entry
+ *     point states a weaker requirement), row-major,
  *     time-major.  The library allocates and frees nothing; scratch comes from `workspace`,
  *     state saved for the backward pass goes to `reserve`; sizes come from lstm_query().
  *   - `stream` is a hipStream_t cast to void* (NULL = the default stream).  Calls only enqueue
