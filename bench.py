@@ -597,7 +597,8 @@ def bench_pooled(args, Bn, synth):
     dt = time.perf_counter() - t0
     B, n, esz = cfg["B"], cfg["n"], 2
     F = 2 * n
-    # pooling kernels: algorithmic bytes = input read once + output written once (+ one argument byte per output element);
+    # pooling kernels: algorithmic bytes = real input frames read once + every output frame written once (+ one argument byte
+    # per element of a real output frame);
     # the backward kernel writes every frame of dy, padded ones included (zeros), so that nothing has to be cleared first
     ms = {"fwd": 0.0, "bwd": 0.0}
     by = {"fwd": 0.0, "bwd": 0.0}
@@ -607,7 +608,8 @@ def bench_pooled(args, Bn, synth):
         if "pooled" not in bf:
             continue
         fin, fout = st.frames_per_layer[k], st.frames_per_layer[k + 1]
-        by["fwd"] += args.steps * (fin * F * esz + fout * F * (esz + 1))
+        Tp = -(-bf["T"] // st.pool)
+        by["fwd"] += args.steps * (fin * F * esz + Tp * B * F * esz + fout * F)          # out is defined (zero) at padded frames too
         by["bwd"] += args.steps * (fout * F * (esz + 1) + bf["T"] * B * F * esz)
     tot_ms, tot_by = ms["fwd"] + ms["bwd"], by["fwd"] + by["bwd"]
     traffic = None

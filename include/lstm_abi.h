@@ -159,7 +159,7 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
  *   dtype: LSTM_F32 (float tensors) or LSTM_BF16_F32STATE (bfloat16 tensors); the maximum is exact in both.
  *   y [T][B][ldy >= F], out [T'][B][ldo >= F], dout like out, dy like y: device pointers, element-aligned
  *   (16-byte aligned rows are faster); leading dimensions in elements.  1 <= pool <= 255.
- *   arg: device, T' * B * F bytes, written by the forward call (offset of the chosen frame inside its window)
+ *   arg: device, T' * B * F bytes, written by the forward call at valid output frames (offset of the chosen frame inside its window)
  *   and read by the backward call; may be NULL in the forward call if no backward call follows.
  *   seq_lens: device int32[B] or NULL (all rows have length T); lens_out: device int32[B] or NULL.
  * Errors: LSTM_ERR_NULL, LSTM_ERR_DIM (negative sizes, F < 1, pool out of range, ld < F), LSTM_ERR_UNSUPPORTED

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void time_pool_fwd_kernel(const T* __restrict_
       } else {
         Store<T>::store(out, orow * ldo + f, best[0]);
       }
-      if (arg) {
+      if (arg && t0 < L) {                                     // padded output frames: the backward pass never reads their bytes
         if (VEC) {                                             // V bytes at once (F, hence every row of arg, is a multiple of V)
           unsigned w[2] = {0u, 0u};
 #pragma unroll
