@@ -1,4 +1,4 @@
-"""Seeded synthetic inputs for the five benchmark configurations.
+"""Seeded synthetic inputs for the benchmark configurations (1-5, the mixed encoder 7, and the decoder step).
 
 This module only draws random numbers and rounds them to the storage type; it holds none of
 the LSTM arithmetic.  Both the CPU oracle's tests and the HIP path's tests take their inputs
