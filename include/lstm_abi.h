@@ -243,6 +243,17 @@ int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, cons
                    int32_t* src, int32_t* label, void* workspace, uint64_t workspace_bytes, void* stream);
 int lstm_beam_gather(int elem_bytes, int Q, int beam, int width, const void* in, int64_t ld_in, const int32_t* src,
                      void* out, int64_t ld_out, void* stream);
+/* lstm_beam_step for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same arguments without the workspace, same results (the
+ * same kernels run).  The step's scratch - the beam survivors of every row - lives in a device array of 512 KiB that is
+ * part of the library's image on every GPU it runs on; the call allocates and frees nothing.
+ *   Limit: Q * beam * beam <= 65536 (e.g. 256 sentences at beam 16), else LSTM_ERR_SIZE.
+ *   Every call on one GPU uses that GPU's one array: calls that may overlap in time on the same GPU (different
+ *   streams, different host threads) race and must be serialised by the caller.  Nothing in the array has to survive
+ *   between calls and nothing needs clearing: a call writes every entry it later reads.
+ * Other errors as lstm_beam_step. */
+int lstm_beam_step_static(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out,
+                          int32_t* src, int32_t* label, void* stream);
 int lstm_embed(int B, int n, int V, const int32_t* label, const void* W_trg, const float* b_trg, void* out,
                int64_t ld_out, void* stream);
 

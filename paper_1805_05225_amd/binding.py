@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED = 1, 2, 4, 8
 EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_time_pool_fwd", "lstm_time_pool_bwd", "lstm_attention_query", "lstm_attention_step",
-           "lstm_readout_query", "lstm_readout", "lstm_beam_query", "lstm_beam_step", "lstm_beam_gather", "lstm_embed",
+           "lstm_readout_query", "lstm_readout", "lstm_beam_query", "lstm_beam_step", "lstm_beam_step_static", "lstm_beam_gather", "lstm_embed",
            "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
            "lstm_strerror")
 
@@ -73,6 +73,8 @@ def _load():
     lib.lstm_beam_query.argtypes = [ip, ip, ip, u64p]
     lib.lstm_beam_step.restype = ip
     lib.lstm_beam_step.argtypes = [ip, ip, ip, vp, i64, vp, vp, vp, vp, vp, ctypes.c_uint64, vp]
+    lib.lstm_beam_step_static.restype = ip
+    lib.lstm_beam_step_static.argtypes = [ip, ip, ip, vp, i64, vp, vp, vp, vp, vp]
     lib.lstm_beam_gather.restype = ip
     lib.lstm_beam_gather.argtypes = [ip, ip, ip, ip, vp, i64, vp, vp, i64, vp]
     lib.lstm_embed.restype = ip
@@ -128,9 +130,10 @@ def _dtype_of(x):
 
 
 def forward(x, W_x, W_h, b=None, h0=None, c0=None, seq_lens=None, *, bidirectional, direction=1, flags=0,
-            workspace=None, want_c=True, want_state=True):
+            workspace=None, want_c=True, want_state=True, poison=False):
     """Allocates the outputs and calls lstm_fwd / blstm_fwd.  Returns a dict with y, c, hT, cT,
-    reserve, workspace and the descriptor (everything the backward call needs)."""
+    reserve, workspace and the descriptor (everything the backward call needs).  poison: fill reserve and workspace
+    with 0xFF bytes first."""
     T, B, n_in = x.shape
     n = W_h.shape[-2]
     D = 2 if bidirectional else 1
@@ -141,6 +144,10 @@ def forward(x, W_x, W_h, b=None, h0=None, c0=None, seq_lens=None, *, bidirection
     reserve = None if infer else torch.empty(rb, dtype=torch.uint8, device=dev)
     if workspace is None or workspace.numel() < wb:
         workspace = torch.empty(wb, dtype=torch.uint8, device=dev)
+    if poison:          # tests: every byte the library has not written reads as NaN
+        workspace.fill_(0xFF)
+        if reserve is not None:
+            reserve.fill_(0xFF)
     desc.reserve_bytes = 0 if infer else rb
     desc.workspace_bytes = workspace.numel()
     y = torch.empty(T, B, D * n, dtype=x.dtype, device=dev)
@@ -279,6 +286,20 @@ def beam_step(logits, score, *, workspace=None):
     _check(lib.lstm_beam_step(Q, beam, V, logits.data_ptr(), logits.stride(0), _ptr(score), _ptr(out), _ptr(src), _ptr(label),
                               _ptr(workspace), workspace.numel(), _stream()))
     return dict(score=out, src=src, label=label, workspace=workspace)
+
+
+def beam_step_static(logits, score):
+    """lstm_beam_step_static: the same step with the library's own scratch array (no workspace, nothing allocated by the
+    call itself; the outputs are the caller's, allocated here)."""
+    Q, beam = score.shape
+    V = logits.shape[1]
+    out = torch.empty(Q, beam, dtype=torch.float32, device=logits.device)
+    src = torch.empty(Q, beam, dtype=torch.int32, device=logits.device)
+    label = torch.empty(Q, beam, dtype=torch.int32, device=logits.device)
+    assert logits.stride(1) == 1 and logits.dtype == torch.float32 and score.dtype == torch.float32
+    _check(lib.lstm_beam_step_static(Q, beam, V, logits.data_ptr(), logits.stride(0), _ptr(score), _ptr(out), _ptr(src), _ptr(label),
+                                     _stream()))
+    return dict(score=out, src=src, label=label)
 
 
 def beam_gather(state, src):

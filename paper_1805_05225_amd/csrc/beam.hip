@@ -10,6 +10,7 @@
 // row, so every row first picks its own best `beam` labels in one pass over its logits (beam_row_kernel, a wavefront per
 // row), and one wavefront per sentence merges the beam * beam survivors (beam_merge_kernel).  Nothing returns to the host.
 #include <algorithm>
+#include <mutex>
 
 #include "../../include/lstm_abi.h"
 #include "common.h"
@@ -19,6 +20,14 @@ namespace {
 
 constexpr int kBeamMax = 16;
 constexpr int kVocabMax = 1 << 26;    // beam * V must fit an int32 flat index
+
+// Scratch of lstm_beam_step_static: Q * beam * beam survivors (value and label) at most kStaticCands of each, e.g. 256
+// sentences at beam 16.  512 KiB of every device the library runs on, held until the process ends.
+constexpr uint64_t kStaticCands = 1u << 16;
+constexpr int kStaticDevices = 64;
+static __device__ __align__(256) unsigned char scratch[2 * kStaticCands * 4];
+std::mutex g_static_mu;
+void* g_static_ptr[kStaticDevices] = {};   // device address of `scratch` per device, from hipGetSymbolAddress
 
 // (value, index) pairs ordered by larger value first, then smaller index: `better(a, b)` = a comes before b
 struct Cand { float v; int i; };
@@ -225,22 +234,9 @@ int lstm_beam_query(int Q, int beam, int V, uint64_t* workspace_bytes) {
   return LSTM_OK;
 }
 
-int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out, int32_t* src,
-                   int32_t* label, void* workspace, uint64_t workspace_bytes, void* stream) {
-  if (!logits || !score_in || !score_out || !src || !label || !workspace) return LSTM_ERR_NULL;
-  int rc = beam_dims(Q, beam, V);
-  if (rc) return rc;
-  if (ld < V) return LSTM_ERR_DIM;
-  if (((uintptr_t)logits | (uintptr_t)score_in | (uintptr_t)score_out | (uintptr_t)src | (uintptr_t)label) & 3) return LSTM_ERR_ALIGN;
-  uint64_t need = 0;
-  lstm_beam_query(Q, beam, V, &need);
-  if (workspace_bytes < need) return LSTM_ERR_SIZE;
-  if (Q == 0) return LSTM_OK;
-  if ((rc = device_ok())) return rc;
-  hipStream_t st = (hipStream_t)stream;
-  char* ws = (char*)(((uintptr_t)workspace + 255) / 256 * 256);
-  float* cand_val = (float*)ws;
-  int* cand_lab = (int*)(ws + ((size_t)Q * beam * beam * 4 + 255) / 256 * 256);
+// both kernels of a step; cand_val / cand_lab hold Q * beam * beam entries each
+static int beam_launch(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out, int32_t* src,
+                       int32_t* label, float* cand_val, int* cand_lab, hipStream_t st) {
   // a lane's list holds as many entries as the beam asks for (in the worst case all of the row's best lie in one lane)
   if (beam <= 4) hipLaunchKernelGGL(beam_row_kernel<4>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
   else if (beam <= 8) hipLaunchKernelGGL(beam_row_kernel<8>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
@@ -249,6 +245,59 @@ int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, cons
   hipLaunchKernelGGL(beam_merge_kernel, dim3(Q), dim3(64), 0, st, cand_val, cand_lab, score_out, src, label, V, beam);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
   return LSTM_OK;
+}
+
+static int beam_step_args(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out, int32_t* src,
+                          int32_t* label) {
+  if (!logits || !score_in || !score_out || !src || !label) return LSTM_ERR_NULL;
+  const int rc = beam_dims(Q, beam, V);
+  if (rc) return rc;
+  if (ld < V) return LSTM_ERR_DIM;
+  if (((uintptr_t)logits | (uintptr_t)score_in | (uintptr_t)score_out | (uintptr_t)src | (uintptr_t)label) & 3) return LSTM_ERR_ALIGN;
+  return LSTM_OK;
+}
+
+int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out, int32_t* src,
+                   int32_t* label, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!workspace) return LSTM_ERR_NULL;
+  int rc = beam_step_args(Q, beam, V, logits, ld, score_in, score_out, src, label);
+  if (rc) return rc;
+  uint64_t need = 0;
+  lstm_beam_query(Q, beam, V, &need);
+  if (workspace_bytes < need) return LSTM_ERR_SIZE;
+  if (Q == 0) return LSTM_OK;
+  if ((rc = device_ok())) return rc;
+  char* ws = (char*)(((uintptr_t)workspace + 255) / 256 * 256);
+  float* cand_val = (float*)ws;
+  int* cand_lab = (int*)(ws + ((size_t)Q * beam * beam * 4 + 255) / 256 * 256);
+  return beam_launch(Q, beam, V, logits, ld, score_in, score_out, src, label, cand_val, cand_lab, (hipStream_t)stream);
+}
+
+// The same step for callers that cannot allocate: the survivors of the rows (the only scratch of the step) go to a
+// device array that is part of the library's image.  Its address on each device is looked up once, with that device
+// current, and kept; host code never uses the array's name for anything else.
+int lstm_beam_step_static(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out,
+                          int32_t* src, int32_t* label, void* stream) {
+  int rc = beam_step_args(Q, beam, V, logits, ld, score_in, score_out, src, label);
+  if (rc) return rc;
+  if ((uint64_t)Q * beam * beam > kStaticCands) return LSTM_ERR_SIZE;
+  if (Q == 0) return LSTM_OK;
+  if ((rc = device_ok())) return rc;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticDevices) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  char* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+      g_static_ptr[dev] = p;
+    }
+    base = (char*)g_static_ptr[dev];
+  }
+  // every entry the merge reads is written by the row kernel of the same call: nothing has to be cleared
+  return beam_launch(Q, beam, V, logits, ld, score_in, score_out, src, label, (float*)base, (int*)(base + kStaticCands * 4),
+                     (hipStream_t)stream);
 }
 
 int lstm_beam_gather(int elem_bytes, int Q, int beam, int width, const void* in, int64_t ld_in, const int32_t* src, void* out,

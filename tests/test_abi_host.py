@@ -170,6 +170,12 @@ def test_beam_argument_errors():
     for k in ("lg", "si", "so", "src", "lab", "ws"):
         assert st(**{k: None}) == -1, k
     assert st(ld=9) == -2 and st(Q=-1) == -2 and st(beam=17) == -4 and st(lg=P + 2) == -5 and st(wsb=8) == -6 and st(Q=0) == 0
+    # the variant with the library's own scratch array: same argument checks, and a size limit instead of a workspace
+    ss = lambda Q=4, beam=3, V=10, lg=P, ld=10, si=P, so=P, src=P, lab=P: L.lstm_beam_step_static(Q, beam, V, lg, ld, si, so, src, lab, None)
+    for k in ("lg", "si", "so", "src", "lab"):
+        assert ss(**{k: None}) == -1, k
+    assert ss(ld=9) == -2 and ss(Q=-1) == -2 and ss(beam=17) == -4 and ss(lg=P + 2) == -5 and ss(Q=0) == 0
+    assert ss(Q=257, beam=16) == -6 and ss(Q=65537, beam=1) == -6
     ga = lambda eb=4, Q=4, beam=3, w=8, i=P, ldi=8, src=P, o=P + 4096, ldo=8: L.lstm_beam_gather(eb, Q, beam, w, i, ldi, src, o, ldo, None)
     assert ga(i=None) == -1 and ga(src=None) == -1 and ga(o=None) == -1
     assert ga(w=0) == -2 and ga(ldi=7) == -2 and ga(ldo=7) == -2 and ga(eb=3) == -4 and ga(o=P) == -4 and ga(i=P + 2) == -5 and ga(Q=0) == 0
