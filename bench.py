@@ -67,7 +67,13 @@ class Stack:
         for bf in self.bufs:
             bf["desc"].workspace_bytes = wmax
 
-    def step(self):
+    def verify(self):
+        """A bounded wait that expires inside a single-launch recurrent kernel leaves invalid results behind a call that
+        returned LSTM_OK (and a drained step is FASTER): the word that says so is checked here (synchronises)."""
+        if self.Bn.sync_status(self.ws):
+            raise RuntimeError("a bounded wait expired inside a recurrent kernel: the timed results are invalid")
+
+    def step(self, check=False):
         Bn, ct = self.Bn, self.ct
         s = torch.cuda.current_stream().cuda_stream
         cur = self.x
@@ -76,6 +82,8 @@ class Stack:
                                   self.lens.data_ptr(), bf["y"].data_ptr(), bf["c"].data_ptr(), None, None,
                                   bf["reserve"].data_ptr(), self.ws.data_ptr(), s)
             assert rc == 0, Bn.strerror(rc)
+            if check:
+                self.verify()
             cur = bf["y"]
         d = self.dy
         for k in range(len(self.layers) - 1, -1, -1):
@@ -87,6 +95,8 @@ class Stack:
                                   d.data_ptr(), None, None, bf["dx"].data_ptr(), bf["dW_x"].data_ptr(), bf["dW_h"].data_ptr(),
                                   bf["db"].data_ptr(), None, None, self.ws.data_ptr(), s)
             assert rc == 0, Bn.strerror(rc)
+            if check:
+                self.verify()
             d = bf["dx"]
 
 
@@ -119,7 +129,9 @@ class MixedStack:
         for bf in self.bufs:
             bf["desc"].workspace_bytes = wmax
 
-    def step(self):
+    verify = Stack.verify
+
+    def step(self, check=False):
         lib, ct = self.Bn.lib, self.ct
         s = torch.cuda.current_stream().cuda_stream
         for (Wx, Wh, b), bf in zip(self.layers, self.bufs):
@@ -128,6 +140,8 @@ class MixedStack:
                     self.lens.data_ptr(), bf["y"].data_ptr(), bf["c"].data_ptr(), None, None, bf["reserve"].data_ptr(),
                     self.ws.data_ptr(), s)
             assert rc == 0, self.Bn.strerror(rc)
+            if check:
+                self.verify()
         d = self.dy
         for k in range(len(self.layers) - 1, -1, -1):
             Wx, Wh, b = self.layers[k]
@@ -137,6 +151,8 @@ class MixedStack:
                     bf["y"].data_ptr(), bf["c"].data_ptr(), bf["reserve"].data_ptr(), d.data_ptr(), None, None, bf["dx"].data_ptr(),
                     bf["dW_x"].data_ptr(), bf["dW_h"].data_ptr(), bf["db"].data_ptr(), None, None, self.ws.data_ptr(), s)
             assert rc == 0, self.Bn.strerror(rc)
+            if check:
+                self.verify()
             d = bf["dx"]
 
 
@@ -159,18 +175,20 @@ def bench_mixed(args, Bn, synth):
     dt = time.perf_counter() - t0
     Bn.profile_enable(False)
     prof = Bn.profile_read()
+    st.verify()                       # the last call of the timed region
+    st.step(check=True)               # and one untimed step with the word checked behind every call
     T, B, n, nl = inp["T"], cfg["B"], cfg["n"], cfg["layers"]
-    # recurrent loops: algorithmic HBM bytes of one time step of ONE direction (as for the bidirectional stacks);
-    # the stack runs (nl + 1) directions' worth of time steps per pass
-    fwd_dir_bytes = 2 * B * 4 * n * 4 + B * n * 4 + B * n * 2
-    bwd_dir_bytes = B * 4 * n * 4 + 2 * B * n * 4 + B * n * 2 + B * 4 * n * 2
-    dir_steps = args.steps * (nl + 1) * T
+    # recurrent loops: algorithmic HBM bytes per REAL frame of one row and ONE direction (as for the bidirectional stacks;
+    # padded frames are skipped by the kernels and not counted); the stack runs (nl + 1) directions over `frames` frames
+    fwd_row_bytes = 2 * 4 * n * 4 + n * 4 + n * 2
+    bwd_row_bytes = 4 * n * 4 + 2 * n * 4 + n * 2 + 4 * n * 2
     def loop(phase, by, name):
         ms, launches = prof[phase]
-        gbs = by * dir_steps / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        total = by * frames * (nl + 1) * args.steps
+        gbs = total / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         return {"bound": "hbm", "kernel": name, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                 "traffic": None, "launches": int(launches), "avg_launch_ms": ms / max(launches, 1),
-                "us_per_layer_time_step": ms * 1e3 / (args.steps * nl * T), "algorithmic_bytes_per_direction_time_step": by}
+                "us_per_layer_time_step": ms * 1e3 / (args.steps * nl * T), "algorithmic_bytes_per_row_frame_direction": by}
     out = {
         "metric": "encoder fwd+bwd frames/sec (n=%d), 1 bidirectional + %d unidirectional layers" % (n, nl - 1),
         "value": frames * args.steps / dt, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -179,8 +197,8 @@ def bench_mixed(args, Bn, synth):
         "config": {"workload": "config 7: 1 BLSTM layer + %d LSTM layers, n_in=%d, n=%d, B=%d, seq_lens~U{%d..%d} (T=%d, %d real frames), "
                                "bf16 storage / f32 state, forward + backward" % (nl - 1, cfg["n_in"], n, B, cfg["len_lo"], cfg["len_hi"], T, frames)},
         "useful_tflops": flops * args.steps / dt / 1e12,
-        "roofline": loop("loop_bwd", bwd_dir_bytes, "backward recurrent loops"),
-        "roofline_forward_loop": loop("loop_fwd", fwd_dir_bytes, "forward recurrent loops"),
+        "roofline": loop("loop_bwd", bwd_row_bytes, "backward recurrent loops"),
+        "roofline_forward_loop": loop("loop_fwd", fwd_row_bytes, "forward recurrent loops"),
         "phases_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
     }
     print(json.dumps(out))
@@ -384,7 +402,7 @@ def bench_decoder_attention(args, Bn, synth):
 
 
 def bench_search_step(args, Bn, synth):
-    """--config 9: one complete step of the batched beam search (Sec. 4; Listing 1): cell, attention, readout, output
+    """--config 9: one complete step of the batched beam search (Sec. 3, Table 2; Listing 1): cell, attention, readout, output
     layer over V = 20000 labels, beam step, state gather and target embedding, for 64 sentences x beam 12, with no host
     round trip between the steps: the labels and hypotheses chosen in step i feed step i+1 on the device.  One "step" is a
     block of 50 dependent search steps; the figure of merit is the latency of one search step."""
@@ -699,38 +717,48 @@ def main():
     dt = time.perf_counter() - t0
     Bn.profile_enable(False)
     prof = Bn.profile_read()
+    st.verify()                       # the last call of the timed region
+    st.step(check=True)               # and one untimed step with the word checked behind every call
 
     ms_per_step = dt / args.steps * 1e3
     T, B, n = inp["T"], cfg["B"], cfg["n"]
     esz = 2 if cfg["dtype"] == "bf16" else 4
     nl = cfg["layers"]
-    # Algorithmic HBM bytes of ONE recurrent time step, both directions, W_h resident on chip:
-    #   forward : read Zx_t (B*4n*4), write gate activations (B*4n*4), c_t (B*n*4), y_t (B*n*esz); c_{t-1} stays on chip
-    #   backward: read gate activations (B*4n*4), c_t and c_{t-1} (2*B*n*4), dy_t (B*n*esz); write dz_t (B*4n*esz)
-    fwd_step_bytes = 2 * (2 * B * 4 * n * 4 + B * n * 4 + B * n * esz)
-    bwd_step_bytes = 2 * (B * 4 * n * 4 + 2 * B * n * 4 + B * n * esz + B * 4 * n * esz)
+    # Algorithmic HBM bytes of the recurrent loops, W_h resident on chip, per REAL frame of one row and one direction
+    # (the kernels skip padded frames, and so does this count):
+    #   forward : read Zx_t (4n*4), write gate activations (4n*4), c_t (n*4), y_t (n*esz); c_{t-1} stays on chip
+    #   backward: read gate activations (4n*4), c_t and c_{t-1} (2*n*4), dy_t (n*esz); write dz_t (4n*esz)
+    # A launch (one layer, both directions) touches `frames` real frames per direction and walks T time steps.
+    fwd_row_bytes = 2 * 4 * n * 4 + n * 4 + n * esz
+    bwd_row_bytes = 4 * n * 4 + 2 * n * 4 + n * esz + 4 * n * esz
     steps_total = args.steps * nl * T
-
-    def loop_roofline(phase, step_bytes, name):
-        ms, launches = prof[phase]
-        per_launch_ms = ms / max(launches, 1)
-        steps_per_launch = steps_total / max(launches, 1)
-        achieved = step_bytes * steps_per_launch / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
-        return {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "launches": int(launches),
-                "avg_launch_ms": per_launch_ms, "us_per_time_step": ms * 1e3 / max(steps_total, 1),
-                "algorithmic_bytes_per_time_step": step_bytes}
-
-    roof_bwd = loop_roofline("loop_bwd", bwd_step_bytes, "backward recurrent loop (both directions, one launch per layer)")
-    roof_fwd = loop_roofline("loop_fwd", fwd_step_bytes, "forward recurrent loop (both directions, one launch per layer)")
+    traffic = {}
     try:   # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as fh:
             tr = json.load(fh)
         if tr.get("workload") == "config %d" % args.config:
-            roof_bwd["traffic"] = tr.get("persist_bwd_bytes_per_launch")
-            roof_fwd["traffic"] = tr.get("persist_fwd_bytes_per_launch")
+            traffic = {"loop_bwd": tr.get("persist_bwd_bytes_per_launch"), "loop_fwd": tr.get("persist_fwd_bytes_per_launch")}
     except (OSError, ValueError):
         pass
+
+    def loop_roofline(phase, row_bytes, name):
+        ms, launches = prof[phase]
+        per_launch_ms = ms / max(launches, 1)
+        launch_bytes = row_bytes * frames * 2                      # both directions, real frames only
+        achieved = launch_bytes / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        padded = row_bytes * T * B * 2 / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        step_bytes = launch_bytes / T
+        tr_bytes = traffic.get(phase)
+        return {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": tr_bytes,
+                "traffic_ratio": (tr_bytes / launch_bytes) if tr_bytes else None, "launches": int(launches),
+                "avg_launch_ms": per_launch_ms, "us_per_time_step": ms * 1e3 / max(steps_total, 1),
+                "step_roofline_us": step_bytes / (HBM_PEAK_GBS * 1e9) * 1e6,
+                "algorithmic_bytes_per_launch": launch_bytes, "algorithmic_bytes_per_time_step": step_bytes,
+                "frac_counting_padded_frames": padded / HBM_PEAK_GBS}
+
+    roof_bwd = loop_roofline("loop_bwd", bwd_row_bytes, "backward recurrent loop (both directions, one launch per layer)")
+    roof_fwd = loop_roofline("loop_fwd", fwd_row_bytes, "forward recurrent loop (both directions, one launch per layer)")
     # hoisted products: algorithmic flops per benchmark step (the products run over the real frames only)
     gemm_flops = {"gemm_zx": 0.0, "gemm_dx": 0.0, "gemm_dwx": 0.0, "gemm_dwh": 0.0}
     for l in range(nl):
@@ -739,6 +767,7 @@ def main():
         gemm_flops["gemm_dx"] += 2.0 * frames * ni * 8 * n
         gemm_flops["gemm_dwx"] += 2.0 * frames * ni * 8 * n
         gemm_flops["gemm_dwh"] += 2.0 * frames * n * 8 * n
+    per_product = {k: (v * args.steps / (prof[k][0] * 1e-3) / 1e12 if prof[k][0] > 0 else 0.0) for k, v in gemm_flops.items()}
     gemm_ms = sum(prof[k][0] for k in gemm_flops)
     gemm_tflops = sum(gemm_flops.values()) * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     mfma_peak = BF16_PEAK_TFLOPS if esz == 2 else 157.3
@@ -757,7 +786,7 @@ def main():
         "roofline": dominant,
         "roofline_forward_loop": roof_fwd if dominant is roof_bwd else roof_bwd,
         "roofline_hoisted_gemms": {"bound": "mfma", "achieved": gemm_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
-                                   "frac": gemm_tflops / mfma_peak,
+                                   "frac": gemm_tflops / mfma_peak, "tflops_per_product": per_product,
                                    "note": "flops of the four hoisted products per layer over the real frames; the operand "
                                            "transposes and the frame map are inside the timed phases"},
         "phases_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},

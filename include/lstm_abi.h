@@ -33,11 +33,13 @@
  *     are bfloat16; b, c, h0, c0, hT, cT, dhT, dcT, dh0, dc0, dW_x, dW_h, db are float.  All
  *     accumulation, the cell state and the gate activations are float in both modes.
  *   - Optional pointers (may be NULL): b (zero bias), h0, c0 (zero state), seq_lens (all rows
- *     have length T), hT, cT, c, dhT, dcT (zero), dx, dh0, dc0 (not produced).
+ *     have length T), hT, cT, dhT, dcT (zero), dx, dh0, dc0 (not produced); c only with LSTM_FLAG_INFERENCE
+ *     (the backward call reads it).
  *   - seq_lens is int32[B] in device memory, any order; values are clamped to [0, T] in the kernels.
  *   - Return value: 0 on success, a negative lstm_status otherwise.  Arguments are validated on
  *     the host before the first HIP call, so every argument error is reported without a GPU.
- *     Nothing throws or aborts across this boundary.
+ *     Nothing throws or aborts across this boundary.  LSTM_OK says that the work was enqueued; it does not cover
+ *     a bounded wait inside a single-launch recurrent kernel that expires later on the device (see lstm_sync_status).
  */
 #ifndef MI355X_LSTM_ABI_H
 #define MI355X_LSTM_ABI_H
@@ -93,9 +95,9 @@ int lstm_query(const lstm_desc* desc, int bidirectional, size_t* reserve_bytes, 
 /* Forward pass of one direction (Listing 1, "rec"/"nativelstm2" with "direction").
  *   x[T,B,n_in]  W_x[n_in,4n]  W_h[n,4n]  b[4n]  h0,c0[B,n]  seq_lens[B]
  *   -> y[T,B,n] (0 at padded frames), c[T,B,n] (cell state after each frame, carried at padded
- *      frames; may be NULL), hT,cT[B,n] (state after each row's last processed valid frame),
+ *      frames; may be NULL with LSTM_FLAG_INFERENCE only), hT,cT[B,n] (state after each row's last processed valid frame),
  *      reserve (opaque: gate activations and the hidden state entering each frame).
- * With T == 1 and LSTM_FLAG_INFERENCE this is the stepped decoder cell (Sec. 5, Listing 1: the decoder's
+ * With T == 1 and LSTM_FLAG_INFERENCE this is the stepped decoder cell (Sec. 7, Listing 1: the decoder's
  * recurrent unit, stepped once per output word for all beam entries): feed hT,cT back as h0,c0.  For
  * bfloat16 storage that step runs as one product [x_t | h] [W_x ; W_h] + b over all rows followed by the
  * cell update; pass LSTM_FLAG_WEIGHTS_PACKED from the second step on to keep the packed weights. */
@@ -144,7 +146,7 @@ int lstm_gemm(int in_bf16, int out_bf16, int a_kcontig, int b_kcontig, int M, in
               const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const float* bias,
               int accumulate, const int32_t* lens, int Bt, int T, void* stream);
 
-/* Max-pooling in time between encoder layers.  The paper's attention-based speech encoder (Sec. 8, the
+/* Max-pooling in time between encoder layers.  The paper's attention-based speech encoder (Sec. 4, the
  * attention model on Switchboard: six bidirectional layers, a maximum taken over time between them, the
  * input shortened by a factor of 8 in total) pools the layer outputs over time; window, stride and padding
  * are not given.  This library's reading: non-overlapping windows of
@@ -219,7 +221,7 @@ int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, co
                  const void* att, int64_t ld_att, int E, const void* W_r, const float* b_r, void* out, int64_t ld_out,
                  void* workspace, uint64_t workspace_bytes, void* stream);
 
-/* One step of batched beam search, entirely on the device (Sec. 4: the decoder is a batched beam search that runs on
+/* One step of batched beam search, entirely on the device (Sec. 3 and Table 2: the decoder is a batched beam search that runs on
  * the GPU, beam size 12; Listing 1: "output_prob" is a softmax over the labels, "output" chooses from it, "trg" embeds
  * the choice).  The paper gives no further detail; this library's reading, with q a sentence, b one of its `beam`
  * hypotheses (row r = q * beam + b of the decoder batch) and v a label:

@@ -23,12 +23,12 @@ lstm_oracle.lstm_fwd with T = 1.
 
 Readings (conventions of this repository; the listing fixes none of them):
   * the decoder batch holds `beam` hypotheses per sentence, those of one sentence next to each other: q(r) = r // beam
-    (Sec. 5 uses beam 12);
+    (Sec. 3, Table 2: beam 12);
   * accum has one number per source position (the listing's "accum_a" adds the weights, which have one), so
     "weight_feedback" is a linear map from 1 to A values: a weight vector w_fb[A] and a bias b_fb[A];
   * positions j >= src_lens[q] take no part: a, accum' and the sum for att are 0 there, values stored there in ctx, H or
     accum are never read; a sentence of length 0 gives a = 0, att = 0;
-  * Sec. 5 mentions an inverse form of the fertility feedback; the listing, which is what is built here, feeds the
+  * Sec. 4 mentions an inverse form of the fertility feedback; the listing, which is what is built here, feeds the
     plain accumulated weights back.
 
 Pins (tests/test_decoder_oracle_pins.py): closed forms (v = 0 gives uniform weights and att = mean of the valid encoder
@@ -96,7 +96,7 @@ def readout(s, trg, att, W_r, b_r):
 
 
 # ---- one step of batched beam search -------------------------------------------------------------------------------
-# The paper decodes with a batched beam search that runs on the GPU, beam size 12 (Sec. 4, the decoding-speed table
+# The paper decodes with a batched beam search that runs on the GPU, beam size 12 (Sec. 3, Table 2, the decoding-speed table
 # and the paragraph before it); it gives no further detail.  Listing 1 supplies the pieces around it: "output_prob" is a
 # softmax over the labels computed from "readout", "output" chooses labels from it, and "trg" embeds the chosen label
 # for the next step.  Reading of this repository for one step, with q a sentence, b one of its `beam` hypotheses

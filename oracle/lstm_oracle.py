@@ -192,7 +192,7 @@ def blstm_bwd(x, W_x, W_h, b, h0, c0, seq_lens, dy, dhT=None, dcT=None):
 
 
 def blstm_stack_fwd(x, layers, seq_lens):
-    """Stack of bidirectional layers (Sec. 5: every encoder layer is bidirectional, so layer k>1
+    """Stack of bidirectional layers (Sec. 4: every encoder layer is bidirectional, so layer k>1
     sees 2n inputs).  layers = list of dicts with W_x[2,n_in_k,4n], W_h[2,n,4n], b[2,4n] (or None).
     Initial states are zero.  -> list of per-layer inputs, final y."""
     acts = []
@@ -217,7 +217,7 @@ def blstm_stack_bwd(acts, layers, seq_lens, dy_top):
 
 
 # ---- encoders that mix bidirectional and unidirectional layers --------------------------------------------------
-# The translation encoder of the paper's speed comparison (Sec. 4, caption of the training-speed table; Sec. 5 for the
+# The translation encoder of the paper's speed comparison (Sec. 3, caption of Table 1, the training-speed table; Sec. 4 for the
 # comparison system) has one bidirectional layer at the bottom and 3 or 5 unidirectional layers above it.  A layer is
 # bidirectional here when its weights carry two directions (W_x[2, n_in, 4n]) and runs forward in time when they carry
 # one (W_x[1, n_in, 4n]); the layer above a bidirectional one sees 2n inputs, the layer above a unidirectional one n.
@@ -257,7 +257,7 @@ def encoder_stack_bwd(acts, layers, seq_lens, dy_top):
 
 
 # ---- max-pooling in time between encoder layers ---------------------------------------------------------------
-# The paper's attention-based speech encoder (Sec. "Speech recognition experiments", Switchboard attention model)
+# The paper's attention-based speech encoder (Sec. 4, the attention model on Switchboard)
 # takes a maximum over time between its six bidirectional layers, which shortens the input by a factor of 8 in
 # total; window, stride and the treatment of padding are not given.  Reading of this repository:
 # non-overlapping windows of `pool` consecutive frames (stride = window; 2 after each of three layers gives the

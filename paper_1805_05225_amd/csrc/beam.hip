@@ -1,4 +1,4 @@
-// One step of batched beam search on the device (Sec. 4: decoding is a batched beam search that runs on the GPU, beam
+// One step of batched beam search on the device (Sec. 3, Table 2: decoding is a batched beam search that runs on the GPU, beam
 // size 12; Listing 1: "output_prob" softmax over the labels, "output" chooses, "trg" embeds the choice):
 //
 //     cand[q, b, v] = score[q, b] + logits[r, v] - logsumexp(logits[r, :]),  r = q * beam + b

@@ -8,15 +8,8 @@
 // once by `launch_transpose` below - a bandwidth-bound pass that costs a few percent of the product
 // it feeds - instead of being transposed on the fly inside the MFMA loop.
 //
-// Two kernels share the tile raster and the epilogue: gemm_dl8_* (K a multiple of 8: operands loaded straight into
-// LDS, eight wavefronts; described where it is defined) and gemm_nt_kernel (any K a multiple of 8), which follows.
-//
-// gemm_nt_kernel: 256x256 output tile per work-group of 4 wavefronts (2x2), each wavefront a 128x128
-// sub-tile = 4x4 MFMA 32x32x16 blocks (256 accumulator registers).  K advances 64 at a time through
-// two LDS stages (rows of 128 bytes + 16 bytes padding; 144 KiB of the 160 KiB LDS).  Global loads run two
-// stages ahead of the MFMAs (one stage in registers, one in LDS); fragments are double-buffered in registers.
-// Per 16-wide k step a wavefront issues 8 LDS reads for 16 MFMAs, half the LDS bandwidth a 128x128
-// work-group tile would need.
+// gemm_dl8_* (operands loaded straight into LDS, eight wavefronts; described where it is defined) serves every K that
+// is a multiple of 8; gemm_tn8_f32 serves the k-major operand pair of the weight gradients.
 #include "common.h"
 #include <algorithm>
 
@@ -25,9 +18,6 @@ namespace {
 
 constexpr int kT = 256;                   // tile edge (both M and N)
 constexpr int kKB = 64;                   // k per stage (bf16 elements)
-constexpr int kStride = 144;              // LDS row stride in bytes
-constexpr int kOpBytes = kT * kStride;    // one operand, one stage
-constexpr int kThreads = 256;
 constexpr int kSupM = 8, kSupN = 4;   // tiles per XCD-resident block (kSupM * kSupN = 32 CUs)
 
 struct NtArgs {
@@ -52,45 +42,6 @@ __device__ __forceinline__ f32x16 mma(uint4 a, uint4 b, f32x16 c) {
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
-
-// One operand of one stage: 256 rows x 8 chunks of 16 bytes; thread handles chunks tid + 256*i, i < 8.
-// Loads go through a buffer descriptor covering exactly the operand's rows: rows past the end read as zero
-// in hardware, so only the K tail needs a mask (and only in the last stage of a segment).
-struct OperandLoader {
-  __amdgpu_buffer_rsrc_t rs;
-  unsigned voff[8];                     // byte offset of chunk i at k = 0
-  int kc8;                              // first k of this thread's chunk inside a stage
-  // `rows` logical rows; with a row map, logical row r lives at physical row map[r] (< phys_rows)
-  __device__ __forceinline__ void init(const char* base, long ld, int rows, int row0, int tid, const int* map = nullptr,
-                                       int phys_rows = 0) {
-    const long bytes = (long)(map ? phys_rows : rows) * ld * 2;
-    rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, bytes > 0x7fffffffL ? 0x7fffffff : (int)bytes, kBufFlags);
-    kc8 = (tid & 7) * 8;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      long row = row0 + ((tid + kThreads * i) >> 3);
-      if (map) row = row < rows ? (long)map[row] : 0x7fffffffL;
-      const long off = (row * ld + kc8) * 2;
-      voff[i] = (off > 0x7ffffff0L || off < 0) ? 0x7ffffff0u : (unsigned)off;   // past-the-end rows land outside the descriptor
-    }
-  }
-  template <bool TAIL>
-  __device__ __forceinline__ void fetch(uint4 (&st)[8], int k0, int K) const {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, voff[i] + k0 * 2, 0, 0);
-      const bool keep = !TAIL || k0 + kc8 < K;
-      st[i] = keep ? make_uint4(x[0], x[1], x[2], x[3]) : make_uint4(0, 0, 0, 0);
-    }
-  }
-};
-__device__ __forceinline__ void commit(const uint4 (&st)[8], char* lds, int tid) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int c = tid + kThreads * i;
-    *(uint4*)(lds + (c >> 3) * kStride + (c & 7) * 16) = st[i];
-  }
-}
 
 // What every kernel variant needs to know about its tile.
 struct TileCoord { int M, K, m0, n0, z, ks, ksplit, pos; bool live; };
@@ -211,108 +162,6 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][TN], char* lds, cons
       }
     }
   }
-}
-
-template <typename TC>
-__global__ __launch_bounds__(kThreads, 1) void gemm_nt_kernel(NtArgs g) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];   // [stage][A | B]
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int r = lane & 31, gq = lane >> 5;
-
-  const TileCoord tc = tile_coord(g);
-  if (!tc.live) return;
-  const int M = tc.M, K = tc.K, m0 = tc.m0, n0 = tc.n0, z = tc.z, ks = tc.ks, ksplit = tc.ksplit;
-
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const int ktiles = (K + kKB - 1) / kKB;
-  const bool ktail = (K % kKB) != 0;
-  const int nstage = ktiles * g.nseg;
-  // stages [it0, it0 + total) belong to this work-group (all of them unless K is split)
-  const int it0 = (int)((long)nstage * ks / ksplit);
-  const int total = (int)((long)nstage * (ks + 1) / ksplit) - it0;
-  OperandLoader la, lb;
-  int seg_loaded = -1;
-  uint4 sa[8], sb[8];
-  // stage `it`: segment it / ktiles, k offset (it % ktiles) * 64
-  auto fetch_a = [&](int rel_it) {
-    const int it = it0 + rel_it;
-    const int seg = it / ktiles, kt = it - seg * ktiles;
-    if (seg != seg_loaded) {
-      la.init(g.A + (g.sAz * z + g.sAseg * seg) * 2, g.lda, M, m0, tid, g.a_rows, g.a_phys_rows);
-      lb.init(g.B + (g.sBz * z + g.sBseg * seg) * 2, g.ldb, g.N, n0, tid);
-      seg_loaded = seg;
-    }
-    if (ktail && kt == ktiles - 1) la.fetch<true>(sa, kt * kKB, K); else la.fetch<false>(sa, kt * kKB, K);
-  };
-  auto fetch_b = [&](int rel_it) {
-    const int it = it0 + rel_it;
-    const int seg = it / ktiles, kt = it - seg * ktiles;
-    if (ktail && kt == ktiles - 1) lb.fetch<true>(sb, kt * kKB, K); else lb.fetch<false>(sb, kt * kKB, K);
-  };
-  // prologue: stage 0 into LDS buffer 0, stage 1 into registers
-  if (total > 0) {
-    fetch_a(0); fetch_b(0);
-    commit(sa, lds, tid);
-    commit(sb, lds + kOpBytes, tid);
-    if (total > 1) { fetch_a(1); fetch_b(1); }
-  }
-  __syncthreads();
-
-  // Main loop.  While stage `it` is multiplied out of LDS buffer it&1: the registers holding stage it+1 are
-  // written to the other buffer (k-steps 0-1), then the loads of stage it+2 are issued (k-steps 2-3), so every
-  // global load has a whole stage of MFMAs to complete.  Fragments for k-step s+1 are read from LDS while
-  // the 16 MFMAs of step s run; the scheduling barriers keep the compiler from collapsing that overlap.
-  // (Moving the barrier to mid-stage and pre-reading the next stage's first fragments measured slower.)
-  for (int it = 0; it < total; ++it) {
-    const int cur = it & 1;
-    const char* As = lds + cur * 2 * kOpBytes + (wm * 128 + r) * kStride + gq * 16;
-    const char* Bs = lds + cur * 2 * kOpBytes + kOpBytes + (wn * 128 + r) * kStride + gq * 16;
-    char* nxt = lds + (cur ^ 1) * 2 * kOpBytes;
-    uint4 fa[2][4], fb[2][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      fa[0][i] = *(const uint4*)(As + i * 32 * kStride);
-      fb[0][i] = *(const uint4*)(Bs + i * 32 * kStride);
-    }
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int c = s & 1;
-      if (s < 3) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          fa[c ^ 1][i] = *(const uint4*)(As + i * 32 * kStride + (s + 1) * 32);
-          fb[c ^ 1][i] = *(const uint4*)(Bs + i * 32 * kStride + (s + 1) * 32);
-        }
-      }
-      if (it + 1 < total) {
-        if (s == 0) commit(sa, nxt, tid);
-        if (s == 1) commit(sb, nxt + kOpBytes, tid);
-      }
-      if (it + 2 < total) {
-        if (s == 2) fetch_a(it + 2);
-        if (s == 3) fetch_b(it + 2);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          acc[i][j] = mma(fa[c][i], fb[c][j], acc[i][j]);
-        }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    __syncthreads();
-  }
-
-  store_tile<TC, 4>(acc, lds, g, M, m0, n0, z, ks, ksplit);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -893,6 +742,7 @@ bool gemm_nt_ok(const GemmArgs& g) {
   const auto a16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
   const long lim = 0x7fffff00L;     // operands are addressed with 32-bit byte offsets
   if ((long)g.M * g.lda * 2 > lim || (long)g.N * g.ldb * 2 > lim) return false;
+  if (g.k_dev && g.K % 64 != 0) return false;     // a device-resident K counts whole 64-wide stages
   return g.in_bf16 && g.a_kcontig && g.b_kcontig && !g.lens && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
          g.sAz % 8 == 0 && g.sBz % 8 == 0 && g.sAseg % 8 == 0 && g.sBseg % 8 == 0 && a16(g.A) && a16(g.B);
 }
@@ -984,17 +834,7 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
     }
     return sum_parts(a, s);
   }
-  const size_t shmem = 4 * kOpBytes;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_nt_kernel<uint16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  if (g.out_bf16) hipLaunchKernelGGL(gemm_nt_kernel<uint16_t>, dim3(tiles, g.nz), dim3(kThreads), shmem, s, a);
-  else hipLaunchKernelGGL(gemm_nt_kernel<float>, dim3(tiles, g.nz * a.ksplit), dim3(kThreads), shmem, s, a);
-  return sum_parts(a, s);
+  return hipErrorInvalidValue;       // unreachable: gemm_nt_ok() refuses a device-resident K whose bound is not a multiple of 64
 }
 
 

@@ -320,9 +320,12 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         e = launch_persist_fwd(pa, s);
       }
       if (e == hipSuccess) done = true;
-      else {                                        // does not fit on the device all at once: one launch per step
+      else if (e == hipErrorCooperativeLaunchTooLarge) {   // nothing was launched (does not fit on the device all at once): one launch per step
         (void)hipGetLastError();
         if ((rc = pack_fwd(false))) return rc;
+      } else {                                      // a later batch slab failed after earlier ones ran: no second attempt on advanced state
+        (void)hipGetLastError();
+        return LSTM_ERR_HIP;
       }
     }
     if (!done) {
@@ -410,6 +413,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
   pa.xcc = (unsigned*)(ws + p.ws_sync) + 64 + 2 * (size_t)p.nrt;
   int variant = kBwdNone;
+  for (size_t d = 0; d < D; ++d) pa.d[d].lddy = (long)(D * n);       // (the choice looks at the frame sizes)
   if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2) variant = persist_bwd_variant(pa);
   const bool use_ll = variant != kBwdNone;
   {
@@ -449,7 +453,10 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       e = launch_persist_bwd(pa, variant, s);
     }
     if (e == hipSuccess) done = true;
-    else {
+    else if (e != hipErrorCooperativeLaunchTooLarge) {   // a later batch slab failed after earlier ones ran
+      (void)hipGetLastError();
+      return LSTM_ERR_HIP;
+    } else {
       (void)hipGetLastError();
       Phase ph(LSTM_PHASE_PREP, 1, s);
       HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));

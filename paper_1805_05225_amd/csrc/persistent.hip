@@ -1531,6 +1531,9 @@ int capacity(K kernel) { return fits_device(kernel, dim3(1, 1, 1)) ? capacity_of
 // further launches on the same stream: batch rows never interact, each launch walks all T steps of its rows.
 // Between launches the table in which exchange groups record their XCD is cleared again.  Returns
 // hipErrorCooperativeLaunchTooLarge without launching anything if not even one row tile fits.
+// Return values: hipSuccess; hipErrorCooperativeLaunchTooLarge = NOTHING was launched (the caller may use another
+// kernel form or the per-step path on the untouched state); any other error = a later slab failed after earlier
+// slabs had already advanced the state of their rows, so the call as a whole has failed and nothing may be re-run.
 template <typename K, typename A>
 hipError_t coop_slabs(K kernel, int grid_x, int rows_per_y, const A& a, hipStream_t s) {
   const int per_rt = 16 / rows_per_y, nrt = cdiv(a.B, 16);
@@ -1544,13 +1547,23 @@ hipError_t coop_slabs(K kernel, int grid_x, int rows_per_y, const A& a, hipStrea
     const dim3 grid(grid_x, per_rt * here, a.ndir);
     if (rt0 > 0 && a.xcc) {
       const hipError_t e = launch_fill_zero(a.xcc, (size_t)grid_x * per_rt * slab * a.ndir * 4, s);
-      if (e != hipSuccess) return e;
+      if (e != hipSuccess) return e == hipErrorCooperativeLaunchTooLarge ? hipErrorLaunchFailure : e;
     }
     void* args[] = {&copy};
     const hipError_t e = hipLaunchCooperativeKernel((const void*)kernel, grid, dim3(256), args, 0, s);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (rt0 == 0) return hipErrorCooperativeLaunchTooLarge;          // the first launch was refused: nothing has run
+      return e == hipErrorCooperativeLaunchTooLarge ? hipErrorLaunchFailure : e;
+    }
   }
   return hipSuccess;
+}
+// The kernels address a frame's arrays with 32-bit byte offsets and park idle lanes at offset 0x7ff00000: every frame
+// array (gate pre-activations [B][4n] float, outputs [B][ld] bf16) and every ring must end below that offset.
+inline bool offsets_fit(long B, long n, long ld_out, long ring_bytes) {
+  const long lim = 0x7ff00000L;
+  return B * 4 * n * 4 < lim && B * ld_out * 2 < lim && ring_bytes < lim;
 }
 template <typename K>
 bool slab_fits(K kernel, int grid_x, int rows_per_y, int ndir) {
@@ -1561,6 +1574,7 @@ bool slab_fits(K kernel, int grid_x, int rows_per_y, int ndir) {
 
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
   if (a.nkc > kLLMaxNkcFwd) return hipErrorCooperativeLaunchTooLarge;
+  if (!offsets_fit(a.B, a.n, std::max(a.d[0].ldy, a.d[a.ndir - 1].ldy), (long)cdiv(a.B, 16) * a.nkc * 1024)) return hipErrorCooperativeLaunchTooLarge;
   // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
   hipError_t e = coop_slabs(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, cdiv(cdiv(a.n, 16), 2), 8, a, s);
   if (e != hipErrorCooperativeLaunchTooLarge) return e;
@@ -1569,6 +1583,9 @@ hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
 }
 int persist_bwd_variant(const PBwdArgs& a) {
   const int t32 = cdiv(cdiv(a.n, 16), 2);
+  if (!offsets_fit(a.B, a.n, std::max(a.d[0].lddy, a.d[a.ndir - 1].lddy),
+                   std::max((long)cdiv(a.B, 16) * a.nkc * 1024, (long)bwdp_ring_bytes(a.B, a.n))))
+    return kBwdNone;
   if (a.n <= 1024 && slab_fits(persist_bwdp_kernel<8>, t32, 8, a.ndir)) return kBwdPartialSums;
   if (a.nkc > kLLMaxNkcBwd) return kBwdNone;
   if (slab_fits(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, t32, 8, a.ndir)) return kBwdDz8;

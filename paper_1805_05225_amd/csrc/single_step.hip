@@ -1,5 +1,5 @@
 // One time step of an LSTM layer for many rows at once (inference, bfloat16 storage): the stepped decoder cell,
-// whose input of a step is an embedding concatenated with a context vector (paper Sec. 5 and Listing 1: a
+// whose input of a step is an embedding concatenated with a context vector (paper Sec. 7, Listing 1: a
 // recurrent unit of 1000 cells fed by 620 + 2000 values, stepped once per output word for every beam entry).
 //
 // With T = 1 nothing can be hoisted and nothing stays resident: the step is ONE dense product

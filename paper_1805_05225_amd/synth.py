@@ -4,9 +4,9 @@ This module only draws random numbers and rounds them to the storage type; it ho
 the LSTM arithmetic.  Both the CPU oracle's tests and the HIP path's tests take their inputs
 from here, so the two sides always see identical values.
 
-The inputs stand in for the paper's WMT 2017 and Switchboard workloads (Sec. 3-5), which are
+The inputs stand in for the paper's WMT 2017 and Switchboard workloads (Sec. 3-4), which are
 not available: only their shapes are used - embedding width 620, 1000 units per direction,
-six bidirectional encoder layers, decoder cell input 620 + 2000, beam 12 (Listing 1, Sec. 5).
+six bidirectional encoder layers, decoder cell input 620 + 2000, beam 12 (Listing 1; Sec. 3, Table 2).
 
 Draw order for configuration k, from torch.Generator(cpu) seeded with 18050522500 + k:
 seq_lens, x, then per layer and per direction W_x, W_h, b, then h0, c0, dy.
@@ -90,7 +90,7 @@ def flops_fwd_bwd(inp):
 
 
 # ---- one step of the attention decoder (Listing 1: 620-wide target embedding, 1000-wide cell, attention and readout,
-# 2000-wide encoder states; Sec. 5: beam 12) ------------------------------------------------------------------------
+# 2000-wide encoder states; Table 2: beam 12) ------------------------------------------------------------------------
 DECODER = dict(Q=64, beam=12, len_lo=20, len_hi=80, A=1000, E=2000, n=1000, n_trg=620, R=1000, w=0.05)
 
 

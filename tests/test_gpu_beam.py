@@ -62,7 +62,8 @@ def _validate(logits, score, beam, got):
     return exact
 
 
-@pytest.mark.parametrize("Q,beam,V,seed", [(3, 4, 50, 0), (5, 12, 20000, 1), (2, 16, 32768, 2), (7, 1, 300, 3), (4, 12, 257, 4)])
+@pytest.mark.parametrize("Q,beam,V,seed", [(3, 4, 50, 0), (5, 12, 20000, 1), (2, 16, 32768, 2), (7, 1, 300, 3), (4, 12, 257, 4),
+                                           (64, 12, 20000, 5)])     # the last: the search benchmark's own size
 def test_beam_step_random(Q, beam, V, seed):
     rng = np.random.default_rng(seed)
     logits = (rng.standard_normal((Q * beam, V)) * 3).astype(np.float32)

@@ -40,7 +40,7 @@ def rnd_case(rng, T, B, n_in, n, D, lens, dt, scale=0.3, with_state=True, with_b
     return c
 
 
-def run_gpu(c, dt, bidir, direction=1, x_override=None, dy_override=None, flags=0):
+def run_gpu(c, dt, bidir, direction=1, x_override=None, dy_override=None, flags=0, poison=False):
     sq = (lambda a: a) if bidir else (lambda a: None if a is None else a[0])
     x = dev(c["x"] if x_override is None else x_override, dt)
     dy = dev(c["dy"] if dy_override is None else dy_override, dt)
@@ -48,7 +48,7 @@ def run_gpu(c, dt, bidir, direction=1, x_override=None, dy_override=None, flags=
     b, h0, c0 = dev(sq(c["b"])), dev(sq(c["h0"])), dev(sq(c["c0"]))
     dhT, dcT = dev(sq(c["dhT"])), dev(sq(c["dcT"]))
     lens = dev(c["lens"]) if c["lens"] is not None else None
-    f = Bn.forward(x, Wx, Wh, b, h0, c0, lens, bidirectional=bidir, direction=direction, flags=flags)
+    f = Bn.forward(x, Wx, Wh, b, h0, c0, lens, bidirectional=bidir, direction=direction, flags=flags, poison=poison)
     assert not Bn.sync_status(f["workspace"]), "a bounded wait expired in the forward kernel"
     g = Bn.backward(f, x, Wx, Wh, h0, c0, lens, dy, dhT, dcT)
     assert not Bn.sync_status(f["workspace"]), "a bounded wait expired in the backward kernel"
@@ -162,7 +162,9 @@ def test_padding_nan_never_reaches_results(dt):
     for b, L in enumerate(lens):
         xn[L:, b] = np.nan
         dyn[L:, b] = np.nan
-    f, g = run_gpu(c, dt, True, x_override=xn, dy_override=dyn)
+    # reserve and workspace start as all-ones bytes (NaN as float and as bfloat16): the forward pass leaves the gate
+    # pre-activations of padded frames unwritten, and nothing may ever read them
+    f, g = run_gpu(c, dt, True, x_override=xn, dy_override=dyn, poison=True)
     fo, go = run_oracle(c, True)
     compare(f, g, fo, go, TOL[dt])
 
@@ -459,27 +461,161 @@ def test_config4_first_layer_full_size():
 
 
 
-def test_config4_deeper_layer_full_size_sampled_rows():
-    """A layer k > 1 of config 4 at its full size (n_in = 2n = 2048, T = 1491, B = 32, n = 1024, bf16), i.e. the products
-    of the benchmark's five upper layers in the benchmark's launch configuration.  The oracle cannot do all 31 597 frames of
-    that shape in test time, but batch rows never interact, so it computes the two shortest rows one by one (as batches of
-    one row cut to their length) and every output that belongs to a row - y, c, hT, cT, dx - is compared for them."""
+@pytest.mark.timeout(900)
+def test_config4_deeper_layer_full_size():
+    """A layer k > 1 of config 4 at its full size (n_in = 2n = 2048, T = 1491, B = 32, n = 1024, bf16): the shape five of
+    the benchmark's six layers run, in the benchmark's launch configuration (products over the 31 597 real frames only,
+    weight gradients with K cut into ranges).  Every output, dW_x, dW_h and db included, element by element against the
+    oracle on all frames (about a minute and a half of oracle time)."""
     inp = synth.make(4, layers=1, n_in=2048)
     c = _config_case(inp)
-    lens = inp["seq_lens"]
     print("  config 4, deeper layer, full size: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
     f, g = run_gpu(c, "bf16", True)
-    for b in np.argsort(lens)[:2]:
-        L = int(lens[b])
-        one = dict(c, x=c["x"][:L, b:b + 1], dy=c["dy"][:L, b:b + 1], lens=np.array([L], dtype=np.int32))
-        fo, go = run_oracle(one, True)
-        print("  row %d (length %d)" % (b, L), flush=True)
-        check("y", f["y"][:L, b:b + 1], fo[0], TOL["bf16"])
-        check("c", f["c"][:, :L, b:b + 1], fo[1], TOL["bf16"])
-        check("hT", f["hT"][:, b:b + 1], fo[2], TOL["bf16"])
-        check("cT", f["cT"][:, b:b + 1], fo[3], TOL["bf16"])
-        check("dx", g["dx"][:L, b:b + 1], go[0], TOL["bf16"])
-        assert float(f["y"][L:, b].float().abs().max()) == 0.0 and float(g["dx"][L:, b].float().abs().max()) == 0.0
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL["bf16"])
+    lens = inp["seq_lens"]
+    b = int(np.argmin(lens))
+    assert float(f["y"][lens[b]:, b].float().abs().max()) == 0.0 and float(g["dx"][lens[b]:, b].float().abs().max()) == 0.0
+
+
+def test_config3_one_layer_full_size():
+    """Config 3's first layer at its full size (620 -> 1000 per direction, B = 64, lengths U{20..80}, bf16): 64 rows x 2
+    directions need more work-groups than the device holds at once, so this is the batch-slab launch path at the real T."""
+    inp = synth.make(3, layers=1)
+    c = _config_case(inp)
+    print("  config 3, first layer, full size: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
+    f, g = run_gpu(c, "bf16", True)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL["bf16"])
+
+
+def test_config3_upper_layer_full_size():
+    """A layer k > 1 of config 3 at its full size (n_in = 2n = 2000, n = 1000, B = 64, T = 80, bf16)."""
+    inp = synth.make(3, layers=1, n_in=2000)
+    c = _config_case(inp)
+    print("  config 3, upper layer, full size: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
+    f, g = run_gpu(c, "bf16", True)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL["bf16"])
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("k,over", [(3, dict(len_lo=8, len_hi=36)), (4, dict(len_lo=10, len_hi=40)), (7, dict(len_lo=8, len_hi=36))])
+def test_six_layer_stack_full_width(k, over):
+    """The whole depth of the three encoder stacks (six layers, the configurations' own n, n_in and B) with the lengths
+    cut to at most 40 frames so that the oracle finishes in seconds: what grows through six bfloat16 layers - the error of
+    y at the top, of dx at the bottom and of every layer's weight gradients - against the float64 oracle stack."""
+    inp = synth.make(k, **over)
+    print("  config %d, six layers: T=%d B=%d n=%d frames=%d" % (k, inp["T"], inp["cfg"]["B"], inp["cfg"]["n"], synth.real_frames(inp)), flush=True)
+    assert len(inp["layers"]) == 6
+    y, dx, grads = _stack_gpu(inp, "bf16")
+    layers = [{kk: v.astype(np.float64) for kk, v in L.items()} for L in inp["layers"]]
+    acts, yo = O.encoder_stack_fwd(inp["x"].astype(np.float64), layers, inp["seq_lens"])
+    dxo, go = O.encoder_stack_bwd(acts, layers, inp["seq_lens"], inp["dy"].astype(np.float64))
+    tol = TOL["bf16"]
+    check("y", y, yo, tol)
+    check("dx", dx, dxo, tol)
+    for l, (g, r) in enumerate(zip(grads, go)):
+        check("dW_x%d" % l, g["dW_x"], r[0], tol)
+        check("dW_h%d" % l, g["dW_h"], r[1], tol)
+        check("db%d" % l, g["db"], r[2], tol)
+
+
+@pytest.mark.parametrize("over,pool_after", [(dict(layers=3, len_lo=9, len_hi=41, B=32), (0, 1)),
+                                             (dict(layers=3, len_lo=0, len_hi=23, B=9, n=72, n_in=24), (0, 1)),
+                                             (dict(layers=2, len_lo=1, len_hi=30, B=5, n=40), (0,))])
+def test_pooled_encoder_chain(over, pool_after):
+    """The pooled encoder as a chain: bidirectional layer -> max-pooling in time (windows of 2, inside each sequence) ->
+    next layer on the pooled frames and the pooled LENGTHS the pooling call wrote on the device, and the backward chain
+    through the pooling's gradient.  Against the same chain composed of the oracle's layer and pooling functions.
+
+    The pooling decides an integer (which frame of a window holds the maximum) from floating-point values that differ
+    between the two sides by the bfloat16 rounding of y, so where two frames of a window are closer than that, either choice
+    is right.  The forward chain is compared directly (the maximum itself is continuous).  For the backward chain the HIP
+    path's choices are first checked for validity against the oracle's y (the chosen frame holds the oracle's maximum up to
+    the tolerance, and the very same frame wherever the oracle's window is decided by more than that), and the oracle's
+    backward chain then routes the gradient through those same choices."""
+    inp = synth.make(4, **over)
+    pool = 2
+    lens0 = inp["seq_lens"]
+    nl = len(inp["layers"])
+    tol = TOL["bf16"]
+    print("  pooled chain: T=%d B=%d n=%d layers=%d" % (inp["T"], inp["cfg"]["B"], inp["cfg"]["n"], nl), flush=True)
+    # HIP forward chain: the lengths of every layer come from the device array the pooling call before it wrote
+    cur_g, lens_g = dev(inp["x"], "bf16"), dev(lens0)
+    g_saved = []
+    for l, L in enumerate(inp["layers"]):
+        Wx, Wh, b = dev(L["W_x"], "bf16"), dev(L["W_h"], "bf16"), dev(L["b"])
+        f = Bn.forward(cur_g, Wx, Wh, b, None, None, lens_g, bidirectional=True, want_state=False)
+        assert not Bn.sync_status(f["workspace"])
+        rec = dict(x=cur_g, lens=lens_g, f=f, Wx=Wx, Wh=Wh, T=cur_g.shape[0])
+        if l in pool_after:
+            r = Bn.time_pool_fwd(f["y"], lens_g, pool)
+            rec.update(arg=r["arg"])
+            cur_g, lens_g = r["out"], r["lens"]
+        else:
+            cur_g = f["y"]
+        g_saved.append(rec)
+    torch.cuda.synchronize()
+    # oracle forward chain, with its own maxima; the HIP path's choices are validated against it layer by layer
+    layers = [{kk: v.astype(np.float64) for kk, v in L.items()} for L in inp["layers"]]
+    cur, lens = inp["x"].astype(np.float64), lens0.copy()
+    o_saved = []
+    for l, L in enumerate(layers):
+        y = O.blstm_fwd(cur, L["W_x"], L["W_h"], L["b"], None, None, lens)[0]
+        rec = dict(x=cur, lens=lens, T=cur.shape[0])
+        if l in pool_after:
+            out, lens_p, arg = O.time_maxpool_fwd(y, lens, pool)
+            arg_g = g_saved[l]["arg"].cpu().numpy().astype(np.int64)
+            Tp, B_, F_ = out.shape
+            valid = (np.arange(Tp)[:, None] < lens_p[None, :])[:, :, None] & np.ones((1, 1, F_), dtype=bool)
+            assert np.all(arg_g[valid] < pool)
+            tt = np.minimum(np.arange(Tp)[:, None, None] * pool + np.where(valid, arg_g, 0), y.shape[0] - 1)
+            inside = tt < np.asarray(lens)[None, :, None]                      # the chosen frame is a real frame of its row
+            assert np.all(inside[valid])
+            chosen = np.take_along_axis(y, tt, axis=0)
+            slack = 2 * tol * np.abs(y).max()
+            assert np.all(np.abs(chosen - out)[valid] <= slack), "a chosen frame does not hold the window's maximum"
+            # where the oracle's window is decided by more than the slack, the choice must be the oracle's
+            other = np.take_along_axis(y, np.minimum(np.arange(Tp)[:, None, None] * pool + (1 - np.where(valid, arg, 0)), y.shape[0] - 1), axis=0)
+            two = valid & ((np.arange(Tp)[:, None, None] * pool + 1) < np.asarray(lens)[None, :, None])
+            decided = two & (np.abs(out - other) > slack)
+            assert np.array_equal(arg_g[decided], arg[decided])
+            print("    layer %d pooling: %d of %d windows decided beyond the slack, %d choices differ from the oracle's" % (
+                l, int(decided.sum()), int(valid.sum()), int((arg_g != arg)[valid].sum())), flush=True)
+            rec.update(arg=np.where(valid, arg_g, 0), lens_p=lens_p)
+            cur, lens = out, lens_p
+        else:
+            cur = y
+        o_saved.append(rec)
+    yo_top = cur
+    assert np.array_equal(lens_g.cpu().numpy(), lens)
+    check("y top", cur_g, yo_top, tol)
+    rng = np.random.default_rng(66)
+    dy_top = torch.from_numpy(rng.standard_normal(yo_top.shape)).to(torch.bfloat16).float().numpy().astype(np.float64)
+    d = dy_top
+    o_grads = [None] * nl
+    for l in range(nl - 1, -1, -1):
+        rec, L = o_saved[l], layers[l]
+        if l in pool_after:
+            d = O.time_maxpool_bwd(d, rec["arg"], rec["lens"], pool, rec["T"])
+        g = O.blstm_bwd(rec["x"], L["W_x"], L["W_h"], L["b"], None, None, rec["lens"], d)
+        o_grads[l] = g
+        d = g[0]
+    dxo = d
+    dg = dev(dy_top, "bf16")
+    for l in range(nl - 1, -1, -1):
+        rec = g_saved[l]
+        if l in pool_after:
+            dg = Bn.time_pool_bwd(dg, rec["arg"], rec["lens"], pool, rec["T"])
+        g = Bn.backward(rec["f"], rec["x"], rec["Wx"], rec["Wh"], None, None, rec["lens"], dg, want_dstate=False)
+        assert not Bn.sync_status(rec["f"]["workspace"])
+        check("dW_x%d" % l, g["dW_x"], o_grads[l][1], tol)
+        check("dW_h%d" % l, g["dW_h"], o_grads[l][2], tol)
+        check("db%d" % l, g["db"], o_grads[l][3], tol)
+        dg = g["dx"]
+    torch.cuda.synchronize()
+    check("dx bottom", dg, dxo, tol)
 
 
 @pytest.mark.parametrize("bidir,B,n_in,n", [(False, 70, 37, 50), (True, 33, 24, 18), (False, 300, 136, 100), (False, 1, 5, 6)])

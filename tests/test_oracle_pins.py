@@ -412,7 +412,7 @@ def _mixed_layers(rng, n_in, n, n_uni):
 
 
 def test_mixed_stack_against_torch_modules():
-    """One bidirectional layer below two unidirectional ones (Sec. 4, caption of the training-speed table) against
+    """One bidirectional layer below two unidirectional ones (Sec. 3, caption of Table 1, the training-speed table) against
     torch.nn.LSTM modules chained over packed sequences: outputs and every gradient."""
     rng = np.random.default_rng(21)
     T, B, n_in, n = 7, 4, 3, 5
