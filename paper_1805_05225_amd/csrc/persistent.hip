@@ -1137,7 +1137,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   // scalar arithmetic, a lane's offset inside the frame never changes, and a lane with nothing to fetch (row past the
   // batch, unit past n, frame past the row's length) has its offset parked outside the frame and gets zeros without
   // touching memory - as does every lane when the frame itself does not exist (zero-sized descriptor).  Nothing is
-  // predicated, so every step issues the same seven loads; with loads that may or may not have been issued the
+  // predicated, so every step issues the same six loads; with loads that may or may not have been issued the
   // compiler has to assume the fewest, and made the wavefront wait for the loads of the NEXT frame, just issued and
   // on their way from HBM, where it only needed those of this one.
   constexpr unsigned kParked = 0x7ff00000u;
@@ -1159,12 +1159,15 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     In in;
     const __amdgpu_buffer_rsrc_t rg = frame_of(d.gates, t, g_bytes);
     in.gi = ld_f(rg, go, 0u); in.gf = ld_f(rg, go, 4u * n); in.gg = ld_f(rg, go, 8u * n); in.go = ld_f(rg, go, 12u * n);
-    in.c_new = ld_f(frame_of(d.cs, t, s_bytes), so, 0u);
     const int tp = d.rev ? t + 1 : t - 1;                  // the frame before t in processing order
     const bool inside = t >= 0 && tp >= 0 && tp < T, initial = t >= 0 && !inside && d.c0 != nullptr;
     const __amdgpu_buffer_rsrc_t rp = initial ? __builtin_amdgcn_make_buffer_rsrc((void*)d.c0, 0, s_bytes, kBufFlags)
                                               : frame_of(d.cs, inside ? tp : -1, s_bytes);
-    in.c_prev = ld_f(rp, so, 0u);
+    // The cell state entering frame t is the state leaving the frame before it, which is the NEXT backward step's
+    // frame: that step takes its c_new from here instead of loading it again (one load per step less).  So the value is
+    // also fetched where frame t itself is padding but the frame before it is real (direction +1, t = the row's length).
+    in.c_prev = ld_f(rp, (d.rev ? t : t - 1) < L ? s_off : kParked, 0u);
+    in.c_new = 0.f;                                        // supplied by the caller
     in.dy_bits = __builtin_amdgcn_raw_buffer_load_b16(frame_of(d.dy, t, y_bytes), yo, 0, 2);
     return in;
   };
@@ -1172,6 +1175,10 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   const long row_last = (long)(d.rev ? 0 : T - 1) * B + b, g_step = (d.rev ? (long)B : -(long)B) * 4 * n;
   unsigned short* dz_p = (unsigned short*)d.DZ + row_last * 4 * n + j;
   In in_a = fetch_in(T - 1), in_b = in_a;
+  {                                                        // the first frame's own cell state: the only one loaded as such
+    const int t0 = d.rev ? 0 : T - 1;
+    in_a.c_new = ld_f(frame_of(d.cs, t0, s_bytes), t0 < L ? s_off : kParked, 0u);
+  }
 
   // consumer side: lane reads output lane/2, row half lane%2 of every producer's block
   const int ccol = lane >> 1, cg = lane & 1;
@@ -1269,6 +1276,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         add(ps, x[1]);
         factors();
         in_next = fetch_in(tau - 1);  // behind the ring loads: loads complete in order, and these come from HBM
+        in_next.c_new = in.c_prev;
         __builtin_amdgcn_sched_barrier(0);
         unsigned long long redo = 0ull;
         constexpr int kGroup = (NPW - 2) / 2;              // the other loads: two groups
@@ -1302,6 +1310,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     } else {
       factors();
       in_next = fetch_in(tau - 1);
+      in_next.c_new = in.c_prev;
     }
     if (pointwise) {
       float dz[4] = {0.f, 0.f, 0.f, 0.f};
@@ -1331,20 +1340,20 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 7][kc * 32 + (lane >> 4) * 8];
       f32x4 acc[16];
-      // Four groups of four column tiles, the k loop inside.  An MFMA of this shape issues every 16 cycles, of which
-      // the wavefront's issue slot is taken for 4 (see the forward kernel for the measurements).  What publishes a group
-      // (two conversions, three moves and one store per tile) is cut into single instructions, and two of them follow
-      // each MFMA of the NEXT group from its third on: by then the group's last result has been written (more than
-      // the 20 wait states mfma_settle would spend), and the instructions cost nothing there, where behind the
-      // group's MFMAs they were a sixth of the step.  Nothing is predicated: lanes that hold no result have their
-      // store offset parked outside the buffer (pub_off), and the two cache policies are two copies of the code.
-      constexpr int kPubSteps = 24;
+      // Sixteen column tiles, the k loop inside.  An MFMA of this shape issues every 16 cycles, of which the wavefront's
+      // issue slot is taken for 4 (see the forward kernel for the measurements).  What publishes a tile (two conversions,
+      // three moves and one store) is cut into single instructions that follow the MFMAs of the tile two behind it:
+      // by then its last result has been written (more than the 20 wait states mfma_settle would spend), the
+      // instructions cost little there, and only the last two tiles are published behind the last MFMA (with groups of
+      // four tiles, as this was first written, a whole group's publishing - a quarter of it - trailed the stream).
+      // Nothing is predicated: lanes that hold no result have their store offset parked outside the buffer (pub_off),
+      // and the two cache policies are two copies of the code.
+      constexpr int kPubSteps = 6, kPubLag = 2;             // a tile is published behind the MFMAs of the tile kPubLag after it
       auto mma_publish = [&](auto local_c) __attribute__((always_inline)) {
         constexpr bool kLocal = decltype(local_c)::value;
-        u32x4 val[2][4];
-        auto pub_step = [&](int g4, int k) __attribute__((always_inline)) {
-          const int cc = k / 6, kk = k % 6, c = g4 * 4 + cc;
-          u32x4& v = val[g4 & 1][cc];
+        u32x4 val[4];
+        auto pub_step = [&](int c, int kk) __attribute__((always_inline)) {
+          u32x4& v = val[c & 3];
           if (kk == 0) v[0] = pack_bf16x2(acc[c][0], acc[c][1]);
           else if (kk == 1) v[2] = pack_bf16x2(acc[c][2], acc[c][3]);
           else if (kk == 2) v[1] = (v[2] & 0xffffu) | tag_hi;
@@ -1354,24 +1363,23 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         };
         operands_settle(av[0], av[1], av[2], av[3]);
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4)
+        for (int c = 0; c < 16; ++c)
 #pragma unroll
-          for (int cc = 0; cc < 4; ++cc)
-#pragma unroll
-            for (int kc = 0; kc < 4; ++kc) {
-              if (kc == 0) mfma_b_agpr_first(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
-              else mfma_b_agpr(acc[g4 * 4 + cc], av[kc], w[kc][g4 * 4 + cc]);
-              const int m = cc * 4 + kc - 2;
-              if (g4 > 0 && m >= 0 && 2 * m < kPubSteps) {
-                __builtin_amdgcn_sched_barrier(0);
-                pub_step(g4 - 1, 2 * m);
-                pub_step(g4 - 1, 2 * m + 1);
-                __builtin_amdgcn_sched_barrier(0);
-              }
+          for (int kc = 0; kc < 4; ++kc) {
+            if (kc == 0) mfma_b_agpr_first(acc[c], av[kc], w[kc][c]);
+            else mfma_b_agpr(acc[c], av[kc], w[kc][c]);
+            if (c >= kPubLag) {                              // steps 0,1 | 2 | 3,4 | 5 of the earlier tile
+              __builtin_amdgcn_sched_barrier(0);
+              const int k0 = kc == 0 ? 0 : kc == 1 ? 2 : kc == 2 ? 3 : 5, k1 = kc == 0 ? 2 : kc == 1 ? 3 : kc == 2 ? 5 : 6;
+              for (int k = k0; k < k1; ++k) pub_step(c - kPubLag, k);
+              __builtin_amdgcn_sched_barrier(0);
             }
+          }
         mfma_settle(acc[12], acc[13], acc[14], acc[15]);
 #pragma unroll
-        for (int k = 0; k < kPubSteps; ++k) pub_step(3, k);
+        for (int c = 16 - kPubLag; c < 16; ++c)
+#pragma unroll
+          for (int k = 0; k < kPubSteps; ++k) pub_step(c, k);
       };
       if (local) mma_publish(std::true_type{});
       else mma_publish(std::false_type{});
