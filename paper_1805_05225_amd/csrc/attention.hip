@@ -240,6 +240,7 @@ hipError_t linear_rows(const void* A, long lda, const void* W, long ldw, const f
   g.nz = 1; g.nseg = 1; g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = false;
   const auto vec = [](const void* p, long ld) { int v = 16; while (v > 2 && (((uintptr_t)p % v) || ((ld * 2) % v))) v >>= 1; return v; };
   g.vecA = vec(A, lda); g.vecB = vec(W, ldw);
+  if (gemm_skinny_ok(g)) return launch_gemm_skinny(g, false, s);       // few rows: one work-group per tile walks the whole K
   if (ksplit > 1 && gemm_nt_ok(g)) { g.ksplit = ksplit; g.parts = parts; }
   return launch_gemm(g, s);
 }
@@ -363,6 +364,15 @@ int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, co
   const long total_cat = (long)B * Kp;
   hipLaunchKernelGGL(concat3_kernel, dim3((unsigned)((total_cat + 255) / 256)), dim3(256), 0, st, (const uint16_t*)s, (long)ld_s, n,
                      (const uint16_t*)trg, (long)ld_trg, n_trg, (const uint16_t*)att, (long)ld_att, E, cat, Kp, B);
+  {                                  // few rows: bias, max(0, .) and the rounding happen in the product's epilogue
+    GemmArgs g = {};
+    g.A = cat; g.B = Wp; g.C = out; g.bias = b_r; g.M = B; g.N = R; g.K = (int)Kp; g.lda = Kp; g.ldb = Kp; g.ldc = ld_out;
+    g.nz = 1; g.nseg = 1; g.a_kcontig = true; g.b_kcontig = true; g.in_bf16 = true; g.out_bf16 = true; g.vecA = 16; g.vecB = 16;
+    if (gemm_skinny_ok(g)) {
+      if (launch_gemm_skinny(g, true, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+      return LSTM_OK;
+    }
+  }
   if (linear_rows(cat, Kp, Wp, Kp, b_r, z, B, R, (int)Kp, parts, ranges_for(B, R, (int)Kp), st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
   const long total = (long)B * R;
   hipLaunchKernelGGL(relu_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, z, (uint16_t*)out, B, R, (long)ld_out);

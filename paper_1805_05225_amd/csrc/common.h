@@ -73,6 +73,12 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s);
 // float C.  Row k of both operands is row k_rows[k] in memory if k_rows is given (launch_gemm routes to it by itself).
 bool gemm_tn_ok(const GemmArgs& g);
 hipError_t launch_gemm_tn(const GemmArgs& g, hipStream_t s);
+// Products with few rows (gemm_skinny.hip): both operands k-contiguous bfloat16 with 16-byte aligned rows, K % 8 == 0,
+// M <= kSkinnyMaxRows, one segment, no row maps, no K ranges: a work-group owns 96 x 128 of C for the whole K, so bias,
+// max(0, .) and the rounding to bfloat16 happen in its epilogue (launch_gemm routes such problems to it by itself).
+constexpr int kSkinnyMaxRows = 1024;
+bool gemm_skinny_ok(const GemmArgs& g);
+hipError_t launch_gemm_skinny(const GemmArgs& g, bool relu, hipStream_t s);
 // dst[c][r] = src[r][c] (16-bit elements), r < R, c < C, dst rows zero-padded up to ld_dst; nz problems with
 // strides s_src / s_dst.  lens != NULL: rows of src are frames (t = r / Bt, b = r % Bt) and are read as zero
 // unless t < lens[b].  With cidx / fidx / count from launch_frame_map the kept frames are packed instead: column
@@ -246,6 +252,13 @@ hipError_t launch_time_pool_fwd(bool bf16, const void* y, long ldy, const int* l
 hipError_t launch_time_pool_bwd(bool bf16, const void* dout, long ldo, const uint8_t* arg, const int* lens, void* dy, long ldy, int T, int B,
                                 int F, int pool, hipStream_t s);
 hipError_t launch_concat_xh(const void* x, const float* h, void* Acat, int B, int n_in, int n_in_pad, int n, int Kc, int ndir, hipStream_t s);
+// The same step with the cell update in the product's epilogue (gemm_skinny.hip):
+// Wcell[ndir][128 * ceil(n/32)][Kc]: row 128 t + 32 q + u = row q n + 32 t + u of Wcat (zeros for units past n), so that
+// a tile of 128 columns holds the four gates of 32 units.  Arguments of the step as for launch_cell_step.
+inline size_t wcell_rows(int n) { return (size_t)128 * ((n + 31) / 32); }
+hipError_t launch_pack_wcell(const void* W_x, const void* W_h, void* Wcell, int n_in, int n_in_pad, int n, int Kc, int ndir, hipStream_t s);
+hipError_t launch_step_cell(const void* Acat, const void* Wcell, const float* bias, const float* h_in, const float* c_in, float* h_out,
+                            float* c_out, void* y, long ldy, float* cs, const int* lens, int B, int n, int Kc, int ndir, hipStream_t s);
 // cell update from the pre-activations z = bias + sum of `nparts` partial products, laid out [ndir][nparts][part floats]
 // with [B][4n] inside a part.  h_in, c_in [ndir][B][n]: state entering the step (NULL = zeros); h_out, c_out: state
 // leaving it (NULL = not wanted); y[B][ldy] (direction d at column d*n); cs[ndir][B][n] or NULL; rows with lens[b] < 1

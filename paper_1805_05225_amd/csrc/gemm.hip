@@ -311,6 +311,7 @@ hipError_t dispatch(const GemmArgs& g, hipStream_t s) {
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0 || g.nz <= 0) return hipSuccess;
+  if (gemm_skinny_ok(g)) return launch_gemm_skinny(g, false, s);
   if (gemm_nt_ok(g)) return launch_gemm_nt(g, s);
   if (gemm_tn_ok(g)) return launch_gemm_tn(g, s);
   if (g.in_bf16) {

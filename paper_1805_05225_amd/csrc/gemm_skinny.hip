@@ -9,10 +9,10 @@
 //             the epilogue adds the bias, applies the LSTM cell and writes y, h', c' - no pre-activations in memory.
 //
 // C[M,N] = A[M,K] B[N,K]^T, both operands bfloat16, k-contiguous, rows 16-byte aligned, K a multiple of 8.
-// Eight wavefronts: wavefront (kg, wn) owns the 96 x 32 block of column group wn (three 32x32x16 MFMA blocks) for the
-// k-steps 2 kg, 2 kg + 1 of every 64-wide stage; the two halves are added in the epilogue.  Two wavefronts per SIMD,
-// so one's LDS reads hide behind the other's MFMAs.  Operands travel from global memory straight into LDS (16 bytes
-// per lane, 1 KiB per wavefront instruction = 8 rows of 128 bytes), two stages, one barrier per stage; bank conflicts
+// Eight wavefronts: wavefront (kq, wc) owns the 96 x 64 block of column half wc (3 x 2 MFMA blocks of 32x32x16) for
+// k-step kq of every 64-wide stage (five fragment reads for six MFMAs; with 96 x 32 per wavefront the LDS reads took
+// longer than the MFMAs); the four shares are added in the epilogue.  Two wavefronts per SIMD.  Operands travel from global memory straight into LDS (16 bytes
+// per lane, 1 KiB per wavefront instruction = 8 rows of 128 bytes), four stages of 64 k, one barrier per stage; bank conflicts
 // are avoided by placement: the 16-byte slot p of row r holds k-chunk p ^ ((r >> 1) & 7).  What bounds it is the path
 // from L2 to LDS (about 47 bytes per clock and compute unit, measured for the large kernels): 28 KiB per stage
 // against 384 clocks of MFMA work, i.e. about 600 clocks per stage.
@@ -27,8 +27,10 @@ constexpr int kTM = 96, kTN = 128;
 constexpr int kRow = 128;                          // bytes per LDS row (64 bfloat16)
 constexpr int kAop = kTM * kRow, kBop = kTN * kRow, kStage = kAop + kBop;      // 12 + 16 KiB
 constexpr int kLoads = (kTM + kTN) / 8;            // wavefront-loads per stage: 12 for A, 16 for B
+constexpr int kDepth = 4;                          // stages in LDS: three in flight while one is multiplied (2: +20 %, 3 and 5: the same)
+constexpr int kDummy = kDepth * kStage;            // 4 KiB that the surplus loads of a stage write zeros to (see the kernel)
 constexpr int kEpStride = kTN + 4;                 // floats per staged row
-constexpr int kLds = 2 * kStage > kTM * kEpStride * 4 ? 2 * kStage : kTM * kEpStride * 4;     // 57344 bytes
+constexpr int kLds = kDummy + 4096;                // 118784 bytes; the epilogue's staging (96 x 132 floats) reuses the stages
 constexpr unsigned kParked = 0x7ffffff0u;
 
 struct SkinnyArgs {
@@ -61,17 +63,17 @@ __device__ __forceinline__ f32x16 mma32(uint4 a, uint4 b, f32x16 c) {
 // Work-group -> tile.  Work-groups are dealt to the eight XCDs round-robin (blockIdx & 7 is the XCD).  The tiles an XCD
 // runs at a time should share operand panels out of its L2: with tiles_m <= 8 row tiles, an XCD takes all row tiles of
 // 32 / bm column tiles at a time (bm = tiles_m rounded up to a power of two); otherwise tiles are dealt row-major.
-struct Tile { int tm, tn; bool live; };
+struct Tile { int tm, tn, pos; bool live; };
 __device__ __forceinline__ Tile tile_of(int tiles_m, int tiles_n) {
-  Tile t = {0, 0, false};
+  Tile t = {0, 0, 0, false};
   const int bid = blockIdx.x;
   if (tiles_m <= 8) {
     const int bm = tiles_m <= 1 ? 1 : tiles_m <= 2 ? 2 : tiles_m <= 4 ? 4 : 8, bn = 32 / bm;
     const int xcd = bid & 7, slot = bid >> 3, group = (slot / 32) * 8 + xcd, pos = slot % 32;
-    t.tm = pos % bm; t.tn = group * bn + pos / bm;
+    t.tm = pos % bm; t.tn = group * bn + pos / bm; t.pos = pos;
     t.live = t.tm < tiles_m && t.tn < tiles_n;
   } else {
-    t.tm = bid % tiles_m; t.tn = bid / tiles_m;
+    t.tm = bid % tiles_m; t.tn = bid / tiles_m; t.pos = bid & 31;
     t.live = t.tn < tiles_n;
   }
   return t;
@@ -90,97 +92,154 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int kg = wave >> 2, wn = wave & 3;
+  const int kq = wave >> 1, wc = wave & 1;          // k-step of a stage (0..3) and column half (64 columns) of this wavefront
   const int r = lane & 31, gq = lane >> 5;
   const int tiles_m = (g.M + kTM - 1) / kTM, tiles_n = (g.N + kTN - 1) / kTN;
   const Tile tl = tile_of(tiles_m, tiles_n);
   if (!tl.live) return;
   const int m0 = tl.tm * kTM, n0 = tl.tn * kTN, z = blockIdx.z;
   const int K = g.K, nstage = (K + 63) / 64;
+  // The work-groups of an XCD that share an operand panel would ask for the same lines at the same time, and all of
+  // them would wait for the one fetch from beyond L2 (whose rate per compute unit is a quarter of the L2's).  So each
+  // of the 32 work-groups an XCD runs together starts at a different k and wraps around: a line is fetched once and
+  // found in L2 by the others when their turn comes (the sum over k does not care about the order).
+  const int rot = (int)(((long)tl.pos * nstage) >> 5);
 
-  f32x16 acc[3];
+  f32x16 acc[3][2];
 #pragma unroll
   for (int i = 0; i < 3; ++i)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // Loads: wavefront-load q of a stage (q = wave + 8 i) fills rows 8 q' .. 8 q' + 7 of A (q < 12) or B; lane l fills
-  // slot l & 7 of row l >> 3 of those, i.e. fetches k-chunk (l & 7) ^ swizzle(row).  Rows past the operand's end and
-  // chunks past K point outside the buffer descriptor and arrive as zeros.
-  constexpr int kPerWave = (kLoads + 7) / 8;       // 4 (the last round has 4 loads for 8 wavefronts)
+  // Loads: wavefront-load q of a stage (q = wave + 8 i, i < 4) fills rows 8 q' .. 8 q' + 7 of A (q < 12) or B (q < 28);
+  // lane l fills slot l & 7 of row l >> 3 of those, i.e. fetches k-chunk (l & 7) ^ swizzle(row).  Rows past the operand's
+  // end and chunks past K point outside the buffer descriptor and arrive as zeros.  Every wavefront issues four loads
+  // per stage, so that one wait count serves all of them: the four surplus ones (q >= 28) have every lane parked and
+  // write their zeros to a spare 4 KiB of LDS without touching memory.
+  constexpr int kPerWave = 4;
   unsigned voff[kPerWave], dst[kPerWave];
   int chunk[kPerWave];
-  bool is_b[kPerWave], on[kPerWave];
+  bool is_b[kPerWave];
   const long a_bytes = (long)g.M * g.lda * 2, b_bytes = (long)g.N * g.ldb * 2;
 #pragma unroll
   for (int i = 0; i < kPerWave; ++i) {
     const int q = wave + 8 * i;
-    on[i] = q < kLoads;
+    const bool real = q < kLoads;
     is_b[i] = q >= kTM / 8;
     const int rg = is_b[i] ? q - kTM / 8 : q;
     const int rl = rg * 8 + (lane >> 3);
-    chunk[i] = (lane & 7) ^ ((rl >> 1) & 7);
+    chunk[i] = real ? (lane & 7) ^ ((rl >> 1) & 7) : 0x10000;            // surplus load: "past K" in every stage
     const long row = (is_b[i] ? n0 : m0) + rl;
-    const bool inside = is_b[i] ? row < g.N : row < g.M;
-    const long off = row * (is_b[i] ? g.ldb : g.lda) * 2 + chunk[i] * 16;
+    const bool inside = real && (is_b[i] ? row < g.N : row < g.M);
+    const long off = row * (is_b[i] ? g.ldb : g.lda) * 2 + (chunk[i] & 7) * 16;
     voff[i] = (inside && off <= 0x7fffff00L) ? (unsigned)off : kParked;
-    dst[i] = (unsigned)((is_b[i] ? kAop : 0) + rg * 1024);
+    dst[i] = real ? (unsigned)((is_b[i] ? kAop : 0) + rg * 1024) : 0u;
   }
   const unsigned lds_base = (unsigned)(unsigned long long)(__attribute__((address_space(3))) char*)lds;
   const u32x4 ra = make_rsrc(g.A + g.sAz * z * 2, a_bytes > 0x7fffff00L ? 0x7fffff00u : (unsigned)a_bytes);
   const u32x4 rb = make_rsrc(g.B + g.sBz * z * 2, b_bytes > 0x7fffff00L ? 0x7fffff00u : (unsigned)b_bytes);
-  auto issue = [&](int it, int buf) __attribute__((always_inline)) {
+  auto issue = [&](int it) __attribute__((always_inline)) {
+    const unsigned buf = lds_base + (unsigned)(it % kDepth) * kStage;
+    const int kt = it + rot < nstage ? it + rot : it + rot - nstage;       // which 64 k this stage holds
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
-      if (!on[i]) continue;                                    // wave-uniform
-      const bool past = it * 64 + chunk[i] * 8 >= K;           // ragged last stage
-      load_to_lds_b128(is_b[i] ? rb : ra, lds_base + buf * kStage + dst[i], past ? kParked : voff[i], (unsigned)it * 128u);
+      const bool past = kt * 64 + chunk[i] * 8 >= K;           // ragged last k-tile (and every surplus load)
+      const unsigned where = (i == 3 && wave >= 4) ? lds_base + kDummy + (unsigned)(wave - 4) * 1024u : buf + dst[i];
+      load_to_lds_b128(is_b[i] ? rb : ra, where, past ? kParked : voff[i], (unsigned)kt * 128u);
     }
   };
-  // Fragment reads: row (i*32 + r) of A / (wn*32 + r) of B, k-chunk 2 s + gq, in slot (2 s + gq) ^ ((row >> 1) & 7)
-  const int sw = (r >> 1) & 7;
-  const int fa_off = r * kRow, fb_off = kAop + (wn * 32 + r) * kRow;
+  // Fragment reads: row (i*32 + r) of A / (wc*64 + j*32 + r) of B, k-chunk 2 kq + gq, in slot (2 kq + gq) ^ ((row >> 1) & 7)
+  const int slot = ((2 * kq + gq) ^ ((r >> 1) & 7)) * 16;
+  const int fa_off = r * kRow + slot, fb_off = kAop + (wc * 64 + r) * kRow + slot;
 
-  issue(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+  // Pipeline: while the MFMAs of stage it run (fragments in registers), the fragments of stage it+1 are read from LDS
+  // and the loads of stages it+2 .. it+4 are in flight (a load from beyond L2 takes longer than two stages of MFMAs:
+  // with one stage ahead the loop ran at memory latency, 1700 clocks per stage; and with fragment reads and MFMAs of
+  // one stage in program order the compiler made every MFMA wait for its own LDS read).  Loads complete in issue
+  // order, four per wavefront and stage: when at most 8 are outstanding, everything up to the stage two behind the
+  // newest has landed.  A buffer is overwritten one iteration after every wavefront has passed the barrier behind
+  // which it read the buffer's fragments (and waited for them).
+  uint4 fa[2][3], fb[2][2];                        // [register set][row block], [register set][column block]
+  auto read_a = [&](int it, int set, int i) __attribute__((always_inline)) {
+    fa[set][i] = *(const uint4*)(lds + (it % kDepth) * kStage + fa_off + i * 32 * kRow);
+  };
+  auto read_b = [&](int it, int set, int j) __attribute__((always_inline)) {
+    fb[set][j] = *(const uint4*)(lds + (it % kDepth) * kStage + fb_off + j * 32 * kRow);
+  };
+  auto wait_stage = [&](int newer) __attribute__((always_inline)) {       // `newer` stages were issued behind the awaited one
+    if (newer >= 4) __builtin_amdgcn_s_waitcnt(0x4070);                    // vmcnt(16) lgkmcnt(0)
+    else if (newer == 3) __builtin_amdgcn_s_waitcnt(0x007c);               // vmcnt(12) lgkmcnt(0)
+    else if (newer == 2) __builtin_amdgcn_s_waitcnt(0x0078);               // vmcnt(8)
+    else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0074);               // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0070);                               // vmcnt(0)
+  };
+#pragma unroll
+  for (int j = 0; j < kDepth; ++j)
+    if (j < nstage) issue(j);
+  wait_stage(min(nstage - 1, kDepth - 1));
   __syncthreads();
-  for (int it = 0; it < nstage; ++it) {
-    const int cur = it & 1;
-    if (it + 1 < nstage) issue(it + 1, cur ^ 1);   // the other buffer was last read before the barrier that ended stage it - 1
-    const char* base = lds + cur * kStage;
-    uint4 fa[2][3], fb[2];
+  read_b(0, 0, 0); read_a(0, 0, 0); read_a(0, 0, 1); read_a(0, 0, 2); read_b(0, 0, 1);
+  // The six MFMAs of a stage in the order (row block, column block) = (0,0) (1,0) (2,0) (0,1) (1,1) (2,1); with `next`,
+  // one fragment read of the following stage goes out behind each of the first five, in the order the MFMAs will want
+  // them.  (All reads in front of the MFMAs held the MFMAs back until the LDS had taken them: reads and MFMAs of a
+  // stage then ran one after the other.)
+  auto mfmas = [&](int set, bool next, int it_next) __attribute__((always_inline)) {
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss) {
-      const int slot = ((2 * (2 * kg + ss) + gq) ^ sw) * 16;
-#pragma unroll
-      for (int i = 0; i < 3; ++i) fa[ss][i] = *(const uint4*)(base + fa_off + i * 32 * kRow + slot);
-      fb[ss] = *(const uint4*)(base + fb_off + slot);
+    for (int m = 0; m < 6; ++m) {
+      const int i = m % 3, j = m / 3;
+      acc[i][j] = mma32(fa[set][i], fb[set][j], acc[i][j]);
+      if (next) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (m == 0) read_b(it_next, set ^ 1, 0);
+        else if (m <= 3) read_a(it_next, set ^ 1, m - 1);
+        else if (m == 4) read_b(it_next, set ^ 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
+  };
+  // one stage with a successor.  No branch between the successor's reads and the MFMAs: where two paths with different
+  // numbers of pending LDS reads met in front of the MFMAs, the compiler made them wait for every read.
+  auto step = [&](int it, int set) __attribute__((always_inline)) {
+    wait_stage(min(nstage - 2 - it, kDepth - 2));                         // stage it+1 landed; own fragment reads of stage it done
+    __syncthreads();
+    if (it + kDepth < nstage) issue(it + kDepth);                         // into the buffer of stage it, now in registers everywhere
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(set, true, it + 1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int it = 0;
+  for (; it + 2 < nstage; it += 2) {
+    step(it, 0);
+    step(it + 1, 1);
+  }
+  if (it + 2 == nstage) {
+    step(it, 0);
+    mfmas(1, false, 0);
+  } else {
+    mfmas(0, false, 0);
+  }
+  __syncthreads();                                 // the stage buffers are free for the epilogue
+
+  // Epilogue.  The four k-steps' shares meet in LDS (the stage buffers are free), one after the other:
+  // acc[i][j][v] is row i*32 + 8 (v / 4) + 4 gq + v % 4, column wc*64 + j*32 + r.
+  float* ep = (float*)lds;
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss)
+  for (int round = 3; round >= 0; --round) {
+    if (kq == round) {
 #pragma unroll
-      for (int i = 0; i < 3; ++i) acc[i] = mma32(fa[ss][i], fb[ss], acc[i]);
-    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): own loads of the next stage landed, own reads done
+      for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            float* e = &ep[(i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3)) * kEpStride + wc * 64 + j * 32 + r];
+            *e = round == 3 ? acc[i][j][v] : *e + acc[i][j][v];
+          }
+    }
     __syncthreads();
   }
-
-  // Epilogue.  The two k-halves meet in LDS (the stage buffers are free: the loop ended with a barrier):
-  // acc[i][v] is row i*32 + 8 (v / 4) + 4 gq + v % 4, column wn*32 + r.
-  float* ep = (float*)lds;
-  if (kg == 1) {
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) ep[(i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3)) * kEpStride + wn * 32 + r] = acc[i][v];
-  }
-  __syncthreads();
-  if (kg == 0) {
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) ep[(i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3)) * kEpStride + wn * 32 + r] += acc[i][v];
-  }
-  __syncthreads();
   if constexpr (!CELL) {
     // thread -> (row, four columns): 32 threads per row, 16 rows per pass
     const int c4 = (tid & 31) * 4, col = n0 + c4;
@@ -307,6 +366,9 @@ __global__ __launch_bounds__(256) void pack_wcell_kernel(const uint16_t* Wx, con
 
 bool gemm_skinny_ok(const GemmArgs& g) {
   const auto a16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
+  // only where the 256 x 256 tiles of the throughput kernel would leave most of the device idle (it is the faster one
+  // from about half a device's worth of tiles: 768 x 20000 x 1000 takes 49 us there and 72 us here)
+  if ((long)cdiv(g.M, 256) * cdiv(g.N, 256) * g.nz >= 128) return false;
   return g.in_bf16 && g.a_kcontig && g.b_kcontig && !g.lens && g.M <= kSkinnyMaxRows && g.nseg == 1 && !g.a_rows && !g.c_rows && !g.m_dev &&
          !g.k_dev && !g.accumulate && g.ksplit <= 1 && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.sAz % 8 == 0 && g.sBz % 8 == 0 &&
          a16(g.A) && a16(g.B) && (long)g.N * g.ldb * 2 <= 0x7fffff00L;

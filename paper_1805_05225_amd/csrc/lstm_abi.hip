@@ -28,7 +28,7 @@ struct Plan {
   size_t ws_Wf, ws_Wb, ws_hfrag0, ws_hfrag1, ws_dzfrag0, ws_dzfrag1, ws_hstate, ws_cstate, ws_Dh, ws_Dc, ws_DZ, ws_Zx,
       ws_colsum, ws_sync, sync_bytes, ws_WxT, ws_xpad, ws_XT, ws_DZT, ws_HT, ws_cidx, ws_fidx, ws_count, ws_Wcat, ws_Acat, ws_parts, workspace_bytes;
   int ks_dwx, ks_dwh, ks_dx;                // K ranges of the weight-gradient products and of dX (few output tiles: the whole device works on them)
-  bool single_step; int Kc, ksplit;         // T == 1 inference in bfloat16: the step is one product over [x | h], K cut in ksplit ranges
+  bool single_step, step_fused; int Kc, ksplit;         // T == 1 inference in bfloat16: the step is one product over [x | h], K cut in ksplit ranges
   bool fast_gemm; int n_in_pad; long TBp;   // bf16 products through the k-contiguous kernel (operands transposed once)
   size_t hfrag_bytes, dzfrag_bytes, DZ_dir_elems, Zx_dir_elems, Wf_bytes;
 };
@@ -89,13 +89,17 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   // k extent of the input projection: a multiple of 8 (16-byte rows), and for narrow inputs a multiple of 64 so that
   // the product runs through the kernel that loads straight into LDS (x is then copied into zero-padded rows)
   p->n_in_pad = d->n_in < 256 ? (d->n_in + 63) / 64 * 64 : (d->n_in + 7) / 8 * 8;
+  // The step's product has few rows: a work-group of the skinny-row kernel walks the whole K and applies the cell in its
+  // epilogue (B <= kSkinnyMaxRows); larger batches go through the throughput kernel, K cut into ranges whose partial
+  // products lie side by side for the cell kernel to add.
+  p->step_fused = p->single_step && d->B <= kSkinnyMaxRows;
   {
     const long tiles = (long)cdiv(B > 0 ? B : 1, 256) * cdiv(4L * d->n, 256) * p->D;
     const long stages = cdiv((long)p->n_in_pad + d->n, 64);
-    p->ksplit = (int)std::max(1L, std::min(std::min(256 / tiles, stages / 4), 8L));
+    p->ksplit = p->step_fused ? 1 : (int)std::max(1L, std::min(std::min(256 / tiles, stages / 4), 8L));
     p->Kc = cdiv((long)p->n_in_pad + d->n, 64L * p->ksplit) * 64 * p->ksplit;
   }
-  p->ws_Zx = take(infer ? D * p->Zx_dir_elems * 4 * (p->single_step ? p->ksplit : 1) : 0);
+  p->ws_Zx = take(infer && !p->step_fused ? D * p->Zx_dir_elems * 4 * (p->single_step ? p->ksplit : 1) : 0);
   p->ws_colsum = take(infer ? 0 : D * 64 * 4 * n * 4);
   // transposed / padded operand copies for the fast bf16 products
   p->fast_gemm = p->bf16 && d->n % 2 == 0;
@@ -110,7 +114,7 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ws_cidx = take(fg ? (size_t)TB * 4 : 0);
   p->ws_fidx = take(fg ? (size_t)p->TBp * 4 : 0);
   p->ws_count = take(fg ? 256 : 0);
-  p->ws_Wcat = take(p->single_step ? D * 4 * n * p->Kc * 2 : 0);
+  p->ws_Wcat = take(p->single_step ? D * std::max((size_t)4 * n, wcell_rows(d->n)) * p->Kc * 2 : 0);
   p->ws_Acat = take(p->single_step ? D * B * p->Kc * 2 : 0);
   // weight-gradient products with few output tiles cut K into ranges whose partial results are summed afterwards
   const auto ksplit_for = [&](long M, long N) {
@@ -205,9 +209,17 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     float* z = (float*)(ws + p.ws_Zx);
     {
       Phase ph(LSTM_PHASE_PREP, 2, s);
-      if (!(desc->flags & LSTM_FLAG_WEIGHTS_PACKED))
-        HIPCHK(launch_pack_wcat(W_x, W_h, Wcat, p.n_in, p.n_in_pad, p.n, p.Kc, p.D, s));
+      if (!(desc->flags & LSTM_FLAG_WEIGHTS_PACKED)) {
+        if (p.step_fused) HIPCHK(launch_pack_wcell(W_x, W_h, Wcat, p.n_in, p.n_in_pad, p.n, p.Kc, p.D, s));
+        else HIPCHK(launch_pack_wcat(W_x, W_h, Wcat, p.n_in, p.n_in_pad, p.n, p.Kc, p.D, s));
+      }
       HIPCHK(launch_concat_xh(x, (const float*)h0, Acat, p.B, p.n_in, p.n_in_pad, p.n, p.Kc, p.D, s));
+    }
+    if (p.step_fused) {                // product, bias, cell update and outputs in one kernel
+      Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
+      HIPCHK(launch_step_cell(Acat, Wcat, (const float*)b, (const float*)h0, (const float*)c0, (float*)hT, (float*)cT, y, (long)(D * n),
+                              (float*)c, seq_lens, p.B, p.n, p.Kc, p.D, s));
+      return LSTM_OK;
     }
     // batch index of the product = K range: A and B advance by Kr columns, C by one partial result
     const long Kr = Kc / p.ksplit, part = (long)p.Zx_dir_elems;
