@@ -158,19 +158,20 @@ struct RingReader {
   // Second pass over the loads marked in `redo`, all of them in flight at once: every round fetches those still
   // marked, hands the ones whose tags have all turned to `use` (operand as loaded, tags included) and keeps the
   // rest for the next round (bounded).
-  template <int NIT, typename F>
+  template <int NIT, int OFF = 0, typename F>
   __device__ __forceinline__ void fix_up_batch(unsigned long long redo, bool& dead, F&& use) const {
+    redo &= ((1ull << NIT) - 1ull) << OFF;                    // loads OFF .. OFF + NIT - 1 of the stream
     for (unsigned poll = 0; redo != 0ull && !dead; ++poll) {
       u32x4 x[NIT];
 #pragma unroll
       for (int i = 0; i < NIT; ++i)
-        if ((redo >> i) & 1ull) x[i] = load_it(it_of(i));
+        if ((redo >> (i + OFF)) & 1ull) x[i] = load_it(it_of(i + OFF));
 #pragma unroll
       for (int i = 0; i < NIT; ++i) {
-        if (!((redo >> i) & 1ull)) continue;
-        if (__builtin_amdgcn_ballot_w64(stale_bits(x[i], it_of(i)) != 0u) == 0ull) {
-          use(i, x[i]);
-          redo &= ~(1ull << i);
+        if (!((redo >> (i + OFF)) & 1ull)) continue;
+        if (__builtin_amdgcn_ballot_w64(stale_bits(x[i], it_of(i + OFF)) != 0u) == 0ull) {
+          use(i + OFF, x[i]);
+          redo &= ~(1ull << (i + OFF));
         }
       }
       if (redo != 0ull && (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u))) {
@@ -299,6 +300,14 @@ constexpr int kPrepDelay = LSTM_PREP_DELAY;
 #ifndef LSTM_OPERAND_NOPS
 #define LSTM_OPERAND_NOPS "7"
 #endif
+// f(integral_constant<0>) ... f(integral_constant<N - 1>): a loop whose counter is a constant expression in the body
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
 __device__ __forceinline__ void operands_settle(u32x4& a, u32x4& b) { asm volatile("s_nop " LSTM_OPERAND_NOPS : "+v"(a), "+v"(b)); }
 __device__ __forceinline__ void operands_settle(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
   asm volatile("s_nop " LSTM_OPERAND_NOPS : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
@@ -771,6 +780,345 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   if (active) {
     d.cstate[(long)b * n + j] = c;
     d.hstate[(long)b * n + j] = h;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward, third decomposition: a work-group owns 32 units for all 16 rows of a row tile.  For batches of more than
+// 32 rows: 64 rows x 2 directions are then 256 work-groups, one launch, where the 32 x 8 form needs two launches
+// that each walk all T steps.  Every MFMA row is a real row (96 MFMAs per wavefront and step, as in the 32 x 8 form,
+// for twice the rows), a load is one whole chunk (12 loads per wavefront and step instead of 6), and a thread
+// updates two cells (rows r8 and r8 + 8).  Ring layout, tags and publishing are those of the 32 x 8 form.
+template <int NIT>
+__global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
+  __shared__ float red[2][4][16][129];                   // two copies, used by even and odd steps: one barrier per step
+  // x W_x + b of the next frame, fetched one step ahead by loads that write LDS instead of registers (the register
+  // file has no room for two sets of 8 values per thread): [set][wavefront][row k, gate q][lane], each thread reading
+  // back exactly what it asked for, so no barrier is involved - only the loads' completion.
+  __shared__ float zxs[2][4][8][64];
+  __shared__ u32x4 rbuf[4][NIT][64];                     // the ring loads of a step: [wavefront][load][lane], written by the memory unit
+  const WgCoord wg = wg_coord();
+  const PFwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
+  const int tile2 = wg.tile, rt = a.rt0 + wg.rt;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // (told to be wave-uniform: it forms scalar LDS addresses below)
+  const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
+  const int ntiles16 = (n + 15) / 16;
+  unsigned* err = a.sync;
+  bool dead = false;
+
+  const int nitv = (nkc + 3) / 4, rot = tile2 % nitv;
+  // Register set `it` holds the chunk that load `it` of the stream fetches; the first kAccIts sets fill the 256
+  // accumulation registers, the rest sit in vector registers (as in the 32 x 8 form).
+  constexpr int kAccIts = NIT < 8 ? NIT : 8;
+  u32x4 wa[kAccIts][2][4];
+  u32x4 wv[NIT - kAccIts > 0 ? NIT - kAccIts : 1][2][4];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int kc = wave + 4 * rot_index(it, rot, nitv);
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+      const int t16 = tile2 * 2 + ct;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint4* src = (kc < nkc && t16 < ntiles16) ? &d.Wf[((long)(t16 * 4 + q) * nkc + kc) * 64 + lane] : &d.Wzero[lane];
+        if (it < kAccIts) wa[it][ct][q] = load_to_agpr(src);
+        else wv[it - kAccIts][ct][q] = *(const u32x4*)src;
+      }
+    }
+  }
+  agpr_loads_done();
+
+  const int r8 = tid >> 5, u = tid & 31;                 // pointwise pairs of this thread: rows r8 and r8 + 8, unit u of 32
+  const int j = tile2 * 32 + u;
+  float c[2] = {0.f, 0.f}, h[2] = {0.f, 0.f};
+  int L[2] = {0, 0};
+  bool active[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int b = rt * 16 + r8 + 8 * k;
+    active[k] = b < B && j < n;
+    if (active[k]) {
+      c[k] = d.cstate[(long)b * n + j];
+      h[k] = d.hstate[(long)b * n + j];
+      L[k] = clamp_len(a.lens, b, T);
+    }
+  }
+  const int pp = u >> 4, m = (u & 15) / 3;
+  const int t16p = tile2 * 2 + pp;
+  const int cch = t16p * 3 + (m >> 1);
+  const bool publishes = (u & 15) % 3 == 0 && t16p < ntiles16;
+  const bool local = a.xcc != nullptr &&
+                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * (int)gridDim.x, gridDim.x, tile2, a.spin_limit);
+
+  constexpr unsigned kParked = 0x7ff00000u;
+  const unsigned g_bytes = (unsigned)B * 4u * n * 4u, y_bytes = (unsigned)B * d.ldy * 2u, s_bytes = (unsigned)B * n * 4u;
+  // offsets of row r8 inside a frame; row r8 + 8 lies a wave-uniform distance behind it (a row of the second half
+  // that exists implies its partner in the first half does), which keeps four registers free
+  const unsigned b0 = (unsigned)(rt * 16 + r8);
+  const unsigned g_off0 = active[0] ? (b0 * 4u * n + j) * 4u : kParked;
+  const unsigned y_off0 = active[0] ? (b0 * d.ldy + j) * 2u : kParked;
+  const unsigned s_off0 = active[0] ? (b0 * n + j) * 4u : kParked;
+  const unsigned pub_off0 = publishes ? (unsigned)((((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r8) * 2 + (m & 1)) * 8u : kParked;
+  auto g_off = [&](int k) { return k == 0 ? g_off0 : (active[1] ? g_off0 + 8u * 4u * n * 4u : kParked); };
+  auto y_off = [&](int k) { return k == 0 ? y_off0 : (active[1] ? y_off0 + 8u * (unsigned)d.ldy * 2u : kParked); };
+  auto s_off = [&](int k) { return k == 0 ? s_off0 : (active[1] ? s_off0 + 8u * n * 4u : kParked); };
+  auto pub_off = [&](int k) { return k == 0 ? pub_off0 : (publishes ? pub_off0 + 8u * 16u : kParked); };
+  auto frame_of = [&](const void* base, int t, unsigned bytes, bool present = true) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (unsigned long long)(unsigned)t * bytes), 0, present && base != nullptr ? bytes : 0u, kBufFlags);
+  };
+  const unsigned zxs_base = (unsigned)(unsigned long long)(__attribute__((address_space(3))) char*)&zxs[0][0][0][0];
+  const unsigned rbuf_base = (unsigned)(unsigned long long)(__attribute__((address_space(3))) char*)&rbuf[0][0][0];
+  // (assembly: the compiler makes every later LDS read wait for all loads of this kind that it knows to be in flight;
+  // the kernel counts them itself - see the wait in front of the cell update)
+  auto fetch_zx = [&](int tau, int set) __attribute__((always_inline)) {
+    const bool ok = tau < T;
+    const int t = d.rev ? T - 1 - tau : tau;
+    const __amdgpu_buffer_rsrc_t rg =
+        __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)d.gates + (unsigned long long)(unsigned)(ok ? t : 0) * g_bytes), 0, ok ? g_bytes : 0u, kBufFlags);
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const unsigned go = t < L[k] ? g_off(k) : kParked;     // (L is 0 in lanes without a row)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const unsigned dst = zxs_base + (unsigned)(((set * 4 + wave) * 8 + k * 4 + q) * 256);
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen nt lds" ::"s"(dst), "v"(go), "s"(rg), "s"((unsigned)q * 4u * n) : "memory");
+      }
+    }
+  };
+  unsigned h_prev_bits[2] = {pack_bf16x2(h[0], 0.f) & 0xffffu, pack_bf16x2(h[1], 0.f) & 0xffffu};
+  fetch_zx(0, 0);
+  PROF_DECL
+  auto step = [&](const int tau, auto parity) __attribute__((always_inline)) {
+    constexpr int kSet = decltype(parity)::value;
+    float (&red_)[4][16][129] = red[decltype(parity)::value];
+    const int t = d.rev ? T - 1 - tau : tau;
+    PROF_MARK(4)
+    const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
+    const RingReader rd = make_reader(rin, nkc, ntiles16 * 3, wave, lane, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
+    f32x4 acc[2][4];
+    {
+      auto mma_one = [&](int it, int ct, int q, const u32x4& a_op) __attribute__((always_inline)) {
+        if (it < kAccIts) mfma_b_agpr(acc[ct][q], a_op, wa[it < kAccIts ? it : 0][ct][q]);
+        else mfma_b_vgpr(acc[ct][q], a_op, wv[it >= kAccIts ? it - kAccIts : 0][ct][q]);
+      };
+      auto use_single = [&](int i, const u32x4& raw) {     // a load fetched again after the stream, tags still in it
+        u32x4 av = {raw[0], raw[1] & 0xffffu, raw[2], raw[3] & 0xffffu}, dummy = av;
+        operands_settle(av, dummy);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) mma_one(i, ct, q, av);
+      };
+      // The loads are consumed in pairs (two chunks, 16 MFMAs); what turns the next pair's loads into operands (tag
+      // test, masking the tags off) is cut into single instructions that follow the first MFMAs of the pair before.
+      static_assert(NIT % 2 == 0, "loads are consumed in pairs");
+      constexpr int NP = NIT / 2, kPrepSteps = 6;
+      // The first pair of loads is the poll and lands in registers.  The others are written to LDS by the memory
+      // unit (rbuf: no registers are held while they are in flight, so all of them fly at once) and are read back
+      // a pair ahead of their MFMAs; loads complete in the order of issue, which is what the counted waits rely on.
+      u32x4 x[2][2];
+      const unsigned tagw = rd.tag << 16;
+      auto issue_dma = [&](int i) __attribute__((always_inline)) {
+        const unsigned dst = rbuf_base + (unsigned)(wave * NIT + i) * 1024u, soff = (unsigned)rd.it_of(i) * rd.it_bytes;
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen sc1 lds" ::"s"(dst), "v"(rd.voff), "s"(rd.rs), "s"(soff) : "memory");
+      };
+      // (Fetching everything along with the first poll - stale loads now being cheap to repeat - was measured 15 % slower
+      // per step: the polled pair then returns behind 10 KiB of other loads, most of which are repeated anyway.)
+      for (unsigned poll = 0;; ++poll) {
+        x[0][0] = rd.load_it(rd.it_of(0));
+        x[0][1] = rd.load_it(rd.it_of(1));
+        __builtin_amdgcn_sched_barrier(0);
+        if (poll == 0) {
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[ct][q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          operands_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+          operands_settle(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (dead) break;
+        const unsigned stale = rd.tag_diff(x[0][0], rd.it_of(0), tagw) | rd.tag_diff(x[0][1], rd.it_of(1), tagw);
+        if (__builtin_amdgcn_ballot_w64(stale > 0xffffu) == 0ull) break;
+        if (poll >= rd.limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+          st_relaxed(err, 1u);
+          dead = true;
+          break;
+        }
+        PROF_POLLS(1)
+      }
+      PROF_MARK(5)
+#pragma unroll
+      for (int i = 2; i < NIT; ++i) issue_dma(i);
+      __builtin_amdgcn_sched_barrier(0);
+      unsigned bad[NP];
+      // pair p + 1 becomes operands behind MFMA `at` of pair p: wait for its loads, read them from LDS (step -1);
+      // tag test and masking (steps 0 .. kPrepSteps - 1) follow a few MFMAs later, when the LDS reads have returned
+      auto prep = [&](auto P, int k) __attribute__((always_inline)) {
+        constexpr int p = decltype(P)::value;
+        u32x4 (&xp)[2] = x[p & 1];
+        if (k < 0) {
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIT - 2 - 2 * p) : "memory");     // all but the loads behind this pair have landed
+          xp[0] = rbuf[wave][2 * p][lane];
+          xp[1] = rbuf[wave][2 * p + 1][lane];
+          return;
+        }
+        const int second = k >= kPrepSteps / 2, i = 2 * p + second, kk = second ? k - kPrepSteps / 2 : k;
+        u32x4& xi = xp[second];
+        if (kk == 0) {
+          const unsigned mm = rd.tag_diff(xi, rd.it_of(i), tagw);
+          bad[p] = second ? (bad[p] | mm) : mm;
+        } else if (kk == 1) {
+          xi[1] &= 0xffffu;
+        } else {
+          xi[3] &= 0xffffu;
+        }
+      };
+      unsigned long long redo = 0ull;
+#pragma unroll
+      for (int k = 0; k < kPrepSteps; ++k) prep(std::integral_constant<int, 0>{}, k);
+      static_for<NP>([&](auto P) __attribute__((always_inline)) {
+        constexpr int p = decltype(P)::value;
+        constexpr std::integral_constant<int, (p + 1 < NP ? p + 1 : p)> P1{};
+        // the second pair's loads have just been issued: reading them early would only stall this pair's MFMAs
+        constexpr int read_at = p == 0 ? 15 : 2, prep_at = p == 0 ? 16 : 9;
+        __builtin_amdgcn_sched_barrier(0);
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad[p] > 0xffffu) == 0ull, 1)) {
+          operands_settle(x[p & 1][0], x[p & 1][1]);
+#pragma unroll
+          for (int o = 0; o < 2; ++o)
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                mma_one(2 * p + o, ct, q, x[p & 1][o]);
+                const int mm = (o * 2 + ct) * 4 + q;
+                if (p + 1 < NP && (mm == read_at || (mm >= prep_at && mm < prep_at + kPrepSteps))) {
+                  __builtin_amdgcn_sched_barrier(0);
+                  prep(P1, mm == read_at ? -1 : mm - prep_at);
+                  __builtin_amdgcn_sched_barrier(0);
+                }
+              }
+          if (p + 1 < NP) {
+#pragma unroll
+            for (int k = 0; k < kPrepSteps; ++k)
+              if (prep_at + k >= 16) prep(P1, k);            // what did not fit behind this pair's MFMAs
+          }
+        } else {
+          // Stale: the pair's loads are issued again at once, behind the others, and looked at after the last pair, so
+          // their round trip passes behind the MFMAs still to come.  (The counted waits of later pairs then wait for
+          // up to that many loads more than they need: loads complete in order, so they wait for no less.)
+          redo |= 3ull << (2 * p);
+          if (p > 0) {
+            issue_dma(2 * p);
+            issue_dma(2 * p + 1);
+          }
+          if (p + 1 < NP) {
+#pragma unroll
+            for (int k = -1; k < kPrepSteps; ++k) prep(P1, k);
+          }
+        }
+      });
+      if (redo >> 2) {                                     // the second look at what was fetched again
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        static_for<NP - 1>([&](auto P) __attribute__((always_inline)) {
+          constexpr int p = decltype(P)::value + 1;
+          if ((redo >> (2 * p)) & 1ull) {
+            const u32x4 y0 = rbuf[wave][2 * p][lane], y1 = rbuf[wave][2 * p + 1][lane];
+            if (__builtin_amdgcn_ballot_w64((rd.stale_bits(y0, rd.it_of(2 * p)) | rd.stale_bits(y1, rd.it_of(2 * p + 1))) != 0u) == 0ull) {
+              use_single(2 * p, y0);
+              use_single(2 * p + 1, y1);
+              redo &= ~(3ull << (2 * p));
+            }
+          }
+        });
+      }
+      PROF_REDO(__popcll(redo))
+      if (redo) {                                          // (a quarter of the loads at a time: registers)
+        rd.template fix_up_batch<NIT / 4, 0>(redo, dead, use_single);
+        rd.template fix_up_batch<NIT / 4, NIT / 4>(redo, dead, use_single);
+        rd.template fix_up_batch<NIT / 4, NIT / 2>(redo, dead, use_single);
+        rd.template fix_up_batch<NIT / 4, 3 * (NIT / 4)>(redo, dead, use_single);
+      }
+      mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3], acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+    }
+    fetch_zx(tau + 1, kSet ^ 1);      // after the ring loads: loads complete in order, and these come from HBM
+    PROF_MARK(0)
+    // (LDS addresses are formed anew in every step: hoisted out of the loop they stay in registers the loop does not have)
+    int lane_ = lane, u_ = u, r8_ = r8;
+    asm volatile("" : "+v"(lane_), "+v"(u_), "+v"(r8_));
+    // accumulator rows 4*(lane/16) + v: every row is one of this work-group's
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red_[wave][4 * (lane_ >> 4) + v][q * 32 + ct * 16 + (lane_ & 15)] = acc[ct][q][v];
+    PROF_MARK(1)
+    // this frame's x W_x + b was asked for one step ago: everything but the 8 loads just issued has completed
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, kParked, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ry = frame_of(d.y, t, y_bytes), rc = frame_of(d.cs, t, s_bytes), rh = frame_of(d.hprev, t, s_bytes >> 1);
+    const __amdgpu_buffer_rsrc_t rw = frame_of(d.gates, t, g_bytes, a.write_gates != 0);
+    // both cells first, then both ring stores (the recurrence's critical stores, close together so that the two halves
+    // of a row tile turn their tags at about the same time), then the outputs
+    CellOut o[2] = {};
+    bool valid[2];
+    unsigned h_bits[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int rr = r8_ + 8 * k;
+      valid[k] = active[k] && t < L[k];
+      if (valid[k]) {
+        float zh[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) zh[q] = red_[0][rr][q * 32 + u_] + red_[1][rr][q * 32 + u_] + red_[2][rr][q * 32 + u_] + red_[3][rr][q * 32 + u_];
+        float zx[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) zx[q] = zxs[kSet][wave][k * 4 + q][lane_];
+        o[k] = lstm_cell(zh, zx, c[k]);
+        c[k] = o[k].c; h[k] = o[k].h;
+      }
+      h_bits[k] = pack_bf16x2(h[k], 0.f) & 0xffffu;         // inactive threads hold h = 0: padding rows / units publish zeros
+    }
+    PROF_MARK(2)
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const unsigned x0 = h_bits[k];
+      const unsigned x1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits[k], 0x101, 0xf, 0xf, true);
+      const unsigned x2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits[k], 0x102, 0xf, 0xf, true);
+      const u32x2 unit = {x0 | (x1 << 16), x2 | (((unsigned)(tau + 2) & 0xffffu) << 16)};
+      if (local) __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off(k), 0, 1);
+      else __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off(k), 0, 16);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {          // layer outputs and what the backward pass needs (2: non-temporal)
+      __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(valid[k] ? h_bits[k] : 0u), ry, y_off(k), 0, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c[k]), rc, s_off(k), 0, 2);
+      __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h_prev_bits[k], rh, s_off(k) >> 1, 0, 2);
+      const unsigned gw = valid[k] ? g_off(k) : kParked;
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[k].gi), rw, gw, 0u, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[k].gf), rw, gw, 4u * n, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[k].gg), rw, gw, 8u * n, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[k].go), rw, gw, 12u * n, 2);
+      h_prev_bits[k] = h_bits[k];
+    }
+    PROF_MARK(3)
+  };
+  for (int tau = 0; tau < T; tau += 2) {
+    step(tau, std::integral_constant<int, 0>{});
+    if (tau + 1 < T) step(tau + 1, std::integral_constant<int, 1>{});
+  }
+  PROF_DUMP("fwd16r", T)
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int b = rt * 16 + r8 + 8 * k;
+    if (active[k]) {
+      d.cstate[(long)b * n + j] = c[k];
+      d.hstate[(long)b * n + j] = h[k];
+    }
   }
 }
 
@@ -1583,6 +1931,14 @@ bool slab_fits(K kernel, int grid_x, int rows_per_y, int ndir) {
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
   if (a.nkc > kLLMaxNkcFwd) return hipErrorCooperativeLaunchTooLarge;
   if (!offsets_fit(a.B, a.n, std::max(a.d[0].ldy, a.d[a.ndir - 1].ldy), (long)cdiv(a.B, 16) * a.nkc * 1024)) return hipErrorCooperativeLaunchTooLarge;
+  const int t32 = cdiv(cdiv(a.n, 16), 2), nrt = cdiv(a.B, 16);
+  // more rows than the 32 x 8 form holds in one launch: 32 units x 16 rows, if that takes a single launch
+  if ((long)t32 * 2 * nrt * a.ndir > capacity(persist_fwd8_kernel<kLLMaxNkcFwd / 4>) &&
+      (long)t32 * nrt * a.ndir <= capacity(persist_fwd16r_kernel<kLLMaxNkcFwd / 4>)) {
+    const hipError_t e16 = coop_slabs(persist_fwd16r_kernel<kLLMaxNkcFwd / 4>, t32, 16, a, s);
+    if (e16 != hipErrorCooperativeLaunchTooLarge) return e16;
+    (void)hipGetLastError();
+  }
   // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
   hipError_t e = coop_slabs(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, cdiv(cdiv(a.n, 16), 2), 8, a, s);
   if (e != hipErrorCooperativeLaunchTooLarge) return e;
