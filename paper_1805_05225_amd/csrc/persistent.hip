@@ -1552,14 +1552,17 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   // One time step.  `in` holds the inputs of this step's frame and `in_next` receives those of the next; the loop
   // below calls it with the two in alternating roles, because a copy at the end of a step would have to wait for
   // the loads (and, counted with them, the step's stores) at that point.
-  auto step = [&](const int tau, const In& in, In& in_next) __attribute__((always_inline)) {
+  // `ring_c`: the step reads partial sums (every step but the first); `pointwise_c`: it has a frame (every step but the
+  // last, which only collects the Dh that leaves the layer).  Constants of the call, so that the loop below is free
+  // of the two exceptions: with them inside, the compiler's wait counts in the loop allowed for paths it never takes.
+  auto step = [&](const int tau, const In& in, In& in_next, auto ring_c, auto pointwise_c) __attribute__((always_inline)) {
     PROF_MARK(4)
     // (told to be wave-uniform: computed next to per-lane uses of tau it ends up in vector registers, and a buffer
     // descriptor derived from it is then applied lane by lane in a loop)
     const int sigma = __builtin_amdgcn_readfirstlane(T - 1 - tau);
     const int t = d.rev ? T - 1 - tau : tau;
     const int t_next = d.rev ? t - 1 : t + 1;
-    const bool pointwise = tau >= 0;
+    constexpr bool pointwise = decltype(pointwise_c)::value;
     const bool valid = pointwise && active && t < L;
 
     // The gate gradients of a valid frame, dh = dy + Dh (recurrent_dev.h has the plain form):
@@ -1576,7 +1579,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         f_o = tc * in.go * (1.f - in.go);
       }
     };
-    if (sigma > 0) {
+    if constexpr (decltype(ring_c)::value) {
       RingReader rd;
       rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + ring_tile), 0, ntile2 * kPartBytes,
                                                 kBufFlags);
@@ -1615,6 +1618,10 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
           PROF_POLLS(1)
         }
         PROF_MARK(5)
+        // Nothing is outstanding here (the poll has just been waited for, and loads complete in order).  Said with an
+        // instruction the compiler takes note of: otherwise it makes the pointwise part below wait for this frame's
+        // inputs, asked for a step ago, with a count that also waits for the next frame's, just asked for.
+        __builtin_amdgcn_s_waitcnt(0x0f70);                // vmcnt(0)
 #pragma unroll
         for (int i = 2; i < NPW; ++i) x[i] = rd.load_it(rd.it_of(i));
         __builtin_amdgcn_sched_barrier(0);
@@ -1623,8 +1630,6 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         add(ps, x[0]);
         add(ps, x[1]);
         factors();
-        in_next = fetch_in(tau - 1);  // behind the ring loads: loads complete in order, and these come from HBM
-        in_next.c_new = in.c_prev;
         __builtin_amdgcn_sched_barrier(0);
         unsigned long long redo = 0ull;
         constexpr int kGroup = (NPW - 2) / 2;              // the other loads: two groups
@@ -1648,7 +1653,16 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
           }
         }
         PROF_REDO(__popcll(redo))
-        if (redo) rd.fix_up_batch<NPW>(redo, dead, [&](int, const u32x4& v) __attribute__((always_inline)) { add(ps, v); });
+        if (redo) {
+          rd.fix_up_batch<NPW>(redo, dead, [&](int, const u32x4& v) __attribute__((always_inline)) { add(ps, v); });
+          // (nothing of that is outstanding any more - said with an instruction the compiler takes note of: it cannot tell
+          // from the loop's exits, and would make whatever reuses those registers below wait for every load in flight)
+          __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+        }
+        // The next frame's inputs, from HBM.  Loads complete in the order of issue: asked for in front of the groups
+        // above (where their latency would be covered best) they held up every ring load behind them - a tenth of the step.
+        in_next = fetch_in(tau - 1);
+        in_next.c_new = in.c_prev;
       }
       PROF_MARK(0)
 #pragma unroll
@@ -1741,9 +1755,19 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     }
   };
   // (tau is told to be wave-uniform: computed next to per-lane uses it ends up in vector registers)
-  for (int tau = T - 1; tau >= -1; tau = __builtin_amdgcn_readfirstlane(tau) - 2) {
-    step(tau, in_a, in_b);
-    if (tau - 1 >= -1) step(__builtin_amdgcn_readfirstlane(tau - 1), in_b, in_a);
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  step(T - 1, in_a, in_b, no, yes);                        // (T >= 2)
+  int tau = T - 2;
+  for (; tau >= 1; tau = __builtin_amdgcn_readfirstlane(tau) - 2) {
+    step(tau, in_b, in_a, yes, yes);
+    step(__builtin_amdgcn_readfirstlane(tau - 1), in_a, in_b, yes, yes);
+  }
+  if (tau == 0) {
+    step(0, in_b, in_a, yes, yes);
+    step(-1, in_a, in_b, yes, no);
+  } else {
+    step(-1, in_b, in_a, yes, no);
   }
   PROF_DUMP("bwdp", T)
   if (active) {
