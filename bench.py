@@ -24,6 +24,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 BF16_PEAK_TFLOPS = 2500.0
+# The benchmark owns the device and uses one stream: the single-launch recurrent kernels are started with ordinary
+# launches (LSTM_FLAG_PLAIN_LAUNCH, 16); every timed run ends with a check that no bounded wait expired.
+LAUNCH_FLAGS = 16
 
 
 def build_stack(inp, Bn):
@@ -52,7 +55,7 @@ class Stack:
         wmax = 0
         cur_in = x.shape[2]
         for (Wx, Wh, b) in layers:
-            desc = Bn.make_desc(T, B, cur_in, n, Bn.LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else Bn.LSTM_F32)
+            desc = Bn.make_desc(T, B, cur_in, n, Bn.LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else Bn.LSTM_F32, 1, LAUNCH_FLAGS)
             rb, wb = Bn.query(desc, True)
             wmax = max(wmax, wb)
             desc.reserve_bytes = rb
@@ -115,7 +118,7 @@ class MixedStack:
         cur = x
         for (Wx, Wh, b) in layers:
             D = Wx.shape[0]
-            desc = Bn.make_desc(T, B, cur.shape[2], n, Bn.LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else Bn.LSTM_F32)
+            desc = Bn.make_desc(T, B, cur.shape[2], n, Bn.LSTM_BF16_F32STATE if x.dtype == torch.bfloat16 else Bn.LSTM_F32, 1, LAUNCH_FLAGS)
             rb, wb = Bn.query(desc, D == 2)
             wmax = max(wmax, wb)
             desc.reserve_bytes = rb
@@ -528,7 +531,7 @@ class PooledStack:
         self.frames_per_layer = []
         for k, (Wx, Wh, b) in enumerate(layers):
             T, cur_in = cur.shape[0], cur.shape[2]
-            desc = Bn.make_desc(T, B, cur_in, n, dtype_id)
+            desc = Bn.make_desc(T, B, cur_in, n, dtype_id, 1, LAUNCH_FLAGS)
             rb, wb = Bn.query(desc, True)
             wmax = max(wmax, wb)
             desc.reserve_bytes = rb
@@ -781,7 +784,7 @@ def main():
                                "(T=%d, %d real frames), %s storage / f32 state, forward + backward" % (
                                    args.config, nl, cfg["n_in"], n, B, cfg["len_lo"], cfg["len_hi"], T, frames,
                                    cfg["dtype"]),
-                   "recurrent_path": "per_step" if args.per_step else "default"},
+                   "recurrent_path": "per_step" if args.per_step else "default", "launch": "plain (LSTM_FLAG_PLAIN_LAUNCH)"},
         "useful_tflops": flops * args.steps / dt / 1e12,
         "roofline": dominant,
         "roofline_forward_loop": roof_fwd if dominant is roof_bwd else roof_bwd,

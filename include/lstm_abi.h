@@ -68,12 +68,19 @@ enum {
   LSTM_FLAG_ACCUMULATE = 1, /* *_bwd: add into dW_x, dW_h, db instead of overwriting them        */
   LSTM_FLAG_PER_STEP = 2,   /* force one kernel launch per time step (no single-launch loop)     */
   LSTM_FLAG_INFERENCE = 4,  /* *_fwd: nothing is saved for backward; reserve may be NULL         */
-  LSTM_FLAG_WEIGHTS_PACKED = 8 /* *_fwd with T == 1 and LSTM_FLAG_INFERENCE: the caller states that the
+  LSTM_FLAG_WEIGHTS_PACKED = 8,/* *_fwd with T == 1 and LSTM_FLAG_INFERENCE: the caller states that the
                               * previous *_fwd call on this workspace had the same T, B, n_in, n, dtype,
                               * bidirectionality and the same W_x, W_h contents, so the packed copy of the
                               * weights that the workspace still holds is used again instead of being
                               * rebuilt (a false statement gives wrong results, not an error).  Ignored
                               * by every other call. */
+  LSTM_FLAG_PLAIN_LAUNCH = 16 /* the single-launch recurrent kernels, whose work-groups wait for each other
+                              * and therefore must all be resident at once, are started with an ordinary
+                              * launch instead of a cooperative one (which costs tens of microseconds of
+                              * idle device per launch).  The caller states that nothing else occupies the
+                              * device while the call's work runs (no other stream, no other process).
+                              * If that is false the work-groups' bounded waits expire: the call's outputs
+                              * are invalid and lstm_sync_status() says so; nothing hangs. */
 };
 
 typedef struct {

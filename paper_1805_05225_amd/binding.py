@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm.so"))   # override: diagnostic builds
 
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
-FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED = 1, 2, 4, 8
+FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED, FLAG_PLAIN_LAUNCH = 1, 2, 4, 8, 16
 EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_time_pool_fwd", "lstm_time_pool_bwd", "lstm_attention_query", "lstm_attention_step",
            "lstm_readout_query", "lstm_readout", "lstm_beam_query", "lstm_beam_step", "lstm_beam_step_static", "lstm_beam_gather", "lstm_embed",
            "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",

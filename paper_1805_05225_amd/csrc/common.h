@@ -174,6 +174,7 @@ struct PFwdArgs {
   unsigned* sync; unsigned spin_limit;
   unsigned* xcc;      // NULL or one zeroed word per work-group (see PBwdArgs)
   int rt0;            // set by the launcher: first 16-row tile of the batch that this launch handles
+  bool plain_launch;  // ordinary instead of cooperative launch (the caller vouches that the device is otherwise idle)
 };
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s);
 
@@ -194,6 +195,7 @@ struct PBwdArgs {
   unsigned* sync; unsigned spin_limit;
   unsigned* xcc;      // NULL or one zeroed word per work-group: lets an exchange group find out whether it shares an XCD
   int rt0;            // set by the launcher: first 16-row tile of the batch that this launch handles
+  bool plain_launch;  // ordinary instead of cooperative launch (the caller vouches that the device is otherwise idle)
 };
 // Which single-launch backward kernel fits the device for this problem (decided before W_h is packed, because the
 // forms pack it differently): partial sums of Dh exchanged (fastest; W_h via launch_pack_wh_bwdp, ring of

@@ -39,7 +39,7 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   const long TB = (long)d->T * d->B;
   if (TB >= (1L << 31) || (long)d->n * 4 >= (1L << 29) || d->n_in >= (1 << 29) || d->B >= (1 << 24)) return LSTM_ERR_DIM;
   if (d->dtype != LSTM_F32 && d->dtype != LSTM_BF16_F32STATE) return LSTM_ERR_UNSUPPORTED;
-  if (d->flags & ~(LSTM_FLAG_ACCUMULATE | LSTM_FLAG_PER_STEP | LSTM_FLAG_INFERENCE | LSTM_FLAG_WEIGHTS_PACKED)) return LSTM_ERR_UNSUPPORTED;
+  if (d->flags & ~(LSTM_FLAG_ACCUMULATE | LSTM_FLAG_PER_STEP | LSTM_FLAG_INFERENCE | LSTM_FLAG_WEIGHTS_PACKED | LSTM_FLAG_PLAIN_LAUNCH)) return LSTM_ERR_UNSUPPORTED;
   if (d->reserved != 0) return LSTM_ERR_UNSUPPORTED;
   p->T = d->T; p->B = d->B; p->n_in = d->n_in; p->n = d->n; p->D = bidir ? 2 : 1;
   p->bf16 = d->dtype == LSTM_BF16_F32STATE;
@@ -308,6 +308,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     if (use_ll) {
       PFwdArgs pa = {};
       pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_f; pa.T = p.T; pa.ndir = p.D; pa.write_gates = infer ? 0 : 1;
+      pa.plain_launch = (desc->flags & LSTM_FLAG_PLAIN_LAUNCH) != 0;
       pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
       pa.xcc = (unsigned*)(ws + p.ws_sync) + 64 + 2 * (size_t)p.nrt;
       const size_t frag_dir = (size_t)p.nrt * p.nkc_ll_f * 1024;
@@ -422,6 +423,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   // single-launch path: bf16 storage, at least two steps, and one of the kernel forms fits the device
   PBwdArgs pa = {};
   pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_b; pa.T = p.T; pa.ndir = p.D;
+  pa.plain_launch = (desc->flags & LSTM_FLAG_PLAIN_LAUNCH) != 0;
   pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
   pa.xcc = (unsigned*)(ws + p.ws_sync) + 64 + 2 * (size_t)p.nrt;
   int variant = kBwdNone;

@@ -1930,7 +1930,10 @@ hipError_t coop_slabs(K kernel, int grid_x, int rows_per_y, const A& a, hipStrea
       if (e != hipSuccess) return e == hipErrorCooperativeLaunchTooLarge ? hipErrorLaunchFailure : e;
     }
     void* args[] = {&copy};
-    const hipError_t e = hipLaunchCooperativeKernel((const void*)kernel, grid, dim3(256), args, 0, s);
+    // (the grid has been checked against what the device holds at once either way; a cooperative launch goes through a
+    // queue of its own, and crossing to it and back leaves the device idle for tens of microseconds)
+    const hipError_t e = a.plain_launch ? hipLaunchKernel((const void*)kernel, grid, dim3(256), args, 0, s)
+                                        : hipLaunchCooperativeKernel((const void*)kernel, grid, dim3(256), args, 0, s);
     if (e != hipSuccess) {
       (void)hipGetLastError();
       if (rt0 == 0) return hipErrorCooperativeLaunchTooLarge;          // the first launch was refused: nothing has run

@@ -84,6 +84,8 @@ def test_direction_dtype_flag_errors():
     assert _fwd(d) == -4
     d = good_desc(); d.flags = 64
     assert _fwd(d) == -4
+    d = good_desc(flags=Bn.FLAG_PLAIN_LAUNCH)                  # a known flag: the sizes are those without it
+    assert (d.reserve_bytes, d.workspace_bytes) == (good_desc().reserve_bytes, good_desc().workspace_bytes)
     d = good_desc(); d.reserved = 1
     assert _fwd(d) == -4
     d = good_desc(flags=Bn.FLAG_INFERENCE)

@@ -274,6 +274,25 @@ def test_single_launch_equals_per_step(dt, B, n, T):
     compare(f2, g2, fo, go, TOL[dt])
 
 
+@pytest.mark.parametrize("B,n,T", [(32, 1024, 12), (64, 1000, 9), (41, 1024, 6), (70, 136, 25)])
+def test_plain_launch_equals_cooperative(B, n, T):
+    """LSTM_FLAG_PLAIN_LAUNCH starts the same kernels with an ordinary launch: same results (to the rounding of a
+    different summation order where a stale ring load was repeated), no bounded wait expired, oracle parity."""
+    rng = np.random.default_rng(3 * B + n + T)
+    lens = rng.integers(0, T + 1, B)
+    lens[0] = T
+    c = rnd_case(rng, T=T, B=B, n_in=24, n=n, D=2, lens=lens, dt="bf16", scale=0.1)
+    print("  plain launch vs cooperative", B, n, T, flush=True)
+    f1, g1 = run_gpu(c, "bf16", True)
+    f2, g2 = run_gpu(c, "bf16", True, flags=Bn.FLAG_PLAIN_LAUNCH)
+    for k in ("y", "c", "hT", "cT"):
+        check(k + " (launch modes)", f2[k], host(f1[k]), 1e-2)
+    for k in ("dx", "dW_x", "dW_h", "db", "dh0", "dc0"):
+        check(k + " (launch modes)", g2[k], host(g1[k]), 1e-2)
+    fo, go = run_oracle(c, True)
+    compare(f2, g2, fo, go, TOL["bf16"])
+
+
 def test_single_launch_random_shapes_bf16():
     """Seeded sweep over batch sizes, hidden sizes (multiples of 4 and not, below and above a 32-unit tile, padded
     and exact), lengths and directions: the single-launch kernels (or their fallbacks) against the oracle."""
@@ -470,7 +489,7 @@ def test_config4_deeper_layer_full_size():
     inp = synth.make(4, layers=1, n_in=2048)
     c = _config_case(inp)
     print("  config 4, deeper layer, full size: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
-    f, g = run_gpu(c, "bf16", True)
+    f, g = run_gpu(c, "bf16", True, flags=Bn.FLAG_PLAIN_LAUNCH)          # the launch mode bench.py times
     fo, go = run_oracle(c, True)
     compare(f, g, fo, go, TOL["bf16"])
     lens = inp["seq_lens"]
@@ -496,6 +515,8 @@ def test_config3_upper_layer_full_size():
     print("  config 3, upper layer, full size: T=%d frames=%d" % (inp["T"], synth.real_frames(inp)), flush=True)
     f, g = run_gpu(c, "bf16", True)
     fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL["bf16"])
+    f, g = run_gpu(c, "bf16", True, flags=Bn.FLAG_PLAIN_LAUNCH)          # the launch mode bench.py times
     compare(f, g, fo, go, TOL["bf16"])
 
 
