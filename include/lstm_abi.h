@@ -274,7 +274,10 @@ int lstm_embed(int B, int n, int V, const int32_t* label, const void* W_trg, con
 int lstm_sync_status(const void* workspace, int32_t* timed_out);
 
 /* Phase timing for benchmarks.  While enabled, every *_fwd / *_bwd call brackets its phases with
- * hipEvents recorded on the call's own stream (the only resource the library ever creates).
+ * hipEvents recorded on the call's own stream (the only resource the library ever creates):
+ * lstm_profile_enable(1) the recurrent loops and the hoisted products (LSTM_PHASE_GEMM_*, LSTM_PHASE_LOOP_*),
+ * lstm_profile_enable(2) also the short phases around them (LSTM_PHASE_PREP, LSTM_PHASE_DB), 0 none.  An event
+ * between two kernels costs a few microseconds of idle device, which is why the short phases are optional.
  * lstm_profile_read() waits for the recorded events, adds each phase's elapsed milliseconds and
  * kernel-launch count into ms[LSTM_PHASE_COUNT] / launches[LSTM_PHASE_COUNT] (caller zeroes them),
  * and releases the events.  Not thread-safe; meant for a single benchmarking thread. */

@@ -157,7 +157,7 @@ int check_device() {
 
 // ---- optional phase timing (hipEvents on the caller's stream) -----------------------------------
 struct PhaseRec { int phase; long launches; hipEvent_t e0, e1; };
-bool g_profile = false;
+int g_profile = 0;              // 0 off, 1 recurrent loops and hoisted products, 2 every phase
 std::vector<PhaseRec> g_recs;
 
 struct Phase {
@@ -165,6 +165,9 @@ struct Phase {
   hipStream_t s;
   Phase(int phase, long launches, hipStream_t stream) : s(stream) {
     if (!g_profile) return;
+    // (an event between two kernels leaves the device idle for some microseconds: the short set-up phases are
+    // bracketed only on request)
+    if (g_profile < 2 && (phase == LSTM_PHASE_PREP || phase == LSTM_PHASE_DB)) return;
     PhaseRec r{phase, launches, nullptr, nullptr};
     if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) { (void)hipGetLastError(); return; }
     (void)hipEventRecord(r.e0, s);
@@ -742,7 +745,7 @@ int lstm_sync_status(const void* workspace, int32_t* timed_out) {
 }
 
 int lstm_profile_enable(int on) {
-  lstm::g_profile = on != 0;
+  lstm::g_profile = on < 0 ? 0 : on > 2 ? 2 : on;
   return LSTM_OK;
 }
 int lstm_profile_read(double* ms, int64_t* launches) {
