@@ -746,22 +746,33 @@ def main():
 
     def loop_roofline(phase, row_bytes, name):
         ms, launches = prof[phase]
+        layer_runs = args.steps * nl                                # times the loop of one layer ran in the timed region
+        per_layer = launches / max(layer_runs, 1)                   # 1; 2 where the batch takes two launches; T on the per-step path
+        per_step_path = T > 2 and per_layer >= T                    # one launch per time step: W_h is not resident
         per_launch_ms = ms / max(launches, 1)
-        launch_bytes = row_bytes * frames * 2                      # both directions, real frames only
-        achieved = launch_bytes / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
-        padded = row_bytes * T * B * 2 / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
-        step_bytes = launch_bytes / T
-        tr_bytes = traffic.get(phase)
-        return {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        layer_ms = ms / max(layer_runs, 1)
+        frame_bytes = row_bytes * frames * 2                        # both directions, real frames only
+        # With one launch per time step nothing stays on chip between launches: every launch also reads W_h of both
+        # directions (n x 4n values each), which belongs to the algorithmic bytes of THAT kernel.
+        weight_bytes = 2 * n * 4 * n * esz * T if per_step_path else 0
+        layer_bytes = frame_bytes + weight_bytes
+        launch_bytes = layer_bytes / max(per_layer, 1)
+        achieved = layer_bytes / (layer_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        padded = (row_bytes * T * B * 2 + weight_bytes) / (layer_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        step_bytes = layer_bytes / T
+        tr_bytes = None if per_step_path else traffic.get(phase)
+        return {"bound": "hbm", "kernel": name + (" (one launch per time step: float storage has no single-launch kernel)" if per_step_path else ""),
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": tr_bytes,
                 "traffic_ratio": (tr_bytes / launch_bytes) if tr_bytes else None, "launches": int(launches),
                 "avg_launch_ms": per_launch_ms, "us_per_time_step": ms * 1e3 / max(steps_total, 1),
                 "step_roofline_us": step_bytes / (HBM_PEAK_GBS * 1e9) * 1e6,
                 "algorithmic_bytes_per_launch": launch_bytes, "algorithmic_bytes_per_time_step": step_bytes,
+                "weight_bytes_per_launch": (2 * n * 4 * n * esz) if per_step_path else 0,
                 "frac_counting_padded_frames": padded / HBM_PEAK_GBS}
 
-    roof_bwd = loop_roofline("loop_bwd", bwd_row_bytes, "backward recurrent loop (both directions, one launch per layer)")
-    roof_fwd = loop_roofline("loop_fwd", fwd_row_bytes, "forward recurrent loop (both directions, one launch per layer)")
+    roof_bwd = loop_roofline("loop_bwd", bwd_row_bytes, "backward recurrent loop (both directions)")
+    roof_fwd = loop_roofline("loop_fwd", fwd_row_bytes, "forward recurrent loop (both directions)")
     # hoisted products: algorithmic flops per benchmark step (the products run over the real frames only)
     gemm_flops = {"gemm_zx": 0.0, "gemm_dx": 0.0, "gemm_dwx": 0.0, "gemm_dwh": 0.0}
     for l in range(nl):
