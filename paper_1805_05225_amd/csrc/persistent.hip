@@ -690,6 +690,10 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad[p] > 0xffffu) == 0ull, 1)) {
           operands_settle(ops[p][0], ops[p][1], ops[p][2], ops[p][3]);
+          // The next frame's x W_x + b, from HBM, goes out where this wavefront's last ring load has arrived.  The CU hands
+          // loads back in the order of issue, other wavefronts' included: a pair earlier, it holds up the ring loads still
+          // in flight (+17 % per step); behind the last pair's MFMAs, where it used to be, it is in the next step's poll's way (+3 %).
+          if (p == NP - 1) fetch_zx(tau + 1, zx_next);
 #pragma unroll
           for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -708,6 +712,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
               }
         } else {                                           // rare once the sample has turned
           redo |= 3ull << (2 * p);
+          if (p == NP - 1) fetch_zx(tau + 1, zx_next);
           if (p + 1 < NP) {
             // The empty statement makes the loads' registers new values on this path: instructions that are the
             // same on both paths are moved in front of the branch, and with them the wait for the next pair's loads.
@@ -718,12 +723,14 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
         }
       }
       PROF_REDO(__popcll(redo))
-      if (redo) rd.fix_up_batch<NL>(redo, dead, use_single);
+      if (redo) {
+        rd.fix_up_batch<NL>(redo, dead, use_single);
+        // (nothing of that is outstanding any more - said with an instruction the compiler takes note of: it cannot tell
+        // from the loop's exits, and would make whatever reuses those registers below wait for every load in flight)
+        __builtin_amdgcn_s_waitcnt(0x0f70);                // vmcnt(0)
+      }
       mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3], acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
     }
-    // after the ring loads: loads complete in order, and these come from HBM.  (Issued earlier, between the first
-    // pair's MFMAs, they made the step 15 % slower.)
-    fetch_zx(tau + 1, zx_next);
     PROF_MARK(0)
     // accumulator rows 4*(lane/16) + v; this work-group's rows sit in fragment rows 0..7
     if (lane < 32) {
@@ -976,6 +983,7 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
         }
       };
       unsigned long long redo = 0ull;
+      bool zx_asked = false;
 #pragma unroll
       for (int k = 0; k < kPrepSteps; ++k) prep(std::integral_constant<int, 0>{}, k);
       static_for<NP>([&](auto P) __attribute__((always_inline)) {
@@ -986,6 +994,12 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad[p] > 0xffffu) == 0ull, 1)) {
           operands_settle(x[p & 1][0], x[p & 1][1]);
+          // The next frame's x W_x + b goes out where this wavefront's last ring load has arrived (see the 32 x 8 kernel) -
+          // unless a pair is being fetched again: the second look below waits for everything in flight, and these come from HBM.
+          if (p == NP - 1 && redo == 0ull) {
+            fetch_zx(tau + 1, kSet ^ 1);
+            zx_asked = true;
+          }
 #pragma unroll
           for (int o = 0; o < 2; ++o)
 #pragma unroll
@@ -1042,8 +1056,8 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
         rd.template fix_up_batch<NIT / 4, 3 * (NIT / 4)>(redo, dead, use_single);
       }
       mfma_settle(acc[0][0], acc[0][1], acc[0][2], acc[0][3], acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+      if (!zx_asked) fetch_zx(tau + 1, kSet ^ 1);
     }
-    fetch_zx(tau + 1, kSet ^ 1);      // after the ring loads: loads complete in order, and these come from HBM
     PROF_MARK(0)
     // (LDS addresses are formed anew in every step: hoisted out of the loop they stay in registers the loop does not have)
     int lane_ = lane, u_ = u, r8_ = r8;
