@@ -138,23 +138,32 @@ struct BwdArgs {
 hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s);
 
 // Single-launch ("persistent") variants for bfloat16 storage: one launch runs every time step with
-// W_h resident in registers.  A work-group owns 16 hidden units for 16 batch rows.  What crosses
-// work-groups (h_t forward, dz_t backward) travels through a two-slot ring in global memory whose
-// every 8-byte unit carries three bf16 values AND a 16-bit step tag, so a consumer needs no barrier
-// and no fence: it re-reads the ring until every tag shows the step it waits for.
-//   K axis of the ring ("slots"): producer p (unit tile) owns kLLSlots consecutive slots per row;
-//   slot w inside a producer: unit m = w/4, position w%4; position 3 is the tag, positions 0..2
-//   carry value 3m + pos (values beyond the producer's count are padding).  Chunks of 8 slots form
-//   MFMA A-fragments exactly as in the per-step kernels.
+// W_h resident in registers.  What crosses work-groups (h_t forward, dz_t or partial sums of Dh backward)
+// travels through a two-slot ring in global memory whose every 8-byte unit carries its values AND a tag
+// of the step that wrote it, so a consumer needs no barrier and no fence: it re-reads the ring until every
+// tag shows the step it waits for.
+//   K axis of the ring ("slots"): producer p (a tile of 16 units) owns kLLSlots consecutive slots per row.
+//   Backward (dz): slot w inside a producer: unit m = w/4, position w%4; position 3 is a 16-bit tag, positions
+//   0..2 carry value 3m + pos (values beyond the producer's count are padding).
+//   Forward (h): all four positions of a unit carry values (slot w = value w).  |h| <= 1, so bit 14 of a bf16 h
+//   (the top bit of the exponent) is always 0; in position 3 that bit IS the tag - one bit is enough to tell a
+//   slot's new contents from what the step two earlier left there - and the reader clears it.  This makes the K
+//   axis dense: 16 slots per 16 units instead of 24, a third fewer chunks, loads and MFMAs per step.
+//   Chunks of 8 slots form MFMA A-fragments exactly as in the per-step kernels.
 // sync[0] is an error word set when a bounded wait expires.
-constexpr int kLLValsFwd = 16, kLLSlotsFwd = 24;     // 16 h values  -> 6 units  -> 3 chunks per producer and row
+constexpr int kLLValsFwd = 16, kLLSlotsFwd = 16;     // 16 h values  -> 4 units  -> 2 chunks per producer and row
 constexpr int kLLValsBwd = 64, kLLSlotsBwd = 88;     // 64 dz values -> 22 units -> 11 chunks
-constexpr int kLLMaxNkcFwd = 48, kLLMaxNkcBwd = 176; // register budget of the kernels (n <= 1024)
+constexpr int kLLMaxNkcFwd = 32, kLLMaxNkcBwd = 176; // register budget of the kernels (n <= 1024)
+constexpr unsigned kLLFwdTagBit = 0x40000000u;       // in the upper dword of a forward unit: bit 14 of the value in position 3
 inline int ll_nkc(int n, int slots) { return (int)((((long)(n + 15) / 16) * slots + 31) / 32); }
 __host__ __device__ inline int ll_slot_value(int w, int nvals) {
   const int pos = w & 3, v = 3 * (w >> 2) + pos;
   return (pos == 3 || v >= nvals) ? -1 : v;
 }
+// The tag bit of the data that step tau consumes (written by step tau - 1 into slot tau & 1; the initial contents of
+// slot 0 carry it for tau = 0): it alternates between consecutive uses of a slot and is 1 at a slot's first use, so a
+// zero-filled slot never looks written.
+__host__ __device__ inline unsigned ll_fwd_tag(unsigned tau) { return ((tau >> 1) & 1u) ^ 1u; }
 
 struct PFwdDir {
   const uint4* Wf;    // [unit tile][gate][nkc][64] chunks
@@ -177,6 +186,7 @@ struct PFwdArgs {
   bool plain_launch;  // ordinary instead of cooperative launch (the caller vouches that the device is otherwise idle)
 };
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s);
+bool persist_fwd_fits(const PFwdArgs& a);     // would launch_persist_fwd launch anything on this device?
 
 struct PBwdDir {
   const uint4* Wb;    // [unit tile][nkc][64] chunks
@@ -211,9 +221,13 @@ inline size_t bwdp_ring_bytes(int B, int n) {                                   
 }
 hipError_t launch_pack_wh_fwd_ll(const void* W_h, uint4* Wf, int n, int nkc, int ndir, hipStream_t s);
 hipError_t launch_pack_wh_bwd_ll(const void* W_h, uint4* Wb, int n, int nkc, int ndir, hipStream_t s);
-// h (float [ndir][B][n]) -> ring slot 0 with tag 1; ring slot 1 cleared
-hipError_t launch_pack_state_ll(const float* h, uint4* ring0, uint4* ring1, int B, int n, int nkc, int nrt, int ndir,
-                                hipStream_t s);
+// ring slot 0 = zeros carrying the tag of step 0, ring slot 1 cleared.  (The initial state does not travel through the ring:
+// launch_h0_term adds its product with W_h to the pre-activations of every row's first frame instead.)
+hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s);
+// gates[first frame of row b][b][:] += bf16(h0[b]) . W_h for every row with a frame (forward: t = 0; reverse: t = len - 1),
+// per direction; gates [T][B][4n] float with `gates_stride` elements between directions.
+hipError_t launch_h0_term(const float* h0, const void* W_h, float* gates, long gates_stride, const int* lens, int T, int B, int n,
+                          int ndir, int rev0, int rev1, hipStream_t s);
 
 // Weight / state packing and small helpers (all enqueue-only).
 hipError_t launch_pack_wh_fwd(const void* W_h, uint4* Wf, int n, int nkc, int ndir, bool bf16, hipStream_t s);

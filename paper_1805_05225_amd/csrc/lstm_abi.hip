@@ -260,8 +260,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     Phase ph(LSTM_PHASE_PREP, 2, s);
     if (ll) {
       HIPCHK(launch_pack_wh_fwd_ll(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_ll_f, p.D, s));
-      HIPCHK(launch_pack_state_ll(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_ll_f, p.nrt,
-                                  p.D, s));
+      HIPCHK(launch_pack_state_ll((uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.nkc_ll_f, p.nrt, p.D, s));
     } else {
       HIPCHK(launch_pack_wh_fwd(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_f, p.D, p.bf16, s));
       HIPCHK(launch_pack_state(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_f, p.nrt,
@@ -330,10 +329,17 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         fd.hprev = infer ? nullptr : rs + d * p.res_dir_stride + p.res_hprev;
         fd.rev = bidir ? d == 1 : desc->direction == -1;
       }
-      hipError_t e;
-      {
+      hipError_t e = hipErrorCooperativeLaunchTooLarge;
+      if (persist_fwd_fits(pa)) {
+        // The initial state does not travel through the exchange ring (what does must keep |h| <= 1): its product with W_h
+        // goes into the pre-activations of every row's first frame, and the kernels start from zeros in the ring.
+        if (h0) {
+          Phase ph(LSTM_PHASE_PREP, 1, s);
+          HIPCHK(launch_h0_term((const float*)h0, W_h, gates, gates_stride, seq_lens, p.T, p.B, p.n, p.D, pa.d[0].rev, pa.d[D - 1].rev, s));
+        }
         Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
         e = launch_persist_fwd(pa, s);
+        if (e == hipErrorCooperativeLaunchTooLarge && h0) e = hipErrorLaunchFailure;   // the pre-activations are no longer what the per-step path expects
       }
       if (e == hipSuccess) done = true;
       else if (e == hipErrorCooperativeLaunchTooLarge) {   // nothing was launched (does not fit on the device all at once): one launch per step

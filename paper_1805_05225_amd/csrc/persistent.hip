@@ -89,7 +89,8 @@ struct RingReader {
   unsigned voff;                         // byte offset of this lane's first load (parked out of range if the lane is off)
   unsigned it_bytes;                     // byte distance between consecutive loads of a lane
   int lim, lim_step;                     // load `it` carries awaited tags for this lane iff lim_step*it < lim
-  unsigned tag;
+  unsigned tag;                          // the awaited tag as it sits in the upper half of a unit's second dword
+  bool bit_tag = false;                  // forward ring: the tag is one bit (kLLFwdTagBit), the rest of that half is a value
   unsigned* err;
   unsigned limit;
 
@@ -102,11 +103,11 @@ struct RingReader {
   // Lanes whose units carry no tag (padding inside the ring, chunks past the end) report nothing, whatever they read.
   __device__ __forceinline__ unsigned tag_diff(const u32x4& x, int it, unsigned tagw) const {
     const unsigned t = (x[1] ^ tagw) | (x[3] ^ tagw);
-    return expects(it) ? t : 0u;
+    return expects(it) ? (bit_tag ? t & kLLFwdTagBit : t) : 0u;
   }
   __device__ __forceinline__ unsigned stale_bits(const u32x4& x, int it) const {
     const unsigned d = ((x[1] >> 16) ^ tag) | ((x[3] >> 16) ^ tag);
-    return lim_step * it < lim ? d : 0u;
+    return lim_step * it < lim ? (bit_tag ? d & (kLLFwdTagBit >> 16) : d) : 0u;
   }
   // bounded wait on the wave's last chunk; returns the number of polls (diagnostics only)
   __device__ __forceinline__ unsigned wait_sample(bool& dead) const {
@@ -381,130 +382,9 @@ __device__ __forceinline__ WgCoord wg_coord() {
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward: z[16 rows, 4 gates x 16 units] = h[16 rows, K] W[K, 64]
-template <int NIT>
-__global__ __launch_bounds__(256) void persist_fwd_kernel(PFwdArgs a) {
-  __shared__ float red[4][16][65];
-  __shared__ unsigned short hb[16][18];
-  const WgCoord wg = wg_coord();
-  const PFwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
-  const int tile = wg.tile, rt = a.rt0 + wg.rt, ntiles = gridDim.x;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
-  unsigned* err = a.sync;
-  bool dead = false;
-
-  const int nitv = (nkc + 3) / 4, rot = tile % nitv;
-  uint4 w[NIT][4];                       // register set `it` holds the chunk that load `it` of the stream fetches
-#pragma unroll
-  for (int it = 0; it < NIT; ++it) {
-    const int kc = wave + 4 * rot_index(it, rot, nitv);
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      w[it][q] = kc < nkc ? d.Wf[((long)(tile * 4 + q) * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
-  }
-
-  const int r = tid >> 4, u = tid & 15;
-  const int b = rt * 16 + r, j = tile * 16 + u;
-  const bool active = b < B && j < n;
-  float c = 0.f, h = 0.f;
-  int L = 0;
-  if (active) {
-    c = d.cstate[(long)b * n + j];
-    h = d.hstate[(long)b * n + j];
-    L = clamp_len(a.lens, b, T);
-  }
-  // the unit this thread publishes (threads 0..95).  Consecutive threads write consecutive 8-byte units, so a
-  // wavefront's publish is one contiguous run of full cache lines: chunk tid/32, row (tid/2)%16, half tid%2.
-  const int r2 = (tid >> 1) & 15, m = ((tid >> 5) << 1) | (tid & 1);
-  const int cch = tile * 3 + (m >> 1);
-  const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r2) * 2 + (m & 1);
-
-  // x W_x + b of a frame does not depend on the recurrence: it is fetched one step ahead
-  float zx[4] = {0.f, 0.f, 0.f, 0.f}, zx_next[4] = {0.f, 0.f, 0.f, 0.f};
-  auto fetch_zx = [&](int tau, float (&z)[4]) {
-    const int t = d.rev ? T - 1 - tau : tau;
-    if (tau < T && active && t < L) {
-      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-      z[0] = gp[0]; z[1] = gp[n]; z[2] = gp[2 * n]; z[3] = gp[3 * n];
-    }
-  };
-  fetch_zx(0, zx);
-  PROF_DECL
-  for (int tau = 0; tau < T; ++tau) {
-    const int t = d.rev ? T - 1 - tau : tau;
-    const bool valid = active && t < L;
-    PROF_MARK(4)
-    const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
-    uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
-    const RingReader rd = make_reader(rin, nkc, ntiles * 3, wave, lane, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
-    const unsigned np_ = rd.wait_sample(dead);
-    (void)np_;
-    PROF_POLLS(np_)
-    PROF_MARK(5)
-    f32x4 acc[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    {
-      // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
-      auto use = [&](int it, uint4 av) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc[q] = Mma16<bf16_t>::run(av, w[it][q], acc[q]);
-      };
-      const unsigned long long redo = rd.stream<NIT, kWindow>(use);
-      PROF_REDO(__popcll(redo))
-      if (redo) rd.fix_up<NIT>(redo, dead, use);
-    }
-    fetch_zx(tau + 1, zx_next);       // after the ring loads: loads complete in order, and these come from HBM
-    PROF_MARK(0)
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][q * 16 + (lane & 15)] = acc[q][v];
-    PROF_MARK(1)
-    __syncthreads();
-
-    const float h_prev = h;
-    CellOut o = {};
-    if (valid) {
-      float zh[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) zh[q] = red[0][r][q * 16 + u] + red[1][r][q * 16 + u] + red[2][r][q * 16 + u] + red[3][r][q * 16 + u];
-      o = lstm_cell(zh, zx, c);
-      c = o.c; h = o.h;
-    }
-    hb[r][u] = f2bf_bits(h);          // inactive threads hold h = 0: padding rows / units publish zeros
-    __syncthreads();
-    PROF_MARK(2)
-    if (tid < 96) {                   // the recurrence's critical store goes out first
-      const int v0 = 3 * m;
-      const unsigned x0 = hb[r2][v0], x1 = v0 + 1 < 16 ? hb[r2][v0 + 1] : 0u, x2 = v0 + 2 < 16 ? hb[r2][v0 + 2] : 0u;
-      store_unit(rout, unit_index, x0, x1, x2, (unsigned)(tau + 2) & 0xffffu);
-    }
-    if (active) {                     // layer outputs and what the backward pass needs
-      Store<bf16_t>::store(d.y, ((long)t * B + b) * d.ldy + j, valid ? h : 0.f);
-      if (d.cs) d.cs[((long)t * B + b) * n + j] = c;
-      if (d.hprev) Store<bf16_t>::store(d.hprev, ((long)t * B + b) * n + j, h_prev);
-      if (valid && a.write_gates) {
-        float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-        gp[0] = o.gi; gp[n] = o.gf; gp[2 * n] = o.gg; gp[3 * n] = o.go;
-      }
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) zx[q] = zx_next[q];
-    PROF_MARK(3)
-  }
-  PROF_DUMP("fwd", T)
-  if (active) {
-    d.cstate[(long)b * n + j] = c;
-    d.hstate[(long)b * n + j] = h;
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// forward, second decomposition: a work-group owns 32 units for 8 batch rows (half a row tile); one load
-// serves two chunks (see make_reader_half).  Half the ring bytes per work-group, twice the W_h slice
-// (384 registers per lane).
+// forward: z[8 rows, 4 gates x 32 units] = h[8 rows, K] W[K, 128].  A work-group owns 32 units for 8 batch rows
+// (half a row tile); one load serves two chunks (see make_reader_half).  The W_h slice fills the 256 accumulation
+// registers of every lane (n = 1024: 8 register sets of 8 fragments).
 template <int NIT>
 __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
   __shared__ float red[2][4][8][129];                    // two copies, used by even and odd steps: one barrier per step
@@ -550,16 +430,20 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     h = d.hstate[(long)b * n + j];
     L = clamp_len(a.lens, b, T);
   }
-  // The unit this thread publishes.  A unit is three consecutive units' h of one row (plus the tag), and a row's 32
-  // units sit in 32 consecutive lanes, so the thread of every third unit of a 16-unit tile takes its neighbours' values
-  // through DPP shifts: no staging in shared memory, no second barrier.  m = which unit of the tile (0..5).
-  const int pp = u >> 4, m = (u & 15) / 3;
+  // The unit this thread publishes.  A unit is four consecutive units' h of one row (the tag is a bit of the fourth), and a
+  // row's 32 units sit in 32 consecutive lanes, so the thread of every fourth unit takes its neighbours' values
+  // through DPP shifts: no staging in shared memory, no second barrier.  m = which unit of the 16-unit tile (0..3).
+  const int pp = u >> 4, m = (u & 15) >> 2;
   const int t16p = tile2 * 2 + pp;
-  const int cch = t16p * 3 + (m >> 1);
+  const int cch = t16p * 2 + (m >> 1);
   const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + half * 8 + r8) * 2 + (m & 1);
-  const bool publishes = (u & 15) % 3 == 0 && t16p < ntiles16;
+  const bool publishes = (u & 3) == 0 && t16p < ntiles16;
   const bool local = a.xcc != nullptr &&
                      group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * (int)gridDim.x, gridDim.x, tile2, a.spin_limit);
+  // Has this row had a frame yet?  Until then it publishes zeros, not the initial state it carries: that state's product
+  // with W_h has been added to the pre-activations of the row's first frame by the host side, and what travels
+  // through the ring must keep |h| <= 1 (the tag bit).
+  bool started = false;
 
   // x W_x + b of a frame is read through a buffer descriptor that covers exactly that frame: a lane with nothing to
   // fetch (row past the batch, unit past n, frame past the row's length) has its offset parked outside and gets zeros
@@ -601,7 +485,8 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     PROF_MARK(4)
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
     uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
-    const RingReader rd = make_reader_half(rin, nkc, ntiles16 * 3, wave, lane, half, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
+    RingReader rd = make_reader_half(rin, nkc, ntiles16 * 2, wave, lane, half, ll_fwd_tag((unsigned)tau) << 14, err, a.spin_limit, rot);
+    rd.bit_tag = true;
     f32x4 acc[2][4];
     {
       // One MFMA of register set `it` into accumulator (ct, q).
@@ -610,7 +495,7 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
         else mfma_b_vgpr(acc[ct][q], a_op, wv[it >= kAccIts ? it - kAccIts : 0][ct][q]);
       };
       auto use_single = [&](int p, const u32x4& raw) {     // a load fetched again after the stream, tags still in it
-        const uint4 av_ = make_uint4(raw[0], raw[1] & 0xffffu, raw[2], raw[3] & 0xffffu);
+        const uint4 av_ = make_uint4(raw[0], raw[1] & ~kLLFwdTagBit, raw[2], raw[3] & ~kLLFwdTagBit);
         const uint4 av2_ = rotate_rows_by_8(av_);
         u32x4 av = {av_.x, av_.y, av_.z, av_.w}, av2 = {av2_.x, av2_.y, av2_.z, av2_.w};
         operands_settle(av, av2);
@@ -674,9 +559,9 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
           const unsigned m = rd.tag_diff(x[i], rd.it_of(i), tagw);
           bad[p] = second ? (bad[p] | m) : m;
         } else if (kk == 1) {
-          x[i][1] &= 0xffffu;
+          x[i][1] &= ~kLLFwdTagBit;
         } else if (kk == 2) {
-          x[i][3] &= 0xffffu;
+          x[i][3] &= ~kLLFwdTagBit;
           ops[p][2 * second] = x[i];
         } else {
           ops[p][2 * second + 1][kk - 3] = (unsigned)__builtin_amdgcn_mov_dpp((int)x[i][kk - 3], 0x128, 0xf, 0xf, false);
@@ -753,13 +638,15 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
       c = o.c; h = o.h;
     }
     const unsigned h_bits = pack_bf16x2(h, 0.f) & 0xffffu; // inactive threads hold h = 0: padding rows / units publish zeros
+    started = started || valid;
     PROF_MARK(2)
     {                                 // the recurrence's critical store goes out first
-      // h of the next and the next but one unit of the tile (DPP row_shl:1, row_shl:2; past the tile's end: zero)
-      const unsigned x0 = h_bits;
-      const unsigned x1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits, 0x101, 0xf, 0xf, true);
-      const unsigned x2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits, 0x102, 0xf, 0xf, true);
-      const u32x2 unit = {x0 | (x1 << 16), x2 | (((unsigned)(tau + 2) & 0xffffu) << 16)};
+      // h of the next three units of the tile (DPP row_shl:1, :2, :3; past the row of 16 lanes: zero)
+      const unsigned x0 = started ? h_bits : 0u;
+      const unsigned x1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0, 0x101, 0xf, 0xf, true);
+      const unsigned x2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0, 0x102, 0xf, 0xf, true);
+      const unsigned x3 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0, 0x103, 0xf, 0xf, true);
+      const u32x2 unit = {x0 | (x1 << 16), x2 | (x3 << 16) | (ll_fwd_tag((unsigned)tau + 1u) << 30)};
       const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, kParked, kBufFlags);
       // 1: workgroup scope, stays in this XCD's L2;  16: agent scope, written through
       if (local) __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off, 0, 1);
@@ -851,10 +738,11 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
       L[k] = clamp_len(a.lens, b, T);
     }
   }
-  const int pp = u >> 4, m = (u & 15) / 3;
+  const int pp = u >> 4, m = (u & 15) >> 2;                // the unit (four units' h, see the 32 x 8 kernel) this thread publishes
   const int t16p = tile2 * 2 + pp;
-  const int cch = t16p * 3 + (m >> 1);
-  const bool publishes = (u & 15) % 3 == 0 && t16p < ntiles16;
+  const int cch = t16p * 2 + (m >> 1);
+  const bool publishes = (u & 3) == 0 && t16p < ntiles16;
+  bool started[2] = {false, false};                      // (see the 32 x 8 kernel)
   const bool local = a.xcc != nullptr &&
                      group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * (int)gridDim.x, gridDim.x, tile2, a.spin_limit);
 
@@ -902,7 +790,8 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
     const int t = d.rev ? T - 1 - tau : tau;
     PROF_MARK(4)
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
-    const RingReader rd = make_reader(rin, nkc, ntiles16 * 3, wave, lane, (unsigned)(tau + 1) & 0xffffu, err, a.spin_limit, rot);
+    RingReader rd = make_reader(rin, nkc, ntiles16 * 2, wave, lane, ll_fwd_tag((unsigned)tau) << 14, err, a.spin_limit, rot);
+    rd.bit_tag = true;
     f32x4 acc[2][4];
     {
       auto mma_one = [&](int it, int ct, int q, const u32x4& a_op) __attribute__((always_inline)) {
@@ -910,7 +799,7 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
         else mfma_b_vgpr(acc[ct][q], a_op, wv[it >= kAccIts ? it - kAccIts : 0][ct][q]);
       };
       auto use_single = [&](int i, const u32x4& raw) {     // a load fetched again after the stream, tags still in it
-        u32x4 av = {raw[0], raw[1] & 0xffffu, raw[2], raw[3] & 0xffffu}, dummy = av;
+        u32x4 av = {raw[0], raw[1] & ~kLLFwdTagBit, raw[2], raw[3] & ~kLLFwdTagBit}, dummy = av;
         operands_settle(av, dummy);
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
@@ -977,9 +866,9 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
           const unsigned mm = rd.tag_diff(xi, rd.it_of(i), tagw);
           bad[p] = second ? (bad[p] | mm) : mm;
         } else if (kk == 1) {
-          xi[1] &= 0xffffu;
+          xi[1] &= ~kLLFwdTagBit;
         } else {
-          xi[3] &= 0xffffu;
+          xi[3] &= ~kLLFwdTagBit;
         }
       };
       unsigned long long redo = 0ull;
@@ -1096,14 +985,16 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
         c[k] = o[k].c; h[k] = o[k].h;
       }
       h_bits[k] = pack_bf16x2(h[k], 0.f) & 0xffffu;         // inactive threads hold h = 0: padding rows / units publish zeros
+      started[k] = started[k] || valid[k];
     }
     PROF_MARK(2)
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
-      const unsigned x0 = h_bits[k];
-      const unsigned x1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits[k], 0x101, 0xf, 0xf, true);
-      const unsigned x2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)h_bits[k], 0x102, 0xf, 0xf, true);
-      const u32x2 unit = {x0 | (x1 << 16), x2 | (((unsigned)(tau + 2) & 0xffffu) << 16)};
+      const unsigned x0 = started[k] ? h_bits[k] : 0u;
+      const unsigned x1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0, 0x101, 0xf, 0xf, true);
+      const unsigned x2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0, 0x102, 0xf, 0xf, true);
+      const unsigned x3 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0, 0x103, 0xf, 0xf, true);
+      const u32x2 unit = {x0 | (x1 << 16), x2 | (x3 << 16) | (ll_fwd_tag((unsigned)tau + 1u) << 30)};
       if (local) __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off(k), 0, 1);
       else __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off(k), 0, 16);
     }
@@ -1820,10 +1711,8 @@ __global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nk
   bf16_t v[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int s = (kc * 4 + g) * 8 + e;
-    const int p = s / kLLSlotsFwd, val = ll_slot_value(s - p * kLLSlotsFwd, kLLValsFwd);
-    const int k = p * 16 + val;
-    v[e] = (val >= 0 && k < n && j < n) ? Wd[(long)k * 4 * n + q * n + j] : (bf16_t)0.f;
+    const int k = (kc * 4 + g) * 8 + e;                    // forward ring: slot = unit index (kLLSlotsFwd = kLLValsFwd)
+    v[e] = (k < n && j < n) ? Wd[(long)k * 4 * n + q * n + j] : (bf16_t)0.f;
   }
   out[idx] = *(uint4*)v;
 }
@@ -1866,25 +1755,27 @@ __global__ void pack_wh_bwdp_kernel(const bf16_t* W, uint4* out, int n, int ntil
   }
   out[idx] = *(uint4*)v;
 }
-// initial state: unit index = ((((dir*nrt + rt)*nkc + kc)*64 + lane)*2 + half) ; ring0 gets h with tag 1, ring1 zeros
-__global__ void pack_state_ll_kernel(const float* h, uint4* ring0, uint4* ring1, int B, int n, int nkc, int nrt, long total) {
+// Initial contents of the forward ring, one 8-byte unit per thread: slot 0 = zeros that carry the tag of step 0, slot 1 = zeros.
+__global__ void pack_state_ll_kernel(uint4* ring0, uint4* ring1, long total) {
   long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int half = idx & 1, lane = (idx >> 1) & 63;
-  long rest = idx >> 7;
-  const int kc = rest % nkc; rest /= nkc;
-  const int rt = rest % nrt, dir = rest / nrt;
-  const int row = rt * 16 + (lane & 15), g = lane >> 4;
-  const int U = (kc * 4 + g) * 2 + half;       // unit-of-three index along K
-  const int p = U / 6, m = U - 6 * p;
-  unsigned x[3];
-#pragma unroll
-  for (int e = 0; e < 3; ++e) {
-    const int val = 3 * m + e, k = p * 16 + val;
-    x[e] = (val < 16 && k < n && row < B) ? (unsigned)f2bf_bits(h[((long)dir * B + row) * n + k]) : 0u;
-  }
-  ((unsigned long long*)ring0)[idx] = (unsigned long long)(x[0] | (x[1] << 16)) | ((unsigned long long)(x[2] | (1u << 16)) << 32);
+  ((unsigned long long*)ring0)[idx] = (unsigned long long)(ll_fwd_tag(0u) * kLLFwdTagBit) << 32;
   ((unsigned long long*)ring1)[idx] = 0ull;
+}
+// The initial state's share of the first frame: gates[t0(b)][b][col] += sum_k bf16(h0[b][k]) W_h[k][col], t0 = the row's
+// first frame in processing order.  One thread per column, a row per blockIdx.y; W_h rows are read coalesced.  Runs only
+// when the caller passes an initial state.
+__global__ __launch_bounds__(256) void h0_term_kernel(const float* h0, const bf16_t* W, float* gates, long gates_stride, const int* lens,
+                                                      int T, int B, int n, int rev0, int rev1) {
+  const int col = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y, dir = blockIdx.z;
+  const int L = clamp_len(lens, b, T);
+  if (col >= 4 * n || L <= 0) return;
+  const float* hb = h0 + ((long)dir * B + b) * n;
+  const bf16_t* Wd = W + (long)dir * n * 4 * n + col;
+  float acc = 0.f;
+  for (int k = 0; k < n; ++k) acc += bf_bits2f(f2bf_bits(hb[k])) * (float)Wd[(long)k * 4 * n];
+  const int t0 = (dir == 0 ? rev0 : rev1) ? L - 1 : 0;
+  gates[dir * gates_stride + ((long)t0 * B + b) * 4 * n + col] += acc;
 }
 
 std::mutex g_capacity_mu;
@@ -1980,11 +1871,16 @@ hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s) {
     if (e16 != hipErrorCooperativeLaunchTooLarge) return e16;
     (void)hipGetLastError();
   }
-  // preferred: 32 units x 8 rows per work-group (half the ring bytes per work-group); same number of work-groups
-  hipError_t e = coop_slabs(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, cdiv(cdiv(a.n, 16), 2), 8, a, s);
-  if (e != hipErrorCooperativeLaunchTooLarge) return e;
-  (void)hipGetLastError();
-  return coop_slabs(persist_fwd_kernel<kLLMaxNkcFwd / 4>, cdiv(a.n, 16), 16, a, s);
+  // 32 units x 8 rows per work-group
+  return coop_slabs(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, t32, 8, a, s);
+}
+// Would launch_persist_fwd launch anything?  (Asked before the initial state's term is added to the pre-activations,
+// which only the single-launch kernels expect there.)
+bool persist_fwd_fits(const PFwdArgs& a) {
+  if (a.nkc > kLLMaxNkcFwd) return false;
+  if (!offsets_fit(a.B, a.n, std::max(a.d[0].ldy, a.d[a.ndir - 1].ldy), (long)cdiv(a.B, 16) * a.nkc * 1024)) return false;
+  const int t32 = cdiv(cdiv(a.n, 16), 2);
+  return slab_fits(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, t32, 8, a.ndir);
 }
 int persist_bwd_variant(const PBwdArgs& a) {
   const int t32 = cdiv(cdiv(a.n, 16), 2);
@@ -2022,10 +1918,16 @@ hipError_t launch_pack_wh_bwd_ll(const void* W, uint4* Wb, int n, int nkc, int n
   hipLaunchKernelGGL(pack_wh_bwd_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wb, n, nkc, total);
   return hipGetLastError();
 }
-hipError_t launch_pack_state_ll(const float* h, uint4* ring0, uint4* ring1, int B, int n, int nkc, int nrt, int ndir,
-                                hipStream_t s) {
+hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s) {
   long total = (long)ndir * nrt * nkc * 64 * 2;
-  hipLaunchKernelGGL(pack_state_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, h, ring0, ring1, B, n, nkc, nrt, total);
+  hipLaunchKernelGGL(pack_state_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, ring0, ring1, total);
+  return hipGetLastError();
+}
+hipError_t launch_h0_term(const float* h0, const void* W_h, float* gates, long gates_stride, const int* lens, int T, int B, int n,
+                          int ndir, int rev0, int rev1, hipStream_t s) {
+  if (B <= 0 || T <= 0) return hipSuccess;
+  hipLaunchKernelGGL(h0_term_kernel, dim3(cdiv(4L * n, 256), B, ndir), dim3(256), 0, s, h0, (const bf16_t*)W_h, gates, gates_stride, lens, T,
+                     B, n, rev0, rev1);
   return hipGetLastError();
 }
 

@@ -293,6 +293,31 @@ def test_plain_launch_equals_cooperative(B, n, T):
     compare(f2, g2, fo, go, TOL["bf16"])
 
 
+@pytest.mark.parametrize("B,n,T", [(19, 1000, 7), (40, 1024, 6), (32, 264, 12)])
+def test_large_initial_state_single_launch(B, n, T):
+    """Initial hidden states far outside (-1, 1), rows of length 0, 1 and T, both directions.  The single-launch forward
+    kernels exchange h through units whose tag is a bit that |h| <= 1 leaves free; the initial state therefore never
+    travels that way (its product with W_h is added to each row's first frame), and rows that have not started publish
+    zeros.  Every output and gradient against the oracle."""
+    rng = np.random.default_rng(11 * B + n + T)
+    lens = rng.integers(0, T + 1, B)
+    lens[0], lens[1], lens[2] = T, 0, 1
+    c = rnd_case(rng, T=T, B=B, n_in=24, n=n, D=2, lens=lens, dt="bf16", scale=0.1)
+    # |h0| up to about 25, on bf16 values: the path rounds the initial state to bf16 where it enters a product, and at this
+    # magnitude that rounding alone would exceed the tolerance against an oracle that keeps the float values
+    c["h0"] = torch.from_numpy(c["h0"] * 12.0).to(torch.bfloat16).to(torch.float64).numpy()
+    print("  large initial state", B, n, T, "max |h0| %.1f" % np.abs(c["h0"]).max(), flush=True)
+    f, g = run_gpu(c, "bf16", True)
+    fo, go = run_oracle(c, True)
+    compare(f, g, fo, go, TOL["bf16"])
+    c1 = rnd_case(rng, T=T, B=B, n_in=24, n=n, D=1, lens=lens, dt="bf16", scale=0.1)
+    c1["h0"] = torch.from_numpy(c1["h0"] * 12.0).to(torch.bfloat16).to(torch.float64).numpy()
+    for direction in (1, -1):
+        f, g = run_gpu(c1, "bf16", False, direction)
+        fo, go = run_oracle(c1, False, direction)
+        compare(f, g, fo, go, TOL["bf16"])
+
+
 def test_single_launch_random_shapes_bf16():
     """Seeded sweep over batch sizes, hidden sizes (multiples of 4 and not, below and above a 32-unit tile, padded
     and exact), lengths and directions: the single-launch kernels (or their fallbacks) against the oracle."""
