@@ -217,7 +217,7 @@ hipError_t launch_pack_wh_bwdp(const void* W_h, uint4* Wb, int n, int ndir, hipS
 inline size_t bwdp_wh_bytes(int n) { return (size_t)((n + 31) / 32) * 262144; }                  // per direction
 inline size_t bwdp_ring_bytes(int B, int n) {                                                      // per direction and slot
   const size_t groups = 2 * (size_t)(((B > 0 ? B : 1) + 15) / 16), tiles = (size_t)((n + 31) / 32);
-  return groups * tiles * tiles * 1024;
+  return groups * tiles * tiles * 512;
 }
 hipError_t launch_pack_wh_fwd_ll(const void* W_h, uint4* Wf, int n, int nkc, int ndir, hipStream_t s);
 hipError_t launch_pack_wh_bwd_ll(const void* W_h, uint4* Wb, int n, int nkc, int ndir, hipStream_t s);

@@ -1344,18 +1344,27 @@ __global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
 // therefore a sum of bf16-rounded partial sums (accumulated in float), not a float product of bf16-rounded dz.
 //
 // With one wavefront per SIMD every instruction's latency is exposed (about 2 ns each), so the formats are chosen
-// to keep instruction counts low: an 8-byte unit holds values of ONE output for three ROWS (plus the tag), which
+// to keep instruction counts low: an 8-byte unit holds values of ONE output for four ROWS, which
 // is how an MFMA accumulator lane holds them, so a producer stores straight from its accumulators - no staging,
 // no cross-lane moves.  Ring layout per direction and slot:
-//   [row group][destination tile][producer tile][32 outputs][2 row halves] x 16 bytes,
-//   16 bytes = unit A (rows 4g, 4g+1, 4g+2, tag) + unit B (row 4g+3, 0, 0, tag).
+//   [row group][destination tile][producer tile][32 outputs][2 row halves] x 8 bytes (rows 4g .. 4g+3 as bf16).
+// The tag is ONE BIT, bit 14 of the fourth value (see the forward ring): the partial sums travel scaled by 2^-32 - the
+// packed W_h carries the factor, so the MFMAs deliver them scaled, and the consumer multiplies its sum by 2^32 - which
+// leaves that bit 0 for every partial sum below 2^33 in magnitude and changes no other bit of any value above 2^-94
+// (a power of two commutes with every rounding on the way).  A partial sum of 2^33 or more cannot be exchanged: its
+// unit looks stale or fresh at random; gradients of that size are past use, and the case mostly ends in an expired wait.
+// Half the bytes and half the ring loads of the format this replaces (3 values + a 16-bit tag per unit, 16 bytes per lane).
 // W_h slice in registers: w[kc][c] = B fragment of gate kc (K = this tile's 32 units) for column tile
 // wave*16 + c of the n outputs.
-constexpr int kPartBytes = 1024;                          // one (producer, destination tile)
+constexpr int kPartBytes = 512;                           // one (producer, destination tile)
+constexpr float kPartScale = 1.f / 4294967296.f;          // 2^-32
+// tag bit of the partial sums that backward step sigma (= T-1-tau) consumes: written by step sigma - 1 into slot
+// (sigma - 1) & 1; alternates between consecutive uses of a slot and is 1 at the first, so zero-filled slots look unwritten
+__device__ __forceinline__ unsigned part_tag(int sigma) { return ((((unsigned)sigma - 1u) >> 1) & 1u) ^ 1u; }
 
 template <int NPW>                                        // producers per wavefront at most: n <= 128 * NPW
 __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
-  __shared__ float red[4][8][33];
+  __shared__ float red[8][8][33];                        // [wavefront, producer of the pair][row][output]
   __shared__ __attribute__((aligned(16))) unsigned short zb[8][136];
   const WgCoord wg = wg_coord();
   const PBwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
@@ -1433,9 +1442,9 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
     in_a.c_new = ld_f(frame_of(d.cs, t0, s_bytes), t0 < L ? s_off : kParked, 0u);
   }
 
-  // consumer side: lane reads output lane/2, row half lane%2 of every producer's block
-  const int ccol = lane >> 1, cg = lane & 1;
-  const int nitv = (ntile2 + 3) / 4, rot = J % nitv;
+  // consumer side: a load covers two producers' blocks; lane reads output lane%32, all eight rows, of producer lane/32
+  const int ccol = lane & 31, chalf = lane >> 5;
+  const int nitv = (ntile2 + 7) / 8, rot = J % nitv;
   const long ring_tile = ((long)R * ntile2 + J) * ntile2 * (kPartBytes / 16);     // uint4 index of [R][J][0]
   // producer side: lanes 0..31 hold rows 4*(lane/16) .. +3 of output column lane%16 of each accumulator tile
   const int pg = (lane >> 4) & 1, pcol = lane & 15;
@@ -1450,7 +1459,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
 #pragma unroll
   for (int c = 0; c < 16; ++c) {
     const int Jd = wave * 8 + (c >> 1);
-    pub_off[c] = lane < 32 ? (unsigned)(((Jd * ntile2 + J) * 32 + (c & 1) * 16 + pcol) * 2 + pg) * 16u : 0xfff00000u;
+    pub_off[c] = lane < 32 ? (unsigned)(((Jd * ntile2 + J) * 32 + (c & 1) * 16 + pcol) * 2 + pg) * 8u : 0xfff00000u;
   }
 
   PROF_DECL
@@ -1488,24 +1497,29 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       RingReader rd;
       rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + ring_tile), 0, ntile2 * kPartBytes,
                                                 kBufFlags);
-      rd.voff = (unsigned)(wave * kPartBytes + lane * 16);
-      rd.it_bytes = 4u * kPartBytes; rd.chunks_per_it = 4;
-      rd.lim = ntile2 - wave; rd.lim_step = 4;
-      rd.nkc = ntile2; rd.wave = wave; rd.tag = (unsigned)sigma & 0xffffu; rd.err = err; rd.limit = a.spin_limit;
+      // load `it` of this wavefront covers producers 2 * (wave + 4 * it) and the one after it (1 KiB)
+      rd.voff = (unsigned)(wave * 2 * kPartBytes + lane * 16);
+      rd.it_bytes = 8u * kPartBytes; rd.chunks_per_it = 4;
+      rd.lim = ntile2 - 2 * wave - chalf; rd.lim_step = 8;
+      rd.nkc = ntile2; rd.wave = wave; rd.tag = part_tag(sigma) << 14; rd.bit_tag = true; rd.err = err; rd.limit = a.spin_limit;
       rd.nitv = nitv; rd.rot = rot;
-      float ps[4] = {0.f, 0.f, 0.f, 0.f};
+      constexpr int NLD = NPW / 2;                          // loads per wavefront
+      float ps[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       {
-        // The sums need none of the tag halves masked off: the shifts drop them.  With one wavefront per SIMD what
+        // The sums need no masking but the tag bit's: the shifts drop the other halves.  With one wavefront per SIMD what
         // bounds this phase is its instruction stream, and a verdict per load (compare, branch, or worse a ballot
-        // handed to scalar registers) cost as much as the additions themselves.  So the loads are taken four at a
-        // time: their values are added into sums of the group's own without looking, the tag differences of the four
-        // are ORed per lane, and one compare and branch decides whether the group's sums count.  A group with a stale
-        // tag in any lane is dropped whole and its loads are fetched again, all at once, by fix_up_batch.
-        auto add = [&](float (&acc)[4], const u32x4& v) __attribute__((always_inline)) {
+        // handed to scalar registers) costs as much as the additions themselves.  So the loads behind the poll are
+        // taken together: their values are added into sums of their own without looking, the tag differences are ORed
+        // per lane, and one compare and branch decides whether those sums count.  If not, the loads are fetched
+        // again, all at once, by fix_up_batch.
+        auto add = [&](float (&acc)[8], const u32x4& v) __attribute__((always_inline)) {
           acc[0] += __uint_as_float(v[0] << 16); acc[1] += __uint_as_float(v[0] & 0xffff0000u);
-          acc[2] += __uint_as_float(v[1] << 16); acc[3] += __uint_as_float(v[2] << 16);
+          acc[2] += __uint_as_float(v[1] << 16); acc[3] += __uint_as_float(v[1] & (0xffff0000u & ~kLLFwdTagBit));
+          acc[4] += __uint_as_float(v[2] << 16); acc[5] += __uint_as_float(v[2] & 0xffff0000u);
+          acc[6] += __uint_as_float(v[3] << 16); acc[7] += __uint_as_float(v[3] & (0xffff0000u & ~kLLFwdTagBit));
         };
-        u32x4 x[NPW];
+        static_assert(NLD >= 2, "the poll is two loads");
+        u32x4 x[NLD];
         const unsigned tagw = rd.tag << 16;
         // The poll is the first two loads, repeated (bounded) until their tags have turned and then kept; the others
         // are issued behind it (see the forward kernel).
@@ -1528,7 +1542,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         // inputs, asked for a step ago, with a count that also waits for the next frame's, just asked for.
         __builtin_amdgcn_s_waitcnt(0x0f70);                // vmcnt(0)
 #pragma unroll
-        for (int i = 2; i < NPW; ++i) x[i] = rd.load_it(rd.it_of(i));
+        for (int i = 2; i < NLD; ++i) x[i] = rd.load_it(rd.it_of(i));
         __builtin_amdgcn_sched_barrier(0);
         // while those loads are on their way: the polled loads' values, and the part of the gate gradients that
         // does not need Dh
@@ -1537,14 +1551,11 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
         factors();
         __builtin_amdgcn_sched_barrier(0);
         unsigned long long redo = 0ull;
-        constexpr int kGroup = (NPW - 2) / 2;              // the other loads: two groups
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-          const int i0 = 2 + g * kGroup, i1 = g == 0 ? 2 + kGroup : NPW;
-          float pg[4] = {0.f, 0.f, 0.f, 0.f};
+        if (NLD > 2) {
+          float pg[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           unsigned bad = 0u;
 #pragma unroll
-          for (int i = i0; i < i1; ++i) {
+          for (int i = 2; i < NLD; ++i) {
             __builtin_amdgcn_sched_barrier(0);             // each load is waited for and consumed in turn
             bad |= rd.tag_diff(x[i], rd.it_of(i), tagw);
             add(pg, x[i]);
@@ -1552,14 +1563,14 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
           __builtin_amdgcn_sched_barrier(0);
           if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad > 0xffffu) == 0ull, 1)) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) ps[v] += pg[v];
+            for (int v = 0; v < 8; ++v) ps[v] += pg[v];
           } else {
-            redo |= ((1ull << i1) - 1ull) & ~((1ull << i0) - 1ull);
+            redo |= ((1ull << NLD) - 1ull) & ~3ull;
           }
         }
         PROF_REDO(__popcll(redo))
         if (redo) {
-          rd.fix_up_batch<NPW>(redo, dead, [&](int, const u32x4& v) __attribute__((always_inline)) { add(ps, v); });
+          rd.fix_up_batch<NLD>(redo, dead, [&](int, const u32x4& v) __attribute__((always_inline)) { add(ps, v); });
           // (nothing of that is outstanding any more - said with an instruction the compiler takes note of: it cannot tell
           // from the loop's exits, and would make whatever reuses those registers below wait for every load in flight)
           __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
@@ -1571,9 +1582,14 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       }
       PROF_MARK(0)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][4 * cg + v][ccol] = ps[v];
+      for (int v = 0; v < 8; ++v) red[2 * wave + chalf][v][ccol] = ps[v];
       __syncthreads();
-      if (active && t_next < L) Dh = red[0][r8][u] + red[1][r8][u] + red[2][r8][u] + red[3][r8][u];
+      if (active && t_next < L) {
+        float sum = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sum += red[k][r8][u];
+        Dh = sum * (1.f / kPartScale);                     // the partial sums travel scaled (see above)
+      }
     } else {
       factors();
       in_next = fetch_in(tau - 1);
@@ -1602,7 +1618,7 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       // beyond the 64-bit units of the other kernels is that an aligned 16-byte lane store is not split below 8 bytes.
       const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
           (void*)(((sigma & 1) ? d.ring1 : d.ring0) + (long)R * ntile2 * ntile2 * (kPartBytes / 16)), 0, ntile2 * ntile2 * kPartBytes, kBufFlags);
-      const unsigned tag_hi = ((unsigned)(sigma + 1) & 0xffffu) << 16;
+      const unsigned tag_hi = part_tag(sigma + 1) << 30;
       u32x4 av[4];
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 7][kc * 32 + (lane >> 4) * 8];
@@ -1615,18 +1631,16 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
       // four tiles, as this was first written, a whole group's publishing - a quarter of it - trailed the stream).
       // Nothing is predicated: lanes that hold no result have their store offset parked outside the buffer (pub_off),
       // and the two cache policies are two copies of the code.
-      constexpr int kPubSteps = 6, kPubLag = 2;             // a tile is published behind the MFMAs of the tile kPubLag after it
+      constexpr int kPubSteps = 4, kPubLag = 2;             // a tile is published behind the MFMAs of the tile kPubLag after it
       auto mma_publish = [&](auto local_c) __attribute__((always_inline)) {
         constexpr bool kLocal = decltype(local_c)::value;
-        u32x4 val[4];
+        u32x2 val[4];
         auto pub_step = [&](int c, int kk) __attribute__((always_inline)) {
-          u32x4& v = val[c & 3];
+          u32x2& v = val[c & 3];
           if (kk == 0) v[0] = pack_bf16x2(acc[c][0], acc[c][1]);
-          else if (kk == 1) v[2] = pack_bf16x2(acc[c][2], acc[c][3]);
-          else if (kk == 2) v[1] = (v[2] & 0xffffu) | tag_hi;
-          else if (kk == 3) v[2] = v[2] >> 16;
-          else if (kk == 4) v[3] = tag_hi;
-          else __builtin_amdgcn_raw_buffer_store_b128(v, ro, pub_off[c], 0, kLocal ? 0 : 16);   // 16: sc1, agent scope, written through
+          else if (kk == 1) v[1] = pack_bf16x2(acc[c][2], acc[c][3]);
+          else if (kk == 2) v[1] |= tag_hi;                  // (bit 14 of the fourth value is 0 below 2^33: see the format)
+          else __builtin_amdgcn_raw_buffer_store_b64(v, ro, pub_off[c], 0, kLocal ? 0 : 16);   // 16: sc1, agent scope, written through
         };
         operands_settle(av[0], av[1], av[2], av[3]);
 #pragma unroll
@@ -1635,10 +1649,9 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
           for (int kc = 0; kc < 4; ++kc) {
             if (kc == 0) mfma_b_agpr_first(acc[c], av[kc], w[kc][c]);
             else mfma_b_agpr(acc[c], av[kc], w[kc][c]);
-            if (c >= kPubLag) {                              // steps 0,1 | 2 | 3,4 | 5 of the earlier tile
+            if (c >= kPubLag) {                              // one step of the earlier tile behind each MFMA
               __builtin_amdgcn_sched_barrier(0);
-              const int k0 = kc == 0 ? 0 : kc == 1 ? 2 : kc == 2 ? 3 : 5, k1 = kc == 0 ? 2 : kc == 1 ? 3 : kc == 2 ? 5 : 6;
-              for (int k = k0; k < k1; ++k) pub_step(c - kPubLag, k);
+              pub_step(c - kPubLag, kc);
               __builtin_amdgcn_sched_barrier(0);
             }
           }
@@ -1751,7 +1764,8 @@ __global__ void pack_wh_bwdp_kernel(const bf16_t* W, uint4* out, int n, int ntil
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int unit = J * 32 + g * 8 + e;
-    v[e] = (jout < n && unit < n) ? Wd[(long)jout * 4 * n + kc * n + unit] : (bf16_t)0.f;
+    // (scaled by 2^-32, exactly: the partial sums of Dh leave the MFMAs scaled, which keeps a bit of their bf16 form free)
+    v[e] = (jout < n && unit < n) ? (bf16_t)((float)Wd[(long)jout * 4 * n + kc * n + unit] * kPartScale) : (bf16_t)0.f;
   }
   out[idx] = *(uint4*)v;
 }
