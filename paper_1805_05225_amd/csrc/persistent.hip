@@ -1707,6 +1707,392 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
   }
 }
 
+// The same kernel for work-groups of 16 rows (two per thread: rows r8 and r8 + 8 of the group), for batches that the
+// 8-row form cannot hold in one launch.  The MFMAs and the publishing stores are the same instructions with all 64 lanes
+// doing real work (the 8-row form computes every row twice); a (producer, destination tile) block is 1 KiB -
+// [32 outputs][4 row quarters] x 8 bytes -, a consumer's load covers one producer (lane = output lane/2, row half lane%2),
+// so a wavefront reads eight loads per step instead of four, and the pointwise part runs twice.
+template <int NPW>                                        // producers per wavefront at most: n <= 128 * NPW
+__global__ __launch_bounds__(256) void persist_bwdp16_kernel(PBwdArgs a) {
+  __shared__ float red[4][16][33];                       // [wavefront][row][output]
+  __shared__ __attribute__((aligned(16))) unsigned short zb[16][136];
+  constexpr int kBlock = 2 * kPartBytes;                 // one (producer, destination tile)
+  const WgCoord wg = wg_coord();
+  const PBwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
+  const int J = wg.tile, R = a.rt0 + wg.rt, ntile2 = gridDim.x;         // R: row group of 16 rows, counted over the whole batch
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n = a.n, B = a.B, T = a.T;
+  unsigned* err = a.sync;
+  bool dead = false;
+
+  u32x4 w[4][16];                                        // all 256 accumulation registers
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+    for (int c = 0; c < 16; ++c) w[kc][c] = load_to_agpr(&d.Wb[((((long)J * 4 + wave) * 4 + kc) * 16 + c) * 64 + lane]);
+  agpr_loads_done();
+
+  const int r8 = tid >> 5, u = tid & 31;                 // pointwise pairs of this thread: rows r8 and r8 + 8, unit u
+  const int b0 = R * 16 + r8, j = J * 32 + u;
+  bool active[2];
+  float Dh[2], Dc[2];
+  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};
+  int L[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int b = b0 + 8 * k;
+    active[k] = b < B && j < n;
+    Dh[k] = 0.f; Dc[k] = 0.f; L[k] = 0;
+    if (active[k]) {
+      Dh[k] = d.Dh[(long)b * n + j];
+      Dc[k] = d.Dc[(long)b * n + j];
+      L[k] = clamp_len(a.lens, b, T);
+    }
+  }
+  // What the gate gradients of one frame need.  dy stays as the 16 bits that were loaded: a conversion right behind
+  // the load would make the wavefront wait for it - and for every load in front of it - where it is issued.
+  struct In { float gi, gf, gg, go, c_new, c_prev; unsigned dy_bits; };
+  // The per-frame arrays are read through buffer descriptors that cover exactly one frame: the frame's address is
+  // scalar arithmetic, a lane's offset inside the frame never changes, and a lane with nothing to fetch (row past the
+  // batch, unit past n, frame past the row's length) has its offset parked outside the frame and gets zeros without
+  // touching memory - as does every lane when the frame itself does not exist (zero-sized descriptor).  Nothing is
+  // predicated, so every step issues the same six loads; with loads that may or may not have been issued the
+  // compiler has to assume the fewest, and made the wavefront wait for the loads of the NEXT frame, just issued and
+  // on their way from HBM, where it only needed those of this one.
+  constexpr unsigned kParked = 0x7ff00000u;
+  const unsigned g_bytes = (unsigned)B * 4u * n * 4u, s_bytes = (unsigned)B * n * 4u, y_bytes = (unsigned)B * d.lddy * 2u;
+  // offsets of row r8 inside a frame; row r8 + 8 lies a wave-uniform distance behind it (and exists only if row r8 does)
+  const unsigned g_off0 = active[0] ? ((unsigned)b0 * 4u * n + j) * 4u : kParked;
+  const unsigned s_off0 = active[0] ? ((unsigned)b0 * n + j) * 4u : kParked;
+  const unsigned y_off0 = active[0] ? ((unsigned)b0 * d.lddy + j) * 2u : kParked;
+  auto g_off = [&](int k) { return k == 0 ? g_off0 : (active[1] ? g_off0 + 8u * 4u * n * 4u : kParked); };
+  auto s_off = [&](int k) { return k == 0 ? s_off0 : (active[1] ? s_off0 + 8u * n * 4u : kParked); };
+  auto y_off = [&](int k) { return k == 0 ? y_off0 : (active[1] ? y_off0 + 8u * (unsigned)d.lddy * 2u : kParked); };
+  auto frame_of = [&](const void* base, int t, unsigned bytes) {
+    const bool ok = t >= 0 && t < T;
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (unsigned long long)(unsigned)(ok ? t : 0) * bytes), 0, ok ? bytes : 0u, kBufFlags);
+  };
+  auto ld_f = [&](__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {     // 2: non-temporal
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 2));
+  };
+  auto fetch_in = [&](int tau, int k) {
+    const int t = tau < 0 ? -1 : (d.rev ? T - 1 - tau : tau);
+    const bool lane_on = t < L[k];                         // (L is 0 in lanes without a row)
+    const unsigned go = lane_on ? g_off(k) : kParked, yo = lane_on ? y_off(k) : kParked;
+    In in;
+    const __amdgpu_buffer_rsrc_t rg = frame_of(d.gates, t, g_bytes);
+    in.gi = ld_f(rg, go, 0u); in.gf = ld_f(rg, go, 4u * n); in.gg = ld_f(rg, go, 8u * n); in.go = ld_f(rg, go, 12u * n);
+    const int tp = d.rev ? t + 1 : t - 1;                  // the frame before t in processing order
+    const bool inside = t >= 0 && tp >= 0 && tp < T, initial = t >= 0 && !inside && d.c0 != nullptr;
+    const __amdgpu_buffer_rsrc_t rp = initial ? __builtin_amdgcn_make_buffer_rsrc((void*)d.c0, 0, s_bytes, kBufFlags)
+                                              : frame_of(d.cs, inside ? tp : -1, s_bytes);
+    // The cell state entering frame t is the state leaving the frame before it, which is the NEXT backward step's
+    // frame: that step takes its c_new from here instead of loading it again (one load per step less).  So the value is
+    // also fetched where frame t itself is padding but the frame before it is real (direction +1, t = the row's length).
+    in.c_prev = ld_f(rp, (d.rev ? t : t - 1) < L[k] ? s_off(k) : kParked, 0u);
+    in.c_new = 0.f;                                        // supplied by the caller
+    in.dy_bits = __builtin_amdgcn_raw_buffer_load_b16(frame_of(d.dy, t, y_bytes), yo, 0, 2);
+    return in;
+  };
+  // entries of DZ, which this thread stores: a pointer that moves by one frame per step
+  const long row_last = (long)(d.rev ? 0 : T - 1) * B + b0, g_step = (d.rev ? (long)B : -(long)B) * 4 * n;
+  unsigned short* dz_p = (unsigned short*)d.DZ + row_last * 4 * n + j;
+  In in_a[2], in_b[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    in_a[k] = fetch_in(T - 1, k);
+    in_b[k] = in_a[k];
+    const int t0 = d.rev ? 0 : T - 1;                      // the first frame's own cell state: the only one loaded as such
+    in_a[k].c_new = ld_f(frame_of(d.cs, t0, s_bytes), t0 < L[k] ? s_off(k) : kParked, 0u);
+  }
+
+  // consumer side: a load covers one producer's block; lane reads output lane/2, rows 8 * (lane%2) .. + 7
+  const int ccol = lane >> 1, chalf = lane & 1;
+  const int nitv = (ntile2 + 3) / 4, rot = J % nitv;
+  const long ring_tile = ((long)R * ntile2 + J) * ntile2 * (kBlock / 16);         // uint4 index of [R][J][0]
+  // producer side: lane holds rows 4*(lane/16) .. +3 of output column lane%16 of each accumulator tile
+  const int pq = lane >> 4, pcol = lane & 15;
+  // (the verdict comes out of shared memory; the compiler has to be told that it is the same in every lane, or the
+  // two copies of the publishing code below become one divergent region)
+  const bool local = __builtin_amdgcn_readfirstlane((int)(a.xcc != nullptr &&
+                     group_is_xcd_local(a.xcc, (wg.dir * (int)gridDim.y + wg.rt) * ntile2, ntile2, J, a.spin_limit))) != 0;
+  // byte offset, from row group R's part of the ring, of what this lane stores for accumulator tile c: destination tile
+  // wave*8 + c/2 (one past the last falls outside the buffer), this producer's block, output column, row quarter
+  unsigned pub_off[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) {
+    const int Jd = wave * 8 + (c >> 1);
+    pub_off[c] = (unsigned)(((Jd * ntile2 + J) * 32 + (c & 1) * 16 + pcol) * 4 + pq) * 8u;
+  }
+
+  PROF_DECL
+  // One time step.  `in` holds the inputs of this step's frame and `in_next` receives those of the next; the loop
+  // below calls it with the two in alternating roles, because a copy at the end of a step would have to wait for
+  // the loads (and, counted with them, the step's stores) at that point.
+  // `ring_c`: the step reads partial sums (every step but the first); `pointwise_c`: it has a frame (every step but the
+  // last, which only collects the Dh that leaves the layer).  Constants of the call, so that the loop below is free
+  // of the two exceptions: with them inside, the compiler's wait counts in the loop allowed for paths it never takes.
+  auto step = [&](const int tau, const In (&in)[2], In (&in_next)[2], auto ring_c, auto pointwise_c) __attribute__((always_inline)) {
+    PROF_MARK(4)
+    // (told to be wave-uniform: computed next to per-lane uses of tau it ends up in vector registers, and a buffer
+    // descriptor derived from it is then applied lane by lane in a loop)
+    const int sigma = __builtin_amdgcn_readfirstlane(T - 1 - tau);
+    const int t = d.rev ? T - 1 - tau : tau;
+    const int t_next = d.rev ? t - 1 : t + 1;
+    constexpr bool pointwise = decltype(pointwise_c)::value;
+    bool valid[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) valid[k] = pointwise && active[k] && t < L[k];
+
+    // The gate gradients of a valid frame, dh = dy + Dh (recurrent_dev.h has the plain form):
+    //   dc = Dc + dh go (1 - tanh(c)^2), Dc' = dc gf, dz = (dc gg gi (1-gi), dc c_prev gf (1-gf), dc gi (1-gg^2), dh tanh(c) go (1-go)).
+    // Everything that does not involve dh or Dc is computed while the ring loads are in flight.
+    float f_c[2], f_i[2], f_f[2], f_g[2], f_o[2];
+    auto factors = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        f_c[k] = 0.f; f_i[k] = 0.f; f_f[k] = 0.f; f_g[k] = 0.f; f_o[k] = 0.f;
+        if (valid[k]) {
+          const float tc = tanhf_(in[k].c_new);
+          f_c[k] = in[k].go * (1.f - tc * tc);
+          f_i[k] = in[k].gg * in[k].gi * (1.f - in[k].gi);
+          f_f[k] = in[k].c_prev * in[k].gf * (1.f - in[k].gf);
+          f_g[k] = in[k].gi * (1.f - in[k].gg * in[k].gg);
+          f_o[k] = tc * in[k].go * (1.f - in[k].go);
+        }
+      }
+    };
+    auto fetch_next = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        in_next[k] = fetch_in(tau - 1, k);
+        in_next[k].c_new = in[k].c_prev;
+      }
+    };
+    if constexpr (decltype(ring_c)::value) {
+      RingReader rd;
+      rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + ring_tile), 0, ntile2 * kBlock,
+                                                kBufFlags);
+      // load `it` of this wavefront covers producer wave + 4 * it (1 KiB)
+      rd.voff = (unsigned)(wave * kBlock + lane * 16);
+      rd.it_bytes = 4u * kBlock; rd.chunks_per_it = 4;
+      rd.lim = ntile2 - wave; rd.lim_step = 4;
+      rd.nkc = ntile2; rd.wave = wave; rd.tag = part_tag(sigma) << 14; rd.bit_tag = true; rd.err = err; rd.limit = a.spin_limit;
+      rd.nitv = nitv; rd.rot = rot;
+      constexpr int NLD = NPW;                              // loads per wavefront
+      float ps[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      {
+        // The sums need no masking but the tag bit's: the shifts drop the other halves.  With one wavefront per SIMD what
+        // bounds this phase is its instruction stream, and a verdict per load (compare, branch, or worse a ballot
+        // handed to scalar registers) costs as much as the additions themselves.  So the loads behind the poll are
+        // taken together: their values are added into sums of their own without looking, the tag differences are ORed
+        // per lane, and one compare and branch decides whether those sums count.  If not, the loads are fetched
+        // again, all at once, by fix_up_batch.
+        auto add = [&](float (&acc)[8], const u32x4& v) __attribute__((always_inline)) {
+          acc[0] += __uint_as_float(v[0] << 16); acc[1] += __uint_as_float(v[0] & 0xffff0000u);
+          acc[2] += __uint_as_float(v[1] << 16); acc[3] += __uint_as_float(v[1] & (0xffff0000u & ~kLLFwdTagBit));
+          acc[4] += __uint_as_float(v[2] << 16); acc[5] += __uint_as_float(v[2] & 0xffff0000u);
+          acc[6] += __uint_as_float(v[3] << 16); acc[7] += __uint_as_float(v[3] & (0xffff0000u & ~kLLFwdTagBit));
+        };
+        static_assert(NLD >= 2, "the poll is two loads");
+        u32x4 x[NLD];
+        const unsigned tagw = rd.tag << 16;
+        // The poll is the first two loads, repeated (bounded) until their tags have turned and then kept; the others
+        // are issued behind it (see the forward kernel).
+        for (unsigned poll = 0;; ++poll) {
+          x[0] = rd.load_it(rd.it_of(0));
+          x[1] = rd.load_it(rd.it_of(1));
+          if (dead) break;
+          const unsigned stale = rd.tag_diff(x[0], rd.it_of(0), tagw) | rd.tag_diff(x[1], rd.it_of(1), tagw);
+          if (__builtin_amdgcn_ballot_w64(stale > 0xffffu) == 0ull) break;
+          if (poll >= rd.limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
+            st_relaxed(err, 1u);
+            dead = true;
+            break;
+          }
+          PROF_POLLS(1)
+        }
+        PROF_MARK(5)
+        // Nothing is outstanding here (the poll has just been waited for, and loads complete in order).  Said with an
+        // instruction the compiler takes note of: otherwise it makes the pointwise part below wait for this frame's
+        // inputs, asked for a step ago, with a count that also waits for the next frame's, just asked for.
+        __builtin_amdgcn_s_waitcnt(0x0f70);                // vmcnt(0)
+#pragma unroll
+        for (int i = 2; i < NLD; ++i) x[i] = rd.load_it(rd.it_of(i));
+        __builtin_amdgcn_sched_barrier(0);
+        // while those loads are on their way: the polled loads' values, and the part of the gate gradients that
+        // does not need Dh
+        add(ps, x[0]);
+        add(ps, x[1]);
+        factors();
+        __builtin_amdgcn_sched_barrier(0);
+        unsigned long long redo = 0ull;
+        constexpr int kGroup = (NLD - 2) / 2;              // the other loads: two groups
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          const int i0 = 2 + g * kGroup, i1 = g == 0 ? 2 + kGroup : NLD;
+          float pg[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          unsigned bad = 0u;
+#pragma unroll
+          for (int i = i0; i < i1; ++i) {
+            __builtin_amdgcn_sched_barrier(0);             // each load is waited for and consumed in turn
+            bad |= rd.tag_diff(x[i], rd.it_of(i), tagw);
+            add(pg, x[i]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad > 0xffffu) == 0ull, 1)) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) ps[v] += pg[v];
+          } else {
+            redo |= ((1ull << i1) - 1ull) & ~((1ull << i0) - 1ull);
+          }
+        }
+        PROF_REDO(__popcll(redo))
+        if (redo) {
+          rd.fix_up_batch<NLD>(redo, dead, [&](int, const u32x4& v) __attribute__((always_inline)) { add(ps, v); });
+          // (nothing of that is outstanding any more - said with an instruction the compiler takes note of: it cannot tell
+          // from the loop's exits, and would make whatever reuses those registers below wait for every load in flight)
+          __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+        }
+        // The next frame's inputs, from HBM.  Loads complete in the order of issue: asked for in front of the groups
+        // above (where their latency would be covered best) they held up every ring load behind them - a tenth of the step.
+        fetch_next();
+      }
+      PROF_MARK(0)
+#pragma unroll
+      for (int v = 0; v < 8; ++v) red[wave][8 * chalf + v][ccol] = ps[v];
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 2; ++k)
+        if (active[k] && t_next < L[k]) {
+          const int rr = r8 + 8 * k;
+          Dh[k] = (red[0][rr][u] + red[1][rr][u] + red[2][rr][u] + red[3][rr][u]) * (1.f / kPartScale);   // the partial sums travel scaled
+        }
+    } else {
+      factors();
+      fetch_next();
+    }
+    if (pointwise) {
+      unsigned short bits[2][4];
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        float dz[4] = {0.f, 0.f, 0.f, 0.f};
+        if (valid[k]) {
+          const float dh = bf_bits2f((unsigned short)in[k].dy_bits) + Dh[k], dc = Dc[k] + dh * f_c[k];
+          Dc[k] = dc * in[k].gf;
+          dz[0] = dc * f_i[k]; dz[1] = dc * f_f[k]; dz[2] = dc * f_g[k]; dz[3] = dh * f_o[k];
+        }
+        const unsigned b01 = pack_bf16x2(dz[0], dz[1]), b23 = pack_bf16x2(dz[2], dz[3]);
+        bits[k][0] = (unsigned short)b01; bits[k][1] = (unsigned short)(b01 >> 16);
+        bits[k][2] = (unsigned short)b23; bits[k][3] = (unsigned short)(b23 >> 16);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          dbsum[q] += dz[q];
+          zb[r8 + 8 * k][q * 32 + u] = bits[k][q];         // inactive threads contribute zeros
+        }
+      }
+      __syncthreads();
+      PROF_MARK(2)
+      // partial sums of Dh for all n outputs: [16 rows, K = 128] x [128, 256 outputs of this wave],
+      // in four groups of four column tiles: while the MFMAs of one group run, the previous group's results are
+      // converted and stored.  One 16-byte store per accumulator tile: the 32 storing lanes of a wavefront cover 512
+      // consecutive bytes.  Each 8-byte half carries its own tag in its upper dword, so the only thing relied on
+      // beyond the 64-bit units of the other kernels is that an aligned 16-byte lane store is not split below 8 bytes.
+      const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(((sigma & 1) ? d.ring1 : d.ring0) + (long)R * ntile2 * ntile2 * (kBlock / 16)), 0, ntile2 * ntile2 * kBlock, kBufFlags);
+      const unsigned tag_hi = part_tag(sigma + 1) << 30;
+      u32x4 av[4];
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc) av[kc] = *(const u32x4*)&zb[lane & 15][kc * 32 + (lane >> 4) * 8];
+      f32x4 acc[16];
+      // Sixteen column tiles, the k loop inside.  An MFMA of this shape issues every 16 cycles, of which the wavefront's
+      // issue slot is taken for 4 (see the forward kernel for the measurements).  What publishes a tile (two conversions,
+      // three moves and one store) is cut into single instructions that follow the MFMAs of the tile two behind it:
+      // by then its last result has been written (more than the 20 wait states mfma_settle would spend), the
+      // instructions cost little there, and only the last two tiles are published behind the last MFMA (with groups of
+      // four tiles, as this was first written, a whole group's publishing - a quarter of it - trailed the stream).
+      // Nothing is predicated: lanes that hold no result have their store offset parked outside the buffer (pub_off),
+      // and the two cache policies are two copies of the code.
+      constexpr int kPubSteps = 4, kPubLag = 2;             // a tile is published behind the MFMAs of the tile kPubLag after it
+      auto mma_publish = [&](auto local_c) __attribute__((always_inline)) {
+        constexpr bool kLocal = decltype(local_c)::value;
+        u32x2 val[4];
+        auto pub_step = [&](int c, int kk) __attribute__((always_inline)) {
+          u32x2& v = val[c & 3];
+          if (kk == 0) v[0] = pack_bf16x2(acc[c][0], acc[c][1]);
+          else if (kk == 1) v[1] = pack_bf16x2(acc[c][2], acc[c][3]);
+          else if (kk == 2) v[1] |= tag_hi;                  // (bit 14 of the fourth value is 0 below 2^33: see the format)
+          else __builtin_amdgcn_raw_buffer_store_b64(v, ro, pub_off[c], 0, kLocal ? 0 : 16);   // 16: sc1, agent scope, written through
+        };
+        operands_settle(av[0], av[1], av[2], av[3]);
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+#pragma unroll
+          for (int kc = 0; kc < 4; ++kc) {
+            if (kc == 0) mfma_b_agpr_first(acc[c], av[kc], w[kc][c]);
+            else mfma_b_agpr(acc[c], av[kc], w[kc][c]);
+            if (c >= kPubLag) {                              // one step of the earlier tile behind each MFMA
+              __builtin_amdgcn_sched_barrier(0);
+              pub_step(c - kPubLag, kc);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        mfma_settle(acc[12], acc[13], acc[14], acc[15]);
+#pragma unroll
+        for (int c = 16 - kPubLag; c < 16; ++c)
+#pragma unroll
+          for (int k = 0; k < kPubSteps; ++k) pub_step(c, k);
+      };
+      if (local) mma_publish(std::true_type{});
+      else mma_publish(std::false_type{});
+      PROF_MARK(1)
+#pragma unroll
+      for (int k = 0; k < 2; ++k)
+        if (active[k]) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) st_stream(dz_p + (long)k * 8 * 4 * n + q * n, bits[k][q]);
+        }
+      dz_p += g_step;
+      PROF_MARK(3)
+    }
+  };
+  // (tau is told to be wave-uniform: computed next to per-lane uses it ends up in vector registers)
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  step(T - 1, in_a, in_b, no, yes);                        // (T >= 2)
+  int tau = T - 2;
+  for (; tau >= 1; tau = __builtin_amdgcn_readfirstlane(tau) - 2) {
+    step(tau, in_b, in_a, yes, yes);
+    step(__builtin_amdgcn_readfirstlane(tau - 1), in_a, in_b, yes, yes);
+  }
+  if (tau == 0) {
+    step(0, in_b, in_a, yes, yes);
+    step(-1, in_a, in_b, yes, no);
+  } else {
+    step(-1, in_b, in_a, yes, no);
+  }
+  PROF_DUMP("bwdp16", T)
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+    if (active[k]) {
+      d.Dh[(long)(b0 + 8 * k) * n + j] = Dh[k];
+      d.Dc[(long)(b0 + 8 * k) * n + j] = Dc[k];
+    }
+  if (d.dbpart) {                       // bias gradient: sum this work-group's 16 rows into the first of its two slices (the other stays zero)
+    __shared__ float dbred[8][129];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dbred[r8][q * 32 + u] = dbsum[q];
+    __syncthreads();
+    if (tid < 128) {
+      const int q = tid >> 5, uu = tid & 31, jj = J * 32 + uu;
+      float sum = 0.f;
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) sum += dbred[rr][q * 32 + uu];
+      if (jj < n) d.dbpart[(long)2 * R * 4 * n + q * n + jj] = sum;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // packing for the ring layout
 // forward weights: chunk index = (((dir*ntile + tile)*4 + q)*nkc + kc)*64 + lane
@@ -1910,7 +2296,16 @@ int persist_bwd_variant(const PBwdArgs& a) {
 hipError_t launch_persist_bwd(const PBwdArgs& a, int variant, hipStream_t s) {
   const int t32 = cdiv(cdiv(a.n, 16), 2);
   switch (variant) {
-    case kBwdPartialSums: return coop_slabs(persist_bwdp_kernel<8>, t32, 8, a, s);
+    case kBwdPartialSums: {
+      // more rows than the 8-row form holds in one launch: 16 rows per work-group, if that takes a single launch
+      const int nrt = cdiv(a.B, 16);
+      if ((long)t32 * 2 * nrt * a.ndir > capacity(persist_bwdp_kernel<8>) && (long)t32 * nrt * a.ndir <= capacity(persist_bwdp16_kernel<8>)) {
+        const hipError_t e16 = coop_slabs(persist_bwdp16_kernel<8>, t32, 16, a, s);
+        if (e16 != hipErrorCooperativeLaunchTooLarge) return e16;
+        (void)hipGetLastError();
+      }
+      return coop_slabs(persist_bwdp_kernel<8>, t32, 8, a, s);
+    }
     case kBwdDz8: return coop_slabs(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, t32, 8, a, s);
     case kBwdDz16: return coop_slabs(persist_bwd_kernel<kLLMaxNkcBwd / 4>, cdiv(a.n, 16), 16, a, s);
     default: return hipErrorCooperativeLaunchTooLarge;
