@@ -1,16 +1,17 @@
 // Single-launch recurrent kernels: the whole time loop of a layer in ONE launch (bfloat16 storage).
 //
 // The per-step kernels pay a launch per time step and re-read their W_h slice from the memory
-// system every step.  Here each work-group (forward: 16 hidden units x 16 batch rows; backward:
-// 32 units x 8 rows, or 16 x 16 when that does not fit) loads its slice of the packed W_h into
-// registers once and then walks all T steps.
+// system every step.  Here each work-group (32 hidden units x 8 batch rows, or x 16 rows for batches
+// that the 8-row form cannot hold in one launch; backward also 16 x 16 and 32 x 8 forms that exchange
+// dz, kept as fallbacks) loads its slice of the packed W_h into registers once and then walks all T steps.
 //
-// Only h_t (forward) or dz_t (backward) crosses work-groups.  Measurements on this device showed
-// that a counter barrier is the wrong tool: atomics on one address serialise at ~16 ns each
+// Only h_t (forward) or partial sums of Dh (backward) cross work-groups.  Measurements on this device
+// showed that a counter barrier is the wrong tool: atomics on one address serialise at ~16 ns each
 // (4 us for 256 work-groups) and agent-scope fences cost microseconds more.  So there is no
 // barrier and no fence here.  The exchanged data lives in a two-slot ring whose every 8-byte unit
-// holds three bf16 values and a 16-bit step tag, written with one 64-bit agent-scope atomic store
-// and read with cache-bypassing 16-byte loads.  A consumer simply re-reads an operand until
+// holds its values AND a tag of the step that wrote it (forward and partial sums: four bf16 values, the tag
+// one bit that their range leaves free; dz: three values and a 16-bit tag), written with one 64-bit
+// store and read with cache-bypassing 16-byte loads.  A consumer simply re-reads an operand until
 // its tags show the step it is waiting for: value and "ready" flag arrive in the same atomic
 // unit, so no ordering between different addresses is ever needed.
 //
@@ -21,8 +22,8 @@
 // Every wait is bounded: after `spin_limit` polls the wave raises the error word sync[0], stops
 // waiting for the rest of the launch and runs to the end (results are then invalid and the word
 // says so); every other wave notices the word in its own wait loop and does the same, so the
-// grid always drains.  The launch is cooperative, which guarantees that all work-groups are
-// resident together (otherwise the launch is refused and the caller uses the per-step kernels).
+// grid always drains.  The grid is checked against what the device holds at once; the launch is
+// cooperative unless the caller vouches that nothing else occupies the device.
 #include "recurrent_dev.h"
 #include <type_traits>
 #include <algorithm>
@@ -74,7 +75,7 @@ __device__ __forceinline__ void st_relaxed(unsigned* p, unsigned v) {
 // so a load past the end (chunks the template bound adds beyond nkc, lanes whose rows this work-group does
 // not own: their offset is parked far outside) returns zeros from the bounds check without touching memory.
 // Padding units inside the ring hold zero values (nobody writes them after the initial fill), so masking off
-// the tag halves is all the clean-up an operand needs.  Keeping branches and lane masks out of this loop
+// the tags is all the clean-up an operand needs.  Keeping branches and lane masks out of this loop
 // matters: with them the instruction stream between two loads, not the memory system, set the step time.
 // Order in which a work-group walks the nitv loads of its row tile: rotated by `rot`, so that the work-groups of
 // one XCD, which all read the same tile at the same time, do not all ask the same L2 channel for the same lines.
