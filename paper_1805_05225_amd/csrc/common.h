@@ -138,28 +138,20 @@ struct BwdArgs {
 hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s);
 
 // Single-launch ("persistent") variants for bfloat16 storage: one launch runs every time step with
-// W_h resident in registers.  What crosses work-groups (h_t forward, dz_t or partial sums of Dh backward)
+// W_h resident in registers.  What crosses work-groups (h_t forward, partial sums of Dh backward)
 // travels through a two-slot ring in global memory whose every 8-byte unit carries its values AND a tag
 // of the step that wrote it, so a consumer needs no barrier and no fence: it re-reads the ring until every
 // tag shows the step it waits for.
-//   K axis of the ring ("slots"): producer p (a tile of 16 units) owns kLLSlots consecutive slots per row.
-//   Backward (dz): slot w inside a producer: unit m = w/4, position w%4; position 3 is a 16-bit tag, positions
-//   0..2 carry value 3m + pos (values beyond the producer's count are padding).
-//   Forward (h): all four positions of a unit carry values (slot w = value w).  |h| <= 1, so bit 14 of a bf16 h
-//   (the top bit of the exponent) is always 0; in position 3 that bit IS the tag - one bit is enough to tell a
-//   slot's new contents from what the step two earlier left there - and the reader clears it.  This makes the K
-//   axis dense: 16 slots per 16 units instead of 24, a third fewer chunks, loads and MFMAs per step.
-//   Chunks of 8 slots form MFMA A-fragments exactly as in the per-step kernels.
+//   Forward (h): the K axis of the ring is the unit index; an 8-byte unit carries four consecutive values of one row.
+//   |h| <= 1, so bit 14 of a bf16 h (the top bit of the exponent) is always 0; in the fourth value that bit IS the
+//   tag - one bit is enough to tell a slot's new contents from what the step two earlier left there - and the reader
+//   clears it.  Chunks of 8 values x 64 lanes form MFMA A-fragments exactly as in the per-step kernels.
+//   Backward (partial sums of Dh): same unit and tag; the layout is described at the kernels.
 // sync[0] is an error word set when a bounded wait expires.
 constexpr int kLLValsFwd = 16, kLLSlotsFwd = 16;     // 16 h values  -> 4 units  -> 2 chunks per producer and row
-constexpr int kLLValsBwd = 64, kLLSlotsBwd = 88;     // 64 dz values -> 22 units -> 11 chunks
-constexpr int kLLMaxNkcFwd = 32, kLLMaxNkcBwd = 176; // register budget of the kernels (n <= 1024)
-constexpr unsigned kLLFwdTagBit = 0x40000000u;       // in the upper dword of a forward unit: bit 14 of the value in position 3
+constexpr int kLLMaxNkcFwd = 32;                     // register budget of the kernels (n <= 1024)
+constexpr unsigned kLLFwdTagBit = 0x40000000u;       // in the upper dword of a unit: bit 14 of the fourth value
 inline int ll_nkc(int n, int slots) { return (int)((((long)(n + 15) / 16) * slots + 31) / 32); }
-__host__ __device__ inline int ll_slot_value(int w, int nvals) {
-  const int pos = w & 3, v = 3 * (w >> 2) + pos;
-  return (pos == 3 || v >= nvals) ? -1 : v;
-}
 // The tag bit of the data that step tau consumes (written by step tau - 1 into slot tau & 1; the initial contents of
 // slot 0 carry it for tau = 0): it alternates between consecutive uses of a slot and is 1 at a slot's first use, so a
 // zero-filled slot never looks written.
@@ -189,7 +181,7 @@ hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s);
 bool persist_fwd_fits(const PFwdArgs& a);     // would launch_persist_fwd launch anything on this device?
 
 struct PBwdDir {
-  const uint4* Wb;    // [unit tile][nkc][64] chunks
+  const uint4* Wb;    // as launch_pack_wh_bwdp writes it
   uint4* ring0; uint4* ring1;
   const float* gates; const float* cs; const float* c0;
   const void* dy; long lddy;
@@ -201,18 +193,16 @@ struct PBwdDir {
 struct PBwdArgs {
   PBwdDir d[2];
   const int* lens;
-  int B, n, nkc, T, ndir;
+  int B, n, T, ndir;
   unsigned* sync; unsigned spin_limit;
   unsigned* xcc;      // NULL or one zeroed word per work-group: lets an exchange group find out whether it shares an XCD
   int rt0;            // set by the launcher: first 16-row tile of the batch that this launch handles
   bool plain_launch;  // ordinary instead of cooperative launch (the caller vouches that the device is otherwise idle)
 };
-// Which single-launch backward kernel fits the device for this problem (decided before W_h is packed, because the
-// forms pack it differently): partial sums of Dh exchanged (fastest; W_h via launch_pack_wh_bwdp, ring of
-// bwdp_ring_bytes per direction and slot), dz exchanged with 32x8 or 16x16 work-groups (launch_pack_wh_bwd_ll), none.
-enum { kBwdNone = 0, kBwdPartialSums = 1, kBwdDz8 = 2, kBwdDz16 = 3 };
-int persist_bwd_variant(const PBwdArgs& a);
-hipError_t launch_persist_bwd(const PBwdArgs& a, int variant, hipStream_t s);
+// Does the single-launch backward kernel (partial sums of Dh exchanged; W_h via launch_pack_wh_bwdp, ring of
+// bwdp_ring_bytes per direction and slot) fit the device for this problem?
+bool persist_bwd_fits(const PBwdArgs& a);
+hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s);
 hipError_t launch_pack_wh_bwdp(const void* W_h, uint4* Wb, int n, int ndir, hipStream_t s);
 inline size_t bwdp_wh_bytes(int n) { return (size_t)((n + 31) / 32) * 262144; }                  // per direction
 inline size_t bwdp_ring_bytes(int B, int n) {                                                      // per direction and slot
@@ -220,7 +210,6 @@ inline size_t bwdp_ring_bytes(int B, int n) {                                   
   return groups * tiles * tiles * 512;
 }
 hipError_t launch_pack_wh_fwd_ll(const void* W_h, uint4* Wf, int n, int nkc, int ndir, hipStream_t s);
-hipError_t launch_pack_wh_bwd_ll(const void* W_h, uint4* Wb, int n, int nkc, int ndir, hipStream_t s);
 // ring slot 0 = zeros carrying the tag of step 0, ring slot 1 cleared.  (The initial state does not travel through the ring:
 // launch_h0_term adds its product with W_h to the pre-activations of every row's first frame instead.)
 hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s);

@@ -21,7 +21,7 @@ struct Plan {
   bool bf16;
   size_t esz;
   int nkc_f, nkc_b, nrt, ntile_f, ntile_b;
-  int nkc_ll_f, nkc_ll_b, ntile16;          // ring layout of the single-launch kernels
+  int nkc_ll_f, ntile16;                    // ring layout of the single-launch forward kernels
   // reserve: per direction [gates float T*B*4n][hprev storage T*B*n]
   size_t res_gates, res_hprev, res_dir_stride, reserve_bytes;
   // workspace
@@ -52,7 +52,6 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ntile_b = cdiv(d->n, 16);
   p->ntile16 = cdiv(d->n, 16);
   p->nkc_ll_f = ll_nkc(d->n, kLLSlotsFwd);
-  p->nkc_ll_b = ll_nkc(d->n, kLLSlotsBwd);
   const size_t n = d->n, D = p->D, B = d->B;
   const bool infer = d->flags & LSTM_FLAG_INFERENCE;
   p->res_gates = 0;
@@ -67,11 +66,9 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->Wf_bytes = D * std::max((size_t)p->ntile_f * 2 * p->nkc_f, (size_t)p->ntile16 * 4 * p->nkc_ll_f) * 1024;
   p->ws_Wf = take(p->Wf_bytes + 1024);            // packed W_h, then one chunk of zeros
   const bool part = p->bf16 && d->n <= 1024;          // the partial-sum backward kernel may be chosen
-  p->ws_Wb = take(infer ? 0 : D * std::max(std::max((size_t)p->ntile_b * p->nkc_b, (size_t)p->ntile16 * p->nkc_ll_b) * 1024,
-                                           part ? bwdp_wh_bytes(d->n) : (size_t)0));
+  p->ws_Wb = take(infer ? 0 : D * std::max((size_t)p->ntile_b * p->nkc_b * 1024, part ? bwdp_wh_bytes(d->n) : (size_t)0));
   p->hfrag_bytes = D * p->nrt * (size_t)std::max(p->nkc_f, p->nkc_ll_f) * 1024;
-  p->dzfrag_bytes = D * std::max(p->nrt * (size_t)std::max(p->nkc_b, p->nkc_ll_b) * 1024,
-                                 part ? bwdp_ring_bytes(d->B, d->n) : (size_t)0);
+  p->dzfrag_bytes = D * std::max(p->nrt * (size_t)p->nkc_b * 1024, part ? bwdp_ring_bytes(d->B, d->n) : (size_t)0);
   p->ws_hfrag0 = take(p->hfrag_bytes);
   p->ws_hfrag1 = take(p->hfrag_bytes);
   p->ws_dzfrag0 = take(infer ? 0 : p->dzfrag_bytes);
@@ -429,20 +426,17 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     if (2 * p.nrt <= kColsumSlices) z.add(ws + p.ws_colsum, D * kColsumSlices * 4 * n * 4);   // bias-gradient slices of row groups the grid lacks
     HIPCHK(launch_fill_zero_many(z, s));
   }
-  // single-launch path: bf16 storage, at least two steps, and one of the kernel forms fits the device
+  // single-launch path: bf16 storage, at least two steps, and the kernel fits the device
   PBwdArgs pa = {};
-  pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_ll_b; pa.T = p.T; pa.ndir = p.D;
+  pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.T = p.T; pa.ndir = p.D;
   pa.plain_launch = (desc->flags & LSTM_FLAG_PLAIN_LAUNCH) != 0;
   pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
   pa.xcc = (unsigned*)(ws + p.ws_sync) + 64 + 2 * (size_t)p.nrt;
-  int variant = kBwdNone;
-  for (size_t d = 0; d < D; ++d) pa.d[d].lddy = (long)(D * n);       // (the choice looks at the frame sizes)
-  if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2) variant = persist_bwd_variant(pa);
-  const bool use_ll = variant != kBwdNone;
+  for (size_t d = 0; d < D; ++d) pa.d[d].lddy = (long)(D * n);       // (the check looks at the frame sizes)
+  const bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && persist_bwd_fits(pa);
   {
     Phase ph(LSTM_PHASE_PREP, 1, s);
-    if (variant == kBwdPartialSums) HIPCHK(launch_pack_wh_bwdp(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, s));
-    else if (use_ll) HIPCHK(launch_pack_wh_bwd_ll(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_ll_b, p.D, s));
+    if (use_ll) HIPCHK(launch_pack_wh_bwdp(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, s));
     else HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
   }
 
@@ -451,9 +445,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   bool done = false;
   const bool db_in_loop = 2 * p.nrt <= kColsumSlices;   // the single-launch kernel also sums the bias gradient
   if (use_ll) {
-    const bool part = variant == kBwdPartialSums;
-    const size_t ring_dir = part ? bwdp_ring_bytes(p.B, p.n) : (size_t)p.nrt * p.nkc_ll_b * 1024;
-    const size_t wb_dir = part ? bwdp_wh_bytes(p.n) : (size_t)p.ntile16 * p.nkc_ll_b * 1024;
+    const size_t ring_dir = bwdp_ring_bytes(p.B, p.n), wb_dir = bwdp_wh_bytes(p.n);
     for (size_t d = 0; d < D; ++d) {
       PBwdDir& bd = pa.d[d];
       bd.Wb = (const uint4*)(ws + p.ws_Wb + d * wb_dir);
@@ -473,7 +465,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     hipError_t e;
     {
       Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);
-      e = launch_persist_bwd(pa, variant, s);
+      e = launch_persist_bwd(pa, s);
     }
     if (e == hipSuccess) done = true;
     else if (e != hipErrorCooperativeLaunchTooLarge) {   // a later batch slab failed after earlier ones ran

@@ -2,16 +2,15 @@
 //
 // The per-step kernels pay a launch per time step and re-read their W_h slice from the memory
 // system every step.  Here each work-group (32 hidden units x 8 batch rows, or x 16 rows for batches
-// that the 8-row form cannot hold in one launch; backward also 16 x 16 and 32 x 8 forms that exchange
-// dz, kept as fallbacks) loads its slice of the packed W_h into registers once and then walks all T steps.
+// that the 8-row form cannot hold in one launch) loads its slice of the packed W_h into registers once and
+// then walks all T steps.
 //
 // Only h_t (forward) or partial sums of Dh (backward) cross work-groups.  Measurements on this device
 // showed that a counter barrier is the wrong tool: atomics on one address serialise at ~16 ns each
 // (4 us for 256 work-groups) and agent-scope fences cost microseconds more.  So there is no
 // barrier and no fence here.  The exchanged data lives in a two-slot ring whose every 8-byte unit
-// holds its values AND a tag of the step that wrote it (forward and partial sums: four bf16 values, the tag
-// one bit that their range leaves free; dz: three values and a 16-bit tag), written with one 64-bit
-// store and read with cache-bypassing 16-byte loads.  A consumer simply re-reads an operand until
+// holds its values AND a tag of the step that wrote it (four bf16 values, the tag one bit that their
+// range leaves free), written with one 64-bit store and read with cache-bypassing 16-byte loads.  A consumer simply re-reads an operand until
 // its tags show the step it is waiting for: value and "ready" flag arrive in the same atomic
 // unit, so no ordering between different addresses is ever needed.
 //
@@ -53,7 +52,6 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #endif
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
-constexpr int kWindow = 10;             // ring loads in flight per wavefront (6 to 16 measured alike; all at once is slower)
 // cache policy of the polling loads: bit 4 = coherent at agent scope (bypasses the XCD-local L2),
 // bit 31 = volatile, so the compiler re-issues the load in every poll
 constexpr int kSc1 = (int)(16u | 0x80000000u);
@@ -67,9 +65,9 @@ __device__ __forceinline__ void st_relaxed(unsigned* p, unsigned v) {
 
 // Ring reads.  One wavefront owns chunks kc = wave + 4*it of its row tile.  Reads of freshly written
 // remote data are latency-bound per compute unit and degrade when more than ~12 KiB per wavefront is in
-// flight, so (a) a wave first polls two of its chunks until they show the awaited tag, which is cheap
-// while the producers are still busy, and only then (b) streams its operands with a bounded window of loads
-// in flight, checking every tag; if any tag is stale the whole stream is repeated.
+// flight, so (a) a wave first polls the first two of its loads until they show the awaited tag, which is cheap
+// while the producers are still busy, and only then (b) fetches the rest, checking every tag; a load whose tags
+// are stale is fetched again on its own (fix_up_batch, or an immediate re-issue through LDS), never the whole set.
 //
 // Nothing in the stream is predicated.  The buffer descriptor covers exactly the nkc chunks of the row tile,
 // so a load past the end (chunks the template bound adds beyond nkc, lanes whose rows this work-group does
@@ -85,13 +83,11 @@ __device__ __forceinline__ int rot_index(int i, int rot, int nitv) {
 }
 struct RingReader {
   __amdgpu_buffer_rsrc_t rs;
-  int nkc, wave, chunks_per_it;
   int rot, nitv;                         // load i of the stream fetches iteration (i + rot) mod nitv of the row tile
   unsigned voff;                         // byte offset of this lane's first load (parked out of range if the lane is off)
   unsigned it_bytes;                     // byte distance between consecutive loads of a lane
   int lim, lim_step;                     // load `it` carries awaited tags for this lane iff lim_step*it < lim
   unsigned tag;                          // the awaited tag as it sits in the upper half of a unit's second dword
-  bool bit_tag = false;                  // forward ring: the tag is one bit (kLLFwdTagBit), the rest of that half is a value
   unsigned* err;
   unsigned limit;
 
@@ -104,58 +100,11 @@ struct RingReader {
   // Lanes whose units carry no tag (padding inside the ring, chunks past the end) report nothing, whatever they read.
   __device__ __forceinline__ unsigned tag_diff(const u32x4& x, int it, unsigned tagw) const {
     const unsigned t = (x[1] ^ tagw) | (x[3] ^ tagw);
-    return expects(it) ? (bit_tag ? t & kLLFwdTagBit : t) : 0u;
+    return expects(it) ? t & kLLFwdTagBit : 0u;
   }
   __device__ __forceinline__ unsigned stale_bits(const u32x4& x, int it) const {
     const unsigned d = ((x[1] >> 16) ^ tag) | ((x[3] >> 16) ^ tag);
-    return lim_step * it < lim ? (bit_tag ? d & (kLLFwdTagBit >> 16) : d) : 0u;
-  }
-  // bounded wait on the wave's last chunk; returns the number of polls (diagnostics only)
-  __device__ __forceinline__ unsigned wait_sample(bool& dead) const {
-    if (dead || wave >= nkc) return 0;
-    // two loads of this wave's stream, the last and the middle one: a second sample costs nothing extra per
-    // poll and makes stale operands in the stream that follows several times rarer
-    const int it = it_of(nitv - 1), it2 = it_of((nitv - 1) / 2);
-    for (unsigned poll = 0;; ++poll) {
-      const u32x4 x = load_it(it);
-      const u32x4 x2 = load_it(it2);
-      if (__all((stale_bits(x, it) | stale_bits(x2, it2)) == 0u)) return poll + 1;
-      if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
-        st_relaxed(err, 1u);
-        dead = true;
-        return poll + 1;
-      }
-    }
-  }
-  // Streams the wave's NIT loads through `use(i, operand)` with at most W loads in flight: a window of that
-  // size is the most the memory path of one compute unit sustains before the latency per load climbs.
-  // A load in which any lane saw a stale tag is skipped (wave-uniform branch) and recorded in the returned bit
-  // mask; `fix_up` then fetches exactly those loads again.  Once the sample has
-  // turned this is rare, and it costs one extra load latency instead of a second pass over everything.
-  template <int NIT, int W, bool PIN = false, typename F>
-  __device__ __forceinline__ unsigned long long stream(F&& use) const {
-    u32x4 x[W];
-    unsigned long long redo = 0ull;
-#pragma unroll
-    for (int i = 0; i < W && i < NIT; ++i) x[i] = load_it(it_of(i));
-    // PIN: nothing is scheduled across this point, so the whole window is issued before anything waits on it
-    // (needed where register pressure would otherwise make the compiler serialise the loads)
-    if (PIN) __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < NIT; ++i) {
-      // PIN: each load is waited for, checked and consumed in turn (otherwise the compiler gathers the waits and
-      // checks of all loads in front of consumers it cannot see into, and nothing overlaps the later loads)
-      if (PIN) __builtin_amdgcn_sched_barrier(0);
-      const u32x4 v = x[i % W];
-      if (i + W < NIT) x[i % W] = load_it(it_of(i + W));
-      // A vector compare into VCC and
-      // a branch on it: anything that routes the verdict through scalar registers (a ballot kept in a mask, selects
-      // on it) stalls on the vector-to-scalar hand-over, which was a third of the backward kernel's stream phase.
-      const unsigned t = tag_diff(v, it_of(i), tag << 16);
-      if (__builtin_expect(__builtin_amdgcn_ballot_w64(t > 0xffffu) == 0ull, 1)) use(i, make_uint4(v[0], v[1] & 0xffffu, v[2], v[3] & 0xffffu));
-      else redo |= 1ull << i;
-    }
-    return redo;
+    return lim_step * it < lim ? d & (kLLFwdTagBit >> 16) : 0u;
   }
   // Second pass over the loads marked in `redo`, all of them in flight at once: every round fetches those still
   // marked, hands the ones whose tags have all turned to `use` (operand as loaded, tags included) and keeps the
@@ -182,28 +131,6 @@ struct RingReader {
       }
     }
   }
-  // Second pass over the loads marked in `redo`: each is polled (bounded) until all its tags are the awaited
-  // ones and then fed to `use`.
-  template <int NIT, typename F>
-  __device__ __forceinline__ void fix_up(unsigned long long redo, bool& dead, F&& use) const {
-#pragma unroll
-    for (int i = 0; i < NIT; ++i) {
-      if (!((redo >> i) & 1ull) || dead) continue;
-      const int it = it_of(i);
-      for (unsigned poll = 0;; ++poll) {
-        const u32x4 v = load_it(it);
-        if (__builtin_amdgcn_ballot_w64(stale_bits(v, it) != 0u) == 0ull) {
-          use(i, make_uint4(v[0], v[1] & 0xffffu, v[2], v[3] & 0xffffu));
-          break;
-        }
-        if (poll >= limit || ((poll & 63u) == 63u && ld_relaxed(err) != 0u)) {
-          st_relaxed(err, 1u);
-          dead = true;
-          break;
-        }
-      }
-    }
-  }
 };
 
 // `nchunk_valid` counts the 16-lane groups (quarter chunks) that producers write; `lane_on` is false for lanes
@@ -214,10 +141,10 @@ __device__ __forceinline__ RingReader make_reader(const uint4* base, int nkc, in
   r.nitv = (nkc + 3) / 4; r.rot = rot;
   r.rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nkc * 1024, kBufFlags);
   r.voff = lane_on ? (unsigned)(wave * 1024 + lane * 16) : 0x7ff00000u;
-  r.it_bytes = 4096u; r.chunks_per_it = 4;
+  r.it_bytes = 4096u;
   r.lim = lane_on ? nchunk_valid - (lane >> 4) - 4 * wave : -0x40000000;
   r.lim_step = 16;
-  r.nkc = nkc; r.wave = wave; r.tag = tag; r.err = err; r.limit = limit;
+  r.tag = tag; r.err = err; r.limit = limit;
   return r;
 }
 
@@ -234,10 +161,10 @@ __device__ __forceinline__ RingReader make_reader_half(const uint4* base, int nk
   const int row = lane & 15, g = lane >> 4, second = row >> 3;
   r.rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nkc * 1024, kBufFlags);
   r.voff = (unsigned)((wave + 4 * second) * 1024 + (g * 16 + half * 8 + (row & 7)) * 16);
-  r.it_bytes = 8192u; r.chunks_per_it = 8;
+  r.it_bytes = 8192u;
   r.lim = nchunk_valid - g - 4 * wave - 16 * second;
   r.lim_step = 32;
-  r.nkc = nkc; r.wave = wave; r.tag = tag; r.err = err; r.limit = limit;
+  r.tag = tag; r.err = err; r.limit = limit;
   return r;
 }
 __device__ __forceinline__ uint4 rotate_rows_by_8(uint4 v) {
@@ -350,16 +277,6 @@ __device__ __forceinline__ bool group_is_xcd_local(unsigned* tab, int group_base
   }
   __syncthreads();
   return verdict != 0;
-}
-
-__device__ __forceinline__ void store_unit(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
-  const unsigned long long u = (unsigned long long)(v0 | (v1 << 16)) | ((unsigned long long)(v2 | (tag << 16)) << 32);
-  __hip_atomic_store((unsigned long long*)ring + unit_index, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// the same unit for a group whose members share an XCD: a store that stays in that XCD's L2
-__device__ __forceinline__ void store_unit_local(uint4* ring, long unit_index, unsigned v0, unsigned v1, unsigned v2, unsigned tag) {
-  const unsigned long long u = (unsigned long long)(v0 | (v1 << 16)) | ((unsigned long long)(v2 | (tag << 16)) << 32);
-  __hip_atomic_store((unsigned long long*)ring + unit_index, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // Work-group -> (unit tile, row tile, direction).  Work-groups are dealt to the 8 XCDs round-robin in launch
@@ -487,7 +404,6 @@ __global__ __launch_bounds__(256) void persist_fwd8_kernel(PFwdArgs a) {
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
     uint4* rout = (tau & 1) ? d.ring0 : d.ring1;
     RingReader rd = make_reader_half(rin, nkc, ntiles16 * 2, wave, lane, half, ll_fwd_tag((unsigned)tau) << 14, err, a.spin_limit, rot);
-    rd.bit_tag = true;
     f32x4 acc[2][4];
     {
       // One MFMA of register set `it` into accumulator (ct, q).
@@ -792,7 +708,6 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
     PROF_MARK(4)
     const uint4* rin = ((tau & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
     RingReader rd = make_reader(rin, nkc, ntiles16 * 2, wave, lane, ll_fwd_tag((unsigned)tau) << 14, err, a.spin_limit, rot);
-    rd.bit_tag = true;
     f32x4 acc[2][4];
     {
       auto mma_one = [&](int it, int ct, int q, const u32x4& a_op) __attribute__((always_inline)) {
@@ -1029,314 +944,6 @@ __global__ __launch_bounds__(256) void persist_fwd16r_kernel(PFwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward: Dh[16 rows, 16 units] = dz[16 rows, K] W^T[K, 16], then the gate gradients of this frame
-struct BwdIn { float gi, gf, gg, go, c_new, c_prev, dy; };
-
-template <int NIT>
-__global__ __launch_bounds__(256) void persist_bwd_kernel(PBwdArgs a) {
-  __shared__ float red[4][16][17];
-  __shared__ unsigned short zb[16][66];
-  const WgCoord wg = wg_coord();
-  const PBwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
-  const int tile = wg.tile, rt = a.rt0 + wg.rt, ntiles = gridDim.x;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
-  unsigned* err = a.sync;
-  bool dead = false;
-
-  const int nitv = (nkc + 3) / 4, rot = tile % nitv;
-  uint4 w[NIT];                          // register set `it` holds the chunk that load `it` of the stream fetches
-#pragma unroll
-  for (int it = 0; it < NIT; ++it) {
-    const int kc = wave + 4 * rot_index(it, rot, nitv);
-    w[it] = kc < nkc ? d.Wb[((long)tile * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
-  }
-
-  const int r = tid >> 4, u = tid & 15;
-  const int b = rt * 16 + r, j = tile * 16 + u;
-  const bool active = b < B && j < n;
-  float Dh = 0.f, Dc = 0.f;
-  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};                 // this (row, unit)'s share of the bias gradient
-  int L = 0;
-  if (active) {
-    Dh = d.Dh[(long)b * n + j];
-    Dc = d.Dc[(long)b * n + j];
-    L = clamp_len(a.lens, b, T);
-  }
-  // everything the gate gradients need except Dh is independent of the recurrence: fetched one step ahead
-  auto fetch_in = [&](int tau) {
-    BwdIn in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const int t = d.rev ? T - 1 - tau : tau;
-    if (tau >= 0 && active && t < L) {
-      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-      in.gi = gp[0]; in.gf = gp[n]; in.gg = gp[2 * n]; in.go = gp[3 * n];
-      in.c_new = d.cs[((long)t * B + b) * n + j];
-      const int tp = d.rev ? t + 1 : t - 1;               // frame processed just before t in the forward pass
-      if (tp >= 0 && tp < T) in.c_prev = d.cs[((long)tp * B + b) * n + j];
-      else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
-      in.dy = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
-    }
-    return in;
-  };
-  BwdIn in = fetch_in(T - 1);
-
-  PROF_DECL
-  for (int tau = T - 1; tau >= -1; --tau) {
-    PROF_MARK(4)
-    const int sigma = T - 1 - tau;                       // count of backward steps done before this one
-    const int t = d.rev ? T - 1 - tau : tau;             // frame of this step (out of range when tau == -1)
-    const int t_next = d.rev ? t - 1 : t + 1;            // frame of the previous backward step
-    const bool pointwise = tau >= 0;
-    const bool valid = pointwise && active && t < L;
-    BwdIn in_next = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-    if (sigma > 0) {
-      const uint4* rin = (((sigma - 1) & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
-      const RingReader rd = make_reader(rin, nkc, ntiles * 11, wave, lane, (unsigned)sigma & 0xffffu, err, a.spin_limit, rot);
-      const unsigned np_ = rd.wait_sample(dead);
-      (void)np_;
-      PROF_POLLS(np_)
-      PROF_MARK(5)
-      f32x4 acc[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      {
-        // four independent accumulators keep the MFMA pipe from waiting on its own result;
-        // chunks beyond nkc hold zeros in both operands, so no guard is needed around the MFMAs
-        auto use = [&](int it, uint4 av) { acc[it & 3] = Mma16<bf16_t>::run(av, w[it], acc[it & 3]); };
-        const unsigned long long redo = rd.stream<NIT, kWindow>(use);
-        PROF_REDO(__popcll(redo))
-        if (redo) rd.fix_up<NIT>(redo, dead, use);
-      }
-      in_next = fetch_in(tau - 1);    // after the ring loads: loads complete in order, and these come from HBM
-      PROF_MARK(0)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = (acc[0][v] + acc[1][v]) + (acc[2][v] + acc[3][v]);
-      __syncthreads();
-      if (active && t_next < L) Dh = red[0][r][u] + red[1][r][u] + red[2][r][u] + red[3][r][u];
-    } else {
-      in_next = fetch_in(tau - 1);
-    }
-    if (pointwise) {
-      float dz[4] = {0.f, 0.f, 0.f, 0.f};
-      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, in.dy + Dh, Dc, dz);
-      unsigned short bits[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        dbsum[q] += dz[q];
-        bits[q] = f2bf_bits(dz[q]);
-        zb[r][q * 16 + u] = bits[q];                       // inactive threads publish zeros
-      }
-      __syncthreads();
-      PROF_MARK(2)
-      uint4* rout = (sigma & 1) ? d.ring1 : d.ring0;
-      const unsigned tag_out = (unsigned)(sigma + 1) & 0xffffu;
-#pragma unroll
-      for (int round = 0; round < 2; ++round) {
-        const int id = tid + 256 * round;
-        if (id < 16 * 22) {                               // consecutive threads -> consecutive 8-byte units
-          const int r2 = (id >> 1) & 15, m = ((id >> 5) << 1) | (id & 1), v0 = 3 * m;
-          const unsigned x0 = zb[r2][v0], x1 = v0 + 1 < 64 ? zb[r2][v0 + 1] : 0u, x2 = v0 + 2 < 64 ? zb[r2][v0 + 2] : 0u;
-          const int cch = tile * 11 + (m >> 1);
-          const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + r2) * 2 + (m & 1);
-          store_unit(rout, unit_index, x0, x1, x2, tag_out);
-        }
-      }
-      if (active) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits[q];
-      }
-      __syncthreads();                                      // zb and red are reused by the next step
-      PROF_MARK(3)
-    }
-    in = in_next;
-  }
-  PROF_DUMP("bwd", T)
-  if (active) {
-    d.Dh[(long)b * n + j] = Dh;
-    d.Dc[(long)b * n + j] = Dc;
-  }
-  if (d.dbpart) {                       // bias gradient: sum this work-group's 16 rows, one slice per row group
-    __shared__ float dbred[16][65];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) dbred[r][q * 16 + u] = dbsum[q];
-    __syncthreads();
-    if (tid < 64) {
-      const int q = tid >> 4, uu = tid & 15, jj = tile * 16 + uu;
-      float sum = 0.f;
-#pragma unroll
-      for (int rr = 0; rr < 16; ++rr) sum += dbred[rr][q * 16 + uu];
-      if (jj < n) {
-        d.dbpart[(long)(2 * rt) * 4 * n + q * n + jj] = sum;
-        d.dbpart[(long)(2 * rt + 1) * 4 * n + q * n + jj] = 0.f;
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// backward, second decomposition: a work-group owns 32 units for 8 batch rows (half a row tile).
-// What bounds the backward step is the ring read, rows x K bytes per work-group; halving the rows halves it.
-// The price is a W_h^T slice twice as large (352 registers per lane), which still fits the register file.
-template <int NIT>
-__global__ __launch_bounds__(256) void persist_bwd8_kernel(PBwdArgs a) {
-  __shared__ float red[4][8][33];
-  __shared__ unsigned short zb[8][2][66];
-  const WgCoord wg = wg_coord();
-  const PBwdDir d = a.d[wg.dir];       // a copy: fields read through a reference are fetched again in every time step
-  const int tile2 = wg.tile, rt = a.rt0 + (wg.rt >> 1), half = wg.rt & 1;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
-  const int ntiles16 = (n + 15) / 16;
-  unsigned* err = a.sync;
-  bool dead = false;
-
-  const int nitv = (nkc + 7) / 8, rot = tile2 % nitv;
-  uint4 w[NIT][2];                       // register sets 2p, 2p+1 hold the two chunks that load p of the stream fetches
-#pragma unroll
-  for (int it = 0; it < NIT; ++it) {
-    const int kc = wave + 4 * (2 * rot_index(it >> 1, rot, nitv) + (it & 1));
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-      const int t16 = tile2 * 2 + ct;
-      w[it][ct] = (kc < nkc && t16 < ntiles16) ? d.Wb[((long)t16 * nkc + kc) * 64 + lane] : make_uint4(0, 0, 0, 0);
-    }
-  }
-
-  const int r8 = tid >> 5, u = tid & 31;                 // pointwise pair of this thread: row r8 of the half, unit u of 32
-  const int b = rt * 16 + half * 8 + r8, j = tile2 * 32 + u;
-  const bool active = b < B && j < n;
-  float Dh = 0.f, Dc = 0.f;
-  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};                 // this (row, unit)'s share of the bias gradient
-  int L = 0;
-  if (active) {
-    Dh = d.Dh[(long)b * n + j];
-    Dc = d.Dc[(long)b * n + j];
-    L = clamp_len(a.lens, b, T);
-  }
-  auto fetch_in = [&](int tau) {
-    BwdIn in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const int t = d.rev ? T - 1 - tau : tau;
-    if (tau >= 0 && active && t < L) {
-      const float* gp = d.gates + ((long)t * B + b) * 4 * n + j;
-      in.gi = gp[0]; in.gf = gp[n]; in.gg = gp[2 * n]; in.go = gp[3 * n];
-      in.c_new = d.cs[((long)t * B + b) * n + j];
-      const int tp = d.rev ? t + 1 : t - 1;
-      if (tp >= 0 && tp < T) in.c_prev = d.cs[((long)tp * B + b) * n + j];
-      else if (d.c0) in.c_prev = d.c0[(long)b * n + j];
-      in.dy = Store<bf16_t>::load(d.dy, ((long)t * B + b) * d.lddy + j);
-    }
-    return in;
-  };
-  BwdIn in = fetch_in(T - 1);
-
-  PROF_DECL
-  for (int tau = T - 1; tau >= -1; --tau) {
-    PROF_MARK(4)
-    const int sigma = T - 1 - tau;
-    const int t = d.rev ? T - 1 - tau : tau;
-    const int t_next = d.rev ? t - 1 : t + 1;
-    const bool pointwise = tau >= 0;
-    const bool valid = pointwise && active && t < L;
-    BwdIn in_next = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-    if (sigma > 0) {
-      const uint4* rin = (((sigma - 1) & 1) ? d.ring1 : d.ring0) + (long)rt * nkc * 64;
-      const RingReader rd = make_reader_half(rin, nkc, ntiles16 * 11, wave, lane, half, (unsigned)sigma & 0xffffu, err, a.spin_limit, rot);
-      const unsigned np_ = rd.wait_sample(dead);
-      (void)np_;
-      PROF_POLLS(np_)
-      PROF_MARK(5)
-      f32x4 acc[2][2];
-#pragma unroll
-      for (int x = 0; x < 2; ++x)
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct) acc[x][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      {
-        auto use = [&](int p, uint4 av) {
-          const uint4 av2 = rotate_rows_by_8(av);
-#pragma unroll
-          for (int ct = 0; ct < 2; ++ct) {
-            acc[0][ct] = Mma16<bf16_t>::run(av, w[2 * p][ct], acc[0][ct]);
-            acc[1][ct] = Mma16<bf16_t>::run(av2, w[2 * p + 1][ct], acc[1][ct]);
-          }
-        };
-        const unsigned long long redo = rd.stream<NIT / 2, kWindow>(use);
-        PROF_REDO(__popcll(redo))
-        if (redo) rd.fix_up<NIT / 2>(redo, dead, use);
-      }
-      in_next = fetch_in(tau - 1);
-      PROF_MARK(0)
-      // accumulator rows 4*(lane/16) + v; this work-group's rows sit in fragment rows 0..7
-      if (lane < 32) {
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][ct * 16 + (lane & 15)] = acc[0][ct][v] + acc[1][ct][v];
-      }
-      __syncthreads();
-      if (active && t_next < L) Dh = red[0][r8][u] + red[1][r8][u] + red[2][r8][u] + red[3][r8][u];
-    } else {
-      in_next = fetch_in(tau - 1);
-    }
-    if (pointwise) {
-      float dz[4] = {0.f, 0.f, 0.f, 0.f};
-      if (valid) lstm_cell_grad(in.gi, in.gf, in.gg, in.go, in.c_new, in.c_prev, in.dy + Dh, Dc, dz);
-      unsigned short bits[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        dbsum[q] += dz[q];
-        bits[q] = f2bf_bits(dz[q]);
-        zb[r8][u >> 4][q * 16 + (u & 15)] = bits[q];      // inactive threads publish zeros
-      }
-      __syncthreads();
-      PROF_MARK(2)
-      uint4* rout = (sigma & 1) ? d.ring1 : d.ring0;
-      const unsigned tag_out = (unsigned)(sigma + 1) & 0xffffu;
-#pragma unroll
-      for (int round = 0; round < 2; ++round) {
-        const int id = tid + 256 * round;                 // 8 rows x 2 producers x 22 units
-        if (id < 8 * 2 * 22) {                            // consecutive threads -> consecutive 8-byte units of a chunk
-          const int pp = id / 176, rest = id - 176 * pp, rr = (rest >> 1) & 7, m = ((rest >> 4) << 1) | (rest & 1), v0 = 3 * m;
-          const int t16 = tile2 * 2 + pp;
-          if (t16 < ntiles16) {
-            const unsigned x0 = zb[rr][pp][v0], x1 = v0 + 1 < 64 ? zb[rr][pp][v0 + 1] : 0u, x2 = v0 + 2 < 64 ? zb[rr][pp][v0 + 2] : 0u;
-            const int cch = t16 * 11 + (m >> 1);
-            const long unit_index = (((long)rt * nkc + (cch >> 2)) * 64 + (cch & 3) * 16 + half * 8 + rr) * 2 + (m & 1);
-            store_unit(rout, unit_index, x0, x1, x2, tag_out);
-          }
-        }
-      }
-      if (active) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) ((unsigned short*)d.DZ)[((long)t * B + b) * 4 * n + q * n + j] = bits[q];
-      }
-      __syncthreads();
-      PROF_MARK(3)
-    }
-    in = in_next;
-  }
-  PROF_DUMP("bwd8", T)
-  if (active) {
-    d.Dh[(long)b * n + j] = Dh;
-    d.Dc[(long)b * n + j] = Dc;
-  }
-  if (d.dbpart) {                       // bias gradient: sum this work-group's 8 rows, one slice per row group
-    __shared__ float dbred[8][129];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) dbred[r8][q * 32 + u] = dbsum[q];
-    __syncthreads();
-    if (tid < 128) {
-      const int q = tid >> 5, uu = tid & 31, jj = tile2 * 32 + uu;
-      float sum = 0.f;
-#pragma unroll
-      for (int rr = 0; rr < 8; ++rr) sum += dbred[rr][q * 32 + uu];
-      if (jj < n) d.dbpart[(long)(2 * a.rt0 + wg.rt) * 4 * n + q * n + jj] = sum;
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // backward, third decomposition ("partial sums"): no dz crosses work-groups.  A work-group still owns 32 units for
 // 8 rows, but it multiplies ITS dz (8 rows x 128 gate columns) by the matching 128 rows of W_h^T for ALL n outputs
 // and publishes, per destination tile of 32 units, a partial sum of Dh (bf16).  A consumer adds the partial sums
@@ -1500,9 +1107,9 @@ __global__ __launch_bounds__(256) void persist_bwdp_kernel(PBwdArgs a) {
                                                 kBufFlags);
       // load `it` of this wavefront covers producers 2 * (wave + 4 * it) and the one after it (1 KiB)
       rd.voff = (unsigned)(wave * 2 * kPartBytes + lane * 16);
-      rd.it_bytes = 8u * kPartBytes; rd.chunks_per_it = 4;
+      rd.it_bytes = 8u * kPartBytes;
       rd.lim = ntile2 - 2 * wave - chalf; rd.lim_step = 8;
-      rd.nkc = ntile2; rd.wave = wave; rd.tag = part_tag(sigma) << 14; rd.bit_tag = true; rd.err = err; rd.limit = a.spin_limit;
+      rd.tag = part_tag(sigma) << 14; rd.err = err; rd.limit = a.spin_limit;
       rd.nitv = nitv; rd.rot = rot;
       constexpr int NLD = NPW / 2;                          // loads per wavefront
       float ps[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -1876,9 +1483,9 @@ __global__ __launch_bounds__(256) void persist_bwdp16_kernel(PBwdArgs a) {
                                                 kBufFlags);
       // load `it` of this wavefront covers producer wave + 4 * it (1 KiB)
       rd.voff = (unsigned)(wave * kBlock + lane * 16);
-      rd.it_bytes = 4u * kBlock; rd.chunks_per_it = 4;
+      rd.it_bytes = 4u * kBlock;
       rd.lim = ntile2 - wave; rd.lim_step = 4;
-      rd.nkc = ntile2; rd.wave = wave; rd.tag = part_tag(sigma) << 14; rd.bit_tag = true; rd.err = err; rd.limit = a.spin_limit;
+      rd.tag = part_tag(sigma) << 14; rd.err = err; rd.limit = a.spin_limit;
       rd.nitv = nitv; rd.rot = rot;
       constexpr int NLD = NPW;                              // loads per wavefront
       float ps[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -2116,27 +1723,6 @@ __global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nk
   }
   out[idx] = *(uint4*)v;
 }
-// backward weights: chunk index = ((dir*ntile + tile)*nkc + kc)*64 + lane ; K runs over the producers' dz values
-__global__ void pack_wh_bwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nkc, long total) {
-  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int lane = idx & 63;
-  long rest = idx >> 6;
-  const int kc = rest % nkc; rest /= nkc;
-  const int ntile = (n + 15) / 16;
-  const int tile = rest % ntile, dir = rest / ntile;
-  const int unit = tile * 16 + (lane & 15), g = lane >> 4;
-  const bf16_t* Wd = W + (long)dir * n * 4 * n;
-  bf16_t v[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int s = (kc * 4 + g) * 8 + e;
-    const int p = s / kLLSlotsBwd, val = ll_slot_value(s - p * kLLSlotsBwd, kLLValsBwd);
-    const int ju = p * 16 + (val & 15), q = val >> 4;
-    v[e] = (val >= 0 && ju < n && unit < n) ? Wd[(long)unit * 4 * n + q * n + ju] : (bf16_t)0.f;
-  }
-  out[idx] = *(uint4*)v;
-}
 // partial-sum backward kernel: chunk index = ((((dir*ntile2 + J)*4 + wave)*4 + kc)*16 + c)*64 + lane ; B fragment of
 // gate kc, K = the 32 units of tile J, columns = outputs (wave*16 + c)*16 .. +15
 __global__ void pack_wh_bwdp_kernel(const bf16_t* W, uint4* out, int n, int ntile2, long total) {
@@ -2283,34 +1869,21 @@ bool persist_fwd_fits(const PFwdArgs& a) {
   const int t32 = cdiv(cdiv(a.n, 16), 2);
   return slab_fits(persist_fwd8_kernel<kLLMaxNkcFwd / 4>, t32, 8, a.ndir);
 }
-int persist_bwd_variant(const PBwdArgs& a) {
+bool persist_bwd_fits(const PBwdArgs& a) {
   const int t32 = cdiv(cdiv(a.n, 16), 2);
-  if (!offsets_fit(a.B, a.n, std::max(a.d[0].lddy, a.d[a.ndir - 1].lddy),
-                   std::max((long)cdiv(a.B, 16) * a.nkc * 1024, (long)bwdp_ring_bytes(a.B, a.n))))
-    return kBwdNone;
-  if (a.n <= 1024 && slab_fits(persist_bwdp_kernel<8>, t32, 8, a.ndir)) return kBwdPartialSums;
-  if (a.nkc > kLLMaxNkcBwd) return kBwdNone;
-  if (slab_fits(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, t32, 8, a.ndir)) return kBwdDz8;
-  if (slab_fits(persist_bwd_kernel<kLLMaxNkcBwd / 4>, cdiv(a.n, 16), 16, a.ndir)) return kBwdDz16;
-  return kBwdNone;
+  if (!offsets_fit(a.B, a.n, std::max(a.d[0].lddy, a.d[a.ndir - 1].lddy), (long)bwdp_ring_bytes(a.B, a.n))) return false;
+  return a.n <= 1024 && slab_fits(persist_bwdp_kernel<8>, t32, 8, a.ndir);
 }
-hipError_t launch_persist_bwd(const PBwdArgs& a, int variant, hipStream_t s) {
+hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s) {
   const int t32 = cdiv(cdiv(a.n, 16), 2);
-  switch (variant) {
-    case kBwdPartialSums: {
-      // more rows than the 8-row form holds in one launch: 16 rows per work-group, if that takes a single launch
-      const int nrt = cdiv(a.B, 16);
-      if ((long)t32 * 2 * nrt * a.ndir > capacity(persist_bwdp_kernel<8>) && (long)t32 * nrt * a.ndir <= capacity(persist_bwdp16_kernel<8>)) {
-        const hipError_t e16 = coop_slabs(persist_bwdp16_kernel<8>, t32, 16, a, s);
-        if (e16 != hipErrorCooperativeLaunchTooLarge) return e16;
-        (void)hipGetLastError();
-      }
-      return coop_slabs(persist_bwdp_kernel<8>, t32, 8, a, s);
-    }
-    case kBwdDz8: return coop_slabs(persist_bwd8_kernel<kLLMaxNkcBwd / 4>, t32, 8, a, s);
-    case kBwdDz16: return coop_slabs(persist_bwd_kernel<kLLMaxNkcBwd / 4>, cdiv(a.n, 16), 16, a, s);
-    default: return hipErrorCooperativeLaunchTooLarge;
+  // more rows than the 8-row form holds in one launch: 16 rows per work-group, if that takes a single launch
+  const int nrt = cdiv(a.B, 16);
+  if ((long)t32 * 2 * nrt * a.ndir > capacity(persist_bwdp_kernel<8>) && (long)t32 * nrt * a.ndir <= capacity(persist_bwdp16_kernel<8>)) {
+    const hipError_t e16 = coop_slabs(persist_bwdp16_kernel<8>, t32, 16, a, s);
+    if (e16 != hipErrorCooperativeLaunchTooLarge) return e16;
+    (void)hipGetLastError();
   }
+  return coop_slabs(persist_bwdp_kernel<8>, t32, 8, a, s);
 }
 hipError_t launch_pack_wh_bwdp(const void* W, uint4* Wb, int n, int ndir, hipStream_t s) {
   const int ntile2 = cdiv(n, 32);
@@ -2321,11 +1894,6 @@ hipError_t launch_pack_wh_bwdp(const void* W, uint4* Wb, int n, int ndir, hipStr
 hipError_t launch_pack_wh_fwd_ll(const void* W, uint4* Wf, int n, int nkc, int ndir, hipStream_t s) {
   long total = (long)ndir * cdiv(n, 16) * 4 * nkc * 64;
   hipLaunchKernelGGL(pack_wh_fwd_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wf, n, nkc, total);
-  return hipGetLastError();
-}
-hipError_t launch_pack_wh_bwd_ll(const void* W, uint4* Wb, int n, int nkc, int ndir, hipStream_t s) {
-  long total = (long)ndir * cdiv(n, 16) * nkc * 64;
-  hipLaunchKernelGGL(pack_wh_bwd_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wb, n, nkc, total);
   return hipGetLastError();
 }
 hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s) {
