@@ -15,6 +15,7 @@
 #include "../../include/lstm_abi.h"
 #include "common.h"
 #include "recurrent_dev.h"
+#include <type_traits>
 
 namespace lstm {
 namespace {
@@ -220,13 +221,33 @@ __global__ void relu_bf16_kernel(const float* __restrict__ z, uint16_t* __restri
 
 // cat[r] = [s[r] | trg[r] | att[r] | zeros up to ldc]: the three inputs of the readout side by side (16-bit elements, any
 // row strides)
+// V elements per thread (V = 4: 8-byte accesses, when every piece starts and ends on a multiple of 4 elements and all
+// rows are 8-byte aligned; K .. ldc-1 is then the zero padding, ldc a multiple of 8).
+template <int V>
 __global__ void concat3_kernel(const uint16_t* __restrict__ x0, long ld0, int k0, const uint16_t* __restrict__ x1, long ld1, int k1,
                                const uint16_t* __restrict__ x2, long ld2, int k2, uint16_t* __restrict__ cat, long ldc, int B) {
+  typedef typename std::conditional<V == 4, uint2, uint16_t>::type vec_t;
   const int K = k0 + k1 + k2;                                  // columns K .. ldc-1 of cat are padding: zeros
-  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (long)B * ldc) return;
-  const int r = (int)(idx / ldc), k = (int)(idx % ldc);
-  cat[idx] = k < k0 ? x0[(long)r * ld0 + k] : (k < k0 + k1 ? x1[(long)r * ld1 + k - k0] : (k < K ? x2[(long)r * ld2 + k - k0 - k1] : (uint16_t)0));
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x, per_row = ldc / V;
+  if (idx >= (long)B * per_row) return;
+  const int r = (int)(idx / per_row), k = (int)(idx % per_row) * V;
+  const uint16_t* src = k < k0 ? x0 + (long)r * ld0 + k : (k < k0 + k1 ? x1 + (long)r * ld1 + k - k0 : x2 + (long)r * ld2 + k - k0 - k1);
+  vec_t v = {};
+  if (k < K) v = *(const vec_t*)src;
+  *(vec_t*)(cat + (long)r * ldc + k) = v;
+}
+hipError_t launch_concat3(const uint16_t* x0, long ld0, int k0, const uint16_t* x1, long ld1, int k1, const uint16_t* x2, long ld2, int k2,
+                          uint16_t* cat, long ldc, int B, hipStream_t s) {
+  const bool v4 = ((k0 | k1 | k2 | (int)(ld0 & 3) | (int)(ld1 & 3) | (int)(ld2 & 3) | (int)(ldc & 3)) & 3) == 0 &&
+                  ((((uintptr_t)x0) | ((uintptr_t)x1) | ((uintptr_t)x2) | ((uintptr_t)cat)) & 7) == 0;
+  if (v4) {
+    const long total = (long)B * (ldc / 4);
+    hipLaunchKernelGGL(concat3_kernel<4>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x0, ld0, k0, x1, ld1, k1, x2, ld2, k2, cat, ldc, B);
+  } else {
+    const long total = (long)B * ldc;
+    hipLaunchKernelGGL(concat3_kernel<1>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x0, ld0, k0, x1, ld1, k1, x2, ld2, k2, cat, ldc, B);
+  }
+  return hipGetLastError();
 }
 
 inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
@@ -361,9 +382,8 @@ int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, co
   float* z = (float*)((char*)cat + up256((size_t)B * Kp * 2));
   float* parts = (float*)((char*)z + up256((size_t)B * R * 4));
   if (!(flags & LSTM_FLAG_WEIGHTS_PACKED) && launch_pad_rows(W_r, Wp, R, K, (int)Kp, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
-  const long total_cat = (long)B * Kp;
-  hipLaunchKernelGGL(concat3_kernel, dim3((unsigned)((total_cat + 255) / 256)), dim3(256), 0, st, (const uint16_t*)s, (long)ld_s, n,
-                     (const uint16_t*)trg, (long)ld_trg, n_trg, (const uint16_t*)att, (long)ld_att, E, cat, Kp, B);
+  if (launch_concat3((const uint16_t*)s, (long)ld_s, n, (const uint16_t*)trg, (long)ld_trg, n_trg, (const uint16_t*)att, (long)ld_att, E, cat,
+                     Kp, B, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
   {                                  // few rows: bias, max(0, .) and the rounding happen in the product's epilogue
     GemmArgs g = {};
     g.A = cat; g.B = Wp; g.C = out; g.bias = b_r; g.M = B; g.N = R; g.K = (int)Kp; g.lda = Kp; g.ldb = Kp; g.ldc = ld_out;

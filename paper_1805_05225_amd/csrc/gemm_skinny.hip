@@ -16,6 +16,11 @@
 // are avoided by placement: the 16-byte slot p of row r holds k-chunk p ^ ((r >> 1) & 7).  What bounds it is the path
 // from L2 to LDS (about 47 bytes per clock and compute unit, measured for the large kernels): 28 KiB per stage
 // against 384 clocks of MFMA work, i.e. about 600 clocks per stage.
+//
+// A second tile shape, 64 rows x 64 columns (every wavefront one k-step of a 64 x 32 block), serves products whose
+// 96 x 128 tiles would occupy less than half the device (the decoder's query projection and readout, 768 x 1000: 64 tiles
+// against 192): what bounds the kernel is the rate at which ONE compute unit pulls operands from L2, so more, smaller
+// tiles finish sooner although they move more bytes in total.
 #include "recurrent_dev.h"
 
 namespace lstm {
@@ -23,14 +28,20 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 constexpr int kBufFlags = 0x00020000;   // raw buffer descriptor word 3 for gfx9-family devices
-constexpr int kTM = 96, kTN = 128;
 constexpr int kRow = 128;                          // bytes per LDS row (64 bfloat16)
-constexpr int kAop = kTM * kRow, kBop = kTN * kRow, kStage = kAop + kBop;      // 12 + 16 KiB
-constexpr int kLoads = (kTM + kTN) / 8;            // wavefront-loads per stage: 12 for A, 16 for B
 constexpr int kDepth = 4;                          // stages in LDS: three in flight while one is multiplied (2: +20 %, 3 and 5: the same)
-constexpr int kDummy = kDepth * kStage;            // 4 KiB that the surplus loads of a stage write zeros to (see the kernel)
-constexpr int kEpStride = kTN + 4;                 // floats per staged row
-constexpr int kLds = kDummy + 4096;                // 118784 bytes; the epilogue's staging (96 x 132 floats) reuses the stages
+// Tile geometry for wavefront blocks of BI x BJ MFMA blocks (32 x 32): the tile is 32 BI rows x 64 BJ columns.
+template <int BI, int BJ>
+struct Geo {
+  static constexpr int kTM = 32 * BI, kTN = 64 * BJ;
+  static constexpr int kAop = kTM * kRow, kBop = kTN * kRow, kStage = kAop + kBop;   // <3,2>: 12 + 16 KiB
+  static constexpr int kLoads = (kTM + kTN) / 8;                                      // wavefront-loads per stage
+  static constexpr int kPerWave = (kLoads + 7) / 8;                                   // issued by every wavefront per stage
+  static constexpr int kDummy = kDepth * kStage;      // 4 KiB that the surplus loads of a stage write zeros to (see the kernel)
+  static constexpr int kEpStride = kTN + 4;           // floats per staged row
+  static constexpr int kLds = kDummy + 4096;          // <3,2>: 118784 bytes; the epilogue's staging reuses the stages
+  static_assert(kTM * kEpStride * 4 <= kDummy, "the epilogue's staging must fit into the stage buffers");
+};
 constexpr unsigned kParked = 0x7ffffff0u;
 
 struct SkinnyArgs {
@@ -61,14 +72,17 @@ __device__ __forceinline__ f32x16 mma32(uint4 a, uint4 b, f32x16 c) {
 }
 
 // Work-group -> tile.  Work-groups are dealt to the eight XCDs round-robin (blockIdx & 7 is the XCD).  The tiles an XCD
-// runs at a time should share operand panels out of its L2: with tiles_m <= 8 row tiles, an XCD takes all row tiles of
+// runs at a time should share operand panels out of its L2: with tiles_m <= 32 row tiles, an XCD takes all row tiles of
 // 32 / bm column tiles at a time (bm = tiles_m rounded up to a power of two); otherwise tiles are dealt row-major.
+// s_waitcnt operand for vmcnt(n) lgkmcnt(0): vmcnt's low four bits sit in bits 3:0, its upper two in bits 15:14
+constexpr int vm_wait(unsigned n) { return (int)(0x0070u | (n & 15u) | ((n >> 4) << 14)); }
 struct Tile { int tm, tn, pos; bool live; };
+__host__ __device__ inline int pow2_at_least(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 __device__ __forceinline__ Tile tile_of(int tiles_m, int tiles_n) {
   Tile t = {0, 0, 0, false};
   const int bid = blockIdx.x;
-  if (tiles_m <= 8) {
-    const int bm = tiles_m <= 1 ? 1 : tiles_m <= 2 ? 2 : tiles_m <= 4 ? 4 : 8, bn = 32 / bm;
+  if (tiles_m <= 32) {
+    const int bm = pow2_at_least(tiles_m), bn = 32 / bm;
     const int xcd = bid & 7, slot = bid >> 3, group = (slot / 32) * 8 + xcd, pos = slot % 32;
     t.tm = pos % bm; t.tn = group * bn + pos / bm; t.pos = pos;
     t.live = t.tm < tiles_m && t.tn < tiles_n;
@@ -79,20 +93,24 @@ __device__ __forceinline__ Tile tile_of(int tiles_m, int tiles_n) {
   return t;
 }
 inline int grid_for(int tiles_m, int tiles_n) {
-  if (tiles_m <= 8) {
-    const int bm = tiles_m <= 1 ? 1 : tiles_m <= 2 ? 2 : tiles_m <= 4 ? 4 : 8, bn = 32 / bm;
+  if (tiles_m <= 32) {
+    const int bm = pow2_at_least(tiles_m), bn = 32 / bm;
     const int groups = cdiv(tiles_n, bn);
     return cdiv(groups, 8) * 8 * 32;
   }
   return tiles_m * tiles_n;
 }
 
-template <bool CELL>
+template <int BI, int BJ, bool CELL>
 __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
+  typedef Geo<BI, BJ> G;
+  constexpr int kTM = G::kTM, kTN = G::kTN, kAop = G::kAop, kStage = G::kStage, kLoads = G::kLoads, kDummy = G::kDummy,
+                kEpStride = G::kEpStride, kPerWave = G::kPerWave;
+  static_assert(!CELL || (BI == 3 && BJ == 2), "the cell epilogue expects the four gates of 32 units in a tile's 128 columns");
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int kq = wave >> 1, wc = wave & 1;          // k-step of a stage (0..3) and column half (64 columns) of this wavefront
+  const int kq = wave >> 1, wc = wave & 1;          // k-step of a stage (0..3) and column half (32 BJ columns) of this wavefront
   const int r = lane & 31, gq = lane >> 5;
   const int tiles_m = (g.M + kTM - 1) / kTM, tiles_n = (g.N + kTN - 1) / kTN;
   const Tile tl = tile_of(tiles_m, tiles_n);
@@ -105,20 +123,19 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
   // found in L2 by the others when their turn comes (the sum over k does not care about the order).
   const int rot = (int)(((long)tl.pos * nstage) >> 5);
 
-  f32x16 acc[3][2];
+  f32x16 acc[BI][BJ];
 #pragma unroll
-  for (int i = 0; i < 3; ++i)
+  for (int i = 0; i < BI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < BJ; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // Loads: wavefront-load q of a stage (q = wave + 8 i, i < 4) fills rows 8 q' .. 8 q' + 7 of A (q < 12) or B (q < 28);
+  // Loads: wavefront-load q of a stage (q = wave + 8 i) fills rows 8 q' .. 8 q' + 7 of A (q < kTM / 8) or B (q < kLoads);
   // lane l fills slot l & 7 of row l >> 3 of those, i.e. fetches k-chunk (l & 7) ^ swizzle(row).  Rows past the operand's
-  // end and chunks past K point outside the buffer descriptor and arrive as zeros.  Every wavefront issues four loads
-  // per stage, so that one wait count serves all of them: the four surplus ones (q >= 28) have every lane parked and
-  // write their zeros to a spare 4 KiB of LDS without touching memory.
-  constexpr int kPerWave = 4;
+  // end and chunks past K point outside the buffer descriptor and arrive as zeros.  Every wavefront issues the same
+  // number of loads per stage, so that one wait count serves all of them: surplus ones (q >= kLoads; four in the 96 x 128
+  // tile) have every lane parked and write their zeros to a spare 4 KiB of LDS without touching memory.
   unsigned voff[kPerWave], dst[kPerWave];
   int chunk[kPerWave];
   bool is_b[kPerWave];
@@ -146,13 +163,13 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
       const bool past = kt * 64 + chunk[i] * 8 >= K;           // ragged last k-tile (and every surplus load)
-      const unsigned where = (i == 3 && wave >= 4) ? lds_base + kDummy + (unsigned)(wave - 4) * 1024u : buf + dst[i];
+      const unsigned where = wave + 8 * i >= kLoads ? lds_base + kDummy + (unsigned)(wave & 3) * 1024u : buf + dst[i];
       load_to_lds_b128(is_b[i] ? rb : ra, where, past ? kParked : voff[i], (unsigned)kt * 128u);
     }
   };
-  // Fragment reads: row (i*32 + r) of A / (wc*64 + j*32 + r) of B, k-chunk 2 kq + gq, in slot (2 kq + gq) ^ ((row >> 1) & 7)
+  // Fragment reads: row (i*32 + r) of A / (wc*32*BJ + j*32 + r) of B, k-chunk 2 kq + gq, in slot (2 kq + gq) ^ ((row >> 1) & 7)
   const int slot = ((2 * kq + gq) ^ ((r >> 1) & 7)) * 16;
-  const int fa_off = r * kRow + slot, fb_off = kAop + (wc * 64 + r) * kRow + slot;
+  const int fa_off = r * kRow + slot, fb_off = kAop + (wc * 32 * BJ + r) * kRow + slot;
 
   // Pipeline: while the MFMAs of stage it run (fragments in registers), the fragments of stage it+1 are read from LDS
   // and the loads of stages it+2 .. it+4 are in flight (a load from beyond L2 takes longer than two stages of MFMAs:
@@ -161,7 +178,7 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
   // order, four per wavefront and stage: when at most 8 are outstanding, everything up to the stage two behind the
   // newest has landed.  A buffer is overwritten one iteration after every wavefront has passed the barrier behind
   // which it read the buffer's fragments (and waited for them).
-  uint4 fa[2][3], fb[2][2];                        // [register set][row block], [register set][column block]
+  uint4 fa[2][BI], fb[2][BJ];                      // [register set][row block], [register set][column block]
   auto read_a = [&](int it, int set, int i) __attribute__((always_inline)) {
     fa[set][i] = *(const uint4*)(lds + (it % kDepth) * kStage + fa_off + i * 32 * kRow);
   };
@@ -169,32 +186,41 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
     fb[set][j] = *(const uint4*)(lds + (it % kDepth) * kStage + fb_off + j * 32 * kRow);
   };
   auto wait_stage = [&](int newer) __attribute__((always_inline)) {       // `newer` stages were issued behind the awaited one
-    if (newer >= 4) __builtin_amdgcn_s_waitcnt(0x4070);                    // vmcnt(16) lgkmcnt(0)
-    else if (newer == 3) __builtin_amdgcn_s_waitcnt(0x007c);               // vmcnt(12) lgkmcnt(0)
-    else if (newer == 2) __builtin_amdgcn_s_waitcnt(0x0078);               // vmcnt(8)
-    else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0074);               // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0070);                               // vmcnt(0)
+    if (newer >= 4) __builtin_amdgcn_s_waitcnt(vm_wait(4 * kPerWave));
+    else if (newer == 3) __builtin_amdgcn_s_waitcnt(vm_wait(3 * kPerWave));
+    else if (newer == 2) __builtin_amdgcn_s_waitcnt(vm_wait(2 * kPerWave));
+    else if (newer == 1) __builtin_amdgcn_s_waitcnt(vm_wait(kPerWave));
+    else __builtin_amdgcn_s_waitcnt(vm_wait(0));
   };
 #pragma unroll
   for (int j = 0; j < kDepth; ++j)
     if (j < nstage) issue(j);
   wait_stage(min(nstage - 1, kDepth - 1));
   __syncthreads();
-  read_b(0, 0, 0); read_a(0, 0, 0); read_a(0, 0, 1); read_a(0, 0, 2); read_b(0, 0, 1);
-  // The six MFMAs of a stage in the order (row block, column block) = (0,0) (1,0) (2,0) (0,1) (1,1) (2,1); with `next`,
-  // one fragment read of the following stage goes out behind each of the first five, in the order the MFMAs will want
-  // them.  (All reads in front of the MFMAs held the MFMAs back until the LDS had taken them: reads and MFMAs of a
-  // stage then ran one after the other.)
+  // fragment read number q of a stage, in the order the MFMAs will want them: B block 0, the A blocks, the other B blocks
+  auto read_nr = [&](int it, int set, int q) __attribute__((always_inline)) {
+    if (q == 0) read_b(it, set, 0);
+    else if (q <= BI) read_a(it, set, q - 1);
+    else if (q < BI + BJ) read_b(it, set, q - BI);
+  };
+#pragma unroll
+  for (int q = 0; q < BI + BJ; ++q) read_nr(0, 0, q);
+  // The MFMAs of a stage in the order (row block, column block) = (0,0) (1,0) .. (0,1) (1,1) ..; with `next`, one
+  // fragment read of the following stage goes out behind each MFMA (96 x 128 tile: behind the first five of six),
+  // what is left of them behind the last.  (All reads in front of the MFMAs held the MFMAs back until the LDS had
+  // taken them: reads and MFMAs of a stage then ran one after the other.)
   auto mfmas = [&](int set, bool next, int it_next) __attribute__((always_inline)) {
 #pragma unroll
-    for (int m = 0; m < 6; ++m) {
-      const int i = m % 3, j = m / 3;
+    for (int m = 0; m < BI * BJ; ++m) {
+      const int i = m % BI, j = m / BI;
       acc[i][j] = mma32(fa[set][i], fb[set][j], acc[i][j]);
       if (next) {
         __builtin_amdgcn_sched_barrier(0);
-        if (m == 0) read_b(it_next, set ^ 1, 0);
-        else if (m <= 3) read_a(it_next, set ^ 1, m - 1);
-        else if (m == 4) read_b(it_next, set ^ 1, 1);
+        read_nr(it_next, set ^ 1, m);
+        if (m == BI * BJ - 1) {
+#pragma unroll
+          for (int q = BI * BJ; q < BI + BJ; ++q) read_nr(it_next, set ^ 1, q);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -223,26 +249,27 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
   __syncthreads();                                 // the stage buffers are free for the epilogue
 
   // Epilogue.  The four k-steps' shares meet in LDS (the stage buffers are free), one after the other:
-  // acc[i][j][v] is row i*32 + 8 (v / 4) + 4 gq + v % 4, column wc*64 + j*32 + r.
+  // acc[i][j][v] is row i*32 + 8 (v / 4) + 4 gq + v % 4, column wc*32*BJ + j*32 + r.
   float* ep = (float*)lds;
 #pragma unroll
   for (int round = 3; round >= 0; --round) {
     if (kq == round) {
 #pragma unroll
-      for (int i = 0; i < 3; ++i)
+      for (int i = 0; i < BI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < BJ; ++j)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            float* e = &ep[(i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3)) * kEpStride + wc * 64 + j * 32 + r];
+            float* e = &ep[(i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3)) * kEpStride + wc * 32 * BJ + j * 32 + r];
             *e = round == 3 ? acc[i][j][v] : *e + acc[i][j][v];
           }
     }
     __syncthreads();
   }
   if constexpr (!CELL) {
-    // thread -> (row, four columns): 32 threads per row, 16 rows per pass
-    const int c4 = (tid & 31) * 4, col = n0 + c4;
+    // thread -> (row, four columns): kTN / 4 threads per row, 512 / (kTN / 4) rows per pass
+    constexpr int kTpr = kTN / 4;
+    const int c4 = (tid % kTpr) * 4, col = n0 + c4;
     const float* bias = g.bias ? g.bias + g.sbiasz * z : nullptr;
     float bv[4] = {0.f, 0.f, 0.f, 0.f};
     if (bias) {
@@ -250,7 +277,7 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
       for (int k = 0; k < 4; ++k) if (col + k < g.N) bv[k] = bias[col + k];
     }
     const bool vec = (g.ldc % 4 == 0) && ((((uintptr_t)g.C) & 15u) == 0) && (g.sCz % 4 == 0) && col + 3 < g.N;
-    for (int rr = tid >> 5; rr < kTM; rr += 16) {
+    for (int rr = tid / kTpr; rr < kTM; rr += 512 / kTpr) {
       const int row = m0 + rr;
       if (row >= g.M || col >= g.N) continue;
       const float4 val = *(const float4*)&ep[rr * kEpStride + c4];
@@ -312,20 +339,25 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
   }
 }
 
-hipError_t launch(const SkinnyArgs& a, hipStream_t s) {
-  if (a.M <= 0 || a.N <= 0 || a.nz <= 0) return hipSuccess;
+template <int BI, int BJ, bool CELL>
+hipError_t launch_as(const SkinnyArgs& a, hipStream_t s) {
+  typedef Geo<BI, BJ> G;
   static bool attr_set = false;
   if (!attr_set) {
-    for (const void* k : {(const void*)skinny_kernel<false>, (const void*)skinny_kernel<true>}) {
-      const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-      if (e != hipSuccess) return e;
-    }
+    const hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<BI, BJ, CELL>, hipFuncAttributeMaxDynamicSharedMemorySize, G::kLds);
+    if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const dim3 grid(grid_for(cdiv(a.M, kTM), cdiv(a.N, kTN)), 1, a.nz);
-  if (a.cell) hipLaunchKernelGGL(skinny_kernel<true>, grid, dim3(512), kLds, s, a);
-  else hipLaunchKernelGGL(skinny_kernel<false>, grid, dim3(512), kLds, s, a);
+  const dim3 grid(grid_for(cdiv(a.M, G::kTM), cdiv(a.N, G::kTN)), 1, a.nz);
+  hipLaunchKernelGGL((skinny_kernel<BI, BJ, CELL>), grid, dim3(512), G::kLds, s, a);
   return hipGetLastError();
+}
+hipError_t launch(const SkinnyArgs& a, hipStream_t s) {
+  if (a.M <= 0 || a.N <= 0 || a.nz <= 0) return hipSuccess;
+  if (a.cell) return launch_as<3, 2, true>(a, s);
+  // fewer 96 x 128 tiles than half the device has compute units: 64 x 64 tiles
+  if ((long)cdiv(a.M, 96) * cdiv(a.N, 128) * a.nz < 128) return launch_as<2, 1, false>(a, s);
+  return launch_as<3, 2, false>(a, s);
 }
 
 // Wcell[d][128 t + 32 q + u][k] = [W_x^T | 0 | W_h^T | 0] row (q n + 32 t + u), zero for units past n; a 64 x 64 tile of

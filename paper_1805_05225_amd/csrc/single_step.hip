@@ -56,6 +56,11 @@ __global__ void concat_kernel(const uint16_t* x, const float* h, uint16_t* Acat,
     const uint2* xp = (const uint2*)(x + (long)b * n_in + k);
     const uint2 lo = xp[0], hi = xp[1];
     o = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  } else if (h && k >= n_in_pad && k + 8 <= n_in_pad + n && n % 4 == 0 && (((uintptr_t)h) & 15) == 0) {   // whole chunk of h, rows 16-byte aligned
+    const float4* hp = (const float4*)(h + ((long)d * B + b) * n + (k - n_in_pad));
+    const float4 lo = hp[0], hi = hp[1];
+    o.x = f2bf_bits(lo.x) | ((unsigned)f2bf_bits(lo.y) << 16); o.y = f2bf_bits(lo.z) | ((unsigned)f2bf_bits(lo.w) << 16);
+    o.z = f2bf_bits(hi.x) | ((unsigned)f2bf_bits(hi.y) << 16); o.w = f2bf_bits(hi.z) | ((unsigned)f2bf_bits(hi.w) << 16);
   } else {
     uint16_t v[8];
 #pragma unroll
