@@ -3,7 +3,7 @@
 //
 //     s_tr[r]   = s[r] W_s + b_s                                       one product over all rows (MFMA)
 //     e[r, j]   = v . tanh(ctx[j, q(r)] + accum[r, j] w_fb + b_fb + s_tr[r]) + b_e      att_energy_kernel (vector ALU)
-//     a[r, :]   = softmax of e[r, :] over j < src_lens[q(r)],  accum' = accum + a        att_softmax_kernel
+//     a[r, :]   = softmax of e[r, :] over j < src_lens[q(r)],  accum' = accum + a        att_context_kernel (its first part)
 //     att[r]    = sum_j a[r, j] H[j, q(r)]                                               att_context_kernel (reads H once per sentence)
 //     readout   = max(0, [s, trg, att] W_r + b_r)                      one product + bias_relu_kernel
 //
@@ -115,56 +115,59 @@ __global__ __launch_bounds__(256) void att_energy_kernel(const uint16_t* __restr
   }
 }
 
-// a[r, :] = softmax of e[r, :] over the valid positions, accum' = accum + a, for every hypothesis of sentence
-// q = blockIdx.x; 16 lanes per hypothesis, e staged in LDS first (one round of global loads).
-// Dynamic LDS: S * kMaxBeam floats, w[j][r].
-__global__ __launch_bounds__(256) void att_softmax_kernel(const float* __restrict__ e, const float* __restrict__ accum_in,
-                                                           const int* __restrict__ lens, float* __restrict__ a_out,
-                                                           float* __restrict__ accum_out, int S, int beam) {
-  extern __shared__ float w[];
-  const int q = blockIdx.x, tid = threadIdx.x;
-  const int L = src_len(lens, q, S);
-  for (int r = tid >> 4; r < beam; r += 16)
-    for (int j = tid & 15; j < L; j += 16) w[j * kMaxBeam + r] = e[((long)q * beam + r) * S + j];
-  __syncthreads();
-  const int r = tid >> 4, l = tid & 15;                         // beam <= 16: one group of 16 lanes per hypothesis
-  if (r >= beam) return;
-  const long row = (long)q * beam + r;
-  float m = -3.0e38f;
-  for (int j = l; j < L; j += 16) m = fmaxf(m, w[j * kMaxBeam + r]);
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-  float z = 0.f;
-  for (int j = l; j < L; j += 16) {
-    const float p = __expf(w[j * kMaxBeam + r] - m);
-    w[j * kMaxBeam + r] = p;
-    z += p;
-  }
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) z += __shfl_xor(z, o);
-  const float inv = L > 0 ? 1.f / z : 0.f;
-  for (int j = l; j < S; j += 16) {
-    const float p = j < L ? w[j * kMaxBeam + r] * inv : 0.f;
-    a_out[row * S + j] = p;
-    accum_out[row * S + j] = j < L ? accum_in[row * S + j] + p : 0.f;
-  }
-}
-
-// att[r] = sum_j a[r][j] H[j][q] for the hypotheses of sentence q = blockIdx.y and the 128 features from
-// blockIdx.x * 128: lane l of every wavefront owns features 2l, 2l + 1 of that slice, the four wavefronts share the
-// source positions (wavefront w takes j = w, w + 4, ...), eight loads in flight per lane, and their partial sums meet in
+// a[r, :] = softmax of e[r, :] over the valid positions, accum' = accum + a, and att[r] = sum_j a[r][j] H[j][q], for
+// the hypotheses of sentence q = blockIdx.y and the 128 features from blockIdx.x * 128.  Every work-group of a sentence
+// works the softmax out for itself (beam x S exponentials from one round of loads: cheaper than a launch of its own and
+// a pass through memory); the one with blockIdx.x == 0 writes a and accum'.  Softmax: 16 lanes per hypothesis, e staged
+// in LDS.  Context: lane l of every wavefront owns features 2l, 2l + 1 of the slice, the four wavefronts share the
+// source positions (wavefront w takes j = w, w + 4, ...), kU loads in flight per lane, and their partial sums meet in
 // LDS.  H is read once for all hypotheses of the sentence.  Dynamic LDS: S * kMaxBeam floats, w[j][r] (rows r >= beam
 // up to the next multiple of 4 hold zeros).
-__global__ __launch_bounds__(256) void att_context_kernel(const uint16_t* __restrict__ H, const float* __restrict__ a,
-                                                           const int* __restrict__ lens, uint16_t* __restrict__ att, long ldatt, int S,
-                                                           int Q, int beam, int E) {
+__global__ __launch_bounds__(256) void att_context_kernel(const uint16_t* __restrict__ H, const float* __restrict__ e,
+                                                           const float* __restrict__ accum_in, const int* __restrict__ lens,
+                                                           float* __restrict__ a_out, float* __restrict__ accum_out,
+                                                           uint16_t* __restrict__ att, long ldatt, int S, int Q, int beam, int E) {
   extern __shared__ float w[];
   __shared__ float red[3][kMaxBeam * 2][64];
   const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int L = src_len(lens, q, S);
   const int nb4 = (beam + 3) >> 2;                              // groups of four hypotheses
-  for (int r = tid >> 4; r < nb4 * 4; r += 16)
-    for (int j = tid & 15; j < L; j += 16) w[j * kMaxBeam + r] = r < beam ? a[((long)q * beam + r) * S + j] : 0.f;
+  {
+    const int r = tid >> 4, l = tid & 15;                       // beam <= 16: one group of 16 lanes per hypothesis
+    const long row = (long)q * beam + r;
+    float m = -3.0e38f;
+    if (r < beam) {
+      for (int j = l; j < L; j += 16) {
+        const float ev = e[row * S + j];
+        w[j * kMaxBeam + r] = ev;
+        m = fmaxf(m, ev);
+      }
+    } else if (r < nb4 * 4) {
+      for (int j = l; j < L; j += 16) w[j * kMaxBeam + r] = 0.f;
+    }
+    // a lane reads back only what it wrote itself until the weights are complete
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (r < beam) {
+      float z = 0.f;
+      for (int j = l; j < L; j += 16) {
+        const float p = __expf(w[j * kMaxBeam + r] - m);
+        w[j * kMaxBeam + r] = p;
+        z += p;
+      }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) z += __shfl_xor(z, o);
+      const float inv = L > 0 ? 1.f / z : 0.f;
+      for (int j = l; j < L; j += 16) w[j * kMaxBeam + r] *= inv;
+      if (blockIdx.x == 0) {
+        for (int j = l; j < S; j += 16) {
+          const float p = j < L ? w[j * kMaxBeam + r] : 0.f;
+          if (a_out) a_out[row * S + j] = p;
+          accum_out[row * S + j] = j < L ? accum_in[row * S + j] + p : 0.f;
+        }
+      }
+    }
+  }
   __syncthreads();
   const int f = (blockIdx.x * 64 + lane) * 2;
   const bool live = f < E;
@@ -322,18 +325,14 @@ int lstm_attention_step(const lstm_att_desc* d, const void* enc, const void* enc
                      b_fb, v, b_e, src_lens, e, d->S, d->Q, d->beam, d->A);
   static bool attr_set = false;                                  // S = 1024 needs 64 KiB of dynamic LDS beside the static arrays
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)att_softmax_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxS * kMaxBeam * 4) != hipSuccess ||
-        hipFuncSetAttribute((const void*)att_context_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxS * kMaxBeam * 4) != hipSuccess) {
+    if (hipFuncSetAttribute((const void*)att_context_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxS * kMaxBeam * 4) != hipSuccess) {
       (void)hipGetLastError();
       return LSTM_ERR_HIP;
     }
     attr_set = true;
   }
-  float* a_buf = a ? a : (float*)((char*)parts + (ks > 1 ? up256((size_t)ks * B * d->A * 4) : 0));
-  hipLaunchKernelGGL(att_softmax_kernel, dim3(d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, e, accum_in, src_lens, a_buf, accum_out, d->S,
-                     d->beam);
   hipLaunchKernelGGL(att_context_kernel, dim3((d->E / 2 + 63) / 64, d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, (const uint16_t*)enc,
-                     a_buf, src_lens, (uint16_t*)att, (long)ld_att, d->S, d->Q, d->beam, d->E);
+                     e, accum_in, src_lens, a, accum_out, (uint16_t*)att, (long)ld_att, d->S, d->Q, d->beam, d->E);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
   return LSTM_OK;
 }
