@@ -11,6 +11,7 @@
 // row), and one wavefront per sentence merges the beam * beam survivors (beam_merge_kernel).  Nothing returns to the host.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 #include "../../include/lstm_abi.h"
 #include "common.h"
@@ -31,17 +32,36 @@ void* g_static_ptr[kStaticDevices] = {};   // device address of `scratch` per de
 
 // (value, index) pairs ordered by larger value first, then smaller index: `better(a, b)` = a comes before b
 struct Cand { float v; int i; };
-__device__ __forceinline__ bool better(const Cand& a, const Cand& b) { return a.v > b.v || (a.v == b.v && a.i < b.i); }
-__device__ __forceinline__ Cand pick(const Cand& a, const Cand& b) { return better(a, b) ? a : b; }
-__device__ __forceinline__ Cand wave_best(Cand c) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    Cand d;
-    d.v = __shfl_xor(c.v, o);
-    d.i = __shfl_xor(c.i, o);
-    c = pick(c, d);
-  }
+__device__ __forceinline__ bool better(const Cand& a, const Cand& b) { return (a.v > b.v) | ((a.v == b.v) & (a.i < b.i)); }
+// field by field: selecting between two structs made the compiler store both to scratch memory and load one back
+__device__ __forceinline__ Cand pick(const Cand& a, const Cand& b) {
+  const bool t = better(a, b);
+  Cand c;
+  c.v = t ? a.v : b.v;
+  c.i = t ? a.i : b.i;
   return c;
+}
+// The best candidate of the wavefront, in every lane.  Six combining steps through DPP moves (neighbour in the quad, other
+// pair of the quad, mirrored half row, mirrored row, last lane of the row before, last lane of the first half), after
+// which lane 63 holds the result; 64 lanes of `__shfl_xor` took six dependent trips through the LDS crossbar per value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ Cand dpp_step(const Cand& c) {
+  Cand d;   // lanes that the move does not reach (row mask, row_bcast sources out of range) keep their own candidate
+  d.v = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(c.v), __float_as_int(c.v), CTRL, ROW_MASK, 0xf, false));
+  d.i = __builtin_amdgcn_update_dpp(c.i, c.i, CTRL, ROW_MASK, 0xf, false);
+  return pick(c, d);
+}
+__device__ __forceinline__ Cand wave_best(Cand c) {
+  c = dpp_step<0xB1, 0xf>(c);       // quad_perm [1,0,3,2]
+  c = dpp_step<0x4E, 0xf>(c);       // quad_perm [2,3,0,1]
+  c = dpp_step<0x141, 0xf>(c);      // row_half_mirror
+  c = dpp_step<0x140, 0xf>(c);      // row_mirror: every lane holds the best of its row of 16
+  c = dpp_step<0x142, 0xa>(c);      // row_bcast15 into rows 1 and 3
+  c = dpp_step<0x143, 0xc>(c);      // row_bcast31 into rows 2 and 3
+  Cand w;
+  w.v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.v), 63));
+  w.i = __builtin_amdgcn_readlane(c.i, 63);
+  return w;
 }
 // A lane's best CAP candidates so far, best first.
 template <int CAP>
@@ -87,84 +107,169 @@ __device__ __forceinline__ void wave_select(TopList<CAP>& t, int beam, F emit) {
   }
 }
 
-// Row r of the logits, one wavefront: a single pass over the row in which every lane keeps the best 16 of the entries it
-// sees (in registers; an insertion is needed ever more rarely as the list fills up with large values) and a running
-// logsumexp, then wave_select.  Writes cand_val[r][k] = score[r] + logits[r][label] - logsumexp and cand_lab[r][k].
-// (Four wavefronts per row, each with a quarter of the row and a second merge, measured slower: 63 -> 77 us.)
-template <int CAP>
-__global__ __launch_bounds__(64) void beam_row_kernel(const float* __restrict__ logits, long ld, const float* __restrict__ score,
-                                                       float* __restrict__ cand_val, int* __restrict__ cand_lab, int V, int beam) {
-  const int r = blockIdx.x, lane = threadIdx.x;
+// Row r of the logits, one work-group of four wavefronts, each with a quarter of the row: a single pass with a running
+// logsumexp.  Sorted lists per lane cost a hundred instructions for the whole wavefront whenever ONE lane has to insert, and
+// with 64 lists some lane nearly always has (59 us for 768 rows of 20000).  Instead a wavefront keeps a bound that at least
+// `beam` of the entries it has seen reach - the `beam`-th largest of its 64 lanes' running maxima, found by bisection over
+// the ordered bit patterns with ballots, renewed once per round of loads - and appends whatever reaches the bound to its
+// candidate buffer in LDS (ballot, count, one store per value): an entry strictly below the bound has `beam` entries in
+// front of it and can be dropped.  A typical row leaves a few hundred candidates, from which `beam` rounds of "every lane
+// offers its best, the wavefront picks" take the row's best, equal values by ascending label.  Should a buffer run short of
+// a round's worth of room (rows that keep rising), it is first cut down to its best `beam` the same way.
+// Writes cand_val[r][k] = score[r] + logits[r][label] - logsumexp and cand_lab[r][k].
+constexpr int kRowU = 4;                         // loads of 16 bytes in flight per lane
+constexpr int kRowRound = 64 * kRowU * 4;        // entries per wavefront and round of loads
+constexpr int kRowCap = kRowRound + 512;         // candidate buffer per wavefront (4 x 12 KiB per work-group)
+// LDS traffic between the lanes of ONE wavefront: its LDS instructions execute in program order, so all that is needed is
+// that the compiler keeps them in that order
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__global__ __launch_bounds__(256) void beam_row_kernel(const float* __restrict__ logits, long ld, const float* __restrict__ score,
+                                                        float* __restrict__ cand_val, int* __restrict__ cand_lab, int V, int beam) {
+  __shared__ float bv[4 * kRowCap];
+  __shared__ int bi[4 * kRowCap];
+  __shared__ int cnt[4];
+  __shared__ float part_m[4], part_z[4];
+  const int r = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float* src = logits + (long)r * ld;
-  TopList<CAP> t;
-  t.clear();
-  float m = -__builtin_inff(), z = 0.f;                          // running maximum and sum of exp(x - m) of this lane's entries
+  const float kNegInf = -__builtin_inff();
+  float m = kNegInf, z = 0.f;                                    // running maximum and sum of exp(x - m) of this lane's entries
   const auto fold = [&](float gm, float gz) {                    // merge (gm, gz) into (m, z)
     const float mn = fmaxf(m, gm);
-    if (mn > -__builtin_inff()) z = z * __expf(m - mn) + gz * __expf(gm - mn);
+    if (mn > kNegInf) z = z * __expf(m - mn) + gz * __expf(gm - mn);
     m = mn;
   };
-  const bool vec = (ld & 3) == 0 && ((uintptr_t)logits & 15) == 0;
-  const int n4 = vec ? V >> 2 : 0;
-  constexpr int kU = 8;                                          // loads of 16 bytes in flight per lane
-  // Inserting is a hundred instructions for the whole wavefront whenever ONE lane needs it, and with 64 private lists
-  // some lane nearly always does.  So entries are first held against a bound that at least `beam` entries seen so far
-  // reach: the `beam`-th largest of the 64 list heads, found by bisection over the ordered bit patterns with ballots,
-  // renewed once per round of loads.  Whatever lies strictly below it cannot be among the row's best `beam`.
-  float bound = -__builtin_inff();
   const int need = min(beam, 64);
-  const auto renew_bound = [&]() {
-    const unsigned f = __float_as_uint(t.v[0]);
-    const unsigned key = (f & 0x80000000u) ? ~f : (f | 0x80000000u);             // larger float <=> larger key
-    unsigned lo = 0u, hi = 0xffffffffu;
+  float bound = kNegInf;
+  const auto renew_bound = [&]() {                               // the need-th largest of the lanes' maxima m, rounded down
+    const unsigned f = __float_as_uint(m);
+    const unsigned key = ((f & 0x80000000u) ? ~f : (f | 0x80000000u)) >> 12;     // larger float => key not smaller; 20 bits
+    unsigned lo = 0u, hi = 0xfffffu;
     while (lo < hi) {
       const unsigned mid = lo + ((hi - lo) >> 1) + 1u;
       if (__popcll(__ballot(key >= mid)) >= need) lo = mid; else hi = mid - 1u;
     }
-    // lo = the need-th largest key; keys at or below that of -inf mean fewer than `need` lanes hold anything yet
-    bound = lo <= 0x007fffffu ? -__builtin_inff() : __uint_as_float((lo & 0x80000000u) ? (lo & 0x7fffffffu) : ~lo);
+    // lo = the need-th largest key: at least `need` maxima are at or above the smallest float with that key.  Keys at or
+    // below that of -inf mean fewer than `need` lanes hold anything yet.
+    const unsigned full = lo << 12;                               // the smallest ordered pattern with this key
+    bound = lo <= (0x007fffffu >> 12) ? kNegInf : __uint_as_float((full & 0x80000000u) ? (full & 0x7fffffffu) : ~full);
   };
-  for (int i0 = lane; i0 < n4; i0 += 64 * kU) {
-    float4 x4[kU];
+  float* wbv = bv + wave * kRowCap;
+  int* wbi = bi + wave * kRowCap;
+  int count = 0;                                                 // candidates in this wavefront's buffer (the same in every lane)
+  const auto append = [&](bool keep, float x, int label) {       // wavefront-wide: every lane calls it
+    const unsigned long long mask = __ballot(keep);
+    if (mask == 0ull) return;
+    if (keep) {
+      const int pos = count + (int)__popcll(mask & ((1ull << lane) - 1ull));
+      wbv[pos] = x;
+      wbi[pos] = label;
+    }
+    count += (int)__popcll(mask);
+  };
+  // One round of picking over this wavefront's buffer (ALL = false, `count` entries) or all four (counts in cnt[]): the
+  // best candidate, which leaves its buffer.  Runs in one wavefront.  (Counts in a private array indexed by the loop
+  // would live in scratch memory: a trip to memory per buffer and round.)
+  const auto pick_best = [&](auto all) {
+    constexpr bool ALL = decltype(all)::value;
+    Cand mine = {kNegInf, 0x7fffffff};
+    int at = -1;
 #pragma unroll
-    for (int u = 0; u < kU; ++u) x4[u] = ((const float4*)src)[min(i0 + u * 64, n4 - 1)];
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const int i4 = i0 + u * 64;
-      if (i4 < n4) {
-        const float x[4] = {x4[u].x, x4[u].y, x4[u].z, x4[u].w};
-        const float gm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-        if (gm > -__builtin_inff()) fold(gm, __expf(x[0] - gm) + __expf(x[1] - gm) + __expf(x[2] - gm) + __expf(x[3] - gm));
-        if (gm >= bound && gm > t.v[CAP - 1]) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (x[e] >= bound && x[e] > t.v[CAP - 1]) t.template insert<true>(Cand{x[e], 4 * i4 + e});
-        }
+    for (int w = 0; w < (ALL ? 4 : 1); ++w) {
+      const int buf = ALL ? w : wave, n = ALL ? cnt[w] : count;
+      for (int p = lane; p < n; p += 64) {
+        const int q = buf * kRowCap + p;
+        const Cand cd = {bv[q], bi[q]};
+        if (cd.i != 0x7fffffff && better(cd, mine)) { mine = cd; at = q; }
       }
     }
+    const Cand win = wave_best(mine);
+    if (at >= 0 && win.i == mine.i) bi[at] = 0x7fffffff;         // labels are unique, so exactly one lane owns the winner
+    wave_lds_sync();
+    return win;
+  };
+  const auto make_room = [&]() {                                 // before a round: room for all its entries
+    if (count <= kRowCap - kRowRound) return;
+    wave_lds_sync();
+    Cand kept = {kNegInf, 0x7fffffff};
+    for (int k = 0; k < need; ++k) {
+      const Cand win = pick_best(std::false_type{});
+      if (lane == k) kept = win;
+    }
+    count = 0;
+    append(kept.i != 0x7fffffff, kept.v, kept.i);
+    wave_lds_sync();
+  };
+  const bool vec = (ld & 3) == 0 && ((uintptr_t)logits & 15) == 0;
+  const int n4 = vec ? V >> 2 : 0;
+  const int q4 = (n4 + 3) >> 2, end4 = min(n4, (wave + 1) * q4);  // this wavefront's 16-byte pieces: [wave * q4, end4)
+  for (int base = wave * q4; base < end4; base += 64 * kRowU) {
+    float4 x4[kRowU];
+    float g[kRowU];
+#pragma unroll
+    for (int u = 0; u < kRowU; ++u) x4[u] = ((const float4*)src)[min(base + lane + u * 64, end4 - 1)];
+#pragma unroll
+    for (int u = 0; u < kRowU; ++u) {
+      const float gm = fmaxf(fmaxf(x4[u].x, x4[u].y), fmaxf(x4[u].z, x4[u].w));
+      g[u] = base + lane + u * 64 < end4 ? gm : kNegInf;
+      if (g[u] > kNegInf) fold(gm, __expf(x4[u].x - gm) + __expf(x4[u].y - gm) + __expf(x4[u].z - gm) + __expf(x4[u].w - gm));
+    }
+    renew_bound();                                               // counts this round's entries as well
+    make_room();
+#pragma unroll
+    for (int u = 0; u < kRowU; ++u) {
+      const bool any = g[u] > kNegInf && g[u] >= bound;
+      if (__ballot(any) == 0ull) continue;
+      const int i4 = base + lane + u * 64;
+      const float x[4] = {x4[u].x, x4[u].y, x4[u].z, x4[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) append(any && x[e] > kNegInf && x[e] >= bound, x[e], 4 * i4 + e);
+    }
+  }
+  for (int base = 4 * n4 + wave * 64 * kRowU; base < V; base += 4 * 64 * kRowU) {   // what 16-byte loads do not cover
+    float x[kRowU];
+#pragma unroll
+    for (int u = 0; u < kRowU; ++u) {
+      const int i = base + lane + u * 64;
+      x[u] = i < V ? src[i] : kNegInf;
+      if (x[u] > kNegInf) fold(x[u], 1.f);
+    }
     renew_bound();
+    make_room();
+#pragma unroll
+    for (int u = 0; u < kRowU; ++u) append(x[u] > kNegInf && x[u] >= bound, x[u], base + lane + u * 64);
   }
-  for (int i = 4 * n4 + lane; i < V; i += 64) {
-    const float x = src[i];
-    if (x > -__builtin_inff()) fold(x, 1.f);
-    if (x > t.v[CAP - 1]) t.template insert<true>(Cand{x, i});
-  }
-  // logsumexp of the whole row
+  // logsumexp of this wavefront's part, then of the whole row
   float mw = m;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mw = fmaxf(mw, __shfl_xor(mw, o));
-  float zw = mw > -__builtin_inff() ? z * __expf(m - mw) : 0.f;
+  float zw = mw > kNegInf ? z * __expf(m - mw) : 0.f;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) zw += __shfl_xor(zw, o);
-  const float lse = mw + __logf(zw);
+  if (lane == 0) { part_m[wave] = mw; part_z[wave] = zw; cnt[wave] = count; }
+  __syncthreads();
+  if (wave != 0) return;
+  const float mr = fmaxf(fmaxf(part_m[0], part_m[1]), fmaxf(part_m[2], part_m[3]));
+  float zr = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) zr += part_m[w] > kNegInf ? part_z[w] * __expf(part_m[w] - mr) : 0.f;
+  const float lse = mr + __logf(zr);
   const float sc = score[r];
-  wave_select(t, beam, [&](int k, const Cand& win) {
-    if (lane == 0) {
-      const bool found = win.i != 0x7fffffff;                    // fewer than `beam` usable labels in the row: the rest never wins
-      cand_val[(long)r * beam + k] = found ? sc + (win.v - lse) : -__builtin_inff();
-      cand_lab[(long)r * beam + k] = found ? win.i : 0;
-    }
-  });
+  // lane k keeps the k-th best and stores it at the end (a store inside the loop would be waited for by the next round's
+  // ordering of the LDS traffic: two microseconds per round)
+  Cand kept = {kNegInf, 0x7fffffff};
+  for (int k = 0; k < beam; ++k) {
+    const Cand win = pick_best(std::true_type{});
+    if (lane == k) kept = win;
+  }
+  if (lane < beam) {
+    const bool found = kept.i != 0x7fffffff;                     // fewer than `beam` usable labels in the row: the rest never wins
+    cand_val[(long)r * beam + lane] = found ? sc + (kept.v - lse) : kNegInf;
+    cand_lab[(long)r * beam + lane] = found ? kept.i : 0;
+  }
 }
 
 // The beam * beam survivors of sentence q = blockIdx.x, one wavefront: the best `beam`, by value and then by flat index
@@ -181,14 +286,14 @@ __global__ __launch_bounds__(64) void beam_merge_kernel(const float* __restrict_
     // a row with fewer than `beam` labels pads with (-inf, label 0): give the padding indices that cannot collide
     t.insert<false>(Cand{val, val == -__builtin_inff() ? 0x7ffffffe - c : flat});
   }
-  wave_select(t, beam, [&](int k, const Cand& win) {
-    if (lane == 0) {
-      const bool real = win.i < beam * V;
-      score_out[q * beam + k] = win.v;
-      src_out[q * beam + k] = real ? win.i / V : 0;
-      label_out[q * beam + k] = real ? win.i % V : 0;
-    }
-  });
+  Cand kept = {-__builtin_inff(), 0x7fffffff};
+  wave_select(t, beam, [&](int k, const Cand& win) { if (lane == k) kept = win; });
+  if (lane < beam) {
+    const bool real = kept.i < beam * V;
+    score_out[q * beam + lane] = kept.v;
+    src_out[q * beam + lane] = real ? kept.i / V : 0;
+    label_out[q * beam + lane] = real ? kept.i % V : 0;
+  }
 }
 
 // out[q * beam + k][0..width) = in[q * beam + src[q * beam + k]][0..width), elements of `esz` bytes copied as bytes pairs
@@ -237,11 +342,7 @@ int lstm_beam_query(int Q, int beam, int V, uint64_t* workspace_bytes) {
 // both kernels of a step; cand_val / cand_lab hold Q * beam * beam entries each
 static int beam_launch(int Q, int beam, int V, const float* logits, int64_t ld, const float* score_in, float* score_out, int32_t* src,
                        int32_t* label, float* cand_val, int* cand_lab, hipStream_t st) {
-  // a lane's list holds as many entries as the beam asks for (in the worst case all of the row's best lie in one lane)
-  if (beam <= 4) hipLaunchKernelGGL(beam_row_kernel<4>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
-  else if (beam <= 8) hipLaunchKernelGGL(beam_row_kernel<8>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
-  else if (beam <= 12) hipLaunchKernelGGL(beam_row_kernel<12>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
-  else hipLaunchKernelGGL(beam_row_kernel<16>, dim3(Q * beam), dim3(64), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
+  hipLaunchKernelGGL(beam_row_kernel, dim3(Q * beam), dim3(256), 0, st, logits, (long)ld, score_in, cand_val, cand_lab, V, beam);
   hipLaunchKernelGGL(beam_merge_kernel, dim3(Q), dim3(64), 0, st, cand_val, cand_lab, score_out, src, label, V, beam);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
   return LSTM_OK;
