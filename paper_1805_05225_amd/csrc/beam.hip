@@ -7,8 +7,9 @@
 //     trg[r] = W_trg[label[r]] + b_trg
 //
 // No candidate list of beam * V entries is ever sorted: a sentence's best `beam` candidates contain at most `beam` from one
-// row, so every row first picks its own best `beam` labels in one pass over its logits (beam_row_kernel, a wavefront per
-// row), and one wavefront per sentence merges the beam * beam survivors (beam_merge_kernel).  Nothing returns to the host.
+// row, so every row first picks its own best `beam` labels in one pass over its logits (beam_row_kernel, a work-group of
+// four wavefronts per row), and one wavefront per sentence merges the beam * beam survivors (beam_merge_kernel).  Nothing
+// returns to the host.
 #include <algorithm>
 #include <mutex>
 #include <type_traits>
@@ -132,7 +133,11 @@ __global__ __launch_bounds__(256) void beam_row_kernel(const float* __restrict__
   __shared__ float bv[4 * kRowCap];
   __shared__ int bi[4 * kRowCap];
   __shared__ int cnt[4];
-  __shared__ float part_m[4], part_z[4];
+  __shared__ float part_m[4], part_z[4], part_b[4];
+  __shared__ float fv[64];                                      // the row's finalists (see the end)
+  __shared__ int fi[64];
+  __shared__ int fcount;
+  if (threadIdx.x == 0) fcount = 0;
   const int r = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float* src = logits + (long)r * ld;
   const float kNegInf = -__builtin_inff();
@@ -249,7 +254,24 @@ __global__ __launch_bounds__(256) void beam_row_kernel(const float* __restrict__
   float zw = mw > kNegInf ? z * __expf(m - mw) : 0.f;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) zw += __shfl_xor(zw, o);
-  if (lane == 0) { part_m[wave] = mw; part_z[wave] = zw; cnt[wave] = count; }
+  if (lane == 0) { part_m[wave] = mw; part_z[wave] = zw; cnt[wave] = count; part_b[wave] = bound; }
+  __syncthreads();
+  // Finalists: every one of the row's best `beam` reaches the largest of the four wavefronts' bounds (at least `beam`
+  // entries of that wavefront's quarter do).  Each wavefront copies its candidates at or above it to a common list of 64;
+  // if they fit - they nearly always do: a few dozen - the first wavefront ranks them in registers (a candidate's place
+  // is the number of better ones: no rounds, nothing through LDS), else it picks from the four buffers round by round.
+  const float top_bound = fmaxf(fmaxf(part_b[0], part_b[1]), fmaxf(part_b[2], part_b[3]));
+  for (int p0 = 0; p0 < count; p0 += 64) {
+    const int p = p0 + lane;
+    const bool keep = p < count && wbv[p] >= top_bound;
+    const unsigned long long mask = __ballot(keep);
+    if (mask == 0ull) continue;
+    int base = 0;
+    if (lane == 0) base = atomicAdd(&fcount, (int)__popcll(mask));
+    base = __builtin_amdgcn_readfirstlane(base);
+    const int pos = base + (int)__popcll(mask & ((1ull << lane) - 1ull));
+    if (keep && pos < 64) { fv[pos] = wbv[p]; fi[pos] = wbi[p]; }
+  }
   __syncthreads();
   if (wave != 0) return;
   const float mr = fmaxf(fmaxf(part_m[0], part_m[1]), fmaxf(part_m[2], part_m[3]));
@@ -258,15 +280,32 @@ __global__ __launch_bounds__(256) void beam_row_kernel(const float* __restrict__
   for (int w = 0; w < 4; ++w) zr += part_m[w] > kNegInf ? part_z[w] * __expf(part_m[w] - mr) : 0.f;
   const float lse = mr + __logf(zr);
   const float sc = score[r];
-  // lane k keeps the k-th best and stores it at the end (a store inside the loop would be waited for by the next round's
-  // ordering of the LDS traffic: two microseconds per round)
+  const int total = fcount;
+  if (total <= 64) {
+    const Cand mine = {lane < total ? fv[lane] : kNegInf, lane < total ? fi[lane] : 0x7fffffff};
+    int place = 0;
+    for (int j = 0; j < total; ++j) {
+      const Cand other = {__int_as_float(__builtin_amdgcn_readlane(__float_as_int(mine.v), j)), __builtin_amdgcn_readlane(mine.i, j)};
+      place += better(other, mine) ? 1 : 0;
+    }
+    if (lane < total && place < beam) {
+      cand_val[(long)r * beam + place] = sc + (mine.v - lse);
+      cand_lab[(long)r * beam + place] = mine.i;
+    }
+    if (lane >= total && lane < beam) {                          // fewer than `beam` usable labels in the row: the rest never wins
+      cand_val[(long)r * beam + lane] = kNegInf;
+      cand_lab[(long)r * beam + lane] = 0;
+    }
+    return;
+  }
+  // lane k keeps the k-th best and stores it at the end
   Cand kept = {kNegInf, 0x7fffffff};
   for (int k = 0; k < beam; ++k) {
     const Cand win = pick_best(std::true_type{});
     if (lane == k) kept = win;
   }
   if (lane < beam) {
-    const bool found = kept.i != 0x7fffffff;                     // fewer than `beam` usable labels in the row: the rest never wins
+    const bool found = kept.i != 0x7fffffff;
     cand_val[(long)r * beam + lane] = found ? sc + (kept.v - lse) : kNegInf;
     cand_lab[(long)r * beam + lane] = found ? kept.i : 0;
   }

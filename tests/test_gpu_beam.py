@@ -90,6 +90,51 @@ def test_beam_step_exact_ties_and_first_step():
     assert src[0].tolist() == [0, 0, 1, 1] and lab[0].tolist() == [2, 5, 2, 5]
 
 
+def test_beam_step_rows_that_stress_the_candidate_buffer():
+    """Rows shaped against the row kernel's filter (a running bound, a candidate buffer that is cut down when it runs short
+    of room, a list of finalists with a fall-back when they do not fit): rising rows let every entry through, constant rows
+    make every entry a finalist and leave the order to the tie rule, rows with a handful of usable labels offer fewer
+    candidates than the beam asks for."""
+    beam, V = 12, 20000
+    rng = np.random.default_rng(21)
+    ramp = (np.arange(V, dtype=np.float32) * np.float32(1e-3))
+    logits = np.stack([ramp,                                   # rising: the best are the last labels
+                       ramp[::-1],                             # falling: the best come first
+                       np.roll(ramp, 7777),                    # the maximum in the middle of a wavefront's quarter
+                       (rng.standard_normal(V) * 3).astype(np.float32)] * 3).astype(np.float32)
+    score = (-rng.uniform(0, 2, (1, beam))).astype(np.float32)
+    exact = _validate(logits, score, beam, _run(logits, score))
+    assert exact >= beam - 2
+    # constant rows: equal candidates inside a hypothesis, the earlier label first; hypotheses apart by their scores
+    logits = np.zeros((beam, V), dtype=np.float32)
+    score = (-0.25 * np.arange(beam, dtype=np.float32))[None, ::-1].copy()                 # the last hypothesis is the best
+    sc, src, lab = _run(logits, score)
+    osc, osrc, olab = D.beam_step(logits.astype(np.float64), score.astype(np.float64), beam)
+    assert np.array_equal(src, osrc) and np.array_equal(lab, olab)
+    assert src[0].tolist() == [beam - 1] * beam and lab[0].tolist() == list(range(beam))
+    np.testing.assert_allclose(sc, osc, rtol=1e-6)
+    # two plateaus: 40 labels share the maximum, spread over the row (more finalists than the wavefront-wide list holds when
+    # every hypothesis has them, and ties across the quarters of a row)
+    logits = np.full((beam, V), -3.0, dtype=np.float32)
+    top = np.sort(rng.choice(V, 40, replace=False))
+    logits[:, top] = 2.0
+    sc, src, lab = _run(logits, score)
+    osc, osrc, olab = D.beam_step(logits.astype(np.float64), score.astype(np.float64), beam)
+    assert np.array_equal(src, osrc) and np.array_equal(lab, olab)
+    assert lab[0].tolist() == top[:beam].tolist()
+    # rows with fewer usable labels than the beam: -inf everywhere else
+    beam2, V2 = 4, 3000
+    logits = np.full((beam2, V2), -np.inf, dtype=np.float32)
+    logits[0, [5, 2999]] = [1.0, 0.5]
+    logits[1, [0, 1500, 17]] = [0.25, 0.75, -1.0]
+    logits[2, 77] = 0.0
+    logits[3, :] = (rng.standard_normal(V2)).astype(np.float32)
+    score = np.array([[0.0, -0.5, -1.0, -30.0]], dtype=np.float32)
+    with np.errstate(all="ignore"):
+        exact = _validate(logits, score, beam2, _run(logits, score))
+    assert exact >= 3
+
+
 def test_beam_step_strided_logits():
     rng = np.random.default_rng(9)
     Q, beam, V = 3, 5, 1000
