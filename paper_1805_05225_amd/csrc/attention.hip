@@ -323,13 +323,12 @@ int lstm_attention_step(const lstm_att_desc* d, const void* enc, const void* enc
   if (linear_rows(s, ld_s, W_s, d->n, b_s, s_tr, B, d->A, d->n, parts, ks, st) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
   hipLaunchKernelGGL(att_energy_kernel, dim3((d->S + kJB - 1) / kJB, d->Q), dim3(256), 0, st, (const uint16_t*)enc_ctx, s_tr, accum_in, w_fb,
                      b_fb, v, b_e, src_lens, e, d->S, d->Q, d->beam, d->A);
-  static bool attr_set = false;                                  // S = 1024 needs 64 KiB of dynamic LDS beside the static arrays
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)att_context_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxS * kMaxBeam * 4) != hipSuccess) {
-      (void)hipGetLastError();
-      return LSTM_ERR_HIP;
-    }
-    attr_set = true;
+  static std::atomic<unsigned long long> attr_set{0};            // S = 1024 needs 64 KiB of dynamic LDS beside the static arrays
+  if (once_per_device(attr_set, [] {
+        return hipFuncSetAttribute((const void*)att_context_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxS * kMaxBeam * 4);
+      }) != hipSuccess) {
+    (void)hipGetLastError();
+    return LSTM_ERR_HIP;
   }
   hipLaunchKernelGGL(att_context_kernel, dim3((d->E / 2 + 63) / 64, d->Q), dim3(256), (size_t)d->S * kMaxBeam * 4, st, (const uint16_t*)enc,
                      e, accum_in, src_lens, a, accum_out, (uint16_t*)att, (long)ld_att, d->S, d->Q, d->beam, d->E);

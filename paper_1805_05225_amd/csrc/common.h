@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace lstm {
 
@@ -272,5 +273,20 @@ hipError_t launch_cell_step(const float* z, long part, int nparts, const float* 
                             float* c_out, void* y, long ldy, float* cs, const int* lens, int B, int n, int ndir, hipStream_t s);
 
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+
+// Host-side set-up that HIP keeps per device (function attributes, what a device is and holds): done once on every
+// device the library is used on, whichever thread gets there first.  `done` holds one bit per device ordinal (ordinals
+// 64 apart share a bit: the set-up is then simply repeated); the set-up must be idempotent, since two threads may both run it.
+template <typename F>
+hipError_t once_per_device(std::atomic<unsigned long long>& done, F&& setup) {
+  int dev = 0;
+  const hipError_t eg = hipGetDevice(&dev);
+  if (eg != hipSuccess) return eg;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  const hipError_t e = setup();
+  if (e == hipSuccess && dev < 64) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 }  // namespace lstm

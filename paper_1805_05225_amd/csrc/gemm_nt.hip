@@ -778,12 +778,11 @@ hipError_t launch_gemm_tn(const GemmArgs& g, hipStream_t s) {
   const int sups = cdiv(cdiv(g.M, kT), kSupM) * cdiv(cdiv(g.N, kT), kSupN);
   a.blocked = sups >= 32 ? 1 : 0;
   const int tiles = a.blocked ? cdiv(sups, 8) * 8 * kSupM * kSupN : cdiv(g.M, kT) * cdiv(g.N, kT);
-  static bool attr_set = false;
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute((const void*)gemm_tn8_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> attr_set{0};
+  const hipError_t ea = once_per_device(attr_set, [] {
+    return hipFuncSetAttribute((const void*)gemm_tn8_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
+  });
+  if (ea != hipSuccess) return ea;
   hipLaunchKernelGGL(gemm_tn8_f32_kernel, dim3(tiles, g.nz * a.ksplit), dim3(512), kDlLds, s, a);
   return sum_parts(a, s);
 }
@@ -809,15 +808,16 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   // operands go straight into LDS; K any multiple of 8 (a device-resident K is a multiple of 64 by contract, and so
   // must then be the host's bound on it)
   if (dl) {
-    static bool dl_attr_set = false;
-    if (!dl_attr_set) {
+    static std::atomic<unsigned long long> dl_attr_set{0};
+    const hipError_t ea = once_per_device(dl_attr_set, [] {
       for (const void* k : {(const void*)gemm_dl8_f32_kernel<false>, (const void*)gemm_dl8_f32_kernel<true>,
                             (const void*)gemm_dl8_bf16_kernel<false>, (const void*)gemm_dl8_bf16_kernel<true>}) {
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kDlLds);
         if (e != hipSuccess) return e;
       }
-      dl_attr_set = true;
-    }
+      return hipSuccess;
+    });
+    if (ea != hipSuccess) return ea;
     const dim3 grid(tiles, g.nz * a.ksplit);
     const bool ragged = g.K % kKB != 0, bf = g.out_bf16 && !parts_bf16;
     if (bf && ragged) hipLaunchKernelGGL(gemm_dl8_bf16_kernel<true>, grid, dim3(512), kDlLds, s, a);

@@ -342,12 +342,11 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyArgs g) {
 template <int BI, int BJ, bool CELL>
 hipError_t launch_as(const SkinnyArgs& a, hipStream_t s) {
   typedef Geo<BI, BJ> G;
-  static bool attr_set = false;
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<BI, BJ, CELL>, hipFuncAttributeMaxDynamicSharedMemorySize, G::kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> attr_set{0};
+  const hipError_t ea = once_per_device(attr_set, [] {
+    return hipFuncSetAttribute((const void*)skinny_kernel<BI, BJ, CELL>, hipFuncAttributeMaxDynamicSharedMemorySize, G::kLds);
+  });
+  if (ea != hipSuccess) return ea;
   const dim3 grid(grid_for(cdiv(a.M, G::kTM), cdiv(a.N, G::kTN)), 1, a.nz);
   hipLaunchKernelGGL((skinny_kernel<BI, BJ, CELL>), grid, dim3(512), G::kLds, s, a);
   return hipGetLastError();

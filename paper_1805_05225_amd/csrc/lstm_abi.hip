@@ -141,15 +141,16 @@ int widest(long ld_elems, long s1, long s2, size_t esz, int cap) {
   return v;
 }
 
-int check_device() {
-  static int cached = 1;   // 1 = unknown, 0 = ok, <0 = error
-  if (cached != 1) return cached;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
-  hipDeviceProp_t prop;
-  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
-  cached = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 0 : LSTM_ERR_HIP;
-  return cached;
+int check_device() {                 // is the current device one this library is built for?  (looked up once per device)
+  static std::atomic<unsigned long long> known_good{0};
+  const hipError_t e = once_per_device(known_good, [] {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorInvalidDevice;
+    return strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? hipSuccess : hipErrorInvalidDevice;
+  });
+  if (e != hipSuccess) { (void)hipGetLastError(); return LSTM_ERR_HIP; }
+  return 0;
 }
 
 // ---- optional phase timing (hipEvents on the caller's stream) -----------------------------------

@@ -1766,36 +1766,31 @@ __global__ __launch_bounds__(256) void h0_term_kernel(const float* h0, const bf1
 }
 
 std::mutex g_capacity_mu;
-std::map<const void*, int> g_capacity;    // kernel -> work-groups of it the current device holds at once
+std::map<std::pair<int, const void*>, int> g_capacity;    // (device, kernel) -> work-groups of the kernel that device holds at once
 
-// Can `grid` be resident all at once (the condition of a cooperative launch)?
+// How many work-groups of `kernel` the current device holds at once (0 if that cannot be found out).
 template <typename K>
-bool fits_device(K kernel, dim3 grid) {
-  static std::mutex mu;
-  static std::map<const void*, int> cache;   // kernel -> work-groups of it the current device can hold at once
-  std::lock_guard<std::mutex> lock(mu);
-  auto it = cache.find((const void*)kernel);
-  if (it == cache.end()) {
-    int dev = 0, per_cu = 0;
+int capacity(K kernel) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return 0; }
+  std::lock_guard<std::mutex> lock(g_capacity_mu);
+  const auto key = std::make_pair(dev, (const void*)kernel);
+  auto it = g_capacity.find(key);
+  if (it == g_capacity.end()) {
+    int per_cu = 0;
     hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess ||
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess) {
       (void)hipGetLastError();
-      return false;
+      return 0;
     }
-    it = cache.emplace((const void*)kernel, per_cu * prop.multiProcessorCount).first;
+    it = g_capacity.emplace(key, per_cu * prop.multiProcessorCount).first;
   }
-  { std::lock_guard<std::mutex> l2(g_capacity_mu); g_capacity[(const void*)kernel] = it->second; }
-  return (long)grid.x * grid.y * grid.z <= it->second;
+  return it->second;
 }
-int capacity_of(const void* kernel) {
-  std::lock_guard<std::mutex> lock(g_capacity_mu);
-  auto it = g_capacity.find(kernel);
-  return it == g_capacity.end() ? 0 : it->second;
-}
-// How many work-groups of `kernel` the device holds at once (0 if that cannot be found out).
+// Can `grid` be resident all at once (the condition of a cooperative launch)?
 template <typename K>
-int capacity(K kernel) { return fits_device(kernel, dim3(1, 1, 1)) ? capacity_of((const void*)kernel) : 0; }
+bool fits_device(K kernel, dim3 grid) { return (long)grid.x * grid.y * grid.z <= capacity(kernel); }
 
 // Cooperative launches over the batch in slabs of whole 16-row tiles.  A work-group owns `rows_per_y` rows (16 or 8),
 // so one row tile takes grid.x * (16 / rows_per_y) * ndir work-groups; as many row tiles as the device can hold at
