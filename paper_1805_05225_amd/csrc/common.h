@@ -55,11 +55,11 @@ struct GemmArgs {
   const int* lens; int Bt; int T;
   bool a_kcontig, b_kcontig;
   bool in_bf16, out_bf16;
-  // Fast kernel only (callers check gemm_nt_ok first and leave these zero otherwise):
-  const int* a_rows; const int* c_rows;   // logical row r of A / C lives at physical row a_rows[r] / c_rows[r]
+  // Row maps (the fast kernels and the generic one; not the few-rows kernel, and not together with `parts` or ksplit there):
+  const int* a_rows; const int* c_rows;   // k-contiguous A: logical row r of A / C lives at physical row a_rows[r] / c_rows[r]
   int a_phys_rows;                        // rows of A in memory when a_rows is given
   const int* m_dev; const int* k_dev;     // M / K read from device memory (capped by M / K above, which size the grid)
-  const int* k_rows; int k_phys_rows;     // k-major kernel only: k -> row of A and of B in memory; rows each holds in memory
+  const int* k_rows; int k_phys_rows;     // both operands k-major: k -> row of A and of B in memory; rows each holds in memory
   int ksplit;                             // > 1: K cut into that many ranges whose parts are ADDED to C atomically
                                           // (float C, nseg == 1; C must hold zeros or the value to add to) ...
   float* parts;                           // ... or, if not NULL (nz * ksplit * M * ldc floats, no c_rows): every range stores

@@ -46,7 +46,7 @@ template <> struct Mma<float> {
 // 128 rows x 8 chunks of 16 bytes; thread handles chunks tid + 256*i, i = 0..3
 template <typename T>
 __device__ __forceinline__ void fetch_kcontig(uint32_t (&st)[16], const char* base, long ld, int rows, int row0,
-                                              int K, int k0, int vec, int tid) {
+                                              int K, int k0, int vec, int tid, const int (&prow)[4]) {
   constexpr int ES = sizeof(T), EPC = 16 / ES;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -54,7 +54,7 @@ __device__ __forceinline__ void fetch_kcontig(uint32_t (&st)[16], const char* ba
     int row = row0 + (c >> 3), k = k0 + (c & 7) * EPC;
     uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
     if (row < rows && k < K) {
-      const char* p = base + ((long)row * ld + k) * ES;
+      const char* p = base + ((long)prow[i] * ld + k) * ES;                       // prow[i]: where logical row `row` lies in memory
       if (vec >= 16 && k + EPC <= K) {
         uint4 v = *(const uint4*)p;
         w0 = v.x; w1 = v.y; w2 = v.z; w3 = v.w;
@@ -96,11 +96,11 @@ __device__ __forceinline__ void commit_kcontig(const uint32_t (&st)[16], char* l
 // bf16: micro-tile of 8 k x 2 m (eight 4-byte loads), two micro-tiles per thread
 template <bool MASK>
 __device__ __forceinline__ void fetch_mcontig_bf16(uint32_t (&st)[16], const char* base, long ld, int cols, int col0,
-                                                   int K, int k0, int vec, int tid, const int* lens, int Bt, int T) {
+                                                   int K, int k0, int vec, int tid, const int* lens, int Bt, int T, const int* krows) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     int c = tid + kThreads * i;
-    int m = col0 + 2 * (c & 63), kb = k0 + (c >> 6) * 8;
+    int m = col0 + 2 * (c & 63), kb = __builtin_amdgcn_readfirstlane(k0 + (c >> 6) * 8);   // (the same in every lane of a wavefront)
     // The frame mask is fetched independently of the data and applied afterwards, so the data loads
     // never wait for the seq_lens loads.
     uint32_t keep = 0xffu;
@@ -118,7 +118,7 @@ __device__ __forceinline__ void fetch_mcontig_bf16(uint32_t (&st)[16], const cha
       int k = kb + kk;
       uint32_t w = 0;
       if (k < K && m < cols) {
-        const char* p = base + ((long)k * ld + m) * 2;
+        const char* p = base + ((long)(krows ? krows[k] : k) * ld + m) * 2;   // k is the same in every lane: a scalar look-up
         if (vec >= 4 && m + 1 < cols) w = *(const uint32_t*)p;
         else {
           w = *(const uint16_t*)p;
@@ -148,11 +148,11 @@ __device__ __forceinline__ void commit_mcontig_bf16(const uint32_t (&st)[16], ch
 // float: micro-tile of 4 k x 1 m, four per thread
 template <bool MASK>
 __device__ __forceinline__ void fetch_mcontig_f32(uint32_t (&st)[16], const char* base, long ld, int cols, int col0,
-                                                  int K, int k0, int tid, const int* lens, int Bt, int T) {
+                                                  int K, int k0, int tid, const int* lens, int Bt, int T, const int* krows) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     int c = tid + kThreads * i;
-    int m = col0 + (c & 127), kb = k0 + (c >> 7) * 4;
+    int m = col0 + (c & 127), kb = __builtin_amdgcn_readfirstlane(k0 + (c >> 7) * 4);     // (the same in every lane of a wavefront)
     uint32_t keep = 0xfu;
     if (MASK) {
       int ft = kb / Bt, fb = kb - ft * Bt;
@@ -166,7 +166,7 @@ __device__ __forceinline__ void fetch_mcontig_f32(uint32_t (&st)[16], const char
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       int k = kb + kk;
-      uint32_t w = (k < K && m < cols) ? *(const uint32_t*)(base + ((long)k * ld + m) * 4) : 0u;
+      uint32_t w = (k < K && m < cols) ? *(const uint32_t*)(base + ((long)(krows ? krows[k] : k) * ld + m) * 4) : 0u;   // scalar look-up
       st[4 * i + kk] = ((keep >> kk) & 1u) ? w : 0u;
     }
   }
@@ -182,15 +182,18 @@ __device__ __forceinline__ void commit_mcontig_f32(const uint32_t (&st)[16], cha
 template <typename T, bool AK, bool BK, bool MASK>
 struct Stager {
   static constexpr int EPT = kRowBytes / (int)sizeof(T);   // k per tile: 64 bf16 / 32 float
-  __device__ static void fetchA(uint32_t (&st)[16], const GemmArgs& g, const char* A, int m0, int k0, int tid) {
-    if constexpr (AK) fetch_kcontig<T>(st, A, g.lda, g.M, m0, g.K, k0, g.vecA, tid);
-    else if constexpr (sizeof(T) == 2) fetch_mcontig_bf16<MASK>(st, A, g.lda, g.M, m0, g.K, k0, g.vecA, tid, g.lens, g.Bt, g.T);
-    else fetch_mcontig_f32<MASK>(st, A, g.lda, g.M, m0, g.K, k0, tid, g.lens, g.Bt, g.T);
+  // M, K: the extents in force (the arguments', or what the device-side counts cut them down to)
+  __device__ static void fetchA(uint32_t (&st)[16], const GemmArgs& g, const char* A, int M, int K, int m0, int k0, int tid,
+                                const int (&prow)[4]) {
+    if constexpr (AK) fetch_kcontig<T>(st, A, g.lda, M, m0, K, k0, g.vecA, tid, prow);
+    else if constexpr (sizeof(T) == 2) fetch_mcontig_bf16<MASK>(st, A, g.lda, M, m0, K, k0, g.vecA, tid, g.lens, g.Bt, g.T, g.k_rows);
+    else fetch_mcontig_f32<MASK>(st, A, g.lda, M, m0, K, k0, tid, g.lens, g.Bt, g.T, g.k_rows);
   }
-  __device__ static void fetchB(uint32_t (&st)[16], const GemmArgs& g, const char* B, int n0, int k0, int tid) {
-    if constexpr (BK) fetch_kcontig<T>(st, B, g.ldb, g.N, n0, g.K, k0, g.vecB, tid);
-    else if constexpr (sizeof(T) == 2) fetch_mcontig_bf16<false>(st, B, g.ldb, g.N, n0, g.K, k0, g.vecB, tid, nullptr, 1, 0);
-    else fetch_mcontig_f32<false>(st, B, g.ldb, g.N, n0, g.K, k0, tid, nullptr, 1, 0);
+  __device__ static void fetchB(uint32_t (&st)[16], const GemmArgs& g, const char* B, int K, int n0, int k0, int tid,
+                                const int (&prow)[4]) {
+    if constexpr (BK) fetch_kcontig<T>(st, B, g.ldb, g.N, n0, K, k0, g.vecB, tid, prow);
+    else if constexpr (sizeof(T) == 2) fetch_mcontig_bf16<false>(st, B, g.ldb, g.N, n0, K, k0, g.vecB, tid, nullptr, 1, 0, AK ? nullptr : g.k_rows);
+    else fetch_mcontig_f32<false>(st, B, g.ldb, g.N, n0, K, k0, tid, nullptr, 1, 0, AK ? nullptr : g.k_rows);
   }
   __device__ static void commitA(const uint32_t (&st)[16], char* lds, int tid) {
     if constexpr (AK) commit_kcontig(st, lds, tid);
@@ -221,7 +224,16 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs g) {
   const int rel = bid - band * 8 * tiles_m;
   const int tn = band * 8 + rel % width, tm = rel / width;
   const int m0 = tm * kBM, n0 = tn * kBN;
-  const int z = blockIdx.y;
+  // blockIdx.y = problem z and, with ksplit > 1 (float C holding zeros or the value to add to), the range of the K axis
+  // that this work-group multiplies; the ranges' parts meet in C by atomic adds
+  const int ks = g.ksplit > 1 ? g.ksplit : 1;
+  const int z = blockIdx.y / ks, range = blockIdx.y - z * ks;
+  // Row maps and device-side extents (the frames that are real, numbered on the device): logical row r of a k-contiguous A
+  // and of C is row a_rows[r] / c_rows[r] in memory, M is cut down to *m_dev; with both operands m-contiguous, row k of
+  // the K axis is row k_rows[k] of A and of B, K cut down to *k_dev.
+  const int M = g.m_dev ? min(g.M, *g.m_dev) : g.M;
+  const int K = g.k_dev ? min(g.K, *g.k_dev) : g.K;
+  if (m0 >= M) return;
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -231,25 +243,34 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int ktiles = (g.K + S::EPT - 1) / S::EPT;
+  // where the rows this thread stages lie in memory (k-contiguous operands: the same rows in every stage)
+  int arow[4], brow[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ra = m0 + ((tid + kThreads * i) >> 3);
+    arow[i] = (AK && g.a_rows && ra < M) ? g.a_rows[ra] : ra;
+    brow[i] = n0 + ((tid + kThreads * i) >> 3);
+  }
+  const int ktiles = (K + S::EPT - 1) / S::EPT;
   const int total = ktiles * g.nseg;
   uint32_t sa[16], sb[16];
   auto fetch = [&](int it) {
     int seg = it / ktiles, kt = it - seg * ktiles;
     const char* A = (const char*)g.A + (g.sAz * z + g.sAseg * seg) * (long)sizeof(T);
     const char* B = (const char*)g.B + (g.sBz * z + g.sBseg * seg) * (long)sizeof(T);
-    S::fetchA(sa, g, A, m0, kt * S::EPT, tid);
-    S::fetchB(sb, g, B, n0, kt * S::EPT, tid);
+    S::fetchA(sa, g, A, M, K, m0, kt * S::EPT, tid, arow);
+    S::fetchB(sb, g, B, K, n0, kt * S::EPT, tid, brow);
   };
-  if (total > 0) {
-    fetch(0);
+  const int it_begin = (int)((long)total * range / ks), it_end = (int)((long)total * (range + 1) / ks);
+  if (it_end > it_begin) {
+    fetch(it_begin);
     S::commitA(sa, lds, tid);
     S::commitB(sb, lds + kTileBytes, tid);
   }
   __syncthreads();
-  for (int it = 0; it < total; ++it) {
-    const int cur = it & 1;
-    if (it + 1 < total) fetch(it + 1);
+  for (int it = it_begin; it < it_end; ++it) {
+    const int cur = (it - it_begin) & 1;
+    if (it + 1 < it_end) fetch(it + 1);
     const char* As = lds + cur * 2 * kTileBytes + (wm * 64 + r) * kLdsStride + gq * 16;
     const char* Bs = lds + cur * 2 * kTileBytes + kTileBytes + (wn * 64 + r) * kLdsStride + gq * 16;
 #pragma unroll
@@ -261,7 +282,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs g) {
       acc[1][0] = Mma<T>::run(a1, b0, acc[1][0]);
       acc[1][1] = Mma<T>::run(a1, b1, acc[1][1]);
     }
-    if (it + 1 < total) {
+    if (it + 1 < it_end) {
       S::commitA(sa, lds + (cur ^ 1) * 2 * kTileBytes, tid);
       S::commitB(sb, lds + (cur ^ 1) * 2 * kTileBytes + kTileBytes, tid);
     }
@@ -275,18 +296,21 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs g) {
   for (int j = 0; j < 2; ++j) {
     const int col = n0 + wn * 64 + j * 32 + r;
     if (col >= g.N) continue;
-    const float bv = bias ? bias[col] : 0.f;
+    const float bv = (bias && range == 0) ? bias[col] : 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-        if (row < g.M) {
+        if (row < M) {
           float val = acc[i][j][v] + bv;
-          long off = (long)row * g.ldc + col;
+          long off = (long)(g.c_rows ? g.c_rows[row] : row) * g.ldc + col;
           if constexpr (sizeof(TC) == 4) {
-            if (g.accumulate) val += ((float*)C)[off];
-            ((float*)C)[off] = val;
+            if (ks > 1) unsafeAtomicAdd((float*)C + off, val);
+            else {
+              if (g.accumulate) val += ((float*)C)[off];
+              ((float*)C)[off] = val;
+            }
           } else {
             ((uint16_t*)C)[off] = f2bf_bits(val);
           }
@@ -298,7 +322,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs g) {
 template <typename T, typename TC>
 hipError_t dispatch(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
-  dim3 grid(tiles_m * tiles_n, g.nz), block(kThreads);
+  if (g.ksplit > 1 && (sizeof(TC) != 4 || g.parts)) return hipErrorInvalidValue;   // ranges of K: float C, added atomically
+  dim3 grid(tiles_m * tiles_n, g.nz * (g.ksplit > 1 ? g.ksplit : 1)), block(kThreads);
   if (g.a_kcontig && !g.b_kcontig) hipLaunchKernelGGL((gemm_kernel<T, TC, true, false, false>), grid, block, 0, s, g);
   else if (g.a_kcontig && g.b_kcontig) hipLaunchKernelGGL((gemm_kernel<T, TC, true, true, false>), grid, block, 0, s, g);
   else if (!g.a_kcontig && !g.b_kcontig && g.lens) hipLaunchKernelGGL((gemm_kernel<T, TC, false, false, true>), grid, block, 0, s, g);

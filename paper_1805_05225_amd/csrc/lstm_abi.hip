@@ -108,9 +108,10 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ws_DZT = take(fg && !infer ? D * 4 * n * p->TBp * 2 : 0);
   p->ws_HT = take(fg && !infer ? D * n * p->TBp * 2 : 0);
   // frame map of the batch (which frames are real), used to leave padded frames out of the products
-  p->ws_cidx = take(fg ? (size_t)TB * 4 : 0);
-  p->ws_fidx = take(fg ? (size_t)p->TBp * 4 : 0);
-  p->ws_count = take(fg ? 256 : 0);
+  const bool fm = fg || !p->bf16;             // (float storage: the generic kernel takes the same row maps)
+  p->ws_cidx = take(fm ? (size_t)TB * 4 : 0);
+  p->ws_fidx = take(fm ? (size_t)p->TBp * 4 : 0);
+  p->ws_count = take(fm ? 256 : 0);
   p->ws_Wcat = take(p->single_step ? D * std::max((size_t)4 * n, wcell_rows(d->n)) * p->Kc * 2 : 0);
   p->ws_Acat = take(p->single_step ? D * B * p->Kc * 2 : 0);
   // weight-gradient products with few output tiles cut K into ranges whose partial results are summed afterwards
@@ -300,6 +301,11 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
           HIPCHK(launch_frame_map(seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), fidx, count, s));
           g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = g.M; g.m_dev = count;
         }
+      } else if (!p.bf16 && seq_lens) {  // float storage: the same selection of real frames, by the generic kernel
+        int* fidx = (int*)(ws + p.ws_fidx);
+        int* count = (int*)(ws + p.ws_count);
+        HIPCHK(launch_frame_map(seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), fidx, count, s));
+        g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = g.M; g.m_dev = count;
       }
       HIPCHK(launch_gemm(g, s));
     }
@@ -524,7 +530,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   int* fidx = (int*)(ws + p.ws_fidx);
   int* count = (int*)(ws + p.ws_count);
   const auto fits = [](long rows, long ld) { return rows * ld * 2 <= 0x7fffff00L; };
-  const bool compact = p.fast_gemm && seq_lens && TB > 0;
+  const bool compact = (p.fast_gemm || !p.bf16) && seq_lens && TB > 0;
   const bool compact_w = compact && fits(p.n_in, p.TBp) && fits(4L * p.n, p.TBp) && fits(p.n, p.TBp);
   if (compact) {
     Phase ph(LSTM_PHASE_PREP, 1, s);
@@ -540,11 +546,21 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.vecA = widest(g.lda, g.sAseg, 0, p.esz, 16);
     g.vecB = widest(g.ldb, g.sBseg, 0, p.esz, 16);
     Phase ph(LSTM_PHASE_GEMM_DX, 1, s);
-    if (compact && gemm_nt_ok(g)) {      // rows of padded frames: zero, and left out of the product
+    if (compact && (gemm_nt_ok(g) || !p.bf16)) {      // rows of padded frames: zero, and left out of the product
       HIPCHK(launch_fill_zero(dx, (size_t)TB * n_in * p.esz, s));
       g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = TB; g.m_dev = count;
     }
     if (p.ks_dx > 1 && gemm_nt_ok(g)) { g.ksplit = p.ks_dx; g.parts = (float*)(ws + p.ws_parts); }
+    if (!p.bf16) {
+      // float storage, generic kernel: rows = frames and n_in columns give few 128 x 128 tiles (config 2: 85 with real
+      // frames), so K = 4n per direction is cut into ranges that add their parts to the zero-filled dx atomically
+      const long tiles = (long)cdiv(TB, 128) * cdiv(p.n_in, 128), stages = (long)p.D * cdiv(4L * p.n, 32);
+      const int ks = (int)std::max(1L, std::min(std::min(384 / std::max(tiles, 1L), stages / 16), 8L));
+      if (ks > 1) {
+        if (!compact) HIPCHK(launch_fill_zero(dx, (size_t)TB * n_in * p.esz, s));
+        g.ksplit = ks;
+      }
+    }
     HIPCHK(launch_gemm(g, s));
   }
   // Weight gradients straight from the frame-major tensors (a row per frame in X, Hprev and DZ: both operands of
@@ -610,7 +626,8 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.lda = n_in; g.ldb = 4 * n; g.ldc = 4 * n;
     g.sAz = 0; g.sBz = (long)p.DZ_dir_elems; g.sCz = (long)(n_in * 4 * n); g.nz = p.D; g.nseg = 1;
     g.a_kcontig = false; g.b_kcontig = false; g.in_bf16 = p.bf16; g.out_bf16 = false; g.accumulate = acc;
-    g.lens = seq_lens; g.Bt = p.B; g.T = p.T;
+    if (compact) { g.k_rows = fidx; g.k_phys_rows = (int)TB; g.k_dev = count; }   // the real frames only
+    else { g.lens = seq_lens; g.Bt = p.B; g.T = p.T; }                              // (or every frame, padded ones read as zero)
     g.vecA = widest(g.lda, 0, 0, p.esz, 4);
     g.vecB = widest(g.ldb, g.sBz, 0, p.esz, 4);
     {
