@@ -21,13 +21,34 @@
 namespace lstm {
 namespace {
 
+// Work-group -> (unit tile, row block, direction).  The work-groups that share a unit tile read the same slice of the
+// packed W_h, 32 MB in all for two directions of n = 1000 in float: as much as the eight XCDs' L2 caches hold together,
+// so it streams in from the memory side in every step - once per row block if those work-groups sit on different
+// XCDs.  Work-groups are dealt to the XCDs round-robin in launch order, so the row blocks of one unit tile are given
+// numbers 8 apart: they run on one XCD at about the same time and the slice comes in once.
+struct StepCoord { int tile, rb, dir; bool live; };
+__device__ __forceinline__ StepCoord step_coord(int ntile, int nrb) {
+  const int ntile8 = (ntile + 7) / 8;
+  const int lin = blockIdx.x, t8 = lin & 7, r = lin >> 3;
+  StepCoord c;
+  c.rb = r % nrb;
+  const int g = r / nrb;
+  c.tile = (g % ntile8) * 8 + t8;
+  c.dir = g / ntile8;
+  c.live = c.tile < ntile;
+  return c;
+}
+inline int step_grid(int ntile, int nrb, int ndir) { return ndir * ((ntile + 7) / 8) * nrb * 8; }
+
 // ------------------------------------------------------------------------------------------------
 // forward step
 template <typename T>
 __global__ __launch_bounds__(256) void step_fwd_kernel(FwdArgs a) {
   __shared__ float red[4][32][33];
-  const FwdDir& d = a.d[blockIdx.z];
-  const int tile = blockIdx.x, rb = blockIdx.y;
+  const StepCoord sc = step_coord((a.n + 7) / 8, (a.B + 31) / 32);
+  if (!sc.live) return;
+  const FwdDir& d = a.d[sc.dir];
+  const int tile = sc.tile, rb = sc.rb;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc;
 
@@ -95,8 +116,10 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(FwdArgs a) {
 template <typename T>
 __global__ __launch_bounds__(256) void step_bwd_kernel(BwdArgs a) {
   __shared__ float red[4][16][17];
-  const BwdDir& d = a.d[blockIdx.z];
-  const int tile = blockIdx.x, rt = blockIdx.y;
+  const StepCoord sc = step_coord((a.n + 15) / 16, (a.B + 15) / 16);
+  if (!sc.live) return;
+  const BwdDir& d = a.d[sc.dir];
+  const int tile = sc.tile, rt = sc.rb;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nkc = a.nkc, n = a.n;
 
@@ -254,13 +277,13 @@ __global__ void colsum_final_kernel(const float* part, float* db, int ncols, int
 }  // namespace
 
 hipError_t launch_step_fwd(const FwdArgs& a, bool bf16, hipStream_t s) {
-  dim3 grid(cdiv(a.n, 8), cdiv(a.B, 32), a.ndir), block(256);
+  dim3 grid(step_grid(cdiv(a.n, 8), cdiv(a.B, 32), a.ndir)), block(256);
   if (bf16) hipLaunchKernelGGL(step_fwd_kernel<bf16_t>, grid, block, 0, s, a);
   else hipLaunchKernelGGL(step_fwd_kernel<float>, grid, block, 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_step_bwd(const BwdArgs& a, bool bf16, hipStream_t s) {
-  dim3 grid(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir), block(256);
+  dim3 grid(step_grid(cdiv(a.n, 16), cdiv(a.B, 16), a.ndir)), block(256);
   if (bf16) hipLaunchKernelGGL(step_bwd_kernel<bf16_t>, grid, block, 0, s, a);
   else hipLaunchKernelGGL(step_bwd_kernel<float>, grid, block, 0, s, a);
   return hipGetLastError();
