@@ -180,6 +180,10 @@ struct PFwdArgs {
 };
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s);
 bool persist_fwd_fits(const PFwdArgs& a);     // would launch_persist_fwd launch anything on this device?
+// Float storage, zero initial hidden state: Wf is the per-step kernel's packed W_h (launch_pack_wh_fwd), ring0 / ring1 its
+// fragment-ordered h buffers (initialised here), y / hprev float; nkc = chunks of 16 k.
+hipError_t launch_persist_fwd_f32(const PFwdArgs& a, hipStream_t s);
+bool persist_fwd_f32_fits(const PFwdArgs& a);
 
 struct PBwdDir {
   const uint4* Wb;    // as launch_pack_wh_bwdp writes it

@@ -357,6 +357,42 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         return LSTM_ERR_HIP;
       }
     }
+    // float storage with a zero initial hidden state: one launch for the whole time loop as well (the kernel works on the
+    // per-step path's packed W_h and h buffers)
+    if (!done && !p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && !h0 && p.n % 8 == 0) {
+      PFwdArgs pa = {};
+      pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_f; pa.T = p.T; pa.ndir = p.D; pa.write_gates = infer ? 0 : 1;
+      pa.plain_launch = (desc->flags & LSTM_FLAG_PLAIN_LAUNCH) != 0;
+      pa.sync = (unsigned*)(ws + p.ws_sync); pa.spin_limit = kSpinLimit;
+      const size_t frag_dir = (size_t)p.nrt * p.nkc_f * 1024;
+      for (size_t d = 0; d < D; ++d) {
+        PFwdDir& fd = pa.d[d];
+        fd.Wf = (const uint4*)(ws + p.ws_Wf + d * (size_t)p.ntile_f * 2 * p.nkc_f * 1024);
+        fd.ring0 = (uint4*)(ws + p.ws_hfrag0 + d * frag_dir);
+        fd.ring1 = (uint4*)(ws + p.ws_hfrag1 + d * frag_dir);
+        fd.gates = gates + d * gates_stride;
+        fd.hstate = hstate + d * B * n;
+        fd.cstate = cstate + d * B * n;
+        fd.y = (char*)y + d * n * p.esz;
+        fd.ldy = (long)(D * n);
+        fd.cs = c ? (float*)c + d * T * B * n : nullptr;
+        fd.hprev = infer ? nullptr : rs + d * p.res_dir_stride + p.res_hprev;
+        fd.rev = bidir ? d == 1 : desc->direction == -1;
+      }
+      hipError_t e;
+      {
+        Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
+        e = launch_persist_fwd_f32(pa, s);
+      }
+      if (e == hipSuccess) done = true;
+      else if (e == hipErrorCooperativeLaunchTooLarge) {   // nothing of the loop ran, but the h buffers may have been initialised for it
+        (void)hipGetLastError();
+        if ((rc = pack_fwd(false))) return rc;
+      } else {
+        (void)hipGetLastError();
+        return LSTM_ERR_HIP;
+      }
+    }
     if (!done) {
     Phase ph(LSTM_PHASE_LOOP_FWD, (long)T, s);
     FwdArgs a = {};

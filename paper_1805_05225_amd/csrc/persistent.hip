@@ -1702,6 +1702,149 @@ __global__ __launch_bounds__(256) void persist_bwdp16_kernel(PBwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// forward, float storage.  The float MFMA (16x16x4) runs at a sixteenth of the bfloat16 rate, so the step is bound by the
+// matrix cores (6.7 us per step for 64 rows x 2 directions of n = 1000 on the whole device), not by the exchange, and
+// the decomposition is chosen for them: a work-group owns 8 units - 32 gate columns, two MFMA column tiles - for ALL
+// rows of a slab of 64 (four row tiles), so that W_h is held exactly once on the device (125 x 2 work-groups, 128
+// registers per lane: the packed slice of the per-step kernel, read once).  The K axis is split over the four wavefronts
+// (chunks of 16 k, wavefront w takes chunks w, w + 4, ...), their accumulators meet in LDS, and a thread updates two cells
+// (one row, two neighbouring units) and publishes them as ONE 8-byte unit of the ring: two float h values, the tag in
+// bit 30 of the second (|h| < 1 leaves the top exponent bit 0, as bit 14 of a bfloat16 value in the other kernels).
+// The ring is the per-step kernel's fragment-ordered h buffer [row tile][chunk][lane] x 16 bytes, a lane's 16 bytes
+// being two such units, so the reader of the other kernels applies unchanged.  The initial hidden state must be zero
+// (rows that have not started publish their carried state, which must stay below 2 in magnitude); callers with an
+// initial state take the per-step path.
+template <int NCH>                                         // chunks per wavefront at most: n <= 64 * NCH
+__global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
+  __shared__ float red[4][64][33];
+  const int tile = blockIdx.x, dir = blockIdx.z;
+  const PFwdDir d = a.d[dir];          // a copy: fields read through a reference are fetched again in every time step
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
+  const int nrt_here = min(4, (B + 15) / 16 - a.rt0);      // row tiles of this slab
+  unsigned* err = a.sync;
+  bool dead = false;
+
+  // W_h slice: chunk kc = wave + 4 it, column tile ct (the per-step kernel's packing)
+  uint4 w[NCH][2];
+#pragma unroll
+  for (int it = 0; it < NCH; ++it) {
+    const int kc = wave + 4 * it;
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+      w[it][ct] = kc < nkc ? d.Wf[((long)(tile * 2 + ct) * nkc + kc) * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+  }
+
+  // pointwise: row `row` of the slab, units 2 up and 2 up + 1 of the tile
+  const int row = tid >> 2, up = tid & 3;
+  const int b = a.rt0 * 16 + row, j = tile * 8 + 2 * up;
+  const bool active = b < B && j < n;                      // (n is a multiple of 8: both units exist or neither)
+  const bool in_slab = row < 16 * nrt_here;
+  float c[2] = {0.f, 0.f}, h[2] = {0.f, 0.f};
+  int L = 0;
+  if (active) {
+    c[0] = d.cstate[(long)b * n + j]; c[1] = d.cstate[(long)b * n + j + 1];
+    L = clamp_len(a.lens, b, T);
+  }
+  // where this thread's unit lies in a ring slot: chunk (tile*8 + 2 up) / 16, lane group ((tile*8 + 2 up) % 16) / 4,
+  // half (up & 1) of that lane's 16 bytes
+  constexpr unsigned kParked = 0x7ff00000u;
+  const int kpub = tile * 8 + 2 * up;
+  const unsigned pub_off = in_slab ? (unsigned)(((((long)(a.rt0 + (row >> 4)) * nkc + (kpub >> 4)) * 64 + ((kpub & 15) >> 2) * 16 + (row & 15)) * 2 + (up & 1)) * 8)
+                                   : kParked;
+  const unsigned ring_bytes = (unsigned)((B + 15) / 16) * nkc * 1024u;
+  const long fg = (long)B * 4 * n, fy = (long)B * d.ldy, fs = (long)B * n;     // elements per frame
+
+  for (int tau = 0; tau < T; ++tau) {
+    float (&red_)[4][64][33] = red;
+    const int t = d.rev ? T - 1 - tau : tau;
+    const bool valid = active && t < L;
+    // this step's x W_x + b: in flight while the products run
+    float zx[4][2];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float2 z2 = valid ? *(const float2*)(d.gates + t * fg + (long)b * 4 * n + q * n + j) : make_float2(0.f, 0.f);
+      zx[q][0] = z2.x; zx[q][1] = z2.y;
+    }
+    f32x4 acc[4][2];
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) acc[rt][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const unsigned tag = ll_fwd_tag((unsigned)tau) << 14, tagw = tag << 16;
+    const uint4* rin = (tau & 1) ? d.ring1 : d.ring0;
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+      if (rt >= nrt_here) break;                           // (the same in every work-group of the launch)
+      const RingReader rd = make_reader(rin + (long)(a.rt0 + rt) * nkc * 64, nkc, (n + 3) / 4, wave, lane, tag, err, a.spin_limit, 0);
+      auto use = [&](int it, const u32x4& x) __attribute__((always_inline)) {
+        const uint4 av = make_uint4(x[0], x[1] & ~kLLFwdTagBit, x[2], x[3] & ~kLLFwdTagBit);
+        acc[rt][0] = Mma16<float>::run(av, w[it][0], acc[rt][0]);
+        acc[rt][1] = Mma16<float>::run(av, w[it][1], acc[rt][1]);
+      };
+      // all loads of the row tile go out; whichever shows a stale tag is fetched again afterwards (bounded)
+      u32x4 x[NCH];
+#pragma unroll
+      for (int it = 0; it < NCH; ++it) x[it] = rd.load_it(it);
+      unsigned long long redo = 0ull;
+#pragma unroll
+      for (int it = 0; it < NCH; ++it) {
+        if (__builtin_amdgcn_ballot_w64(rd.tag_diff(x[it], it, tagw) != 0u) == 0ull) use(it, x[it]);
+        else redo |= 1ull << it;
+      }
+      if (redo) rd.fix_up_batch<NCH>(redo, dead, use);
+    }
+    // accumulator rows 4 * (lane / 16) + v of the row tile, column lane % 16 of the column tile
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red_[wave][rt * 16 + 4 * (lane >> 4) + v][ct * 16 + (lane & 15)] = acc[rt][ct][v];
+    __syncthreads();
+    float hprev[2] = {h[0], h[1]};
+    CellOut o[2] = {};
+    if (valid) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        float zh[4], zk[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = q * 8 + 2 * up + k;
+          zh[q] = red_[0][row][col] + red_[1][row][col] + red_[2][row][col] + red_[3][row][col];
+          zk[q] = zx[q][k];
+        }
+        o[k] = lstm_cell(zh, zk, c[k]);
+        c[k] = o[k].c; h[k] = o[k].h;
+      }
+    }
+    __syncthreads();                  // (the next step's accumulators may be written: a step is 7 us, the barrier nothing)
+    {                                 // the recurrence's critical store goes out first (16: agent scope, written through)
+      const u32x2 unit = {__float_as_uint(h[0]), __float_as_uint(h[1]) | (ll_fwd_tag((unsigned)tau + 1u) << 30)};
+      const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, ring_bytes, kBufFlags);
+      __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off, 0, 16);
+    }
+    if (active) {                     // layer outputs and what the backward pass needs
+      *(float2*)((float*)d.y + t * fy + (long)b * d.ldy + j) = valid ? make_float2(h[0], h[1]) : make_float2(0.f, 0.f);
+      if (d.cs) *(float2*)(d.cs + t * fs + (long)b * n + j) = make_float2(c[0], c[1]);
+      if (d.hprev) *(float2*)((float*)d.hprev + t * fs + (long)b * n + j) = make_float2(hprev[0], hprev[1]);
+      if (valid && a.write_gates) {
+        float* gp = d.gates + t * fg + (long)b * 4 * n + j;
+        *(float2*)gp = make_float2(o[0].gi, o[1].gi);
+        *(float2*)(gp + n) = make_float2(o[0].gf, o[1].gf);
+        *(float2*)(gp + 2 * n) = make_float2(o[0].gg, o[1].gg);
+        *(float2*)(gp + 3 * n) = make_float2(o[0].go, o[1].go);
+      }
+    }
+  }
+  if (active) {
+    *(float2*)(d.cstate + (long)b * n + j) = make_float2(c[0], c[1]);
+    *(float2*)(d.hstate + (long)b * n + j) = make_float2(h[0], h[1]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // packing for the ring layout
 // forward weights: chunk index = (((dir*ntile + tile)*4 + q)*nkc + kc)*64 + lane
 __global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nkc, long total) {
@@ -1890,6 +2033,52 @@ hipError_t launch_pack_wh_fwd_ll(const void* W, uint4* Wf, int n, int nkc, int n
   long total = (long)ndir * cdiv(n, 16) * 4 * nkc * 64;
   hipLaunchKernelGGL(pack_wh_fwd_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wf, n, nkc, total);
   return hipGetLastError();
+}
+// float ring, before the first step: slot 0 holds zeros that carry the tag of step 0 in every unit, slot 1 is cleared
+__global__ void init_ring_f32_kernel(uint4* ring0, uint4* ring1, long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const unsigned t = ll_fwd_tag(0u) << 30;
+  ring0[idx] = make_uint4(0u, t, 0u, t);
+  ring1[idx] = make_uint4(0u, 0u, 0u, 0u);
+}
+bool persist_fwd_f32_fits(const PFwdArgs& a) {
+  constexpr int kNch = 16;
+  if (a.n % 8 != 0 || a.nkc > 4 * kNch || a.T < 2) return false;
+  const long ring_bytes = (long)cdiv(a.B, 16) * a.nkc * 1024;
+  if (ring_bytes >= 0x7ff00000L) return false;
+  for (int d = 0; d < a.ndir; ++d) {
+    const PFwdDir& f = a.d[d];
+    if ((((uintptr_t)f.y | (uintptr_t)f.cs | (uintptr_t)f.hprev | (uintptr_t)f.gates | (uintptr_t)f.hstate | (uintptr_t)f.cstate) & 7) || (f.ldy & 1))
+      return false;
+  }
+  return (long)cdiv(a.n, 8) * a.ndir <= capacity(persist_fwd_f32_kernel<kNch>);
+}
+// One launch per slab of 64 rows (each walks all T steps of its rows; batch rows never interact).
+hipError_t launch_persist_fwd_f32(const PFwdArgs& a, hipStream_t s) {
+  constexpr int kNch = 16;
+  if (!persist_fwd_f32_fits(a)) return hipErrorCooperativeLaunchTooLarge;
+  const int nrt = cdiv(a.B, 16);
+  {
+    const long total = (long)nrt * a.nkc * 64;
+    for (int d = 0; d < a.ndir; ++d)
+      hipLaunchKernelGGL(init_ring_f32_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, a.d[d].ring0, a.d[d].ring1, total);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  }
+  for (int rt0 = 0; rt0 < nrt; rt0 += 4) {
+    PFwdArgs copy = a;
+    copy.rt0 = rt0;
+    const dim3 grid(cdiv(a.n, 8), 1, a.ndir);
+    void* args[] = {&copy};
+    const hipError_t e = a.plain_launch ? hipLaunchKernel((const void*)persist_fwd_f32_kernel<kNch>, grid, dim3(256), args, 0, s)
+                                        : hipLaunchCooperativeKernel((const void*)persist_fwd_f32_kernel<kNch>, grid, dim3(256), args, 0, s);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (rt0 == 0) return hipErrorCooperativeLaunchTooLarge;          // the first launch was refused: nothing has run
+      return e == hipErrorCooperativeLaunchTooLarge ? hipErrorLaunchFailure : e;
+    }
+  }
+  return hipSuccess;
 }
 hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s) {
   long total = (long)ndir * nrt * nkc * 64 * 2;

@@ -274,6 +274,32 @@ def test_single_launch_equals_per_step(dt, B, n, T):
     compare(f2, g2, fo, go, TOL[dt])
 
 
+@pytest.mark.parametrize("B,n,T,bidir,direction", [(64, 1000, 12, True, 1), (70, 136, 9, True, 1), (3, 8, 33, True, 1),
+                                                    (150, 264, 5, False, -1), (17, 1024, 6, False, 1), (33, 40, 2, True, 1)])
+def test_float_single_launch_forward(B, n, T, bidir, direction):
+    """Float storage with a zero initial hidden state runs its forward time loop in one launch (n a multiple of 8): rows of
+    length 0, 1 and T, one to three slabs of 64 rows with ragged last slabs, both directions and each alone, an initial cell
+    state; compared with one launch per time step, with the ordinary launch mode, and with the oracle."""
+    rng = np.random.default_rng(7 * B + n + T)
+    lens = rng.integers(0, T + 1, B)
+    lens[0] = T
+    if B > 2:
+        lens[1], lens[2] = 0, 1
+    c = rnd_case(rng, T=T, B=B, n_in=24, n=n, D=2 if bidir else 1, lens=lens, dt="f32", scale=0.1)
+    c["h0"] = None                                     # (the single-launch kernel is for a zero initial hidden state)
+    print("  float single launch", B, n, T, bidir, direction, flush=True)
+    f1, g1 = run_gpu(c, "f32", bidir, direction)
+    f2, g2 = run_gpu(c, "f32", bidir, direction, flags=Bn.FLAG_PER_STEP)
+    f3, g3 = run_gpu(c, "f32", bidir, direction, flags=Bn.FLAG_PLAIN_LAUNCH)
+    for k in ("y", "c", "hT", "cT"):
+        check(k + " (paths)", f1[k], host(f2[k]), 1e-5)
+        check(k + " (launch modes)", f3[k], host(f1[k]), 1e-5)
+    for k in ("dx", "dW_x", "dW_h", "db", "dc0"):
+        check(k + " (paths)", g1[k], host(g2[k]), 1e-5)
+    fo, go = run_oracle(c, bidir, direction)
+    compare(f1, g1, fo, go, TOL["f32"])
+
+
 @pytest.mark.parametrize("B,n,T", [(32, 1024, 12), (64, 1000, 9), (41, 1024, 6), (70, 136, 25)])
 def test_plain_launch_equals_cooperative(B, n, T):
     """LSTM_FLAG_PLAIN_LAUNCH starts the same kernels with an ordinary launch: same results (to the rounding of a
