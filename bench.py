@@ -761,9 +761,15 @@ def main():
         padded = (row_bytes * T * B * 2 + weight_bytes) / (layer_ms * 1e-3) / 1e9 if ms > 0 else 0.0
         step_bytes = layer_bytes / T
         tr_bytes = None if per_step_path else traffic.get(phase)
-        return {"bound": "hbm", "kernel": name + (" (one launch per time step: float storage has no single-launch kernel)" if per_step_path else ""),
+        # the recurrent product itself (h W_h or dz W_h^T: 8 n^2 flops per real frame of a row) against the MFMA peak of
+        # the storage type: what bounds the float single-launch kernel (the float MFMA runs at 1/16 of the bf16 rate)
+        rec_tflops = 8.0 * n * n * frames * 2 / (layer_ms * 1e-3) / 1e12 if ms > 0 else 0.0
+        mfma_peak_loop = BF16_PEAK_TFLOPS if esz == 2 else 157.3
+        return {"bound": "hbm", "kernel": name + (" (one launch per time step)" if per_step_path else ""),
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": tr_bytes,
+                "recurrent_product_tflops": rec_tflops, "recurrent_product_frac_of_mfma_peak": rec_tflops / mfma_peak_loop,
+                "recurrent_product_frac_counting_padded_rows": rec_tflops * (T * B) / max(frames, 1) / mfma_peak_loop,
                 "traffic_ratio": (tr_bytes / launch_bytes) if tr_bytes else None, "launches": int(launches),
                 "avg_launch_ms": per_launch_ms, "us_per_time_step": ms * 1e3 / max(steps_total, 1),
                 "step_roofline_us": step_bytes / (HBM_PEAK_GBS * 1e9) * 1e6,

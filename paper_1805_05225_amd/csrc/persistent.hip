@@ -1702,146 +1702,178 @@ __global__ __launch_bounds__(256) void persist_bwdp16_kernel(PBwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward, float storage.  The float MFMA (16x16x4) runs at a sixteenth of the bfloat16 rate, so the step is bound by the
-// matrix cores (6.7 us per step for 64 rows x 2 directions of n = 1000 on the whole device), not by the exchange, and
-// the decomposition is chosen for them: a work-group owns 8 units - 32 gate columns, two MFMA column tiles - for ALL
-// rows of a slab of 64 (four row tiles), so that W_h is held exactly once on the device (125 x 2 work-groups, 128
-// registers per lane: the packed slice of the per-step kernel, read once).  The K axis is split over the four wavefronts
-// (chunks of 16 k, wavefront w takes chunks w, w + 4, ...), their accumulators meet in LDS, and a thread updates two cells
-// (one row, two neighbouring units) and publishes them as ONE 8-byte unit of the ring: two float h values, the tag in
-// bit 30 of the second (|h| < 1 leaves the top exponent bit 0, as bit 14 of a bfloat16 value in the other kernels).
-// The ring is the per-step kernel's fragment-ordered h buffer [row tile][chunk][lane] x 16 bytes, a lane's 16 bytes
-// being two such units, so the reader of the other kernels applies unchanged.  The initial hidden state must be zero
-// (rows that have not started publish their carried state, which must stay below 2 in magnitude); callers with an
-// initial state take the per-step path.
+// forward, float storage.  The float MFMA (16x16x4) runs at a sixteenth of the bfloat16 rate: 7.1 us per step for 64 rows
+// x 2 directions of n = 1000 on the whole device, so here the matrix cores bound the step, and the exchange has to stay
+// out of their way.  Two things compete with them.  (1) Every work-group reads the whole h of its rows in float, from
+// beyond L2 (an exchange group spans several XCDs), so rows per work-group are traded against copies of W_h: a work-group
+// owns 16 units - 64 gate columns, four MFMA column tiles - for a slab of 32 rows: 63 x 2 slabs x 2 directions = 252
+// work-groups for config 2, W_h held twice on the device (256 registers per lane: the per-step kernel's packed slices of
+// two 8-unit tiles), 128 KiB of ring read per work-group and step (with 8 units x 64 rows, 256 KiB, the step took 13.8 us
+// against 11 for its products alone).  (2) The round trip of the exchange - reduce, cell, publish, and the consumers' loads,
+// about 2.5 us - which nothing overlaps if all rows move in lock step (12.0 us per step).  The two row tiles of a slab
+// are different batch rows, i.e. independent recurrences: they are walked HALF A STEP APART, one's products running
+// while the other's h travels.
+// The K axis is split over the four wavefronts (chunks of 16 k, wavefront w takes chunks w, w + 4, ...), their accumulators
+// meet in LDS, a thread updates one cell per row tile, and two neighbouring units are published as ONE 8-byte unit of the
+// ring: two float h values, the tag in bit 30 of the second (|h| < 1 leaves the top exponent bit 0, as bit 14 of a
+// bfloat16 value in the other kernels).  The ring is the per-step kernel's fragment-ordered h buffer [row tile][chunk][lane]
+// x 16 bytes, a lane's 16 bytes being two such units, so the reader of the other kernels applies unchanged.  The initial
+// hidden state must be zero (rows that have not started publish their carried state, which must stay below 2 in
+// magnitude); callers with an initial state take the per-step path.
 template <int NCH>                                         // chunks per wavefront at most: n <= 64 * NCH
 __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
-  __shared__ float red[4][64][33];
-  const int tile = blockIdx.x, dir = blockIdx.z;
+  __shared__ float red[4][16][65];
+  const int tile = blockIdx.x, dir = blockIdx.z;           // tile: 16 units
   const PFwdDir d = a.d[dir];          // a copy: fields read through a reference are fetched again in every time step
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nkc = a.nkc, n = a.n, B = a.B, T = a.T;
-  const int nrt_here = min(4, (B + 15) / 16 - a.rt0);      // row tiles of this slab
+  const int rt_base = a.rt0 + 2 * (int)blockIdx.y;         // first 16-row tile of this work-group's slab
+  const int nrt_here = min(2, (B + 15) / 16 - rt_base);
+  const int ntile8 = (n + 7) / 8;
   unsigned* err = a.sync;
   bool dead = false;
 
-  // W_h slice: chunk kc = wave + 4 it, column tile ct (the per-step kernel's packing)
-  uint4 w[NCH][2];
+  // W_h slice: chunk kc = wave + 4 it; column tile ct = tile of 8 units (ct >> 1), its gates i,f (ct & 1 = 0) or g,o
+  // (the per-step kernel's packing)
+  uint4 w[NCH][4];
 #pragma unroll
   for (int it = 0; it < NCH; ++it) {
     const int kc = wave + 4 * it;
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
-      w[it][ct] = kc < nkc ? d.Wf[((long)(tile * 2 + ct) * nkc + kc) * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+    for (int ct = 0; ct < 4; ++ct) {
+      const int tile8 = tile * 2 + (ct >> 1);
+      w[it][ct] = (kc < nkc && tile8 < ntile8) ? d.Wf[((long)(tile8 * 2 + (ct & 1)) * nkc + kc) * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+    }
   }
 
-  // pointwise: row `row` of the slab, units 2 up and 2 up + 1 of the tile
-  const int row = tid >> 2, up = tid & 3;
-  const int b = a.rt0 * 16 + row, j = tile * 8 + 2 * up;
-  const bool active = b < B && j < n;                      // (n is a multiple of 8: both units exist or neither)
-  const bool in_slab = row < 16 * nrt_here;
+  // pointwise: row r16 of each row tile, unit u of the tile's 16
+  const int r16 = tid >> 4, u = tid & 15;
+  const int j = tile * 16 + u;
   float c[2] = {0.f, 0.f}, h[2] = {0.f, 0.f};
-  int L = 0;
-  if (active) {
-    c[0] = d.cstate[(long)b * n + j]; c[1] = d.cstate[(long)b * n + j + 1];
-    L = clamp_len(a.lens, b, T);
+  int L[2] = {0, 0};
+  bool active[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int b = (rt_base + k) * 16 + r16;
+    active[k] = k < nrt_here && b < B && j < n;
+    if (active[k]) {
+      c[k] = d.cstate[(long)b * n + j];
+      L[k] = clamp_len(a.lens, b, T);
+    }
   }
-  // where this thread's unit lies in a ring slot: chunk (tile*8 + 2 up) / 16, lane group ((tile*8 + 2 up) % 16) / 4,
-  // half (up & 1) of that lane's 16 bytes
+  // The even unit of a pair publishes both: chunk j / 16, lane group (j % 16) / 4, half ((j % 4) / 2) of that lane's 16 bytes
   constexpr unsigned kParked = 0x7ff00000u;
-  const int kpub = tile * 8 + 2 * up;
-  const unsigned pub_off = in_slab ? (unsigned)(((((long)(a.rt0 + (row >> 4)) * nkc + (kpub >> 4)) * 64 + ((kpub & 15) >> 2) * 16 + (row & 15)) * 2 + (up & 1)) * 8)
-                                   : kParked;
+  const bool publishes = (u & 1) == 0 && j < n;            // (n is a multiple of 8: the odd partner exists as well)
+  const unsigned pub_in_tile = (unsigned)((((long)(j >> 4) * 64 + ((j & 15) >> 2) * 16 + r16) * 2 + ((j >> 1) & 1)) * 8);
   const unsigned ring_bytes = (unsigned)((B + 15) / 16) * nkc * 1024u;
   const long fg = (long)B * 4 * n, fy = (long)B * d.ldy, fs = (long)B * n;     // elements per frame
+  // columns of this thread's cell among the work-group's 64: 32 per tile of 8 units, then gate q, unit
+  const int col0 = (u >> 3) * 32 + (u & 7);
+  PROF_DECL
+  // The first half of a half step's ring loads goes out before the reduction and the cell update of the half step
+  // before it (their values were published half a step earlier) and is there when the products begin; the second half
+  // goes out then and arrives behind the first half's products.  (All of them early does not fit the register file.)
+  u32x4 x[NCH];
+  auto reader = [&](int tau, int k) __attribute__((always_inline)) {
+    return make_reader(((tau & 1) ? d.ring1 : d.ring0) + (long)(rt_base + k) * nkc * 64, nkc, (n + 3) / 4, wave, lane,
+                       ll_fwd_tag((unsigned)tau) << 14, err, a.spin_limit, 0);
+  };
+  auto issue_loads = [&](int tau, int k) __attribute__((always_inline)) {
+    const RingReader rn = reader(tau, k);
+#pragma unroll
+    for (int it = 0; it < NCH / 2; ++it) x[it] = rn.load_it(it);
+  };
+  if (T > 0) issue_loads(0, 0);
 
   for (int tau = 0; tau < T; ++tau) {
-    float (&red_)[4][64][33] = red;
     const int t = d.rev ? T - 1 - tau : tau;
-    const bool valid = active && t < L;
-    // this step's x W_x + b: in flight while the products run
-    float zx[4][2];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float2 z2 = valid ? *(const float2*)(d.gates + t * fg + (long)b * 4 * n + q * n + j) : make_float2(0.f, 0.f);
-      zx[q][0] = z2.x; zx[q][1] = z2.y;
-    }
-    f32x4 acc[4][2];
-#pragma unroll
-    for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) acc[rt][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
     const unsigned tag = ll_fwd_tag((unsigned)tau) << 14, tagw = tag << 16;
-    const uint4* rin = (tau & 1) ? d.ring1 : d.ring0;
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
-      if (rt >= nrt_here) break;                           // (the same in every work-group of the launch)
-      const RingReader rd = make_reader(rin + (long)(a.rt0 + rt) * nkc * 64, nkc, (n + 3) / 4, wave, lane, tag, err, a.spin_limit, 0);
+    for (int k = 0; k < 2; ++k) {                          // the slab's two row tiles, half a step apart
+      if (k >= nrt_here) break;                            // (the same in every work-group of the launch)
+      PROF_MARK(4)
+      const int b = (rt_base + k) * 16 + r16;
+      const bool valid = active[k] && t < L[k];
+      // this frame's x W_x + b: in flight while the products run
+      float zx[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) zx[q] = valid ? d.gates[t * fg + (long)b * 4 * n + q * n + j] : 0.f;
+      f32x4 acc[4];
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const RingReader rd = reader(tau, k);
       auto use = [&](int it, const u32x4& x) __attribute__((always_inline)) {
-        const uint4 av = make_uint4(x[0], x[1] & ~kLLFwdTagBit, x[2], x[3] & ~kLLFwdTagBit);
-        acc[rt][0] = Mma16<float>::run(av, w[it][0], acc[rt][0]);
-        acc[rt][1] = Mma16<float>::run(av, w[it][1], acc[rt][1]);
-      };
-      // all loads of the row tile go out; whichever shows a stale tag is fetched again afterwards (bounded)
-      u32x4 x[NCH];
+        const float av[4] = {__uint_as_float(x[0]), __uint_as_float(x[1] & ~kLLFwdTagBit), __uint_as_float(x[2]),
+                             __uint_as_float(x[3] & ~kLLFwdTagBit)};
 #pragma unroll
-      for (int it = 0; it < NCH; ++it) x[it] = rd.load_it(it);
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct) {
+            const float we = __uint_as_float(e == 0 ? w[it][ct].x : e == 1 ? w[it][ct].y : e == 2 ? w[it][ct].z : w[it][ct].w);
+            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[e], we, acc[ct], 0, 0, 0);
+          }
+      };
+#pragma unroll
+      for (int it = NCH / 2; it < NCH; ++it) x[it] = rd.load_it(it);
+      // a load with a stale tag is fetched again (bounded) - rare, since the values were published half a step ago
       unsigned long long redo = 0ull;
 #pragma unroll
       for (int it = 0; it < NCH; ++it) {
         if (__builtin_amdgcn_ballot_w64(rd.tag_diff(x[it], it, tagw) != 0u) == 0ull) use(it, x[it]);
-        else redo |= 1ull << it;
+        else { redo |= 1ull << it; PROF_REDO(1) }
       }
-      if (redo) rd.fix_up_batch<NCH>(redo, dead, use);
-    }
-    // accumulator rows 4 * (lane / 16) + v of the row tile, column lane % 16 of the column tile
+      if (redo) rd.template fix_up_batch<NCH>(redo, dead, use);
+      if (k + 1 < nrt_here) issue_loads(tau, k + 1);
+      else if (tau + 1 < T) issue_loads(tau + 1, 0);
+      PROF_MARK(0)
+      // accumulator rows 4 * (lane / 16) + v of the row tile, column lane % 16 of the column tile
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt)
+      for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red_[wave][rt * 16 + 4 * (lane >> 4) + v][ct * 16 + (lane & 15)] = acc[rt][ct][v];
-    __syncthreads();
-    float hprev[2] = {h[0], h[1]};
-    CellOut o[2] = {};
-    if (valid) {
-#pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        float zh[4], zk[4];
+        for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][ct * 16 + (lane & 15)] = acc[ct][v];
+      PROF_MARK(1)
+      __syncthreads();
+      const float hprev = h[k];
+      CellOut o = {};
+      if (valid) {
+        float zh[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int col = q * 8 + 2 * up + k;
-          zh[q] = red_[0][row][col] + red_[1][row][col] + red_[2][row][col] + red_[3][row][col];
-          zk[q] = zx[q][k];
+          const int col = col0 + q * 8;
+          zh[q] = red[0][r16][col] + red[1][r16][col] + red[2][r16][col] + red[3][r16][col];
         }
-        o[k] = lstm_cell(zh, zk, c[k]);
-        c[k] = o[k].c; h[k] = o[k].h;
+        o = lstm_cell(zh, zx, c[k]);
+        c[k] = o.c; h[k] = o.h;
       }
-    }
-    __syncthreads();                  // (the next step's accumulators may be written: a step is 7 us, the barrier nothing)
-    {                                 // the recurrence's critical store goes out first (16: agent scope, written through)
-      const u32x2 unit = {__float_as_uint(h[0]), __float_as_uint(h[1]) | (ll_fwd_tag((unsigned)tau + 1u) << 30)};
-      const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, ring_bytes, kBufFlags);
-      __builtin_amdgcn_raw_buffer_store_b64(unit, ro, pub_off, 0, 16);
-    }
-    if (active) {                     // layer outputs and what the backward pass needs
-      *(float2*)((float*)d.y + t * fy + (long)b * d.ldy + j) = valid ? make_float2(h[0], h[1]) : make_float2(0.f, 0.f);
-      if (d.cs) *(float2*)(d.cs + t * fs + (long)b * n + j) = make_float2(c[0], c[1]);
-      if (d.hprev) *(float2*)((float*)d.hprev + t * fs + (long)b * n + j) = make_float2(hprev[0], hprev[1]);
-      if (valid && a.write_gates) {
-        float* gp = d.gates + t * fg + (long)b * 4 * n + j;
-        *(float2*)gp = make_float2(o[0].gi, o[1].gi);
-        *(float2*)(gp + n) = make_float2(o[0].gf, o[1].gf);
-        *(float2*)(gp + 2 * n) = make_float2(o[0].gg, o[1].gg);
-        *(float2*)(gp + 3 * n) = make_float2(o[0].go, o[1].go);
+      __syncthreads();                // (the accumulators of the other row tile may be written)
+      PROF_MARK(2)
+      {                               // the recurrence's critical store goes out first (16: agent scope, written through)
+        const unsigned h_odd = (unsigned)__builtin_amdgcn_mov_dpp((int)__float_as_uint(h[k]), 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]: the neighbour's h
+        const u32x2 unit = {__float_as_uint(h[k]), h_odd | (ll_fwd_tag((unsigned)tau + 1u) << 30)};
+        const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, ring_bytes, kBufFlags);
+        __builtin_amdgcn_raw_buffer_store_b64(unit, ro, publishes ? (unsigned)(rt_base + k) * (unsigned)nkc * 1024u + pub_in_tile : kParked, 0, 16);
       }
+      if (active[k]) {                // layer outputs and what the backward pass needs
+        ((float*)d.y)[t * fy + (long)b * d.ldy + j] = valid ? h[k] : 0.f;
+        if (d.cs) d.cs[t * fs + (long)b * n + j] = c[k];
+        if (d.hprev) ((float*)d.hprev)[t * fs + (long)b * n + j] = hprev;
+        if (valid && a.write_gates) {
+          float* gp = d.gates + t * fg + (long)b * 4 * n + j;
+          gp[0] = o.gi; gp[n] = o.gf; gp[2 * n] = o.gg; gp[3 * n] = o.go;
+        }
+      }
+      PROF_MARK(3)
     }
   }
-  if (active) {
-    *(float2*)(d.cstate + (long)b * n + j) = make_float2(c[0], c[1]);
-    *(float2*)(d.hstate + (long)b * n + j) = make_float2(h[0], h[1]);
-  }
+  PROF_DUMP("fwdf32", T)
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+    if (active[k]) {
+      const int b = (rt_base + k) * 16 + r16;
+      d.cstate[(long)b * n + j] = c[k];
+      d.hstate[(long)b * n + j] = h[k];
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -2052,29 +2084,31 @@ bool persist_fwd_f32_fits(const PFwdArgs& a) {
     if ((((uintptr_t)f.y | (uintptr_t)f.cs | (uintptr_t)f.hprev | (uintptr_t)f.gates | (uintptr_t)f.hstate | (uintptr_t)f.cstate) & 7) || (f.ldy & 1))
       return false;
   }
-  return (long)cdiv(a.n, 8) * a.ndir <= capacity(persist_fwd_f32_kernel<kNch>);
+  return (long)cdiv(a.n, 16) * a.ndir <= capacity(persist_fwd_f32_kernel<kNch>);
 }
-// One launch per slab of 64 rows (each walks all T steps of its rows; batch rows never interact).
+// As many slabs of 32 rows per launch as the device holds at once (each launch walks all T steps of its rows; batch
+// rows never interact).
 hipError_t launch_persist_fwd_f32(const PFwdArgs& a, hipStream_t s) {
   constexpr int kNch = 16;
   if (!persist_fwd_f32_fits(a)) return hipErrorCooperativeLaunchTooLarge;
-  const int nrt = cdiv(a.B, 16);
+  const int nrt = cdiv(a.B, 16), nslab = cdiv(nrt, 2), grid_x = cdiv(a.n, 16);
+  const int per_launch = (int)std::min<long>(nslab, capacity(persist_fwd_f32_kernel<kNch>) / ((long)grid_x * a.ndir));
   {
     const long total = (long)nrt * a.nkc * 64;
     for (int d = 0; d < a.ndir; ++d)
       hipLaunchKernelGGL(init_ring_f32_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, a.d[d].ring0, a.d[d].ring1, total);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   }
-  for (int rt0 = 0; rt0 < nrt; rt0 += 4) {
+  for (int slab0 = 0; slab0 < nslab; slab0 += per_launch) {
     PFwdArgs copy = a;
-    copy.rt0 = rt0;
-    const dim3 grid(cdiv(a.n, 8), 1, a.ndir);
+    copy.rt0 = 2 * slab0;
+    const dim3 grid(grid_x, std::min(per_launch, nslab - slab0), a.ndir);
     void* args[] = {&copy};
     const hipError_t e = a.plain_launch ? hipLaunchKernel((const void*)persist_fwd_f32_kernel<kNch>, grid, dim3(256), args, 0, s)
                                         : hipLaunchCooperativeKernel((const void*)persist_fwd_f32_kernel<kNch>, grid, dim3(256), args, 0, s);
     if (e != hipSuccess) {
       (void)hipGetLastError();
-      if (rt0 == 0) return hipErrorCooperativeLaunchTooLarge;          // the first launch was refused: nothing has run
+      if (slab0 == 0) return hipErrorCooperativeLaunchTooLarge;        // the first launch was refused: nothing has run
       return e == hipErrorCooperativeLaunchTooLarge ? hipErrorLaunchFailure : e;
     }
   }
