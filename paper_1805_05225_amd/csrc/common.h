@@ -209,6 +209,16 @@ struct PBwdArgs {
 bool persist_bwd_fits(const PBwdArgs& a);
 hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s);
 hipError_t launch_pack_wh_bwdp(const void* W_h, uint4* Wb, int n, int ndir, hipStream_t s);
+// Float storage: the same exchange of partial sums in float.  W_h^T via launch_pack_wh_bwd_f32p (bwd_f32_wh_bytes per
+// direction), rings of bwd_f32_ring_bytes per direction and slot, zero-filled; gates, cs, dy, DZ float; dbpart unused.
+bool persist_bwd_f32_fits(const PBwdArgs& a);
+hipError_t launch_persist_bwd_f32(const PBwdArgs& a, hipStream_t s);
+hipError_t launch_pack_wh_bwd_f32p(const void* W_h, void* Wb, int n, int ndir, hipStream_t s);
+inline size_t bwd_f32_wh_bytes(int n) { return (size_t)((n + 15) / 16) * 4 * 16 * 16 * 64 * 4; }
+inline size_t bwd_f32_ring_bytes(int B, int n) {
+  const size_t tiles = (size_t)((n + 15) / 16), rts = 2 * (size_t)(((B > 0 ? B : 1) + 31) / 32);
+  return rts * tiles * tiles * 1024;
+}
 inline size_t bwdp_wh_bytes(int n) { return (size_t)((n + 31) / 32) * 262144; }                  // per direction
 inline size_t bwdp_ring_bytes(int B, int n) {                                                      // per direction and slot
   const size_t groups = 2 * (size_t)(((B > 0 ? B : 1) + 15) / 16), tiles = (size_t)((n + 31) / 32);

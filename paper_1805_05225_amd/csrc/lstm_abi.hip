@@ -66,9 +66,13 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->Wf_bytes = D * std::max((size_t)p->ntile_f * 2 * p->nkc_f, (size_t)p->ntile16 * 4 * p->nkc_ll_f) * 1024;
   p->ws_Wf = take(p->Wf_bytes + 1024);            // packed W_h, then one chunk of zeros
   const bool part = p->bf16 && d->n <= 1024;          // the partial-sum backward kernel may be chosen
-  p->ws_Wb = take(infer ? 0 : D * std::max((size_t)p->ntile_b * p->nkc_b * 1024, part ? bwdp_wh_bytes(d->n) : (size_t)0));
+  // float storage: the single-launch backward kernel (batches of up to 256 rows: its rings grow with B n^2 / 16)
+  const bool part32 = !p->bf16 && d->n % 8 == 0 && d->n <= 1024 && d->B <= 256;
+  p->ws_Wb = take(infer ? 0 : D * std::max({(size_t)p->ntile_b * p->nkc_b * 1024, part ? bwdp_wh_bytes(d->n) : (size_t)0,
+                                            part32 ? bwd_f32_wh_bytes(d->n) : (size_t)0}));
   p->hfrag_bytes = D * p->nrt * (size_t)std::max(p->nkc_f, p->nkc_ll_f) * 1024;
-  p->dzfrag_bytes = D * std::max(p->nrt * (size_t)p->nkc_b * 1024, part ? bwdp_ring_bytes(d->B, d->n) : (size_t)0);
+  p->dzfrag_bytes = D * std::max({p->nrt * (size_t)p->nkc_b * 1024, part ? bwdp_ring_bytes(d->B, d->n) : (size_t)0,
+                                  part32 ? bwd_f32_ring_bytes(d->B, d->n) : (size_t)0});
   p->ws_hfrag0 = take(p->hfrag_bytes);
   p->ws_hfrag1 = take(p->hfrag_bytes);
   p->ws_dzfrag0 = take(infer ? 0 : p->dzfrag_bytes);
@@ -480,18 +484,22 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   pa.xcc = (unsigned*)(ws + p.ws_sync) + 64 + 2 * (size_t)p.nrt;
   for (size_t d = 0; d < D; ++d) pa.d[d].lddy = (long)(D * n);       // (the check looks at the frame sizes)
   const bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && persist_bwd_fits(pa);
+  const bool use_ll32 = !p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.n % 8 == 0 && p.n <= 1024 && p.B <= 256 &&
+                        persist_bwd_f32_fits(pa);
   {
     Phase ph(LSTM_PHASE_PREP, 1, s);
     if (use_ll) HIPCHK(launch_pack_wh_bwdp(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, s));
+    else if (use_ll32) HIPCHK(launch_pack_wh_bwd_f32p(W_h, ws + p.ws_Wb, p.n, p.D, s));
     else HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
   }
 
   const size_t frag_dir = (size_t)p.nrt * p.nkc_b * 1024;
   char* DZ = ws + p.ws_DZ;
   bool done = false;
-  const bool db_in_loop = 2 * p.nrt <= kColsumSlices;   // the single-launch kernel also sums the bias gradient
-  if (use_ll) {
-    const size_t ring_dir = bwdp_ring_bytes(p.B, p.n), wb_dir = bwdp_wh_bytes(p.n);
+  const bool db_in_loop = use_ll && 2 * p.nrt <= kColsumSlices;   // the bfloat16 single-launch kernel also sums the bias gradient
+  if (use_ll || use_ll32) {
+    const size_t ring_dir = use_ll ? bwdp_ring_bytes(p.B, p.n) : bwd_f32_ring_bytes(p.B, p.n);
+    const size_t wb_dir = use_ll ? bwdp_wh_bytes(p.n) : bwd_f32_wh_bytes(p.n);
     for (size_t d = 0; d < D; ++d) {
       PBwdDir& bd = pa.d[d];
       bd.Wb = (const uint4*)(ws + p.ws_Wb + d * wb_dir);
@@ -511,7 +519,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     hipError_t e;
     {
       Phase ph(LSTM_PHASE_LOOP_BWD, 1, s);
-      e = launch_persist_bwd(pa, s);
+      e = use_ll ? launch_persist_bwd(pa, s) : launch_persist_bwd_f32(pa, s);
     }
     if (e == hipSuccess) done = true;
     else if (e != hipErrorCooperativeLaunchTooLarge) {   // a later batch slab failed after earlier ones ran

@@ -1877,6 +1877,168 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// backward, float storage: partial sums of Dh, as in the bfloat16 kernels, in the decomposition of the float forward
+// kernel (16 units x a slab of 32 rows per work-group, the slab's two row tiles half a step apart).  A work-group
+// multiplies ITS dz (16 rows x 64 gate columns, through LDS, never leaving the compute unit) by the matching 64 rows of W_h^T
+// for ALL n outputs - 256 registers per lane hold that slice, 16 column tiles x 16 k-steps per wavefront - and publishes,
+// per destination tile of 16 units, the accumulator tile as it stands: a lane's four floats (rows 4g .. 4g+3 of one output)
+// are two 8-byte units, the tag bit 30 of each unit's second float.  Partial sums are not bounded by 1, so they travel scaled
+// by 2^-32 (the packed W_h^T carries the factor; the consumer multiplies its sum by 2^32): bit 30 is then 0 for every partial
+// sum below 2^33 in magnitude, and no other bit of a value above 2^-94 changes.  A consumer adds the blocks of its tile from
+// all producers (1 KiB each, one 16-byte load per lane: the producer's accumulator layout), wavefront w taking producers
+// w, w + 4, ..., and the four sums meet in LDS.
+// Ring per direction and slot: [row tile][destination tile][producer tile] x 1 KiB.  K axis of the product: gate column
+// kappa = 16 kg + s of the work-group's 64 (gate kappa / 16, unit kappa % 16) is k-step s of lane group kg, so that a lane
+// reads its sixteen A values from sixteen consecutive floats of a dz row in LDS.
+template <int NCT>                                         // column tiles per wavefront at most: n <= 64 * NCT
+__global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
+  __shared__ float red[4][16][17];                         // [wavefront][row][output]
+  __shared__ __attribute__((aligned(16))) float zb[16][68];// dz of the row tile in hand: [row][gate column kappa]
+  const int J = blockIdx.x, dir = blockIdx.z;              // J: tile of 16 units
+  const PBwdDir d = a.d[dir];          // a copy: fields read through a reference are fetched again in every time step
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = a.n, B = a.B, T = a.T;
+  const int ntile = (n + 15) / 16;
+  const int rt_base = a.rt0 + 2 * (int)blockIdx.y;         // first 16-row tile of this work-group's slab
+  const int nrt_here = min(2, (B + 15) / 16 - rt_base);
+  unsigned* err = a.sync;
+  bool dead = false;
+
+  // W_h^T slice: column tile wave + 4 ci of the outputs, k-step s (launch_pack_wh_bwd_f32p)
+  float w[NCT][16];
+#pragma unroll
+  for (int ci = 0; ci < NCT; ++ci)
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const float4 v = ((const float4*)d.Wb)[((((long)J * 4 + wave) * NCT + ci) * 4 + s4) * 64 + lane];
+      w[ci][4 * s4] = v.x; w[ci][4 * s4 + 1] = v.y; w[ci][4 * s4 + 2] = v.z; w[ci][4 * s4 + 3] = v.w;
+    }
+
+  // pointwise: row r16 of each row tile, unit u of the tile's 16
+  const int r16 = tid >> 4, u = tid & 15;
+  const int j = J * 16 + u;
+  float Dh[2] = {0.f, 0.f}, Dc[2] = {0.f, 0.f};
+  int L[2] = {0, 0};
+  bool active[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int b = (rt_base + k) * 16 + r16;
+    active[k] = k < nrt_here && b < B && j < n;
+    if (active[k]) {
+      Dh[k] = d.Dh[(long)b * n + j];
+      Dc[k] = d.Dc[(long)b * n + j];
+      L[k] = clamp_len(a.lens, b, T);
+    }
+  }
+  const long fg = (long)B * 4 * n, fy = (long)B * d.lddy, fs = (long)B * n;    // elements per frame
+  const unsigned ring_bytes = (unsigned)((B + 15) / 16) * (unsigned)ntile * (unsigned)ntile * 1024u;
+  PROF_DECL
+
+  // Steps sigma = 0 .. T-1 work on frames (the last frame in processing order first); step T only collects the Dh that
+  // leaves the layer.
+  for (int sigma = 0; sigma <= T; ++sigma) {
+    const int tau = T - 1 - sigma;                         // position in processing order; -1 in the collecting step
+    const int t = d.rev ? T - 1 - tau : tau;               // this step's frame (outside [0, T) in the collecting step)
+    const int t_next = d.rev ? t - 1 : t + 1;              // the frame of the step before: where the partial sums come from
+    const bool pointwise = sigma < T;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {                          // the slab's two row tiles, half a step apart
+      if (k >= nrt_here) break;                            // (the same in every work-group of the launch)
+      PROF_MARK(4)
+      const int b = (rt_base + k) * 16 + r16;
+      const bool valid = pointwise && active[k] && t < L[k];
+      // what the gate gradients of the frame need: in flight while the partial sums are collected
+      float gi = 0.f, gf = 0.f, gg = 0.f, go = 0.f, c_new = 0.f, c_prev = 0.f, dy = 0.f;
+      if (valid) {
+        const float* gp = d.gates + t * fg + (long)b * 4 * n + j;
+        gi = gp[0]; gf = gp[n]; gg = gp[2 * n]; go = gp[3 * n];
+        c_new = d.cs[t * fs + (long)b * n + j];
+        const int tp = d.rev ? t + 1 : t - 1;              // the frame before t in processing order
+        c_prev = (tp >= 0 && tp < T) ? d.cs[tp * fs + (long)b * n + j] : (d.c0 ? d.c0[(long)b * n + j] : 0.f);
+        dy = ((const float*)d.dy)[t * fy + (long)b * d.lddy + j];
+      }
+      if (sigma > 0) {                                     // the partial sums of Dh that the step before published
+        RingReader rd;
+        const long tile_base = (((long)(rt_base + k) * ntile + J) * ntile) * 64;                 // uint4 index of [row tile][J][0]
+        rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + tile_base), 0, ntile * 1024, kBufFlags);
+        rd.voff = (unsigned)(wave * 1024 + lane * 16);     // load `it` of this wavefront covers producer wave + 4 it
+        rd.it_bytes = 4096u;
+        rd.lim = ntile - wave; rd.lim_step = 4;
+        rd.tag = part_tag(sigma) << 14; rd.err = err; rd.limit = a.spin_limit;
+        rd.nitv = (ntile + 3) / 4; rd.rot = 0;
+        const unsigned tagw = rd.tag << 16;
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
+        auto add = [&](int, const u32x4& v) __attribute__((always_inline)) {
+          ps[0] += __uint_as_float(v[0]); ps[1] += __uint_as_float(v[1] & ~kLLFwdTagBit);
+          ps[2] += __uint_as_float(v[2]); ps[3] += __uint_as_float(v[3] & ~kLLFwdTagBit);
+        };
+        u32x4 x[NCT];
+#pragma unroll
+        for (int it = 0; it < NCT; ++it) x[it] = rd.load_it(it);
+        unsigned long long redo = 0ull;
+#pragma unroll
+        for (int it = 0; it < NCT; ++it) {
+          if (__builtin_amdgcn_ballot_w64(rd.tag_diff(x[it], it, tagw) != 0u) == 0ull) add(it, x[it]);
+          else { redo |= 1ull << it; PROF_REDO(1) }
+        }
+        if (redo) rd.template fix_up_batch<NCT>(redo, dead, add);
+        // a lane's sums: rows 4 (lane / 16) + v of output lane % 16
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = ps[v];
+      }
+      PROF_MARK(0)
+      __syncthreads();
+      if (sigma > 0 && active[k] && t_next >= 0 && t_next < L[k])
+        Dh[k] = (red[0][r16][u] + red[1][r16][u] + red[2][r16][u] + red[3][r16][u]) * (1.f / kPartScale);
+      float dz[4] = {0.f, 0.f, 0.f, 0.f};
+      if (valid) lstm_cell_grad(gi, gf, gg, go, c_new, c_prev, dy + Dh[k], Dc[k], dz);
+      if (pointwise) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) zb[r16][q * 16 + u] = dz[q];
+        if (active[k]) {
+          float* zp = (float*)d.DZ + t * fg + (long)b * 4 * n + j;
+          zp[0] = dz[0]; zp[n] = dz[1]; zp[2 * n] = dz[2]; zp[3 * n] = dz[3];
+        }
+      }
+      PROF_MARK(2)
+      __syncthreads();
+      if (pointwise) {
+        // A operand: row lane % 16, gate columns 16 (lane / 16) .. + 15
+        float av[16];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+          const float4 v = *(const float4*)&zb[lane & 15][(lane >> 4) * 16 + 4 * s4];
+          av[4 * s4] = v.x; av[4 * s4 + 1] = v.y; av[4 * s4 + 2] = v.z; av[4 * s4 + 3] = v.w;
+        }
+        const unsigned tag_hi = part_tag(sigma + 1) << 30;
+        const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((sigma & 1) ? d.ring1 : d.ring0), 0, ring_bytes, kBufFlags);
+        // destination tile wave + 4 ci (one past the last: parked), this producer's block
+        const unsigned pub0 = (unsigned)((((rt_base + k) * ntile + wave) * ntile + J) * 1024 + lane * 16);
+#pragma unroll
+        for (int ci = 0; ci < NCT; ++ci) {
+          f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s], w[ci][s], acc, 0, 0, 0);
+          const u32x4 unit = {__float_as_uint(acc[0]), __float_as_uint(acc[1]) | tag_hi, __float_as_uint(acc[2]), __float_as_uint(acc[3]) | tag_hi};
+          const unsigned off = wave + 4 * ci < ntile ? pub0 + (unsigned)(4 * ci) * (unsigned)ntile * 1024u : 0x7ff00000u;
+          __builtin_amdgcn_raw_buffer_store_b128(unit, ro, off, 0, 16);    // 16: agent scope, written through
+        }
+      }
+      PROF_MARK(1)
+    }
+  }
+  PROF_DUMP("bwdf32", T)
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+    if (active[k]) {
+      const int b = (rt_base + k) * 16 + r16;
+      d.Dh[(long)b * n + j] = Dh[k];
+      d.Dc[(long)b * n + j] = Dc[k];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // packing for the ring layout
 // forward weights: chunk index = (((dir*ntile + tile)*4 + q)*nkc + kc)*64 + lane
 __global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nkc, long total) {
@@ -2106,6 +2268,58 @@ hipError_t launch_persist_fwd_f32(const PFwdArgs& a, hipStream_t s) {
     void* args[] = {&copy};
     const hipError_t e = a.plain_launch ? hipLaunchKernel((const void*)persist_fwd_f32_kernel<kNch>, grid, dim3(256), args, 0, s)
                                         : hipLaunchCooperativeKernel((const void*)persist_fwd_f32_kernel<kNch>, grid, dim3(256), args, 0, s);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (slab0 == 0) return hipErrorCooperativeLaunchTooLarge;        // the first launch was refused: nothing has run
+      return e == hipErrorCooperativeLaunchTooLarge ? hipErrorLaunchFailure : e;
+    }
+  }
+  return hipSuccess;
+}
+// W_h^T for the float partial-sum backward kernel, scaled by 2^-32: float index
+// ((((dir*ntile + J)*4 + wave)*NCT + ci)*16 + s)*64 + lane holds W_h[unit (wave + 4 ci)*16 + lane%16][gate column
+// (kappa/16)*n + J*16 + kappa%16], kappa = 16 (lane/16) + s; stored so that a lane's k-steps 4 s4 .. 4 s4 + 3 are one float4:
+// float4 index ((((dir*ntile + J)*4 + wave)*NCT + ci)*4 + s4)*64 + lane.
+__global__ void pack_wh_bwd_f32p_kernel(const float* W, float* out, int n, int ntile, int nct, long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int e = idx & 3;
+  long rest = idx >> 2;
+  const int lane = rest & 63; rest >>= 6;
+  const int s4 = rest & 3; rest >>= 2;
+  const int ci = rest % nct; rest /= nct;
+  const int wave = rest & 3; rest >>= 2;
+  const int J = rest % ntile, dir = rest / ntile;
+  const int s = 4 * s4 + e, kappa = 16 * (lane >> 4) + s;
+  const int unit_in = (wave + 4 * ci) * 16 + (lane & 15), unit_out = J * 16 + (kappa & 15), q = kappa >> 4;
+  const float* Wd = W + (long)dir * n * 4 * n;
+  out[idx] = (unit_in < n && unit_out < n) ? Wd[(long)unit_in * 4 * n + q * n + unit_out] * kPartScale : 0.f;
+}
+constexpr int kBwdF32Nct = 16;
+bool persist_bwd_f32_fits(const PBwdArgs& a) {
+  if (a.n % 8 != 0 || a.n > 64 * kBwdF32Nct || a.T < 2) return false;
+  const long ntile = cdiv(a.n, 16);
+  if ((long)cdiv(a.B, 16) * ntile * ntile * 1024 >= 0x7ff00000L) return false;
+  return ntile * a.ndir <= capacity(persist_bwd_f32_kernel<kBwdF32Nct>);
+}
+hipError_t launch_pack_wh_bwd_f32p(const void* W, void* Wb, int n, int ndir, hipStream_t s) {
+  const int ntile = cdiv(n, 16);
+  const long total = (long)ndir * ntile * 4 * kBwdF32Nct * 16 * 64;
+  hipLaunchKernelGGL(pack_wh_bwd_f32p_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const float*)W, (float*)Wb, n, ntile, kBwdF32Nct, total);
+  return hipGetLastError();
+}
+// As many slabs of 32 rows per launch as the device holds at once; the rings must hold zeros.
+hipError_t launch_persist_bwd_f32(const PBwdArgs& a, hipStream_t s) {
+  if (!persist_bwd_f32_fits(a)) return hipErrorCooperativeLaunchTooLarge;
+  const int nrt = cdiv(a.B, 16), nslab = cdiv(nrt, 2), grid_x = cdiv(a.n, 16);
+  const int per_launch = (int)std::min<long>(nslab, capacity(persist_bwd_f32_kernel<kBwdF32Nct>) / ((long)grid_x * a.ndir));
+  for (int slab0 = 0; slab0 < nslab; slab0 += per_launch) {
+    PBwdArgs copy = a;
+    copy.rt0 = 2 * slab0;
+    const dim3 grid(grid_x, std::min(per_launch, nslab - slab0), a.ndir);
+    void* args[] = {&copy};
+    const hipError_t e = a.plain_launch ? hipLaunchKernel((const void*)persist_bwd_f32_kernel<kBwdF32Nct>, grid, dim3(256), args, 0, s)
+                                        : hipLaunchCooperativeKernel((const void*)persist_bwd_f32_kernel<kBwdF32Nct>, grid, dim3(256), args, 0, s);
     if (e != hipSuccess) {
       (void)hipGetLastError();
       if (slab0 == 0) return hipErrorCooperativeLaunchTooLarge;        // the first launch was refused: nothing has run
