@@ -275,11 +275,13 @@ def test_single_launch_equals_per_step(dt, B, n, T):
 
 
 @pytest.mark.parametrize("B,n,T,bidir,direction", [(64, 1000, 12, True, 1), (70, 136, 9, True, 1), (3, 8, 33, True, 1),
-                                                    (150, 264, 5, False, -1), (17, 1024, 6, False, 1), (33, 40, 2, True, 1)])
-def test_float_single_launch_forward(B, n, T, bidir, direction):
-    """Float storage with a zero initial hidden state runs its forward time loop in one launch (n a multiple of 8): rows of
-    length 0, 1 and T, one to three slabs of 64 rows with ragged last slabs, both directions and each alone, an initial cell
-    state; compared with one launch per time step, with the ordinary launch mode, and with the oracle."""
+                                                    (150, 264, 5, False, -1), (17, 1024, 6, False, 1), (33, 40, 2, True, 1),
+                                                    (100, 1000, 4, True, 1)])
+def test_float_single_launch_loops(B, n, T, bidir, direction):
+    """Float storage runs its time loops in one launch each (n a multiple of 8; forward: zero initial hidden state): rows of
+    length 0, 1 and T, one to five slabs of 32 rows with ragged last slabs and, in the last case, more slabs than one launch
+    holds, both directions and each alone, an initial cell state; compared with one launch per time step, with the ordinary
+    launch mode, and with the oracle."""
     rng = np.random.default_rng(7 * B + n + T)
     lens = rng.integers(0, T + 1, B)
     lens[0] = T
@@ -294,8 +296,9 @@ def test_float_single_launch_forward(B, n, T, bidir, direction):
     for k in ("y", "c", "hT", "cT"):
         check(k + " (paths)", f1[k], host(f2[k]), 1e-5)
         check(k + " (launch modes)", f3[k], host(f1[k]), 1e-5)
-    for k in ("dx", "dW_x", "dW_h", "db", "dc0"):
+    for k in ("dx", "dW_x", "dW_h", "db", "dh0", "dc0"):
         check(k + " (paths)", g1[k], host(g2[k]), 1e-5)
+        check(k + " (launch modes)", g3[k], host(g1[k]), 1e-5)
     fo, go = run_oracle(c, bidir, direction)
     compare(f1, g1, fo, go, TOL["f32"])
 
