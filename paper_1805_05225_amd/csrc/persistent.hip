@@ -1934,6 +1934,29 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
   const long fg = (long)B * 4 * n, fy = (long)B * d.lddy, fs = (long)B * n;    // elements per frame
   const unsigned ring_bytes = (unsigned)((B + 15) / 16) * (unsigned)ntile * (unsigned)ntile * 1024u;
   PROF_DECL
+  // The reader of the partial sums that step sigma consumes for row tile k, and their loads: kPre of them go out before the
+  // products of the half step before (what they fetch was published half a step earlier), the rest when their turn comes.
+#ifndef LSTM_BWD_F32_PRE
+#define LSTM_BWD_F32_PRE 6
+#endif
+  constexpr int kPre = LSTM_BWD_F32_PRE;
+  u32x4 x[NCT];
+  auto reader = [&](int sigma, int k) __attribute__((always_inline)) {
+    RingReader rd;
+    const long tile_base = (((long)(rt_base + k) * ntile + J) * ntile) * 64;                   // uint4 index of [row tile][J][0]
+    rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + tile_base), 0, ntile * 1024, kBufFlags);
+    rd.voff = (unsigned)(wave * 1024 + lane * 16);       // load `it` of this wavefront covers producer wave + 4 it
+    rd.it_bytes = 4096u;
+    rd.lim = ntile - wave; rd.lim_step = 4;
+    rd.tag = part_tag(sigma) << 14; rd.err = err; rd.limit = a.spin_limit;
+    rd.nitv = (ntile + 3) / 4; rd.rot = 0;
+    return rd;
+  };
+  auto prefetch = [&](int sigma, int k) __attribute__((always_inline)) {
+    const RingReader rn = reader(sigma, k);
+#pragma unroll
+    for (int it = 0; it < kPre; ++it) x[it] = rn.load_it(it);
+  };
 
   // Steps sigma = 0 .. T-1 work on frames (the last frame in processing order first); step T only collects the Dh that
   // leaves the layer.
@@ -1959,23 +1982,18 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
         dy = ((const float*)d.dy)[t * fy + (long)b * d.lddy + j];
       }
       if (sigma > 0) {                                     // the partial sums of Dh that the step before published
-        RingReader rd;
-        const long tile_base = (((long)(rt_base + k) * ntile + J) * ntile) * 64;                 // uint4 index of [row tile][J][0]
-        rd.rs = __builtin_amdgcn_make_buffer_rsrc((void*)((((sigma - 1) & 1) ? d.ring1 : d.ring0) + tile_base), 0, ntile * 1024, kBufFlags);
-        rd.voff = (unsigned)(wave * 1024 + lane * 16);     // load `it` of this wavefront covers producer wave + 4 it
-        rd.it_bytes = 4096u;
-        rd.lim = ntile - wave; rd.lim_step = 4;
-        rd.tag = part_tag(sigma) << 14; rd.err = err; rd.limit = a.spin_limit;
-        rd.nitv = (ntile + 3) / 4; rd.rot = 0;
+        const RingReader rd = reader(sigma, k);
         const unsigned tagw = rd.tag << 16;
         float ps[4] = {0.f, 0.f, 0.f, 0.f};
         auto add = [&](int, const u32x4& v) __attribute__((always_inline)) {
           ps[0] += __uint_as_float(v[0]); ps[1] += __uint_as_float(v[1] & ~kLLFwdTagBit);
           ps[2] += __uint_as_float(v[2]); ps[3] += __uint_as_float(v[3] & ~kLLFwdTagBit);
         };
-        u32x4 x[NCT];
+        // (a slab of one row tile has no other half step to hide behind: what it consumes is published by the half step
+        // before it, so nothing was issued ahead)
+        if (nrt_here < 2) prefetch(sigma, k);
 #pragma unroll
-        for (int it = 0; it < NCT; ++it) x[it] = rd.load_it(it);
+        for (int it = kPre; it < NCT; ++it) x[it] = rd.load_it(it);
         unsigned long long redo = 0ull;
 #pragma unroll
         for (int it = 0; it < NCT; ++it) {
@@ -2003,6 +2021,11 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
       }
       PROF_MARK(2)
       __syncthreads();
+      // the next half step's first loads: the other row tile's, whose partial sums were published half a step ago
+      if (nrt_here == 2) {
+        const int k_n = k ^ 1, sigma_n = k == 0 ? sigma : sigma + 1;
+        if (sigma_n >= 1 && sigma_n <= T) prefetch(sigma_n, k_n);
+      }
       if (pointwise) {
         // A operand: row lane % 16, gate columns 16 (lane / 16) .. + 15
         float av[16];
