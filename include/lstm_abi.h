@@ -69,7 +69,7 @@ enum {
   LSTM_FLAG_PER_STEP = 2,   /* force one kernel launch per time step (no single-launch loop; the default is
                               * one launch for the whole time loop where a kernel for it exists: bfloat16
                               * storage with n <= 1024; float storage with n a multiple of 8 and
-                              * n <= 1024 - forward with h0 == NULL, backward with B <= 256) */
+                              * n <= 1024, backward with B <= 256) */
   LSTM_FLAG_INFERENCE = 4,  /* *_fwd: nothing is saved for backward; reserve may be NULL         */
   LSTM_FLAG_WEIGHTS_PACKED = 8,/* *_fwd with T == 1 and LSTM_FLAG_INFERENCE: the caller states that the
                               * previous *_fwd call on this workspace had the same T, B, n_in, n, dtype,

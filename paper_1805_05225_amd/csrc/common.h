@@ -180,7 +180,7 @@ struct PFwdArgs {
 };
 hipError_t launch_persist_fwd(const PFwdArgs& a, hipStream_t s);
 bool persist_fwd_fits(const PFwdArgs& a);     // would launch_persist_fwd launch anything on this device?
-// Float storage, zero initial hidden state: Wf is the per-step kernel's packed W_h (launch_pack_wh_fwd), ring0 / ring1 its
+// Float storage (an initial hidden state goes through launch_h0_term, as for bfloat16): Wf is the per-step kernel's packed W_h (launch_pack_wh_fwd), ring0 / ring1 its
 // fragment-ordered h buffers (initialised here), y / hprev float; nkc = chunks of 16 k.
 hipError_t launch_persist_fwd_f32(const PFwdArgs& a, hipStream_t s);
 bool persist_fwd_f32_fits(const PFwdArgs& a);
@@ -230,7 +230,7 @@ hipError_t launch_pack_wh_fwd_ll(const void* W_h, uint4* Wf, int n, int nkc, int
 hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s);
 // gates[first frame of row b][b][:] += bf16(h0[b]) . W_h for every row with a frame (forward: t = 0; reverse: t = len - 1),
 // per direction; gates [T][B][4n] float with `gates_stride` elements between directions.
-hipError_t launch_h0_term(const float* h0, const void* W_h, float* gates, long gates_stride, const int* lens, int T, int B, int n,
+hipError_t launch_h0_term(const float* h0, const void* W_h, bool bf16, float* gates, long gates_stride, const int* lens, int T, int B, int n,
                           int ndir, int rev0, int rev1, hipStream_t s);
 
 // Weight / state packing and small helpers (all enqueue-only).

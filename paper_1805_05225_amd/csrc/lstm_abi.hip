@@ -346,7 +346,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         // goes into the pre-activations of every row's first frame, and the kernels start from zeros in the ring.
         if (h0) {
           Phase ph(LSTM_PHASE_PREP, 1, s);
-          HIPCHK(launch_h0_term((const float*)h0, W_h, gates, gates_stride, seq_lens, p.T, p.B, p.n, p.D, pa.d[0].rev, pa.d[D - 1].rev, s));
+          HIPCHK(launch_h0_term((const float*)h0, W_h, true, gates, gates_stride, seq_lens, p.T, p.B, p.n, p.D, pa.d[0].rev, pa.d[D - 1].rev, s));
         }
         Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
         e = launch_persist_fwd(pa, s);
@@ -361,9 +361,9 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         return LSTM_ERR_HIP;
       }
     }
-    // float storage with a zero initial hidden state: one launch for the whole time loop as well (the kernel works on the
-    // per-step path's packed W_h and h buffers)
-    if (!done && !p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && !h0 && p.n % 8 == 0) {
+    // float storage: one launch for the whole time loop as well (the kernel works on the per-step path's packed W_h and
+    // h buffers)
+    if (!done && !p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.n % 8 == 0) {
       PFwdArgs pa = {};
       pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.nkc = p.nkc_f; pa.T = p.T; pa.ndir = p.D; pa.write_gates = infer ? 0 : 1;
       pa.plain_launch = (desc->flags & LSTM_FLAG_PLAIN_LAUNCH) != 0;
@@ -383,10 +383,15 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
         fd.hprev = infer ? nullptr : rs + d * p.res_dir_stride + p.res_hprev;
         fd.rev = bidir ? d == 1 : desc->direction == -1;
       }
-      hipError_t e;
-      {
+      hipError_t e = hipErrorCooperativeLaunchTooLarge;
+      if (persist_fwd_f32_fits(pa)) {
+        if (h0) {   // (as on the bfloat16 path: the initial state enters through the pre-activations of every row's first frame)
+          Phase ph(LSTM_PHASE_PREP, 1, s);
+          HIPCHK(launch_h0_term((const float*)h0, W_h, false, gates, gates_stride, seq_lens, p.T, p.B, p.n, p.D, pa.d[0].rev, pa.d[D - 1].rev, s));
+        }
         Phase ph(LSTM_PHASE_LOOP_FWD, 1, s);
         e = launch_persist_fwd_f32(pa, s);
+        if (e == hipErrorCooperativeLaunchTooLarge && h0) e = hipErrorLaunchFailure;   // the pre-activations are no longer what the per-step path expects
       }
       if (e == hipSuccess) done = true;
       else if (e == hipErrorCooperativeLaunchTooLarge) {   // nothing of the loop ran, but the h buffers may have been initialised for it

@@ -1717,9 +1717,9 @@ __global__ __launch_bounds__(256) void persist_bwdp16_kernel(PBwdArgs a) {
 // meet in LDS, a thread updates one cell per row tile, and two neighbouring units are published as ONE 8-byte unit of the
 // ring: two float h values, the tag in bit 30 of the second (|h| < 1 leaves the top exponent bit 0, as bit 14 of a
 // bfloat16 value in the other kernels).  The ring is the per-step kernel's fragment-ordered h buffer [row tile][chunk][lane]
-// x 16 bytes, a lane's 16 bytes being two such units, so the reader of the other kernels applies unchanged.  The initial
-// hidden state must be zero (rows that have not started publish their carried state, which must stay below 2 in
-// magnitude); callers with an initial state take the per-step path.
+// x 16 bytes, a lane's 16 bytes being two such units, so the reader of the other kernels applies unchanged.  An initial
+// hidden state never enters the ring (it is not bounded by 1): rows publish zeros until their first frame is done, and
+// launch_h0_term has added h0 W_h to that frame's pre-activations.
 template <int NCH>                                         // chunks per wavefront at most: n <= 64 * NCH
 __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
   __shared__ float red[4][16][65];
@@ -1753,12 +1753,16 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
   float c[2] = {0.f, 0.f}, h[2] = {0.f, 0.f};
   int L[2] = {0, 0};
   bool active[2];
+  // A row publishes zeros until its first frame has been processed: its initial hidden state (not bounded by 1, so not
+  // fit for the ring) reaches that frame through the pre-activations instead (launch_h0_term).
+  bool started[2] = {false, false};
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const int b = (rt_base + k) * 16 + r16;
     active[k] = k < nrt_here && b < B && j < n;
     if (active[k]) {
       c[k] = d.cstate[(long)b * n + j];
+      h[k] = d.hstate[(long)b * n + j];
       L[k] = clamp_len(a.lens, b, T);
     }
   }
@@ -1846,11 +1850,13 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
         o = lstm_cell(zh, zx, c[k]);
         c[k] = o.c; h[k] = o.h;
       }
+      started[k] = started[k] || valid;
       __syncthreads();                // (the accumulators of the other row tile may be written)
       PROF_MARK(2)
       {                               // the recurrence's critical store goes out first (16: agent scope, written through)
-        const unsigned h_odd = (unsigned)__builtin_amdgcn_mov_dpp((int)__float_as_uint(h[k]), 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]: the neighbour's h
-        const u32x2 unit = {__float_as_uint(h[k]), h_odd | (ll_fwd_tag((unsigned)tau + 1u) << 30)};
+        const unsigned h_pub = started[k] ? __float_as_uint(h[k]) : 0u;
+        const unsigned h_odd = (unsigned)__builtin_amdgcn_mov_dpp((int)h_pub, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]: the neighbour's h
+        const u32x2 unit = {h_pub, h_odd | (ll_fwd_tag((unsigned)tau + 1u) << 30)};
         const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((tau & 1) ? d.ring0 : d.ring1), 0, ring_bytes, kBufFlags);
         __builtin_amdgcn_raw_buffer_store_b64(unit, ro, publishes ? (unsigned)(rt_base + k) * (unsigned)nkc * 1024u + pub_in_tile : kParked, 0, 16);
       }
@@ -2112,15 +2118,16 @@ __global__ void pack_state_ll_kernel(uint4* ring0, uint4* ring1, long total) {
 // The initial state's share of the first frame: gates[t0(b)][b][col] += sum_k bf16(h0[b][k]) W_h[k][col], t0 = the row's
 // first frame in processing order.  One thread per column, a row per blockIdx.y; W_h rows are read coalesced.  Runs only
 // when the caller passes an initial state.
-__global__ __launch_bounds__(256) void h0_term_kernel(const float* h0, const bf16_t* W, float* gates, long gates_stride, const int* lens,
+template <typename TW>                                     // bfloat16 storage: h0 rounded as the recurrence would feed it
+__global__ __launch_bounds__(256) void h0_term_kernel(const float* h0, const TW* W, float* gates, long gates_stride, const int* lens,
                                                       int T, int B, int n, int rev0, int rev1) {
   const int col = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y, dir = blockIdx.z;
   const int L = clamp_len(lens, b, T);
   if (col >= 4 * n || L <= 0) return;
   const float* hb = h0 + ((long)dir * B + b) * n;
-  const bf16_t* Wd = W + (long)dir * n * 4 * n + col;
+  const TW* Wd = W + (long)dir * n * 4 * n + col;
   float acc = 0.f;
-  for (int k = 0; k < n; ++k) acc += bf_bits2f(f2bf_bits(hb[k])) * (float)Wd[(long)k * 4 * n];
+  for (int k = 0; k < n; ++k) acc += (sizeof(TW) == 2 ? bf_bits2f(f2bf_bits(hb[k])) : hb[k]) * (float)Wd[(long)k * 4 * n];
   const int t0 = (dir == 0 ? rev0 : rev1) ? L - 1 : 0;
   gates[dir * gates_stride + ((long)t0 * B + b) * 4 * n + col] += acc;
 }
@@ -2356,11 +2363,12 @@ hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, in
   hipLaunchKernelGGL(pack_state_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, ring0, ring1, total);
   return hipGetLastError();
 }
-hipError_t launch_h0_term(const float* h0, const void* W_h, float* gates, long gates_stride, const int* lens, int T, int B, int n,
+hipError_t launch_h0_term(const float* h0, const void* W_h, bool bf16, float* gates, long gates_stride, const int* lens, int T, int B, int n,
                           int ndir, int rev0, int rev1, hipStream_t s) {
   if (B <= 0 || T <= 0) return hipSuccess;
-  hipLaunchKernelGGL(h0_term_kernel, dim3(cdiv(4L * n, 256), B, ndir), dim3(256), 0, s, h0, (const bf16_t*)W_h, gates, gates_stride, lens, T,
-                     B, n, rev0, rev1);
+  const dim3 grid(cdiv(4L * n, 256), B, ndir);
+  if (bf16) hipLaunchKernelGGL(h0_term_kernel<bf16_t>, grid, dim3(256), 0, s, h0, (const bf16_t*)W_h, gates, gates_stride, lens, T, B, n, rev0, rev1);
+  else hipLaunchKernelGGL(h0_term_kernel<float>, grid, dim3(256), 0, s, h0, (const float*)W_h, gates, gates_stride, lens, T, B, n, rev0, rev1);
   return hipGetLastError();
 }
 

@@ -185,7 +185,12 @@ def test_blstm_equals_two_lstm_and_stepping_equals_sequence():
     x = dev(c["x"], dt)
     Wx, Wh, b = dev(c["W_x"][0], dt), dev(c["W_h"][0], dt), dev(c["b"][0])
     h, cc = dev(c["h0"][0]), dev(c["c0"][0])
-    full = Bn.forward(x, Wx, Wh, b, h, cc, None, bidirectional=False, direction=1)
+    # T = 1 calls run the per-step kernel: bit for bit the sequence call on the same kernels (one launch per time step),
+    # and to rounding the sequence call on its default path (one launch for the whole loop, another summation order)
+    full = Bn.forward(x, Wx, Wh, b, h, cc, None, bidirectional=False, direction=1, flags=Bn.FLAG_PER_STEP)
+    full_default = Bn.forward(x, Wx, Wh, b, h, cc, None, bidirectional=False, direction=1)
+    for k in ("y", "hT", "cT"):
+        check(k + " (paths)", full_default[k], host(full[k]), 1e-5)
     ys = []
     for t in range(6):
         s = Bn.forward(x[t:t + 1].clone(), Wx, Wh, b, h, cc, None, bidirectional=False, direction=1,
@@ -278,7 +283,7 @@ def test_single_launch_equals_per_step(dt, B, n, T):
                                                     (150, 264, 5, False, -1), (17, 1024, 6, False, 1), (33, 40, 2, True, 1),
                                                     (100, 1000, 4, True, 1)])
 def test_float_single_launch_loops(B, n, T, bidir, direction):
-    """Float storage runs its time loops in one launch each (n a multiple of 8; forward: zero initial hidden state): rows of
+    """Float storage runs its time loops in one launch each (n a multiple of 8): rows of
     length 0, 1 and T, one to five slabs of 32 rows with ragged last slabs and, in the last case, more slabs than one launch
     holds, both directions and each alone, an initial cell state; compared with one launch per time step, with the ordinary
     launch mode, and with the oracle."""
@@ -288,16 +293,20 @@ def test_float_single_launch_loops(B, n, T, bidir, direction):
     if B > 2:
         lens[1], lens[2] = 0, 1
     c = rnd_case(rng, T=T, B=B, n_in=24, n=n, D=2 if bidir else 1, lens=lens, dt="f32", scale=0.1)
-    c["h0"] = None                                     # (the single-launch kernel is for a zero initial hidden state)
+    if (B + T) % 2:                                    # without an initial hidden state in about half of the cases; with one, its
+        c["h0"] = None                                 # values (N(0, 1/4), many beyond 1 - and times 8 below) never enter the ring
+    else:
+        c["h0"] = c["h0"] * 8.0
+    # (the paths sum in different orders; with initial states of magnitude 10 their pre-activations differ by a few 1e-5)
     print("  float single launch", B, n, T, bidir, direction, flush=True)
     f1, g1 = run_gpu(c, "f32", bidir, direction)
     f2, g2 = run_gpu(c, "f32", bidir, direction, flags=Bn.FLAG_PER_STEP)
     f3, g3 = run_gpu(c, "f32", bidir, direction, flags=Bn.FLAG_PLAIN_LAUNCH)
     for k in ("y", "c", "hT", "cT"):
-        check(k + " (paths)", f1[k], host(f2[k]), 1e-5)
+        check(k + " (paths)", f1[k], host(f2[k]), 5e-5)
         check(k + " (launch modes)", f3[k], host(f1[k]), 1e-5)
     for k in ("dx", "dW_x", "dW_h", "db", "dh0", "dc0"):
-        check(k + " (paths)", g1[k], host(g2[k]), 1e-5)
+        check(k + " (paths)", g1[k], host(g2[k]), 5e-5)
         check(k + " (launch modes)", g3[k], host(g1[k]), 1e-5)
     fo, go = run_oracle(c, bidir, direction)
     compare(f1, g1, fo, go, TOL["f32"])
