@@ -11,7 +11,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmi355x_lstm.so")
-SOURCES = ["gemm.hip", "gemm_nt.hip", "gemm_skinny.hip", "recurrent.hip", "persistent.hip", "single_step.hip", "time_pool.hip", "attention.hip", "beam.hip", "lstm_abi.hip"]
+SOURCES = ["gemm.hip", "gemm_nt.hip", "gemm_skinny.hip", "gemm_float.hip", "recurrent.hip", "persistent.hip", "single_step.hip", "time_pool.hip", "attention.hip", "beam.hip", "lstm_abi.hip"]
 # packed-FP32 instructions are switched off: some of their forms have produced wrong results on the test machines
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -74,6 +74,11 @@ hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s);
 // float C.  Row k of both operands is row k_rows[k] in memory if k_rows is given (launch_gemm routes to it by itself).
 bool gemm_tn_ok(const GemmArgs& g);
 hipError_t launch_gemm_tn(const GemmArgs& g, hipStream_t s);
+// Float storage (gemm_float.hip): operands as they lie in memory, rows 16-byte aligned, extents along 16-byte chunks
+// multiples of 4 (K for a k-contiguous operand, M / N for a k-major one); row maps, device-resident M / K, segments
+// and atomic K ranges as above (launch_gemm routes to it by itself; what it does not take goes to the generic kernel).
+bool gemm_float_ok(const GemmArgs& g);
+hipError_t launch_gemm_float(const GemmArgs& g, hipStream_t s);
 // Products with few rows (gemm_skinny.hip): both operands k-contiguous bfloat16 with 16-byte aligned rows, K % 8 == 0,
 // M <= kSkinnyMaxRows, one segment, no row maps, no K ranges: a work-group owns 96 x 128 of C for the whole K, so bias,
 // max(0, .) and the rounding to bfloat16 happen in its epilogue (launch_gemm routes such problems to it by itself).

@@ -339,6 +339,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (gemm_skinny_ok(g)) return launch_gemm_skinny(g, false, s);
   if (gemm_nt_ok(g)) return launch_gemm_nt(g, s);
   if (gemm_tn_ok(g)) return launch_gemm_tn(g, s);
+  if (gemm_float_ok(g)) return launch_gemm_float(g, s);
   if (g.in_bf16) {
     if (g.out_bf16) return dispatch<bf16_t, bf16_t>(g, s);
     return dispatch<bf16_t, float>(g, s);

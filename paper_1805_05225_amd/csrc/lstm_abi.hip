@@ -132,6 +132,9 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
     // rows' tiles do any work: 384 instead of 256 work-groups are aimed at.  Config 3: 160 tiles, 96 of them real, two
     // ranges instead of one: dX 1.44 -> 0.89 ms per step.)
     p->ks_dx = fg && !infer && p->bf16 && tiles > 0 ? (int)std::max(1L, std::min(std::min(384 / tiles, stages / 16), 8L)) : 1;
+    // float storage: 128 x 128 tiles; with fewer than 512 of them each XCD takes an eighth of K for all tiles (gemm_float.hip)
+    const long tiles_f = (long)cdiv(TB, 128) * cdiv(d->n_in, 128), stages_f = (long)p->D * cdiv(4L * d->n, 32);
+    if (!p->bf16 && !infer && tiles_f > 0 && tiles_f < 512 && stages_f >= 64) p->ks_dx = 8;
   }
   p->ks_dwx = fg && !infer ? ksplit_for(d->n_in, 4L * d->n) : 1;
   p->ks_dwh = fg && !infer ? ksplit_for(d->n, 4L * d->n) : 1;
@@ -603,7 +606,11 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = TB; g.m_dev = count;
     }
     if (p.ks_dx > 1 && gemm_nt_ok(g)) { g.ksplit = p.ks_dx; g.parts = (float*)(ws + p.ws_parts); }
-    if (!p.bf16) {
+    if (!p.bf16 && p.ks_dx == 8) {
+      g.ksplit = 8; g.parts = (float*)(ws + p.ws_parts);
+      if (!gemm_float_ok(g)) { g.ksplit = 0; g.parts = nullptr; }
+    }
+    if (!p.bf16 && !g.parts) {
       // float storage, generic kernel: rows = frames and n_in columns give few 128 x 128 tiles (config 2: 85 with real
       // frames), so K = 4n per direction is cut into ranges that add their parts to the zero-filled dx atomically
       const long tiles = (long)cdiv(TB, 128) * cdiv(p.n_in, 128), stages = (long)p.D * cdiv(4L * p.n, 32);

@@ -97,6 +97,8 @@ def test_gemm_layouts(dt, M, N, K):
     C0 = torch.from_numpy(rng.standard_normal((M, N))).float().cuda()
     C = Bn.gemm(Ad.t().contiguous(), Bd, a_kcontig=False, b_kcontig=False, M=M, N=N, K=K, C=C0.clone(), accumulate=True)
     check("TN+acc", C, (ref + C0.cpu().double()).numpy(), tol)
+    C = Bn.gemm(Ad.t().contiguous(), Bd, a_kcontig=False, b_kcontig=False, M=M, N=N, K=K)
+    check("TN", C, ref.numpy(), tol)
     if dt == "bf16":
         C = Bn.gemm(Ad, Bd.t().contiguous(), a_kcontig=True, b_kcontig=True, M=M, N=N, K=K, out_dtype=torch.bfloat16)
         check("NT->bf16", C, ref.numpy(), 1e-2)
