@@ -229,6 +229,31 @@ constexpr int kPrepDelay = LSTM_PREP_DELAY;
 #ifndef LSTM_OPERAND_NOPS
 #define LSTM_OPERAND_NOPS "7"
 #endif
+// s_waitcnt vmcnt(n) for an n that is constant after unrolling (0 .. 15; the instruction takes an immediate).
+// Where a kernel consumes a ring load while younger stores are in flight it waits with this, n = the number of
+// YOUNGER LOADS: loads return in the order of issue among themselves, but stores were seen to be acknowledged ahead of
+// older loads that bypass L2, so a count that includes the younger stores - what the compiler emits - can be reached
+// while the load is still on its way.
+__device__ __forceinline__ void wait_loads_but(int n) {
+  switch (n < 15 ? n : 15) {
+    case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+    case 1: __builtin_amdgcn_s_waitcnt(0x0f71); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0f72); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0f73); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0f74); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x0f75); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0f76); break;
+    case 7: __builtin_amdgcn_s_waitcnt(0x0f77); break;
+    case 8: __builtin_amdgcn_s_waitcnt(0x0f78); break;
+    case 9: __builtin_amdgcn_s_waitcnt(0x0f79); break;
+    case 10: __builtin_amdgcn_s_waitcnt(0x0f7a); break;
+    case 11: __builtin_amdgcn_s_waitcnt(0x0f7b); break;
+    case 12: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
+    case 13: __builtin_amdgcn_s_waitcnt(0x0f7d); break;
+    case 14: __builtin_amdgcn_s_waitcnt(0x0f7e); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0f7f); break;
+  }
+}
 // f(integral_constant<0>) ... f(integral_constant<N - 1>): a loop whose counter is a constant expression in the body
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -1824,6 +1849,7 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
       unsigned long long redo = 0ull;
 #pragma unroll
       for (int it = 0; it < NCH; ++it) {
+        wait_loads_but(NCH - 1 - it);                      // (the first half went out before the last half step's stores)
         if (__builtin_amdgcn_ballot_w64(rd.tag_diff(x[it], it, tagw) != 0u) == 0ull) use(it, x[it]);
         else { redo |= 1ull << it; PROF_REDO(1) }
       }
@@ -1940,13 +1966,20 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
   const long fg = (long)B * 4 * n, fy = (long)B * d.lddy, fs = (long)B * n;    // elements per frame
   const unsigned ring_bytes = (unsigned)((B + 15) / 16) * (unsigned)ntile * (unsigned)ntile * 1024u;
   PROF_DECL
-  // The reader of the partial sums that step sigma consumes for row tile k, and their loads: kPre of them go out before the
-  // products of the half step before (what they fetch was published half a step earlier), the rest when their turn comes.
-#ifndef LSTM_BWD_F32_PRE
-#define LSTM_BWD_F32_PRE 6
+  // The reader of the partial sums that step sigma consumes for row tile k.  In a slab of two row tiles they are collected
+  // DURING the products of the half step before (the other row tile's): what they fetch was published half a step
+  // earlier, the loads run kWin ahead of the additions, one load and one addition behind each column tile's MFMAs, and
+  // the matrix cores do not wait for the exchange.  `ps_c` / `redo_c` carry the sums (and which loads came back with
+  // a stale tag) into the next half step.
+#ifndef LSTM_BWD_F32_WIN
+#define LSTM_BWD_F32_WIN 6
 #endif
-  constexpr int kPre = LSTM_BWD_F32_PRE;
+  constexpr int kWin = LSTM_BWD_F32_WIN;
+  static_assert(kWin >= 1 && kWin <= 16 && kWin <= NCT, "wait_loads_but covers up to 15 younger loads");
   u32x4 x[NCT];
+  float ps_c[4] = {0.f, 0.f, 0.f, 0.f};
+  unsigned long long redo_c = 0ull;
+  bool have_c = false;
   auto reader = [&](int sigma, int k) __attribute__((always_inline)) {
     RingReader rd;
     const long tile_base = (((long)(rt_base + k) * ntile + J) * ntile) * 64;                   // uint4 index of [row tile][J][0]
@@ -1958,10 +1991,9 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
     rd.nitv = (ntile + 3) / 4; rd.rot = 0;
     return rd;
   };
-  auto prefetch = [&](int sigma, int k) __attribute__((always_inline)) {
-    const RingReader rn = reader(sigma, k);
-#pragma unroll
-    for (int it = 0; it < kPre; ++it) x[it] = rn.load_it(it);
+  auto add_to = [](float (&ps)[4], const u32x4& v) __attribute__((always_inline)) {
+    ps[0] += __uint_as_float(v[0]); ps[1] += __uint_as_float(v[1] & ~kLLFwdTagBit);
+    ps[2] += __uint_as_float(v[2]); ps[3] += __uint_as_float(v[3] & ~kLLFwdTagBit);
   };
 
   // Steps sigma = 0 .. T-1 work on frames (the last frame in processing order first); step T only collects the Dh that
@@ -1990,21 +2022,22 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
       if (sigma > 0) {                                     // the partial sums of Dh that the step before published
         const RingReader rd = reader(sigma, k);
         const unsigned tagw = rd.tag << 16;
-        float ps[4] = {0.f, 0.f, 0.f, 0.f};
-        auto add = [&](int, const u32x4& v) __attribute__((always_inline)) {
-          ps[0] += __uint_as_float(v[0]); ps[1] += __uint_as_float(v[1] & ~kLLFwdTagBit);
-          ps[2] += __uint_as_float(v[2]); ps[3] += __uint_as_float(v[3] & ~kLLFwdTagBit);
-        };
-        // (a slab of one row tile has no other half step to hide behind: what it consumes is published by the half step
-        // before it, so nothing was issued ahead)
-        if (nrt_here < 2) prefetch(sigma, k);
+        float ps[4] = {ps_c[0], ps_c[1], ps_c[2], ps_c[3]};
+        unsigned long long redo = redo_c;
+        auto add = [&](int, const u32x4& v) __attribute__((always_inline)) { add_to(ps, v); };
+        if (!have_c) {
+          // nothing was collected ahead: a slab of one row tile has no other half step to hide behind (what it consumes
+          // is published by the half step before it), and the collecting step follows no products
 #pragma unroll
-        for (int it = kPre; it < NCT; ++it) x[it] = rd.load_it(it);
-        unsigned long long redo = 0ull;
+          for (int v = 0; v < 4; ++v) ps[v] = 0.f;
+          redo = 0ull;
 #pragma unroll
-        for (int it = 0; it < NCT; ++it) {
-          if (__builtin_amdgcn_ballot_w64(rd.tag_diff(x[it], it, tagw) != 0u) == 0ull) add(it, x[it]);
-          else { redo |= 1ull << it; PROF_REDO(1) }
+          for (int it = 0; it < NCT; ++it) x[it] = rd.load_it(it);
+#pragma unroll
+          for (int it = 0; it < NCT; ++it) {
+            if (__builtin_amdgcn_ballot_w64(rd.tag_diff(x[it], it, tagw) != 0u) == 0ull) add(it, x[it]);
+            else { redo |= 1ull << it; PROF_REDO(1) }
+          }
         }
         if (redo) rd.template fix_up_batch<NCT>(redo, dead, add);
         // a lane's sums: rows 4 (lane / 16) + v of output lane % 16
@@ -2027,12 +2060,19 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
       }
       PROF_MARK(2)
       __syncthreads();
-      // the next half step's first loads: the other row tile's, whose partial sums were published half a step ago
-      if (nrt_here == 2) {
-        const int k_n = k ^ 1, sigma_n = k == 0 ? sigma : sigma + 1;
-        if (sigma_n >= 1 && sigma_n <= T) prefetch(sigma_n, k_n);
-      }
+      have_c = false;
       if (pointwise) {
+        // what the next half step consumes (the other row tile's partial sums, published half a step ago) is collected here
+        const int k_n = k ^ 1, sigma_n = k == 0 ? sigma : sigma + 1;
+        const bool collect = nrt_here == 2 && sigma_n >= 1 && sigma_n <= T;
+        const RingReader rn = reader(sigma_n, k_n);
+        const unsigned tagw_n = rn.tag << 16;
+        float psn[4] = {0.f, 0.f, 0.f, 0.f};
+        unsigned long long redo_n = 0ull;
+        if (collect) {
+#pragma unroll
+          for (int it = 0; it < kWin; ++it) x[it] = rn.load_it(it);
+        }
         // A operand: row lane % 16, gate columns 16 (lane / 16) .. + 15
         float av[16];
 #pragma unroll
@@ -2049,9 +2089,21 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
           f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s], w[ci][s], acc, 0, 0, 0);
+          if (collect) {                                   // (behind the MFMAs just issued: they run while this does)
+            wait_loads_but((NCT - 1 - ci) < (kWin - 1) ? (NCT - 1 - ci) : (kWin - 1));     // the younger loads: the window's others
+            if (__builtin_amdgcn_ballot_w64(rn.tag_diff(x[ci % kWin], ci, tagw_n) != 0u) == 0ull) add_to(psn, x[ci % kWin]);
+            else { redo_n |= 1ull << ci; PROF_REDO(1) }
+            if (ci + kWin < NCT) x[ci % kWin] = rn.load_it(ci + kWin);
+          }
           const u32x4 unit = {__float_as_uint(acc[0]), __float_as_uint(acc[1]) | tag_hi, __float_as_uint(acc[2]), __float_as_uint(acc[3]) | tag_hi};
           const unsigned off = wave + 4 * ci < ntile ? pub0 + (unsigned)(4 * ci) * (unsigned)ntile * 1024u : 0x7ff00000u;
           __builtin_amdgcn_raw_buffer_store_b128(unit, ro, off, 0, 16);    // 16: agent scope, written through
+        }
+        if (collect) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) ps_c[v] = psn[v];
+          redo_c = redo_n;
+          have_c = true;
         }
       }
       PROF_MARK(1)
