@@ -504,7 +504,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   const size_t frag_dir = (size_t)p.nrt * p.nkc_b * 1024;
   char* DZ = ws + p.ws_DZ;
   bool done = false;
-  const bool db_in_loop = use_ll && 2 * p.nrt <= kColsumSlices;   // the bfloat16 single-launch kernel also sums the bias gradient
+  const bool db_in_loop = (use_ll || use_ll32) && 2 * p.nrt <= kColsumSlices;   // the single-launch kernels also sum the bias gradient
   if (use_ll || use_ll32) {
     const size_t ring_dir = use_ll ? bwdp_ring_bytes(p.B, p.n) : bwd_f32_ring_bytes(p.B, p.n);
     const size_t wb_dir = use_ll ? bwdp_wh_bytes(p.n) : bwd_f32_wh_bytes(p.n);

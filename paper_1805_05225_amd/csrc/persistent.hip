@@ -1803,6 +1803,10 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
   // The first half of a half step's ring loads goes out before the reduction and the cell update of the half step
   // before it (their values were published half a step earlier) and is there when the products begin; the second half
   // goes out then and arrives behind the first half's products.  (All of them early does not fit the register file.)
+#ifndef LSTM_FWD_F32_EARLY
+#define LSTM_FWD_F32_EARLY (NCH / 2)
+#endif
+  constexpr int kEarly = LSTM_FWD_F32_EARLY;
   u32x4 x[NCH];
   auto reader = [&](int tau, int k) __attribute__((always_inline)) {
     return make_reader(((tau & 1) ? d.ring1 : d.ring0) + (long)(rt_base + k) * nkc * 64, nkc, (n + 3) / 4, wave, lane,
@@ -1811,7 +1815,7 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
   auto issue_loads = [&](int tau, int k) __attribute__((always_inline)) {
     const RingReader rn = reader(tau, k);
 #pragma unroll
-    for (int it = 0; it < NCH / 2; ++it) x[it] = rn.load_it(it);
+    for (int it = 0; it < kEarly; ++it) x[it] = rn.load_it(it);
   };
   if (T > 0) issue_loads(0, 0);
 
@@ -1844,7 +1848,7 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
           }
       };
 #pragma unroll
-      for (int it = NCH / 2; it < NCH; ++it) x[it] = rd.load_it(it);
+      for (int it = kEarly; it < NCH; ++it) x[it] = rd.load_it(it);
       // a load with a stale tag is fetched again (bounded) - rare, since the values were published half a step ago
       unsigned long long redo = 0ull;
 #pragma unroll
@@ -1951,6 +1955,7 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
   const int r16 = tid >> 4, u = tid & 15;
   const int j = J * 16 + u;
   float Dh[2] = {0.f, 0.f}, Dc[2] = {0.f, 0.f};
+  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};                    // bias gradient of this thread's unit over its two rows and all frames
   int L[2] = {0, 0};
   bool active[2];
 #pragma unroll
@@ -2052,6 +2057,8 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
       if (valid) lstm_cell_grad(gi, gf, gg, go, c_new, c_prev, dy + Dh[k], Dc[k], dz);
       if (pointwise) {
 #pragma unroll
+        for (int q = 0; q < 4; ++q) dbsum[q] += dz[q];       // (zero where the frame is padding)
+#pragma unroll
         for (int q = 0; q < 4; ++q) zb[r16][q * 16 + u] = dz[q];
         if (active[k]) {
           float* zp = (float*)d.DZ + t * fg + (long)b * 4 * n + j;
@@ -2117,6 +2124,19 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
       d.Dh[(long)b * n + j] = Dh[k];
       d.Dc[(long)b * n + j] = Dc[k];
     }
+  if (d.dbpart) {                       // bias gradient: this work-group's 32 rows summed into the first of the slab's four slices (the others stay zero)
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) zb[r16][q * 16 + u] = dbsum[q];
+    __syncthreads();
+    if (tid < 64) {
+      const int q = tid >> 4, uu = tid & 15, jj = J * 16 + uu;
+      float sum = 0.f;
+#pragma unroll
+      for (int rr = 0; rr < 16; ++rr) sum += zb[rr][q * 16 + uu];
+      if (jj < n) d.dbpart[(long)2 * rt_base * 4 * n + q * n + jj] = sum;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
