@@ -191,7 +191,7 @@ hipError_t launch_persist_fwd_f32(const PFwdArgs& a, hipStream_t s);
 bool persist_fwd_f32_fits(const PFwdArgs& a);
 
 struct PBwdDir {
-  const uint4* Wb;    // as launch_pack_wh_bwdp writes it
+  const uint4* Wb;    // as launch_prep_bwd_ll writes it
   uint4* ring0; uint4* ring1;
   const float* gates; const float* cs; const float* c0;
   const void* dy; long lddy;
@@ -209,11 +209,10 @@ struct PBwdArgs {
   int rt0;            // set by the launcher: first 16-row tile of the batch that this launch handles
   bool plain_launch;  // ordinary instead of cooperative launch (the caller vouches that the device is otherwise idle)
 };
-// Does the single-launch backward kernel (partial sums of Dh exchanged; W_h via launch_pack_wh_bwdp, ring of
+// Does the single-launch backward kernel (partial sums of Dh exchanged; W_h via launch_prep_bwd_ll, ring of
 // bwdp_ring_bytes per direction and slot) fit the device for this problem?
 bool persist_bwd_fits(const PBwdArgs& a);
 hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s);
-hipError_t launch_pack_wh_bwdp(const void* W_h, uint4* Wb, int n, int ndir, hipStream_t s);
 // Float storage: the same exchange of partial sums in float.  W_h^T via launch_pack_wh_bwd_f32p (bwd_f32_wh_bytes per
 // direction), rings of bwd_f32_ring_bytes per direction and slot, zero-filled; gates, cs, dy, DZ float; dbpart unused.
 bool persist_bwd_f32_fits(const PBwdArgs& a);
@@ -229,10 +228,8 @@ inline size_t bwdp_ring_bytes(int B, int n) {                                   
   const size_t groups = 2 * (size_t)(((B > 0 ? B : 1) + 15) / 16), tiles = (size_t)((n + 31) / 32);
   return groups * tiles * tiles * 512;
 }
-hipError_t launch_pack_wh_fwd_ll(const void* W_h, uint4* Wf, int n, int nkc, int ndir, hipStream_t s);
-// ring slot 0 = zeros carrying the tag of step 0, ring slot 1 cleared.  (The initial state does not travel through the ring:
-// launch_h0_term adds its product with W_h to the pre-activations of every row's first frame instead.)
-hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s);
+// (launch_prep_fwd_ll: W_h in ring order; ring slot 0 = zeros carrying the tag of step 0, ring slot 1 cleared.  The initial state does
+// not travel through the ring: launch_h0_term adds its product with W_h to the pre-activations of every row's first frame instead.)
 // gates[first frame of row b][b][:] += bf16(h0[b]) . W_h for every row with a frame (forward: t = 0; reverse: t = len - 1),
 // per direction; gates [T][B][4n] float with `gates_stride` elements between directions.
 hipError_t launch_h0_term(const float* h0, const void* W_h, bool bf16, float* gates, long gates_stride, const int* lens, int T, int B, int n,
@@ -260,6 +257,10 @@ struct ZeroRegions {
   void add(void* p, size_t bytes);
 };
 hipError_t launch_fill_zero_many(const ZeroRegions& r, hipStream_t s);
+// The set-up of a bfloat16 single-launch loop in one launch: the fills of `z`, W_h in the kernel's order and (forward) the initial ring.
+hipError_t launch_prep_fwd_ll(const ZeroRegions& z, const void* W, uint4* Wf, int n, int nkc, int ndir, uint4* ring0, uint4* ring1,
+                              int nrt, hipStream_t s);
+hipError_t launch_prep_bwd_ll(const ZeroRegions& z, const void* W, uint4* Wb, int n, int ndir, hipStream_t s);
 // db[c] (+)= sum_rows DZ[row][c]; part = float scratch [nsplit][ncols] per direction
 // db[dir][c] (+)= sum over the first nslices slices of part[dir][kColsumSlices][ncols]
 constexpr int kColsumSlices = 64;

@@ -261,24 +261,23 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     if (c0) HIPCHK(launch_copy(cstate, c0, state_bytes, s)); else z.add(cstate, state_bytes);
     if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd)
       z.add(ws + p.ws_Wf + p.Wf_bytes, 1024);              // the chunk of zeros behind the packed W_h (single-launch path)
-    HIPCHK(launch_fill_zero_many(z, s));
+    // (on the single-launch path the fills, the packed W_h and the initial ring are one launch)
+    if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd)
+      HIPCHK(launch_prep_fwd_ll(z, W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_ll_f, p.D, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1),
+                                p.nrt, s));
+    else HIPCHK(launch_fill_zero_many(z, s));
   }
   // single-launch path: bf16 storage, at least two steps, register budget of the kernel
   bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd;
-  auto pack_fwd = [&](bool ll) -> int {
+  auto pack_fwd = [&]() -> int {            // the per-step kernels' order (also what a single-launch path that does not start falls back to)
     Phase ph(LSTM_PHASE_PREP, 2, s);
-    if (ll) {
-      HIPCHK(launch_pack_wh_fwd_ll(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_ll_f, p.D, s));
-      HIPCHK(launch_pack_state_ll((uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.nkc_ll_f, p.nrt, p.D, s));
-    } else {
-      HIPCHK(launch_pack_wh_fwd(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_f, p.D, p.bf16, s));
-      HIPCHK(launch_pack_state(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_f, p.nrt,
-                               p.D, p.bf16, s));
-    }
+    HIPCHK(launch_pack_wh_fwd(W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_f, p.D, p.bf16, s));
+    HIPCHK(launch_pack_state(hstate, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1), p.B, p.n, p.nkc_f, p.nrt,
+                             p.D, p.bf16, s));
     return LSTM_OK;
   };
-  if (T > 0) {
-    if ((rc = pack_fwd(use_ll))) return rc;
+  if (T > 0 && !use_ll) {
+    if ((rc = pack_fwd())) return rc;
   }
   if (T > 0) {
     // hoisted input projection for all frames and both directions: Zx = X W_x + b
@@ -358,7 +357,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       if (e == hipSuccess) done = true;
       else if (e == hipErrorCooperativeLaunchTooLarge) {   // nothing was launched (does not fit on the device all at once): one launch per step
         (void)hipGetLastError();
-        if ((rc = pack_fwd(false))) return rc;
+        if ((rc = pack_fwd())) return rc;
       } else {                                      // a later batch slab failed after earlier ones ran: no second attempt on advanced state
         (void)hipGetLastError();
         return LSTM_ERR_HIP;
@@ -399,7 +398,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       if (e == hipSuccess) done = true;
       else if (e == hipErrorCooperativeLaunchTooLarge) {   // nothing of the loop ran, but the h buffers may have been initialised for it
         (void)hipGetLastError();
-        if ((rc = pack_fwd(false))) return rc;
+        if ((rc = pack_fwd())) return rc;
       } else {
         (void)hipGetLastError();
         return LSTM_ERR_HIP;
@@ -473,17 +472,6 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     }
     return LSTM_OK;
   }
-  {
-    Phase ph(LSTM_PHASE_PREP, 5, s);
-    ZeroRegions z;
-    z.add(ws + p.ws_sync, p.sync_bytes);
-    if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else z.add(Dh, state_bytes);
-    if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else z.add(Dc, state_bytes);
-    z.add(ws + p.ws_dzfrag0, p.dzfrag_bytes);
-    z.add(ws + p.ws_dzfrag1, p.dzfrag_bytes);
-    if (2 * p.nrt <= kColsumSlices) z.add(ws + p.ws_colsum, D * kColsumSlices * 4 * n * 4);   // bias-gradient slices of row groups the grid lacks
-    HIPCHK(launch_fill_zero_many(z, s));
-  }
   // single-launch path: bf16 storage, at least two steps, and the kernel fits the device
   PBwdArgs pa = {};
   pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.T = p.T; pa.ndir = p.D;
@@ -495,9 +483,21 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   const bool use_ll32 = !p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.n % 8 == 0 && p.n <= 1024 && p.B <= 256 &&
                         persist_bwd_f32_fits(pa);
   {
+    Phase ph(LSTM_PHASE_PREP, 5, s);
+    ZeroRegions z;
+    z.add(ws + p.ws_sync, p.sync_bytes);
+    if (dhT) HIPCHK(launch_copy(Dh, dhT, state_bytes, s)); else z.add(Dh, state_bytes);
+    if (dcT) HIPCHK(launch_copy(Dc, dcT, state_bytes, s)); else z.add(Dc, state_bytes);
+    z.add(ws + p.ws_dzfrag0, p.dzfrag_bytes);
+    z.add(ws + p.ws_dzfrag1, p.dzfrag_bytes);
+    if (2 * p.nrt <= kColsumSlices) z.add(ws + p.ws_colsum, D * kColsumSlices * 4 * n * 4);   // bias-gradient slices of row groups the grid lacks
+    // (the bfloat16 single-launch path clears and packs W_h^T in one launch)
+    if (use_ll) HIPCHK(launch_prep_bwd_ll(z, W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, s));
+    else HIPCHK(launch_fill_zero_many(z, s));
+  }
+  if (!use_ll) {
     Phase ph(LSTM_PHASE_PREP, 1, s);
-    if (use_ll) HIPCHK(launch_pack_wh_bwdp(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, s));
-    else if (use_ll32) HIPCHK(launch_pack_wh_bwd_f32p(W_h, ws + p.ws_Wb, p.n, p.D, s));
+    if (use_ll32) HIPCHK(launch_pack_wh_bwd_f32p(W_h, ws + p.ws_Wb, p.n, p.D, s));
     else HIPCHK(launch_pack_wh_bwd(W_h, (uint4*)(ws + p.ws_Wb), p.n, p.nkc_b, p.D, p.bf16, s));
   }
 

@@ -2142,8 +2142,7 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
 // ------------------------------------------------------------------------------------------------
 // packing for the ring layout
 // forward weights: chunk index = (((dir*ntile + tile)*4 + q)*nkc + kc)*64 + lane
-__global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nkc, long total) {
-  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void pack_wh_fwd_ll_body(long idx, const bf16_t* W, uint4* out, int n, int nkc, long total) {
   if (idx >= total) return;
   const int lane = idx & 63;
   long rest = idx >> 6;
@@ -2163,8 +2162,7 @@ __global__ void pack_wh_fwd_ll_kernel(const bf16_t* W, uint4* out, int n, int nk
 }
 // partial-sum backward kernel: chunk index = ((((dir*ntile2 + J)*4 + wave)*4 + kc)*16 + c)*64 + lane ; B fragment of
 // gate kc, K = the 32 units of tile J, columns = outputs (wave*16 + c)*16 .. +15
-__global__ void pack_wh_bwdp_kernel(const bf16_t* W, uint4* out, int n, int ntile2, long total) {
-  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void pack_wh_bwdp_body(long idx, const bf16_t* W, uint4* out, int n, int ntile2, long total) {
   if (idx >= total) return;
   const int lane = idx & 63, c = (idx >> 6) & 15, kc = (idx >> 10) & 3, wave = (idx >> 12) & 3;
   const long rest = idx >> 14;
@@ -2181,11 +2179,39 @@ __global__ void pack_wh_bwdp_kernel(const bf16_t* W, uint4* out, int n, int ntil
   out[idx] = *(uint4*)v;
 }
 // Initial contents of the forward ring, one 8-byte unit per thread: slot 0 = zeros that carry the tag of step 0, slot 1 = zeros.
-__global__ void pack_state_ll_kernel(uint4* ring0, uint4* ring1, long total) {
-  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void pack_state_ll_body(long idx, uint4* ring0, uint4* ring1, long total) {
   if (idx >= total) return;
   ((unsigned long long*)ring0)[idx] = (unsigned long long)(ll_fwd_tag(0u) * kLLFwdTagBit) << 32;
   ((unsigned long long*)ring1)[idx] = 0ull;
+}
+// Everything a bfloat16 single-launch loop needs set up, in ONE launch (three kernels in a row cost three start-ups and run one
+// after the other; none of them depends on another): blocks [0, first_pack) clear the regions of `z` (as fill_zero_many_kernel does),
+// blocks [first_pack, first_ring) bring W_h into the kernel's order (forward: ring order; backward: the partial-sum kernel's),
+// blocks from first_ring on (forward only) write the initial ring.
+struct PrepArgs {
+  ZeroRegions z;
+  const bf16_t* W; uint4* Wout; int n, nk; long w_total;   // nk: nkc (forward) / ntile2 (backward)
+  uint4* ring0; uint4* ring1; long ring_total;
+  int first_pack, first_ring, backward;
+};
+__global__ __launch_bounds__(256) void prep_ll_kernel(PrepArgs a) {
+  const int bid = blockIdx.x;
+  if (bid < a.first_pack) {
+    int k = 0;
+#pragma unroll
+    for (int j = 1; j < ZeroRegions::kMax; ++j)
+      if (j < a.z.count && bid >= a.z.first_block[j]) k = j;
+    uint32_t* p = (uint32_t*)a.z.ptr[k];
+    const size_t nwords = a.z.words[k];
+    const size_t nb = (size_t)(a.z.first_block[k + 1] - a.z.first_block[k]);
+    for (size_t i = (size_t)(bid - a.z.first_block[k]) * 256 + threadIdx.x; i < nwords; i += nb * 256) p[i] = 0u;
+  } else if (bid < a.first_ring) {
+    const long idx = (long)(bid - a.first_pack) * 256 + threadIdx.x;
+    if (a.backward) pack_wh_bwdp_body(idx, a.W, a.Wout, a.n, a.nk, a.w_total);
+    else pack_wh_fwd_ll_body(idx, a.W, a.Wout, a.n, a.nk, a.w_total);
+  } else {
+    pack_state_ll_body((long)(bid - a.first_ring) * 256 + threadIdx.x, a.ring0, a.ring1, a.ring_total);
+  }
 }
 // The initial state's share of the first frame: gates[t0(b)][b][col] += sum_k bf16(h0[b][k]) W_h[k][col], t0 = the row's
 // first frame in processing order.  One thread per column, a row per blockIdx.y; W_h rows are read coalesced.  Runs only
@@ -2319,15 +2345,26 @@ hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s) {
   }
   return coop_slabs(persist_bwdp_kernel<8>, t32, 8, a, s);
 }
-hipError_t launch_pack_wh_bwdp(const void* W, uint4* Wb, int n, int ndir, hipStream_t s) {
-  const int ntile2 = cdiv(n, 32);
-  long total = (long)ndir * ntile2 * 4 * 4 * 16 * 64;
-  hipLaunchKernelGGL(pack_wh_bwdp_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wb, n, ntile2, total);
+hipError_t launch_prep_fwd_ll(const ZeroRegions& z, const void* W, uint4* Wf, int n, int nkc, int ndir, uint4* ring0, uint4* ring1,
+                              int nrt, hipStream_t s) {
+  if (z.overflow) return hipErrorInvalidValue;
+  PrepArgs a = {};
+  a.z = z; a.W = (const bf16_t*)W; a.Wout = Wf; a.n = n; a.nk = nkc; a.w_total = (long)ndir * cdiv(n, 16) * 4 * nkc * 64;
+  a.ring0 = ring0; a.ring1 = ring1; a.ring_total = (long)ndir * nrt * nkc * 64 * 2;
+  a.first_pack = z.count ? z.first_block[z.count] : 0;
+  a.first_ring = a.first_pack + cdiv(a.w_total, 256);
+  a.backward = 0;
+  hipLaunchKernelGGL(prep_ll_kernel, dim3(a.first_ring + cdiv(a.ring_total, 256)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
-hipError_t launch_pack_wh_fwd_ll(const void* W, uint4* Wf, int n, int nkc, int ndir, hipStream_t s) {
-  long total = (long)ndir * cdiv(n, 16) * 4 * nkc * 64;
-  hipLaunchKernelGGL(pack_wh_fwd_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)W, Wf, n, nkc, total);
+hipError_t launch_prep_bwd_ll(const ZeroRegions& z, const void* W, uint4* Wb, int n, int ndir, hipStream_t s) {
+  if (z.overflow) return hipErrorInvalidValue;
+  PrepArgs a = {};
+  a.z = z; a.W = (const bf16_t*)W; a.Wout = Wb; a.n = n; a.nk = cdiv(n, 32); a.w_total = (long)ndir * a.nk * 4 * 4 * 16 * 64;
+  a.first_pack = z.count ? z.first_block[z.count] : 0;
+  a.first_ring = a.first_pack + cdiv(a.w_total, 256);
+  a.backward = 1;
+  hipLaunchKernelGGL(prep_ll_kernel, dim3(a.first_ring), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 // float ring, before the first step: slot 0 holds zeros that carry the tag of step 0 in every unit, slot 1 is cleared
@@ -2429,11 +2466,6 @@ hipError_t launch_persist_bwd_f32(const PBwdArgs& a, hipStream_t s) {
     }
   }
   return hipSuccess;
-}
-hipError_t launch_pack_state_ll(uint4* ring0, uint4* ring1, int nkc, int nrt, int ndir, hipStream_t s) {
-  long total = (long)ndir * nrt * nkc * 64 * 2;
-  hipLaunchKernelGGL(pack_state_ll_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, ring0, ring1, total);
-  return hipGetLastError();
 }
 hipError_t launch_h0_term(const float* h0, const void* W_h, bool bf16, float* gates, long gates_stride, const int* lens, int T, int B, int n,
                           int ndir, int rev0, int rev1, hipStream_t s) {
