@@ -257,10 +257,12 @@ struct ZeroRegions {
   void add(void* p, size_t bytes);
 };
 hipError_t launch_fill_zero_many(const ZeroRegions& r, hipStream_t s);
-// The set-up of a bfloat16 single-launch loop in one launch: the fills of `z`, W_h in the kernel's order and (forward) the initial ring.
+// The set-up of a bfloat16 single-launch loop in one launch: the fills of `z`, W_h in the kernel's order, (forward) the initial
+// ring, and the frame map of launch_frame_map if fm.cidx is not NULL.
+struct FrameMapArgs { const int* lens; int T, B; int* cidx; int* fidx; int* count; };
 hipError_t launch_prep_fwd_ll(const ZeroRegions& z, const void* W, uint4* Wf, int n, int nkc, int ndir, uint4* ring0, uint4* ring1,
-                              int nrt, hipStream_t s);
-hipError_t launch_prep_bwd_ll(const ZeroRegions& z, const void* W, uint4* Wb, int n, int ndir, hipStream_t s);
+                              int nrt, const FrameMapArgs& fm, hipStream_t s);
+hipError_t launch_prep_bwd_ll(const ZeroRegions& z, const void* W, uint4* Wb, int n, int ndir, const FrameMapArgs& fm, hipStream_t s);
 // db[c] (+)= sum_rows DZ[row][c]; part = float scratch [nsplit][ncols] per direction
 // db[dir][c] (+)= sum over the first nslices slices of part[dir][kColsumSlices][ncols]
 constexpr int kColsumSlices = 64;

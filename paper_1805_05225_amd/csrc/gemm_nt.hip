@@ -11,6 +11,7 @@
 // gemm_dl8_* (operands loaded straight into LDS, eight wavefronts; described where it is defined) serves every K that
 // is a multiple of 8; gemm_tn8_f32 serves the k-major operand pair of the weight gradients.
 #include "common.h"
+#include "recurrent_dev.h"
 #include <algorithm>
 
 namespace lstm {
@@ -690,41 +691,7 @@ __global__ void zero_tail_kernel(uint16_t* dst, long rows, long ldd, const int* 
 // in (t, b) order: cidx[t*B + b] = that number or -1, fidx[number] = t*B + b, count[0] = how many are kept,
 // count[1] = count[0] rounded up to a multiple of 64.  One wavefront per time step.
 __global__ __launch_bounds__(256) void frame_map_kernel(const int* lens, int T, int B, int* cidx, int* fidx, int* count) {
-  const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (t >= T) return;
-  // kept frames before time t: sum over b of min(len_b, t)
-  long before = 0, all = 0;
-  for (int b = lane; b < B; b += 64) {
-    int L = lens[b];
-    L = L < 0 ? 0 : (L > T ? T : L);
-    before += L < t ? L : t;
-    all += L;
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    before += __shfl_xor(before, o);
-    all += __shfl_xor(all, o);
-  }
-  if (t == 0 && lane == 0) {
-    count[0] = (int)all;
-    count[1] = (int)((all + 63) / 64 * 64);
-  }
-  int base = (int)before;
-  for (int b0 = 0; b0 < B; b0 += 64) {
-    const int b = b0 + lane;
-    bool keep = false;
-    if (b < B) {
-      int L = lens[b];
-      L = L < 0 ? 0 : (L > T ? T : L);
-      keep = t < L;
-    }
-    const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
-    const int mine = base + __popcll(m & ((1ull << lane) - 1ull));
-    if (b < B) cidx[(long)t * B + b] = keep ? mine : -1;
-    if (keep) fidx[mine] = t * B + b;
-    base += __popcll(m);
-  }
+  frame_map_body(blockIdx.x, lens, T, B, cidx, fidx, count);
 }
 
 // dst[r][c] = src[r][c] for c < C, zero for C <= c < ldd  (rows made 16-byte aligned)

@@ -253,6 +253,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     }
     return LSTM_OK;
   }
+  bool frames_mapped = false;            // the frame map was written by the set-up launch
   {
     Phase ph(LSTM_PHASE_PREP, 5, s);
     ZeroRegions z;
@@ -262,10 +263,15 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd)
       z.add(ws + p.ws_Wf + p.Wf_bytes, 1024);              // the chunk of zeros behind the packed W_h (single-launch path)
     // (on the single-launch path the fills, the packed W_h and the initial ring are one launch)
-    if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd)
+    if (p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd) {
+      FrameMapArgs fm = {};
+      if (p.fast_gemm && seq_lens) {   // the input projection below goes over the real frames
+        fm = {seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), (int*)(ws + p.ws_fidx), (int*)(ws + p.ws_count)};
+        frames_mapped = true;
+      }
       HIPCHK(launch_prep_fwd_ll(z, W_h, (uint4*)(ws + p.ws_Wf), p.n, p.nkc_ll_f, p.D, (uint4*)(ws + p.ws_hfrag0), (uint4*)(ws + p.ws_hfrag1),
-                                p.nrt, s));
-    else HIPCHK(launch_fill_zero_many(z, s));
+                                p.nrt, fm, s));
+    } else HIPCHK(launch_fill_zero_many(z, s));
   }
   // single-launch path: bf16 storage, at least two steps, register budget of the kernel
   bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.nkc_ll_f <= kLLMaxNkcFwd;
@@ -307,7 +313,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
           // frames stay unwritten and are never read
           int* fidx = (int*)(ws + p.ws_fidx);
           int* count = (int*)(ws + p.ws_count);
-          HIPCHK(launch_frame_map(seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), fidx, count, s));
+          if (!frames_mapped) HIPCHK(launch_frame_map(seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), fidx, count, s));
           g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = g.M; g.m_dev = count;
         }
       } else if (!p.bf16 && seq_lens) {  // float storage: the same selection of real frames, by the generic kernel
@@ -472,6 +478,11 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     }
     return LSTM_OK;
   }
+  // With sequence lengths given, the products behind the loop run over the real frames only (about two thirds of T*B for
+  // the length mix of speech batches): frames are numbered once, row-indexed products gather / scatter through
+  // that numbering and the transposed operands of the weight gradients are packed by it.
+  const int TB = (int)(T * B);
+  const bool compact = (p.fast_gemm || !p.bf16) && seq_lens && TB > 0;
   // single-launch path: bf16 storage, at least two steps, and the kernel fits the device
   PBwdArgs pa = {};
   pa.lens = seq_lens; pa.B = p.B; pa.n = p.n; pa.T = p.T; pa.ndir = p.D;
@@ -492,8 +503,11 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     z.add(ws + p.ws_dzfrag1, p.dzfrag_bytes);
     if (2 * p.nrt <= kColsumSlices) z.add(ws + p.ws_colsum, D * kColsumSlices * 4 * n * 4);   // bias-gradient slices of row groups the grid lacks
     // (the bfloat16 single-launch path clears and packs W_h^T in one launch)
-    if (use_ll) HIPCHK(launch_prep_bwd_ll(z, W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, s));
-    else HIPCHK(launch_fill_zero_many(z, s));
+    if (use_ll) {
+      FrameMapArgs fm = {};
+      if (compact) fm = {seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), (int*)(ws + p.ws_fidx), (int*)(ws + p.ws_count)};
+      HIPCHK(launch_prep_bwd_ll(z, W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, fm, s));
+    } else HIPCHK(launch_fill_zero_many(z, s));
   }
   if (!use_ll) {
     Phase ph(LSTM_PHASE_PREP, 1, s);
@@ -577,17 +591,12 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     if (dc0) HIPCHK(launch_copy(dc0, Dc, state_bytes, s));
   }
 
-  const int TB = (int)(T * B);
-  // With sequence lengths given, the products below run over the real frames only (about two thirds of T*B for
-  // the length mix of speech batches): frames are numbered once, row-indexed products gather / scatter through
-  // that numbering and the transposed operands of the weight gradients are packed by it.
   int* cidx = (int*)(ws + p.ws_cidx);
   int* fidx = (int*)(ws + p.ws_fidx);
   int* count = (int*)(ws + p.ws_count);
   const auto fits = [](long rows, long ld) { return rows * ld * 2 <= 0x7fffff00L; };
-  const bool compact = (p.fast_gemm || !p.bf16) && seq_lens && TB > 0;
   const bool compact_w = compact && fits(p.n_in, p.TBp) && fits(4L * p.n, p.TBp) && fits(p.n, p.TBp);
-  if (compact) {
+  if (compact && !use_ll) {          // (the bfloat16 single-launch path numbered the frames in its set-up launch)
     Phase ph(LSTM_PHASE_PREP, 1, s);
     HIPCHK(launch_frame_map(seq_lens, p.T, p.B, cidx, fidx, count, s));
   }

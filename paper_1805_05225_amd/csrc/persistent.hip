@@ -2187,12 +2187,14 @@ __device__ __forceinline__ void pack_state_ll_body(long idx, uint4* ring0, uint4
 // Everything a bfloat16 single-launch loop needs set up, in ONE launch (three kernels in a row cost three start-ups and run one
 // after the other; none of them depends on another): blocks [0, first_pack) clear the regions of `z` (as fill_zero_many_kernel does),
 // blocks [first_pack, first_ring) bring W_h into the kernel's order (forward: ring order; backward: the partial-sum kernel's),
-// blocks from first_ring on (forward only) write the initial ring.
+// blocks [first_ring, first_map) (forward only) write the initial ring, blocks from first_map on number the real frames
+// (frame_map_body) when the products that follow go over real frames only.
 struct PrepArgs {
   ZeroRegions z;
   const bf16_t* W; uint4* Wout; int n, nk; long w_total;   // nk: nkc (forward) / ntile2 (backward)
   uint4* ring0; uint4* ring1; long ring_total;
-  int first_pack, first_ring, backward;
+  const int* lens; int T, B; int* cidx; int* fidx; int* count;     // frame map (cidx == NULL: none)
+  int first_pack, first_ring, first_map, backward;
 };
 __global__ __launch_bounds__(256) void prep_ll_kernel(PrepArgs a) {
   const int bid = blockIdx.x;
@@ -2209,8 +2211,10 @@ __global__ __launch_bounds__(256) void prep_ll_kernel(PrepArgs a) {
     const long idx = (long)(bid - a.first_pack) * 256 + threadIdx.x;
     if (a.backward) pack_wh_bwdp_body(idx, a.W, a.Wout, a.n, a.nk, a.w_total);
     else pack_wh_fwd_ll_body(idx, a.W, a.Wout, a.n, a.nk, a.w_total);
-  } else {
+  } else if (bid < a.first_map) {
     pack_state_ll_body((long)(bid - a.first_ring) * 256 + threadIdx.x, a.ring0, a.ring1, a.ring_total);
+  } else {
+    frame_map_body(bid - a.first_map, a.lens, a.T, a.B, a.cidx, a.fidx, a.count);
   }
 }
 // The initial state's share of the first frame: gates[t0(b)][b][col] += sum_k bf16(h0[b][k]) W_h[k][col], t0 = the row's
@@ -2346,25 +2350,29 @@ hipError_t launch_persist_bwd(const PBwdArgs& a, hipStream_t s) {
   return coop_slabs(persist_bwdp_kernel<8>, t32, 8, a, s);
 }
 hipError_t launch_prep_fwd_ll(const ZeroRegions& z, const void* W, uint4* Wf, int n, int nkc, int ndir, uint4* ring0, uint4* ring1,
-                              int nrt, hipStream_t s) {
+                              int nrt, const FrameMapArgs& fm, hipStream_t s) {
   if (z.overflow) return hipErrorInvalidValue;
   PrepArgs a = {};
   a.z = z; a.W = (const bf16_t*)W; a.Wout = Wf; a.n = n; a.nk = nkc; a.w_total = (long)ndir * cdiv(n, 16) * 4 * nkc * 64;
   a.ring0 = ring0; a.ring1 = ring1; a.ring_total = (long)ndir * nrt * nkc * 64 * 2;
   a.first_pack = z.count ? z.first_block[z.count] : 0;
   a.first_ring = a.first_pack + cdiv(a.w_total, 256);
+  a.first_map = a.first_ring + cdiv(a.ring_total, 256);
   a.backward = 0;
-  hipLaunchKernelGGL(prep_ll_kernel, dim3(a.first_ring + cdiv(a.ring_total, 256)), dim3(256), 0, s, a);
+  a.lens = fm.lens; a.T = fm.T; a.B = fm.B; a.cidx = fm.cidx; a.fidx = fm.fidx; a.count = fm.count;
+  hipLaunchKernelGGL(prep_ll_kernel, dim3(a.first_map + (fm.cidx ? cdiv(fm.T, 4) : 0)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
-hipError_t launch_prep_bwd_ll(const ZeroRegions& z, const void* W, uint4* Wb, int n, int ndir, hipStream_t s) {
+hipError_t launch_prep_bwd_ll(const ZeroRegions& z, const void* W, uint4* Wb, int n, int ndir, const FrameMapArgs& fm, hipStream_t s) {
   if (z.overflow) return hipErrorInvalidValue;
   PrepArgs a = {};
   a.z = z; a.W = (const bf16_t*)W; a.Wout = Wb; a.n = n; a.nk = cdiv(n, 32); a.w_total = (long)ndir * a.nk * 4 * 4 * 16 * 64;
   a.first_pack = z.count ? z.first_block[z.count] : 0;
   a.first_ring = a.first_pack + cdiv(a.w_total, 256);
+  a.first_map = a.first_ring;
   a.backward = 1;
-  hipLaunchKernelGGL(prep_ll_kernel, dim3(a.first_ring), dim3(256), 0, s, a);
+  a.lens = fm.lens; a.T = fm.T; a.B = fm.B; a.cidx = fm.cidx; a.fidx = fm.fidx; a.count = fm.count;
+  hipLaunchKernelGGL(prep_ll_kernel, dim3(a.first_map + (fm.cidx ? cdiv(fm.T, 4) : 0)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 // float ring, before the first step: slot 0 holds zeros that carry the tag of step 0 in every unit, slot 1 is cleared

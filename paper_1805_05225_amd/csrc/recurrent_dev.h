@@ -5,6 +5,46 @@
 namespace lstm {
 namespace {
 
+// Frame map of a batch of end-padded sequences (see launch_frame_map), the work of one block of 256 threads: four time steps,
+// one wavefront each.  Shared by the kernel of its own and by the set-up kernel of the single-launch loops.
+__device__ __forceinline__ void frame_map_body(int block, const int* lens, int T, int B, int* cidx, int* fidx, int* count) {
+  const int lane = threadIdx.x & 63;
+  const int t = block * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  // kept frames before time t: sum over b of min(len_b, t)
+  long before = 0, all = 0;
+  for (int b = lane; b < B; b += 64) {
+    int L = lens[b];
+    L = L < 0 ? 0 : (L > T ? T : L);
+    before += L < t ? L : t;
+    all += L;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    before += __shfl_xor(before, o);
+    all += __shfl_xor(all, o);
+  }
+  if (t == 0 && lane == 0) {
+    count[0] = (int)all;
+    count[1] = (int)((all + 63) / 64 * 64);
+  }
+  int base = (int)before;
+  for (int b0 = 0; b0 < B; b0 += 64) {
+    const int b = b0 + lane;
+    bool keep = false;
+    if (b < B) {
+      int L = lens[b];
+      L = L < 0 ? 0 : (L > T ? T : L);
+      keep = t < L;
+    }
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
+    const int mine = base + __popcll(m & ((1ull << lane) - 1ull));
+    if (b < B) cidx[(long)t * B + b] = keep ? mine : -1;
+    if (keep) fidx[mine] = t * B + b;
+    base += __popcll(m);
+  }
+}
+
 template <typename T> struct Mma16;
 template <> struct Mma16<bf16_t> {
   __device__ static f32x4 run(uint4 a, uint4 b, f32x4 c) {
