@@ -493,6 +493,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
   const bool use_ll = p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && persist_bwd_fits(pa);
   const bool use_ll32 = !p.bf16 && !(desc->flags & LSTM_FLAG_PER_STEP) && T >= 2 && p.n % 8 == 0 && p.n <= 1024 && p.B <= 256 &&
                         persist_bwd_f32_fits(pa);
+  bool dx_cleared = false;
   {
     Phase ph(LSTM_PHASE_PREP, 5, s);
     ZeroRegions z;
@@ -506,6 +507,10 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     if (use_ll) {
       FrameMapArgs fm = {};
       if (compact) fm = {seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), (int*)(ws + p.ws_fidx), (int*)(ws + p.ws_count)};
+      if (compact && dx && ((size_t)TB * n_in * p.esz) % 4 == 0) {   // dX is scattered to the real frames' rows: the padded frames' rows are cleared here
+        z.add(dx, (size_t)TB * n_in * p.esz);
+        dx_cleared = true;
+      }
       HIPCHK(launch_prep_bwd_ll(z, W_h, (uint4*)(ws + p.ws_Wb), p.n, p.D, fm, s));
     } else HIPCHK(launch_fill_zero_many(z, s));
   }
@@ -611,7 +616,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
     g.vecB = widest(g.ldb, g.sBseg, 0, p.esz, 16);
     Phase ph(LSTM_PHASE_GEMM_DX, 1, s);
     if (compact && (gemm_nt_ok(g) || !p.bf16)) {      // rows of padded frames: zero, and left out of the product
-      HIPCHK(launch_fill_zero(dx, (size_t)TB * n_in * p.esz, s));
+      if (!dx_cleared) HIPCHK(launch_fill_zero(dx, (size_t)TB * n_in * p.esz, s));
       g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = TB; g.m_dev = count;
     }
     if (p.ks_dx > 1 && gemm_nt_ok(g)) { g.ksplit = p.ks_dx; g.parts = (float*)(ws + p.ws_parts); }
