@@ -269,7 +269,16 @@ __global__ void colsum_final_kernel(const float* part, float* db, int ncols, int
   int c = blockIdx.x * blockDim.x + threadIdx.x, dir = blockIdx.y;
   if (c >= ncols) return;
   float s = 0.f;
-  for (int sp = 0; sp < nslices; ++sp) s += part[((long)dir * kColsumSplit + sp) * ncols + c];
+  const float* p = part + (long)dir * kColsumSplit * ncols + c;
+  int sp = 0;
+  for (; sp + 8 <= nslices; sp += 8) {                   // eight loads in flight (one at a time, each costs a trip to memory)
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = p[(long)(sp + k) * ncols];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += v[k];
+  }
+  for (; sp < nslices; ++sp) s += p[(long)sp * ncols];
   float* o = db + (long)dir * ncols + c;
   *o = accumulate ? *o + s : s;
 }
