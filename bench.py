@@ -453,6 +453,8 @@ def bench_search_step(args, Bn, synth):
     st = torch.cuda.current_stream().cuda_stream
     lib = Bn.lib
     NEV = 6
+    # what follows the hypotheses after a step, per parity of the step (the buffers alternate): one launch for all four
+    gather = [Bn.gather_items([(h_new, h[1 - p]), (c_new, c[1 - p]), (accum_new, accum[1 - p]), (att_buf, xin[1 - p][:, nt:])]) for p in range(2)]
 
     def one(i, first, ev=None):
         p = i % 2
@@ -472,10 +474,8 @@ def bench_search_step(args, Bn, synth):
         if ev: ev[4].record()
         ck(lib.lstm_beam_step(Q, beam, V, logits.data_ptr(), V, score[p].data_ptr(), score[1 - p].data_ptr(), src.data_ptr(), label.data_ptr(),
                               ws_beam.data_ptr(), ws_beam.numel(), st))
-        for (a_in, a_out, width, ld_out, eb) in ((h_new, h[1 - p].data_ptr(), n, n, 4), (c_new, c[1 - p].data_ptr(), n, n, 4),
-                                                   (accum_new, accum[1 - p].data_ptr(), S, S, 4),
-                                                   (att_buf, xin[1 - p].data_ptr() + 2 * nt, E, nt + E, 2)):
-            ck(lib.lstm_beam_gather(eb, Q, beam, width, a_in.data_ptr(), width, src.data_ptr(), a_out, ld_out, st))
+        # the state rows follow their hypotheses: h, c, the attention's accumulated weights and the context (into the next input)
+        ck(lib.lstm_beam_gather_many(Q, beam, 4, gather[p], src.data_ptr(), st))
         ck(lib.lstm_embed(B, nt, V, label.data_ptr(), W_trg.data_ptr(), None, xin[1 - p].data_ptr(), nt + E, st))
         if ev: ev[5].record()
 

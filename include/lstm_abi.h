@@ -19,7 +19,7 @@
  * Beside the layer (lstm_query, lstm_fwd, lstm_bwd, blstm_fwd, blstm_bwd) the library holds what the paper's encoders
  * and decoder put around it, each documented at its declaration below: the hoisted product by itself (lstm_gemm),
  * max-pooling in time between encoder layers (lstm_time_pool_fwd / _bwd), one step of the attention decoder
- * (lstm_attention_step, lstm_readout), one step of batched beam search (lstm_beam_step, lstm_beam_gather, lstm_embed),
+ * (lstm_attention_step, lstm_readout), one step of batched beam search (lstm_beam_step, lstm_beam_gather, lstm_beam_gather_many, lstm_embed),
  * and diagnostics (lstm_sync_status, lstm_profile_*, lstm_strerror).
  *
  * Conventions common to every entry point
@@ -245,6 +245,8 @@ int lstm_readout(int flags, int B, int R, const void* s, int64_t ld_s, int n, co
  * lstm_beam_gather moves per-hypothesis state behind the choice: out[q*beam + k][0..width) = in[q*beam + src[q, k]][..]
  *   for rows of `width` elements of elem_bytes (2 or 4) bytes; in and out must be different buffers; values of src
  *   outside [0, beam) are clamped.
+ * lstm_beam_gather_many does the same for `count` (1 .. 8) arrays in ONE launch: `items` is a HOST array, read during the
+ *   call; every array follows the same `src`.  Rows are copied in the widest units their alignment allows.
  * lstm_embed is Listing 1's "trg": out[r] = W_trg[label[r]] + b_trg with W_trg bfloat16 [V][n], b_trg float [n] or NULL,
  *   out bfloat16 [B][ld_out >= n]; a label outside [0, V) gives the bias alone.
  * Device pointers owned by the caller; the calls only enqueue work and nothing is copied to the host.
@@ -255,6 +257,15 @@ int lstm_beam_step(int Q, int beam, int V, const float* logits, int64_t ld, cons
                    int32_t* src, int32_t* label, void* workspace, uint64_t workspace_bytes, void* stream);
 int lstm_beam_gather(int elem_bytes, int Q, int beam, int width, const void* in, int64_t ld_in, const int32_t* src,
                      void* out, int64_t ld_out, void* stream);
+typedef struct lstm_gather_item {
+  int32_t elem_bytes;          /* 2 or 4 */
+  int32_t width;               /* elements per row */
+  const void* in;              /* device [Q*beam][ld_in] */
+  int64_t ld_in;               /* elements */
+  void* out;                   /* device [Q*beam][ld_out], not `in` */
+  int64_t ld_out;
+} lstm_gather_item;
+int lstm_beam_gather_many(int Q, int beam, int count, const lstm_gather_item* items, const int32_t* src, void* stream);
 /* lstm_beam_step for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
  * tight serving loops, harnesses that forbid allocation.  Same arguments without the workspace, same results (the
  * same kernels run).  The step's scratch - the beam survivors of every row - lives in a device array of 512 KiB that is

@@ -15,9 +15,14 @@ LIB_PATH = os.environ.get("MI355X_LSTM_LIB", os.path.join(_HERE, "libmi355x_lstm
 LSTM_F32, LSTM_BF16_F32STATE = 0, 1
 FLAG_ACCUMULATE, FLAG_PER_STEP, FLAG_INFERENCE, FLAG_WEIGHTS_PACKED, FLAG_PLAIN_LAUNCH = 1, 2, 4, 8, 16
 EXPORTS = ("lstm_query", "lstm_fwd", "lstm_bwd", "blstm_fwd", "blstm_bwd", "lstm_gemm", "lstm_time_pool_fwd", "lstm_time_pool_bwd", "lstm_attention_query", "lstm_attention_step",
-           "lstm_readout_query", "lstm_readout", "lstm_beam_query", "lstm_beam_step", "lstm_beam_step_static", "lstm_beam_gather", "lstm_embed",
+           "lstm_readout_query", "lstm_readout", "lstm_beam_query", "lstm_beam_step", "lstm_beam_step_static", "lstm_beam_gather", "lstm_beam_gather_many", "lstm_embed",
            "lstm_sync_status", "lstm_profile_enable", "lstm_profile_read",
            "lstm_strerror")
+
+
+class GatherItem(ctypes.Structure):
+    _fields_ = [("elem_bytes", ctypes.c_int32), ("width", ctypes.c_int32), ("inp", ctypes.c_void_p), ("ld_in", ctypes.c_int64),
+                ("out", ctypes.c_void_p), ("ld_out", ctypes.c_int64)]
 
 
 class AttDesc(ctypes.Structure):
@@ -77,6 +82,8 @@ def _load():
     lib.lstm_beam_step_static.argtypes = [ip, ip, ip, vp, i64, vp, vp, vp, vp, vp]
     lib.lstm_beam_gather.restype = ip
     lib.lstm_beam_gather.argtypes = [ip, ip, ip, ip, vp, i64, vp, vp, i64, vp]
+    lib.lstm_beam_gather_many.restype = ip
+    lib.lstm_beam_gather_many.argtypes = [ip, ip, ip, ctypes.POINTER(GatherItem), vp, vp]
     lib.lstm_embed.restype = ip
     lib.lstm_embed.argtypes = [ip, ip, ip, vp, vp, vp, vp, i64, vp]
     lib.lstm_sync_status.restype = ip
@@ -310,6 +317,25 @@ def beam_gather(state, src):
     _check(lib.lstm_beam_gather(state.element_size(), Q, beam, state.shape[1], state.data_ptr(), state.stride(0), _ptr(src), _ptr(out),
                                 out.stride(0), _stream()))
     return out
+
+
+def gather_items(pairs):
+    """ctypes array of lstm_gather_item for (in, out) pairs of 2-D tensors (float or bfloat16, rows contiguous)."""
+    arr = (GatherItem * len(pairs))()
+    for it, (a, o) in zip(arr, pairs):
+        assert a.stride(1) == 1 and o.stride(1) == 1 and a.dtype == o.dtype and a.shape == o.shape
+        it.elem_bytes, it.width, it.inp, it.ld_in, it.out, it.ld_out = a.element_size(), a.shape[1], a.data_ptr(), a.stride(0), o.data_ptr(), o.stride(0)
+    return arr
+
+
+def beam_gather_many(states, src, outs=None):
+    """beam_gather for up to 8 state arrays in one launch (lstm_beam_gather_many); `outs` may be views with a larger row stride."""
+    Q, beam = src.shape
+    if outs is None:
+        outs = [torch.empty_like(a) for a in states]
+    arr = gather_items(list(zip(states, outs)))
+    _check(lib.lstm_beam_gather_many(Q, beam, len(arr), arr, _ptr(src), _stream()))
+    return outs
 
 
 def embed(label, W_trg, b_trg=None, *, out=None):

@@ -335,15 +335,36 @@ __global__ __launch_bounds__(64) void beam_merge_kernel(const float* __restrict_
   }
 }
 
-// out[q * beam + k][0..width) = in[q * beam + src[q * beam + k]][0..width), elements of `esz` bytes copied as bytes pairs
-__global__ void beam_gather_kernel(const uint16_t* __restrict__ in, long ld_in, const int* __restrict__ src, uint16_t* __restrict__ out,
-                                   long ld_out, int rows, int beam, int halves) {
-  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (long)rows * halves) return;
-  const int r = (int)(idx / halves), c = (int)(idx % halves);
-  int s = src[r];
-  s = s < 0 ? 0 : (s >= beam ? beam - 1 : s);
-  out[(long)r * ld_out + c] = in[((long)(r / beam) * beam + s) * ld_in + c];
+// out[q * beam + k][0..width) = in[q * beam + src[q * beam + k]][0..width) for up to kGatherMax arrays in one launch.  Array i
+// is copied in units of unit[i] bytes (16, 8, 4 or 2: the widest that its row length, leading dimensions and base addresses
+// allow), one unit per thread; blocks [first_block[i], first_block[i+1]) work on array i.
+constexpr int kGatherMax = 8;
+struct GatherArgs {
+  const char* in[kGatherMax]; char* out[kGatherMax];
+  long ld_in[kGatherMax], ld_out[kGatherMax];          // bytes
+  int units[kGatherMax], unit[kGatherMax];             // units per row; bytes per unit
+  int first_block[kGatherMax + 1];
+  int count, rows, beam;
+  const int* src;
+};
+__global__ __launch_bounds__(256) void beam_gather_kernel(GatherArgs a) {
+  int i = 0;
+#pragma unroll
+  for (int j = 1; j < kGatherMax; ++j)
+    if (j < a.count && (int)blockIdx.x >= a.first_block[j]) i = j;
+  const long idx = (long)((int)blockIdx.x - a.first_block[i]) * 256 + threadIdx.x;
+  const int upr = a.units[i];
+  if (idx >= (long)a.rows * upr) return;
+  const int r = (int)(idx / upr), c = (int)(idx - (long)r * upr);
+  int s = a.src[r];
+  s = s < 0 ? 0 : (s >= a.beam ? a.beam - 1 : s);
+  const int u = a.unit[i];
+  const char* pi = a.in[i] + ((long)(r / a.beam) * a.beam + s) * a.ld_in[i] + (long)c * u;
+  char* po = a.out[i] + (long)r * a.ld_out[i] + (long)c * u;
+  if (u == 16) *(uint4*)po = *(const uint4*)pi;
+  else if (u == 8) *(uint2*)po = *(const uint2*)pi;
+  else if (u == 4) *(uint32_t*)po = *(const uint32_t*)pi;
+  else *(uint16_t*)po = *(const uint16_t*)pi;
 }
 
 // trg[r] = W[label[r]] + b (bfloat16 table and result, float bias); labels outside [0, V) give the bias alone
@@ -440,22 +461,42 @@ int lstm_beam_step_static(int Q, int beam, int V, const float* logits, int64_t l
                      (hipStream_t)stream);
 }
 
-int lstm_beam_gather(int elem_bytes, int Q, int beam, int width, const void* in, int64_t ld_in, const int32_t* src, void* out,
-                     int64_t ld_out, void* stream) {
-  if (!in || !src || !out) return LSTM_ERR_NULL;
-  if (Q < 0 || beam < 1 || width < 1 || ld_in < width || ld_out < width || (long)Q * beam > 0x7fffffffL / 16) return LSTM_ERR_DIM;
-  if (elem_bytes != 2 && elem_bytes != 4) return LSTM_ERR_UNSUPPORTED;
-  if ((((uintptr_t)in | (uintptr_t)out) & (elem_bytes - 1)) || ((uintptr_t)src & 3)) return LSTM_ERR_ALIGN;
-  if (in == out) return LSTM_ERR_UNSUPPORTED;                     // rows are read while others are written
+int lstm_beam_gather_many(int Q, int beam, int count, const lstm_gather_item* items, const int32_t* src, void* stream) {
+  if (!items || !src) return LSTM_ERR_NULL;
+  if (count < 1 || count > kGatherMax) return LSTM_ERR_DIM;
+  if (Q < 0 || beam < 1 || (long)Q * beam > 0x7fffffffL / 16) return LSTM_ERR_DIM;
+  if ((uintptr_t)src & 3) return LSTM_ERR_ALIGN;
+  GatherArgs a = {};
+  a.count = count; a.rows = Q * beam; a.beam = beam; a.src = src;
+  for (int i = 0; i < count; ++i) {
+    const lstm_gather_item& it = items[i];
+    if (!it.in || !it.out) return LSTM_ERR_NULL;
+    if (it.width < 1 || it.ld_in < it.width || it.ld_out < it.width) return LSTM_ERR_DIM;
+    if (it.elem_bytes != 2 && it.elem_bytes != 4) return LSTM_ERR_UNSUPPORTED;
+    if (((uintptr_t)it.in | (uintptr_t)it.out) & (uintptr_t)(it.elem_bytes - 1)) return LSTM_ERR_ALIGN;
+    if (it.in == it.out) return LSTM_ERR_UNSUPPORTED;             // rows are read while others are written
+    const long row_bytes = (long)it.width * it.elem_bytes, lbi = (long)it.ld_in * it.elem_bytes, lbo = (long)it.ld_out * it.elem_bytes;
+    const uintptr_t all = (uintptr_t)it.in | (uintptr_t)it.out | (uintptr_t)row_bytes | (uintptr_t)lbi | (uintptr_t)lbo;
+    const int u = !(all & 15) ? 16 : !(all & 7) ? 8 : !(all & 3) ? 4 : 2;
+    a.in[i] = (const char*)it.in; a.out[i] = (char*)it.out; a.ld_in[i] = lbi; a.ld_out[i] = lbo;
+    a.unit[i] = u; a.units[i] = (int)(row_bytes / u);
+    const long blocks = ((long)a.rows * a.units[i] + 255) / 256;
+    if (blocks + a.first_block[i] > 0x7fffffffL) return LSTM_ERR_DIM;
+    a.first_block[i + 1] = a.first_block[i] + (int)blocks;
+  }
   if (Q == 0) return LSTM_OK;
   int rc = device_ok();
   if (rc) return rc;
-  const int halves = width * (elem_bytes / 2), rows = Q * beam;
-  const long total = (long)rows * halves;
-  hipLaunchKernelGGL(beam_gather_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)in,
-                     (long)ld_in * (elem_bytes / 2), src, (uint16_t*)out, (long)ld_out * (elem_bytes / 2), rows, beam, halves);
+  hipLaunchKernelGGL(beam_gather_kernel, dim3((unsigned)a.first_block[count]), dim3(256), 0, (hipStream_t)stream, a);
   if (hipGetLastError() != hipSuccess) return LSTM_ERR_HIP;
   return LSTM_OK;
+}
+
+int lstm_beam_gather(int elem_bytes, int Q, int beam, int width, const void* in, int64_t ld_in, const int32_t* src, void* out,
+                     int64_t ld_out, void* stream) {
+  if (!in || !src || !out) return LSTM_ERR_NULL;
+  const lstm_gather_item it = {elem_bytes, width, in, ld_in, out, ld_out};
+  return lstm_beam_gather_many(Q, beam, 1, &it, src, stream);
 }
 
 int lstm_embed(int B, int n, int V, const int32_t* label, const void* W_trg, const float* b_trg, void* out, int64_t ld_out, void* stream) {

@@ -181,6 +181,16 @@ def test_beam_argument_errors():
     ga = lambda eb=4, Q=4, beam=3, w=8, i=P, ldi=8, src=P, o=P + 4096, ldo=8: L.lstm_beam_gather(eb, Q, beam, w, i, ldi, src, o, ldo, None)
     assert ga(i=None) == -1 and ga(src=None) == -1 and ga(o=None) == -1
     assert ga(w=0) == -2 and ga(ldi=7) == -2 and ga(ldo=7) == -2 and ga(eb=3) == -4 and ga(o=P) == -4 and ga(i=P + 2) == -5 and ga(Q=0) == 0
+    def gm(count=2, Q=4, beam=3, src=P, **over):
+        arr = (Bn.GatherItem * 8)()
+        for it in arr:
+            it.elem_bytes, it.width, it.inp, it.ld_in, it.out, it.ld_out = 4, 8, P, 8, P + 4096, 8
+        for k, v in over.items():
+            setattr(arr[1], k, v)
+        return L.lstm_beam_gather_many(Q, beam, count, arr, src, None)
+    assert gm(count=0) == -2 and gm(count=9) == -2 and gm(src=None) == -1 and gm(Q=-1) == -2 and gm(Q=0) == 0
+    assert L.lstm_beam_gather_many(4, 3, 1, None, P, None) == -1
+    assert gm(inp=None) == -1 and gm(width=0) == -2 and gm(ld_out=7) == -2 and gm(elem_bytes=8) == -4 and gm(out=P) == -4 and gm(inp=P + 2) == -5
     em = lambda B=4, n=8, V=10, lab=P, W=P, b=None, o=P, ldo=8: L.lstm_embed(B, n, V, lab, W, b, o, ldo, None)
     assert em(lab=None) == -1 and em(W=None) == -1 and em(o=None) == -1
     assert em(n=0) == -2 and em(V=0) == -2 and em(ldo=7) == -2 and em(o=P + 1) == -5 and em(b=P + 2) == -5 and em(B=0) == 0

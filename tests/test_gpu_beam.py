@@ -156,6 +156,16 @@ def test_gather_and_embed_are_exact():
         torch.cuda.synchronize()
         want = D.gather_rows(st.float().cpu().numpy(), src, beam)
         assert np.array_equal(out.float().cpu().numpy(), want)
+    # several arrays in one launch: every unit width (16, 8, 4 and 2 bytes), an output that is a column block of a wider buffer
+    shapes = ((torch.float32, 1000, 0), (torch.float32, 80, 0), (torch.bfloat16, 2000, 620), (torch.bfloat16, 79, 0), (torch.float32, 3, 0),
+              (torch.bfloat16, 36, 2))
+    states = [torch.from_numpy(rng.standard_normal((Q * beam, w)).astype(np.float32)).to(dt).cuda() for dt, w, _ in shapes]
+    wide = [torch.zeros(Q * beam, w + off, dtype=dt).cuda() for dt, w, off in shapes]
+    outs = Bn.beam_gather_many(states, torch.from_numpy(src).cuda(), [b[:, off:] for b, (_, _, off) in zip(wide, shapes)])
+    torch.cuda.synchronize()
+    for st, o, b, (_, _, off) in zip(states, outs, wide, shapes):
+        assert np.array_equal(o.float().cpu().numpy(), D.gather_rows(st.float().cpu().numpy(), src, beam))
+        assert not b[:, :off].any()                                       # nothing written outside the block
     V, n = 500, 620
     W = torch.from_numpy(rng.standard_normal((V, n)).astype(np.float32)).to(torch.bfloat16)
     b = rng.standard_normal(n).astype(np.float32)
