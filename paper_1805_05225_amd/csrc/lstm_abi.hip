@@ -112,7 +112,7 @@ int make_plan(const lstm_desc* d, int bidir, Plan* p) {
   p->ws_DZT = take(fg && !infer ? D * 4 * n * p->TBp * 2 : 0);
   p->ws_HT = take(fg && !infer ? D * n * p->TBp * 2 : 0);
   // frame map of the batch (which frames are real), used to leave padded frames out of the products
-  const bool fm = fg || !p->bf16;             // (float storage: the generic kernel takes the same row maps)
+  const bool fm = fg || !p->bf16;             // (float storage: its product kernels take the same row maps)
   p->ws_cidx = take(fm ? (size_t)TB * 4 : 0);
   p->ws_fidx = take(fm ? (size_t)p->TBp * 4 : 0);
   p->ws_count = take(fm ? 256 : 0);
@@ -316,7 +316,7 @@ int run_fwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
           if (!frames_mapped) HIPCHK(launch_frame_map(seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), fidx, count, s));
           g.a_rows = fidx; g.c_rows = fidx; g.a_phys_rows = g.M; g.m_dev = count;
         }
-      } else if (!p.bf16 && seq_lens) {  // float storage: the same selection of real frames, by the generic kernel
+      } else if (!p.bf16 && seq_lens) {  // float storage: the same selection of real frames
         int* fidx = (int*)(ws + p.ws_fidx);
         int* count = (int*)(ws + p.ws_count);
         HIPCHK(launch_frame_map(seq_lens, p.T, p.B, (int*)(ws + p.ws_cidx), fidx, count, s));
@@ -625,7 +625,7 @@ int run_bwd(const lstm_desc* desc, int bidir, const void* x, const void* W_x, co
       if (!gemm_float_ok(g)) { g.ksplit = 0; g.parts = nullptr; }
     }
     if (!p.bf16 && !g.parts) {
-      // float storage, generic kernel: rows = frames and n_in columns give few 128 x 128 tiles (config 2: 85 with real
+      // float storage, shapes the eight-range form above does not take: rows = frames and n_in columns give few 128 x 128 tiles (config 2: 85 with real
       // frames), so K = 4n per direction is cut into ranges that add their parts to the zero-filled dx atomically
       const long tiles = (long)cdiv(TB, 128) * cdiv(p.n_in, 128), stages = (long)p.D * cdiv(4L * p.n, 32);
       const int ks = (int)std::max(1L, std::min(std::min(384 / std::max(tiles, 1L), stages / 16), 8L));
