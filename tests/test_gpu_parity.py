@@ -283,12 +283,13 @@ def test_single_launch_equals_per_step(dt, B, n, T):
 
 @pytest.mark.parametrize("B,n,T,bidir,direction", [(64, 1000, 12, True, 1), (70, 136, 9, True, 1), (3, 8, 33, True, 1),
                                                     (150, 264, 5, False, -1), (17, 1024, 6, False, 1), (33, 40, 2, True, 1),
-                                                    (100, 1000, 4, True, 1)])
+                                                    (100, 1000, 4, True, 1), (64, 1000, 150, True, 1)])
 def test_float_single_launch_loops(B, n, T, bidir, direction):
     """Float storage runs its time loops in one launch each (n a multiple of 8): rows of
     length 0, 1 and T, one to five slabs of 32 rows with ragged last slabs and, in the last case, more slabs than one launch
-    holds, both directions and each alone, an initial cell state; compared with one launch per time step, with the ordinary
-    launch mode, and with the oracle."""
+    holds, both directions and each alone, an initial cell state, and one long case (150 steps at the full width: the kernels
+    consume ring loads while stores are in flight, and a wait that is one load short shows as a wrong row now and then);
+    compared with one launch per time step, with the ordinary launch mode, and with the oracle."""
     rng = np.random.default_rng(7 * B + n + T)
     lens = rng.integers(0, T + 1, B)
     lens[0] = T
