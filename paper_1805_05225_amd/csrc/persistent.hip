@@ -234,26 +234,17 @@ constexpr int kPrepDelay = LSTM_PREP_DELAY;
 // YOUNGER LOADS: loads return in the order of issue among themselves, but stores were seen to be acknowledged ahead of
 // older loads that bypass L2, so a count that includes the younger stores - what the compiler emits - can be reached
 // while the load is still on its way.
-__device__ __forceinline__ void wait_loads_but(int n) {
+// The wait names the registers it is for: an assembly statement that "rewrites" them, so that no instruction reading them can
+// be scheduled in front of it (in straight-line code the compiler would otherwise be free to, with only its own wait before them).
+#define LSTM_WAIT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" : "+v"(x)); break;
+__device__ __forceinline__ void wait_loads_but(int n, u32x4& x) {
   switch (n < 15 ? n : 15) {
-    case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
-    case 1: __builtin_amdgcn_s_waitcnt(0x0f71); break;
-    case 2: __builtin_amdgcn_s_waitcnt(0x0f72); break;
-    case 3: __builtin_amdgcn_s_waitcnt(0x0f73); break;
-    case 4: __builtin_amdgcn_s_waitcnt(0x0f74); break;
-    case 5: __builtin_amdgcn_s_waitcnt(0x0f75); break;
-    case 6: __builtin_amdgcn_s_waitcnt(0x0f76); break;
-    case 7: __builtin_amdgcn_s_waitcnt(0x0f77); break;
-    case 8: __builtin_amdgcn_s_waitcnt(0x0f78); break;
-    case 9: __builtin_amdgcn_s_waitcnt(0x0f79); break;
-    case 10: __builtin_amdgcn_s_waitcnt(0x0f7a); break;
-    case 11: __builtin_amdgcn_s_waitcnt(0x0f7b); break;
-    case 12: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
-    case 13: __builtin_amdgcn_s_waitcnt(0x0f7d); break;
-    case 14: __builtin_amdgcn_s_waitcnt(0x0f7e); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0f7f); break;
+    LSTM_WAIT_CASE(0) LSTM_WAIT_CASE(1) LSTM_WAIT_CASE(2) LSTM_WAIT_CASE(3) LSTM_WAIT_CASE(4) LSTM_WAIT_CASE(5) LSTM_WAIT_CASE(6) LSTM_WAIT_CASE(7)
+    LSTM_WAIT_CASE(8) LSTM_WAIT_CASE(9) LSTM_WAIT_CASE(10) LSTM_WAIT_CASE(11) LSTM_WAIT_CASE(12) LSTM_WAIT_CASE(13) LSTM_WAIT_CASE(14)
+    default: asm volatile("s_waitcnt vmcnt(15)" : "+v"(x)); break;
   }
 }
+#undef LSTM_WAIT_CASE
 // f(integral_constant<0>) ... f(integral_constant<N - 1>): a loop whose counter is a constant expression in the body
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -1853,7 +1844,7 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
       unsigned long long redo = 0ull;
 #pragma unroll
       for (int it = 0; it < NCH; ++it) {
-        wait_loads_but(NCH - 1 - it);                      // (the first half went out before the last half step's stores)
+        wait_loads_but(NCH - 1 - it, x[it]);               // (the first half went out before the last half step's stores)
         if (__builtin_amdgcn_ballot_w64(rd.tag_diff(x[it], it, tagw) != 0u) == 0ull) use(it, x[it]);
         else { redo |= 1ull << it; PROF_REDO(1) }
       }
@@ -2097,7 +2088,7 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
 #pragma unroll
           for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s], w[ci][s], acc, 0, 0, 0);
           if (collect) {                                   // (behind the MFMAs just issued: they run while this does)
-            wait_loads_but((NCT - 1 - ci) < (kWin - 1) ? (NCT - 1 - ci) : (kWin - 1));     // the younger loads: the window's others
+            wait_loads_but((NCT - 1 - ci) < (kWin - 1) ? (NCT - 1 - ci) : (kWin - 1), x[ci % kWin]);     // the younger loads: the window's others
             if (__builtin_amdgcn_ballot_w64(rn.tag_diff(x[ci % kWin], ci, tagw_n) != 0u) == 0ull) add_to(psn, x[ci % kWin]);
             else { redo_n |= 1ull << ci; PROF_REDO(1) }
             if (ci + kWin < NCT) x[ci % kWin] = rn.load_it(ci + kWin);
