@@ -217,6 +217,14 @@ __device__ __forceinline__ void mfma_b_vgpr(f32x4& acc, const u32x4& a, const u3
 __device__ __forceinline__ void mfma_b_agpr_first(f32x4& acc, const u32x4& a, const u32x4& b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
 }
+// The float MFMA (16x16x4): A one float per lane in a vector register, B one float per lane in an accumulation register.
+__device__ __forceinline__ void mfma4_b_agpr(f32x4& acc, float a, unsigned b) {
+  asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma4_b_agpr_first(f32x4& acc, float a, unsigned b) {
+  asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_settle(f32x4& a0) { asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a0)); }
 // Wait states between the last ordinary (vector ALU, DPP, LDS) write of registers and an MFMA reading them.  For
 // MFMAs it emits itself the compiler knows what the hardware needs; for these it cannot, and an MFMA issued right
 // behind DPP moves was observed to read the old register contents.
@@ -1933,14 +1941,15 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
   bool dead = false;
 
   // W_h^T slice: column tile wave + 4 ci of the outputs, k-step s (launch_pack_wh_bwd_f32p)
-  float w[NCT][16];
+  // It fills the 256 accumulation registers of every lane and stays there: the MFMAs read it from them (inline assembly, as in
+  // the bfloat16 kernels; left to the compiler the slice is spread over both register files and copied back before every use, with
+  // the architectural registers filled to the last one).
+  u32x4 w[NCT][4];
 #pragma unroll
   for (int ci = 0; ci < NCT; ++ci)
 #pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) {
-      const float4 v = ((const float4*)d.Wb)[((((long)J * 4 + wave) * NCT + ci) * 4 + s4) * 64 + lane];
-      w[ci][4 * s4] = v.x; w[ci][4 * s4 + 1] = v.y; w[ci][4 * s4 + 2] = v.z; w[ci][4 * s4 + 3] = v.w;
-    }
+    for (int s4 = 0; s4 < 4; ++s4) w[ci][s4] = load_to_agpr((const uint4*)d.Wb + ((((long)J * 4 + wave) * NCT + ci) * 4 + s4) * 64 + lane);
+  agpr_loads_done();
 
   // pointwise: row r16 of each row tile, unit u of the tile's 16
   const int r16 = tid >> 4, u = tid & 15;
@@ -2082,21 +2091,32 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
         const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc((void*)((sigma & 1) ? d.ring1 : d.ring0), 0, ring_bytes, kBufFlags);
         // destination tile wave + 4 ci (one past the last: parked), this producer's block
         const unsigned pub0 = (unsigned)((((rt_base + k) * ntile + wave) * ntile + J) * 1024 + lane * 16);
+        // The accumulator of column tile ci is published behind the MFMAs of column tile ci + 1: by then its last MFMA has long
+        // finished (the compiler does not see the MFMAs in the assembly text and inserts no wait states for their results).
+        auto publish = [&](int ci, const f32x4& acc) __attribute__((always_inline)) {
+          const u32x4 unit = {__float_as_uint(acc[0]), __float_as_uint(acc[1]) | tag_hi, __float_as_uint(acc[2]), __float_as_uint(acc[3]) | tag_hi};
+          const unsigned off = wave + 4 * ci < ntile ? pub0 + (unsigned)(4 * ci) * (unsigned)ntile * 1024u : 0x7ff00000u;
+          __builtin_amdgcn_raw_buffer_store_b128(unit, ro, off, 0, 16);    // 16: agent scope, written through
+        };
+        f32x4 acc2[2];
 #pragma unroll
         for (int ci = 0; ci < NCT; ++ci) {
-          f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+          f32x4& acc = acc2[ci & 1];
 #pragma unroll
-          for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s], w[ci][s], acc, 0, 0, 0);
+          for (int s = 0; s < 16; ++s) {
+            if (s == 0) mfma4_b_agpr_first(acc, av[0], w[ci][0][0]);
+            else mfma4_b_agpr(acc, av[s], w[ci][s >> 2][s & 3]);
+          }
+          if (ci > 0) publish(ci - 1, acc2[(ci - 1) & 1]);
           if (collect) {                                   // (behind the MFMAs just issued: they run while this does)
             wait_loads_but((NCT - 1 - ci) < (kWin - 1) ? (NCT - 1 - ci) : (kWin - 1), x[ci % kWin]);     // the younger loads: the window's others
             if (__builtin_amdgcn_ballot_w64(rn.tag_diff(x[ci % kWin], ci, tagw_n) != 0u) == 0ull) add_to(psn, x[ci % kWin]);
             else { redo_n |= 1ull << ci; PROF_REDO(1) }
             if (ci + kWin < NCT) x[ci % kWin] = rn.load_it(ci + kWin);
           }
-          const u32x4 unit = {__float_as_uint(acc[0]), __float_as_uint(acc[1]) | tag_hi, __float_as_uint(acc[2]), __float_as_uint(acc[3]) | tag_hi};
-          const unsigned off = wave + 4 * ci < ntile ? pub0 + (unsigned)(4 * ci) * (unsigned)ntile * 1024u : 0x7ff00000u;
-          __builtin_amdgcn_raw_buffer_store_b128(unit, ro, off, 0, 16);    // 16: agent scope, written through
         }
+        mfma_settle(acc2[(NCT - 1) & 1]);
+        publish(NCT - 1, acc2[(NCT - 1) & 1]);
         if (collect) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) ps_c[v] = psn[v];
