@@ -1760,16 +1760,20 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
 
   // W_h slice: chunk kc = wave + 4 it; column tile ct = tile of 8 units (ct >> 1), its gates i,f (ct & 1 = 0) or g,o
   // (the per-step kernel's packing)
-  uint4 w[NCH][4];
+  // It fills the 256 accumulation registers of every lane and the MFMAs read it there (inline assembly, as in the bfloat16
+  // kernels).  A chunk past the end of K or a column tile past n takes the last valid one's weights instead of zeros: the h
+  // values of such a chunk arrive as zeros (the ring's descriptor ends before them), and such columns are never stored.
+  u32x4 w[NCH][4];
 #pragma unroll
   for (int it = 0; it < NCH; ++it) {
-    const int kc = wave + 4 * it;
+    const int kc = min(wave + 4 * it, nkc - 1);
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
-      const int tile8 = tile * 2 + (ct >> 1);
-      w[it][ct] = (kc < nkc && tile8 < ntile8) ? d.Wf[((long)(tile8 * 2 + (ct & 1)) * nkc + kc) * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+      const int tile8 = min(tile * 2 + (ct >> 1), ntile8 - 1);
+      w[it][ct] = load_to_agpr(&d.Wf[((long)(tile8 * 2 + (ct & 1)) * nkc + kc) * 64 + lane]);
     }
   }
+  agpr_loads_done();
 
   // pointwise: row r16 of each row tile, unit u of the tile's 16
   const int r16 = tid >> 4, u = tid & 15;
@@ -1834,17 +1838,15 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
       f32x4 acc[4];
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      operands_settle(acc[0], acc[1], acc[2], acc[3]);     // (the MFMAs are assembly text: wait states by hand)
       const RingReader rd = reader(tau, k);
       auto use = [&](int it, const u32x4& x) __attribute__((always_inline)) {
-        const float av[4] = {__uint_as_float(x[0]), __uint_as_float(x[1] & ~kLLFwdTagBit), __uint_as_float(x[2]),
-                             __uint_as_float(x[3] & ~kLLFwdTagBit)};
+        u32x4 av = {x[0], x[1] & ~kLLFwdTagBit, x[2], x[3] & ~kLLFwdTagBit};
+        asm volatile("s_nop 4" : "+v"(av));                // masked just now by the vector ALU
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-          for (int ct = 0; ct < 4; ++ct) {
-            const float we = __uint_as_float(e == 0 ? w[it][ct].x : e == 1 ? w[it][ct].y : e == 2 ? w[it][ct].z : w[it][ct].w);
-            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[e], we, acc[ct], 0, 0, 0);
-          }
+          for (int ct = 0; ct < 4; ++ct) mfma4_b_agpr(acc[ct], __uint_as_float(av[e]), w[it][ct][e]);
       };
 #pragma unroll
       for (int it = kEarly; it < NCH; ++it) x[it] = rd.load_it(it);
@@ -1859,6 +1861,7 @@ __global__ __launch_bounds__(256) void persist_fwd_f32_kernel(PFwdArgs a) {
       if (redo) rd.template fix_up_batch<NCH>(redo, dead, use);
       if (k + 1 < nrt_here) issue_loads(tau, k + 1);
       else if (tau + 1 < T) issue_loads(tau + 1, 0);
+      mfma_settle(acc[0], acc[1], acc[2], acc[3]);         // (behind the loads: their issue covers part of the wait)
       PROF_MARK(0)
       // accumulator rows 4 * (lane / 16) + v of the row tile, column lane % 16 of the column tile
 #pragma unroll
