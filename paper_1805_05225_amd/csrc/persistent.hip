@@ -1977,8 +1977,8 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
   // The reader of the partial sums that step sigma consumes for row tile k.  In a slab of two row tiles they are collected
   // DURING the products of the half step before (the other row tile's): what they fetch was published half a step
   // earlier, the loads run kWin ahead of the additions, one load and one addition behind each column tile's MFMAs, and
-  // the matrix cores do not wait for the exchange.  `ps_c` / `redo_c` carry the sums (and which loads came back with
-  // a stale tag) into the next half step.
+  // the matrix cores do not wait for the exchange.  `ps_c` / `redo_c` carry the sums (or, if a tag was stale, the order to fetch
+  // everything again) into the next half step.
 #ifndef LSTM_BWD_F32_WIN
 #define LSTM_BWD_F32_WIN 6
 #endif
@@ -2078,7 +2078,7 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
         const RingReader rn = reader(sigma_n, k_n);
         const unsigned tagw_n = rn.tag << 16;
         float psn[4] = {0.f, 0.f, 0.f, 0.f};
-        unsigned long long redo_n = 0ull;
+        unsigned stale_n = 0u;
         if (collect) {
 #pragma unroll
           for (int it = 0; it < kWin; ++it) x[it] = rn.load_it(it);
@@ -2113,17 +2113,21 @@ __global__ __launch_bounds__(256) void persist_bwd_f32_kernel(PBwdArgs a) {
           if (ci > 0) publish(ci - 1, acc2[(ci - 1) & 1]);
           if (collect) {                                   // (behind the MFMAs just issued: they run while this does)
             wait_loads_but((NCT - 1 - ci) < (kWin - 1) ? (NCT - 1 - ci) : (kWin - 1), x[ci % kWin]);     // the younger loads: the window's others
-            if (__builtin_amdgcn_ballot_w64(rn.tag_diff(x[ci % kWin], ci, tagw_n) != 0u) == 0ull) add_to(psn, x[ci % kWin]);
-            else { redo_n |= 1ull << ci; PROF_REDO(1) }
+            stale_n |= rn.tag_diff(x[ci % kWin], ci, tagw_n);      // looked at once, behind the last load
+            add_to(psn, x[ci % kWin]);
             if (ci + kWin < NCT) x[ci % kWin] = rn.load_it(ci + kWin);
           }
         }
         mfma_settle(acc2[(NCT - 1) & 1]);
         publish(NCT - 1, acc2[(NCT - 1) & 1]);
         if (collect) {
+          // The tags are looked at once, here: a test and a branch per load cost a twentieth of the step.  A stale tag anywhere
+          // (a tenth of the half steps): the sums are dropped and the next half step fetches every load again.
+          const bool again = __builtin_amdgcn_ballot_w64(stale_n != 0u) != 0ull;
+          if (again) { PROF_REDO(NCT) }
 #pragma unroll
-          for (int v = 0; v < 4; ++v) ps_c[v] = psn[v];
-          redo_c = redo_n;
+          for (int v = 0; v < 4; ++v) ps_c[v] = again ? 0.f : psn[v];
+          redo_c = again ? (1ull << NCT) - 1ull : 0ull;
           have_c = true;
         }
       }
